@@ -1,0 +1,437 @@
+"""CPU oracle for Diversely Stale Parameters (DSP) -- TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, fp64 statement of what the DSP training step computes, written from the
+paper; it shares no code with the HIP library and must never be imported by the product
+path (only tests, the smoke check and the benchmark's CPU-baseline leg may use it).
+
+What follows the paper, and where:
+
+* Section 2, Eq. (1): the CNN is K consecutive blocks h_{k+1} = f_k(h_k; x_k), loss L(h_K, l).
+  ``CNNBlock`` is one f_k (a list of textbook layers, arithmetic in ``layers.c``/numpy);
+  ``SoftmaxCE`` is L.
+* Section 2, Eq. (2): the chain rule per block -> ``CNNBlock.vjp``.
+* Section 2, Eq. (3): stochastic unified momentum -> ``SUM`` (s = 0 heavy ball, s = 1 Nesterov).
+* Section 3.1: layer-wise staleness = number of parameter updates between the forward and the
+  backward use of a block's parameters for one mini-batch.
+* Section 3.2, Eq. (5): the DSP gradient -- block k recomputes f_k on the input it *stored*
+  (produced by the lower blocks' forward parameters) with its *current* (backward) parameters
+  and applies the chain rule with the delayed error gradient.
+* Section 3.3 and Appendix A: the batch pipeline -- block k owns FIFO queues M_k (inputs),
+  P_k (outputs), Q_k (gradients) of lengths 1+m_k, 1+p_k, 1+q_k with
+  q_k = m_{k-1} - p_{k-1} - m_k, q_0 = 0, p_{K-1} = 0.  ``DSPOracle`` moves real tagged items
+  through real queues; it never computes a batch index in closed form.
+
+Readings taken where the paper is silent (all listed in the design notes of the repository):
+a queue of length 1+n releases its oldest item once it holds 1+n items, i.e. it delays by n
+ticks; inside one tick a block runs forward(a), then recompute+backward(b) with the same
+parameters, then its update; ticks in which no gradient has arrived make no update; the
+last block may have m = 0 (the paper's own configurations do); all m = p = 0 is ordinary
+backpropagation; Q_k holds the gradients block k emits for block k-1; the mini-batch loss is
+the mean over the batch; weight decay, if any, is added to the gradient of weight tensors only.
+
+Parity pins (see tests): exact rational worked example, finite differences, adjoint
+identities, torch-autograd + SGD for the zero-staleness case, closed forms for BN /
+softmax / momentum.  The loss trajectory on the synthetic CNN workloads has no pin other
+than those (parity unpinned beyond them: the paper prints no numbers for synthetic data).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from collections import deque
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "layers.c")
+_SO = os.path.join(_HERE, "_build", "liboracle_layers.so")
+_lib_handle = None
+
+
+def build(force=False):
+    """Compiles layers.c with gcc (plain C, -O2, OpenMP on outer loops only)."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        os.makedirs(os.path.dirname(_SO), exist_ok=True)
+        tmp = _SO + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _SO)
+    return _SO
+
+
+def _lib():
+    global _lib_handle
+    if _lib_handle is None:
+        _lib_handle = ctypes.CDLL(build())
+    return _lib_handle
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+# --------------------------------------------------------------------------- layers (fp64, NCHW)
+def conv2d_forward(x, w, stride, pad):
+    x, w = _f64(x), _f64(w)
+    N, C, H, W = x.shape
+    K, C2, R, S = w.shape
+    assert C == C2
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    y = np.empty((N, K, Ho, Wo))
+    _lib().oracle_conv2d_forward(_p(x), _p(w), _p(y), N, C, H, W, K, R, S, stride, pad)
+    return y
+
+
+def conv2d_backward_data(dy, w, x_shape, stride, pad):
+    dy, w = _f64(dy), _f64(w)
+    N, C, H, W = x_shape
+    K, _, R, S = w.shape
+    dx = np.empty(x_shape)
+    _lib().oracle_conv2d_backward_data(_p(dy), _p(w), _p(dx), N, C, H, W, K, R, S, stride, pad)
+    return dx
+
+
+def conv2d_backward_weight(x, dy, w_shape, stride, pad):
+    x, dy = _f64(x), _f64(dy)
+    N, C, H, W = x.shape
+    K, _, R, S = w_shape
+    dw = np.empty(w_shape)
+    _lib().oracle_conv2d_backward_weight(_p(x), _p(dy), _p(dw), N, C, H, W, K, R, S, stride, pad)
+    return dw
+
+
+def bn_forward(x, gamma, beta, eps):
+    x, gamma, beta = _f64(x), _f64(gamma), _f64(beta)
+    N, C, H, W = x.shape
+    y, mean, invstd = np.empty_like(x), np.empty(C), np.empty(C)
+    _lib().oracle_bn_forward(_p(x), _p(gamma), _p(beta), ctypes.c_double(eps), _p(y), _p(mean), _p(invstd),
+                             N, C, H * W)
+    return y, mean, invstd
+
+
+def bn_backward(dy, x, gamma, mean, invstd):
+    dy, x, gamma = _f64(dy), _f64(x), _f64(gamma)
+    N, C, H, W = x.shape
+    dx, dg, db = np.empty_like(x), np.empty(C), np.empty(C)
+    _lib().oracle_bn_backward(_p(dy), _p(x), _p(gamma), _p(_f64(mean)), _p(_f64(invstd)), _p(dx), _p(dg),
+                              _p(db), N, C, H * W)
+    return dx, dg, db
+
+
+def maxpool_forward(x, k, stride, pad):
+    x = _f64(x)
+    N, C, H, W = x.shape
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    y = np.empty((N, C, Ho, Wo))
+    arg = np.empty((N, C, Ho, Wo), np.int32)
+    _lib().oracle_maxpool_forward(_p(x), _p(y), _p(arg), N, C, H, W, k, stride, pad)
+    return y, arg
+
+
+def maxpool_backward(dy, arg, x_shape):
+    dy = _f64(dy)
+    N, C, H, W = x_shape
+    dx = np.empty(x_shape)
+    _lib().oracle_maxpool_backward(_p(dy), _p(arg), _p(dx), N, C, H, W, dy.shape[2], dy.shape[3])
+    return dx
+
+
+class SoftmaxCE:
+    """L(h_K, l): mean over the mini-batch of -log softmax(h_K)[l]; returns (loss, dL/dh_K)."""
+
+    def value_and_grad(self, z, labels):
+        z = _f64(z)
+        n = z.shape[0]
+        zs = z - z.max(axis=1, keepdims=True)
+        logp = zs - np.log(np.exp(zs).sum(axis=1, keepdims=True))
+        loss = -logp[np.arange(n), labels].mean()
+        g = np.exp(logp)
+        g[np.arange(n), labels] -= 1.0
+        return float(loss), g / n
+
+
+# --------------------------------------------------------------------------- one block f_k
+class CNNBlock:
+    """f_k(h_k; x_k) for a layer list (see workloads.configs) and its VJP (Eq. (2)).
+
+    ``params`` is a list (one entry per layer) of dicts of fp64 arrays: conv {"w"},
+    bn {"gamma", "beta"}, linear {"w", "c"}.  A trailing ``softmax_ce`` layer is not part of
+    f_k: it is the loss L and is handled by the pipeline.
+    """
+
+    def __init__(self, layers, params, first_block, eps=1e-5):
+        self.layers = [L for L in layers if L["op"] != "softmax_ce"]
+        self.x = [{k: _f64(v).copy() for k, v in d.items()} for d in params[:len(self.layers)]]
+        self.first_block = first_block  # no gradient w.r.t. the data h_0 is formed (q_0 = 0)
+        self.eps = eps
+
+    # -- parameters as one flat list of arrays (what the optimiser sees)
+    def param_list(self):
+        return [d[k] for d in self.x for k in d]
+
+    def decay_mask(self):
+        return [k == "w" for d in self.x for k in d]
+
+    def set_param_list(self, new):
+        it = iter(new)
+        for d in self.x:
+            for k in d:
+                d[k] = next(it)
+
+    def forward(self, h, params=None):
+        """Returns (h_{k+1}, cache) with every intermediate tensor kept."""
+        P = self.x if params is None else params
+        h = _f64(h)
+        T, aux = [], []
+        src = lambda i: h if i == -1 else T[i]  # noqa: E731
+        for L, prm in zip(self.layers, P):
+            x = src(L["in"])
+            op = L["op"]
+            if op == "conv":
+                T.append(conv2d_forward(x, prm["w"], L["stride"], L["pad"]))
+                aux.append(None)
+            elif op == "bn":
+                z, mean, invstd = bn_forward(x, prm["gamma"], prm["beta"], self.eps)
+                if L["res"] is not None:
+                    z = z + src(L["res"])
+                T.append(np.maximum(z, 0.0) if L["relu"] else z)
+                aux.append((mean, invstd, z))
+            elif op == "maxpool":
+                y, arg = maxpool_forward(x, L["k"], L["stride"], L["pad"])
+                T.append(y)
+                aux.append(arg)
+            elif op == "gap":
+                T.append(x.mean(axis=(2, 3)))
+                aux.append(None)
+            elif op == "linear":
+                T.append(x @ prm["w"].T + prm["c"])
+                aux.append(None)
+            else:
+                raise ValueError(op)
+        return T[-1], (h, T, aux)
+
+    def backward(self, cache, g_out, params=None):
+        """Chain rule through the cached forward: returns (G_{h_k} or None, G_{x_k} as a flat list)."""
+        P = self.x if params is None else params
+        h, T, aux = cache
+        dT = [None] * len(T)
+        dT[-1] = _f64(g_out)
+        dh = [None]
+        grads = [dict() for _ in self.layers]
+
+        def src(i):
+            return h if i == -1 else T[i]
+
+        def add(i, v):
+            if i == -1:
+                dh[0] = v if dh[0] is None else dh[0] + v
+            else:
+                dT[i] = v if dT[i] is None else dT[i] + v
+
+        for i in reversed(range(len(self.layers))):
+            L, prm, g = self.layers[i], P[i], dT[i]
+            assert g is not None, "tensor %d has no consumer" % i
+            x = src(L["in"])
+            op = L["op"]
+            if op == "conv":
+                grads[i]["w"] = conv2d_backward_weight(x, g, prm["w"].shape, L["stride"], L["pad"])
+                if not (L["in"] == -1 and self.first_block):
+                    add(L["in"], conv2d_backward_data(g, prm["w"], x.shape, L["stride"], L["pad"]))
+            elif op == "bn":
+                mean, invstd, z = aux[i]
+                if L["relu"]:
+                    g = g * (z > 0.0)  # ReLU'(0) = 0
+                if L["res"] is not None:
+                    add(L["res"], g)
+                dx, dg, db = bn_backward(g, x, prm["gamma"], mean, invstd)
+                grads[i]["gamma"], grads[i]["beta"] = dg, db
+                add(L["in"], dx)
+            elif op == "maxpool":
+                add(L["in"], maxpool_backward(g, aux[i], x.shape))
+            elif op == "gap":
+                hw = x.shape[2] * x.shape[3]
+                add(L["in"], np.broadcast_to(g[:, :, None, None] / hw, x.shape).copy())
+            elif op == "linear":
+                grads[i]["w"] = g.T @ x
+                grads[i]["c"] = g.sum(axis=0)
+                add(L["in"], g @ prm["w"])
+        flat = [grads[i][k] for i, d in enumerate(self.x) for k in d]
+        return (None if self.first_block else dh[0]), flat
+
+    def vjp(self, h, g_out):
+        """Eq. (5), lines 1-2: recompute f_k on the stored input with the *current* parameters, then chain rule."""
+        _, cache = self.forward(h)
+        return self.backward(cache, g_out)
+
+
+# --------------------------------------------------------------------------- Eq. (3)
+class SUM:
+    """Stochastic unified momentum, Eq. (3):
+
+        y^{n+1}   = x^n - alpha G,     y^{s,n+1} = x^n - s alpha G,
+        x^{n+1}   = y^{n+1} + beta (y^{s,n+1} - y^{s,n}),       y^{s,0} = x^0.
+
+    s = 0 is heavy-ball momentum SGD (the optimiser of the paper's experiments), beta = 0 is SGD.
+    Works on any list of objects supporting + - * (numpy arrays, Fractions).
+    """
+
+    def __init__(self, x0, alpha, beta, s=0, wd=0, decay_mask=None):
+        self.alpha, self.beta, self.s, self.wd = alpha, beta, s, wd
+        self.ys = [v * 1 for v in x0]
+        self.mask = decay_mask or [True] * len(x0)
+        self.n_updates = 0
+        self.last_step = None  # x^{n+1} - x^n of the latest update
+
+    def step(self, x, G):
+        new, step = [], []
+        for i, (xi, gi) in enumerate(zip(x, G)):
+            if self.wd and self.mask[i]:
+                gi = gi + self.wd * xi
+            y = xi - self.alpha * gi
+            ys = xi - self.s * self.alpha * gi
+            xn = y + self.beta * (ys - self.ys[i])
+            self.ys[i] = ys
+            new.append(xn)
+            step.append(xn - xi)
+        self.n_updates += 1
+        self.last_step = step
+        return new
+
+
+# --------------------------------------------------------------------------- the batch pipeline
+def queue_lengths(p, m):
+    """Appendix A: q_0 = 0, q_k = m_{k-1} - p_{k-1} - m_k; validates the schedule.
+
+    Accepted: (i) the all-zero schedule = ordinary backpropagation (Section 3.1, remark a);
+    (ii) p_k > 0 for k < K-1, p_{K-1} = 0, m_k > 0 for k < K-1, m_{K-1} >= 0, q_k > 0 for k >= 1.
+    """
+    K = len(m)
+    if len(p) != K:
+        raise ValueError("p and m must have K entries each")
+    if all(v == 0 for v in p) and all(v == 0 for v in m):
+        return [0] * K
+    if p[K - 1] != 0:
+        raise ValueError("p_{K-1} must be 0")
+    if any(v <= 0 for v in p[:K - 1]):
+        raise ValueError("p_k must be > 0 for k < K-1")
+    if any(v <= 0 for v in m[:K - 1]) or m[K - 1] < 0:
+        raise ValueError("m_k must be > 0 for k < K-1 and >= 0 for the last block")
+    q = [0] + [m[k - 1] - p[k - 1] - m[k] for k in range(1, K)]
+    if any(v <= 0 for v in q[1:]):
+        raise ValueError("q_k = m_{k-1} - p_{k-1} - m_k must be > 0")
+    return q
+
+
+class _Fifo:
+    """A FIFO queue of fixed length: once it holds ``length`` items, pop() hands out the oldest."""
+
+    def __init__(self, length):
+        self.length = length
+        self.items = deque()
+
+    def push(self, item):
+        assert len(self.items) < self.length, "queue overflow"
+        self.items.append(item)
+
+    def full(self):
+        return len(self.items) == self.length
+
+    def pop(self):
+        return self.items.popleft()
+
+
+class DSPOracle:
+    """DSP(p_0..p_{K-1}; m_0..m_{K-1}) over K blocks, one ``tick`` per fresh mini-batch.
+
+    ``blocks[k]`` must offer forward(h) -> (h_next, cache), vjp(h, g) -> (g_h, [g_x...]),
+    param_list(), set_param_list(list), decay_mask(); ``loss`` offers
+    value_and_grad(h_K, label) -> (value, G_{h_K}).
+    """
+
+    def __init__(self, blocks, loss, p, m, lr, beta, wd=0, s=0, external_gradient=False):
+        self.blocks, self.loss = blocks, loss
+        self.K = K = len(blocks)
+        self.p, self.m = list(p), list(m)
+        self.q = queue_lengths(self.p, self.m)
+        self.M = [_Fifo(1 + self.m[k]) for k in range(K)]
+        self.P = [_Fifo(1 + self.p[k]) for k in range(K)]
+        self.Q = [_Fifo(1 + self.q[k]) for k in range(K)]
+        # error gradient at the top of the last block, held until that block's backward (delay m_{K-1})
+        self.QK = _Fifo(1 + self.m[K - 1])
+        self.opt = [SUM(b.param_list(), lr, beta, s=s, wd=wd, decay_mask=b.decay_mask()) for b in blocks]
+        self.external_gradient = external_gradient
+        self.tau = 0
+        self.log = []  # one dict per tick: what every block did
+
+    def tick(self, h0, label, top_gradient=None):
+        """Feeds mini-batch number ``tau``; returns this tick's record.
+
+        ``top_gradient(batch_id, h_K)`` supplies G_{h_K} when the pipeline is a lone block fed
+        with an external error gradient instead of a loss.
+        """
+        K, tau = self.K, self.tau
+        rec = {"tau": tau, "fwd": [None] * K, "bwd": [None] * K, "version": [o.n_updates for o in self.opt],
+               "loss": None, "loss_batch": None, "out": [None] * K, "g_in": [None] * K, "g_x": [None] * K,
+               "h_in_fwd": [None] * K, "h_in_bwd": [None] * K, "g_out": [None] * K}
+        pending = [None] * K
+
+        # forward: the data source feeds block 0; block k>0 takes what P_{k-1} releases
+        for k in range(K):
+            if k == 0:
+                item = (tau, h0, label)
+            elif self.P[k - 1].full():
+                item = self.P[k - 1].pop()
+            else:
+                continue
+            a, h, lab = item
+            self.M[k].push(item)
+            out, _ = self.blocks[k].forward(h)
+            rec["fwd"][k], rec["h_in_fwd"][k], rec["out"][k] = a, h, out
+            if k < K - 1:
+                self.P[k].push((a, out, lab))
+            else:
+                if self.external_gradient:
+                    g = top_gradient(a, out)
+                else:
+                    val, g = self.loss.value_and_grad(out, lab)
+                    rec["loss"], rec["loss_batch"] = val, a
+                self.QK.push((a, g))
+
+        # recompute + backward: the stored input and the delayed error gradient must carry the same tag
+        for k in reversed(range(K)):
+            if not self.M[k].full():
+                continue
+            gq = self.QK if k == K - 1 else self.Q[k + 1]
+            if not gq.full():
+                continue
+            b, h, _ = self.M[k].pop()
+            bg, g = gq.pop()
+            assert b == bg, "block %d: stored input of batch %d met the gradient of batch %d" % (k, b, bg)
+            g_h, g_x = self.blocks[k].vjp(h, g)  # same parameters as this tick's forward
+            rec["bwd"][k], rec["h_in_bwd"][k], rec["g_out"][k] = b, h, g
+            rec["g_in"][k], rec["g_x"][k] = g_h, g_x
+            if k > 0:
+                self.Q[k].push((b, g_h))
+            pending[k] = g_x
+
+        # update last: x_k <- SUM(x_k, G_{x_k})
+        for k in range(K):
+            if pending[k] is not None:
+                self.blocks[k].set_param_list(self.opt[k].step(self.blocks[k].param_list(), pending[k]))
+        self.tau += 1
+        self.log.append({k: rec[k] for k in ("tau", "fwd", "bwd", "version", "loss", "loss_batch")})
+        return rec
+
+
+def build_cnn_oracle(cfg, params_per_block, lr=None, beta=None, wd=None, p=None, m=None, eps=1e-5):
+    """A DSPOracle over the CNN blocks of a workload config (see workloads.configs)."""
+    blocks = [CNNBlock(layers, prm, first_block=(k == 0 and cfg.get("data_input", True)), eps=eps)
+              for k, (layers, prm) in enumerate(zip(cfg["blocks"], params_per_block))]
+    ext = cfg.get("classes") is None
+    return DSPOracle(blocks, SoftmaxCE(), cfg["p"] if p is None else p, cfg["m"] if m is None else m,
+                     cfg["lr"] if lr is None else lr, cfg["beta"] if beta is None else beta,
+                     wd=cfg["wd"] if wd is None else wd, external_gradient=ext)
