@@ -1,0 +1,239 @@
+/*
+ * dsp.h -- C ABI of the MI355X (gfx950) library for the per-block training step of
+ * Diversely Stale Parameters (DSP).
+ *
+ * Vocabulary follows the paper.  A CNN is split into K consecutive blocks
+ * h_{k+1} = f_k(h_k; x_k) with loss L(h_K, l) (Section 2, Eq. (1)).  In the batch pipeline
+ * DSP(p_0..p_{K-1}; m_0..m_{K-1}) (Section 3.3, Appendix A) block k, at every tick,
+ *   1. runs the forward pass of the newest mini-batch a on its current parameters and stores
+ *      the block INPUT h_k(a) (queue M_k, 1+m_k entries; no activations, no weight copies),
+ *   2. recomputes f_k on the input h_k(b) it stored m_k mini-batches earlier, with the SAME
+ *      current parameters, and back-propagates the delayed error gradient G_{h_{k+1}}(b)
+ *      (Section 3.2, Eq. (5)): G_{x_k}(b), G_{h_k}(b),
+ *   3. applies a momentum-SGD update (Section 2, Eq. (3) with s = 0).
+ * m_k is the layer-wise staleness of block k (Section 3.1): m_k updates separate the forward
+ * and the backward use of x_k for one mini-batch.
+ *
+ * Conventions
+ *   - Every function returns a dsp_status; nothing throws or aborts across this boundary.
+ *   - "d_" pointers are DEVICE pointers on the current HIP device, "h_" pointers are HOST
+ *     pointers.  Streams are hipStream_t passed as void* (NULL = the null stream).
+ *   - Activations and error gradients cross the boundary in NHWC order in the block's
+ *     storage type (float for DSP_FP32, bfloat16 for DSP_BF16); tensors after a global
+ *     average pool (N x C) and the loss are always float.
+ *   - Parameters cross the boundary on the HOST as float in "layer order": for each layer in
+ *     turn, conv: w[cout][cin][r][s]; bn: gamma[c], beta[c]; linear: W[cout][cin], c[cout].
+ *   - The library allocates device memory only in the *_init calls; the step calls launch
+ *     kernels asynchronously on the given stream and allocate nothing.
+ *   - Objects are not thread-safe; calls on one block must be issued in pipeline order
+ *     (forward, then recompute_backward, then param_update) or DSP_ESTATE is returned.
+ */
+#ifndef DSP_H
+#define DSP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum dsp_status {
+    DSP_OK = 0,
+    DSP_EINVAL = 1, /* bad argument / descriptor / schedule (Appendix A violated) */
+    DSP_ESTATE = 2, /* call out of pipeline order */
+    DSP_ENOMEM = 3, /* device or host allocation failed */
+    DSP_EHIP = 4    /* a HIP runtime call failed; see dsp_last_error() */
+} dsp_status;
+
+typedef enum dsp_dtype {
+    DSP_FP32 = 0, /* fp32 storage, fp32 MFMA */
+    DSP_BF16 = 1  /* bf16 storage of activations/gradients/shadow weights, bf16 MFMA with fp32
+                     accumulation; fp32 master weights, momentum, weight gradients, BN statistics */
+} dsp_dtype;
+
+typedef enum dsp_op {
+    DSP_OP_CONV = 0,      /* cross-correlation, zero padding, no bias */
+    DSP_OP_BN = 1,        /* training-mode batch norm [+ residual add] [+ ReLU] */
+    DSP_OP_MAXPOOL = 2,   /* r x r window, stride, pad (-inf padding, first maximum wins) */
+    DSP_OP_GAP = 3,       /* global average pool over H, W */
+    DSP_OP_LINEAR = 4,    /* z = W h + c */
+    DSP_OP_SOFTMAX_CE = 5 /* L = mean over the batch of -log softmax(z)[label]; last block only */
+} dsp_op;
+
+/* One layer of a block.  Layer i produces tensor i; in0 = -1 names the block input h_k. */
+typedef struct dsp_layer_desc {
+    int32_t op;     /* dsp_op */
+    int32_t in0;    /* producer of the input: layer index, or -1 for the block input */
+    int32_t in1;    /* BN only: tensor added after normalisation (residual), or -2 for none */
+    int32_t cin;    /* conv/linear input channels; BN channels */
+    int32_t cout;   /* conv/linear output channels */
+    int32_t r, s;   /* conv filter height/width; maxpool window (r) */
+    int32_t stride; /* conv/maxpool stride */
+    int32_t pad;    /* conv/maxpool padding */
+    int32_t relu;   /* BN only: apply ReLU after (BN + residual) */
+} dsp_layer_desc;
+
+/* One block of the split CNN and its place in DSP(p; m). */
+typedef struct dsp_block_desc {
+    int32_t n_layers;
+    const dsp_layer_desc* layers;
+    int32_t N, C, H, W;       /* mini-batch size and shape of the block input h_k */
+    int32_t dtype;            /* dsp_dtype */
+    int32_t k, K;             /* index of this block, number of blocks */
+    int32_t m_k;              /* layer-wise staleness: the stored-input queue M_k has 1+m_k entries */
+    int32_t p_prev;           /* p_{k-1} (0 for a stand-alone block): the output queue P_{k-1} of the block
+                                 below is fused into M_k, which then has 1+m_k+p_prev entries, so the
+                                 producer writes h_k straight into its slot (no copy between queues) */
+    int32_t needs_input_grad; /* 0 for the block that reads the data h_0 (q_0 = 0): G_{h_0} is not formed */
+    float bn_eps;
+} dsp_block_desc;
+
+typedef struct dsp_block dsp_block;
+typedef struct dsp_pipeline dsp_pipeline;
+
+/* ---- schedule (host only; Section 3.3 and Appendix A) ------------------------------------ */
+
+/*
+ * Validates DSP(p; m) and writes q_k = m_{k-1} - p_{k-1} - m_k (q_0 = 0) into q[K].
+ * Accepted: p_k > 0 for k < K-1, p_{K-1} = 0, m_k > 0 for k < K-1, m_{K-1} >= 0 (the paper's own
+ * schedules end in m = 0), q_k > 0 for k >= 1; or the all-zero schedule, which is ordinary
+ * backpropagation (Section 3.1, remark a).  Anything else: DSP_EINVAL.
+ */
+int dsp_schedule_validate(int32_t K, const int32_t* p, const int32_t* m, int32_t* q);
+
+/*
+ * Closed-form position of block k at tick tau: forward mini-batch a = tau - sum_{j<k} p_j,
+ * backward mini-batch b = a - m_k (either is -1 while the pipeline fills), the number of updates
+ * already applied to x_k (= max(0, b)), and the queue slots: M_k slot of a and of b (ring of
+ * 1+m_k+p_{k-1} entries), Q_k slot written for b (ring of 1+q_k entries; -1 for k = 0) and the
+ * Q_{k+1} slot read for b (-1 for the last block).  out[7] = {a, b, version, slot_fwd, slot_bwd,
+ * q_write_slot, q_read_slot}.
+ */
+int dsp_schedule_index(int32_t K, const int32_t* p, const int32_t* m, int32_t k, int64_t tau, int64_t out[7]);
+
+/* Queue memory in ELEMENTS for per-block boundary sizes h_elems[k] = |h_k|, k = 0..K (Section 3.3:
+ * space O(L + sum_k (m_k + p_k + q_k))): sum_k (1+m_k+p_{k-1}) |h_k| + (1+q_k) |h_k| [k >= 1]. */
+int dsp_schedule_queue_elems(int32_t K, const int32_t* p, const int32_t* m, const int64_t* h_elems,
+                             int64_t* total);
+
+/* ---- one block (Section 2 Eq. (1)-(3), Section 3.2 Eq. (5)) ------------------------------ */
+
+/*
+ * Builds block k: checks the layer graph, copies h_params (n_params floats, layer order) to the
+ * device, zeroes the momentum, sets the update counter ("parameter version") to 0 and allocates
+ * the stored-input ring, the recompute workspace and the gradient buffers.  *out owns them.
+ */
+int dsp_block_init(const dsp_block_desc* desc, const float* h_params, size_t n_params, dsp_block** out);
+int dsp_block_destroy(dsp_block* b);
+
+/*
+ * Forward pass of mini-batch batch_id on the current parameters (Eq. (5), third line: what
+ * flows upward is produced by forward parameters).  batch_id must be the next id in order
+ * (0, 1, 2, ...).  Stores the input into ring slot batch_id mod ring_entries (no copy if d_in
+ * already is dsp_block_input_slot(batch_id)), writes h_{k+1}(batch_id) to d_out (may be NULL
+ * for the last block).  Last block with a softmax_ce layer: d_labels = int32[N] labels,
+ * d_loss = one float receiving the mini-batch loss; its own G_{h_K} is kept for the backward.
+ */
+int dsp_block_forward(dsp_block* b, int64_t batch_id, const void* d_in, void* d_out, const int32_t* d_labels,
+                      float* d_loss, void* stream);
+
+/*
+ * Eq. (5), lines 1-2: recomputes f_k on the stored input h_k(batch_id) with the CURRENT parameters
+ * and back-propagates d_grad_out = G_{h_{k+1}}(batch_id) (NULL: the block's own loss gradient).
+ * batch_id must equal (latest forward id) - m_k and follow the previous backward id.  Writes
+ * G_{h_k} to d_grad_in (ignored when needs_input_grad = 0) and leaves G_{x_k} in a library buffer
+ * for dsp_param_update.  With m_k = 0 the forward pass just run is reused instead of recomputed.
+ */
+int dsp_block_recompute_backward(dsp_block* b, int64_t batch_id, const void* d_grad_out, void* d_grad_in,
+                                 void* stream);
+
+/*
+ * Momentum SGD (Eq. (3), s = 0, constant step): v <- momentum * v + (G + weight_decay * x),
+ * x <- x - lr * v; weight_decay acts on conv/linear weights only.  Consumes the pending G_{x_k}
+ * exactly once (DSP_ESTATE if there is none) and increments the update counter.
+ */
+int dsp_param_update(dsp_block* b, float lr, float momentum, float weight_decay, void* stream);
+
+/* Device address of the M_k ring slot that will hold h_k(batch_id). */
+int dsp_block_input_slot(dsp_block* b, int64_t batch_id, void** d_slot);
+
+/* out[8] = {updates applied, next forward id, next backward id, ring entries, pending gradient (0/1),
+ * parameter count, update count at the forward of the batch whose backward comes next (-1 if none),
+ * slot of that batch}. */
+int dsp_block_query(const dsp_block* b, int64_t out[8]);
+/* Shape (N, C, H, W) of h_{k+1}; H = W = 1 after a pool/linear layer.  out[4] = 1 if it is float
+ * whatever the block dtype (behind a global average pool), else 0. */
+int dsp_block_output_shape(const dsp_block* b, int32_t out[5]);
+/* Shape (N, C, H, W) of h_k and the block dtype: out[5] = {N, C, H, W, dtype}. */
+int dsp_block_input_shape(const dsp_block* b, int32_t out[5]);
+/* Bytes held on the device: stored-input ring, workspace (activations + gradients), parameters. */
+int dsp_block_memory(const dsp_block* b, size_t* ring_bytes, size_t* workspace_bytes, size_t* param_bytes);
+
+/* Host <-> device state in layer order (synchronous; they synchronise the device first). */
+int dsp_block_get_params(dsp_block* b, float* h_dst, size_t n);
+int dsp_block_set_params(dsp_block* b, const float* h_src, size_t n);
+int dsp_block_get_momentum(dsp_block* b, float* h_dst, size_t n);
+int dsp_block_set_momentum(dsp_block* b, const float* h_src, size_t n);
+int dsp_block_get_grads(dsp_block* b, float* h_dst, size_t n);
+
+/* ---- K blocks on K HIP streams of one GPU (Section 3.3) ---------------------------------- */
+
+/*
+ * Wires K blocks (built with matching k, K, m_k, p_prev = p_{k-1}) into DSP(p; m): one stream per
+ * block, gradient rings Q_k of 1+q_k entries, a label ring, a loss history of max_ticks floats.
+ * The blocks stay owned by the caller and must outlive the pipeline.
+ */
+int dsp_pipeline_init(int32_t K, dsp_block* const* blocks, const int32_t* p, const int32_t* m, float lr,
+                      float momentum, float weight_decay, int64_t max_ticks, dsp_pipeline** out);
+int dsp_pipeline_destroy(dsp_pipeline* pl);
+
+/*
+ * One tick: feeds mini-batch number tau (d_batch: NHWC block-0 input, d_labels: int32[N], both
+ * ready on `stream`); every block k with a >= 0 runs forward(a), then, if b >= 0,
+ * recompute_backward(b) and its update, on its own stream.  Blocks never depend on each other
+ * inside a tick; across ticks each stream waits for its neighbours' previous tick.  On return
+ * `stream` is ordered after the copies of d_batch/d_labels, so the caller may refill them.
+ * If h_loss != NULL the call blocks until the loss of this tick is known and returns it with
+ * its mini-batch id (*loss_batch_id = -1 while the pipeline fills); pass NULL to stay asynchronous
+ * and read the history later with dsp_pipeline_losses().
+ */
+int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_labels, float* h_loss,
+                      int64_t* loss_batch_id, void* stream);
+
+/* Straggler emulation: block k's stream spins for `microseconds` before its work in every tick. */
+int dsp_pipeline_set_delay(dsp_pipeline* pl, int32_t k, int32_t microseconds);
+/* Waits for all K streams. */
+int dsp_pipeline_sync(dsp_pipeline* pl);
+/* Copies the losses of mini-batches [0, n) to h_dst after a sync; n <= number of losses produced. */
+int dsp_pipeline_losses(dsp_pipeline* pl, float* h_dst, int64_t n, int64_t* n_available);
+/* Number of ticks issued so far. */
+int dsp_pipeline_ticks(const dsp_pipeline* pl, int64_t* ticks);
+
+/* ---- single-layer entry points (used by the kernel parity tests and micro-benchmarks) ------ */
+
+/*
+ * Convolution kernels on NHWC device tensors of type `dtype`; filters in the library's layout:
+ * d_w  = w[cout][r][s][cin] (forward / backward-weight), d_wt = w[cin][R-1-r][S-1-s][cout]
+ * (backward-data).  dsp_conv_workspace_bytes() sizes d_workspace for backward-weight (split
+ * reduction partials).  accumulate != 0 adds into d_dx instead of overwriting.
+ */
+int dsp_conv_forward(int32_t dtype, const void* d_x, const void* d_w, void* d_y, int32_t N, int32_t H, int32_t W,
+                     int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride, int32_t pad, void* stream);
+int dsp_conv_backward_data(int32_t dtype, const void* d_dy, const void* d_wt, void* d_dx, int32_t N, int32_t H,
+                           int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride, int32_t pad,
+                           int32_t accumulate, void* stream);
+int dsp_conv_backward_weight(int32_t dtype, const void* d_x, const void* d_dy, float* d_dw, int32_t N, int32_t H,
+                             int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride,
+                             int32_t pad, void* d_workspace, size_t workspace_bytes, void* stream);
+int dsp_conv_workspace_bytes(int32_t N, int32_t H, int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s,
+                             int32_t stride, int32_t pad, size_t* bytes);
+
+const char* dsp_strerror(int status);
+/* Text of the most recent failure on this thread ("" if none). */
+const char* dsp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSP_H */

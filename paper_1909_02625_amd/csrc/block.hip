@@ -1,0 +1,652 @@
+// Host engine of one DSP block: layer graph, device buffers, the stored-input ring M_k, the
+// forward / recompute+backward / update sequence of Section 3.2-3.3 of the paper, and the C ABI.
+//
+// Per block, per tick (in this order, all asynchronous on the caller's stream):
+//   forward(a)              f_k on the newest mini-batch with the live parameters; its input is
+//                           kept in ring slot a mod (1+m_k+p_{k-1}); nothing else is kept.
+//   recompute_backward(b)   b = a - m_k: f_k again on the stored input with the SAME live
+//                           parameters (Eq. (5)), keeping conv inputs / BN statistics / ReLU
+//                           outputs in the workspace, then the reverse sweep.
+//   param_update            v <- beta v + G, x <- x - alpha v; shadow weight copies refreshed.
+// There is exactly one live copy of the parameters (no weight stashing); "stale" only means
+// that m_k updates happen between the forward and the backward of one mini-batch.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+namespace dsp {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+struct Tensor {
+    int N = 0, C = 0, H = 1, W = 1;
+    bool is_float = false;  // tensors behind a global average pool are fp32 whatever the block dtype
+    size_t elems = 0;
+    void* act = nullptr;
+    void* grad = nullptr;
+    size_t bytes(int dtype) const { return elems * (is_float ? 4 : dtype_size(dtype)); }
+};
+
+struct Layer {
+    dsp_layer_desc d;
+    ConvShape cs;
+    size_t p0 = 0, p1 = 0;  // offsets of (w | gamma | W) and (beta | bias) in the parameter arrays
+    size_t wt_off = 0;      // offset of the backward-data filter copy
+    float* mean = nullptr;
+    float* invstd = nullptr;
+    uint8_t* argmax = nullptr;
+    bool in0_grad = true;  // form the gradient w.r.t. in0
+    bool in1_grad = true;
+    bool in0_acc = false;  // add to (true) or overwrite (false) the gradient buffer of in0
+    bool in1_acc = false;
+};
+
+}  // namespace dsp
+
+using namespace dsp;
+
+struct dsp_block {
+    dsp_block_desc desc;
+    std::vector<Layer> layers;
+    std::vector<Tensor> T;
+    Tensor input;
+    int out_idx = -1;   // tensor that is h_{k+1}
+    int loss_idx = -1;  // softmax_ce layer, if any
+    int dtype = DSP_FP32;
+
+    size_t nP = 0;
+    float *x = nullptr, *v = nullptr, *g = nullptr;
+    uint8_t* decay = nullptr;
+    int32_t* tmap = nullptr;
+    void* wf16 = nullptr;  // bf16 copy of x in the same layout (bf16 blocks only)
+    void* wt = nullptr;    // backward-data filter copies [cin][R-1-r][S-1-s][cout] in the storage type
+    size_t wt_elems = 0;
+    std::vector<int32_t> perm;  // library index -> layer-order index
+
+    int ring_entries = 1;
+    char* ring = nullptr;
+    size_t slot_bytes = 0;
+    std::vector<int64_t> slot_version;
+
+    float* dz_ring = nullptr;  // loss gradient of the last 1+m_k mini-batches (last block only)
+    size_t dz_elems = 0;
+    float* row_loss = nullptr;
+    float* loss_sink = nullptr;
+
+    void* wgrad_ws = nullptr;
+    size_t wgrad_ws_bytes = 0;
+    double* bn_partial = nullptr;
+    float* bn_coef = nullptr;
+
+    size_t ring_bytes = 0, ws_bytes = 0, param_bytes = 0;
+    std::vector<void*> allocs;
+
+    int64_t version = 0, next_fwd = 0, next_bwd = 0;
+    bool pending = false;
+};
+
+namespace dsp {
+
+static int dev_alloc(dsp_block* b, void** p, size_t bytes, size_t* counter)
+{
+    if (bytes == 0) bytes = 16;
+    hipError_t e = hipMalloc(p, bytes);
+    if (e != hipSuccess) {
+        set_error("hipMalloc(%zu) failed: %s", bytes, hipGetErrorString(e));
+        return DSP_ENOMEM;
+    }
+    b->allocs.push_back(*p);
+    if (counter) *counter += bytes;
+    return DSP_OK;
+}
+
+static const void* weights_for_forward(const dsp_block* b, const Layer& L)
+{
+    return b->dtype == DSP_BF16 ? (const void*)((const bf16_t*)b->wf16 + L.p0) : (const void*)(b->x + L.p0);
+}
+static const void* weights_for_dgrad(const dsp_block* b, const Layer& L)
+{
+    return b->dtype == DSP_BF16 ? (const void*)((const bf16_t*)b->wt + L.wt_off) : (const void*)((const float*)b->wt + L.wt_off);
+}
+
+static int build_graph(dsp_block* b)
+{
+    const dsp_block_desc& d = b->desc;
+    DSP_REQUIRE(d.n_layers > 0 && d.layers != nullptr, DSP_EINVAL, "block: no layers");
+    DSP_REQUIRE(d.N > 0 && d.C > 0 && d.H > 0 && d.W > 0, DSP_EINVAL, "block: bad input shape");
+    DSP_REQUIRE(d.dtype == DSP_FP32 || d.dtype == DSP_BF16, DSP_EINVAL, "block: bad dtype");
+    DSP_REQUIRE(d.K >= 1 && d.k >= 0 && d.k < d.K, DSP_EINVAL, "block: bad k/K");
+    DSP_REQUIRE(d.m_k >= 0 && d.p_prev >= 0, DSP_EINVAL, "block: m_k and p_prev must be >= 0");
+    DSP_REQUIRE(d.bn_eps > 0.f, DSP_EINVAL, "block: bn_eps must be > 0");
+    b->dtype = d.dtype;
+    b->input.N = d.N; b->input.C = d.C; b->input.H = d.H; b->input.W = d.W;
+    b->input.elems = (size_t)d.N * d.C * d.H * d.W;
+    b->layers.resize(d.n_layers);
+    b->T.resize(d.n_layers);
+    size_t poff = 0, wtoff = 0;
+    for (int i = 0; i < d.n_layers; ++i) {
+        Layer& L = b->layers[i];
+        L.d = d.layers[i];
+        DSP_REQUIRE(L.d.in0 >= -1 && L.d.in0 < i, DSP_EINVAL, "layer %d: in0 must name an earlier tensor", i);
+        const Tensor& s = L.d.in0 < 0 ? b->input : b->T[L.d.in0];
+        Tensor& t = b->T[i];
+        t.N = s.N;
+        switch (L.d.op) {
+        case DSP_OP_CONV:
+            DSP_REQUIRE(!s.is_float && s.C == L.d.cin && L.d.cout > 0 && L.d.r > 0 && L.d.s > 0 && L.d.stride > 0 &&
+                            L.d.pad >= 0, DSP_EINVAL, "layer %d: conv shape mismatch", i);
+            L.cs = make_conv_shape(s.N, s.H, s.W, L.d.cin, L.d.cout, L.d.r, L.d.s, L.d.stride, L.d.pad);
+            DSP_REQUIRE(L.cs.Ho > 0 && L.cs.Wo > 0, DSP_EINVAL, "layer %d: empty conv output", i);
+            t.C = L.d.cout; t.H = L.cs.Ho; t.W = L.cs.Wo;
+            L.p0 = poff;
+            poff += (size_t)L.d.cout * L.d.cin * L.d.r * L.d.s;
+            L.wt_off = wtoff;
+            wtoff += (size_t)L.d.cout * L.d.cin * L.d.r * L.d.s;
+            break;
+        case DSP_OP_BN:
+            DSP_REQUIRE(!s.is_float && s.C == L.d.cin, DSP_EINVAL, "layer %d: bn channel mismatch", i);
+            DSP_REQUIRE(L.d.in1 == -2 || (L.d.in1 >= -1 && L.d.in1 < i), DSP_EINVAL, "layer %d: bad residual", i);
+            if (L.d.in1 != -2) {
+                const Tensor& r = L.d.in1 < 0 ? b->input : b->T[L.d.in1];
+                DSP_REQUIRE(!r.is_float && r.C == s.C && r.H == s.H && r.W == s.W, DSP_EINVAL,
+                            "layer %d: residual shape mismatch", i);
+            }
+            t.C = s.C; t.H = s.H; t.W = s.W;
+            L.p0 = poff; L.p1 = poff + s.C;
+            poff += 2 * (size_t)s.C;
+            break;
+        case DSP_OP_MAXPOOL:
+            DSP_REQUIRE(!s.is_float && L.d.r > 0 && L.d.stride > 0 && L.d.pad >= 0 && L.d.pad < L.d.r, DSP_EINVAL,
+                        "layer %d: bad maxpool", i);
+            t.C = s.C;
+            t.H = (s.H + 2 * L.d.pad - L.d.r) / L.d.stride + 1;
+            t.W = (s.W + 2 * L.d.pad - L.d.r) / L.d.stride + 1;
+            DSP_REQUIRE(t.H > 0 && t.W > 0, DSP_EINVAL, "layer %d: empty maxpool output", i);
+            break;
+        case DSP_OP_GAP:
+            DSP_REQUIRE(!s.is_float, DSP_EINVAL, "layer %d: gap input must be a feature map", i);
+            t.C = s.C; t.H = 1; t.W = 1; t.is_float = true;
+            break;
+        case DSP_OP_LINEAR:
+            DSP_REQUIRE(s.is_float && s.C == L.d.cin && L.d.cout > 0, DSP_EINVAL, "layer %d: linear shape mismatch", i);
+            t.C = L.d.cout; t.H = 1; t.W = 1; t.is_float = true;
+            L.p0 = poff; L.p1 = poff + (size_t)L.d.cin * L.d.cout;
+            poff += (size_t)L.d.cin * L.d.cout + L.d.cout;
+            break;
+        case DSP_OP_SOFTMAX_CE:
+            DSP_REQUIRE(s.is_float && i == d.n_layers - 1 && d.k == d.K - 1, DSP_EINVAL,
+                        "layer %d: softmax_ce must close the last block", i);
+            t.C = 1; t.H = 1; t.W = 1; t.is_float = true;
+            b->loss_idx = i;
+            break;
+        default:
+            DSP_REQUIRE(false, DSP_EINVAL, "layer %d: unknown op %d", i, L.d.op);
+        }
+        t.elems = (size_t)t.N * t.C * t.H * t.W;
+    }
+    b->out_idx = b->loss_idx >= 0 ? b->layers[b->loss_idx].d.in0 : d.n_layers - 1;
+    DSP_REQUIRE(b->out_idx >= 0, DSP_EINVAL, "block: the loss needs a producing layer");
+    b->nP = poff;
+    b->wt_elems = wtoff;
+
+    // every tensor must be consumed (or be the block output); decide overwrite vs accumulate for
+    // each gradient buffer by walking the layers in backward order
+    std::vector<char> written(d.n_layers + 1, 0);  // index t+1
+    for (int i = d.n_layers - 1; i >= 0; --i) {
+        Layer& L = b->layers[i];
+        if (L.d.op == DSP_OP_SOFTMAX_CE) { written[L.d.in0 + 1] = 1; continue; }
+        if (i != b->out_idx) DSP_REQUIRE(written[i + 1], DSP_EINVAL, "layer %d: output is never used", i);
+        L.in0_grad = !(L.d.in0 < 0 && !d.needs_input_grad);
+        if (L.in0_grad) { L.in0_acc = written[L.d.in0 + 1]; written[L.d.in0 + 1] = 1; }
+        if (L.d.op == DSP_OP_BN && L.d.in1 != -2) {
+            L.in1_grad = !(L.d.in1 < 0 && !d.needs_input_grad);
+            if (L.in1_grad) { L.in1_acc = written[L.d.in1 + 1]; written[L.d.in1 + 1] = 1; }
+        } else {
+            L.in1_grad = false;
+        }
+    }
+    if (d.needs_input_grad) DSP_REQUIRE(written[0], DSP_EINVAL, "block: the input never reaches a layer");
+
+    // parameter index maps
+    b->perm.resize(b->nP);
+    std::vector<int32_t> tmap(b->nP, -1);
+    std::vector<uint8_t> decay(b->nP, 0);
+    for (int i = 0; i < d.n_layers; ++i) {
+        const Layer& L = b->layers[i];
+        if (L.d.op == DSP_OP_CONV) {
+            const int Co = L.d.cout, Ci = L.d.cin, R = L.d.r, S = L.d.s;
+            for (int co = 0; co < Co; ++co)
+                for (int r = 0; r < R; ++r)
+                    for (int s = 0; s < S; ++s)
+                        for (int ci = 0; ci < Ci; ++ci) {
+                            const size_t lib = L.p0 + (((size_t)co * R + r) * S + s) * Ci + ci;
+                            b->perm[lib] = (int32_t)(L.p0 + (((size_t)co * Ci + ci) * R + r) * S + s);
+                            decay[lib] = 1;
+                            if (L.in0_grad)
+                                tmap[lib] = (int32_t)(L.wt_off + (((size_t)ci * R + (R - 1 - r)) * S + (S - 1 - s)) * Co + co);
+                        }
+        } else if (L.d.op == DSP_OP_BN) {
+            for (size_t j = 0; j < 2 * (size_t)L.d.cin; ++j) b->perm[L.p0 + j] = (int32_t)(L.p0 + j);
+        } else if (L.d.op == DSP_OP_LINEAR) {
+            const size_t nw = (size_t)L.d.cin * L.d.cout;
+            for (size_t j = 0; j < nw + L.d.cout; ++j) {
+                b->perm[L.p0 + j] = (int32_t)(L.p0 + j);
+                if (j < nw) decay[L.p0 + j] = 1;
+            }
+        }
+    }
+    DSP_REQUIRE(b->nP < (1ull << 31), DSP_EINVAL, "block: too many parameters");
+
+    // device buffers
+    const size_t esz = dtype_size(b->dtype);
+    DSP_TRY(dev_alloc(b, (void**)&b->x, b->nP * 4, &b->param_bytes));
+    DSP_TRY(dev_alloc(b, (void**)&b->v, b->nP * 4, &b->param_bytes));
+    DSP_TRY(dev_alloc(b, (void**)&b->g, b->nP * 4, &b->param_bytes));
+    DSP_TRY(dev_alloc(b, (void**)&b->decay, b->nP, &b->param_bytes));
+    DSP_TRY(dev_alloc(b, (void**)&b->tmap, b->nP * 4, &b->param_bytes));
+    DSP_TRY(dev_alloc(b, &b->wt, b->wt_elems * esz, &b->param_bytes));
+    if (b->dtype == DSP_BF16) DSP_TRY(dev_alloc(b, &b->wf16, b->nP * 2, &b->param_bytes));
+    if (b->nP) {
+        DSP_HIP(hipMemcpy(b->decay, decay.data(), b->nP, hipMemcpyHostToDevice));
+        DSP_HIP(hipMemcpy(b->tmap, tmap.data(), b->nP * 4, hipMemcpyHostToDevice));
+        DSP_HIP(hipMemset(b->v, 0, b->nP * 4));
+        DSP_HIP(hipMemset(b->g, 0, b->nP * 4));
+    }
+
+    b->ring_entries = 1 + d.m_k + d.p_prev;
+    b->slot_bytes = (b->input.elems * esz + 255) / 256 * 256;
+    DSP_TRY(dev_alloc(b, (void**)&b->ring, b->slot_bytes * b->ring_entries, &b->ring_bytes));
+    b->slot_version.assign(b->ring_entries, -1);
+
+    int max_c = 1;
+    size_t ws = 0;
+    for (int i = 0; i < d.n_layers; ++i) {
+        Layer& L = b->layers[i];
+        Tensor& t = b->T[i];
+        if (L.d.op == DSP_OP_SOFTMAX_CE) continue;
+        DSP_TRY(dev_alloc(b, &t.act, t.bytes(b->dtype), &b->ws_bytes));
+        if (i != b->out_idx || b->loss_idx >= 0) DSP_TRY(dev_alloc(b, &t.grad, t.bytes(b->dtype), &b->ws_bytes));
+        if (L.d.op == DSP_OP_BN) {
+            DSP_TRY(dev_alloc(b, (void**)&L.mean, (size_t)L.d.cin * 4, &b->ws_bytes));
+            DSP_TRY(dev_alloc(b, (void**)&L.invstd, (size_t)L.d.cin * 4, &b->ws_bytes));
+            if (L.d.cin > max_c) max_c = L.d.cin;
+        }
+        if (L.d.op == DSP_OP_MAXPOOL) DSP_TRY(dev_alloc(b, (void**)&L.argmax, t.elems, &b->ws_bytes));
+        if (L.d.op == DSP_OP_CONV) {
+            const size_t w = conv_backward_weight_workspace(L.cs);
+            if (w > ws) ws = w;
+        }
+    }
+    b->wgrad_ws_bytes = ws;
+    DSP_TRY(dev_alloc(b, &b->wgrad_ws, ws, &b->ws_bytes));
+    DSP_TRY(dev_alloc(b, (void**)&b->bn_partial, (size_t)bn_max_partial_blocks() * max_c * 2 * sizeof(double), &b->ws_bytes));
+    DSP_TRY(dev_alloc(b, (void**)&b->bn_coef, (size_t)3 * max_c * 4, &b->ws_bytes));
+    DSP_TRY(dev_alloc(b, (void**)&b->loss_sink, 4, &b->ws_bytes));
+    if (b->loss_idx >= 0) {
+        const Tensor& z = b->T[b->out_idx];
+        b->dz_elems = z.elems;
+        DSP_TRY(dev_alloc(b, (void**)&b->dz_ring, z.elems * 4 * (1 + d.m_k), &b->ws_bytes));
+        DSP_TRY(dev_alloc(b, (void**)&b->row_loss, (size_t)z.N * 4, &b->ws_bytes));
+    }
+    return DSP_OK;
+}
+
+static int upload_params(dsp_block* b, const float* h, float* dst)
+{
+    std::vector<float> lib(b->nP);
+    for (size_t i = 0; i < b->nP; ++i) lib[i] = h[b->perm[i]];
+    if (b->nP) DSP_HIP(hipMemcpy(dst, lib.data(), b->nP * 4, hipMemcpyHostToDevice));
+    return DSP_OK;
+}
+
+static int download_params(dsp_block* b, const float* src, float* h)
+{
+    std::vector<float> lib(b->nP);
+    DSP_HIP(hipDeviceSynchronize());
+    if (b->nP) DSP_HIP(hipMemcpy(lib.data(), src, b->nP * 4, hipMemcpyDeviceToHost));
+    for (size_t i = 0; i < b->nP; ++i) h[b->perm[i]] = lib[i];
+    return DSP_OK;
+}
+
+// f_k on `in` with the live parameters; the block output goes to out_override if given.
+static int run_forward(dsp_block* b, const void* in, void* out_override, const int32_t* labels, float* loss,
+                       float* dz_slot, hipStream_t st)
+{
+    const int n = (int)b->layers.size();
+    for (int i = 0; i < n; ++i) {
+        Layer& L = b->layers[i];
+        const Tensor& s = L.d.in0 < 0 ? b->input : b->T[L.d.in0];
+        const void* src = L.d.in0 < 0 ? in : b->T[L.d.in0].act;
+        Tensor& t = b->T[i];
+        void* dst = (i == b->out_idx && out_override) ? out_override : t.act;
+        switch (L.d.op) {
+        case DSP_OP_CONV:
+            DSP_TRY(launch_conv_forward(b->dtype, L.cs, src, weights_for_forward(b, L), dst, st));
+            break;
+        case DSP_OP_BN: {
+            const void* res = L.d.in1 == -2 ? nullptr : (L.d.in1 < 0 ? in : b->T[L.d.in1].act);
+            BnBuffers buf{b->bn_partial, L.mean, L.invstd, b->bn_coef};
+            DSP_TRY(launch_bn_forward(b->dtype, src, res, dst, b->x + L.p0, b->x + L.p1, b->desc.bn_eps,
+                                      (int64_t)s.N * s.H * s.W, s.C, L.d.relu != 0, buf, st));
+            break;
+        }
+        case DSP_OP_MAXPOOL:
+            DSP_TRY(launch_maxpool_forward(b->dtype, src, dst, L.argmax, s.N, s.H, s.W, s.C, L.d.r, L.d.stride, L.d.pad, st));
+            break;
+        case DSP_OP_GAP:
+            DSP_TRY(launch_gap_forward(b->dtype, src, (float*)dst, s.N, s.H * s.W, s.C, st));
+            break;
+        case DSP_OP_LINEAR:
+            DSP_TRY(launch_linear_forward((const float*)src, b->x + L.p0, b->x + L.p1, (float*)dst, s.N, L.d.cin, L.d.cout, st));
+            break;
+        case DSP_OP_SOFTMAX_CE:
+            DSP_TRY(launch_softmax_ce((const float*)src, labels, loss, dz_slot, b->row_loss, s.N, s.C, st));
+            break;
+        }
+    }
+    return DSP_OK;
+}
+
+// Reverse sweep over the tensors left by run_forward (all in the workspace).
+static int run_backward(dsp_block* b, const void* in, const void* gout, void* gin, hipStream_t st)
+{
+    const int n = (int)b->layers.size();
+    auto grad_of = [&](int t) -> void* { return t < 0 ? gin : b->T[t].grad; };
+    for (int i = n - 1; i >= 0; --i) {
+        Layer& L = b->layers[i];
+        if (L.d.op == DSP_OP_SOFTMAX_CE) continue;
+        const Tensor& s = L.d.in0 < 0 ? b->input : b->T[L.d.in0];
+        const void* src = L.d.in0 < 0 ? in : b->T[L.d.in0].act;
+        const void* dy = (i == b->out_idx) ? gout : b->T[i].grad;
+        switch (L.d.op) {
+        case DSP_OP_CONV:
+            DSP_TRY(launch_conv_backward_weight(b->dtype, L.cs, src, dy, b->g + L.p0, b->wgrad_ws, b->wgrad_ws_bytes, st));
+            if (L.in0_grad)
+                DSP_TRY(launch_conv_backward_data(b->dtype, L.cs, dy, weights_for_dgrad(b, L), grad_of(L.d.in0), L.in0_acc, st));
+            break;
+        case DSP_OP_BN: {
+            BnBuffers buf{b->bn_partial, L.mean, L.invstd, b->bn_coef};
+            void* dres = L.in1_grad ? grad_of(L.d.in1) : nullptr;
+            DSP_REQUIRE(L.in0_grad, DSP_EINVAL, "bn directly on the data input is not supported");
+            DSP_TRY(launch_bn_backward(b->dtype, dy, src, b->T[i].act, grad_of(L.d.in0), dres, L.in1_acc, L.in0_acc,
+                                       b->x + L.p0, b->g + L.p0, b->g + L.p1, (int64_t)s.N * s.H * s.W, s.C,
+                                       L.d.relu != 0, buf, st));
+            break;
+        }
+        case DSP_OP_MAXPOOL:
+            if (L.in0_grad)
+                DSP_TRY(launch_maxpool_backward(b->dtype, dy, L.argmax, grad_of(L.d.in0), L.in0_acc, s.N, s.H, s.W, s.C,
+                                                L.d.r, L.d.stride, L.d.pad, st));
+            break;
+        case DSP_OP_GAP:
+            if (L.in0_grad)
+                DSP_TRY(launch_gap_backward(b->dtype, (const float*)dy, grad_of(L.d.in0), L.in0_acc, s.N, s.H * s.W, s.C, st));
+            break;
+        case DSP_OP_LINEAR:
+            DSP_REQUIRE(!L.in0_acc, DSP_EINVAL, "linear input with several consumers is not supported");
+            DSP_TRY(launch_linear_backward((const float*)src, b->x + L.p0, (const float*)dy,
+                                           L.in0_grad ? (float*)grad_of(L.d.in0) : nullptr, b->g + L.p0, b->g + L.p1,
+                                           s.N, L.d.cin, L.d.cout, st));
+            break;
+        }
+    }
+    return DSP_OK;
+}
+
+}  // namespace dsp
+
+// ================================================================================================
+extern "C" {
+
+int dsp_block_init(const dsp_block_desc* desc, const float* h_params, size_t n_params, dsp_block** out)
+{
+    DSP_REQUIRE(desc && out, DSP_EINVAL, "dsp_block_init: null argument");
+    *out = nullptr;
+    dsp_block* b = new (std::nothrow) dsp_block();
+    DSP_REQUIRE(b, DSP_ENOMEM, "dsp_block_init: out of host memory");
+    b->desc = *desc;
+    int rc = build_graph(b);
+    if (rc == DSP_OK && n_params != b->nP) {
+        set_error("dsp_block_init: expected %zu parameters, got %zu", b->nP, n_params);
+        rc = DSP_EINVAL;
+    }
+    if (rc == DSP_OK && b->nP && !h_params) {
+        set_error("dsp_block_init: null parameters");
+        rc = DSP_EINVAL;
+    }
+    if (rc == DSP_OK) rc = upload_params(b, h_params, b->x);
+    if (rc == DSP_OK) rc = launch_refresh_shadows(b->dtype, b->x, b->tmap, b->wf16, b->wt, b->nP, nullptr);
+    if (rc == DSP_OK && hipDeviceSynchronize() != hipSuccess) {
+        set_error("dsp_block_init: device synchronisation failed");
+        rc = DSP_EHIP;
+    }
+    b->desc.layers = nullptr;  // the caller's array is not kept
+    if (rc != DSP_OK) {
+        dsp_block_destroy(b);
+        return rc;
+    }
+    *out = b;
+    return DSP_OK;
+}
+
+int dsp_block_destroy(dsp_block* b)
+{
+    if (!b) return DSP_OK;
+    (void)hipDeviceSynchronize();
+    for (void* p : b->allocs) (void)hipFree(p);
+    delete b;
+    return DSP_OK;
+}
+
+int dsp_block_input_slot(dsp_block* b, int64_t batch_id, void** d_slot)
+{
+    DSP_REQUIRE(b && d_slot && batch_id >= 0, DSP_EINVAL, "dsp_block_input_slot: bad argument");
+    *d_slot = b->ring + (size_t)(batch_id % b->ring_entries) * b->slot_bytes;
+    return DSP_OK;
+}
+
+int dsp_block_forward(dsp_block* b, int64_t batch_id, const void* d_in, void* d_out, const int32_t* d_labels,
+                      float* d_loss, void* stream)
+{
+    DSP_REQUIRE(b && d_in, DSP_EINVAL, "dsp_block_forward: null argument");
+    hipStream_t st = (hipStream_t)stream;
+    const int m = b->desc.m_k;
+    DSP_REQUIRE(batch_id == b->next_fwd, DSP_ESTATE, "dsp_block_forward: expected mini-batch %lld, got %lld",
+                (long long)b->next_fwd, (long long)batch_id);
+    const int64_t due = batch_id - m;  // backward that must have been done before this forward
+    DSP_REQUIRE(!b->pending && b->next_bwd == (due > 0 ? due : 0), DSP_ESTATE,
+                "dsp_block_forward: the previous tick's backward/update has not been issued");
+    DSP_REQUIRE(b->loss_idx < 0 || d_labels, DSP_EINVAL, "dsp_block_forward: the last block needs labels");
+    const int slot = (int)(batch_id % b->ring_entries);
+    void* slot_ptr = b->ring + (size_t)slot * b->slot_bytes;
+    if (d_in != slot_ptr)
+        DSP_HIP(hipMemcpyAsync(slot_ptr, d_in, b->input.elems * dtype_size(b->dtype), hipMemcpyDeviceToDevice, st));
+    b->slot_version[slot] = b->version;
+    float* dz = b->loss_idx >= 0 ? b->dz_ring + (size_t)(batch_id % (1 + m)) * b->dz_elems : nullptr;
+    float* loss = d_loss ? d_loss : b->loss_sink;
+    const Tensor& o = b->T[b->out_idx];
+    if (m == 0) {
+        // this forward is also the "recompute" of the backward that follows: keep everything
+        DSP_TRY(run_forward(b, slot_ptr, nullptr, d_labels, loss, dz, st));
+        if (d_out) DSP_HIP(hipMemcpyAsync(d_out, o.act, o.bytes(b->dtype), hipMemcpyDeviceToDevice, st));
+    } else {
+        DSP_TRY(run_forward(b, slot_ptr, d_out, d_labels, loss, dz, st));
+    }
+    b->next_fwd = batch_id + 1;
+    return DSP_OK;
+}
+
+int dsp_block_recompute_backward(dsp_block* b, int64_t batch_id, const void* d_grad_out, void* d_grad_in, void* stream)
+{
+    DSP_REQUIRE(b, DSP_EINVAL, "dsp_block_recompute_backward: null block");
+    hipStream_t st = (hipStream_t)stream;
+    const int m = b->desc.m_k;
+    DSP_REQUIRE(!b->pending && batch_id == b->next_bwd && batch_id == b->next_fwd - 1 - m, DSP_ESTATE,
+                "dsp_block_recompute_backward: mini-batch %lld is not due (next backward %lld, latest forward %lld, m_k %d)",
+                (long long)batch_id, (long long)b->next_bwd, (long long)b->next_fwd - 1, m);
+    DSP_REQUIRE(b->loss_idx >= 0 || d_grad_out, DSP_EINVAL, "dsp_block_recompute_backward: no error gradient");
+    DSP_REQUIRE(!b->desc.needs_input_grad || d_grad_in, DSP_EINVAL, "dsp_block_recompute_backward: no room for G_h");
+    const int slot = (int)(batch_id % b->ring_entries);
+    void* slot_ptr = b->ring + (size_t)slot * b->slot_bytes;
+    const void* gout = d_grad_out;
+    if (b->loss_idx >= 0 && !d_grad_out) gout = b->dz_ring + (size_t)(batch_id % (1 + m)) * b->dz_elems;
+    if (m > 0) DSP_TRY(run_forward(b, slot_ptr, nullptr, nullptr, b->loss_sink, nullptr, st));
+    DSP_TRY(run_backward(b, slot_ptr, gout, d_grad_in, st));
+    b->next_bwd = batch_id + 1;
+    b->pending = true;
+    return DSP_OK;
+}
+
+int dsp_param_update(dsp_block* b, float lr, float momentum, float weight_decay, void* stream)
+{
+    DSP_REQUIRE(b, DSP_EINVAL, "dsp_param_update: null block");
+    DSP_REQUIRE(b->pending, DSP_ESTATE, "dsp_param_update: no pending gradient");
+    DSP_TRY(launch_sgd_update(b->dtype, b->x, b->v, b->g, b->decay, b->tmap, b->wf16, b->wt, b->nP, lr, momentum,
+                              weight_decay, (hipStream_t)stream));
+    b->pending = false;
+    b->version += 1;
+    return DSP_OK;
+}
+
+int dsp_block_query(const dsp_block* b, int64_t out[8])
+{
+    DSP_REQUIRE(b && out, DSP_EINVAL, "dsp_block_query: null argument");
+    out[0] = b->version;
+    out[1] = b->next_fwd;
+    out[2] = b->next_bwd;
+    out[3] = b->ring_entries;
+    out[4] = b->pending ? 1 : 0;
+    out[5] = (int64_t)b->nP;
+    const bool stored = b->next_bwd < b->next_fwd;
+    const int slot = (int)(b->next_bwd % b->ring_entries);
+    out[6] = stored ? b->slot_version[slot] : -1;
+    out[7] = stored ? slot : -1;
+    return DSP_OK;
+}
+
+int dsp_block_output_shape(const dsp_block* b, int32_t out[5])
+{
+    DSP_REQUIRE(b && out, DSP_EINVAL, "dsp_block_output_shape: null argument");
+    const Tensor& o = b->T[b->out_idx];
+    out[0] = o.N; out[1] = o.C; out[2] = o.H; out[3] = o.W; out[4] = o.is_float ? 1 : 0;
+    return DSP_OK;
+}
+
+int dsp_block_input_shape(const dsp_block* b, int32_t out[5])
+{
+    DSP_REQUIRE(b && out, DSP_EINVAL, "dsp_block_input_shape: null argument");
+    out[0] = b->input.N; out[1] = b->input.C; out[2] = b->input.H; out[3] = b->input.W; out[4] = b->dtype;
+    return DSP_OK;
+}
+
+int dsp_block_memory(const dsp_block* b, size_t* ring_bytes, size_t* workspace_bytes, size_t* param_bytes)
+{
+    DSP_REQUIRE(b, DSP_EINVAL, "dsp_block_memory: null block");
+    if (ring_bytes) *ring_bytes = b->ring_bytes;
+    if (workspace_bytes) *workspace_bytes = b->ws_bytes;
+    if (param_bytes) *param_bytes = b->param_bytes;
+    return DSP_OK;
+}
+
+int dsp_block_get_params(dsp_block* b, float* h_dst, size_t n)
+{
+    DSP_REQUIRE(b && h_dst && n == b->nP, DSP_EINVAL, "dsp_block_get_params: bad argument");
+    return download_params(b, b->x, h_dst);
+}
+int dsp_block_set_params(dsp_block* b, const float* h_src, size_t n)
+{
+    DSP_REQUIRE(b && h_src && n == b->nP, DSP_EINVAL, "dsp_block_set_params: bad argument");
+    DSP_HIP(hipDeviceSynchronize());
+    DSP_TRY(upload_params(b, h_src, b->x));
+    DSP_TRY(launch_refresh_shadows(b->dtype, b->x, b->tmap, b->wf16, b->wt, b->nP, nullptr));
+    DSP_HIP(hipDeviceSynchronize());
+    return DSP_OK;
+}
+int dsp_block_get_momentum(dsp_block* b, float* h_dst, size_t n)
+{
+    DSP_REQUIRE(b && h_dst && n == b->nP, DSP_EINVAL, "dsp_block_get_momentum: bad argument");
+    return download_params(b, b->v, h_dst);
+}
+int dsp_block_set_momentum(dsp_block* b, const float* h_src, size_t n)
+{
+    DSP_REQUIRE(b && h_src && n == b->nP, DSP_EINVAL, "dsp_block_set_momentum: bad argument");
+    DSP_HIP(hipDeviceSynchronize());
+    return upload_params(b, h_src, b->v);
+}
+int dsp_block_get_grads(dsp_block* b, float* h_dst, size_t n)
+{
+    DSP_REQUIRE(b && h_dst && n == b->nP, DSP_EINVAL, "dsp_block_get_grads: bad argument");
+    return download_params(b, b->g, h_dst);
+}
+
+// ---- single-layer entry points ---------------------------------------------------------------------
+int dsp_conv_forward(int32_t dtype, const void* d_x, const void* d_w, void* d_y, int32_t N, int32_t H, int32_t W,
+                     int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride, int32_t pad, void* stream)
+{
+    DSP_REQUIRE(d_x && d_w && d_y && (dtype == DSP_FP32 || dtype == DSP_BF16), DSP_EINVAL, "dsp_conv_forward: bad argument");
+    DSP_REQUIRE(N > 0 && H > 0 && W > 0 && cin > 0 && cout > 0 && r > 0 && s > 0 && stride > 0 && pad >= 0, DSP_EINVAL,
+                "dsp_conv_forward: bad shape");
+    return launch_conv_forward(dtype, make_conv_shape(N, H, W, cin, cout, r, s, stride, pad), d_x, d_w, d_y, (hipStream_t)stream);
+}
+
+int dsp_conv_backward_data(int32_t dtype, const void* d_dy, const void* d_wt, void* d_dx, int32_t N, int32_t H,
+                           int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride, int32_t pad,
+                           int32_t accumulate, void* stream)
+{
+    DSP_REQUIRE(d_dy && d_wt && d_dx && (dtype == DSP_FP32 || dtype == DSP_BF16), DSP_EINVAL, "dsp_conv_backward_data: bad argument");
+    DSP_REQUIRE(N > 0 && H > 0 && W > 0 && cin > 0 && cout > 0 && r > 0 && s > 0 && stride > 0 && pad >= 0, DSP_EINVAL,
+                "dsp_conv_backward_data: bad shape");
+    return launch_conv_backward_data(dtype, make_conv_shape(N, H, W, cin, cout, r, s, stride, pad), d_dy, d_wt, d_dx,
+                                     accumulate != 0, (hipStream_t)stream);
+}
+
+int dsp_conv_backward_weight(int32_t dtype, const void* d_x, const void* d_dy, float* d_dw, int32_t N, int32_t H,
+                             int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride, int32_t pad,
+                             void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    DSP_REQUIRE(d_x && d_dy && d_dw && (dtype == DSP_FP32 || dtype == DSP_BF16), DSP_EINVAL, "dsp_conv_backward_weight: bad argument");
+    DSP_REQUIRE(N > 0 && H > 0 && W > 0 && cin > 0 && cout > 0 && r > 0 && s > 0 && stride > 0 && pad >= 0, DSP_EINVAL,
+                "dsp_conv_backward_weight: bad shape");
+    return launch_conv_backward_weight(dtype, make_conv_shape(N, H, W, cin, cout, r, s, stride, pad), d_x, d_dy, d_dw,
+                                       d_workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int dsp_conv_workspace_bytes(int32_t N, int32_t H, int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s,
+                             int32_t stride, int32_t pad, size_t* bytes)
+{
+    DSP_REQUIRE(bytes && N > 0 && H > 0 && W > 0 && cin > 0 && cout > 0 && r > 0 && s > 0 && stride > 0 && pad >= 0,
+                DSP_EINVAL, "dsp_conv_workspace_bytes: bad argument");
+    const ConvShape c = make_conv_shape(N, H, W, cin, cout, r, s, stride, pad);
+    DSP_REQUIRE(c.Ho > 0 && c.Wo > 0, DSP_EINVAL, "dsp_conv_workspace_bytes: empty output");
+    *bytes = conv_backward_weight_workspace(c);
+    return DSP_OK;
+}
+
+const char* dsp_strerror(int status)
+{
+    switch (status) {
+    case DSP_OK: return "ok";
+    case DSP_EINVAL: return "invalid argument, descriptor or schedule";
+    case DSP_ESTATE: return "call out of pipeline order";
+    case DSP_ENOMEM: return "out of memory";
+    case DSP_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+const char* dsp_last_error(void) { return dsp::g_err; }
+
+}  // extern "C"

@@ -1,0 +1,374 @@
+// Training-mode batch normalisation fused with the residual add and the ReLU that follow it,
+// forward and backward, on NHWC tensors x[M][C] (M = N*H*W rows, channels contiguous).
+//
+// These layers carry no reuse: each is a stream over HBM, so the kernels are built around
+// 16-byte coalesced row segments.  Thread t of a 256-thread workgroup owns the channel vector
+// (t mod CV) and walks rows t/CV, t/CV + RL, ...; per-channel sums are accumulated in fp64
+// registers (free in an HBM-bound kernel, and it removes the cancellation in E[x^2]-E[x]^2),
+// combined through LDS, written as one partial per workgroup, and merged by a one-wave-per-
+// channel kernel in a fixed order, so results are identical from run to run.
+//
+//   forward :  stats-partial -> finalize (mean, invstd, scale/shift) -> apply (+res, ReLU)
+//   backward:  reduce-partial (sum dz, sum dz*xhat) -> finalize (dgamma, dbeta, coefficients)
+//              -> apply (dx, and dz into the residual branch)
+#include "common.h"
+
+namespace dsp {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxPartialBlocks = 512;
+
+template <typename T, int VW>
+struct VecIO;
+
+template <>
+struct VecIO<float, 4> {
+    __device__ static inline void load(const float* p, float (&v)[4])
+    {
+        const float4 t = *(const float4*)p;
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    }
+    __device__ static inline void store(float* p, const float (&v)[4]) { *(float4*)p = make_float4(v[0], v[1], v[2], v[3]); }
+};
+template <>
+struct VecIO<float, 1> {
+    __device__ static inline void load(const float* p, float (&v)[1]) { v[0] = *p; }
+    __device__ static inline void store(float* p, const float (&v)[1]) { *p = v[0]; }
+};
+template <>
+struct VecIO<bf16_t, 8> {
+    __device__ static inline void load(const bf16_t* p, float (&v)[8])
+    {
+        const uint4 t = *(const uint4*)p;
+        const uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    __device__ static inline void store(bf16_t* p, const float (&v)[8])
+    {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            w[i] = (uint32_t)float_to_bf16(v[2 * i]).bits | ((uint32_t)float_to_bf16(v[2 * i + 1]).bits << 16);
+        *(uint4*)p = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+template <>
+struct VecIO<bf16_t, 1> {
+    __device__ static inline void load(const bf16_t* p, float (&v)[1]) { v[0] = bf16_to_float(*p); }
+    __device__ static inline void store(bf16_t* p, const float (&v)[1]) { *p = float_to_bf16(v[0]); }
+};
+
+// Layout of a workgroup over x[M][C]: CV channel vectors per row, RL row lanes.
+struct RowLayout {
+    int cv;   // channel vectors per row (C / VW)
+    int cvb;  // channel vectors handled by one workgroup column (min(cv, 256))
+    int rl;   // row lanes per workgroup (256 / cvb)
+};
+inline RowLayout make_layout(int C, int VW)
+{
+    RowLayout L;
+    L.cv = C / VW;
+    L.cvb = L.cv < kThreads ? L.cv : kThreads;
+    L.rl = kThreads / L.cvb;
+    return L;
+}
+
+// ---- per-channel sums ---------------------------------------------------------------------------
+// MODE 0: s0 = sum x, s1 = sum x^2.
+// MODE 1: dz = dy * [y > 0] (if RELU); s0 = sum dz, s1 = sum dz * (x - mean) * invstd.
+// part[blockIdx.x][c][2]; blockIdx.y walks channel groups when C/VW > 256.
+template <typename T, int VW, int MODE, bool RELU>
+__global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__ x, const T* __restrict__ dy,
+                                                           const T* __restrict__ y, const float* __restrict__ mean,
+                                                           const float* __restrict__ invstd, double* __restrict__ part,
+                                                           int64_t M, int C, RowLayout L, int rows_per_block)
+{
+    __shared__ double red[kThreads][2];
+    const int tid = threadIdx.x;
+    const int cvi = blockIdx.y * L.cvb + tid % L.cvb;
+    const int rlane = tid / L.cvb;
+    const bool active = rlane < L.rl && cvi < L.cv;
+    const int c0 = cvi * VW;
+    double s0[VW], s1[VW];
+#pragma unroll
+    for (int i = 0; i < VW; ++i) s0[i] = s1[i] = 0.0;
+    float mu[VW], is[VW];
+    if (MODE == 1 && active) {
+#pragma unroll
+        for (int i = 0; i < VW; ++i) {
+            mu[i] = mean[c0 + i];
+            is[i] = invstd[c0 + i];
+        }
+    }
+    const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
+    const int64_t r_end = r_begin + rows_per_block < M ? r_begin + rows_per_block : M;
+    if (active) {
+        for (int64_t r = r_begin + rlane; r < r_end; r += L.rl) {
+            float xv[VW];
+            VecIO<T, VW>::load(x + r * C + c0, xv);
+            if (MODE == 0) {
+#pragma unroll
+                for (int i = 0; i < VW; ++i) {
+                    s0[i] += (double)xv[i];
+                    s1[i] += (double)xv[i] * (double)xv[i];
+                }
+            } else {
+                float gv[VW], yv[VW];
+                VecIO<T, VW>::load(dy + r * C + c0, gv);
+                if (RELU) VecIO<T, VW>::load(y + r * C + c0, yv);
+#pragma unroll
+                for (int i = 0; i < VW; ++i) {
+                    const float dz = (!RELU || yv[i] > 0.f) ? gv[i] : 0.f;
+                    s0[i] += (double)dz;
+                    s1[i] += (double)(dz * ((xv[i] - mu[i]) * is[i]));
+                }
+            }
+        }
+    }
+    // combine the row lanes of each channel vector (fixed order), one channel of the vector at a time
+#pragma unroll
+    for (int i = 0; i < VW; ++i) {
+        red[tid][0] = s0[i];
+        red[tid][1] = s1[i];
+        __syncthreads();
+        if (active && rlane == 0) {
+            double a = 0.0, b = 0.0;
+            for (int k = 0; k < L.rl; ++k) {
+                a += red[k * L.cvb + tid][0];
+                b += red[k * L.cvb + tid][1];
+            }
+            double* dst = part + ((int64_t)blockIdx.x * C + c0 + i) * 2;
+            dst[0] = a;
+            dst[1] = b;
+        }
+        __syncthreads();
+    }
+}
+
+__device__ inline double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;
+}
+
+// One wave per channel merges the partials.  Forward: mean, invstd, coef = {scale, shift}.
+__global__ __launch_bounds__(64) void bn_fwd_finalize_kernel(const double* __restrict__ part, int nblk, int C,
+                                                             double inv_M, float eps, const float* __restrict__ gamma,
+                                                             const float* __restrict__ beta, float* __restrict__ mean,
+                                                             float* __restrict__ invstd, float* __restrict__ coef)
+{
+    const int c = blockIdx.x, lane = threadIdx.x;
+    double a = 0.0, b = 0.0;
+    for (int k = lane; k < nblk; k += 64) {
+        a += part[((int64_t)k * C + c) * 2];
+        b += part[((int64_t)k * C + c) * 2 + 1];
+    }
+    a = wave_sum(a);
+    b = wave_sum(b);
+    if (lane == 0) {
+        const double mu = a * inv_M;
+        double var = b * inv_M - mu * mu;
+        if (var < 0.0) var = 0.0;
+        const double is = 1.0 / sqrt(var + (double)eps);
+        mean[c] = (float)mu;
+        invstd[c] = (float)is;
+        const double sc = (double)gamma[c] * is;
+        coef[c] = (float)sc;
+        coef[C + c] = (float)((double)beta[c] - mu * sc);
+    }
+}
+
+// Backward: dgamma, dbeta and dx = c1*dz - c2*x + c0 with
+// c1 = gamma*invstd, c2 = c1*invstd*dgamma/M, c0 = c2*mean - c1*dbeta/M.
+__global__ __launch_bounds__(64) void bn_bwd_finalize_kernel(const double* __restrict__ part, int nblk, int C,
+                                                             double inv_M, const float* __restrict__ gamma,
+                                                             const float* __restrict__ mean,
+                                                             const float* __restrict__ invstd, float* __restrict__ dgamma,
+                                                             float* __restrict__ dbeta, float* __restrict__ coef)
+{
+    const int c = blockIdx.x, lane = threadIdx.x;
+    double a = 0.0, b = 0.0;
+    for (int k = lane; k < nblk; k += 64) {
+        a += part[((int64_t)k * C + c) * 2];
+        b += part[((int64_t)k * C + c) * 2 + 1];
+    }
+    a = wave_sum(a);
+    b = wave_sum(b);
+    if (lane == 0) {
+        dbeta[c] = (float)a;
+        dgamma[c] = (float)b;
+        const double c1 = (double)gamma[c] * (double)invstd[c];
+        const double c2 = c1 * (double)invstd[c] * b * inv_M;
+        coef[c] = (float)c1;
+        coef[C + c] = (float)c2;
+        coef[2 * C + c] = (float)(c2 * (double)mean[c] - c1 * a * inv_M);
+    }
+}
+
+// y = [relu](scale*x + shift [+ res])
+template <typename T, int VW, bool RELU, bool HAS_RES>
+__global__ __launch_bounds__(kThreads) void bn_fwd_apply_kernel(const T* __restrict__ x, const T* __restrict__ res,
+                                                                T* __restrict__ y, const float* __restrict__ coef,
+                                                                int64_t nvec, int C, int cv)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * kThreads) {
+        const int c0 = (int)(i % cv) * VW;
+        float xv[VW], rv[VW], ov[VW];
+        VecIO<T, VW>::load(x + i * VW, xv);
+        if (HAS_RES) VecIO<T, VW>::load(res + i * VW, rv);
+#pragma unroll
+        for (int k = 0; k < VW; ++k) {
+            float v = xv[k] * coef[c0 + k] + coef[C + c0 + k];
+            if (HAS_RES) v += rv[k];
+            if (RELU) v = v > 0.f ? v : 0.f;
+            ov[k] = v;
+        }
+        VecIO<T, VW>::store(y + i * VW, ov);
+    }
+}
+
+// dz = dy*[y>0];  dx (+)= c1*dz - c2*x + c0;  dres (+)= dz
+template <typename T, int VW, bool RELU, bool HAS_RES, bool RES_ACC, bool DX_ACC>
+__global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                                const T* __restrict__ y, T* __restrict__ dx,
+                                                                T* __restrict__ dres, const float* __restrict__ coef,
+                                                                int64_t nvec, int C, int cv)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * kThreads) {
+        const int c0 = (int)(i % cv) * VW;
+        float gv[VW], xv[VW], yv[VW], ov[VW], rv[VW];
+        VecIO<T, VW>::load(dy + i * VW, gv);
+        VecIO<T, VW>::load(x + i * VW, xv);
+        if (RELU) VecIO<T, VW>::load(y + i * VW, yv);
+        if (DX_ACC) VecIO<T, VW>::load(dx + i * VW, ov);
+        if (HAS_RES && RES_ACC) VecIO<T, VW>::load(dres + i * VW, rv);
+#pragma unroll
+        for (int k = 0; k < VW; ++k) {
+            const float dz = (!RELU || yv[k] > 0.f) ? gv[k] : 0.f;
+            const float d = coef[c0 + k] * dz - coef[C + c0 + k] * xv[k] + coef[2 * C + c0 + k];
+            ov[k] = DX_ACC ? ov[k] + d : d;
+            if (HAS_RES) rv[k] = RES_ACC ? rv[k] + dz : dz;
+        }
+        VecIO<T, VW>::store(dx + i * VW, ov);
+        if (HAS_RES) VecIO<T, VW>::store(dres + i * VW, rv);
+    }
+}
+
+int plan_rows(int64_t M, const RowLayout& L, int* nblk)
+{
+    // every thread should see >= 8 rows; at most kMaxPartialBlocks workgroups
+    int64_t rows = (int64_t)L.rl * 8;
+    int64_t blocks = (M + rows - 1) / rows;
+    if (blocks > kMaxPartialBlocks) {
+        blocks = kMaxPartialBlocks;
+        rows = (M + blocks - 1) / blocks;
+        blocks = (M + rows - 1) / rows;
+    }
+    *nblk = (int)blocks;
+    return (int)rows;
+}
+
+inline int apply_grid(int64_t nvec)
+{
+    int64_t g = (nvec + kThreads - 1) / kThreads;
+    const int64_t cap = 256 * 16;
+    return (int)(g < cap ? (g < 1 ? 1 : g) : cap);
+}
+
+template <typename T, int VW>
+int bn_forward_t(const void* x, const void* res, void* y, const float* gamma, const float* beta, float eps, int64_t M,
+                 int C, bool relu, const BnBuffers& buf, hipStream_t st)
+{
+    const RowLayout L = make_layout(C, VW);
+    int nblk;
+    const int rows = plan_rows(M, L, &nblk);
+    const dim3 grid(nblk, ceil_div(L.cv, L.cvb));
+    hipLaunchKernelGGL((bn_sums_kernel<T, VW, 0, false>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)nullptr,
+                       (const T*)nullptr, (const float*)nullptr, (const float*)nullptr, buf.partial, M, C, L, rows);
+    hipLaunchKernelGGL(bn_fwd_finalize_kernel, dim3(C), dim3(64), 0, st, (const double*)buf.partial, nblk, C,
+                       1.0 / (double)M, eps, gamma, beta, buf.mean, buf.invstd, buf.coef);
+    const int64_t nvec = M * (C / VW);
+    const dim3 ag(apply_grid(nvec));
+#define BN_APPLY(R, H)                                                                                             \
+    hipLaunchKernelGGL((bn_fwd_apply_kernel<T, VW, R, H>), ag, dim3(kThreads), 0, st, (const T*)x, (const T*)res, \
+                       (T*)y, (const float*)buf.coef, nvec, C, L.cv)
+    if (relu) {
+        if (res) BN_APPLY(true, true); else BN_APPLY(true, false);
+    } else {
+        if (res) BN_APPLY(false, true); else BN_APPLY(false, false);
+    }
+#undef BN_APPLY
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+template <typename T, int VW, bool RELU>
+int bn_backward_t(const void* dy, const void* x, const void* y, void* dx, void* dres, bool racc, bool xacc,
+                  const float* gamma, float* dgamma, float* dbeta, int64_t M, int C, const BnBuffers& buf, hipStream_t st)
+{
+    const RowLayout L = make_layout(C, VW);
+    int nblk;
+    const int rows = plan_rows(M, L, &nblk);
+    const dim3 grid(nblk, ceil_div(L.cv, L.cvb));
+    hipLaunchKernelGGL((bn_sums_kernel<T, VW, 1, RELU>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)dy,
+                       (const T*)y, (const float*)buf.mean, (const float*)buf.invstd, buf.partial, M, C, L, rows);
+    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(C), dim3(64), 0, st, (const double*)buf.partial, nblk, C,
+                       1.0 / (double)M, gamma, (const float*)buf.mean, (const float*)buf.invstd, dgamma, dbeta, buf.coef);
+    const int64_t nvec = M * (C / VW);
+    const dim3 ag(apply_grid(nvec));
+#define BN_BAPPLY(H, RA, XA)                                                                                      \
+    hipLaunchKernelGGL((bn_bwd_apply_kernel<T, VW, RELU, H, RA, XA>), ag, dim3(kThreads), 0, st, (const T*)dy,   \
+                       (const T*)x, (const T*)y, (T*)dx, (T*)dres, (const float*)buf.coef, nvec, C, L.cv)
+    if (dres) {
+        if (racc) { if (xacc) BN_BAPPLY(true, true, true); else BN_BAPPLY(true, true, false); }
+        else      { if (xacc) BN_BAPPLY(true, false, true); else BN_BAPPLY(true, false, false); }
+    } else {
+        if (xacc) BN_BAPPLY(false, false, true); else BN_BAPPLY(false, false, false);
+    }
+#undef BN_BAPPLY
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+}  // namespace
+
+int bn_max_partial_blocks() { return kMaxPartialBlocks; }
+
+int launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
+                      float eps, int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st)
+{
+    DSP_REQUIRE(M > 0 && C > 0, DSP_EINVAL, "bn: bad shape");
+    if (dtype == DSP_BF16) {
+        if (C % 8 == 0) return bn_forward_t<bf16_t, 8>(x, res, y, gamma, beta, eps, M, C, relu, buf, st);
+        return bn_forward_t<bf16_t, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st);
+    }
+    if (C % 4 == 0) return bn_forward_t<float, 4>(x, res, y, gamma, beta, eps, M, C, relu, buf, st);
+    return bn_forward_t<float, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st);
+}
+
+int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, void* dx, void* dres,
+                       bool dres_accumulate, bool dx_accumulate, const float* gamma, float* dgamma, float* dbeta,
+                       int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st)
+{
+    DSP_REQUIRE(M > 0 && C > 0, DSP_EINVAL, "bn: bad shape");
+#define BN_BWD(T, VW)                                                                                              \
+    (relu ? bn_backward_t<T, VW, true>(dy, x, y, dx, dres, dres_accumulate, dx_accumulate, gamma, dgamma, dbeta, M, \
+                                       C, buf, st)                                                                 \
+          : bn_backward_t<T, VW, false>(dy, x, y, dx, dres, dres_accumulate, dx_accumulate, gamma, dgamma, dbeta,  \
+                                        M, C, buf, st))
+    if (dtype == DSP_BF16) {
+        if (C % 8 == 0) return BN_BWD(bf16_t, 8);
+        return BN_BWD(bf16_t, 1);
+    }
+    if (C % 4 == 0) return BN_BWD(float, 4);
+    return BN_BWD(float, 1);
+#undef BN_BWD
+}
+
+}  // namespace dsp

@@ -1,0 +1,155 @@
+// Shared declarations of the gfx950 DSP library: status/error plumbing, storage types,
+// bf16 conversion, and the launch interface between the host engine and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/dsp.h"
+
+namespace dsp {
+
+// ---- error plumbing ---------------------------------------------------------------------------
+void set_error(const char* fmt, ...);
+
+#define DSP_HIP(call)                                                                      \
+    do {                                                                                   \
+        hipError_t e__ = (call);                                                           \
+        if (e__ != hipSuccess) {                                                           \
+            ::dsp::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e__), __FILE__, __LINE__); \
+            return DSP_EHIP;                                                               \
+        }                                                                                  \
+    } while (0)
+
+#define DSP_TRY(call)                   \
+    do {                                \
+        int s__ = (call);               \
+        if (s__ != DSP_OK) return s__;  \
+    } while (0)
+
+#define DSP_REQUIRE(cond, status, ...)  \
+    do {                                \
+        if (!(cond)) {                  \
+            ::dsp::set_error(__VA_ARGS__); \
+            return (status);            \
+        }                               \
+    } while (0)
+
+// ---- storage types ----------------------------------------------------------------------------
+// bfloat16 is kept as its raw 16 bits; conversion is round-to-nearest-even (NaN stays NaN).
+struct bf16_t {
+    uint16_t bits;
+};
+
+__host__ __device__ inline float bf16_to_float(bf16_t v)
+{
+    union {
+        uint32_t u;
+        float f;
+    } c;
+    c.u = (uint32_t)v.bits << 16;
+    return c.f;
+}
+
+__host__ __device__ inline bf16_t float_to_bf16(float f)
+{
+    union {
+        uint32_t u;
+        float f;
+    } c;
+    c.f = f;
+    bf16_t r;
+    if ((c.u & 0x7fffffffu) > 0x7f800000u) {  // NaN
+        r.bits = (uint16_t)((c.u >> 16) | 0x40u);
+        return r;
+    }
+    c.u += 0x7fffu + ((c.u >> 16) & 1u);
+    r.bits = (uint16_t)(c.u >> 16);
+    return r;
+}
+
+template <typename T>
+__host__ __device__ inline float to_float(T v);
+template <>
+__host__ __device__ inline float to_float<float>(float v) { return v; }
+template <>
+__host__ __device__ inline float to_float<bf16_t>(bf16_t v) { return bf16_to_float(v); }
+
+template <typename T>
+__host__ __device__ inline T from_float(float v);
+template <>
+__host__ __device__ inline float from_float<float>(float v) { return v; }
+template <>
+__host__ __device__ inline bf16_t from_float<bf16_t>(float v) { return float_to_bf16(v); }
+
+inline size_t dtype_size(int dtype) { return dtype == DSP_BF16 ? 2 : 4; }
+
+inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+// ---- convolution launchers (conv_igemm.hip) -------------------------------------------------
+// Geometry of one convolution y = conv(x, w): x is N x H x W x Cin (NHWC), y is N x Ho x Wo x Cout.
+struct ConvShape {
+    int N, H, W, Cin, Cout, R, S, stride, pad, Ho, Wo;
+};
+
+inline ConvShape make_conv_shape(int N, int H, int W, int Cin, int Cout, int R, int S, int stride, int pad)
+{
+    ConvShape c{N, H, W, Cin, Cout, R, S, stride, pad, 0, 0};
+    c.Ho = (H + 2 * pad - R) / stride + 1;
+    c.Wo = (W + 2 * pad - S) / stride + 1;
+    return c;
+}
+
+// y = conv(x, w);  w in [Cout][R][S][Cin].
+int launch_conv_forward(int dtype, const ConvShape& c, const void* x, const void* w, void* y, hipStream_t st);
+// dx (+)= conv^T(dy, w);  wt in [Cin][R-1-r][S-1-s][Cout].
+int launch_conv_backward_data(int dtype, const ConvShape& c, const void* dy, const void* wt, void* dx,
+                              bool accumulate, hipStream_t st);
+// dw[Cout][R][S][Cin] (float) = sum over (n, ho, wo) of dy * x;  ws holds the split partials.
+int launch_conv_backward_weight(int dtype, const ConvShape& c, const void* x, const void* dy, float* dw, void* ws,
+                                size_t ws_bytes, hipStream_t st);
+size_t conv_backward_weight_workspace(const ConvShape& c);
+
+// ---- batch norm (+ residual + ReLU) launchers (bn.hip) ----------------------------------------
+struct BnBuffers {
+    double* partial;  // [max_blocks][C][2] partial sums
+    float* mean;      // [C]
+    float* invstd;    // [C]
+    float* coef;      // [3*C] per-channel coefficients handed from the reduce to the apply kernel
+};
+int bn_max_partial_blocks();
+// y = [relu]( gamma * (x - mean) * invstd + beta [+ res] ), statistics over the M rows of x[M][C].
+int launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
+                      float eps, int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st);
+// Backward of the map above given dy and the saved x, y, mean, invstd:
+// dz = dy * [y > 0]; dres (+)= dz; dgamma, dbeta; dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M).
+int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, void* dx, void* dres,
+                       bool dres_accumulate, bool dx_accumulate, const float* gamma, float* dgamma, float* dbeta,
+                       int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st);
+
+// ---- small layers and the update (misc.hip) ---------------------------------------------------
+int launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* argmax, int N, int H, int W, int C, int k,
+                           int stride, int pad, hipStream_t st);
+int launch_maxpool_backward(int dtype, const void* dy, const uint8_t* argmax, void* dx, bool accumulate, int N,
+                            int H, int W, int C, int k, int stride, int pad, hipStream_t st);
+int launch_gap_forward(int dtype, const void* x, float* y, int N, int HW, int C, hipStream_t st);
+int launch_gap_backward(int dtype, const float* dy, void* dx, bool accumulate, int N, int HW, int C,
+                        hipStream_t st);
+int launch_linear_forward(const float* x, const float* w, const float* bias, float* z, int N, int Cin, int Cout,
+                          hipStream_t st);
+int launch_linear_backward(const float* x, const float* w, const float* dz, float* dx, float* dw, float* dbias,
+                           int N, int Cin, int Cout, hipStream_t st);
+// loss = mean_n -log softmax(z_n)[label_n];  dz = (softmax - onehot) / N;  row_loss is scratch [N].
+int launch_softmax_ce(const float* z, const int32_t* labels, float* loss, float* dz, float* row_loss, int N,
+                      int C, hipStream_t st);
+// v <- momentum*v + (g + wd*x*[decay]);  x <- x - lr*v;  shadow copies refreshed in the same pass:
+// wf16[i] = bf16(x[i]) if wf16 != nullptr;  wt[tmap[i]] = T(x[i]) where tmap[i] >= 0.
+int launch_sgd_update(int dtype, float* x, float* v, const float* g, const uint8_t* decay, const int32_t* tmap,
+                      void* wf16, void* wt, size_t n, float lr, float momentum, float wd, hipStream_t st);
+// Same shadow refresh without an update (after init / set_params).
+int launch_refresh_shadows(int dtype, const float* x, const int32_t* tmap, void* wf16, void* wt, size_t n,
+                           hipStream_t st);
+int launch_spin(int microseconds, hipStream_t st);
+
+}  // namespace dsp

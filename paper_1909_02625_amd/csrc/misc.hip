@@ -1,0 +1,332 @@
+// Small layers that close the loop of a block (max-pool, global average pool, linear head,
+// softmax cross-entropy) and the fused momentum-SGD update.  None of them is a contraction worth
+// the matrix cores; they are written as coalesced NHWC streams.
+#include "common.h"
+
+namespace dsp {
+namespace {
+
+constexpr int kThreads = 256;
+
+inline int grid_for(int64_t n, int cap = 256 * 32)
+{
+    int64_t g = (n + kThreads - 1) / kThreads;
+    if (g < 1) g = 1;
+    return (int)(g < cap ? g : cap);
+}
+
+// ---- max pool ------------------------------------------------------------------------------------
+// Window scan in row-major order, strict ">" so the first maximum wins; argmax keeps r*k+s.
+template <typename T>
+__global__ void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, uint8_t* __restrict__ arg, int N, int H,
+                                   int W, int C, int Ho, int Wo, int k, int stride, int pad)
+{
+    const int64_t total = (int64_t)N * Ho * Wo * C;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
+        const int c = (int)(i % C);
+        int64_t t = i / C;
+        const int wo = (int)(t % Wo);
+        t /= Wo;
+        const int ho = (int)(t % Ho), n = (int)(t / Ho);
+        float best = -INFINITY;
+        int a = 255;
+        for (int r = 0; r < k; ++r)
+            for (int s = 0; s < k; ++s) {
+                const int hi = ho * stride + r - pad, wi = wo * stride + s - pad;
+                if (hi < 0 || hi >= H || wi < 0 || wi >= W) continue;
+                const float v = to_float<T>(x[(((int64_t)n * H + hi) * W + wi) * C + c]);
+                if (v > best) { best = v; a = r * k + s; }
+            }
+        y[i] = from_float<T>(best);
+        if (arg) arg[i] = (uint8_t)a;
+    }
+}
+
+// dx[n,hi,wi,c] (+)= sum of dy over the windows whose recorded argmax is this pixel.
+template <typename T, bool ACC>
+__global__ void maxpool_bwd_kernel(const T* __restrict__ dy, const uint8_t* __restrict__ arg, T* __restrict__ dx, int N,
+                                   int H, int W, int C, int Ho, int Wo, int k, int stride, int pad)
+{
+    const int64_t total = (int64_t)N * H * W * C;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
+        const int c = (int)(i % C);
+        int64_t t = i / C;
+        const int wi = (int)(t % W);
+        t /= W;
+        const int hi = (int)(t % H), n = (int)(t / H);
+        float s = 0.f;
+        for (int r = 0; r < k; ++r) {
+            const int hn = hi + pad - r;
+            if (hn < 0 || hn % stride) continue;
+            const int ho = hn / stride;
+            if (ho >= Ho) continue;
+            for (int q = 0; q < k; ++q) {
+                const int wn = wi + pad - q;
+                if (wn < 0 || wn % stride) continue;
+                const int wo = wn / stride;
+                if (wo >= Wo) continue;
+                const int64_t o = (((int64_t)n * Ho + ho) * Wo + wo) * C + c;
+                if (arg[o] == r * k + q) s += to_float<T>(dy[o]);
+            }
+        }
+        dx[i] = from_float<T>(ACC ? to_float<T>(dx[i]) + s : s);
+    }
+}
+
+// ---- global average pool ------------------------------------------------------------------------
+template <typename T>
+__global__ void gap_fwd_kernel(const T* __restrict__ x, float* __restrict__ y, int N, int HW, int C)
+{
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= N * C) return;
+    const int n = i / C, c = i % C;
+    float s = 0.f;
+    for (int p = 0; p < HW; ++p) s += to_float<T>(x[((int64_t)n * HW + p) * C + c]);
+    y[i] = s / (float)HW;
+}
+
+template <typename T, bool ACC>
+__global__ void gap_bwd_kernel(const float* __restrict__ dy, T* __restrict__ dx, int N, int HW, int C)
+{
+    const int64_t total = (int64_t)N * HW * C;
+    const float inv = 1.f / (float)HW;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
+        const int c = (int)(i % C), n = (int)(i / ((int64_t)HW * C));
+        const float g = dy[n * C + c] * inv;
+        dx[i] = from_float<T>(ACC ? to_float<T>(dx[i]) + g : g);
+    }
+}
+
+// ---- linear head (fp32) ----------------------------------------------------------------------------
+__global__ void linear_fwd_kernel(const float* __restrict__ x, const float* __restrict__ w,
+                                  const float* __restrict__ bias, float* __restrict__ z, int N, int Cin, int Cout)
+{
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= N * Cout) return;
+    const int n = i / Cout, j = i % Cout;
+    float s = 0.f;
+    for (int c = 0; c < Cin; ++c) s += x[n * Cin + c] * w[j * Cin + c];
+    z[i] = s + bias[j];
+}
+
+// dx[n][c] = sum_j dz[n][j] w[j][c]
+__global__ void linear_bwd_x_kernel(const float* __restrict__ dz, const float* __restrict__ w, float* __restrict__ dx,
+                                    int N, int Cin, int Cout)
+{
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= N * Cin) return;
+    const int n = i / Cin, c = i % Cin;
+    float s = 0.f;
+    for (int j = 0; j < Cout; ++j) s += dz[n * Cout + j] * w[j * Cin + c];
+    dx[i] = s;
+}
+
+// dw[j][c] = sum_n dz[n][j] x[n][c];  dbias[j] = sum_n dz[n][j]
+__global__ void linear_bwd_w_kernel(const float* __restrict__ dz, const float* __restrict__ x, float* __restrict__ dw,
+                                    float* __restrict__ dbias, int N, int Cin, int Cout)
+{
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= Cout * (Cin + 1)) return;
+    const int j = i / (Cin + 1), c = i % (Cin + 1);
+    float s = 0.f;
+    if (c < Cin) {
+        for (int n = 0; n < N; ++n) s += dz[n * Cout + j] * x[n * Cin + c];
+        dw[j * Cin + c] = s;
+    } else {
+        for (int n = 0; n < N; ++n) s += dz[n * Cout + j];
+        dbias[j] = s;
+    }
+}
+
+// ---- softmax cross-entropy --------------------------------------------------------------------------
+// One wave per sample: max, sum of exponentials, loss_n = log(sum) - (z_label - max),
+// dz = (softmax - onehot)/N.  The mean over samples is taken by a second single-wave kernel.
+__global__ __launch_bounds__(64) void softmax_ce_rows_kernel(const float* __restrict__ z,
+                                                             const int32_t* __restrict__ labels,
+                                                             float* __restrict__ row_loss, float* __restrict__ dz, int N,
+                                                             int C)
+{
+    const int n = blockIdx.x, lane = threadIdx.x;
+    const float* zr = z + (int64_t)n * C;
+    float mx = -INFINITY;
+    for (int c = lane; c < C; c += 64) mx = fmaxf(mx, zr[c]);
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    float se = 0.f;
+    for (int c = lane; c < C; c += 64) se += expf(zr[c] - mx);
+    for (int off = 32; off > 0; off >>= 1) se += __shfl_xor(se, off, 64);
+    const int lab = labels[n];
+    const float inv_n = 1.f / (float)N;
+    for (int c = lane; c < C; c += 64) {
+        const float p = expf(zr[c] - mx) / se;
+        dz[(int64_t)n * C + c] = (p - (c == lab ? 1.f : 0.f)) * inv_n;
+    }
+    // a label outside [0, C) never indexes memory: its sample contributes NaN to the loss
+    if (lane == 0) row_loss[n] = (lab >= 0 && lab < C) ? logf(se) - (zr[lab] - mx) : NAN;
+}
+
+__global__ __launch_bounds__(64) void mean_kernel(const float* __restrict__ v, float* __restrict__ out, int n)
+{
+    const int lane = threadIdx.x;
+    double s = 0.0;
+    for (int i = lane; i < n; i += 64) s += (double)v[i];
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+    if (lane == 0) *out = (float)(s / (double)n);
+}
+
+// ---- momentum SGD + shadow refresh ---------------------------------------------------------------
+template <typename TS, bool UPDATE>
+__global__ void sgd_update_kernel(float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
+                                  const uint8_t* __restrict__ decay, const int32_t* __restrict__ tmap,
+                                  bf16_t* __restrict__ wf16, TS* __restrict__ wt, size_t n, float lr, float momentum,
+                                  float wd)
+{
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (size_t)gridDim.x * kThreads) {
+        float xi = x[i];
+        if (UPDATE) {
+            float gi = g[i];
+            if (wd != 0.f && decay[i]) gi += wd * xi;
+            const float vi = momentum * v[i] + gi;
+            v[i] = vi;
+            xi -= lr * vi;
+            x[i] = xi;
+        }
+        if (wf16) wf16[i] = float_to_bf16(xi);
+        const int32_t t = tmap[i];
+        if (t >= 0) wt[t] = from_float<TS>(xi);
+    }
+}
+
+__global__ void spin_kernel(long long cycles)
+{
+    const long long t0 = wall_clock64();
+    while (wall_clock64() - t0 < cycles) {}
+}
+
+}  // namespace
+
+int launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* argmax, int N, int H, int W, int C, int k,
+                           int stride, int pad, hipStream_t st)
+{
+    DSP_REQUIRE(k * k < 255, DSP_EINVAL, "maxpool: window too large");
+    const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
+    const int64_t total = (int64_t)N * Ho * Wo * C;
+    if (dtype == DSP_BF16)
+        hipLaunchKernelGGL(maxpool_fwd_kernel<bf16_t>, dim3(grid_for(total)), dim3(kThreads), 0, st, (const bf16_t*)x,
+                           (bf16_t*)y, argmax, N, H, W, C, Ho, Wo, k, stride, pad);
+    else
+        hipLaunchKernelGGL(maxpool_fwd_kernel<float>, dim3(grid_for(total)), dim3(kThreads), 0, st, (const float*)x,
+                           (float*)y, argmax, N, H, W, C, Ho, Wo, k, stride, pad);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+int launch_maxpool_backward(int dtype, const void* dy, const uint8_t* argmax, void* dx, bool accumulate, int N,
+                            int H, int W, int C, int k, int stride, int pad, hipStream_t st)
+{
+    const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
+    const int64_t total = (int64_t)N * H * W * C;
+#define MP_BWD(T, A)                                                                                            \
+    hipLaunchKernelGGL((maxpool_bwd_kernel<T, A>), dim3(grid_for(total)), dim3(kThreads), 0, st, (const T*)dy, \
+                       argmax, (T*)dx, N, H, W, C, Ho, Wo, k, stride, pad)
+    if (dtype == DSP_BF16) { if (accumulate) MP_BWD(bf16_t, true); else MP_BWD(bf16_t, false); }
+    else                   { if (accumulate) MP_BWD(float, true); else MP_BWD(float, false); }
+#undef MP_BWD
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+int launch_gap_forward(int dtype, const void* x, float* y, int N, int HW, int C, hipStream_t st)
+{
+    const dim3 grid(ceil_div((int64_t)N * C, kThreads));
+    if (dtype == DSP_BF16)
+        hipLaunchKernelGGL(gap_fwd_kernel<bf16_t>, grid, dim3(kThreads), 0, st, (const bf16_t*)x, y, N, HW, C);
+    else
+        hipLaunchKernelGGL(gap_fwd_kernel<float>, grid, dim3(kThreads), 0, st, (const float*)x, y, N, HW, C);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+int launch_gap_backward(int dtype, const float* dy, void* dx, bool accumulate, int N, int HW, int C, hipStream_t st)
+{
+    const int64_t total = (int64_t)N * HW * C;
+#define GAP_BWD(T, A) \
+    hipLaunchKernelGGL((gap_bwd_kernel<T, A>), dim3(grid_for(total)), dim3(kThreads), 0, st, dy, (T*)dx, N, HW, C)
+    if (dtype == DSP_BF16) { if (accumulate) GAP_BWD(bf16_t, true); else GAP_BWD(bf16_t, false); }
+    else                   { if (accumulate) GAP_BWD(float, true); else GAP_BWD(float, false); }
+#undef GAP_BWD
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+int launch_linear_forward(const float* x, const float* w, const float* bias, float* z, int N, int Cin, int Cout,
+                          hipStream_t st)
+{
+    hipLaunchKernelGGL(linear_fwd_kernel, dim3(ceil_div((int64_t)N * Cout, kThreads)), dim3(kThreads), 0, st, x, w, bias,
+                       z, N, Cin, Cout);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+int launch_linear_backward(const float* x, const float* w, const float* dz, float* dx, float* dw, float* dbias,
+                           int N, int Cin, int Cout, hipStream_t st)
+{
+    if (dx)
+        hipLaunchKernelGGL(linear_bwd_x_kernel, dim3(ceil_div((int64_t)N * Cin, kThreads)), dim3(kThreads), 0, st, dz, w,
+                           dx, N, Cin, Cout);
+    hipLaunchKernelGGL(linear_bwd_w_kernel, dim3(ceil_div((int64_t)Cout * (Cin + 1), kThreads)), dim3(kThreads), 0, st,
+                       dz, x, dw, dbias, N, Cin, Cout);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+int launch_softmax_ce(const float* z, const int32_t* labels, float* loss, float* dz, float* row_loss, int N, int C,
+                      hipStream_t st)
+{
+    hipLaunchKernelGGL(softmax_ce_rows_kernel, dim3(N), dim3(64), 0, st, z, labels, row_loss, dz, N, C);
+    hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(64), 0, st, (const float*)row_loss, loss, N);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+int launch_sgd_update(int dtype, float* x, float* v, const float* g, const uint8_t* decay, const int32_t* tmap,
+                      void* wf16, void* wt, size_t n, float lr, float momentum, float wd, hipStream_t st)
+{
+    if (n == 0) return DSP_OK;
+    const dim3 grid(grid_for((int64_t)n));
+    if (dtype == DSP_BF16)
+        hipLaunchKernelGGL((sgd_update_kernel<bf16_t, true>), grid, dim3(kThreads), 0, st, x, v, g, decay, tmap,
+                           (bf16_t*)wf16, (bf16_t*)wt, n, lr, momentum, wd);
+    else
+        hipLaunchKernelGGL((sgd_update_kernel<float, true>), grid, dim3(kThreads), 0, st, x, v, g, decay, tmap,
+                           (bf16_t*)nullptr, (float*)wt, n, lr, momentum, wd);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+int launch_refresh_shadows(int dtype, const float* x, const int32_t* tmap, void* wf16, void* wt, size_t n,
+                           hipStream_t st)
+{
+    if (n == 0) return DSP_OK;
+    const dim3 grid(grid_for((int64_t)n));
+    if (dtype == DSP_BF16)
+        hipLaunchKernelGGL((sgd_update_kernel<bf16_t, false>), grid, dim3(kThreads), 0, st, (float*)x, (float*)nullptr,
+                           (const float*)nullptr, (const uint8_t*)nullptr, tmap, (bf16_t*)wf16, (bf16_t*)wt, n, 0.f, 0.f,
+                           0.f);
+    else
+        hipLaunchKernelGGL((sgd_update_kernel<float, false>), grid, dim3(kThreads), 0, st, (float*)x, (float*)nullptr,
+                           (const float*)nullptr, (const uint8_t*)nullptr, tmap, (bf16_t*)nullptr, (float*)wt, n, 0.f,
+                           0.f, 0.f);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+int launch_spin(int microseconds, hipStream_t st)
+{
+    if (microseconds <= 0) return DSP_OK;
+    // wall_clock64 ticks at 100 MHz on this family
+    hipLaunchKernelGGL(spin_kernel, dim3(1), dim3(1), 0, st, (long long)microseconds * 100);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+}  // namespace dsp
