@@ -140,6 +140,15 @@ def maxpool_backward(dy, arg, x_shape):
     return dx
 
 
+def round_bf16(a):
+    """Nearest bfloat16 (8 exponent bits, 7 fraction bits; ties to even), returned as fp64."""
+    f = np.ascontiguousarray(a, dtype=np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+    out = r.astype(np.uint32).view(np.float32).astype(np.float64)
+    return np.where(np.isfinite(f), out, f.astype(np.float64)).reshape(np.shape(a))
+
+
 class SoftmaxCE:
     """L(h_K, l): mean over the mini-batch of -log softmax(h_K)[l]; returns (loss, dL/dh_K)."""
 
@@ -163,11 +172,25 @@ class CNNBlock:
     f_k: it is the loss L and is handled by the pipeline.
     """
 
-    def __init__(self, layers, params, first_block, eps=1e-5):
+    def __init__(self, layers, params, first_block, eps=1e-5, storage=None):
         self.layers = [L for L in layers if L["op"] != "softmax_ce"]
         self.x = [{k: _f64(v).copy() for k, v in d.items()} for d in params[:len(self.layers)]]
         self.first_block = first_block  # no gradient w.r.t. the data h_0 is formed (q_0 = 0)
         self.eps = eps
+        # storage = "bf16": every feature map, every error gradient of a feature map and the
+        # conv filters are rounded to bfloat16 where a bf16 implementation stores them (the
+        # arithmetic stays fp64; master parameters, weight gradients, BN statistics and the
+        # pooled head stay unrounded).  A ReLU mask is an integer decision taken on a stored
+        # value, so a comparison with a bf16 implementation is only meaningful if both sides
+        # take it in the same precision.
+        assert storage in (None, "bf16")
+        self._rnd = round_bf16 if storage == "bf16" else (lambda a: a)
+        # Diagnostics for comparisons with finite-precision implementations: a ReLU input z whose
+        # magnitude is below knife_tau times the magnitude of the terms it was summed from may
+        # legitimately fall on either branch there.  last_knife lists (count, elements) per ReLU
+        # layer of the latest vjp(); it does not influence any result.
+        self.knife_tau = 0.0
+        self.last_knife = []
 
     # -- parameters as one flat list of arrays (what the optimiser sees)
     def param_list(self):
@@ -185,6 +208,7 @@ class CNNBlock:
     def forward(self, h, params=None):
         """Returns (h_{k+1}, cache) with every intermediate tensor kept."""
         P = self.x if params is None else params
+        rnd = self._rnd
         h = _f64(h)
         T, aux = [], []
         src = lambda i: h if i == -1 else T[i]  # noqa: E731
@@ -192,14 +216,21 @@ class CNNBlock:
             x = src(L["in"])
             op = L["op"]
             if op == "conv":
-                T.append(conv2d_forward(x, prm["w"], L["stride"], L["pad"]))
+                T.append(rnd(conv2d_forward(x, rnd(prm["w"]), L["stride"], L["pad"])))
                 aux.append(None)
             elif op == "bn":
                 z, mean, invstd = bn_forward(x, prm["gamma"], prm["beta"], self.eps)
+                cshape = (1, -1, 1, 1)
+                mag = (np.abs(prm["gamma"] * invstd).reshape(cshape) * (np.abs(x) + np.abs(mean).reshape(cshape))
+                       + np.abs(prm["beta"]).reshape(cshape)) if (L["relu"] and self.knife_tau > 0) else 0.0
                 if L["res"] is not None:
+                    mag = mag + np.abs(src(L["res"]))
                     z = z + src(L["res"])
-                T.append(np.maximum(z, 0.0) if L["relu"] else z)
-                aux.append((mean, invstd, z))
+                knife = (int((np.abs(z) < self.knife_tau * (mag + 1e-300)).sum()), z.size) if (
+                    L["relu"] and self.knife_tau > 0) else None
+                y = rnd(np.maximum(z, 0.0) if L["relu"] else z)
+                T.append(y)
+                aux.append((mean, invstd, y, knife))
             elif op == "maxpool":
                 y, arg = maxpool_forward(x, L["k"], L["stride"], L["pad"])
                 T.append(y)
@@ -226,9 +257,13 @@ class CNNBlock:
         def src(i):
             return h if i == -1 else T[i]
 
-        def add(i, v):
+        rnd = self._rnd
+
+        def add(i, v):  # gradients of feature maps are stored (hence rounded) after every contribution
             if i == -1:
-                dh[0] = v if dh[0] is None else dh[0] + v
+                dh[0] = rnd(v if dh[0] is None else dh[0] + v)
+            elif T[i].ndim == 4:
+                dT[i] = rnd(v if dT[i] is None else dT[i] + v)
             else:
                 dT[i] = v if dT[i] is None else dT[i] + v
 
@@ -240,11 +275,11 @@ class CNNBlock:
             if op == "conv":
                 grads[i]["w"] = conv2d_backward_weight(x, g, prm["w"].shape, L["stride"], L["pad"])
                 if not (L["in"] == -1 and self.first_block):
-                    add(L["in"], conv2d_backward_data(g, prm["w"], x.shape, L["stride"], L["pad"]))
+                    add(L["in"], conv2d_backward_data(g, rnd(prm["w"]), x.shape, L["stride"], L["pad"]))
             elif op == "bn":
-                mean, invstd, z = aux[i]
+                mean, invstd, y, _ = aux[i]
                 if L["relu"]:
-                    g = g * (z > 0.0)  # ReLU'(0) = 0
+                    g = g * (y > 0.0)  # ReLU'(0) = 0, decided on the stored output
                 if L["res"] is not None:
                     add(L["res"], g)
                 dx, dg, db = bn_backward(g, x, prm["gamma"], mean, invstd)
@@ -265,6 +300,7 @@ class CNNBlock:
     def vjp(self, h, g_out):
         """Eq. (5), lines 1-2: recompute f_k on the stored input with the *current* parameters, then chain rule."""
         _, cache = self.forward(h)
+        self.last_knife = [a[3] for a in cache[2] if isinstance(a, tuple) and len(a) == 4 and a[3] is not None]
         return self.backward(cache, g_out)
 
 
@@ -427,9 +463,10 @@ class DSPOracle:
         return rec
 
 
-def build_cnn_oracle(cfg, params_per_block, lr=None, beta=None, wd=None, p=None, m=None, eps=1e-5):
+def build_cnn_oracle(cfg, params_per_block, lr=None, beta=None, wd=None, p=None, m=None, eps=1e-5, storage=None):
     """A DSPOracle over the CNN blocks of a workload config (see workloads.configs)."""
-    blocks = [CNNBlock(layers, prm, first_block=(k == 0 and cfg.get("data_input", True)), eps=eps)
+    blocks = [CNNBlock(layers, prm, first_block=(k == 0 and cfg.get("data_input", True)), eps=eps,
+                       storage=storage)
               for k, (layers, prm) in enumerate(zip(cfg["blocks"], params_per_block))]
     ext = cfg.get("classes") is None
     return DSPOracle(blocks, SoftmaxCE(), cfg["p"] if p is None else p, cfg["m"] if m is None else m,

@@ -329,7 +329,11 @@ static int run_forward(dsp_block* b, const void* in, void* out_override, const i
     for (int i = 0; i < n; ++i) {
         Layer& L = b->layers[i];
         const Tensor& s = L.d.in0 < 0 ? b->input : b->T[L.d.in0];
-        const void* src = L.d.in0 < 0 ? in : b->T[L.d.in0].act;
+        // the block output lives in out_override when one is given (only the loss may read it back)
+        auto act_of = [&](int t) -> const void* {
+            return t < 0 ? in : ((t == b->out_idx && out_override) ? out_override : b->T[t].act);
+        };
+        const void* src = act_of(L.d.in0);
         Tensor& t = b->T[i];
         void* dst = (i == b->out_idx && out_override) ? out_override : t.act;
         switch (L.d.op) {
@@ -337,7 +341,7 @@ static int run_forward(dsp_block* b, const void* in, void* out_override, const i
             DSP_TRY(launch_conv_forward(b->dtype, L.cs, src, weights_for_forward(b, L), dst, st));
             break;
         case DSP_OP_BN: {
-            const void* res = L.d.in1 == -2 ? nullptr : (L.d.in1 < 0 ? in : b->T[L.d.in1].act);
+            const void* res = L.d.in1 == -2 ? nullptr : act_of(L.d.in1);
             BnBuffers buf{b->bn_partial, L.mean, L.invstd, b->bn_coef};
             DSP_TRY(launch_bn_forward(b->dtype, src, res, dst, b->x + L.p0, b->x + L.p1, b->desc.bn_eps,
                                       (int64_t)s.N * s.H * s.W, s.C, L.d.relu != 0, buf, st));
@@ -353,7 +357,12 @@ static int run_forward(dsp_block* b, const void* in, void* out_override, const i
             DSP_TRY(launch_linear_forward((const float*)src, b->x + L.p0, b->x + L.p1, (float*)dst, s.N, L.d.cin, L.d.cout, st));
             break;
         case DSP_OP_SOFTMAX_CE:
-            DSP_TRY(launch_softmax_ce((const float*)src, labels, loss, dz_slot, b->row_loss, s.N, s.C, st));
+            // the loss and its gradient belong to the forward pass (Eq. (5), third line); a recompute
+            // (labels == nullptr) reuses the gradient stored then and must not touch them
+            if (labels) {
+                DSP_REQUIRE(loss && dz_slot, DSP_EINVAL, "softmax_ce: missing loss buffers");
+                DSP_TRY(launch_softmax_ce((const float*)src, labels, loss, dz_slot, b->row_loss, s.N, s.C, st));
+            }
             break;
         }
     }

@@ -282,6 +282,7 @@ int launch_linear_backward(const float* x, const float* w, const float* dz, floa
 int launch_softmax_ce(const float* z, const int32_t* labels, float* loss, float* dz, float* row_loss, int N, int C,
                       hipStream_t st)
 {
+    DSP_REQUIRE(z && labels && loss && dz && row_loss && N > 0 && C > 0, DSP_EINVAL, "softmax_ce: null buffer or empty shape");
     hipLaunchKernelGGL(softmax_ce_rows_kernel, dim3(N), dim3(64), 0, st, z, labels, row_loss, dz, N, C);
     hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(64), 0, st, (const float*)row_loss, loss, N);
     DSP_HIP(hipGetLastError());
