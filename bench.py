@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the DSP block step on one MI355X.
+
+A "step" is one pipeline tick: every block of DSP(p; m) runs forward(a), recompute+backward(b) and
+its momentum-SGD update on its own HIP stream, on synthetic inputs that are already resident in
+HBM.  Prints ONE JSON line (see README for the fields).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet20|resnet56|resnet18|resnet50_conv4x|tiny2]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"fp32": 157.3, "bf16": 2500.0}  # MI355X dense MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="resnet20")
+    ap.add_argument("--dtype", default=None, choices=[None, "fp32", "bf16"])
+    ap.add_argument("--batch", type=int, default=None, help="override the mini-batch size (not the headline number)")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the CPU-oracle baseline leg (0 = skip)")
+    ap.add_argument("--profile-steps", type=int, default=10)
+    return ap.parse_args()
+
+
+class Workload:
+    """Library objects + resident synthetic inputs for one configuration."""
+
+    def __init__(self, name, dtype_name, batch, max_ticks):
+        import numpy as np
+        import torch
+
+        import paper_1909_02625_amd as D
+        from tests.gpu_harness import block_shapes, build_gpu_blocks, round_like, to_dev
+        from workloads import get_config, make_batch, make_params
+        from workloads.gen import make_error_gradient
+
+        self.D, self.torch = D, torch
+        self.cfg = cfg = get_config(name, batch=batch)
+        self.dtype_name = dtype_name or cfg["dtypes"][0]
+        self.dtype = D.DSP_BF16 if self.dtype_name == "bf16" else D.DSP_FP32
+        rng = np.random.default_rng(cfg["seed"])
+        self.params = [make_params(layers, rng) for layers in cfg["blocks"]]
+        self.blocks = build_gpu_blocks(cfg, self.params, self.dtype)
+        self.shapes = block_shapes(cfg)
+        self.N = cfg["input"][0]
+        self.external = cfg.get("classes") is None
+        nbuf = 4
+        self.batches = []
+        for _ in range(nbuf):
+            x, y = make_batch(rng, cfg["input"], cfg["classes"])
+            g = None
+            if self.external:
+                g = to_dev(round_like(make_error_gradient(rng, self.shapes[-1], cfg.get("grad_std", 0.1)), self.dtype),
+                           self.dtype)
+            self.batches.append((to_dev(x, self.dtype), None if y is None else torch.from_numpy(y).cuda(), g))
+        self.pl = None
+        self.tick = 0
+        if not self.external:
+            self.pl = D.dsp_pipeline_init(self.blocks, cfg["p"], cfg["m"], cfg["lr"], cfg["beta"], cfg["wd"], max_ticks)
+        else:
+            self.out = torch.empty(int(np.prod(self.shapes[-1])), device="cuda",
+                                   dtype=torch.bfloat16 if self.dtype == D.DSP_BF16 else torch.float32)
+            self.gin = torch.empty(int(np.prod(self.shapes[0])), device="cuda", dtype=self.out.dtype)
+        torch.cuda.synchronize()
+
+    def step(self):
+        D, cfg = self.D, self.cfg
+        x, y, g = self.batches[self.tick % len(self.batches)]
+        if self.pl is not None:
+            D.dsp_pipeline_step(self.pl, x, y)
+        else:  # a lone mid-network block fed with an external error gradient
+            b, m = self.blocks[0], cfg["m"][0]
+            D.dsp_block_forward(b, self.tick, x, self.out)
+            if self.tick - m >= 0:
+                D.dsp_block_recompute_backward(b, self.tick - m, g, self.gin)
+                D.dsp_param_update(b, cfg["lr"], cfg["beta"], cfg["wd"])
+        self.tick += 1
+
+    def sync(self):
+        if self.pl is not None:
+            self.D.dsp_pipeline_sync(self.pl)
+        self.torch.cuda.synchronize()
+
+    def close(self):
+        from tests.gpu_harness import destroy_blocks
+        if self.pl is not None:
+            self.D.dsp_pipeline_destroy(self.pl)
+        destroy_blocks(self.blocks)
+
+
+def cpu_baseline(name, batch, seconds):
+    """The CPU oracle (as is) on the first ticks of the same workload: images/s over the steady ticks."""
+    import numpy as np
+
+    from oracle import dsp_oracle as O
+    from workloads import get_config, make_batch, make_params
+    from workloads.gen import make_error_gradient
+
+    cfg = get_config(name, batch=batch)
+    rng = np.random.default_rng(cfg["seed"])
+    params = [make_params(layers, rng) for layers in cfg["blocks"]]
+    orc = O.build_cnn_oracle(cfg, params)
+    fill = max(sum(cfg["p"][:k]) + cfg["m"][k] for k in range(cfg["K"]))
+    ext = cfg.get("classes") is None
+    steady, t_steady, t_start, tick = 0, 0.0, time.perf_counter(), 0
+    while True:
+        x, y = make_batch(rng, cfg["input"], cfg["classes"])
+        t0 = time.perf_counter()
+        orc.tick(x, y, top_gradient=(lambda a, out: make_error_gradient(rng, out.shape, 0.1).astype(np.float64)) if ext else None)
+        dt = time.perf_counter() - t0
+        if tick >= fill:
+            steady += 1
+            t_steady += dt
+        tick += 1
+        if steady >= 1 and time.perf_counter() - t_start > seconds:
+            break
+        if steady >= 8:
+            break
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": cfg["input"][0] * steady / t_steady, "unit": "images/s", "cores": cores, "kind": "oracle",
+            "sample": "%d steady ticks (after %d fill ticks) of %s at batch %d, fp64, plain C loops + OpenMP over the batch"
+                      % (steady, fill, name, cfg["input"][0])}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the K blocks share it on K HIP streams); --gpus %d is not supported"
+              % a.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_1909_02625_amd as D
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    total_ticks = a.warmup + a.steps + a.profile_steps + 4
+    w = Workload(a.workload, a.dtype, a.batch, total_ticks)
+    for _ in range(a.warmup):
+        w.step()
+    w.sync()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        w.step()
+    w.sync()
+    t1 = time.perf_counter()
+    ms = (t1 - t0) * 1e3 / a.steps
+    value = w.N * a.steps / (t1 - t0)
+
+    # per-kernel time of the same ticks, from event pairs recorded around every launch on its own stream
+    table = []
+    if a.profile_steps > 0:
+        D.dsp_profile_start(200000)
+        for _ in range(a.profile_steps):
+            w.step()
+        w.sync()
+        table = D.dsp_profile_stop()
+    roof, kernels, conv_util = None, [], None
+    if table:
+        tot_ms = sum(k["ms"] for k in table)
+        peak = PEAK_TFLOPS[w.dtype_name]
+        for k in sorted(table, key=lambda k: -k["ms"]):
+            avg_us = 1e3 * k["ms"] / k["launches"]
+            rate = k["units"] / (k["ms"] * 1e-3) if k["ms"] > 0 else 0.0
+            kernels.append({"name": k["name"], "launches_per_step": k["launches"] / a.profile_steps,
+                            "avg_us": round(avg_us, 2), "share": round(k["ms"] / tot_ms, 4),
+                            ("tflops" if k["unit_kind"] == "flop" else "gbs"):
+                                round(rate / (1e12 if k["unit_kind"] == "flop" else 1e9), 2)})
+        conv = [k for k in table if k["unit_kind"] == "flop"]
+        if conv:
+            conv_util = 100.0 * sum(k["units"] for k in conv) / (sum(k["ms"] for k in conv) * 1e-3) / (peak * 1e12)
+        dom = max(table, key=lambda k: k["ms"])
+        if dom["unit_kind"] == "flop":
+            ach = dom["units"] / (dom["ms"] * 1e-3) / 1e12
+            roof = {"bound": "mfma", "kernel": dom["name"], "achieved": round(ach, 3), "peak": peak, "unit": "TFLOP/s",
+                    "frac": round(ach / peak, 4), "traffic": None,
+                    "avg_launch_us": round(1e3 * dom["ms"] / dom["launches"], 2),
+                    "flop_per_launch": dom["units"] / dom["launches"]}
+        else:
+            ach = dom["units"] / (dom["ms"] * 1e-3) / 1e9
+            roof = {"bound": "hbm", "kernel": dom["name"], "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None,
+                    "avg_launch_us": round(1e3 * dom["ms"] / dom["launches"], 2),
+                    "bytes_per_launch": dom["units"] / dom["launches"]}
+    w.close()
+
+    base = None
+    if a.cpu_seconds > 0:
+        base = cpu_baseline(a.workload, a.batch, a.cpu_seconds)
+
+    cfg = w.cfg
+    out = {
+        "metric": "images/sec per DSP block step (fwd+recompute+bwd+update)",
+        "value": round(value, 1), "unit": "images/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if w.dtype_name == "fp32" else "bf16", "data": "synthetic",
+        "config": {"workload": "%s: DSP(%s;%s), K=%d blocks on %d HIP streams, batch %d x %dx%dx%d, one pipeline tick per step"
+                               % (a.workload, ",".join(map(str, cfg["p"])), ",".join(map(str, cfg["m"])), cfg["K"],
+                                  cfg["K"], cfg["input"][0], cfg["input"][1], cfg["input"][2], cfg["input"][3]),
+                   "lr": cfg["lr"], "momentum": cfg["beta"]},
+        "conv_mfma_util_pct": None if conv_util is None else round(conv_util, 3),
+        "roofline": roof, "cpu_baseline": base, "kernels": kernels[:12],
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -229,6 +229,24 @@ int dsp_conv_backward_weight(int32_t dtype, const void* d_x, const void* d_dy, f
 int dsp_conv_workspace_bytes(int32_t N, int32_t H, int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s,
                              int32_t stride, int32_t pad, size_t* bytes);
 
+/* ---- in-situ kernel timing (measurement support) ------------------------------------------------ */
+
+/*
+ * Between dsp_profile_start and dsp_profile_stop every kernel launch of the library carries its own
+ * start and stop event, filled from the timestamps of that kernel's dispatch on the stream it runs on
+ * (at most max_launches launches; events are created here, so call it outside timed regions; not
+ * usable under stream capture).  dsp_profile_stop synchronises the device and sums, per
+ * kernel name, the launches, the milliseconds between the event pairs and the algorithmic work of
+ * the launches: unit_kind 0 = floating-point operations (2 per multiply-accumulate of the
+ * convolution as defined, padding taps and skipped strided taps not counted), unit_kind 1 = bytes
+ * that have to cross HBM once (each operand read once, each result written once).
+ * dsp_profile_get returns entry i of that table.  Process-wide, not thread-safe.
+ */
+int dsp_profile_start(int32_t max_launches);
+int dsp_profile_stop(int32_t* n_kernels);
+int dsp_profile_get(int32_t i, char* name, size_t name_len, int64_t* launches, double* total_ms, double* total_units,
+                    int32_t* unit_kind);
+
 const char* dsp_strerror(int status);
 /* Text of the most recent failure on this thread ("" if none). */
 const char* dsp_last_error(void);

@@ -21,6 +21,7 @@ __all__ = [
     "dsp_pipeline_init", "dsp_pipeline_destroy", "dsp_pipeline_step", "dsp_pipeline_set_delay",
     "dsp_pipeline_sync", "dsp_pipeline_losses", "dsp_pipeline_ticks",
     "dsp_conv_forward", "dsp_conv_backward_data", "dsp_conv_backward_weight", "dsp_conv_workspace_bytes",
+    "dsp_profile_start", "dsp_profile_stop", "dsp_profile_get",
     "dsp_strerror", "dsp_last_error", "EXPORTED_SYMBOLS",
 ]
 
@@ -57,6 +58,10 @@ def lib():
     """Loads the built library (building it first only if no binary exists at all)."""
     global _LIB
     if _LIB is None:
+        # PyTorch owns the device memory and streams handed to the library, so both must talk to ONE
+        # HIP runtime: importing torch first makes the loader bind libamdhip64.so.7 to the copy torch
+        # ships (two runtimes in a process do not see each other's devices or allocations).
+        import torch  # noqa: F401
         path = lib_path()
         if not os.path.exists(path):
             from . import build as _build
@@ -99,6 +104,9 @@ _SIGNATURES = {
     "dsp_conv_backward_data": [_i32, _vp, _vp, _vp] + [_i32] * 10 + [_vp],
     "dsp_conv_backward_weight": [_i32, _vp, _vp, _vp] + [_i32] * 9 + [_vp, _sz, _vp],
     "dsp_conv_workspace_bytes": [_i32] * 9 + [C.POINTER(_sz)],
+    "dsp_profile_start": [_i32],
+    "dsp_profile_stop": [_pi32],
+    "dsp_profile_get": [_i32, C.c_char_p, _sz, _pi64, C.POINTER(C.c_double), C.POINTER(C.c_double), _pi32],
 }
 EXPORTED_SYMBOLS = sorted(list(_SIGNATURES) + ["dsp_strerror", "dsp_last_error"])
 
@@ -336,6 +344,26 @@ def dsp_conv_workspace_bytes(N, H, W, cin, cout, r, s, stride, pad):
     out = C.c_size_t()
     check(lib().dsp_conv_workspace_bytes(N, H, W, cin, cout, r, s, stride, pad, C.byref(out)), "dsp_conv_workspace_bytes")
     return out.value
+
+
+def dsp_profile_start(max_launches):
+    check(lib().dsp_profile_start(max_launches), "dsp_profile_start")
+
+
+def dsp_profile_stop():
+    """Returns the per-kernel table: list of dicts (name, launches, ms, units, unit_kind)."""
+    n = C.c_int32()
+    check(lib().dsp_profile_stop(C.byref(n)), "dsp_profile_stop")
+    return [dsp_profile_get(i) for i in range(n.value)]
+
+
+def dsp_profile_get(i):
+    name = C.create_string_buffer(128)
+    launches, ms, units, kind = C.c_int64(), C.c_double(), C.c_double(), C.c_int32()
+    check(lib().dsp_profile_get(i, name, 128, C.byref(launches), C.byref(ms), C.byref(units), C.byref(kind)),
+          "dsp_profile_get")
+    return {"name": name.value.decode(), "launches": launches.value, "ms": ms.value, "units": units.value,
+            "unit_kind": "flop" if kind.value == 0 else "byte"}
 
 
 def dsp_strerror(status):

@@ -14,7 +14,9 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <map>
 #include <new>
+#include <string>
 #include <vector>
 
 #include "common.h"
@@ -29,6 +31,35 @@ void set_error(const char* fmt, ...)
     va_start(ap, fmt);
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
+}
+
+// ---- in-situ kernel timing ------------------------------------------------------------------------
+bool g_profile_on = false;
+namespace {
+struct ProfRec {
+    const char* name;
+    double units;
+    int unit_kind;
+};
+std::vector<hipEvent_t> g_prof_events;  // 2 per launch
+std::vector<ProfRec> g_prof_recs;
+size_t g_prof_capacity = 0;
+struct ProfAgg {
+    std::string name;
+    int64_t launches = 0;
+    double ms = 0, units = 0;
+    int unit_kind = 0;
+};
+std::vector<ProfAgg> g_prof_result;
+}  // namespace
+
+void ProfScope::begin(const char* name, double units, int unit_kind)
+{
+    if (g_prof_recs.size() >= g_prof_capacity) return;  // profile full: later launches go untimed
+    const size_t slot = g_prof_recs.size();
+    g_prof_recs.push_back({name, units, unit_kind});
+    start = g_prof_events[2 * slot];
+    stop = g_prof_events[2 * slot + 1];
 }
 
 struct Tensor {
@@ -641,6 +672,62 @@ int dsp_conv_workspace_bytes(int32_t N, int32_t H, int32_t W, int32_t cin, int32
     const ConvShape c = make_conv_shape(N, H, W, cin, cout, r, s, stride, pad);
     DSP_REQUIRE(c.Ho > 0 && c.Wo > 0, DSP_EINVAL, "dsp_conv_workspace_bytes: empty output");
     *bytes = conv_backward_weight_workspace(c);
+    return DSP_OK;
+}
+
+// ---- in-situ kernel timing ---------------------------------------------------------------------------
+int dsp_profile_start(int32_t max_launches)
+{
+    DSP_REQUIRE(max_launches > 0 && max_launches <= (1 << 20), DSP_EINVAL, "dsp_profile_start: bad max_launches");
+    DSP_REQUIRE(!g_profile_on, DSP_ESTATE, "dsp_profile_start: a profile is already running");
+    while (g_prof_events.size() < 2 * (size_t)max_launches) {
+        hipEvent_t e;
+        DSP_HIP(hipEventCreate(&e));
+        g_prof_events.push_back(e);
+    }
+    g_prof_recs.clear();
+    g_prof_recs.reserve(max_launches);
+    g_prof_capacity = max_launches;
+    g_prof_result.clear();
+    g_profile_on = true;
+    return DSP_OK;
+}
+
+int dsp_profile_stop(int32_t* n_kernels)
+{
+    DSP_REQUIRE(g_profile_on, DSP_ESTATE, "dsp_profile_stop: no profile is running");
+    g_profile_on = false;
+    DSP_HIP(hipDeviceSynchronize());
+    std::map<std::string, size_t> index;
+    for (size_t i = 0; i < g_prof_recs.size(); ++i) {
+        float ms = 0.f;
+        DSP_HIP(hipEventElapsedTime(&ms, g_prof_events[2 * i], g_prof_events[2 * i + 1]));
+        auto it = index.find(g_prof_recs[i].name);
+        if (it == index.end()) {
+            it = index.emplace(g_prof_recs[i].name, g_prof_result.size()).first;
+            g_prof_result.push_back(ProfAgg());
+            g_prof_result.back().name = g_prof_recs[i].name;
+            g_prof_result.back().unit_kind = g_prof_recs[i].unit_kind;
+        }
+        ProfAgg& a = g_prof_result[it->second];
+        a.launches += 1;
+        a.ms += ms;
+        a.units += g_prof_recs[i].units;
+    }
+    if (n_kernels) *n_kernels = (int32_t)g_prof_result.size();
+    return DSP_OK;
+}
+
+int dsp_profile_get(int32_t i, char* name, size_t name_len, int64_t* launches, double* total_ms, double* total_units,
+                    int32_t* unit_kind)
+{
+    DSP_REQUIRE(i >= 0 && (size_t)i < g_prof_result.size(), DSP_EINVAL, "dsp_profile_get: index out of range");
+    const ProfAgg& a = g_prof_result[i];
+    if (name && name_len) snprintf(name, name_len, "%s", a.name.c_str());
+    if (launches) *launches = a.launches;
+    if (total_ms) *total_ms = a.ms;
+    if (total_units) *total_units = a.units;
+    if (unit_kind) *unit_kind = a.unit_kind;
     return DSP_OK;
 }
 

@@ -289,15 +289,23 @@ int bn_forward_t(const void* x, const void* res, void* y, const float* gamma, co
     int nblk;
     const int rows = plan_rows(M, L, &nblk);
     const dim3 grid(nblk, ceil_div(L.cv, L.cvb));
-    hipLaunchKernelGGL((bn_sums_kernel<T, VW, 0, false>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)nullptr,
-                       (const T*)nullptr, (const float*)nullptr, (const float*)nullptr, buf.partial, M, C, L, rows);
-    hipLaunchKernelGGL(bn_fwd_finalize_kernel, dim3(C), dim3(64), 0, st, (const double*)buf.partial, nblk, C,
-                       1.0 / (double)M, eps, gamma, beta, buf.mean, buf.invstd, buf.coef);
+    const double tensor_bytes = (double)M * C * sizeof(T);
+    {
+        ProfScope ps(sizeof(T) == 2 ? "bn_stats<bf16>" : "bn_stats<fp32>", tensor_bytes, 1);
+        DSP_LAUNCH(ps, (bn_sums_kernel<T, VW, 0, false>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)nullptr,
+                   (const T*)nullptr, (const float*)nullptr, (const float*)nullptr, buf.partial, M, C, L, rows);
+    }
+    {
+        ProfScope ps("bn_fwd_finalize", (double)nblk * C * 16.0, 1);
+        DSP_LAUNCH(ps, bn_fwd_finalize_kernel, dim3(C), dim3(64), 0, st, (const double*)buf.partial, nblk, C,
+                   1.0 / (double)M, eps, gamma, beta, buf.mean, buf.invstd, buf.coef);
+    }
     const int64_t nvec = M * (C / VW);
     const dim3 ag(apply_grid(nvec));
-#define BN_APPLY(R, H)                                                                                             \
-    hipLaunchKernelGGL((bn_fwd_apply_kernel<T, VW, R, H>), ag, dim3(kThreads), 0, st, (const T*)x, (const T*)res, \
-                       (T*)y, (const float*)buf.coef, nvec, C, L.cv)
+    ProfScope ps(sizeof(T) == 2 ? "bn_apply_relu<bf16>" : "bn_apply_relu<fp32>", tensor_bytes * (res ? 3 : 2), 1);
+#define BN_APPLY(R, H)                                                                                          \
+    DSP_LAUNCH(ps, (bn_fwd_apply_kernel<T, VW, R, H>), ag, dim3(kThreads), 0, st, (const T*)x, (const T*)res, \
+               (T*)y, (const float*)buf.coef, nvec, C, L.cv)
     if (relu) {
         if (res) BN_APPLY(true, true); else BN_APPLY(true, false);
     } else {
@@ -316,15 +324,25 @@ int bn_backward_t(const void* dy, const void* x, const void* y, void* dx, void* 
     int nblk;
     const int rows = plan_rows(M, L, &nblk);
     const dim3 grid(nblk, ceil_div(L.cv, L.cvb));
-    hipLaunchKernelGGL((bn_sums_kernel<T, VW, 1, RELU>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)dy,
-                       (const T*)y, (const float*)buf.mean, (const float*)buf.invstd, buf.partial, M, C, L, rows);
-    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(C), dim3(64), 0, st, (const double*)buf.partial, nblk, C,
-                       1.0 / (double)M, gamma, (const float*)buf.mean, (const float*)buf.invstd, dgamma, dbeta, buf.coef);
+    const double tensor_bytes = (double)M * C * sizeof(T);
+    {
+        ProfScope ps(sizeof(T) == 2 ? "bn_bwd_reduce<bf16>" : "bn_bwd_reduce<fp32>", tensor_bytes * (RELU ? 3 : 2), 1);
+        DSP_LAUNCH(ps, (bn_sums_kernel<T, VW, 1, RELU>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)dy,
+                   (const T*)y, (const float*)buf.mean, (const float*)buf.invstd, buf.partial, M, C, L, rows);
+    }
+    {
+        ProfScope ps("bn_bwd_finalize", (double)nblk * C * 16.0, 1);
+        DSP_LAUNCH(ps, bn_bwd_finalize_kernel, dim3(C), dim3(64), 0, st, (const double*)buf.partial, nblk, C,
+                   1.0 / (double)M, gamma, (const float*)buf.mean, (const float*)buf.invstd, dgamma, dbeta, buf.coef);
+    }
     const int64_t nvec = M * (C / VW);
     const dim3 ag(apply_grid(nvec));
-#define BN_BAPPLY(H, RA, XA)                                                                                      \
-    hipLaunchKernelGGL((bn_bwd_apply_kernel<T, VW, RELU, H, RA, XA>), ag, dim3(kThreads), 0, st, (const T*)dy,   \
-                       (const T*)x, (const T*)y, (T*)dx, (T*)dres, (const float*)buf.coef, nvec, C, L.cv)
+    // reads dy, x (and y for the ReLU mask, and the old values where it accumulates); writes dx (and dres)
+    ProfScope ps(sizeof(T) == 2 ? "bn_bwd_apply<bf16>" : "bn_bwd_apply<fp32>",
+                 tensor_bytes * (2 + (RELU ? 1 : 0) + 1 + (xacc ? 1 : 0) + (dres ? 1 + (racc ? 1 : 0) : 0)), 1);
+#define BN_BAPPLY(H, RA, XA)                                                                                   \
+    DSP_LAUNCH(ps, (bn_bwd_apply_kernel<T, VW, RELU, H, RA, XA>), ag, dim3(kThreads), 0, st, (const T*)dy,    \
+               (const T*)x, (const T*)y, (T*)dx, (T*)dres, (const float*)buf.coef, nvec, C, L.cv)
     if (dres) {
         if (racc) { if (xacc) BN_BAPPLY(true, true, true); else BN_BAPPLY(true, true, false); }
         else      { if (xacc) BN_BAPPLY(true, false, true); else BN_BAPPLY(true, false, false); }

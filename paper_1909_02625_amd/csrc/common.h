@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -151,5 +152,31 @@ int launch_sgd_update(int dtype, float* x, float* v, const float* g, const uint8
 int launch_refresh_shadows(int dtype, const float* x, const int32_t* tmap, void* wf16, void* wt, size_t n,
                            hipStream_t st);
 int launch_spin(int microseconds, hipStream_t st);
+
+// ---- in-situ kernel timing (block.hip) ----------------------------------------------------------
+// While a profile is running (dsp_profile_start .. dsp_profile_stop) every instrumented launch goes
+// through hipExtLaunchKernelGGL with a start and a stop event of its own, which the runtime fills
+// from the timestamps of that kernel's dispatch packet (the same source a kernel trace uses), so a
+// launch is timed exactly, on whatever stream it runs, without serialising the streams.  The pairs
+// are read back and summed per kernel name at stop.  `units` is the algorithmic work of the launch:
+// floating-point operations (unit_kind 0) or bytes that must cross HBM (unit_kind 1).
+extern bool g_profile_on;
+struct ProfScope {
+    hipEvent_t start = nullptr, stop = nullptr;
+    ProfScope(const char* name, double units, int unit_kind)
+    {
+        if (g_profile_on) begin(name, units, unit_kind);
+    }
+    void begin(const char* name, double units, int unit_kind);
+};
+
+// Launches `kernel`; with an active ProfScope `ps` the launch carries its own timing events.
+#define DSP_LAUNCH(ps, kernel, grid, block, lds, st, ...)                                              \
+    do {                                                                                               \
+        if ((ps).start)                                                                                \
+            hipExtLaunchKernelGGL(kernel, grid, block, lds, st, (ps).start, (ps).stop, 0, __VA_ARGS__); \
+        else                                                                                           \
+            hipLaunchKernelGGL(kernel, grid, block, lds, st, __VA_ARGS__);                             \
+    } while (0)
 
 }  // namespace dsp

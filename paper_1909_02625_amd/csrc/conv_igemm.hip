@@ -15,6 +15,8 @@
 // LDS tiles whose rows hold BKB bytes of k plus a 16-byte pad (conflict-free ds_read_b128);
 // every lane feeds the MFMA with 16-byte k-runs (8 bf16 -> one 32x32x16 / 16x16x32 MFMA,
 // 4 floats -> four 32x32x2 / 16x16x4 MFMAs).  Accumulation is fp32 in both storage types.
+#include <stdio.h>
+
 #include "common.h"
 
 namespace dsp {
@@ -445,18 +447,42 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
 }
 
 // dw[i] = sum over slices of part[slice][i], slices in ascending order (run-to-run identical).
-__global__ void wgrad_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw, int n, int splits)
+// A workgroup owns 32 consecutive elements; 8 lanes per element each add every 8th slice, then the
+// 8 lane sums are added in lane order: a fixed summation tree, many loads in flight per element.
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw, int n,
+                                                           int splits)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
+    __shared__ float red[8][33];
+    const int col = threadIdx.x & 31, lane = threadIdx.x >> 5;
+    const int i = blockIdx.x * 32 + col;
     float s = 0.f;
-    for (int k = 0; k < splits; ++k) s += part[(int64_t)k * n + i];
-    dw[i] = s;
+    if (i < n)
+        for (int k = lane; k < splits; k += 8) s += part[(int64_t)k * n + i];
+    red[lane][col] = s;
+    __syncthreads();
+    if (lane == 0 && i < n) {
+        float t = red[0][col];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) t += red[k][col];
+        dw[i] = t;
+    }
 }
 
 // ---- host-side dispatch -------------------------------------------------------------------------
+template <typename TL>
+const char* tile_name(const char* what, bool vec, bool accum)
+{
+    // one name per kernel instantiation, e.g. "conv_gather_gemm<fp32,mfma32,BM128,BN64,vec>"
+    static char names[4][96];
+    char* n = names[(vec ? 1 : 0) + (accum ? 2 : 0)];
+    if (!n[0])
+        snprintf(n, 96, "%s<%s,mfma%d,BM%d,BN%d,%s%s>", what, sizeof(typename TL::T) == 2 ? "bf16" : "fp32", TL::MT, TL::BM,
+                 TL::BN, vec ? "vec" : "scalar", accum ? ",acc" : "");
+    return n;
+}
+
 template <typename TL, bool VEC, bool ACCUM>
-int run_gather(const GatherGeom& g, const void* in, const void* w, void* out, hipStream_t st)
+int run_gather(const GatherGeom& g, const void* in, const void* w, void* out, hipStream_t st, double flops)
 {
     typedef typename TL::T T;
     const int64_t tiles = (int64_t)ceil_div(g.M, TL::BM) * ceil_div(g.Co, TL::BN);
@@ -467,35 +493,43 @@ int run_gather(const GatherGeom& g, const void* in, const void* w, void* out, hi
         DSP_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES));
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(kThreads), TL::LDS_BYTES, st, (const T*)in, (const T*)w,
-                       (T*)out, g);
+    {
+        ProfScope ps(tile_name<TL>("conv_gather_gemm", VEC, ACCUM), flops, 0);
+        DSP_LAUNCH(ps, kern, dim3((unsigned)tiles), dim3(kThreads), TL::LDS_BYTES, st, (const T*)in, (const T*)w, (T*)out, g);
+    }
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }
 
 template <typename TL>
-int run_gather_v(const GatherGeom& g, bool vec, bool accum, const void* in, const void* w, void* out, hipStream_t st)
+int run_gather_v(const GatherGeom& g, bool vec, bool accum, const void* in, const void* w, void* out, hipStream_t st,
+                 double flops)
 {
-    if (vec) return accum ? run_gather<TL, true, true>(g, in, w, out, st) : run_gather<TL, true, false>(g, in, w, out, st);
-    return accum ? run_gather<TL, false, true>(g, in, w, out, st) : run_gather<TL, false, false>(g, in, w, out, st);
+    if (vec)
+        return accum ? run_gather<TL, true, true>(g, in, w, out, st, flops)
+                     : run_gather<TL, true, false>(g, in, w, out, st, flops);
+    return accum ? run_gather<TL, false, true>(g, in, w, out, st, flops)
+                 : run_gather<TL, false, false>(g, in, w, out, st, flops);
 }
 
 template <typename T>
-int dispatch_gather(const GatherGeom& g, bool accum, const void* in, const void* w, void* out, hipStream_t st)
+int dispatch_gather(const GatherGeom& g, bool accum, const void* in, const void* w, void* out, hipStream_t st,
+                    double flops)
 {
     constexpr int E = 16 / (int)sizeof(T);
     // 16-byte gathers need channel runs of E elements and 16-byte aligned bases
     const bool vec = (g.Ci % E) == 0 && ((uintptr_t)in % 16) == 0 && ((uintptr_t)w % 16) == 0;
     // tile by output-channel count; the small-channel tiles keep the whole channel range in one workgroup
-    if (g.Co <= 16) return run_gather_v<Tile<T, 16, 4, 1, 4, 1, 64>>(g, vec, accum, in, w, out, st);
-    if (g.Co <= 32) return run_gather_v<Tile<T, 32, 4, 1, 2, 1, 64>>(g, vec, accum, in, w, out, st);
+    if (g.Co <= 16) return run_gather_v<Tile<T, 16, 4, 1, 4, 1, 64>>(g, vec, accum, in, w, out, st, flops);
+    if (g.Co <= 32) return run_gather_v<Tile<T, 32, 4, 1, 2, 1, 64>>(g, vec, accum, in, w, out, st, flops);
     const int64_t big_tiles = (int64_t)ceil_div(g.M, 128) * ceil_div(g.Co, 128);
-    if (g.Co % 128 == 0 && big_tiles >= 512) return run_gather_v<Tile<T, 32, 2, 2, 2, 2, 64>>(g, vec, accum, in, w, out, st);
-    return run_gather_v<Tile<T, 32, 2, 2, 2, 1, 64>>(g, vec, accum, in, w, out, st);
+    if (g.Co % 128 == 0 && big_tiles >= 512)
+        return run_gather_v<Tile<T, 32, 2, 2, 2, 2, 64>>(g, vec, accum, in, w, out, st, flops);
+    return run_gather_v<Tile<T, 32, 2, 2, 2, 1, 64>>(g, vec, accum, in, w, out, st, flops);
 }
 
 template <typename TL, bool VEC>
-int run_wgrad(const WgradGeom& g0, int splits, const void* x, const void* dy, float* dst, hipStream_t st)
+int run_wgrad(const WgradGeom& g0, int splits, const void* x, const void* dy, float* dst, hipStream_t st, double flops)
 {
     typedef typename TL::T T;
     WgradGeom g = g0;
@@ -506,7 +540,10 @@ int run_wgrad(const WgradGeom& g0, int splits, const void* x, const void* dy, fl
         DSP_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES));
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(tiles, splits), dim3(kThreads), TL::LDS_BYTES, st, (const T*)x, (const T*)dy, dst, g);
+    {
+        ProfScope ps(tile_name<TL>("conv_wgrad", VEC, false), flops, 0);
+        DSP_LAUNCH(ps, kern, dim3(tiles, splits), dim3(kThreads), TL::LDS_BYTES, st, (const T*)x, (const T*)dy, dst, g);
+    }
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }
@@ -517,11 +554,11 @@ int wgrad_splits(const ConvShape& c, int bm, int bn, int bk, int* m_per_split)
 {
     const int64_t M = (int64_t)c.N * c.Ho * c.Wo, Kdim = (int64_t)c.R * c.S * c.Cin;
     const int tiles = ceil_div(c.Cout, bm) * ceil_div(Kdim, bn);
-    int want = ceil_div(1024, tiles);
-    const int max_by_len = (int)((M + 4 * bk - 1) / (4 * bk));
+    int want = ceil_div(512, tiles);  // about two workgroups per compute unit
+    const int max_by_len = (int)((M + 8 * bk - 1) / (8 * bk));
     if (want > max_by_len) want = max_by_len;
     if (want < 1) want = 1;
-    if (want > 512) want = 512;
+    if (want > 256) want = 256;
     int per = (int)((M + want - 1) / want);
     per = ceil_div(per, bk) * bk;
     *m_per_split = per;
@@ -541,7 +578,7 @@ WgradPlan wgrad_plan(int dtype, const ConvShape& c)
 
 template <typename T>
 int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes,
-                   hipStream_t st)
+                   hipStream_t st, double flops)
 {
     constexpr int E = 16 / (int)sizeof(T);
     const int dtype = sizeof(T) == 2 ? DSP_BF16 : DSP_FP32;
@@ -560,21 +597,39 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
     const bool vec = (c.Cin % E) == 0 && (c.Cout % E) == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)dy % 16) == 0;
     int rc;
     if (c.Cout <= 16)
-        rc = vec ? run_wgrad<Tile<T, 16, 1, 4, 1, 1, 64>, true>(g, splits, x, dy, dst, st)
-                 : run_wgrad<Tile<T, 16, 1, 4, 1, 1, 64>, false>(g, splits, x, dy, dst, st);
+        rc = vec ? run_wgrad<Tile<T, 16, 1, 4, 1, 1, 64>, true>(g, splits, x, dy, dst, st, flops)
+                 : run_wgrad<Tile<T, 16, 1, 4, 1, 1, 64>, false>(g, splits, x, dy, dst, st, flops);
     else if (c.Cout <= 32)
-        rc = vec ? run_wgrad<Tile<T, 32, 1, 4, 1, 1, 64>, true>(g, splits, x, dy, dst, st)
-                 : run_wgrad<Tile<T, 32, 1, 4, 1, 1, 64>, false>(g, splits, x, dy, dst, st);
+        rc = vec ? run_wgrad<Tile<T, 32, 1, 4, 1, 1, 64>, true>(g, splits, x, dy, dst, st, flops)
+                 : run_wgrad<Tile<T, 32, 1, 4, 1, 1, 64>, false>(g, splits, x, dy, dst, st, flops);
     else
-        rc = vec ? run_wgrad<Tile<T, 32, 2, 2, 1, 1, 64>, true>(g, splits, x, dy, dst, st)
-                 : run_wgrad<Tile<T, 32, 2, 2, 1, 1, 64>, false>(g, splits, x, dy, dst, st);
+        rc = vec ? run_wgrad<Tile<T, 32, 2, 2, 1, 1, 64>, true>(g, splits, x, dy, dst, st, flops)
+                 : run_wgrad<Tile<T, 32, 2, 2, 1, 1, 64>, false>(g, splits, x, dy, dst, st, flops);
     DSP_TRY(rc);
     if (splits > 1) {
-        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(ceil_div(n, 256)), dim3(256), 0, st, (const float*)ws, dw, (int)n,
-                           splits);
+        ProfScope ps("wgrad_reduce", (double)n * (splits + 1) * 4.0, 1);
+        DSP_LAUNCH(ps, wgrad_reduce_kernel, dim3(ceil_div(n, 32)), dim3(256), 0, st, (const float*)ws, dw, (int)n, splits);
         DSP_HIP(hipGetLastError());
     }
     return DSP_OK;
+}
+
+// Multiply-accumulates of the convolution as defined (taps that fall on padding are not counted);
+// forward, backward-data and backward-weight each perform exactly this many.
+double conv_macs(const ConvShape& c)
+{
+    int64_t vh = 0, vw = 0;
+    for (int o = 0; o < c.Ho; ++o)
+        for (int r = 0; r < c.R; ++r) {
+            const int t = o * c.stride - c.pad + r;
+            vh += (t >= 0 && t < c.H);
+        }
+    for (int o = 0; o < c.Wo; ++o)
+        for (int s = 0; s < c.S; ++s) {
+            const int t = o * c.stride - c.pad + s;
+            vw += (t >= 0 && t < c.W);
+        }
+    return (double)c.N * (double)vh * (double)vw * (double)c.Cin * (double)c.Cout;
 }
 
 int check_shape(const ConvShape& c)
@@ -596,8 +651,9 @@ int launch_conv_forward(int dtype, const ConvShape& c, const void* x, const void
     GatherGeom g{c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.pad, c.stride, 1, 0, 0};
     g.M = c.N * c.Ho * c.Wo;
     g.Kdim = c.R * c.S * c.Cin;
-    return dtype == DSP_BF16 ? dispatch_gather<bf16_t>(g, false, x, w, y, st)
-                             : dispatch_gather<float>(g, false, x, w, y, st);
+    const double flops = 2.0 * conv_macs(c);
+    return dtype == DSP_BF16 ? dispatch_gather<bf16_t>(g, false, x, w, y, st, flops)
+                             : dispatch_gather<float>(g, false, x, w, y, st, flops);
 }
 
 int launch_conv_backward_data(int dtype, const ConvShape& c, const void* dy, const void* wt, void* dx,
@@ -609,8 +665,9 @@ int launch_conv_backward_data(int dtype, const ConvShape& c, const void* dy, con
     GatherGeom g{c.N, c.Ho, c.Wo, c.Cout, c.H, c.W, c.Cin, c.R, c.S, c.R - 1 - c.pad, c.S - 1 - c.pad, 1, c.stride, 0, 0};
     g.M = c.N * c.H * c.W;
     g.Kdim = c.R * c.S * c.Cout;
-    return dtype == DSP_BF16 ? dispatch_gather<bf16_t>(g, accumulate, dy, wt, dx, st)
-                             : dispatch_gather<float>(g, accumulate, dy, wt, dx, st);
+    const double flops = 2.0 * conv_macs(c);
+    return dtype == DSP_BF16 ? dispatch_gather<bf16_t>(g, accumulate, dy, wt, dx, st, flops)
+                             : dispatch_gather<float>(g, accumulate, dy, wt, dx, st, flops);
 }
 
 size_t conv_backward_weight_workspace(const ConvShape& c)
@@ -630,8 +687,9 @@ int launch_conv_backward_weight(int dtype, const ConvShape& c, const void* x, co
                                 size_t ws_bytes, hipStream_t st)
 {
     DSP_TRY(check_shape(c));
-    return dtype == DSP_BF16 ? dispatch_wgrad<bf16_t>(c, x, dy, dw, ws, ws_bytes, st)
-                             : dispatch_wgrad<float>(c, x, dy, dw, ws, ws_bytes, st);
+    const double flops = 2.0 * conv_macs(c);
+    return dtype == DSP_BF16 ? dispatch_wgrad<bf16_t>(c, x, dy, dw, ws, ws_bytes, st, flops)
+                             : dispatch_wgrad<float>(c, x, dy, dw, ws, ws_bytes, st, flops);
 }
 
 }  // namespace dsp

@@ -1,0 +1,109 @@
+"""CPU-only checks of the library's host logic: the shared object loads, exports every symbol the header
+declares, and its closed-form schedule arithmetic agrees with the oracle's real FIFO queues."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1909_02625_amd as D
+from oracle import dsp_oracle as O
+from tests.test_oracle_pins import PAPER_TUPLES, _run_counting
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "dsp.h")
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(dsp_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert len(names) >= 30
+    lib = ctypes.CDLL(D.lib_path())
+    for n in names:
+        assert hasattr(lib, n), "libdsp_hip.so does not export %s" % n
+    assert sorted(D.EXPORTED_SYMBOLS) == names, "binding and header disagree"
+    for n in names:  # the binding offers the same names
+        assert hasattr(D, n), n
+
+
+def test_strerror_and_status_codes():
+    assert D.dsp_strerror(0) == "ok"
+    assert "order" in D.dsp_strerror(2)
+    with pytest.raises(D.DSPError) as e:
+        D.dsp_schedule_validate((1, 1), (2, 0))   # p_{K-1} != 0
+    assert e.value.status == 1 and "p_{K-1}" in str(e.value)
+
+
+@pytest.mark.parametrize("p,m,q", PAPER_TUPLES)
+def test_schedule_validate_matches_paper_tuples(p, m, q):
+    assert D.dsp_schedule_validate(p, m) == list(q) == O.queue_lengths(p, m)
+
+
+@pytest.mark.parametrize("p,m", [((1, 0), (1, 0)), ((2, 0), (2, 0)), ((1, 1, 0), (2, 2, 0)), ((0, 0), (2, 0)),
+                                 ((1, 0), (0, 0)), ((1, 1, 0), (4, 4, 0)), ((1, 0), (2, -1))])
+def test_schedule_rejects_what_the_oracle_rejects(p, m):
+    with pytest.raises(ValueError):
+        O.queue_lengths(p, m)
+    with pytest.raises(D.DSPError):
+        D.dsp_schedule_validate(p, m)
+
+
+@pytest.mark.parametrize("p,m,_q", PAPER_TUPLES + [((1, 0), (2, 0), None), ((1, 1, 0), (7, 3, 1), None),
+                                                   ((2, 1, 3, 0), (12, 8, 4, 0), None), ((0, 0, 0), (0, 0, 0), None)])
+def test_closed_form_index_equals_fifo_simulation(p, m, _q):
+    """Brute force: the oracle pushes tagged items through real queues for 64 ticks; the library's closed
+    form must name the same forward batch, backward batch and update count for every block and tick, and
+    its ring slots must never collide (a slot is not rewritten while a batch that still needs it lives there)."""
+    K = len(p)
+    _, orc = _run_counting(p, m, 64)
+    q = D.dsp_schedule_validate(p, m)
+    live = [dict() for _ in range(K)]     # ring slot -> batch held, per block
+    for rec in orc.log:
+        tau = rec["tau"]
+        for k in range(K):
+            ix = D.dsp_schedule_index(p, m, k, tau)
+            assert ix["a"] == (rec["fwd"][k] if rec["fwd"][k] is not None else -1)
+            assert ix["b"] == (rec["bwd"][k] if rec["bwd"][k] is not None else -1)
+            assert ix["version"] == rec["version"][k]
+            ring = 1 + m[k] + (p[k - 1] if k else 0)
+            if ix["b"] >= 0:
+                assert ix["slot_bwd"] == ix["b"] % ring
+                assert ix["q_write"] == (ix["b"] % (1 + q[k]) if k > 0 else -1)
+                assert ix["q_read"] == (ix["b"] % (1 + q[k + 1]) if k < K - 1 else -1)
+            # the producer (block k-1, or the data source) fills slot of batch tau - P_{k-1} at this tick
+            a_prod = tau - sum(p[:k - 1]) if k > 0 else tau
+            if a_prod >= 0:
+                slot = a_prod % ring
+                old = live[k].get(slot)
+                if old is not None:
+                    # the batch being overwritten must already have had its backward in block k
+                    assert old + sum(p[:k]) + m[k] <= tau - 1, (k, tau, old)
+                live[k][slot] = a_prod
+
+
+def test_queue_memory_formula():
+    """Section 3.3: extra space O(sum_k m_k + p_k + q_k) -- rings hold (1+m_k+p_{k-1}) inputs and (1+q_k) gradients."""
+    p, m = (1, 1, 0), (4, 2, 0)
+    h = [100, 40, 20, 10]
+    q = D.dsp_schedule_validate(p, m)
+    want = (1 + 4) * 100 + (1 + 2 + 1) * 40 + (1 + 0 + 1) * 20 + (1 + q[1]) * 40 + (1 + q[2]) * 20
+    assert D.dsp_schedule_queue_elems(p, m, h) == want
+    # never more than the paper's three separate queues per block
+    paper = sum((1 + m[k]) * h[k] + (1 + p[k]) * h[k + 1] + (1 + q[k]) * h[k] for k in range(3))
+    assert want <= paper
+
+
+def test_make_block_desc_marshalling():
+    from workloads import get_config
+    cfg = get_config("resnet20", batch=4, hw=8)
+    desc, keep = D.make_block_desc(cfg["blocks"][1], (4, 16, 8, 8), D.DSP_FP32, 1, 3, 2, p_prev=1)
+    assert desc.n_layers == len(cfg["blocks"][1]) and desc.m_k == 2 and desc.p_prev == 1
+    ops = [keep[i].op for i in range(desc.n_layers)]
+    assert ops[0] == 0 and ops[1] == 1
+    res = [keep[i].in1 for i in range(desc.n_layers) if keep[i].op == 1]
+    assert -2 in res and any(r >= -1 for r in res)
