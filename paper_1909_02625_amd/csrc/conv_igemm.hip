@@ -11,10 +11,11 @@
 // xcol / dycol are never materialised: the loader gathers 16-byte channel runs of the NHWC
 // tensor straight into LDS (zero for padding; for a strided backward-data only taps that hit an
 // output pixel are non-zero).  All kernels share one tile engine: a 256-thread workgroup
-// (4 waves) owns a BM x BN output tile; the K dimension is streamed through double-buffered
-// LDS tiles whose rows hold BKB bytes of k plus a 16-byte pad (conflict-free ds_read_b128);
-// every lane feeds the MFMA with 16-byte k-runs (8 bf16 -> one 32x32x16 / 16x16x32 MFMA,
-// 4 floats -> four 32x32x2 / 16x16x4 MFMAs).  Accumulation is fp32 in both storage types.
+// (4 waves) owns a BM x BN output tile; the K dimension is streamed through LDS tiles whose rows
+// hold BKB bytes of k plus a 16-byte pad; every lane feeds the MFMA with 16-byte k-runs
+// (8 bf16 -> one 32x32x16 / 16x16x32 MFMA, 4 floats -> four 32x32x2 / 16x16x4 MFMAs).
+// Accumulation is fp32 in both storage types.  Tiles are chosen per launch so that even the
+// small CIFAR-shaped layers put a few hundred workgroups on the 256 compute units.
 #include <stdio.h>
 
 #include "common.h"
@@ -84,11 +85,13 @@ __device__ inline int acc_row(int lane, int j)
     return (lane >> 4) * 4 + j;
 }
 
+constexpr int cmax(int a, int b) { return a > b ? a : b; }
+
 // ---- tile configuration -----------------------------------------------------------------------
-template <typename T_, int MT_, int WGM_, int WGN_, int TM_, int TN_, int BKB_>
+template <typename T_, int MT_, int WGM_, int WGN_, int TM_, int TN_, int BKB_, int STAGES_>
 struct Tile {
     typedef T_ T;
-    static constexpr int MT = MT_, WGM = WGM_, WGN = WGN_, TM = TM_, TN = TN_, BKB = BKB_;
+    static constexpr int MT = MT_, WGM = WGM_, WGN = WGN_, TM = TM_, TN = TN_, BKB = BKB_, STAGES = STAGES_;
     static_assert(WGM * WGN == 4, "four waves per workgroup");
     static constexpr int BM = WGM * TM * MT;
     static constexpr int BN = WGN * TN * MT;
@@ -101,8 +104,13 @@ struct Tile {
     static constexpr int A_CHUNKS = BM * CPR, B_CHUNKS = BN * CPR;
     static constexpr int A_PER = (A_CHUNKS + kThreads - 1) / kThreads;
     static constexpr int B_PER = (B_CHUNKS + kThreads - 1) / kThreads;
-    static constexpr int LDS_BYTES = 2 * (BM + BN) * ROWB;
-    static_assert(BKB % KSB == 0 && kThreads % CPR == 0, "tile shape");
+    static constexpr int STAGE_BYTES = (BM + BN) * ROWB;
+    static constexpr int LOAD_BYTES = STAGES * STAGE_BYTES;
+    // the output tile is staged through LDS so that global stores are whole 16-byte runs
+    static constexpr int EPI_ROWB = BN * (int)sizeof(T) + 16;
+    static constexpr int EPI_BYTES = BM * EPI_ROWB;
+    static constexpr int LDS_BYTES = cmax(LOAD_BYTES, EPI_BYTES);
+    static_assert(BKB % KSB == 0 && kThreads % CPR == 0 && (STAGES == 1 || STAGES == 2), "tile shape");
 };
 
 template <typename TL>
@@ -127,6 +135,17 @@ __device__ inline void mma_tile(const char* sA, const char* sB, int wave_m, int 
     }
 }
 
+template <typename TL>
+__device__ inline void zero_acc(typename Mma<typename TL::T, TL::MT>::Acc (&acc)[TL::TM][TL::TN])
+{
+#pragma unroll
+    for (int i = 0; i < TL::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TL::TN; ++j)
+#pragma unroll
+            for (int e = 0; e < Mma<typename TL::T, TL::MT>::kAcc; ++e) acc[i][j][e] = 0.f;
+}
+
 // ---- forward / backward-data ------------------------------------------------------------------
 // The gathered tensor `in` is N x Hi x Wi x Ci; output rows m = (n, ho, wo) over N x Ho x Wo.
 // Tap (r, s) of output pixel (ho, wo) reads position t = o*ostride - pad + tap; with idil = 2
@@ -134,22 +153,33 @@ __device__ inline void mma_tile(const char* sA, const char* sB, int wave_m, int 
 struct GatherGeom {
     int N, Hi, Wi, Ci, Ho, Wo, Co, R, S, pad_h, pad_w, ostride, idil;
     int M, Kdim;
+    int accum;    // add to `out` instead of overwriting it
+    int out_vec;  // `out` rows can be written as whole 16-byte runs
 };
 
-template <typename TL, bool VEC, bool ACCUM>
+// 16-byte loads through a buffer descriptor: the hardware returns zeros for any offset at or past
+// `bytes`, so padding taps, rows past the end of the tensor and the k tail need no branch and no
+// zero fill -- the lane just presents an out-of-range offset.
+constexpr uint32_t kOutOfRange = 0xfffffff0u;
+
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ inline u32x4 load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
+{
+    return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0));
+}
+
+template <typename TL, bool VEC>
 __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typename TL::T* __restrict__ in,
                                                                     const typename TL::T* __restrict__ wgt,
                                                                     typename TL::T* __restrict__ out, GatherGeom g)
 {
     typedef typename TL::T T;
     constexpr int E = TL::E, CPR = TL::CPR, ROWS_PER_PASS = kThreads / CPR;
+    constexpr uint32_t SZ = sizeof(T);
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    char* sA[2];
-    char* sB[2];
-    sA[0] = smem;
-    sA[1] = smem + (TL::BM + TL::BN) * TL::ROWB;
-    sB[0] = sA[0] + TL::BM * TL::ROWB;
-    sB[1] = sA[1] + TL::BM * TL::ROWB;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave / TL::WGN, wave_n = wave % TL::WGN;
@@ -157,28 +187,49 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
     const int tiles_n = (g.Co + TL::BN - 1) / TL::BN;
     const int m0 = (blockIdx.x / tiles_n) * TL::BM, n0 = (blockIdx.x % tiles_n) * TL::BN;
 
-    const int kc = tid % CPR;      // which 16-byte run of the k tile this thread moves
-    const int row0 = tid / CPR;    // first tile row it moves; further rows are +ROWS_PER_PASS apart
+    const int kc = tid % CPR;    // which 16-byte run of the k tile this thread moves
+    const int row0 = tid / CPR;  // first tile row it moves; further rows are +ROWS_PER_PASS apart
+    const bool dil = g.idil == 2;
+    const bool masked = VEC && !dil;  // plain vector path: per-row tap masks
 
-    // per-row gather state of the A operand
-    int64_t a_base[TL::A_PER];
-    int a_th0[TL::A_PER], a_tw0[TL::A_PER];
+    // Per-row gather state of the A operand (byte offsets modulo 2^32; tensors are < 4 GB, checked on the host).
+    //   masked:    a_off = byte offset of pixel (ho*ostride - pad_h, wo*ostride - pad_w) of the row's image
+    //              (may lie before the tensor), a_aux = bit (r*S + s) set iff tap (r, s) falls inside the image
+    //   otherwise: a_off = byte offset of the row's image, a_aux = th0 (low half) | tw0 (high half)
+    uint32_t a_off[TL::A_PER], a_aux[TL::A_PER];
 #pragma unroll
     for (int i = 0; i < TL::A_PER; ++i) {
         const int row = row0 + i * ROWS_PER_PASS;
         const int m = m0 + row;
+        a_off[i] = 0;
+        a_aux[i] = masked ? 0u : 0x80008000u;  // nothing valid
         if (row < TL::BM && m < g.M) {
             const int wo = m % g.Wo, t = m / g.Wo, ho = t % g.Ho, n = t / g.Ho;
-            a_base[i] = (int64_t)n * g.Hi * g.Wi * g.Ci;
-            a_th0[i] = ho * g.ostride - g.pad_h;
-            a_tw0[i] = wo * g.ostride - g.pad_w;
-        } else {
-            a_base[i] = -1;
-            a_th0[i] = a_tw0[i] = 0;
+            const int th0 = ho * g.ostride - g.pad_h, tw0 = wo * g.ostride - g.pad_w;
+            const uint32_t img = (uint32_t)n * g.Hi * g.Wi * g.Ci * SZ;
+            if (masked) {
+                uint32_t mask = 0;
+                for (int r = 0; r < g.R; ++r)
+                    for (int s = 0; s < g.S; ++s)
+                        mask |= (uint32_t)(th0 + r >= 0 && th0 + r < g.Hi && tw0 + s >= 0 && tw0 + s < g.Wi) << (r * g.S + s);
+                a_off[i] = img + (uint32_t)((th0 * g.Wi + tw0) * g.Ci) * SZ;
+                a_aux[i] = mask;
+            } else {
+                a_off[i] = img;
+                a_aux[i] = ((uint32_t)th0 & 0xffffu) | ((uint32_t)tw0 << 16);
+            }
         }
     }
+    uint32_t b_off[TL::B_PER];
+#pragma unroll
+    for (int i = 0; i < TL::B_PER; ++i) {
+        const int row = row0 + i * ROWS_PER_PASS, co = n0 + row;
+        b_off[i] = (row < TL::BN && co < g.Co) ? (uint32_t)(co * g.Kdim) * SZ : kOutOfRange;
+    }
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc(in, (uint32_t)g.N * g.Hi * g.Wi * g.Ci * SZ);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(wgt, (uint32_t)g.Co * g.Kdim * SZ);
 
-    // k position of this thread's run: element kk = (r*S + s)*Ci + ci
+    // k position of this thread's run: element kk = (kr*S + ks)*Ci + kci
     int kk = kc * E, kr = 0, ks = 0, kci = kc * E;
     while (kci >= g.Ci) {
         kci -= g.Ci;
@@ -186,63 +237,59 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
     }
 
     u32x4 ra[TL::A_PER], rb[TL::B_PER];
+    const T zero = from_float<T>(0.f);
 
-    auto gather_one = [&](int64_t base, int th0, int tw0, int r, int s, int ci) -> T {
-        int th = th0 + r, tw = tw0 + s;
-        bool ok = base >= 0 && th >= 0 && tw >= 0;
-        if (g.idil == 2) {
+    // byte offset of tap (r, s), channel ci of the row described by (off, aux), or kOutOfRange  [unmasked rows]
+    auto tap_offset = [&](uint32_t off, uint32_t aux, int r, int s, int ci) -> uint32_t {
+        int th = (int)(int16_t)(aux & 0xffffu) + r, tw = (int)(int16_t)(aux >> 16) + s;
+        bool ok = th >= 0 && tw >= 0;
+        if (dil) {
             ok = ok && ((th | tw) & 1) == 0;
             th >>= 1;
             tw >>= 1;
         }
         ok = ok && th < g.Hi && tw < g.Wi;
-        return ok ? in[base + ((int64_t)th * g.Wi + tw) * g.Ci + ci] : from_float<T>(0.f);
+        return ok ? off + (uint32_t)((th * g.Wi + tw) * g.Ci + ci) * SZ : kOutOfRange;
     };
 
     auto load_tiles = [&]() {
         if (VEC) {
             const bool k_ok = kk < g.Kdim;
+            if (!dil) {
+                const uint32_t tap_off = (uint32_t)((kr * g.Wi + ks) * g.Ci + kci) * SZ;
+                const int tap = kr * g.S + ks;
 #pragma unroll
-            for (int i = 0; i < TL::A_PER; ++i) {
-                int th = a_th0[i] + kr, tw = a_tw0[i] + ks;
-                bool ok = k_ok && a_base[i] >= 0 && th >= 0 && tw >= 0;
-                if (g.idil == 2) {
-                    ok = ok && ((th | tw) & 1) == 0;
-                    th >>= 1;
-                    tw >>= 1;
+                for (int i = 0; i < TL::A_PER; ++i) {
+                    const bool ok = k_ok && ((a_aux[i] >> tap) & 1u) != 0;
+                    ra[i] = load16(rin, ok ? a_off[i] + tap_off : kOutOfRange);
                 }
-                ok = ok && th < g.Hi && tw < g.Wi;
-                u32x4 v = {0, 0, 0, 0};
-                if (ok) v = *(const u32x4*)(in + a_base[i] + ((int64_t)th * g.Wi + tw) * g.Ci + kci);
-                ra[i] = v;
-            }
+            } else {
 #pragma unroll
-            for (int i = 0; i < TL::B_PER; ++i) {
-                const int row = row0 + i * ROWS_PER_PASS, co = n0 + row;
-                u32x4 v = {0, 0, 0, 0};
-                if (row < TL::BN && co < g.Co && k_ok) v = *(const u32x4*)(wgt + (int64_t)co * g.Kdim + kk);
-                rb[i] = v;
+                for (int i = 0; i < TL::A_PER; ++i)
+                    ra[i] = load16(rin, k_ok ? tap_offset(a_off[i], a_aux[i], kr, ks, kci) : kOutOfRange);
             }
+            const uint32_t kkb = (uint32_t)kk * SZ;
+#pragma unroll
+            for (int i = 0; i < TL::B_PER; ++i)
+                rb[i] = load16(rw, (k_ok && b_off[i] != kOutOfRange) ? b_off[i] + kkb : kOutOfRange);
         } else {
-            // generic path (channel count not a multiple of the 16-byte run): element-wise gather
+            // generic path (channel count not a multiple of the 16-byte run, unaligned bases, huge filters)
 #pragma unroll
             for (int i = 0; i < TL::A_PER; ++i) {
                 alignas(16) T tmp[E];
                 for (int e = 0; e < E; ++e) {
                     const int k = kk + e;
                     const int tap = k / g.Ci, ci = k % g.Ci;
-                    tmp[e] = k < g.Kdim ? gather_one(a_base[i], a_th0[i], a_tw0[i], tap / g.S, tap % g.S, ci)
-                                        : from_float<T>(0.f);
+                    const uint32_t o = k < g.Kdim ? tap_offset(a_off[i], a_aux[i], tap / g.S, tap % g.S, ci) : kOutOfRange;
+                    tmp[e] = o != kOutOfRange ? in[o / SZ] : zero;
                 }
                 ra[i] = *(const u32x4*)tmp;
             }
 #pragma unroll
             for (int i = 0; i < TL::B_PER; ++i) {
-                const int row = row0 + i * ROWS_PER_PASS, co = n0 + row;
                 alignas(16) T tmp[E];
                 for (int e = 0; e < E; ++e)
-                    tmp[e] = (row < TL::BN && co < g.Co && kk + e < g.Kdim) ? wgt[(int64_t)co * g.Kdim + kk + e]
-                                                                           : from_float<T>(0.f);
+                    tmp[e] = (b_off[i] != kOutOfRange && kk + e < g.Kdim) ? wgt[b_off[i] / SZ + kk + e] : zero;
                 rb[i] = *(const u32x4*)tmp;
             }
         }
@@ -256,68 +303,138 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
         }
     };
     auto store_tiles = [&](int buf) {
+        char* sA = smem + buf * TL::STAGE_BYTES;
+        char* sB = sA + TL::BM * TL::ROWB;
 #pragma unroll
         for (int i = 0; i < TL::A_PER; ++i) {
             const int row = row0 + i * ROWS_PER_PASS;
-            if (row < TL::BM) *(u32x4*)(sA[buf] + row * TL::ROWB + kc * 16) = ra[i];
+            if (row < TL::BM) *(u32x4*)(sA + row * TL::ROWB + kc * 16) = ra[i];
         }
 #pragma unroll
         for (int i = 0; i < TL::B_PER; ++i) {
             const int row = row0 + i * ROWS_PER_PASS;
-            if (row < TL::BN) *(u32x4*)(sB[buf] + row * TL::ROWB + kc * 16) = rb[i];
+            if (row < TL::BN) *(u32x4*)(sB + row * TL::ROWB + kc * 16) = rb[i];
         }
     };
 
     typename Mma<T, TL::MT>::Acc acc[TL::TM][TL::TN];
-#pragma unroll
-    for (int i = 0; i < TL::TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TL::TN; ++j)
-#pragma unroll
-            for (int e = 0; e < Mma<T, TL::MT>::kAcc; ++e) acc[i][j][e] = 0.f;
+    zero_acc<TL>(acc);
 
     const int nk = (g.Kdim + TL::BK - 1) / TL::BK;
     load_tiles();
-    store_tiles(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) {
-            advance_k();
-            load_tiles();
+    if (TL::STAGES == 2) {
+        store_tiles(0);
+        __syncthreads();
+        for (int kt = 0; kt < nk; ++kt) {
+            const int cur = kt & 1;
+            if (kt + 1 < nk) {
+                advance_k();
+                load_tiles();
+            }
+            mma_tile<TL>(smem + cur * TL::STAGE_BYTES, smem + cur * TL::STAGE_BYTES + TL::BM * TL::ROWB, wave_m, wave_n,
+                         lane, acc);
+            if (kt + 1 < nk) store_tiles(cur ^ 1);
+            __syncthreads();
         }
-        mma_tile<TL>(sA[cur], sB[cur], wave_m, wave_n, lane, acc);
-        if (kt + 1 < nk) store_tiles(cur ^ 1);
+    } else {
+        for (int kt = 0; kt < nk; ++kt) {
+            if (kt > 0) __syncthreads();  // every wave has finished reading the previous tile
+            store_tiles(0);
+            __syncthreads();
+            if (kt + 1 < nk) {  // the next tile's global loads fly while this one is multiplied
+                advance_k();
+                load_tiles();
+            }
+            mma_tile<TL>(smem, smem + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
+        }
         __syncthreads();
     }
 
-    // epilogue: lanes of one accumulator register cover MT consecutive channels of one output row
+    // ---- epilogue: (optionally add the old values,) stage the tile in LDS, store 16-byte runs ----
+    constexpr int kAcc = Mma<T, TL::MT>::kAcc;
+    if (g.accum) {
+#pragma unroll
+        for (int i = 0; i < TL::TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TL::TN; ++j) {
+                const int col = n0 + (wave_n * TL::TN + j) * TL::MT + lane % TL::MT;
+#pragma unroll
+                for (int e = 0; e < kAcc; ++e) {
+                    const int m = m0 + (wave_m * TL::TM + i) * TL::MT + acc_row<TL::MT>(lane, e);
+                    if (m < g.M && col < g.Co) acc[i][j][e] += to_float<T>(out[(int64_t)m * g.Co + col]);
+                }
+            }
+    }
 #pragma unroll
     for (int i = 0; i < TL::TM; ++i)
 #pragma unroll
         for (int j = 0; j < TL::TN; ++j) {
-            const int col = n0 + (wave_n * TL::TN + j) * TL::MT + lane % TL::MT;
+            const int lcol = (wave_n * TL::TN + j) * TL::MT + lane % TL::MT;
 #pragma unroll
-            for (int e = 0; e < Mma<T, TL::MT>::kAcc; ++e) {
-                const int m = m0 + (wave_m * TL::TM + i) * TL::MT + acc_row<TL::MT>(lane, e);
-                if (m < g.M && col < g.Co) {
-                    T* p = out + (int64_t)m * g.Co + col;
-                    float v = acc[i][j][e];
-                    if (ACCUM) v += to_float<T>(*p);
-                    *p = from_float<T>(v);
-                }
+            for (int e = 0; e < kAcc; ++e) {
+                const int lrow = (wave_m * TL::TM + i) * TL::MT + acc_row<TL::MT>(lane, e);
+                *(T*)(smem + lrow * TL::EPI_ROWB + lcol * (int)sizeof(T)) = from_float<T>(acc[i][j][e]);
             }
         }
+    __syncthreads();
+    constexpr int OCPR = TL::BN / E;  // 16-byte runs per tile row
+    for (int c = tid; c < TL::BM * OCPR; c += kThreads) {
+        const int lrow = c / OCPR, cc = (c % OCPR) * E;
+        const int m = m0 + lrow, col = n0 + cc;
+        if (m >= g.M || col >= g.Co) continue;
+        const char* src = smem + lrow * TL::EPI_ROWB + cc * (int)sizeof(T);
+        T* dst = out + (int64_t)m * g.Co + col;
+        if (g.out_vec && col + E <= g.Co) {
+            *(u32x4*)dst = *(const u32x4*)src;
+        } else {
+            for (int e = 0; e < E && col + e < g.Co; ++e) dst[e] = ((const T*)src)[e];
+        }
+    }
 }
 
 // ---- backward-weight --------------------------------------------------------------------------
-// dw[co][j] = sum_m dy[m][co] * xcol[m][j].  Both operands are stored with m as the slow index,
-// so the loader transposes 16-byte channel runs into LDS rows that are contiguous in m.
-// blockIdx.y selects a slice of m; slices are summed afterwards in a fixed order.
+// dw[co][j] = sum_m dy[m][co] * xcol[m][j].  Both operands are stored with m as the slow index while
+// the MFMA wants runs along m, so the loader moves E x E micro-tiles (E rows of m, one 16-byte
+// channel run each; E = 8 for bf16, 4 for fp32), transposes them in registers and writes E
+// 16-byte runs along m into LDS.  Lanes of one 8-lane group own consecutive m groups of the
+// same channel group: their LDS writes are one contiguous 128-byte stripe and their global reads
+// are 128-byte row segments.  blockIdx.y selects a slice of m; slices are summed afterwards in a
+// fixed order.
 struct WgradGeom {
     int N, H, W, Ci, Ho, Wo, Co, R, S, pad, stride;
     int M, Kdim, m_per_split;
 };
+
+template <typename T>
+__device__ inline void transpose_micro(const u32x4 (&in)[16 / sizeof(T)], u32x4 (&out)[16 / sizeof(T)]);
+
+template <>
+__device__ inline void transpose_micro<float>(const u32x4 (&in)[4], u32x4 (&out)[4])
+{
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        u32x4 v = {in[0][c], in[1][c], in[2][c], in[3][c]};
+        out[c] = v;
+    }
+}
+
+template <>
+__device__ inline void transpose_micro<bf16_t>(const u32x4 (&in)[8], u32x4 (&out)[8])
+{
+    // in[e] = 8 channels of row e (2 per dword); out[c] = 8 rows of channel c (2 per dword, row 2i in the low half)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        u32x4 lo, hi;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t a = in[2 * i][j], b = in[2 * i + 1][j];
+            lo[i] = (a & 0xffffu) | (b << 16);
+            hi[i] = (a >> 16) | (b & 0xffff0000u);
+        }
+        out[2 * j] = lo;
+        out[2 * j + 1] = hi;
+    }
+}
 
 template <typename TL, bool VEC>
 __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL::T* __restrict__ x,
@@ -326,13 +443,8 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
 {
     typedef typename TL::T T;
     constexpr int E = TL::E, BKm = TL::BK;
+    static_assert(TL::STAGES == 2, "backward-weight double-buffers its LDS tiles");
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    char* sA[2];
-    char* sB[2];
-    sA[0] = smem;
-    sA[1] = smem + (TL::BM + TL::BN) * TL::ROWB;
-    sB[0] = sA[0] + TL::BM * TL::ROWB;
-    sB[1] = sA[1] + TL::BM * TL::ROWB;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave / TL::WGN, wave_n = wave % TL::WGN;
@@ -341,95 +453,188 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
     const int j0 = (blockIdx.x % tiles_n) * TL::BN;  // first (r,s,ci) column of the tile
     const int m_begin = blockIdx.y * g.m_per_split;
     const int m_end = min(g.M, m_begin + g.m_per_split);
-
-    // A' (dy): chunk = E channels of one m row;  B' (x): chunk = E input channels of one tap of one m row
-    constexpr int A_CPR = TL::BM / E > 0 ? TL::BM / E : 1, B_CPR = TL::BN / E > 0 ? TL::BN / E : 1;
-    constexpr int A_CH = A_CPR * BKm, B_CH = B_CPR * BKm;
-    constexpr int A_PER = (A_CH + kThreads - 1) / kThreads, B_PER = (B_CH + kThreads - 1) / kThreads;
+    const int nk = (m_end - m_begin + BKm - 1) / BKm;
 
     typename Mma<T, TL::MT>::Acc acc[TL::TM][TL::TN];
-#pragma unroll
-    for (int i = 0; i < TL::TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TL::TN; ++j)
-#pragma unroll
-            for (int e = 0; e < Mma<T, TL::MT>::kAcc; ++e) acc[i][j][e] = 0.f;
+    zero_acc<TL>(acc);
 
-    alignas(16) T ra[A_PER][E];
-    alignas(16) T rb[B_PER][E];
-    const T zero = from_float<T>(0.f);
-
-    auto load_tiles = [&](int mb) {
+    if (VEC) {
+        constexpr int MG = BKm / E;                       // m groups per LDS row
+        constexpr int NA = (TL::BM / E) * MG, NB = (TL::BN / E) * MG;
+        constexpr int PER = (NA + NB + kThreads - 1) / kThreads;
+        static_assert(TL::BM % E == 0 && TL::BN % E == 0 && BKm % E == 0, "micro-tiles must tile the LDS tile");
+        // fixed per micro-tile: which operand, channel group, m group; for x also the tap and the pixel walk
+        int mt_row[PER];      // LDS row of channel 0 of the micro-tile (B rows follow the BM A rows), -1 = none
+        int mt_col[PER];      // global channel / column offset of the 16-byte run (-1: outside the tensor)
+        int mt_mg[PER];
+        int px_n[PER], px_h[PER], px_w[PER], tap_r[PER], tap_s[PER];
 #pragma unroll
-        for (int i = 0; i < A_PER; ++i) {
-            const int c = tid + i * kThreads, mrow = c / A_CPR, cc = (c % A_CPR) * E;
-            const int m = mb + mrow, co = c0 + cc;
-            const bool ok = c < A_CH && m < m_end;
-            if (VEC) {
-                u32x4 v = {0, 0, 0, 0};
-                if (ok && co < g.Co) v = *(const u32x4*)(dy + (int64_t)m * g.Co + co);
-                *(u32x4*)ra[i] = v;
-            } else {
-                for (int e = 0; e < E; ++e)
-                    ra[i][e] = (ok && co + e < g.Co && cc + e < TL::BM) ? dy[(int64_t)m * g.Co + co + e] : zero;
+        for (int i = 0; i < PER; ++i) {
+            const int c = tid + i * kThreads;
+            mt_row[i] = -1;
+            mt_col[i] = -1;
+            mt_mg[i] = 0;
+            px_n[i] = px_h[i] = px_w[i] = tap_r[i] = tap_s[i] = 0;
+            if (c < NA) {
+                const int mg = c % MG, cg = c / MG;
+                mt_row[i] = cg * E;
+                mt_mg[i] = mg;
+                mt_col[i] = (c0 + cg * E < g.Co) ? c0 + cg * E : -1;
+            } else if (c < NA + NB) {
+                const int cb = c - NA, mg = cb % MG, cg = cb / MG;
+                mt_row[i] = TL::BM + cg * E;
+                mt_mg[i] = mg;
+                const int j = j0 + cg * E;
+                if (j < g.Kdim) {
+                    const int tap = j / g.Ci;
+                    mt_col[i] = j % g.Ci;
+                    tap_r[i] = tap / g.S;
+                    tap_s[i] = tap % g.S;
+                }
+                const int m = m_begin + mg * E;  // first row of the micro-tile in the first k step
+                px_w[i] = m % g.Wo;
+                const int t = m / g.Wo;
+                px_h[i] = t % g.Ho;
+                px_n[i] = t / g.Ho;
             }
         }
+        u32x4 regs[PER][E];
+
+        constexpr uint32_t SZ = sizeof(T);
+        const __amdgpu_buffer_rsrc_t rdy = make_rsrc(dy, (uint32_t)g.M * g.Co * SZ);
+        const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)g.N * g.H * g.W * g.Ci * SZ);
+        auto load_tiles = [&](int mb) {
 #pragma unroll
-        for (int i = 0; i < B_PER; ++i) {
-            const int c = tid + i * kThreads, mrow = c / B_CPR, cc = (c % B_CPR) * E;
-            const int m = mb + mrow, j = j0 + cc;
-            const bool ok = c < B_CH && m < m_end;
-            const int wo = m % g.Wo, t = m / g.Wo, ho = t % g.Ho, n = t / g.Ho;
-            if (VEC) {
-                const int tap = j / g.Ci, ci = j % g.Ci, r = tap / g.S, s = tap % g.S;
-                const int hi = ho * g.stride - g.pad + r, wi = wo * g.stride - g.pad + s;
-                u32x4 v = {0, 0, 0, 0};
-                if (ok && j < g.Kdim && hi >= 0 && hi < g.H && wi >= 0 && wi < g.W)
-                    v = *(const u32x4*)(x + (((int64_t)n * g.H + hi) * g.W + wi) * g.Ci + ci);
-                *(u32x4*)rb[i] = v;
-            } else {
+            for (int i = 0; i < PER; ++i) {
+                const int c = tid + i * kThreads;
+                const int mfirst = mb + mt_mg[i] * E;
+                if (c < NA) {
+                    // E consecutive rows of dy: offsets Co apart; out-of-range rows read as zeros
+                    uint32_t off = mt_col[i] >= 0 ? (uint32_t)(mfirst * g.Co + mt_col[i]) * SZ : kOutOfRange;
+                    const uint32_t step = (uint32_t)g.Co * SZ;
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        regs[i][e] = load16(rdy, (mt_col[i] >= 0 && mfirst + e < m_end) ? off : kOutOfRange);
+                        off += step;
+                    }
+                } else if (c < NA + NB) {
+                    // E consecutive output pixels, one tap: walk along the image row, re-derive on wrap
+                    int n = px_n[i], h = px_h[i], w = px_w[i];
+                    int hi = h * g.stride - g.pad + tap_r[i], wi = w * g.stride - g.pad + tap_s[i];
+                    bool hok = mt_col[i] >= 0 && hi >= 0 && hi < g.H;
+                    uint32_t rowoff = (uint32_t)(((n * g.H + hi) * g.W) * g.Ci + mt_col[i]) * SZ;
+                    const uint32_t pix = (uint32_t)g.Ci * SZ;
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        const bool ok = hok && wi >= 0 && wi < g.W && mfirst + e < m_end;
+                        regs[i][e] = load16(rx, ok ? rowoff + (uint32_t)wi * pix : kOutOfRange);
+                        wi += g.stride;
+                        if (++w == g.Wo) {
+                            w = 0;
+                            wi = tap_s[i] - g.pad;
+                            if (++h == g.Ho) { h = 0; ++n; }
+                            hi = h * g.stride - g.pad + tap_r[i];
+                            hok = mt_col[i] >= 0 && hi >= 0 && hi < g.H;
+                            rowoff = (uint32_t)(((n * g.H + hi) * g.W) * g.Ci + mt_col[i]) * SZ;
+                        }
+                    }
+                    // walk this micro-tile's first pixel to the next k step
+                    int wn = px_w[i] + BKm;
+                    while (wn >= g.Wo) {
+                        wn -= g.Wo;
+                        if (++px_h[i] == g.Ho) { px_h[i] = 0; ++px_n[i]; }
+                    }
+                    px_w[i] = wn;
+                }
+            }
+        };
+        auto store_tiles = [&](int buf) {
+            char* base = smem + buf * TL::STAGE_BYTES;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                if (mt_row[i] < 0) continue;
+                u32x4 tr[E];
+                transpose_micro<T>(regs[i], tr);
+#pragma unroll
+                for (int ch = 0; ch < E; ++ch) *(u32x4*)(base + (mt_row[i] + ch) * TL::ROWB + mt_mg[i] * 16) = tr[ch];
+            }
+        };
+        if (nk > 0) {
+            load_tiles(m_begin);
+            store_tiles(0);
+        }
+        __syncthreads();
+        for (int kt = 0; kt < nk; ++kt) {
+            const int cur = kt & 1;
+            if (kt + 1 < nk) load_tiles(m_begin + (kt + 1) * BKm);
+            mma_tile<TL>(smem + cur * TL::STAGE_BYTES, smem + cur * TL::STAGE_BYTES + TL::BM * TL::ROWB, wave_m, wave_n,
+                         lane, acc);
+            if (kt + 1 < nk) store_tiles(cur ^ 1);
+            __syncthreads();
+        }
+    } else {
+        // generic path: element-wise loads and LDS writes
+        constexpr int A_CPR = TL::BM / E, B_CPR = TL::BN / E;
+        constexpr int A_CH = A_CPR * BKm, B_CH = B_CPR * BKm;
+        constexpr int A_PER = (A_CH + kThreads - 1) / kThreads, B_PER = (B_CH + kThreads - 1) / kThreads;
+        alignas(16) T ra[A_PER][E];
+        alignas(16) T rb[B_PER][E];
+        const T zero = from_float<T>(0.f);
+        auto load_tiles = [&](int mb) {
+#pragma unroll
+            for (int i = 0; i < A_PER; ++i) {
+                const int c = tid + i * kThreads, mrow = c / A_CPR, cc = (c % A_CPR) * E;
+                const int m = mb + mrow, co = c0 + cc;
+                const bool ok = c < A_CH && m < m_end;
+                for (int e = 0; e < E; ++e) ra[i][e] = (ok && co + e < g.Co) ? dy[(int64_t)m * g.Co + co + e] : zero;
+            }
+#pragma unroll
+            for (int i = 0; i < B_PER; ++i) {
+                const int c = tid + i * kThreads, mrow = c / B_CPR, cc = (c % B_CPR) * E;
+                const int m = mb + mrow, j = j0 + cc;
+                const bool ok = c < B_CH && m < m_end;
+                const int wo = m % g.Wo, t = m / g.Wo, ho = t % g.Ho, n = t / g.Ho;
                 for (int e = 0; e < E; ++e) {
                     const int je = j + e;
                     const int tap = je / g.Ci, ci = je % g.Ci, r = tap / g.S, s = tap % g.S;
                     const int hi = ho * g.stride - g.pad + r, wi = wo * g.stride - g.pad + s;
-                    rb[i][e] = (ok && je < g.Kdim && cc + e < TL::BN && hi >= 0 && hi < g.H && wi >= 0 && wi < g.W)
+                    rb[i][e] = (ok && je < g.Kdim && hi >= 0 && hi < g.H && wi >= 0 && wi < g.W)
                                    ? x[(((int64_t)n * g.H + hi) * g.W + wi) * g.Ci + ci]
                                    : zero;
                 }
             }
+        };
+        auto store_tiles = [&](int buf) {
+            char* sA = smem + buf * TL::STAGE_BYTES;
+            char* sB = sA + TL::BM * TL::ROWB;
+#pragma unroll
+            for (int i = 0; i < A_PER; ++i) {
+                const int c = tid + i * kThreads, mrow = c / A_CPR, cc = (c % A_CPR) * E;
+                if (c < A_CH)
+#pragma unroll
+                    for (int e = 0; e < E; ++e) *(T*)(sA + (cc + e) * TL::ROWB + mrow * (int)sizeof(T)) = ra[i][e];
+            }
+#pragma unroll
+            for (int i = 0; i < B_PER; ++i) {
+                const int c = tid + i * kThreads, mrow = c / B_CPR, cc = (c % B_CPR) * E;
+                if (c < B_CH)
+#pragma unroll
+                    for (int e = 0; e < E; ++e) *(T*)(sB + (cc + e) * TL::ROWB + mrow * (int)sizeof(T)) = rb[i][e];
+            }
+        };
+        if (nk > 0) {
+            load_tiles(m_begin);
+            store_tiles(0);
         }
-    };
-    auto store_tiles = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < A_PER; ++i) {
-            const int c = tid + i * kThreads, mrow = c / A_CPR, cc = (c % A_CPR) * E;
-            if (c < A_CH)
-#pragma unroll
-                for (int e = 0; e < E; ++e)
-                    if (cc + e < TL::BM) *(T*)(sA[buf] + (cc + e) * TL::ROWB + mrow * (int)sizeof(T)) = ra[i][e];
-        }
-#pragma unroll
-        for (int i = 0; i < B_PER; ++i) {
-            const int c = tid + i * kThreads, mrow = c / B_CPR, cc = (c % B_CPR) * E;
-            if (c < B_CH)
-#pragma unroll
-                for (int e = 0; e < E; ++e)
-                    if (cc + e < TL::BN) *(T*)(sB[buf] + (cc + e) * TL::ROWB + mrow * (int)sizeof(T)) = rb[i][e];
-        }
-    };
-
-    const int nk = (m_end - m_begin + BKm - 1) / BKm;
-    if (nk > 0) {
-        load_tiles(m_begin);
-        store_tiles(0);
-    }
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) load_tiles(m_begin + (kt + 1) * BKm);
-        mma_tile<TL>(sA[cur], sB[cur], wave_m, wave_n, lane, acc);
-        if (kt + 1 < nk) store_tiles(cur ^ 1);
         __syncthreads();
+        for (int kt = 0; kt < nk; ++kt) {
+            const int cur = kt & 1;
+            if (kt + 1 < nk) load_tiles(m_begin + (kt + 1) * BKm);
+            mma_tile<TL>(smem + cur * TL::STAGE_BYTES, smem + cur * TL::STAGE_BYTES + TL::BM * TL::ROWB, wave_m, wave_n,
+                         lane, acc);
+            if (kt + 1 < nk) store_tiles(cur ^ 1);
+            __syncthreads();
+        }
     }
 
     float* dst = part + (int64_t)blockIdx.y * g.Co * g.Kdim;
@@ -470,31 +675,31 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
 
 // ---- host-side dispatch -------------------------------------------------------------------------
 template <typename TL>
-const char* tile_name(const char* what, bool vec, bool accum)
+const char* tile_name(const char* what, bool vec)
 {
     // one name per kernel instantiation, e.g. "conv_gather_gemm<fp32,mfma32,BM128,BN64,vec>"
-    static char names[4][96];
-    char* n = names[(vec ? 1 : 0) + (accum ? 2 : 0)];
+    static char names[2][96];
+    char* n = names[vec ? 1 : 0];
     if (!n[0])
-        snprintf(n, 96, "%s<%s,mfma%d,BM%d,BN%d,%s%s>", what, sizeof(typename TL::T) == 2 ? "bf16" : "fp32", TL::MT, TL::BM,
-                 TL::BN, vec ? "vec" : "scalar", accum ? ",acc" : "");
+        snprintf(n, 96, "%s<%s,mfma%d,BM%d,BN%d,BK%d,%s>", what, sizeof(typename TL::T) == 2 ? "bf16" : "fp32", TL::MT,
+                 TL::BM, TL::BN, TL::BK, vec ? "vec" : "scalar");
     return n;
 }
 
-template <typename TL, bool VEC, bool ACCUM>
+template <typename TL, bool VEC>
 int run_gather(const GatherGeom& g, const void* in, const void* w, void* out, hipStream_t st, double flops)
 {
     typedef typename TL::T T;
     const int64_t tiles = (int64_t)ceil_div(g.M, TL::BM) * ceil_div(g.Co, TL::BN);
     DSP_REQUIRE(tiles > 0 && tiles < (1ll << 31), DSP_EINVAL, "conv: bad tile count");
-    auto kern = conv_gather_gemm_kernel<TL, VEC, ACCUM>;
+    auto kern = conv_gather_gemm_kernel<TL, VEC>;
     static bool attr_done = false;
     if (!attr_done && TL::LDS_BYTES > 48 * 1024) {
         DSP_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES));
         attr_done = true;
     }
     {
-        ProfScope ps(tile_name<TL>("conv_gather_gemm", VEC, ACCUM), flops, 0);
+        ProfScope ps(tile_name<TL>("conv_gather_gemm", VEC), flops, 0);
         DSP_LAUNCH(ps, kern, dim3((unsigned)tiles), dim3(kThreads), TL::LDS_BYTES, st, (const T*)in, (const T*)w, (T*)out, g);
     }
     DSP_HIP(hipGetLastError());
@@ -502,78 +707,99 @@ int run_gather(const GatherGeom& g, const void* in, const void* w, void* out, hi
 }
 
 template <typename TL>
-int run_gather_v(const GatherGeom& g, bool vec, bool accum, const void* in, const void* w, void* out, hipStream_t st,
-                 double flops)
+int run_gather_v(const GatherGeom& g, bool vec, const void* in, const void* w, void* out, hipStream_t st, double flops)
 {
-    if (vec)
-        return accum ? run_gather<TL, true, true>(g, in, w, out, st, flops)
-                     : run_gather<TL, true, false>(g, in, w, out, st, flops);
-    return accum ? run_gather<TL, false, true>(g, in, w, out, st, flops)
-                 : run_gather<TL, false, false>(g, in, w, out, st, flops);
+    return vec ? run_gather<TL, true>(g, in, w, out, st, flops) : run_gather<TL, false>(g, in, w, out, st, flops);
 }
 
+// Enough workgroups to put more than one on each of the 256 compute units.
+constexpr int64_t kEnoughTiles = 384;
+
+inline int64_t tile_count(const GatherGeom& g, int bm, int bn) { return (int64_t)ceil_div(g.M, bm) * ceil_div(g.Co, bn); }
+
 template <typename T>
-int dispatch_gather(const GatherGeom& g, bool accum, const void* in, const void* w, void* out, hipStream_t st,
-                    double flops)
+int dispatch_gather(GatherGeom g, bool accum, const void* in, const void* w, void* out, hipStream_t st, double flops)
 {
     constexpr int E = 16 / (int)sizeof(T);
-    // 16-byte gathers need channel runs of E elements and 16-byte aligned bases
-    const bool vec = (g.Ci % E) == 0 && ((uintptr_t)in % 16) == 0 && ((uintptr_t)w % 16) == 0;
-    // tile by output-channel count; the small-channel tiles keep the whole channel range in one workgroup
-    if (g.Co <= 16) return run_gather_v<Tile<T, 16, 4, 1, 4, 1, 64>>(g, vec, accum, in, w, out, st, flops);
-    if (g.Co <= 32) return run_gather_v<Tile<T, 32, 4, 1, 2, 1, 64>>(g, vec, accum, in, w, out, st, flops);
-    const int64_t big_tiles = (int64_t)ceil_div(g.M, 128) * ceil_div(g.Co, 128);
-    if (g.Co % 128 == 0 && big_tiles >= 512)
-        return run_gather_v<Tile<T, 32, 2, 2, 2, 2, 64>>(g, vec, accum, in, w, out, st, flops);
-    return run_gather_v<Tile<T, 32, 2, 2, 2, 1, 64>>(g, vec, accum, in, w, out, st, flops);
+    constexpr int KB = sizeof(T) == 2 ? 128 : 64;  // bytes of k per LDS row: 64 bf16 / 16 floats
+    // 16-byte gathers need channel runs of E elements, 16-byte aligned bases and tap masks of 16 bits
+    // (tap masks hold up to 32 taps; larger filters take the generic path)
+    const bool vec = (g.Ci % E) == 0 && ((uintptr_t)in % 16) == 0 && ((uintptr_t)w % 16) == 0 && g.R * g.S <= 32;
+    g.accum = accum ? 1 : 0;
+    g.out_vec = ((g.Co % E) == 0 && ((uintptr_t)out % 16) == 0) ? 1 : 0;
+    // largest tile of the channel class that still yields enough workgroups, else the smallest
+    if (g.Co <= 16) {
+        if (tile_count(g, 256, 16) >= kEnoughTiles)
+            return run_gather_v<Tile<T, 16, 4, 1, 4, 1, 64, 2>>(g, vec, in, w, out, st, flops);
+        return run_gather_v<Tile<T, 16, 4, 1, 1, 1, 64, 2>>(g, vec, in, w, out, st, flops);
+    }
+    if (g.Co <= 32) {
+        if (tile_count(g, 256, 32) >= kEnoughTiles)
+            return run_gather_v<Tile<T, 32, 4, 1, 2, 1, 64, 2>>(g, vec, in, w, out, st, flops);
+        return run_gather_v<Tile<T, 32, 4, 1, 1, 1, 64, 2>>(g, vec, in, w, out, st, flops);
+    }
+    if (g.Co % 128 == 0 && tile_count(g, 128, 128) >= kEnoughTiles)
+        return run_gather_v<Tile<T, 32, 2, 2, 2, 2, KB, 2>>(g, vec, in, w, out, st, flops);
+    if (tile_count(g, 128, 64) >= kEnoughTiles)
+        return run_gather_v<Tile<T, 32, 2, 2, 2, 1, KB, 2>>(g, vec, in, w, out, st, flops);
+    return run_gather_v<Tile<T, 32, 2, 2, 1, 1, KB, 2>>(g, vec, in, w, out, st, flops);
 }
 
 template <typename TL, bool VEC>
-int run_wgrad(const WgradGeom& g0, int splits, const void* x, const void* dy, float* dst, hipStream_t st, double flops)
+int run_wgrad(const WgradGeom& g, int splits, const void* x, const void* dy, float* dst, hipStream_t st, double flops)
 {
     typedef typename TL::T T;
-    WgradGeom g = g0;
     const int tiles = ceil_div(g.Co, TL::BM) * ceil_div(g.Kdim, TL::BN);
     auto kern = conv_wgrad_kernel<TL, VEC>;
     static bool attr_done = false;
-    if (!attr_done && TL::LDS_BYTES > 48 * 1024) {
-        DSP_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES));
+    if (!attr_done && TL::LOAD_BYTES > 48 * 1024) {
+        DSP_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LOAD_BYTES));
         attr_done = true;
     }
     {
-        ProfScope ps(tile_name<TL>("conv_wgrad", VEC, false), flops, 0);
-        DSP_LAUNCH(ps, kern, dim3(tiles, splits), dim3(kThreads), TL::LDS_BYTES, st, (const T*)x, (const T*)dy, dst, g);
+        ProfScope ps(tile_name<TL>("conv_wgrad", VEC), flops, 0);
+        DSP_LAUNCH(ps, kern, dim3(tiles, splits), dim3(kThreads), TL::LOAD_BYTES, st, (const T*)x, (const T*)dy, dst, g);
     }
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }
 
-// Slices of the (n, ho, wo) range: enough workgroups to cover the chip a few times, each slice a
-// whole number of LDS tiles and at least 4 of them.
-int wgrad_splits(const ConvShape& c, int bm, int bn, int bk, int* m_per_split)
+template <typename TL>
+int run_wgrad_v(const WgradGeom& g, int splits, bool vec, const void* x, const void* dy, float* dst, hipStream_t st,
+                double flops)
+{
+    return vec ? run_wgrad<TL, true>(g, splits, x, dy, dst, st, flops) : run_wgrad<TL, false>(g, splits, x, dy, dst, st, flops);
+}
+
+// Tile of the backward-weight GEMM (output Cout x R*S*Cin) and the m extent of one LDS tile.
+struct WgradPlan {
+    int bm, bn, bk, id;
+};
+WgradPlan wgrad_plan(int dtype, const ConvShape& c)
+{
+    const int bk = dtype == DSP_BF16 ? 64 : 16;
+    const int64_t kdim = (int64_t)c.R * c.S * c.Cin;
+    if (c.Cout <= 16) return {16, 64, bk, 0};
+    if (c.Cout <= 32) return {32, 128, bk, 1};
+    if (c.Cout >= 128 && kdim >= 512) return {128, 128, bk, 3};
+    return {64, 64, bk, 2};
+}
+
+// Slices of the (n, ho, wo) range: about two workgroups per compute unit, each slice a whole number
+// of LDS tiles and at least 8 of them.
+int wgrad_splits(const ConvShape& c, const WgradPlan& pl, int* m_per_split)
 {
     const int64_t M = (int64_t)c.N * c.Ho * c.Wo, Kdim = (int64_t)c.R * c.S * c.Cin;
-    const int tiles = ceil_div(c.Cout, bm) * ceil_div(Kdim, bn);
-    int want = ceil_div(512, tiles);  // about two workgroups per compute unit
-    const int max_by_len = (int)((M + 8 * bk - 1) / (8 * bk));
+    const int tiles = ceil_div(c.Cout, pl.bm) * ceil_div(Kdim, pl.bn);
+    int want = ceil_div(512, tiles);
+    const int max_by_len = (int)((M + 8 * pl.bk - 1) / (8 * pl.bk));
     if (want > max_by_len) want = max_by_len;
     if (want < 1) want = 1;
     if (want > 256) want = 256;
     int per = (int)((M + want - 1) / want);
-    per = ceil_div(per, bk) * bk;
+    per = ceil_div(per, pl.bk) * pl.bk;
     *m_per_split = per;
     return ceil_div(M, per);
-}
-
-struct WgradPlan {
-    int bm, bn, bk;
-};
-WgradPlan wgrad_plan(int dtype, const ConvShape& c)
-{
-    const int bk = dtype == DSP_BF16 ? 32 : 16;
-    if (c.Cout <= 16) return {16, 64, bk};
-    if (c.Cout <= 32) return {32, 128, bk};
-    return {64, 64, bk};
 }
 
 template <typename T>
@@ -581,12 +807,13 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
                    hipStream_t st, double flops)
 {
     constexpr int E = 16 / (int)sizeof(T);
+    constexpr int KB = sizeof(T) == 2 ? 128 : 64;
     const int dtype = sizeof(T) == 2 ? DSP_BF16 : DSP_FP32;
     const WgradPlan pl = wgrad_plan(dtype, c);
     WgradGeom g{c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.stride, 0, 0, 0};
     g.M = c.N * c.Ho * c.Wo;
     g.Kdim = c.R * c.S * c.Cin;
-    const int splits = wgrad_splits(c, pl.bm, pl.bn, pl.bk, &g.m_per_split);
+    const int splits = wgrad_splits(c, pl, &g.m_per_split);
     const size_t n = (size_t)c.Cout * g.Kdim;
     float* dst = dw;
     if (splits > 1) {
@@ -596,15 +823,12 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
     }
     const bool vec = (c.Cin % E) == 0 && (c.Cout % E) == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)dy % 16) == 0;
     int rc;
-    if (c.Cout <= 16)
-        rc = vec ? run_wgrad<Tile<T, 16, 1, 4, 1, 1, 64>, true>(g, splits, x, dy, dst, st, flops)
-                 : run_wgrad<Tile<T, 16, 1, 4, 1, 1, 64>, false>(g, splits, x, dy, dst, st, flops);
-    else if (c.Cout <= 32)
-        rc = vec ? run_wgrad<Tile<T, 32, 1, 4, 1, 1, 64>, true>(g, splits, x, dy, dst, st, flops)
-                 : run_wgrad<Tile<T, 32, 1, 4, 1, 1, 64>, false>(g, splits, x, dy, dst, st, flops);
-    else
-        rc = vec ? run_wgrad<Tile<T, 32, 2, 2, 1, 1, 64>, true>(g, splits, x, dy, dst, st, flops)
-                 : run_wgrad<Tile<T, 32, 2, 2, 1, 1, 64>, false>(g, splits, x, dy, dst, st, flops);
+    switch (pl.id) {
+    case 0: rc = run_wgrad_v<Tile<T, 16, 1, 4, 1, 1, KB, 2>>(g, splits, vec, x, dy, dst, st, flops); break;
+    case 1: rc = run_wgrad_v<Tile<T, 32, 1, 4, 1, 1, KB, 2>>(g, splits, vec, x, dy, dst, st, flops); break;
+    case 3: rc = run_wgrad_v<Tile<T, 32, 2, 2, 2, 2, KB, 2>>(g, splits, vec, x, dy, dst, st, flops); break;
+    default: rc = run_wgrad_v<Tile<T, 32, 2, 2, 1, 1, KB, 2>>(g, splits, vec, x, dy, dst, st, flops); break;
+    }
     DSP_TRY(rc);
     if (splits > 1) {
         ProfScope ps("wgrad_reduce", (double)n * (splits + 1) * 4.0, 1);
@@ -637,9 +861,10 @@ int check_shape(const ConvShape& c)
     DSP_REQUIRE(c.N > 0 && c.H > 0 && c.W > 0 && c.Cin > 0 && c.Cout > 0 && c.R > 0 && c.S > 0 && c.stride > 0 &&
                     c.pad >= 0 && c.Ho > 0 && c.Wo > 0,
                 DSP_EINVAL, "conv: bad shape");
-    DSP_REQUIRE((int64_t)c.N * c.H * c.W * c.Cin < (1ll << 31) && (int64_t)c.N * c.Ho * c.Wo * c.Cout < (1ll << 31) &&
-                    (int64_t)c.N * c.Ho * c.Wo < (1ll << 31) && (int64_t)c.R * c.S * c.Cin * c.Cout < (1ll << 31),
-                DSP_EINVAL, "conv: tensor too large for 32-bit row indices");
+    DSP_REQUIRE(c.H < 32000 && c.W < 32000, DSP_EINVAL, "conv: image side too large");
+    DSP_REQUIRE((int64_t)c.N * c.H * c.W * c.Cin < (1ll << 30) && (int64_t)c.N * c.Ho * c.Wo * c.Cout < (1ll << 30) &&
+                    (int64_t)c.R * c.S * c.Cin * c.Cout < (1ll << 30),
+                DSP_EINVAL, "conv: tensor too large for 32-bit byte offsets (2^30 elements per tensor at most)");
     return DSP_OK;
 }
 
@@ -648,7 +873,7 @@ int check_shape(const ConvShape& c)
 int launch_conv_forward(int dtype, const ConvShape& c, const void* x, const void* w, void* y, hipStream_t st)
 {
     DSP_TRY(check_shape(c));
-    GatherGeom g{c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.pad, c.stride, 1, 0, 0};
+    GatherGeom g{c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.pad, c.stride, 1, 0, 0, 0, 0};
     g.M = c.N * c.Ho * c.Wo;
     g.Kdim = c.R * c.S * c.Cin;
     const double flops = 2.0 * conv_macs(c);
@@ -662,7 +887,8 @@ int launch_conv_backward_data(int dtype, const ConvShape& c, const void* dy, con
     DSP_TRY(check_shape(c));
     DSP_REQUIRE(c.stride == 1 || c.stride == 2, DSP_EINVAL, "conv backward-data: stride %d unsupported", c.stride);
     // dx[n,hi,wi,ci] = sum_{r',s',co} dy[n, (hi - (R-1-pad) + r')/stride, ...][co] * wt[ci][r'][s'][co]
-    GatherGeom g{c.N, c.Ho, c.Wo, c.Cout, c.H, c.W, c.Cin, c.R, c.S, c.R - 1 - c.pad, c.S - 1 - c.pad, 1, c.stride, 0, 0};
+    GatherGeom g{c.N, c.Ho, c.Wo, c.Cout, c.H, c.W, c.Cin, c.R, c.S, c.R - 1 - c.pad, c.S - 1 - c.pad, 1, c.stride,
+                 0, 0, 0, 0};
     g.M = c.N * c.H * c.W;
     g.Kdim = c.R * c.S * c.Cout;
     const double flops = 2.0 * conv_macs(c);
@@ -676,7 +902,7 @@ size_t conv_backward_weight_workspace(const ConvShape& c)
     for (int dtype = 0; dtype < 2; ++dtype) {
         const WgradPlan pl = wgrad_plan(dtype, c);
         int per;
-        const int splits = wgrad_splits(c, pl.bm, pl.bn, pl.bk, &per);
+        const int splits = wgrad_splits(c, pl, &per);
         const size_t b = splits > 1 ? (size_t)splits * c.Cout * c.R * c.S * c.Cin * sizeof(float) : 0;
         if (b > worst) worst = b;
     }
