@@ -201,6 +201,15 @@ int dsp_pipeline_destroy(dsp_pipeline* pl);
 int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_labels, float* h_loss,
                       int64_t* loss_batch_id, void* stream);
 
+/*
+ * How the launches of a tick reach the GPU (results are bit-identical in every mode):
+ *  - launch threads (default on): the chain of block k >= 1 is issued by a host thread of its own while
+ *    the caller's thread issues block 0; the call returns when every chain has been enqueued.
+ *  - graph replay (default off): steady-state ticks are recorded once per ring position into HIP graphs
+ *    and replayed with one launch each.
+ */
+int dsp_pipeline_set_launch_threads(dsp_pipeline* pl, int32_t enable);
+int dsp_pipeline_set_graph_replay(dsp_pipeline* pl, int32_t enable);
 /* Straggler emulation: block k's stream spins for `microseconds` before its work in every tick. */
 int dsp_pipeline_set_delay(dsp_pipeline* pl, int32_t k, int32_t microseconds);
 /* Waits for all K streams. */

@@ -19,6 +19,7 @@ __all__ = [
     "dsp_block_input_shape", "dsp_block_memory", "dsp_block_get_params", "dsp_block_set_params",
     "dsp_block_get_momentum", "dsp_block_set_momentum", "dsp_block_get_grads",
     "dsp_pipeline_init", "dsp_pipeline_destroy", "dsp_pipeline_step", "dsp_pipeline_set_delay",
+    "dsp_pipeline_set_graph_replay", "dsp_pipeline_set_launch_threads",
     "dsp_pipeline_sync", "dsp_pipeline_losses", "dsp_pipeline_ticks",
     "dsp_conv_forward", "dsp_conv_backward_data", "dsp_conv_backward_weight", "dsp_conv_workspace_bytes",
     "dsp_profile_start", "dsp_profile_stop", "dsp_profile_get",
@@ -97,6 +98,8 @@ _SIGNATURES = {
     "dsp_pipeline_destroy": [_vp],
     "dsp_pipeline_step": [_vp, _vp, _vp, _pf, _pi64, _vp],
     "dsp_pipeline_set_delay": [_vp, _i32, _i32],
+    "dsp_pipeline_set_graph_replay": [_vp, _i32],
+    "dsp_pipeline_set_launch_threads": [_vp, _i32],
     "dsp_pipeline_sync": [_vp],
     "dsp_pipeline_losses": [_vp, _pf, _i64, _pi64],
     "dsp_pipeline_ticks": [_vp, _pi64],
@@ -302,6 +305,14 @@ def dsp_pipeline_step(pl, d_batch, d_labels, want_loss=False, stream=None):
 
 def dsp_pipeline_set_delay(pl, k, microseconds):
     check(lib().dsp_pipeline_set_delay(pl, k, microseconds), "dsp_pipeline_set_delay")
+
+
+def dsp_pipeline_set_graph_replay(pl, enable):
+    check(lib().dsp_pipeline_set_graph_replay(pl, int(bool(enable))), "dsp_pipeline_set_graph_replay")
+
+
+def dsp_pipeline_set_launch_threads(pl, enable):
+    check(lib().dsp_pipeline_set_launch_threads(pl, int(bool(enable))), "dsp_pipeline_set_launch_threads")
 
 
 def dsp_pipeline_sync(pl):

@@ -127,6 +127,7 @@ struct dsp_block {
 
     int64_t version = 0, next_fwd = 0, next_bwd = 0;
     bool pending = false;
+    bool dry = false;  // advance the host-side state only: the launches of this tick are replayed from a HIP graph
 };
 
 namespace dsp {
@@ -446,6 +447,8 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
     return DSP_OK;
 }
 
+void block_set_dry(dsp_block* b, bool dry) { b->dry = dry; }
+
 }  // namespace dsp
 
 // ================================================================================================
@@ -512,9 +515,11 @@ int dsp_block_forward(dsp_block* b, int64_t batch_id, const void* d_in, void* d_
     DSP_REQUIRE(b->loss_idx < 0 || d_labels, DSP_EINVAL, "dsp_block_forward: the last block needs labels");
     const int slot = (int)(batch_id % b->ring_entries);
     void* slot_ptr = b->ring + (size_t)slot * b->slot_bytes;
+    b->slot_version[slot] = b->version;
+    b->next_fwd = batch_id + 1;
+    if (b->dry) return DSP_OK;
     if (d_in != slot_ptr)
         DSP_HIP(hipMemcpyAsync(slot_ptr, d_in, b->input.elems * dtype_size(b->dtype), hipMemcpyDeviceToDevice, st));
-    b->slot_version[slot] = b->version;
     float* dz = b->loss_idx >= 0 ? b->dz_ring + (size_t)(batch_id % (1 + m)) * b->dz_elems : nullptr;
     float* loss = d_loss ? d_loss : b->loss_sink;
     const Tensor& o = b->T[b->out_idx];
@@ -525,7 +530,6 @@ int dsp_block_forward(dsp_block* b, int64_t batch_id, const void* d_in, void* d_
     } else {
         DSP_TRY(run_forward(b, slot_ptr, d_out, d_labels, loss, dz, st));
     }
-    b->next_fwd = batch_id + 1;
     return DSP_OK;
 }
 
@@ -543,10 +547,11 @@ int dsp_block_recompute_backward(dsp_block* b, int64_t batch_id, const void* d_g
     void* slot_ptr = b->ring + (size_t)slot * b->slot_bytes;
     const void* gout = d_grad_out;
     if (b->loss_idx >= 0 && !d_grad_out) gout = b->dz_ring + (size_t)(batch_id % (1 + m)) * b->dz_elems;
-    if (m > 0) DSP_TRY(run_forward(b, slot_ptr, nullptr, nullptr, b->loss_sink, nullptr, st));
-    DSP_TRY(run_backward(b, slot_ptr, gout, d_grad_in, st));
     b->next_bwd = batch_id + 1;
     b->pending = true;
+    if (b->dry) return DSP_OK;
+    if (m > 0) DSP_TRY(run_forward(b, slot_ptr, nullptr, nullptr, b->loss_sink, nullptr, st));
+    DSP_TRY(run_backward(b, slot_ptr, gout, d_grad_in, st));
     return DSP_OK;
 }
 
@@ -554,10 +559,11 @@ int dsp_param_update(dsp_block* b, float lr, float momentum, float weight_decay,
 {
     DSP_REQUIRE(b, DSP_EINVAL, "dsp_param_update: null block");
     DSP_REQUIRE(b->pending, DSP_ESTATE, "dsp_param_update: no pending gradient");
-    DSP_TRY(launch_sgd_update(b->dtype, b->x, b->v, b->g, b->decay, b->tmap, b->wf16, b->wt, b->nP, lr, momentum,
-                              weight_decay, (hipStream_t)stream));
     b->pending = false;
     b->version += 1;
+    if (b->dry) return DSP_OK;
+    DSP_TRY(launch_sgd_update(b->dtype, b->x, b->v, b->g, b->decay, b->tmap, b->wf16, b->wt, b->nP, lr, momentum,
+                              weight_decay, (hipStream_t)stream));
     return DSP_OK;
 }
 

@@ -9,7 +9,13 @@
 
 #include "../../include/dsp.h"
 
+struct dsp_block;
+
 namespace dsp {
+
+// While a block is "dry" its step calls check and advance the host-side state (batch ids, update
+// counter) but launch nothing: the pipeline replays the launches of that tick from a HIP graph.
+void block_set_dry(dsp_block* b, bool dry);
 
 // ---- error plumbing ---------------------------------------------------------------------------
 void set_error(const char* fmt, ...);
@@ -152,6 +158,8 @@ int launch_sgd_update(int dtype, float* x, float* v, const float* g, const uint8
 int launch_refresh_shadows(int dtype, const float* x, const int32_t* tmap, void* wf16, void* wt, size_t n,
                            hipStream_t st);
 int launch_spin(int microseconds, hipStream_t st);
+// history[counter[0]] = *loss; counter[0] += 1   (one thread; keeps the loss history index on the device)
+int launch_record_loss(const float* loss, float* history, int32_t* counter, int64_t capacity, hipStream_t st);
 
 // ---- in-situ kernel timing (block.hip) ----------------------------------------------------------
 // While a profile is running (dsp_profile_start .. dsp_profile_stop) every instrumented launch goes

@@ -196,6 +196,14 @@ __global__ void sgd_update_kernel(float* __restrict__ x, float* __restrict__ v, 
     }
 }
 
+__global__ void record_loss_kernel(const float* __restrict__ loss, float* __restrict__ history, int32_t* counter,
+                                   long long capacity)
+{
+    const int32_t i = counter[0];
+    if (i >= 0 && i < capacity) history[i] = loss[0];
+    counter[0] = i + 1;
+}
+
 __global__ void spin_kernel(long long cycles)
 {
     const long long t0 = wall_clock64();
@@ -319,6 +327,13 @@ int launch_refresh_shadows(int dtype, const float* x, const int32_t* tmap, void*
         hipLaunchKernelGGL((sgd_update_kernel<float, false>), grid, dim3(kThreads), 0, st, (float*)x, (float*)nullptr,
                            (const float*)nullptr, (const uint8_t*)nullptr, tmap, (bf16_t*)nullptr, (float*)wt, n, 0.f,
                            0.f, 0.f);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+int launch_record_loss(const float* loss, float* history, int32_t* counter, int64_t capacity, hipStream_t st)
+{
+    hipLaunchKernelGGL(record_loss_kernel, dim3(1), dim3(1), 0, st, loss, history, counter, (long long)capacity);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }

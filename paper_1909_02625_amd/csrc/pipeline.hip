@@ -7,7 +7,18 @@
 // Which mini-batch a block touches depends only on the tick number, so results do not depend
 // on timing; streams only have to respect "a slot is written one tick or more before it is
 // read, and read before it is rewritten", which waiting for both neighbours' previous tick gives.
+//
+// Steady-state ticks are launch-bound on small layers (hundreds of kernels of a few microseconds),
+// so once the pipeline is full each tick is captured into a HIP graph -- one per phase of the ring
+// rotation, lcm(ring sizes) of them -- with the K block chains as parallel branches, and later
+// ticks of the same phase replay that graph with a single launch while the blocks' host-side
+// state is advanced without launching.
+#include <condition_variable>
+#include <mutex>
 #include <new>
+#include <numeric>
+#include <string>
+#include <thread>
 #include <vector>
 
 #include "common.h"
@@ -40,6 +51,20 @@ int validate_schedule(int K, const int32_t* p, const int32_t* m, int32_t* q)
     return DSP_OK;
 }
 
+constexpr int kMaxGraphs = 128;
+
+// One host thread per block stream: a tick is a few hundred kernel launches of a few microseconds of
+// host time each, so issuing the K chains from K threads keeps the launch rate off the critical path.
+struct Worker {
+    std::thread th;
+    std::mutex mu;
+    std::condition_variable cv;
+    bool has_job = false, finished = false, quit = false;
+    int64_t tau = 0;
+    int rc = DSP_OK;
+    std::string err;
+};
+
 }  // namespace
 
 struct dsp_pipeline {
@@ -50,16 +75,76 @@ struct dsp_pipeline {
     float lr = 0, momentum = 0, wd = 0;
     std::vector<hipStream_t> streams;
     std::vector<hipEvent_t> done[2];  // done[tau % 2][k]: block k finished tick tau
-    hipEvent_t in_ready = nullptr, in_copied = nullptr;
+    std::vector<hipEvent_t> join;     // graph capture: branch k joins stream 0
+    hipEvent_t in_ready = nullptr, in_copied = nullptr, fork = nullptr;
     std::vector<char*> qring;         // Q_k, k >= 1
     std::vector<size_t> qslot_bytes;
     int32_t* labels = nullptr;
     int label_slots = 1, N = 0;
-    float* losses = nullptr;
+    size_t in_bytes = 0;
+    float* losses = nullptr;     // loss of mini-batch i at losses[i]
+    float* loss_tmp = nullptr;   // loss of the tick in flight
+    int32_t* loss_count = nullptr;
     int64_t max_ticks = 0, tau = 0;
     std::vector<int32_t> delay_us;
     std::vector<void*> allocs;
+    // launch threads for blocks 1..K-1 (block 0 is issued by the caller's thread)
+    std::vector<Worker*> workers;
+    int device = 0;
+    bool use_threads = true;
+    // graph replay (off by default: on this runtime replaying a few hundred nodes costs more host time
+    // than issuing them from K threads)
+    bool use_graphs = false;
+    int period = 0;      // ticks after which every ring is back in the same position (0: too long, no graphs)
+    int64_t fill = 0;    // first tick at which every block runs forward, backward and update
+    std::vector<hipGraphExec_t> graphs;
 };
+
+static int run_block_tick(dsp_pipeline* pl, int k, int64_t tau);
+
+static void worker_main(dsp_pipeline* pl, int k)
+{
+    Worker* w = pl->workers[k];
+    (void)hipSetDevice(pl->device);
+    std::unique_lock<std::mutex> lk(w->mu);
+    for (;;) {
+        w->cv.wait(lk, [&] { return w->has_job || w->quit; });
+        if (w->quit) return;
+        w->has_job = false;
+        const int64_t tau = w->tau;
+        lk.unlock();
+        const int rc = run_block_tick(pl, k, tau);
+        lk.lock();
+        w->rc = rc;
+        w->err = rc == DSP_OK ? "" : dsp_last_error();
+        w->finished = true;
+        w->cv.notify_all();
+    }
+}
+
+static void stop_workers(dsp_pipeline* pl)
+{
+    for (Worker* w : pl->workers) {
+        if (!w) continue;
+        {
+            std::lock_guard<std::mutex> g(w->mu);
+            w->quit = true;
+        }
+        w->cv.notify_all();
+        if (w->th.joinable()) w->th.join();
+        delete w;
+    }
+    pl->workers.clear();
+}
+
+static void drop_graphs(dsp_pipeline* pl)
+{
+    for (hipGraphExec_t& g : pl->graphs)
+        if (g) {
+            (void)hipGraphExecDestroy(g);
+            g = nullptr;
+        }
+}
 
 extern "C" {
 
@@ -105,14 +190,26 @@ int dsp_schedule_queue_elems(int32_t K, const int32_t* p, const int32_t* m, cons
 int dsp_pipeline_destroy(dsp_pipeline* pl)
 {
     if (!pl) return DSP_OK;
+    stop_workers(pl);
     (void)hipDeviceSynchronize();
+    drop_graphs(pl);
     for (hipStream_t s : pl->streams) (void)hipStreamDestroy(s);
     for (int i = 0; i < 2; ++i)
         for (hipEvent_t e : pl->done[i]) (void)hipEventDestroy(e);
+    for (hipEvent_t e : pl->join) (void)hipEventDestroy(e);
     if (pl->in_ready) (void)hipEventDestroy(pl->in_ready);
     if (pl->in_copied) (void)hipEventDestroy(pl->in_copied);
+    if (pl->fork) (void)hipEventDestroy(pl->fork);
     for (void* a : pl->allocs) (void)hipFree(a);
     delete pl;
+    return DSP_OK;
+}
+
+static int pl_alloc(dsp_pipeline* pl, void** p, size_t bytes)
+{
+    hipError_t e = hipMalloc(p, bytes ? bytes : 16);
+    DSP_REQUIRE(e == hipSuccess, DSP_ENOMEM, "dsp_pipeline_init: hipMalloc(%zu) failed: %s", bytes, hipGetErrorString(e));
+    pl->allocs.push_back(*p);
     return DSP_OK;
 }
 
@@ -122,11 +219,16 @@ static int pipeline_build(dsp_pipeline* pl, dsp_block* const* blocks)
     int64_t info[8];
     int32_t shape[5], prev_out[5] = {0, 0, 0, 0, 0};
     int dtype0 = 0;
+    int64_t period = 1;
     for (int k = 0; k < K; ++k) {
         DSP_REQUIRE(blocks[k], DSP_EINVAL, "dsp_pipeline_init: null block %d", k);
         dsp_block* b = blocks[k];
         DSP_TRY(dsp_block_input_shape(b, shape));
-        if (k == 0) dtype0 = shape[4];
+        if (k == 0) {
+            dtype0 = shape[4];
+            pl->N = shape[0];
+            pl->in_bytes = (size_t)shape[0] * shape[1] * shape[2] * shape[3] * dtype_size(dtype0);
+        }
         DSP_REQUIRE(shape[4] == dtype0, DSP_EINVAL, "dsp_pipeline_init: block %d has another dtype", k);
         if (k > 0)
             DSP_REQUIRE(prev_out[4] == 0 && shape[0] == prev_out[0] && shape[1] == prev_out[1] && shape[2] == prev_out[2] &&
@@ -139,6 +241,12 @@ static int pipeline_build(dsp_pipeline* pl, dsp_block* const* blocks)
                     k, (long long)info[3], want);
         DSP_REQUIRE(info[1] == 0 && info[2] == 0, DSP_ESTATE, "dsp_pipeline_init: block %d has already been stepped", k);
         pl->blocks.push_back(b);
+        period = std::lcm(period, (int64_t)want);
+        period = std::lcm(period, (int64_t)(1 + pl->m[k]));  // the last block's loss-gradient ring
+        if (k > 0) period = std::lcm(period, (int64_t)(1 + pl->q[k]));
+        if (period > kMaxGraphs) period = kMaxGraphs + 1;
+        const int64_t full = pl->P[k] + pl->m[k];
+        if (full > pl->fill) pl->fill = full;
     }
     for (int k = 0; k < K; ++k) {
         hipStream_t s;
@@ -149,9 +257,13 @@ static int pipeline_build(dsp_pipeline* pl, dsp_block* const* blocks)
             DSP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
             pl->done[i].push_back(e);
         }
+        hipEvent_t e;
+        DSP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        pl->join.push_back(e);
     }
     DSP_HIP(hipEventCreateWithFlags(&pl->in_ready, hipEventDisableTiming));
     DSP_HIP(hipEventCreateWithFlags(&pl->in_copied, hipEventDisableTiming));
+    DSP_HIP(hipEventCreateWithFlags(&pl->fork, hipEventDisableTiming));
     // Q_k holds G_{h_k}: same bytes as block k's input slot.
     pl->qring.assign(K, nullptr);
     pl->qslot_bytes.assign(K, 0);
@@ -160,26 +272,33 @@ static int pipeline_build(dsp_pipeline* pl, dsp_block* const* blocks)
         size_t bytes = (size_t)shape[0] * shape[1] * shape[2] * shape[3] * 4;  // upper bound (fp32)
         bytes = (bytes + 255) / 256 * 256;
         void* ptr;
-        hipError_t e = hipMalloc(&ptr, bytes * (1 + pl->q[k]));
-        DSP_REQUIRE(e == hipSuccess, DSP_ENOMEM, "dsp_pipeline_init: hipMalloc failed: %s", hipGetErrorString(e));
-        pl->allocs.push_back(ptr);
+        DSP_TRY(pl_alloc(pl, &ptr, bytes * (1 + pl->q[k])));
         pl->qring[k] = (char*)ptr;
         pl->qslot_bytes[k] = bytes;
     }
-    DSP_TRY(dsp_block_output_shape(pl->blocks[0], shape));
-    pl->N = shape[0];
     pl->label_slots = pl->P[K - 1] + K;
+    period = std::lcm(period, (int64_t)pl->label_slots);
+    pl->period = (pl->serial || period > kMaxGraphs) ? 0 : (int)period;
+    pl->graphs.assign(pl->period, nullptr);
     void* ptr;
-    hipError_t e = hipMalloc(&ptr, (size_t)pl->label_slots * pl->N * 4);
-    DSP_REQUIRE(e == hipSuccess, DSP_ENOMEM, "dsp_pipeline_init: hipMalloc failed: %s", hipGetErrorString(e));
-    pl->allocs.push_back(ptr);
+    DSP_TRY(pl_alloc(pl, &ptr, (size_t)pl->label_slots * pl->N * 4));
     pl->labels = (int32_t*)ptr;
-    e = hipMalloc(&ptr, (size_t)(pl->max_ticks + 1) * 4);
-    DSP_REQUIRE(e == hipSuccess, DSP_ENOMEM, "dsp_pipeline_init: hipMalloc failed: %s", hipGetErrorString(e));
-    pl->allocs.push_back(ptr);
+    DSP_TRY(pl_alloc(pl, &ptr, (size_t)(pl->max_ticks + 1) * 4));
     pl->losses = (float*)ptr;
+    DSP_TRY(pl_alloc(pl, &ptr, 16));
+    pl->loss_tmp = (float*)ptr;
+    pl->loss_count = (int32_t*)ptr + 2;
     DSP_HIP(hipMemset(pl->losses, 0, (size_t)(pl->max_ticks + 1) * 4));
+    DSP_HIP(hipMemset(pl->loss_tmp, 0, 16));
     DSP_HIP(hipDeviceSynchronize());
+    DSP_HIP(hipGetDevice(&pl->device));
+    pl->workers.assign(K, nullptr);
+    if (!pl->serial)
+        for (int k = 1; k < K; ++k) {
+            pl->workers[k] = new (std::nothrow) Worker();
+            DSP_REQUIRE(pl->workers[k], DSP_ENOMEM, "dsp_pipeline_init: out of host memory");
+            pl->workers[k]->th = std::thread(worker_main, pl, k);
+        }
     return DSP_OK;
 }
 
@@ -219,7 +338,125 @@ int dsp_pipeline_set_delay(dsp_pipeline* pl, int32_t k, int32_t microseconds)
 {
     DSP_REQUIRE(pl && k >= 0 && k < pl->K && microseconds >= 0 && microseconds <= 1000000, DSP_EINVAL,
                 "dsp_pipeline_set_delay: bad argument");
+    if (pl->delay_us[k] != microseconds) {
+        DSP_HIP(hipDeviceSynchronize());
+        drop_graphs(pl);  // the delay kernel is part of the captured ticks
+    }
     pl->delay_us[k] = microseconds;
+    return DSP_OK;
+}
+
+int dsp_pipeline_set_graph_replay(dsp_pipeline* pl, int32_t enable)
+{
+    DSP_REQUIRE(pl, DSP_EINVAL, "dsp_pipeline_set_graph_replay: null pipeline");
+    pl->use_graphs = enable != 0;
+    return DSP_OK;
+}
+
+int dsp_pipeline_set_launch_threads(dsp_pipeline* pl, int32_t enable)
+{
+    DSP_REQUIRE(pl, DSP_EINVAL, "dsp_pipeline_set_launch_threads: null pipeline");
+    pl->use_threads = enable != 0;
+    return DSP_OK;
+}
+
+// Forward / backward / update of block k at tick tau on stream st (what a tick consists of).
+static int block_tick(dsp_pipeline* pl, int k, int64_t tau, hipStream_t st, bool do_fwd, bool do_bwd, bool dry = false)
+{
+    const int K = pl->K;
+    const int64_t a = tau - pl->P[k];
+    if (a < 0) return DSP_OK;
+    dsp_block* b = pl->blocks[k];
+    const int64_t bb = a - pl->m[k];
+    if (do_fwd) {
+        void* in;
+        DSP_TRY(dsp_block_input_slot(b, a, &in));  // block 0: filled by the data source copy of this tick
+        void* out = nullptr;
+        if (k < K - 1) DSP_TRY(dsp_block_input_slot(pl->blocks[k + 1], a, &out));
+        const int32_t* lab = pl->labels + (size_t)(a % pl->label_slots) * pl->N;
+        const bool last = k == K - 1;
+        DSP_TRY(dsp_block_forward(b, a, in, out, last ? lab : nullptr, last ? pl->loss_tmp : nullptr, st));
+        if (last && !dry) DSP_TRY(launch_record_loss(pl->loss_tmp, pl->losses, pl->loss_count, pl->max_ticks + 1, st));
+    }
+    if (do_bwd && bb >= 0) {
+        const void* gout = k < K - 1 ? pl->qring[k + 1] + (size_t)(bb % (1 + pl->q[k + 1])) * pl->qslot_bytes[k + 1] : nullptr;
+        void* gin = k > 0 ? pl->qring[k] + (size_t)(bb % (1 + pl->q[k])) * pl->qslot_bytes[k] : nullptr;
+        DSP_TRY(dsp_block_recompute_backward(b, bb, gout, gin, st));
+        DSP_TRY(dsp_param_update(b, pl->lr, pl->momentum, pl->wd, st));
+    }
+    return DSP_OK;
+}
+
+// The chain of block k at tick tau, issued kernel by kernel on the block's own stream.
+static int run_block_tick(dsp_pipeline* pl, int k, int64_t tau)
+{
+    const int K = pl->K;
+    const int cur = (int)(tau & 1), prev = cur ^ 1;
+    hipStream_t st = pl->streams[k];
+    // Neighbours' previous tick: the slots this block reads were written then or earlier, and
+    // the slots it writes were last read then or earlier.  (The labels of the mini-batch the
+    // last block sees now were copied on stream 0 P_{K-1} >= K-1 ticks ago, which this chain
+    // of waits orders; the label ring has P_{K-1}+K slots so a slot is not refilled too early.)
+    if (tau > 0) {
+        if (k > 0) DSP_HIP(hipStreamWaitEvent(st, pl->done[prev][k - 1], 0));
+        if (k < K - 1) DSP_HIP(hipStreamWaitEvent(st, pl->done[prev][k + 1], 0));
+    }
+    if (pl->delay_us[k] > 0) DSP_TRY(launch_spin(pl->delay_us[k], st));
+    DSP_TRY(block_tick(pl, k, tau, st, true, true));
+    DSP_HIP(hipEventRecord(pl->done[cur][k], st));
+    return DSP_OK;
+}
+
+// All K block chains of tick tau: kernel by kernel (one stream and, unless a profile is being taken,
+// one host thread per block), or recorded into a graph capture.
+static int issue_tick(dsp_pipeline* pl, int64_t tau, bool capturing)
+{
+    const int K = pl->K;
+    hipStream_t s0 = pl->streams[0];
+    if (!capturing) {
+        const bool threads = pl->use_threads && K > 1 && !g_profile_on;
+        if (threads)
+            for (int k = 1; k < K; ++k) {
+                Worker* w = pl->workers[k];
+                {
+                    std::lock_guard<std::mutex> g(w->mu);
+                    w->tau = tau;
+                    w->finished = false;
+                    w->has_job = true;
+                }
+                w->cv.notify_all();
+            }
+        int rc = run_block_tick(pl, 0, tau);
+        std::string err = rc == DSP_OK ? "" : dsp_last_error();
+        for (int k = 1; k < K; ++k) {
+            int rk;
+            if (threads) {
+                Worker* w = pl->workers[k];
+                std::unique_lock<std::mutex> lk(w->mu);
+                w->cv.wait(lk, [&] { return w->finished; });
+                rk = w->rc;
+                if (rk != DSP_OK && rc == DSP_OK) err = w->err;
+            } else {
+                rk = run_block_tick(pl, k, tau);
+                if (rk != DSP_OK && rc == DSP_OK) err = dsp_last_error();
+            }
+            if (rc == DSP_OK) rc = rk;
+        }
+        if (rc != DSP_OK) set_error("%s", err.c_str());
+        return rc;
+    }
+    DSP_HIP(hipEventRecord(pl->fork, s0));
+    for (int k = 1; k < K; ++k) DSP_HIP(hipStreamWaitEvent(pl->streams[k], pl->fork, 0));
+    for (int k = 0; k < K; ++k) {
+        hipStream_t st = pl->streams[k];
+        if (pl->delay_us[k] > 0) DSP_TRY(launch_spin(pl->delay_us[k], st));
+        DSP_TRY(block_tick(pl, k, tau, st, true, true));
+    }
+    if (capturing)
+        for (int k = 1; k < K; ++k) {
+            DSP_HIP(hipEventRecord(pl->join[k], pl->streams[k]));
+            DSP_HIP(hipStreamWaitEvent(s0, pl->join[k], 0));
+        }
     return DSP_OK;
 }
 
@@ -232,67 +469,60 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
     const int64_t tau = pl->tau;
     const int cur = (int)(tau & 1), prev = cur ^ 1;
     hipStream_t user = (hipStream_t)stream;
+    hipStream_t s0 = pl->streams[0];
+
+    const bool graph_tick = pl->use_graphs && pl->period > 0 && !g_profile_on && tau > pl->fill;
+    const int phase = graph_tick ? (int)(tau % pl->period) : 0;
 
     // the data source: copy the mini-batch into block 0's ring slot and the labels into the label ring
-    hipStream_t s0 = pl->streams[0];
     DSP_HIP(hipEventRecord(pl->in_ready, user));
     DSP_HIP(hipStreamWaitEvent(s0, pl->in_ready, 0));
-    // (the mini-batch itself is copied into block 0's ring slot by dsp_block_forward, on stream 0)
+    if (tau > 0 && !pl->serial) {
+        // block 0's slot for this tick is free (its own earlier ticks ran on this stream); a graph tick
+        // additionally starts only after every stream has finished the previous tick
+        for (int k = 1; k < K; ++k)
+            if (graph_tick || k == 1) DSP_HIP(hipStreamWaitEvent(s0, pl->done[prev][k], 0));
+    }
+    void* slot0;
+    DSP_TRY(dsp_block_input_slot(pl->blocks[0], tau, &slot0));
+    DSP_HIP(hipMemcpyAsync(slot0, d_batch, pl->in_bytes, hipMemcpyDeviceToDevice, s0));
     if (d_labels)
         DSP_HIP(hipMemcpyAsync(pl->labels + (size_t)(tau % pl->label_slots) * pl->N, d_labels, (size_t)pl->N * 4,
                                hipMemcpyDeviceToDevice, s0));
-
-    auto block_tick = [&](int k, hipStream_t st, bool do_fwd, bool do_bwd) -> int {
-        const int64_t a = tau - pl->P[k];
-        if (a < 0) return DSP_OK;
-        dsp_block* b = pl->blocks[k];
-        const int64_t bb = a - pl->m[k];
-        if (do_fwd) {
-            const void* in;
-            if (k == 0) {
-                in = d_batch;  // copied into the ring by the block itself
-            } else {
-                void* sl;
-                DSP_TRY(dsp_block_input_slot(b, a, &sl));
-                in = sl;
-            }
-            void* out = nullptr;
-            if (k < K - 1) DSP_TRY(dsp_block_input_slot(pl->blocks[k + 1], a, &out));
-            const int32_t* lab = pl->labels + (size_t)(a % pl->label_slots) * pl->N;
-            DSP_TRY(dsp_block_forward(b, a, in, out, k == K - 1 ? lab : nullptr, k == K - 1 ? pl->losses + a : nullptr, st));
-            if (k == 0) {
-                DSP_HIP(hipEventRecord(pl->in_copied, st));
-                DSP_HIP(hipStreamWaitEvent(user, pl->in_copied, 0));
-            }
-        }
-        if (do_bwd && bb >= 0) {
-            const void* gout = k < K - 1 ? pl->qring[k + 1] + (size_t)(bb % (1 + pl->q[k + 1])) * pl->qslot_bytes[k + 1] : nullptr;
-            void* gin = k > 0 ? pl->qring[k] + (size_t)(bb % (1 + pl->q[k])) * pl->qslot_bytes[k] : nullptr;
-            DSP_TRY(dsp_block_recompute_backward(b, bb, gout, gin, st));
-            DSP_TRY(dsp_param_update(b, pl->lr, pl->momentum, pl->wd, st));
-        }
-        return DSP_OK;
-    };
+    DSP_HIP(hipEventRecord(pl->in_copied, s0));
+    DSP_HIP(hipStreamWaitEvent(user, pl->in_copied, 0));
 
     if (pl->serial) {
         // ordinary backpropagation: forward up the chain, backward down the chain, one stream
-        for (int k = 0; k < K; ++k) DSP_TRY(block_tick(k, s0, true, false));
-        for (int k = K - 1; k >= 0; --k) DSP_TRY(block_tick(k, s0, false, true));
+        for (int k = 0; k < K; ++k) DSP_TRY(block_tick(pl, k, tau, s0, true, false));
+        for (int k = K - 1; k >= 0; --k) DSP_TRY(block_tick(pl, k, tau, s0, false, true));
+    } else if (!graph_tick) {
+        DSP_TRY(issue_tick(pl, tau, false));
     } else {
-        for (int k = 0; k < K; ++k) {
-            hipStream_t st = pl->streams[k];
-            // Neighbours' previous tick: the slots this block reads were written then or earlier, and
-            // the slots it writes were last read then or earlier.  (The labels of the mini-batch the
-            // last block sees now were copied on stream 0 P_{K-1} >= K-1 ticks ago, which this chain
-            // of waits orders; the label ring has P_{K-1}+K slots so a slot is not refilled too early.)
-            if (tau > 0) {
-                if (k > 0) DSP_HIP(hipStreamWaitEvent(st, pl->done[prev][k - 1], 0));
-                if (k < K - 1) DSP_HIP(hipStreamWaitEvent(st, pl->done[prev][k + 1], 0));
-            }
-            if (pl->delay_us[k] > 0) DSP_TRY(launch_spin(pl->delay_us[k], st));
-            DSP_TRY(block_tick(k, st, true, true));
-            DSP_HIP(hipEventRecord(pl->done[cur][k], st));
+        if (!pl->graphs[phase]) {
+            // record this tick once; its launches are replayed whenever the rings are in this position again
+            hipGraph_t graph = nullptr;
+            DSP_HIP(hipStreamBeginCapture(s0, hipStreamCaptureModeRelaxed));
+            const int rc = issue_tick(pl, tau, true);
+            const hipError_t e = hipStreamEndCapture(s0, &graph);
+            DSP_TRY(rc);
+            DSP_REQUIRE(e == hipSuccess && graph, DSP_EHIP, "dsp_pipeline_step: graph capture failed: %s", hipGetErrorString(e));
+            hipGraphExec_t exec = nullptr;
+            const hipError_t e2 = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+            (void)hipGraphDestroy(graph);
+            DSP_REQUIRE(e2 == hipSuccess && exec, DSP_EHIP, "dsp_pipeline_step: graph instantiation failed: %s",
+                        hipGetErrorString(e2));
+            pl->graphs[phase] = exec;
+        } else {
+            // advance every block's host-side state exactly as the recorded launches would
+            for (int k = 0; k < K; ++k) block_set_dry(pl->blocks[k], true);
+            int rc = DSP_OK;
+            for (int k = 0; k < K && rc == DSP_OK; ++k) rc = block_tick(pl, k, tau, nullptr, true, true, true);
+            for (int k = 0; k < K; ++k) block_set_dry(pl->blocks[k], false);
+            DSP_TRY(rc);
         }
+        DSP_HIP(hipGraphLaunch(pl->graphs[phase], s0));
+        for (int k = 0; k < K; ++k) DSP_HIP(hipEventRecord(pl->done[cur][k], s0));
     }
     pl->tau = tau + 1;
 
@@ -301,7 +531,7 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
     if (h_loss) {
         *h_loss = 0.f;
         if (a_last >= 0) {
-            hipStream_t sl = pl->serial ? s0 : pl->streams[K - 1];
+            hipStream_t sl = (pl->serial || graph_tick) ? s0 : pl->streams[K - 1];
             DSP_HIP(hipStreamSynchronize(sl));
             DSP_HIP(hipMemcpy(h_loss, pl->losses + a_last, 4, hipMemcpyDeviceToHost));
         }

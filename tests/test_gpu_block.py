@@ -273,7 +273,8 @@ def _manual_schedule(cfg, params, batches, dtype):
 
 
 @pytest.mark.parametrize("name,dtype,ticks,kw", [
-    ("resnet20", D.DSP_FP32, 14, {"batch": 16, "hw": 16}),
+    ("tiny2", D.DSP_FP32, 30, {}),                                    # ring period 6: every tick graph replayed 4x
+    ("resnet20", D.DSP_FP32, 50, {"batch": 8, "hw": 16}),             # ring period 20: graphs replayed twice
     ("resnet56", D.DSP_BF16, 14, {"batch": 8, "hw": 16}),
     ("resnet18", D.DSP_BF16, 12, {"batch": 4, "hw": 64}),
     ("resnet20", D.DSP_FP32, 12, {"batch": 4, "hw": 8, "p": (2, 2, 0), "m": (6, 3, 0)}),   # p = 2: deeper queues
@@ -323,6 +324,38 @@ def test_pipeline_loss_trajectory(name, dtype, ticks, kw, rtol):
     assert versions == [o.n_updates for o in orc.opt]
     for k in range(cfg["K"]):
         assert rel_err(final[k], _flat(orc.blocks[k].param_list())) < (rtol if rtol <= 1e-3 else 1e-1)
+
+
+def test_graph_replay_equals_kernel_by_kernel_issue():
+    """Ticks replayed from HIP graphs (with the program's own synchronisations and host reads in between)
+    give the bits of the same ticks issued kernel by kernel."""
+    outs = []
+    for graphs in (True, False):
+        cfg, params, rng = _setup("resnet20", batch=8, hw=16)
+        blocks = build_gpu_blocks(cfg, params, D.DSP_FP32)
+        pl = D.dsp_pipeline_init(blocks, cfg["p"], cfg["m"], cfg["lr"], cfg["beta"], cfg["wd"], 70)
+        D.dsp_pipeline_set_graph_replay(pl, graphs)
+        seen = []
+        for tau in range(70):
+            x, y = make_batch(rng, cfg["input"], cfg["classes"])
+            loss, bid = D.dsp_pipeline_step(pl, to_dev(x, D.DSP_FP32), torch.from_numpy(y).cuda(), want_loss=(tau % 7 == 0))
+            if loss is not None:
+                seen.append((bid, loss))
+            if tau % 11 == 0:
+                torch.cuda.synchronize()
+        losses = D.dsp_pipeline_losses(pl)
+        prm = [D.dsp_block_get_params(b) for b in blocks]
+        ver = [D.dsp_block_query(b)["version"] for b in blocks]
+        D.dsp_pipeline_destroy(pl)
+        destroy_blocks(blocks)
+        outs.append((losses, prm, ver, seen))
+    assert np.array_equal(outs[0][0], outs[1][0]) and len(outs[0][0]) == 68
+    assert outs[0][2] == outs[1][2] == [66, 67, 68]
+    assert outs[0][3] == outs[1][3]
+    for bid, loss in outs[0][3]:
+        assert loss == outs[0][0][bid]
+    for a, b in zip(outs[0][1], outs[1][1]):
+        assert np.array_equal(a, b)
 
 
 def test_zero_staleness_pipeline_is_backprop():
