@@ -83,6 +83,9 @@ struct Layer {
     bool in1_grad = true;
     bool in0_acc = false;  // add to (true) or overwrite (false) the gradient buffer of in0
     bool in1_acc = false;
+    // conv: the next layer is a batch norm of this output, so the conv kernel also leaves the per-tile
+    // column sums in the block's partial-sum buffer; bn: number of such tiles (0 = sum x itself)
+    int sum_tiles = 0;
 };
 
 }  // namespace dsp
@@ -324,7 +327,16 @@ static int build_graph(dsp_block* b)
     }
     b->wgrad_ws_bytes = ws;
     DSP_TRY(dev_alloc(b, &b->wgrad_ws, ws, &b->ws_bytes));
-    DSP_TRY(dev_alloc(b, (void**)&b->bn_partial, (size_t)bn_max_partial_blocks() * max_c * 2 * sizeof(double), &b->ws_bytes));
+    size_t partial_elems = (size_t)bn_max_partial_blocks() * max_c;
+    for (int i = 0; i + 1 < d.n_layers; ++i) {
+        Layer& L = b->layers[i];
+        Layer& nx = b->layers[i + 1];
+        if (L.d.op != DSP_OP_CONV || nx.d.op != DSP_OP_BN || nx.d.in0 != i) continue;
+        L.sum_tiles = nx.sum_tiles = conv_forward_row_tiles(b->dtype, L.cs);
+        const size_t e = (size_t)L.sum_tiles * L.d.cout;
+        if (e > partial_elems) partial_elems = e;
+    }
+    DSP_TRY(dev_alloc(b, (void**)&b->bn_partial, partial_elems * 2 * sizeof(double), &b->ws_bytes));
     DSP_TRY(dev_alloc(b, (void**)&b->bn_coef, (size_t)3 * max_c * 4, &b->ws_bytes));
     DSP_TRY(dev_alloc(b, (void**)&b->loss_sink, 4, &b->ws_bytes));
     if (b->loss_idx >= 0) {
@@ -370,13 +382,14 @@ static int run_forward(dsp_block* b, const void* in, void* out_override, const i
         void* dst = (i == b->out_idx && out_override) ? out_override : t.act;
         switch (L.d.op) {
         case DSP_OP_CONV:
-            DSP_TRY(launch_conv_forward(b->dtype, L.cs, src, weights_for_forward(b, L), dst, st));
+            DSP_TRY(launch_conv_forward(b->dtype, L.cs, src, weights_for_forward(b, L), dst, st,
+                                        L.sum_tiles > 0 ? b->bn_partial : nullptr));
             break;
         case DSP_OP_BN: {
             const void* res = L.d.in1 == -2 ? nullptr : act_of(L.d.in1);
             BnBuffers buf{b->bn_partial, L.mean, L.invstd, b->bn_coef};
             DSP_TRY(launch_bn_forward(b->dtype, src, res, dst, b->x + L.p0, b->x + L.p1, b->desc.bn_eps,
-                                      (int64_t)s.N * s.H * s.W, s.C, L.d.relu != 0, buf, st));
+                                      (int64_t)s.N * s.H * s.W, s.C, L.d.relu != 0, buf, st, L.sum_tiles));
             break;
         }
         case DSP_OP_MAXPOOL:

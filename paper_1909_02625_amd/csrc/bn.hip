@@ -283,14 +283,16 @@ inline int apply_grid(int64_t nvec)
 
 template <typename T, int VW>
 int bn_forward_t(const void* x, const void* res, void* y, const float* gamma, const float* beta, float eps, int64_t M,
-                 int C, bool relu, const BnBuffers& buf, hipStream_t st)
+                 int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed)
 {
     const RowLayout L = make_layout(C, VW);
     int nblk;
     const int rows = plan_rows(M, L, &nblk);
     const dim3 grid(nblk, ceil_div(L.cv, L.cvb));
     const double tensor_bytes = (double)M * C * sizeof(T);
-    {
+    if (presummed > 0) {
+        nblk = presummed;
+    } else {
         ProfScope ps(sizeof(T) == 2 ? "bn_stats<bf16>" : "bn_stats<fp32>", tensor_bytes, 1);
         DSP_LAUNCH(ps, (bn_sums_kernel<T, VW, 0, false>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)nullptr,
                    (const T*)nullptr, (const float*)nullptr, (const float*)nullptr, buf.partial, M, C, L, rows);
@@ -359,15 +361,15 @@ int bn_backward_t(const void* dy, const void* x, const void* y, void* dx, void* 
 int bn_max_partial_blocks() { return kMaxPartialBlocks; }
 
 int launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
-                      float eps, int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st)
+                      float eps, int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed)
 {
-    DSP_REQUIRE(M > 0 && C > 0, DSP_EINVAL, "bn: bad shape");
+    DSP_REQUIRE(M > 0 && C > 0 && presummed >= 0, DSP_EINVAL, "bn: bad shape");
     if (dtype == DSP_BF16) {
-        if (C % 8 == 0) return bn_forward_t<bf16_t, 8>(x, res, y, gamma, beta, eps, M, C, relu, buf, st);
-        return bn_forward_t<bf16_t, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st);
+        if (C % 8 == 0) return bn_forward_t<bf16_t, 8>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed);
+        return bn_forward_t<bf16_t, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed);
     }
-    if (C % 4 == 0) return bn_forward_t<float, 4>(x, res, y, gamma, beta, eps, M, C, relu, buf, st);
-    return bn_forward_t<float, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st);
+    if (C % 4 == 0) return bn_forward_t<float, 4>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed);
+    return bn_forward_t<float, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed);
 }
 
 int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, void* dx, void* dres,

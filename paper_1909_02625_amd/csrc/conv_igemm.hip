@@ -18,6 +18,8 @@
 // small CIFAR-shaped layers put a few hundred workgroups on the 256 compute units.
 #include <stdio.h>
 
+#include <atomic>
+
 #include "common.h"
 
 namespace dsp {
@@ -109,8 +111,10 @@ struct Tile {
     // the output tile is staged through LDS so that global stores are whole 16-byte runs
     static constexpr int EPI_ROWB = BN * (int)sizeof(T) + 16;
     static constexpr int EPI_BYTES = BM * EPI_ROWB;
-    static constexpr int LDS_BYTES = cmax(LOAD_BYTES, EPI_BYTES);
+    static constexpr int STATS_BYTES = kThreads * 2 * (int)sizeof(double);  // column-sum scratch behind the staged tile
+    static constexpr int LDS_BYTES = cmax(LOAD_BYTES, EPI_BYTES + STATS_BYTES);
     static_assert(BKB % KSB == 0 && kThreads % CPR == 0 && (STAGES == 1 || STAGES == 2), "tile shape");
+    static_assert(kThreads % BN == 0 && EPI_BYTES % 8 == 0, "column sums: whole row groups, aligned scratch");
 };
 
 template <typename TL>
@@ -155,6 +159,9 @@ struct GatherGeom {
     int M, Kdim;
     int accum;    // add to `out` instead of overwriting it
     int out_vec;  // `out` rows can be written as whole 16-byte runs
+    // if set: per row tile, the column sums {sum y, sum y^2} of the values as stored, [row tile][Co][2];
+    // lets the batch norm that consumes `out` skip its own pass over the tensor
+    double* stats;
 };
 
 // 16-byte loads through a buffer descriptor: the hardware returns zeros for any offset at or past
@@ -388,6 +395,32 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
             *(u32x4*)dst = *(const u32x4*)src;
         } else {
             for (int e = 0; e < E && col + e < g.Co; ++e) dst[e] = ((const T*)src)[e];
+        }
+    }
+    if (g.stats) {
+        // column sums of the staged tile (rows past M hold zeros): thread = (row group, column)
+        constexpr int G = kThreads / TL::BN;
+        const int c = tid % TL::BN, rg = tid / TL::BN;
+        float s0 = 0.f, s1 = 0.f;
+        for (int r = rg; r < TL::BM; r += G) {
+            const float v = to_float<T>(*(const T*)(smem + r * TL::EPI_ROWB + c * (int)sizeof(T)));
+            s0 += v;
+            s1 += v * v;
+        }
+        double* sred = (double*)(smem + TL::EPI_BYTES);
+        sred[(rg * TL::BN + c) * 2] = (double)s0;
+        sred[(rg * TL::BN + c) * 2 + 1] = (double)s1;
+        __syncthreads();
+        if (rg == 0 && n0 + c < g.Co) {
+            double a = 0.0, b = 0.0;
+#pragma unroll
+            for (int k = 0; k < G; ++k) {
+                a += sred[(k * TL::BN + c) * 2];
+                b += sred[(k * TL::BN + c) * 2 + 1];
+            }
+            double* dst = g.stats + ((int64_t)(blockIdx.x / tiles_n) * g.Co + n0 + c) * 2;
+            dst[0] = a;
+            dst[1] = b;
         }
     }
 }
@@ -651,39 +684,143 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
         }
 }
 
-// dw[i] = sum over slices of part[slice][i], slices in ascending order (run-to-run identical).
-// A workgroup owns 32 consecutive elements; 8 lanes per element each add every 8th slice, then the
-// 8 lane sums are added in lane order: a fixed summation tree, many loads in flight per element.
+// Backward-weight of an fp32 layer with 16 input and 16 output channels.  The GEMM output is only
+// 16 x (R*S*16), so LDS tiling buys nothing: each wave streams its own output pixels straight from
+// global memory into the 16x16x4 MFMA operand layout (lane = (pixel % 4) * 16 + channel, one
+// coalesced 256-byte load per operand and step) and keeps all R*S accumulator tiles in registers.
+// Waves of a workgroup interleave at 4-pixel granularity, are summed through LDS in wave order and
+// written as one slice of the partial buffer.
+template <int R, int S>
+__global__ __launch_bounds__(kThreads) void conv_wgrad_c16_kernel(const float* __restrict__ x,
+                                                                  const float* __restrict__ dy,
+                                                                  float* __restrict__ part, WgradGeom g)
+{
+    constexpr int TAPS = R * S;
+    __shared__ float red[4][TAPS * 256];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 15, kq = lane >> 4;
+    const int m_begin = blockIdx.x * g.m_per_split;
+    const int m_end = min(g.M, m_begin + g.m_per_split);
+    const int nsteps = (m_end - m_begin + 15) / 16;
+    const __amdgpu_buffer_rsrc_t rdy = make_rsrc(dy, (uint32_t)g.M * 16 * 4);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)g.N * g.H * g.W * 16 * 4);
+
+    f32x4 acc[TAPS];
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    int m = m_begin + 4 * wave + kq;
+    int wo = m % g.Wo, tq = m / g.Wo, ho = tq % g.Ho, n = tq / g.Ho;
+    // operands of the pixel (n, ho, wo) this lane holds in the current step; zeros past the slice
+    auto fetch = [&](float& a, float (&b)[TAPS]) {
+        const bool live = m < m_end;
+        a = __builtin_bit_cast(
+            float, __builtin_amdgcn_raw_buffer_load_b32(rdy, live ? (uint32_t)(m * 16 + col) * 4u : kOutOfRange, 0, 0));
+        const int hi0 = ho * g.stride - g.pad, wi0 = wo * g.stride - g.pad;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int hi = hi0 + r;
+            const bool hok = live && hi >= 0 && hi < g.H;
+            const uint32_t rowoff = (uint32_t)((n * g.H + hi) * g.W);
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                const int wi = wi0 + s;
+                const bool ok = hok && wi >= 0 && wi < g.W;
+                b[r * S + s] = __builtin_bit_cast(
+                    float, __builtin_amdgcn_raw_buffer_load_b32(
+                               rx, ok ? ((rowoff + (uint32_t)wi) * 16u + (uint32_t)col) * 4u : kOutOfRange, 0, 0));
+            }
+        }
+        m += 16;
+        wo += 16;
+        while (wo >= g.Wo) {
+            wo -= g.Wo;
+            if (++ho == g.Ho) { ho = 0; ++n; }
+        }
+    };
+    // four steps of operands in flight per wave; steps past the slice read zeros
+    constexpr int DEPTH = 4;
+    float a[DEPTH], b[DEPTH][TAPS];
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) fetch(a[d], b[d]);
+    for (int it = 0; it < nsteps; it += DEPTH) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+#pragma unroll
+            for (int t = 0; t < TAPS; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[d], b[d][t], acc[t], 0, 0, 0);
+            fetch(a[d], b[d]);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) red[wave][(t * 4 + j) * 64 + lane] = acc[t][j];
+    __syncthreads();
+    float* dst = part + (int64_t)blockIdx.x * 16 * g.Kdim;
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t) {
+        const int idx = t * 256 + tid;
+        const float v = ((red[0][idx] + red[1][idx]) + red[2][idx]) + red[3][idx];
+        const int j = tid >> 6, l = tid & 63, co = (l >> 4) * 4 + j, ci = l & 15;
+        dst[co * g.Kdim + t * 16 + ci] = v;
+    }
+}
+
+// dw[i] = sum over slices of part[slice][i] in a fixed summation tree (run-to-run identical).
+// A workgroup owns 32 consecutive elements: 8 threads cover them with 16-byte loads, 32 such
+// thread rows each add every 32nd slice, and the 32 row sums are then added in row order.
+// VW = 4 needs n % 4 == 0 and a 16-byte aligned partial buffer.
+template <int VW>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw, int n,
                                                            int splits)
 {
-    __shared__ float red[8][33];
-    const int col = threadIdx.x & 31, lane = threadIdx.x >> 5;
-    const int i = blockIdx.x * 32 + col;
-    float s = 0.f;
-    if (i < n)
-        for (int k = lane; k < splits; k += 8) s += part[(int64_t)k * n + i];
-    red[lane][col] = s;
-    __syncthreads();
-    if (lane == 0 && i < n) {
-        float t = red[0][col];
+    constexpr int COLS = 32 / VW, ROWS = 256 / COLS;
+    __shared__ float red[ROWS][33];
+    const int cg = threadIdx.x % COLS, row = threadIdx.x / COLS;
+    const int i = blockIdx.x * 32 + cg * VW;
+    float s[VW];
 #pragma unroll
-        for (int k = 1; k < 8; ++k) t += red[k][col];
-        dw[i] = t;
+    for (int v = 0; v < VW; ++v) s[v] = 0.f;
+    if (i < n) {
+#pragma unroll 4
+        for (int k = row; k < splits; k += ROWS) {
+            const float* src = part + (int64_t)k * n + i;
+            if (VW == 4) {
+                const f32x4 t = *(const f32x4*)src;
+#pragma unroll
+                for (int v = 0; v < VW; ++v) s[v] += t[v];
+            } else {
+                s[0] += src[0];
+            }
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < VW; ++v) red[row][cg * VW + v] = s[v];
+    __syncthreads();
+    const int c = threadIdx.x;
+    if (c < 32 && blockIdx.x * 32 + c < n) {
+        float t = red[0][c];
+#pragma unroll 8
+        for (int k = 1; k < ROWS; ++k) t += red[k][c];
+        dw[blockIdx.x * 32 + c] = t;
     }
 }
 
 // ---- host-side dispatch -------------------------------------------------------------------------
-template <typename TL>
-const char* tile_name(const char* what, bool vec)
+struct KernelName {
+    char text[96];
+};
+
+// One name per kernel instantiation, e.g. "conv_gather_gemm<fp32,mfma32,BM128,BN64,BK16,vec>".
+template <typename TL, bool VEC, bool WGRAD>
+const char* tile_name()
 {
-    // one name per kernel instantiation, e.g. "conv_gather_gemm<fp32,mfma32,BM128,BN64,vec>"
-    static char names[2][96];
-    char* n = names[vec ? 1 : 0];
-    if (!n[0])
-        snprintf(n, 96, "%s<%s,mfma%d,BM%d,BN%d,BK%d,%s>", what, sizeof(typename TL::T) == 2 ? "bf16" : "fp32", TL::MT,
-                 TL::BM, TL::BN, TL::BK, vec ? "vec" : "scalar");
-    return n;
+    static const KernelName name = [] {
+        KernelName k;
+        snprintf(k.text, sizeof(k.text), "%s<%s,mfma%d,BM%d,BN%d,BK%d,%s>", WGRAD ? "conv_wgrad" : "conv_gather_gemm",
+                 sizeof(typename TL::T) == 2 ? "bf16" : "fp32", TL::MT, TL::BM, TL::BN, TL::BK, VEC ? "vec" : "scalar");
+        return k;
+    }();
+    return name.text;
 }
 
 template <typename TL, bool VEC>
@@ -693,13 +830,13 @@ int run_gather(const GatherGeom& g, const void* in, const void* w, void* out, hi
     const int64_t tiles = (int64_t)ceil_div(g.M, TL::BM) * ceil_div(g.Co, TL::BN);
     DSP_REQUIRE(tiles > 0 && tiles < (1ll << 31), DSP_EINVAL, "conv: bad tile count");
     auto kern = conv_gather_gemm_kernel<TL, VEC>;
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done && TL::LDS_BYTES > 48 * 1024) {
         DSP_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES));
         attr_done = true;
     }
     {
-        ProfScope ps(tile_name<TL>("conv_gather_gemm", VEC), flops, 0);
+        ProfScope ps(tile_name<TL, VEC, false>(), flops, 0);
         DSP_LAUNCH(ps, kern, dim3((unsigned)tiles), dim3(kThreads), TL::LDS_BYTES, st, (const T*)in, (const T*)w, (T*)out, g);
     }
     DSP_HIP(hipGetLastError());
@@ -717,6 +854,27 @@ constexpr int64_t kEnoughTiles = 384;
 
 inline int64_t tile_count(const GatherGeom& g, int bm, int bn) { return (int64_t)ceil_div(g.M, bm) * ceil_div(g.Co, bn); }
 
+// Largest tile of the channel class that still yields enough workgroups, else the smallest.
+// Returns the tile id used by dispatch_gather and the tile's row count.
+template <typename T>
+int select_gather_tile(const GatherGeom& g, int* bm)
+{
+    if (g.Co <= 16) {
+        if (tile_count(g, 256, 16) >= kEnoughTiles) { *bm = 256; return 0; }
+        *bm = 64;
+        return 1;
+    }
+    if (g.Co <= 32) {
+        if (tile_count(g, 256, 32) >= kEnoughTiles) { *bm = 256; return 2; }
+        *bm = 128;
+        return 3;
+    }
+    if (g.Co % 128 == 0 && tile_count(g, 128, 128) >= kEnoughTiles) { *bm = 128; return 4; }
+    if (tile_count(g, 128, 64) >= kEnoughTiles) { *bm = 128; return 5; }
+    *bm = 64;
+    return 6;
+}
+
 template <typename T>
 int dispatch_gather(GatherGeom g, bool accum, const void* in, const void* w, void* out, hipStream_t st, double flops)
 {
@@ -727,22 +885,16 @@ int dispatch_gather(GatherGeom g, bool accum, const void* in, const void* w, voi
     const bool vec = (g.Ci % E) == 0 && ((uintptr_t)in % 16) == 0 && ((uintptr_t)w % 16) == 0 && g.R * g.S <= 32;
     g.accum = accum ? 1 : 0;
     g.out_vec = ((g.Co % E) == 0 && ((uintptr_t)out % 16) == 0) ? 1 : 0;
-    // largest tile of the channel class that still yields enough workgroups, else the smallest
-    if (g.Co <= 16) {
-        if (tile_count(g, 256, 16) >= kEnoughTiles)
-            return run_gather_v<Tile<T, 16, 4, 1, 4, 1, 64, 2>>(g, vec, in, w, out, st, flops);
-        return run_gather_v<Tile<T, 16, 4, 1, 1, 1, 64, 2>>(g, vec, in, w, out, st, flops);
+    int bm;
+    switch (select_gather_tile<T>(g, &bm)) {
+    case 0: return run_gather_v<Tile<T, 16, 4, 1, 4, 1, 64, 2>>(g, vec, in, w, out, st, flops);
+    case 1: return run_gather_v<Tile<T, 16, 4, 1, 1, 1, 64, 2>>(g, vec, in, w, out, st, flops);
+    case 2: return run_gather_v<Tile<T, 32, 4, 1, 2, 1, 64, 2>>(g, vec, in, w, out, st, flops);
+    case 3: return run_gather_v<Tile<T, 32, 4, 1, 1, 1, 64, 2>>(g, vec, in, w, out, st, flops);
+    case 4: return run_gather_v<Tile<T, 32, 2, 2, 2, 2, KB, 2>>(g, vec, in, w, out, st, flops);
+    case 5: return run_gather_v<Tile<T, 32, 2, 2, 2, 1, KB, 2>>(g, vec, in, w, out, st, flops);
+    default: return run_gather_v<Tile<T, 32, 2, 2, 1, 1, KB, 2>>(g, vec, in, w, out, st, flops);
     }
-    if (g.Co <= 32) {
-        if (tile_count(g, 256, 32) >= kEnoughTiles)
-            return run_gather_v<Tile<T, 32, 4, 1, 2, 1, 64, 2>>(g, vec, in, w, out, st, flops);
-        return run_gather_v<Tile<T, 32, 4, 1, 1, 1, 64, 2>>(g, vec, in, w, out, st, flops);
-    }
-    if (g.Co % 128 == 0 && tile_count(g, 128, 128) >= kEnoughTiles)
-        return run_gather_v<Tile<T, 32, 2, 2, 2, 2, KB, 2>>(g, vec, in, w, out, st, flops);
-    if (tile_count(g, 128, 64) >= kEnoughTiles)
-        return run_gather_v<Tile<T, 32, 2, 2, 2, 1, KB, 2>>(g, vec, in, w, out, st, flops);
-    return run_gather_v<Tile<T, 32, 2, 2, 1, 1, KB, 2>>(g, vec, in, w, out, st, flops);
 }
 
 template <typename TL, bool VEC>
@@ -751,13 +903,13 @@ int run_wgrad(const WgradGeom& g, int splits, const void* x, const void* dy, flo
     typedef typename TL::T T;
     const int tiles = ceil_div(g.Co, TL::BM) * ceil_div(g.Kdim, TL::BN);
     auto kern = conv_wgrad_kernel<TL, VEC>;
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done && TL::LOAD_BYTES > 48 * 1024) {
         DSP_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LOAD_BYTES));
         attr_done = true;
     }
     {
-        ProfScope ps(tile_name<TL>("conv_wgrad", VEC), flops, 0);
+        ProfScope ps(tile_name<TL, VEC, true>(), flops, 0);
         DSP_LAUNCH(ps, kern, dim3(tiles, splits), dim3(kThreads), TL::LOAD_BYTES, st, (const T*)x, (const T*)dy, dst, g);
     }
     DSP_HIP(hipGetLastError());
@@ -802,6 +954,23 @@ int wgrad_splits(const ConvShape& c, const WgradPlan& pl, int* m_per_split)
     return ceil_div(M, per);
 }
 
+// The register-streaming kernel serves fp32 layers with 16 -> 16 channels and 3x3 or 1x1 filters.
+bool wgrad_c16_eligible(int dtype, const ConvShape& c)
+{
+    return dtype == DSP_FP32 && c.Cin == 16 && c.Cout == 16 && ((c.R == 3 && c.S == 3) || (c.R == 1 && c.S == 1));
+}
+
+// About two workgroups per compute unit; a slice is a multiple of the 16 pixels one step covers.
+int wgrad_c16_splits(const ConvShape& c, int* m_per_split)
+{
+    const int64_t M = (int64_t)c.N * c.Ho * c.Wo;
+    int per = (int)((M + 511) / 512);
+    if (per < 64) per = 64;
+    per = ceil_div(per, 16) * 16;
+    *m_per_split = per;
+    return ceil_div(M, per);
+}
+
 template <typename T>
 int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes,
                    hipStream_t st, double flops)
@@ -813,7 +982,8 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
     WgradGeom g{c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.stride, 0, 0, 0};
     g.M = c.N * c.Ho * c.Wo;
     g.Kdim = c.R * c.S * c.Cin;
-    const int splits = wgrad_splits(c, pl, &g.m_per_split);
+    const bool c16 = wgrad_c16_eligible(dtype, c);
+    const int splits = c16 ? wgrad_c16_splits(c, &g.m_per_split) : wgrad_splits(c, pl, &g.m_per_split);
     const size_t n = (size_t)c.Cout * g.Kdim;
     float* dst = dw;
     if (splits > 1) {
@@ -823,6 +993,16 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
     }
     const bool vec = (c.Cin % E) == 0 && (c.Cout % E) == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)dy % 16) == 0;
     int rc;
+    if (c16) {
+        ProfScope ps(c.R == 3 ? "conv_wgrad_c16<fp32,3x3>" : "conv_wgrad_c16<fp32,1x1>", flops, 0);
+        if (c.R == 3)
+            DSP_LAUNCH(ps, (conv_wgrad_c16_kernel<3, 3>), dim3(splits), dim3(kThreads), 0, st, (const float*)x,
+                       (const float*)dy, dst, g);
+        else
+            DSP_LAUNCH(ps, (conv_wgrad_c16_kernel<1, 1>), dim3(splits), dim3(kThreads), 0, st, (const float*)x,
+                       (const float*)dy, dst, g);
+        rc = DSP_OK;
+    } else
     switch (pl.id) {
     case 0: rc = run_wgrad_v<Tile<T, 16, 1, 4, 1, 1, KB, 2>>(g, splits, vec, x, dy, dst, st, flops); break;
     case 1: rc = run_wgrad_v<Tile<T, 32, 1, 4, 1, 1, KB, 2>>(g, splits, vec, x, dy, dst, st, flops); break;
@@ -832,7 +1012,12 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
     DSP_TRY(rc);
     if (splits > 1) {
         ProfScope ps("wgrad_reduce", (double)n * (splits + 1) * 4.0, 1);
-        DSP_LAUNCH(ps, wgrad_reduce_kernel, dim3(ceil_div(n, 32)), dim3(256), 0, st, (const float*)ws, dw, (int)n, splits);
+        if (n % 4 == 0 && ((uintptr_t)ws % 16) == 0)
+            DSP_LAUNCH(ps, wgrad_reduce_kernel<4>, dim3(ceil_div(n, 32)), dim3(256), 0, st, (const float*)ws, dw, (int)n,
+                       splits);
+        else
+            DSP_LAUNCH(ps, wgrad_reduce_kernel<1>, dim3(ceil_div(n, 32)), dim3(256), 0, st, (const float*)ws, dw, (int)n,
+                       splits);
         DSP_HIP(hipGetLastError());
     }
     return DSP_OK;
@@ -870,12 +1055,28 @@ int check_shape(const ConvShape& c)
 
 }  // namespace
 
-int launch_conv_forward(int dtype, const ConvShape& c, const void* x, const void* w, void* y, hipStream_t st)
+static GatherGeom forward_geom(const ConvShape& c)
 {
-    DSP_TRY(check_shape(c));
-    GatherGeom g{c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.pad, c.stride, 1, 0, 0, 0, 0};
+    GatherGeom g{c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.pad, c.stride, 1, 0, 0, 0, 0, nullptr};
     g.M = c.N * c.Ho * c.Wo;
     g.Kdim = c.R * c.S * c.Cin;
+    return g;
+}
+
+int conv_forward_row_tiles(int dtype, const ConvShape& c)
+{
+    const GatherGeom g = forward_geom(c);
+    int bm;
+    if (dtype == DSP_BF16) select_gather_tile<bf16_t>(g, &bm); else select_gather_tile<float>(g, &bm);
+    return ceil_div(g.M, bm);
+}
+
+int launch_conv_forward(int dtype, const ConvShape& c, const void* x, const void* w, void* y, hipStream_t st,
+                        double* column_sums)
+{
+    DSP_TRY(check_shape(c));
+    GatherGeom g = forward_geom(c);
+    g.stats = column_sums;
     const double flops = 2.0 * conv_macs(c);
     return dtype == DSP_BF16 ? dispatch_gather<bf16_t>(g, false, x, w, y, st, flops)
                              : dispatch_gather<float>(g, false, x, w, y, st, flops);
@@ -888,7 +1089,7 @@ int launch_conv_backward_data(int dtype, const ConvShape& c, const void* dy, con
     DSP_REQUIRE(c.stride == 1 || c.stride == 2, DSP_EINVAL, "conv backward-data: stride %d unsupported", c.stride);
     // dx[n,hi,wi,ci] = sum_{r',s',co} dy[n, (hi - (R-1-pad) + r')/stride, ...][co] * wt[ci][r'][s'][co]
     GatherGeom g{c.N, c.Ho, c.Wo, c.Cout, c.H, c.W, c.Cin, c.R, c.S, c.R - 1 - c.pad, c.S - 1 - c.pad, 1, c.stride,
-                 0, 0, 0, 0};
+                 0, 0, 0, 0, nullptr};
     g.M = c.N * c.H * c.W;
     g.Kdim = c.R * c.S * c.Cout;
     const double flops = 2.0 * conv_macs(c);
@@ -902,7 +1103,7 @@ size_t conv_backward_weight_workspace(const ConvShape& c)
     for (int dtype = 0; dtype < 2; ++dtype) {
         const WgradPlan pl = wgrad_plan(dtype, c);
         int per;
-        const int splits = wgrad_splits(c, pl, &per);
+        const int splits = wgrad_c16_eligible(dtype, c) ? wgrad_c16_splits(c, &per) : wgrad_splits(c, pl, &per);
         const size_t b = splits > 1 ? (size_t)splits * c.Cout * c.R * c.S * c.Cin * sizeof(float) : 0;
         if (b > worst) worst = b;
     }

@@ -21,6 +21,8 @@ SHAPES = [
     (2, 20, 20, 3, 64, 7, 7, 2, 3),     # stem 7x7/2
     (2, 6, 6, 8, 8, 3, 3, 1, 1),        # channel count below the tile width
     (1, 5, 5, 24, 40, 3, 3, 1, 1),      # channel counts that are no power of two
+    (4, 13, 13, 16, 16, 3, 3, 2, 1),    # 16 -> 16 channels, stride 2, several slices with a ragged tail
+    (2, 11, 11, 16, 16, 1, 1, 1, 0),    # 16 -> 16 channels, 1x1
 ]
 
 
