@@ -149,11 +149,35 @@ int dsp_block_recompute_backward(dsp_block* b, int64_t batch_id, const void* d_g
                                  void* stream);
 
 /*
+ * dsp_block_forward(batch_fwd, ...) followed by dsp_block_recompute_backward(batch_bwd, ...) as one
+ * call, with the same arguments, checks and results (bit-identical).  Both forward sweeps of a tick --
+ * the current mini-batch and the recompute of the stale one -- evaluate f_k with the same parameters
+ * (Section 3: the update comes after both), so for m_k > 0 every layer serves both with one kernel
+ * launch that carries two problem instances; this needs the second buffer set of
+ * dsp_block_enable_forward_lane, which the first call allocates.  batch_bwd must be
+ * batch_fwd - m_k >= 0; dsp_param_update still follows.
+ */
+int dsp_block_step(dsp_block* b, int64_t batch_fwd, const void* d_in, void* d_out, const int32_t* d_labels, float* d_loss,
+                   int64_t batch_bwd, const void* d_grad_out, void* d_grad_in, void* stream);
+
+/*
  * Momentum SGD (Eq. (3), s = 0, constant step): v <- momentum * v + (G + weight_decay * x),
  * x <- x - lr * v; weight_decay acts on conv/linear weights only.  Consumes the pending G_{x_k}
  * exactly once (DSP_ESTATE if there is none) and increments the update counter.
  */
 int dsp_param_update(dsp_block* b, float lr, float momentum, float weight_decay, void* stream);
+
+/*
+ * Allocates a second set of the buffers a forward pass writes.  Afterwards dsp_block_forward no
+ * longer touches anything dsp_block_recompute_backward reads or writes, so the two calls of one
+ * tick may be enqueued on different streams: the forward of mini-batch a and the backward of
+ * mini-batch a - m_k use the same parameters and are independent until the update (Section 3,
+ * Figure 2).  The caller must order both before dsp_param_update, and the next dsp_block_forward
+ * after that update.  Results are bit-identical to the single-stream order.  Only for m_k > 0
+ * (DSP_EINVAL otherwise: with m_k = 0 the backward reuses the forward's activations); calling it
+ * again is a no-op.  The extra memory shows up in dsp_block_memory's workspace figure.
+ */
+int dsp_block_enable_forward_lane(dsp_block* b);
 
 /* Device address of the M_k ring slot that will hold h_k(batch_id). */
 int dsp_block_input_slot(dsp_block* b, int64_t batch_id, void** d_slot);
@@ -210,6 +234,20 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
  */
 int dsp_pipeline_set_launch_threads(dsp_pipeline* pl, int32_t enable);
 int dsp_pipeline_set_graph_replay(dsp_pipeline* pl, int32_t enable);
+/*
+ *  - forward streams (default off): a block with m_k > 0 runs the forward pass of the current
+ *    mini-batch on a second stream, concurrently with the recompute + backward of the stale one
+ *    (dsp_block_enable_forward_lane); the update waits for both.  Must be set before the first
+ *    dsp_pipeline_step (DSP_ESTATE afterwards).
+ */
+int dsp_pipeline_set_forward_streams(dsp_pipeline* pl, int32_t enable);
+/*
+ *  - twin launches (default on): once a block runs both a forward and a backward in a tick it uses
+ *    dsp_block_step, i.e. one launch per layer for the forward of the current mini-batch and the
+ *    recompute of the stale one.  Ignored for blocks that use a forward stream.  May be changed
+ *    between steps.
+ */
+int dsp_pipeline_set_twin_launches(dsp_pipeline* pl, int32_t enable);
 /* Straggler emulation: block k's stream spins for `microseconds` before its work in every tick. */
 int dsp_pipeline_set_delay(dsp_pipeline* pl, int32_t k, int32_t microseconds);
 /* Waits for all K streams. */

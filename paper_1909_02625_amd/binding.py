@@ -19,7 +19,8 @@ __all__ = [
     "dsp_block_input_shape", "dsp_block_memory", "dsp_block_get_params", "dsp_block_set_params",
     "dsp_block_get_momentum", "dsp_block_set_momentum", "dsp_block_get_grads",
     "dsp_pipeline_init", "dsp_pipeline_destroy", "dsp_pipeline_step", "dsp_pipeline_set_delay",
-    "dsp_pipeline_set_graph_replay", "dsp_pipeline_set_launch_threads",
+    "dsp_pipeline_set_graph_replay", "dsp_pipeline_set_launch_threads", "dsp_pipeline_set_forward_streams",
+    "dsp_block_enable_forward_lane", "dsp_block_step", "dsp_pipeline_set_twin_launches",
     "dsp_pipeline_sync", "dsp_pipeline_losses", "dsp_pipeline_ticks",
     "dsp_conv_forward", "dsp_conv_backward_data", "dsp_conv_backward_weight", "dsp_conv_workspace_bytes",
     "dsp_profile_start", "dsp_profile_stop", "dsp_profile_get",
@@ -100,6 +101,10 @@ _SIGNATURES = {
     "dsp_pipeline_set_delay": [_vp, _i32, _i32],
     "dsp_pipeline_set_graph_replay": [_vp, _i32],
     "dsp_pipeline_set_launch_threads": [_vp, _i32],
+    "dsp_pipeline_set_forward_streams": [_vp, _i32],
+    "dsp_block_enable_forward_lane": [_vp],
+    "dsp_pipeline_set_twin_launches": [_vp, _i32],
+    "dsp_block_step": [_vp, _i64, _vp, _vp, _vp, _vp, _i64, _vp, _vp, _vp],
     "dsp_pipeline_sync": [_vp],
     "dsp_pipeline_losses": [_vp, _pf, _i64, _pi64],
     "dsp_pipeline_ticks": [_vp, _pi64],
@@ -213,6 +218,12 @@ def dsp_block_recompute_backward(b, batch_id, d_grad_out=None, d_grad_in=None, s
           "dsp_block_recompute_backward")
 
 
+def dsp_block_step(b, batch_fwd, d_in, d_out=None, d_labels=None, d_loss=None, batch_bwd=0, d_grad_out=None,
+                   d_grad_in=None, stream=None):
+    check(lib().dsp_block_step(b, batch_fwd, _ptr(d_in), _ptr(d_out), _ptr(d_labels), _ptr(d_loss), batch_bwd,
+                               _ptr(d_grad_out), _ptr(d_grad_in), _stream(stream)), "dsp_block_step")
+
+
 def dsp_param_update(b, lr, momentum, weight_decay=0.0, stream=None):
     check(lib().dsp_param_update(b, lr, momentum, weight_decay, _stream(stream)), "dsp_param_update")
 
@@ -313,6 +324,18 @@ def dsp_pipeline_set_graph_replay(pl, enable):
 
 def dsp_pipeline_set_launch_threads(pl, enable):
     check(lib().dsp_pipeline_set_launch_threads(pl, int(bool(enable))), "dsp_pipeline_set_launch_threads")
+
+
+def dsp_pipeline_set_forward_streams(pl, enable):
+    check(lib().dsp_pipeline_set_forward_streams(pl, int(bool(enable))), "dsp_pipeline_set_forward_streams")
+
+
+def dsp_pipeline_set_twin_launches(pl, enable):
+    check(lib().dsp_pipeline_set_twin_launches(pl, int(bool(enable))), "dsp_pipeline_set_twin_launches")
+
+
+def dsp_block_enable_forward_lane(b):
+    check(lib().dsp_block_enable_forward_lane(b), "dsp_block_enable_forward_lane")
 
 
 def dsp_pipeline_sync(pl):

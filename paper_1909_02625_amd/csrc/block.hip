@@ -92,6 +92,17 @@ struct Layer {
 
 using namespace dsp;
 
+// A second set of the buffers a forward pass writes (activations, batch-norm statistics and scratch,
+// pooling indices), so that the forward pass of the current mini-batch can run on another stream
+// while the recompute / backward of a stale one uses the primary set.
+struct ForwardLane {
+    std::vector<void*> act;
+    std::vector<float*> mean, invstd;
+    std::vector<uint8_t*> argmax;
+    double* bn_partial = nullptr;
+    float* bn_coef = nullptr;
+};
+
 struct dsp_block {
     dsp_block_desc desc;
     std::vector<Layer> layers;
@@ -124,6 +135,9 @@ struct dsp_block {
     size_t wgrad_ws_bytes = 0;
     double* bn_partial = nullptr;
     float* bn_coef = nullptr;
+    size_t bn_partial_elems = 0;
+    int bn_max_c = 1;
+    ForwardLane* fwd_lane = nullptr;  // set by dsp_block_enable_forward_lane
 
     size_t ring_bytes = 0, ws_bytes = 0, param_bytes = 0;
     std::vector<void*> allocs;
@@ -336,6 +350,8 @@ static int build_graph(dsp_block* b)
         const size_t e = (size_t)L.sum_tiles * L.d.cout;
         if (e > partial_elems) partial_elems = e;
     }
+    b->bn_partial_elems = partial_elems;
+    b->bn_max_c = max_c;
     DSP_TRY(dev_alloc(b, (void**)&b->bn_partial, partial_elems * 2 * sizeof(double), &b->ws_bytes));
     DSP_TRY(dev_alloc(b, (void**)&b->bn_coef, (size_t)3 * max_c * 4, &b->ws_bytes));
     DSP_TRY(dev_alloc(b, (void**)&b->loss_sink, 4, &b->ws_bytes));
@@ -365,8 +381,17 @@ static int download_params(dsp_block* b, const float* src, float* h)
     return DSP_OK;
 }
 
-// f_k on `in` with the live parameters; the block output goes to out_override if given.
-static int run_forward(dsp_block* b, const void* in, void* out_override, const int32_t* labels, float* loss,
+// One forward pass: where it reads its input, where the block output goes (nullptr: the lane's own
+// buffer) and which buffer set it writes (nullptr: the primary set, the one the backward sweep reads).
+struct ForwardPass {
+    const ForwardLane* lane;
+    const void* in;
+    void* out_override;
+};
+
+// f_k with the live parameters.  `twin` != nullptr runs a second pass (a recompute: no loss) through
+// the same launches wherever the layer kernels take two instances, else right after the first.
+static int run_forward(dsp_block* b, const ForwardPass& P, const ForwardPass* twin, const int32_t* labels, float* loss,
                        float* dz_slot, hipStream_t st)
 {
     const int n = (int)b->layers.size();
@@ -374,39 +399,60 @@ static int run_forward(dsp_block* b, const void* in, void* out_override, const i
         Layer& L = b->layers[i];
         const Tensor& s = L.d.in0 < 0 ? b->input : b->T[L.d.in0];
         // the block output lives in out_override when one is given (only the loss may read it back)
-        auto act_of = [&](int t) -> const void* {
-            return t < 0 ? in : ((t == b->out_idx && out_override) ? out_override : b->T[t].act);
+        auto act_of = [&](const ForwardPass& p, int t) -> void* {
+            if (t == b->out_idx && p.out_override) return p.out_override;
+            return p.lane ? p.lane->act[t] : b->T[t].act;
         };
-        const void* src = act_of(L.d.in0);
-        Tensor& t = b->T[i];
-        void* dst = (i == b->out_idx && out_override) ? out_override : t.act;
+        auto src_of = [&](const ForwardPass& p, int t) -> const void* { return t < 0 ? p.in : act_of(p, t); };
+        auto bn_buffers = [&](const ForwardPass& p) {
+            return BnBuffers{p.lane ? p.lane->bn_partial : b->bn_partial, p.lane ? p.lane->mean[i] : L.mean,
+                             p.lane ? p.lane->invstd[i] : L.invstd, p.lane ? p.lane->bn_coef : b->bn_coef};
+        };
+        const int passes = twin ? 2 : 1;
         switch (L.d.op) {
-        case DSP_OP_CONV:
-            DSP_TRY(launch_conv_forward(b->dtype, L.cs, src, weights_for_forward(b, L), dst, st,
-                                        L.sum_tiles > 0 ? b->bn_partial : nullptr));
+        case DSP_OP_CONV: {
+            ConvForwardTwin tw{};
+            if (twin) tw = ConvForwardTwin{src_of(*twin, L.d.in0), act_of(*twin, i), L.sum_tiles > 0 ? bn_buffers(*twin).partial : nullptr};
+            DSP_TRY(launch_conv_forward(b->dtype, L.cs, src_of(P, L.d.in0), weights_for_forward(b, L), act_of(P, i), st,
+                                        L.sum_tiles > 0 ? bn_buffers(P).partial : nullptr, twin ? &tw : nullptr));
             break;
+        }
         case DSP_OP_BN: {
-            const void* res = L.d.in1 == -2 ? nullptr : act_of(L.d.in1);
-            BnBuffers buf{b->bn_partial, L.mean, L.invstd, b->bn_coef};
-            DSP_TRY(launch_bn_forward(b->dtype, src, res, dst, b->x + L.p0, b->x + L.p1, b->desc.bn_eps,
-                                      (int64_t)s.N * s.H * s.W, s.C, L.d.relu != 0, buf, st, L.sum_tiles));
+            BnForwardTwin tw{};
+            if (twin)
+                tw = BnForwardTwin{src_of(*twin, L.d.in0), L.d.in1 == -2 ? nullptr : src_of(*twin, L.d.in1), act_of(*twin, i),
+                                   bn_buffers(*twin)};
+            DSP_TRY(launch_bn_forward(b->dtype, src_of(P, L.d.in0), L.d.in1 == -2 ? nullptr : src_of(P, L.d.in1),
+                                      act_of(P, i), b->x + L.p0, b->x + L.p1, b->desc.bn_eps, (int64_t)s.N * s.H * s.W, s.C,
+                                      L.d.relu != 0, bn_buffers(P), st, L.sum_tiles, twin ? &tw : nullptr));
             break;
         }
         case DSP_OP_MAXPOOL:
-            DSP_TRY(launch_maxpool_forward(b->dtype, src, dst, L.argmax, s.N, s.H, s.W, s.C, L.d.r, L.d.stride, L.d.pad, st));
+            for (int q = 0; q < passes; ++q) {
+                const ForwardPass& p = q ? *twin : P;
+                DSP_TRY(launch_maxpool_forward(b->dtype, src_of(p, L.d.in0), act_of(p, i), p.lane ? p.lane->argmax[i] : L.argmax,
+                                               s.N, s.H, s.W, s.C, L.d.r, L.d.stride, L.d.pad, st));
+            }
             break;
         case DSP_OP_GAP:
-            DSP_TRY(launch_gap_forward(b->dtype, src, (float*)dst, s.N, s.H * s.W, s.C, st));
+            for (int q = 0; q < passes; ++q) {
+                const ForwardPass& p = q ? *twin : P;
+                DSP_TRY(launch_gap_forward(b->dtype, src_of(p, L.d.in0), (float*)act_of(p, i), s.N, s.H * s.W, s.C, st));
+            }
             break;
         case DSP_OP_LINEAR:
-            DSP_TRY(launch_linear_forward((const float*)src, b->x + L.p0, b->x + L.p1, (float*)dst, s.N, L.d.cin, L.d.cout, st));
+            for (int q = 0; q < passes; ++q) {
+                const ForwardPass& p = q ? *twin : P;
+                DSP_TRY(launch_linear_forward((const float*)src_of(p, L.d.in0), b->x + L.p0, b->x + L.p1, (float*)act_of(p, i),
+                                              s.N, L.d.cin, L.d.cout, st));
+            }
             break;
         case DSP_OP_SOFTMAX_CE:
             // the loss and its gradient belong to the forward pass (Eq. (5), third line); a recompute
-            // (labels == nullptr) reuses the gradient stored then and must not touch them
+            // (labels == nullptr, and always the twin) reuses the gradient stored then and must not touch them
             if (labels) {
                 DSP_REQUIRE(loss && dz_slot, DSP_EINVAL, "softmax_ce: missing loss buffers");
-                DSP_TRY(launch_softmax_ce((const float*)src, labels, loss, dz_slot, b->row_loss, s.N, s.C, st));
+                DSP_TRY(launch_softmax_ce((const float*)src_of(P, L.d.in0), labels, loss, dz_slot, b->row_loss, s.N, s.C, st));
             }
             break;
         }
@@ -503,7 +549,43 @@ int dsp_block_destroy(dsp_block* b)
     if (!b) return DSP_OK;
     (void)hipDeviceSynchronize();
     for (void* p : b->allocs) (void)hipFree(p);
+    delete b->fwd_lane;
     delete b;
+    return DSP_OK;
+}
+
+int dsp_block_enable_forward_lane(dsp_block* b)
+{
+    DSP_REQUIRE(b, DSP_EINVAL, "dsp_block_enable_forward_lane: null block");
+    DSP_REQUIRE(b->desc.m_k > 0, DSP_EINVAL,
+                "dsp_block_enable_forward_lane: with m_k = 0 the backward reuses the forward's activations");
+    if (b->fwd_lane) return DSP_OK;
+    ForwardLane* ln = new (std::nothrow) ForwardLane();
+    DSP_REQUIRE(ln, DSP_ENOMEM, "dsp_block_enable_forward_lane: out of host memory");
+    const int n = (int)b->layers.size();
+    ln->act.assign(n, nullptr);
+    ln->mean.assign(n, nullptr);
+    ln->invstd.assign(n, nullptr);
+    ln->argmax.assign(n, nullptr);
+    int rc = DSP_OK;
+    for (int i = 0; i < n && rc == DSP_OK; ++i) {
+        const Layer& L = b->layers[i];
+        const Tensor& t = b->T[i];
+        if (L.d.op == DSP_OP_SOFTMAX_CE) continue;
+        rc = dev_alloc(b, &ln->act[i], t.bytes(b->dtype), &b->ws_bytes);
+        if (rc == DSP_OK && L.d.op == DSP_OP_BN) {
+            rc = dev_alloc(b, (void**)&ln->mean[i], (size_t)L.d.cin * 4, &b->ws_bytes);
+            if (rc == DSP_OK) rc = dev_alloc(b, (void**)&ln->invstd[i], (size_t)L.d.cin * 4, &b->ws_bytes);
+        }
+        if (rc == DSP_OK && L.d.op == DSP_OP_MAXPOOL) rc = dev_alloc(b, (void**)&ln->argmax[i], t.elems, &b->ws_bytes);
+    }
+    if (rc == DSP_OK) rc = dev_alloc(b, (void**)&ln->bn_partial, b->bn_partial_elems * 2 * sizeof(double), &b->ws_bytes);
+    if (rc == DSP_OK) rc = dev_alloc(b, (void**)&ln->bn_coef, (size_t)3 * b->bn_max_c * 4, &b->ws_bytes);
+    if (rc != DSP_OK) {
+        delete ln;  // the device buffers stay on the block's list and are freed with it
+        return rc;
+    }
+    b->fwd_lane = ln;
     return DSP_OK;
 }
 
@@ -514,34 +596,81 @@ int dsp_block_input_slot(dsp_block* b, int64_t batch_id, void** d_slot)
     return DSP_OK;
 }
 
+}  // extern "C"
+
+namespace dsp {
+
+// Checks and host-side state of a forward call; stores the input into its ring slot.
+struct ForwardCall {
+    void* slot;
+    float* dz;
+    float* loss;
+};
+static int forward_begin(dsp_block* b, int64_t batch_id, const void* d_in, const int32_t* d_labels, float* d_loss,
+                         hipStream_t st, ForwardCall* fc, const char* who)
+{
+    const int m = b->desc.m_k;
+    DSP_REQUIRE(batch_id == b->next_fwd, DSP_ESTATE, "%s: expected mini-batch %lld, got %lld", who, (long long)b->next_fwd,
+                (long long)batch_id);
+    const int64_t due = batch_id - m;  // backward that must have been done before this forward
+    DSP_REQUIRE(!b->pending && b->next_bwd == (due > 0 ? due : 0), DSP_ESTATE,
+                "%s: the previous tick's backward/update has not been issued", who);
+    DSP_REQUIRE(b->loss_idx < 0 || d_labels, DSP_EINVAL, "%s: the last block needs labels", who);
+    const int slot = (int)(batch_id % b->ring_entries);
+    fc->slot = b->ring + (size_t)slot * b->slot_bytes;
+    fc->dz = b->loss_idx >= 0 ? b->dz_ring + (size_t)(batch_id % (1 + m)) * b->dz_elems : nullptr;
+    fc->loss = d_loss ? d_loss : b->loss_sink;
+    b->slot_version[slot] = b->version;
+    b->next_fwd = batch_id + 1;
+    if (!b->dry && d_in != fc->slot)
+        DSP_HIP(hipMemcpyAsync(fc->slot, d_in, b->input.elems * dtype_size(b->dtype), hipMemcpyDeviceToDevice, st));
+    return DSP_OK;
+}
+
+// Checks and host-side state of a recompute + backward call.
+struct BackwardCall {
+    void* slot;
+    const void* gout;
+};
+static int backward_begin(dsp_block* b, int64_t batch_id, const void* d_grad_out, void* d_grad_in, BackwardCall* bc,
+                          const char* who)
+{
+    const int m = b->desc.m_k;
+    DSP_REQUIRE(!b->pending && batch_id == b->next_bwd && batch_id == b->next_fwd - 1 - m, DSP_ESTATE,
+                "%s: mini-batch %lld is not due (next backward %lld, latest forward %lld, m_k %d)", who, (long long)batch_id,
+                (long long)b->next_bwd, (long long)b->next_fwd - 1, m);
+    DSP_REQUIRE(b->loss_idx >= 0 || d_grad_out, DSP_EINVAL, "%s: no error gradient", who);
+    DSP_REQUIRE(!b->desc.needs_input_grad || d_grad_in, DSP_EINVAL, "%s: no room for G_h", who);
+    const int slot = (int)(batch_id % b->ring_entries);
+    bc->slot = b->ring + (size_t)slot * b->slot_bytes;
+    bc->gout = d_grad_out;
+    if (b->loss_idx >= 0 && !d_grad_out) bc->gout = b->dz_ring + (size_t)(batch_id % (1 + m)) * b->dz_elems;
+    b->next_bwd = batch_id + 1;
+    b->pending = true;
+    return DSP_OK;
+}
+
+}  // namespace dsp
+
+extern "C" {
+
 int dsp_block_forward(dsp_block* b, int64_t batch_id, const void* d_in, void* d_out, const int32_t* d_labels,
                       float* d_loss, void* stream)
 {
     DSP_REQUIRE(b && d_in, DSP_EINVAL, "dsp_block_forward: null argument");
     hipStream_t st = (hipStream_t)stream;
-    const int m = b->desc.m_k;
-    DSP_REQUIRE(batch_id == b->next_fwd, DSP_ESTATE, "dsp_block_forward: expected mini-batch %lld, got %lld",
-                (long long)b->next_fwd, (long long)batch_id);
-    const int64_t due = batch_id - m;  // backward that must have been done before this forward
-    DSP_REQUIRE(!b->pending && b->next_bwd == (due > 0 ? due : 0), DSP_ESTATE,
-                "dsp_block_forward: the previous tick's backward/update has not been issued");
-    DSP_REQUIRE(b->loss_idx < 0 || d_labels, DSP_EINVAL, "dsp_block_forward: the last block needs labels");
-    const int slot = (int)(batch_id % b->ring_entries);
-    void* slot_ptr = b->ring + (size_t)slot * b->slot_bytes;
-    b->slot_version[slot] = b->version;
-    b->next_fwd = batch_id + 1;
+    ForwardCall fc;
+    DSP_TRY(forward_begin(b, batch_id, d_in, d_labels, d_loss, st, &fc, "dsp_block_forward"));
     if (b->dry) return DSP_OK;
-    if (d_in != slot_ptr)
-        DSP_HIP(hipMemcpyAsync(slot_ptr, d_in, b->input.elems * dtype_size(b->dtype), hipMemcpyDeviceToDevice, st));
-    float* dz = b->loss_idx >= 0 ? b->dz_ring + (size_t)(batch_id % (1 + m)) * b->dz_elems : nullptr;
-    float* loss = d_loss ? d_loss : b->loss_sink;
     const Tensor& o = b->T[b->out_idx];
-    if (m == 0) {
+    if (b->desc.m_k == 0) {
         // this forward is also the "recompute" of the backward that follows: keep everything
-        DSP_TRY(run_forward(b, slot_ptr, nullptr, d_labels, loss, dz, st));
+        DSP_TRY(run_forward(b, ForwardPass{nullptr, fc.slot, nullptr}, nullptr, d_labels, fc.loss, fc.dz, st));
         if (d_out) DSP_HIP(hipMemcpyAsync(d_out, o.act, o.bytes(b->dtype), hipMemcpyDeviceToDevice, st));
     } else {
-        DSP_TRY(run_forward(b, slot_ptr, d_out, d_labels, loss, dz, st));
+        // the activations are thrown away (the backward of this mini-batch recomputes them); d_out == nullptr
+        // (a last block whose output nobody takes) leaves the output in the lane's own buffer
+        DSP_TRY(run_forward(b, ForwardPass{b->fwd_lane, fc.slot, d_out}, nullptr, d_labels, fc.loss, fc.dz, st));
     }
     return DSP_OK;
 }
@@ -550,21 +679,37 @@ int dsp_block_recompute_backward(dsp_block* b, int64_t batch_id, const void* d_g
 {
     DSP_REQUIRE(b, DSP_EINVAL, "dsp_block_recompute_backward: null block");
     hipStream_t st = (hipStream_t)stream;
-    const int m = b->desc.m_k;
-    DSP_REQUIRE(!b->pending && batch_id == b->next_bwd && batch_id == b->next_fwd - 1 - m, DSP_ESTATE,
-                "dsp_block_recompute_backward: mini-batch %lld is not due (next backward %lld, latest forward %lld, m_k %d)",
-                (long long)batch_id, (long long)b->next_bwd, (long long)b->next_fwd - 1, m);
-    DSP_REQUIRE(b->loss_idx >= 0 || d_grad_out, DSP_EINVAL, "dsp_block_recompute_backward: no error gradient");
-    DSP_REQUIRE(!b->desc.needs_input_grad || d_grad_in, DSP_EINVAL, "dsp_block_recompute_backward: no room for G_h");
-    const int slot = (int)(batch_id % b->ring_entries);
-    void* slot_ptr = b->ring + (size_t)slot * b->slot_bytes;
-    const void* gout = d_grad_out;
-    if (b->loss_idx >= 0 && !d_grad_out) gout = b->dz_ring + (size_t)(batch_id % (1 + m)) * b->dz_elems;
-    b->next_bwd = batch_id + 1;
-    b->pending = true;
+    BackwardCall bc;
+    DSP_TRY(backward_begin(b, batch_id, d_grad_out, d_grad_in, &bc, "dsp_block_recompute_backward"));
     if (b->dry) return DSP_OK;
-    if (m > 0) DSP_TRY(run_forward(b, slot_ptr, nullptr, nullptr, b->loss_sink, nullptr, st));
-    DSP_TRY(run_backward(b, slot_ptr, gout, d_grad_in, st));
+    if (b->desc.m_k > 0)
+        DSP_TRY(run_forward(b, ForwardPass{nullptr, bc.slot, nullptr}, nullptr, nullptr, b->loss_sink, nullptr, st));
+    DSP_TRY(run_backward(b, bc.slot, bc.gout, d_grad_in, st));
+    return DSP_OK;
+}
+
+int dsp_block_step(dsp_block* b, int64_t batch_fwd, const void* d_in, void* d_out, const int32_t* d_labels, float* d_loss,
+                   int64_t batch_bwd, const void* d_grad_out, void* d_grad_in, void* stream)
+{
+    DSP_REQUIRE(b && d_in, DSP_EINVAL, "dsp_block_step: null argument");
+    hipStream_t st = (hipStream_t)stream;
+    if (b->desc.m_k > 0 && !b->fwd_lane && !b->dry) DSP_TRY(dsp_block_enable_forward_lane(b));
+    ForwardCall fc;
+    BackwardCall bc;
+    DSP_TRY(forward_begin(b, batch_fwd, d_in, d_labels, d_loss, st, &fc, "dsp_block_step"));
+    DSP_TRY(backward_begin(b, batch_bwd, d_grad_out, d_grad_in, &bc, "dsp_block_step"));
+    if (b->dry) return DSP_OK;
+    if (b->desc.m_k == 0) {
+        const Tensor& o = b->T[b->out_idx];
+        DSP_TRY(run_forward(b, ForwardPass{nullptr, fc.slot, nullptr}, nullptr, d_labels, fc.loss, fc.dz, st));
+        if (d_out) DSP_HIP(hipMemcpyAsync(d_out, o.act, o.bytes(b->dtype), hipMemcpyDeviceToDevice, st));
+    } else {
+        // forward of batch_fwd (lane buffers, output to d_out) and recompute of batch_bwd (primary buffers)
+        // in one sweep: the two passes use the same parameters
+        const ForwardPass recompute{nullptr, bc.slot, nullptr};
+        DSP_TRY(run_forward(b, ForwardPass{b->fwd_lane, fc.slot, d_out}, &recompute, d_labels, fc.loss, fc.dz, st));
+    }
+    DSP_TRY(run_backward(b, bc.slot, bc.gout, d_grad_in, st));
     return DSP_OK;
 }
 

@@ -86,8 +86,14 @@ template <typename T, int VW, int MODE, bool RELU>
 __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__ x, const T* __restrict__ dy,
                                                            const T* __restrict__ y, const float* __restrict__ mean,
                                                            const float* __restrict__ invstd, double* __restrict__ part,
-                                                           int64_t M, int C, RowLayout L, int rows_per_block)
+                                                           int64_t M, int C, RowLayout L, int rows_per_block,
+                                                           const T* __restrict__ x1, double* __restrict__ part1)
 {
+    // blockIdx.z = 1: the second instance of a twin launch (other tensor, same shape)
+    if (blockIdx.z) {
+        x = x1;
+        part = part1;
+    }
     __shared__ double red[kThreads][2];
     const int tid = threadIdx.x;
     const int cvi = blockIdx.y * L.cvb + tid % L.cvb;
@@ -158,11 +164,19 @@ __device__ inline double wave_sum(double v)
 }
 
 // One wave per channel merges the partials.  Forward: mean, invstd, coef = {scale, shift}.
-__global__ __launch_bounds__(64) void bn_fwd_finalize_kernel(const double* __restrict__ part, int nblk, int C,
-                                                             double inv_M, float eps, const float* __restrict__ gamma,
-                                                             const float* __restrict__ beta, float* __restrict__ mean,
-                                                             float* __restrict__ invstd, float* __restrict__ coef)
+struct BnStatOut {
+    const double* part;
+    float *mean, *invstd, *coef;
+};
+__global__ __launch_bounds__(64) void bn_fwd_finalize_kernel(BnStatOut o0, BnStatOut o1, int nblk, int C, double inv_M,
+                                                             float eps, const float* __restrict__ gamma,
+                                                             const float* __restrict__ beta)
 {
+    const BnStatOut o = blockIdx.y ? o1 : o0;
+    const double* __restrict__ part = o.part;
+    float* __restrict__ mean = o.mean;
+    float* __restrict__ invstd = o.invstd;
+    float* __restrict__ coef = o.coef;
     const int c = blockIdx.x, lane = threadIdx.x;
     double a = 0.0, b = 0.0;
     for (int k = lane; k < nblk; k += 64) {
@@ -211,12 +225,21 @@ __global__ __launch_bounds__(64) void bn_bwd_finalize_kernel(const double* __res
     }
 }
 
-// y = [relu](scale*x + shift [+ res])
+// y = [relu](scale*x + shift [+ res]); blockIdx.y selects the instance of a twin launch
+struct BnApplyIo {
+    const void* x;
+    const void* res;
+    void* y;
+    const float* coef;
+};
 template <typename T, int VW, bool RELU, bool HAS_RES>
-__global__ __launch_bounds__(kThreads) void bn_fwd_apply_kernel(const T* __restrict__ x, const T* __restrict__ res,
-                                                                T* __restrict__ y, const float* __restrict__ coef,
-                                                                int64_t nvec, int C, int cv)
+__global__ __launch_bounds__(kThreads) void bn_fwd_apply_kernel(BnApplyIo io0, BnApplyIo io1, int64_t nvec, int C, int cv)
 {
+    const BnApplyIo io = blockIdx.y ? io1 : io0;
+    const T* __restrict__ x = (const T*)io.x;
+    const T* __restrict__ res = (const T*)io.res;
+    T* __restrict__ y = (T*)io.y;
+    const float* __restrict__ coef = io.coef;
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * kThreads) {
         const int c0 = (int)(i % cv) * VW;
         float xv[VW], rv[VW], ov[VW];
@@ -283,31 +306,36 @@ inline int apply_grid(int64_t nvec)
 
 template <typename T, int VW>
 int bn_forward_t(const void* x, const void* res, void* y, const float* gamma, const float* beta, float eps, int64_t M,
-                 int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed)
+                 int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed, const BnForwardTwin* tw)
 {
     const RowLayout L = make_layout(C, VW);
     int nblk;
     const int rows = plan_rows(M, L, &nblk);
-    const dim3 grid(nblk, ceil_div(L.cv, L.cvb));
-    const double tensor_bytes = (double)M * C * sizeof(T);
+    const unsigned ni = tw ? 2 : 1;
+    const dim3 grid(nblk, ceil_div(L.cv, L.cvb), ni);
+    const double tensor_bytes = (double)M * C * sizeof(T) * ni;
     if (presummed > 0) {
         nblk = presummed;
     } else {
         ProfScope ps(sizeof(T) == 2 ? "bn_stats<bf16>" : "bn_stats<fp32>", tensor_bytes, 1);
         DSP_LAUNCH(ps, (bn_sums_kernel<T, VW, 0, false>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)nullptr,
-                   (const T*)nullptr, (const float*)nullptr, (const float*)nullptr, buf.partial, M, C, L, rows);
+                   (const T*)nullptr, (const float*)nullptr, (const float*)nullptr, buf.partial, M, C, L, rows,
+                   (const T*)(tw ? tw->x : nullptr), tw ? tw->buf.partial : nullptr);
     }
     {
-        ProfScope ps("bn_fwd_finalize", (double)nblk * C * 16.0, 1);
-        DSP_LAUNCH(ps, bn_fwd_finalize_kernel, dim3(C), dim3(64), 0, st, (const double*)buf.partial, nblk, C,
-                   1.0 / (double)M, eps, gamma, beta, buf.mean, buf.invstd, buf.coef);
+        const BnStatOut o0{buf.partial, buf.mean, buf.invstd, buf.coef};
+        const BnStatOut o1 = tw ? BnStatOut{tw->buf.partial, tw->buf.mean, tw->buf.invstd, tw->buf.coef} : o0;
+        ProfScope ps("bn_fwd_finalize", (double)nblk * C * 16.0 * ni, 1);
+        DSP_LAUNCH(ps, bn_fwd_finalize_kernel, dim3(C, ni), dim3(64), 0, st, o0, o1, nblk, C, 1.0 / (double)M, eps, gamma,
+                   beta);
     }
     const int64_t nvec = M * (C / VW);
-    const dim3 ag(apply_grid(nvec));
+    const dim3 ag(apply_grid(nvec), ni);
+    const BnApplyIo io0{x, res, y, buf.coef};
+    const BnApplyIo io1 = tw ? BnApplyIo{tw->x, tw->res, tw->y, tw->buf.coef} : io0;
     ProfScope ps(sizeof(T) == 2 ? "bn_apply_relu<bf16>" : "bn_apply_relu<fp32>", tensor_bytes * (res ? 3 : 2), 1);
-#define BN_APPLY(R, H)                                                                                          \
-    DSP_LAUNCH(ps, (bn_fwd_apply_kernel<T, VW, R, H>), ag, dim3(kThreads), 0, st, (const T*)x, (const T*)res, \
-               (T*)y, (const float*)buf.coef, nvec, C, L.cv)
+#define BN_APPLY(R, H) \
+    DSP_LAUNCH(ps, (bn_fwd_apply_kernel<T, VW, R, H>), ag, dim3(kThreads), 0, st, io0, io1, nvec, C, L.cv)
     if (relu) {
         if (res) BN_APPLY(true, true); else BN_APPLY(true, false);
     } else {
@@ -330,7 +358,8 @@ int bn_backward_t(const void* dy, const void* x, const void* y, void* dx, void* 
     {
         ProfScope ps(sizeof(T) == 2 ? "bn_bwd_reduce<bf16>" : "bn_bwd_reduce<fp32>", tensor_bytes * (RELU ? 3 : 2), 1);
         DSP_LAUNCH(ps, (bn_sums_kernel<T, VW, 1, RELU>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)dy,
-                   (const T*)y, (const float*)buf.mean, (const float*)buf.invstd, buf.partial, M, C, L, rows);
+                   (const T*)y, (const float*)buf.mean, (const float*)buf.invstd, buf.partial, M, C, L, rows,
+                   (const T*)nullptr, (double*)nullptr);
     }
     {
         ProfScope ps("bn_bwd_finalize", (double)nblk * C * 16.0, 1);
@@ -361,15 +390,19 @@ int bn_backward_t(const void* dy, const void* x, const void* y, void* dx, void* 
 int bn_max_partial_blocks() { return kMaxPartialBlocks; }
 
 int launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
-                      float eps, int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed)
+                      float eps, int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed,
+                      const BnForwardTwin* twin)
 {
     DSP_REQUIRE(M > 0 && C > 0 && presummed >= 0, DSP_EINVAL, "bn: bad shape");
+    if (twin)
+        DSP_REQUIRE(twin->x && twin->y && (twin->res != nullptr) == (res != nullptr), DSP_EINVAL,
+                    "bn forward: incomplete second instance");
     if (dtype == DSP_BF16) {
-        if (C % 8 == 0) return bn_forward_t<bf16_t, 8>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed);
-        return bn_forward_t<bf16_t, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed);
+        if (C % 8 == 0) return bn_forward_t<bf16_t, 8>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin);
+        return bn_forward_t<bf16_t, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin);
     }
-    if (C % 4 == 0) return bn_forward_t<float, 4>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed);
-    return bn_forward_t<float, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed);
+    if (C % 4 == 0) return bn_forward_t<float, 4>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin);
+    return bn_forward_t<float, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin);
 }
 
 int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, void* dx, void* dres,

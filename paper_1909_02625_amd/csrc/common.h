@@ -111,8 +111,16 @@ inline ConvShape make_conv_shape(int N, int H, int W, int Cin, int Cout, int R, 
 // y = conv(x, w);  w in [Cout][R][S][Cin].  With column_sums != nullptr the kernel also writes, per row
 // tile t of y[M][Cout] (conv_forward_row_tiles of them), column_sums[(t*Cout + c)*2 + {0,1}] =
 // {sum y, sum y^2} over the tile's rows of the values as stored -- the statistics a batch norm on y needs.
+// twin != nullptr: the same launch also computes twin->y = conv(twin->x, w) (and twin->column_sums if
+// column_sums is given): the forward pass of the current mini-batch and the recompute of a stale one
+// share their parameters, so one launch per layer serves both.
+struct ConvForwardTwin {
+    const void* x;
+    void* y;
+    double* column_sums;
+};
 int launch_conv_forward(int dtype, const ConvShape& c, const void* x, const void* w, void* y, hipStream_t st,
-                        double* column_sums = nullptr);
+                        double* column_sums = nullptr, const ConvForwardTwin* twin = nullptr);
 int conv_forward_row_tiles(int dtype, const ConvShape& c);
 // dx (+)= conv^T(dy, w);  wt in [Cin][R-1-r][S-1-s][Cout].
 int launch_conv_backward_data(int dtype, const ConvShape& c, const void* dy, const void* wt, void* dx,
@@ -133,8 +141,17 @@ int bn_max_partial_blocks();
 // y = [relu]( gamma * (x - mean) * invstd + beta [+ res] ), statistics over the M rows of x[M][C].
 // presummed > 0: buf.partial already holds that many per-tile column sums of x (written by the
 // convolution that produced x), so the pass that sums x is skipped.
+// twin != nullptr: a second instance (same shape and parameters, its own tensors and statistics
+// buffers) is normalised by the same launches.
+struct BnForwardTwin {
+    const void* x;
+    const void* res;
+    void* y;
+    BnBuffers buf;
+};
 int launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
-                      float eps, int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed = 0);
+                      float eps, int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed = 0,
+                      const BnForwardTwin* twin = nullptr);
 // Backward of the map above given dy and the saved x, y, mean, invstd:
 // dz = dy * [y > 0]; dres (+)= dz; dgamma, dbeta; dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M).
 int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, void* dx, void* dres,

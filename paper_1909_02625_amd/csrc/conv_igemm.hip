@@ -162,6 +162,12 @@ struct GatherGeom {
     // if set: per row tile, the column sums {sum y, sum y^2} of the values as stored, [row tile][Co][2];
     // lets the batch norm that consumes `out` skip its own pass over the tensor
     double* stats;
+    // A launch may carry a second instance of the same problem (same shapes and filters, other
+    // tensors), selected by blockIdx.y: the forward pass of the current mini-batch and the recompute of
+    // a stale one use the same parameters, so each layer serves both with one launch.
+    const void* in1;
+    void* out1;
+    double* stats1;
 };
 
 // 16-byte loads through a buffer descriptor: the hardware returns zeros for any offset at or past
@@ -179,14 +185,17 @@ __device__ inline u32x4 load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
 }
 
 template <typename TL, bool VEC>
-__global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typename TL::T* __restrict__ in,
+__global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typename TL::T* __restrict__ in_,
                                                                     const typename TL::T* __restrict__ wgt,
-                                                                    typename TL::T* __restrict__ out, GatherGeom g)
+                                                                    typename TL::T* __restrict__ out_, GatherGeom g)
 {
     typedef typename TL::T T;
     constexpr int E = TL::E, CPR = TL::CPR, ROWS_PER_PASS = kThreads / CPR;
     constexpr uint32_t SZ = sizeof(T);
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    const T* __restrict__ in = blockIdx.y ? (const T*)g.in1 : in_;
+    T* __restrict__ out = blockIdx.y ? (T*)g.out1 : out_;
+    double* stats = blockIdx.y ? g.stats1 : g.stats;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave / TL::WGN, wave_n = wave % TL::WGN;
@@ -397,7 +406,7 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
             for (int e = 0; e < E && col + e < g.Co; ++e) dst[e] = ((const T*)src)[e];
         }
     }
-    if (g.stats) {
+    if (stats) {
         // column sums of the staged tile (rows past M hold zeros): thread = (row group, column)
         constexpr int G = kThreads / TL::BN;
         const int c = tid % TL::BN, rg = tid / TL::BN;
@@ -418,7 +427,144 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
                 a += sred[(k * TL::BN + c) * 2];
                 b += sred[(k * TL::BN + c) * 2 + 1];
             }
-            double* dst = g.stats + ((int64_t)(blockIdx.x / tiles_n) * g.Co + n0 + c) * 2;
+            double* dst = stats + ((int64_t)(blockIdx.x / tiles_n) * g.Co + n0 + c) * 2;
+            dst[0] = a;
+            dst[1] = b;
+        }
+    }
+}
+
+// ---- fp32 3x3 convolutions with 16 or 32 channels on both sides ----------------------------------
+// With so few channels the whole filter bank of 16 output channels fits in registers (9 * Ci / 16
+// 16-byte runs per lane), so no operand needs LDS: the MFMA computes y^T, D[co][pixel] with
+// A = filters (row co = lane % 16, k-run lane / 16) held for the whole kernel and B = the gathered
+// pixels, one coalesced 16-byte run per lane, tap and 16 channels (16 consecutive pixels = 1 KB per
+// wave load).  Lane (pixel p, quarter q) uses element e of its run in MFMA e, which pairs channel
+// 4q + e on both operands.  The result leaves each lane with 4 consecutive output channels of one
+// pixel: one 16-byte store.  A wave owns one group of 16 output channels and walks groups of 16
+// pixels; the column sums for a following batch norm are accumulated on the way.
+template <int CI16>
+__global__ __launch_bounds__(kThreads) void conv3x3_direct_f32_kernel(const float* __restrict__ in_,
+                                                                      const float* __restrict__ wgt,
+                                                                      float* __restrict__ out_, GatherGeom g)
+{
+    constexpr int TAPS = 9;
+    const float* __restrict__ in = blockIdx.y ? (const float*)g.in1 : in_;
+    float* __restrict__ out = blockIdx.y ? (float*)g.out1 : out_;
+    double* stats = blockIdx.y ? g.stats1 : g.stats;
+    __shared__ double red[4][16][2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, px = lane & 15, kq = lane >> 4;
+    const int cgs = g.Co >> 4;               // groups of 16 output channels (1 or 2)
+    const int cg = wave % cgs, pw = wave / cgs, PW = 4 / cgs;
+    const int groups = (g.M + 15) >> 4;
+
+    f32x4 wreg[TAPS][CI16];
+    {
+        const float* wrow = wgt + (size_t)(cg * 16 + px) * g.Kdim + 4 * kq;
+        if (((uintptr_t)wgt & 15) == 0) {
+#pragma unroll
+            for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+                for (int c = 0; c < CI16; ++c) wreg[t][c] = *(const f32x4*)(wrow + t * g.Ci + c * 16);
+        } else {
+#pragma unroll
+            for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+                for (int c = 0; c < CI16; ++c) {
+                    const float* p = wrow + t * g.Ci + c * 16;
+                    wreg[t][c] = f32x4{p[0], p[1], p[2], p[3]};
+                }
+        }
+    }
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc(in, (uint32_t)g.N * g.Hi * g.Wi * g.Ci * 4u);
+    float s0[4] = {0.f, 0.f, 0.f, 0.f}, s1[4] = {0.f, 0.f, 0.f, 0.f};
+
+    // 16-byte runs of pixel group grp, all taps; a group past the end reads zeros
+    auto gather = [&](f32x4 (&xin)[TAPS][CI16], int grp) {
+        const int m = grp * 16 + px;
+        const bool live = grp < groups && m < g.M;
+        const int wo = m % g.Wo, tq = m / g.Wo, ho = tq % g.Ho, n = tq / g.Ho;
+        const int th0 = ho * g.ostride - g.pad_h, tw0 = wo * g.ostride - g.pad_w;
+        const uint32_t base = (uint32_t)(((n * g.Hi + th0) * g.Wi + tw0) * g.Ci + 4 * kq) * 4u;
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const bool hok = live && th0 + r >= 0 && th0 + r < g.Hi;
+#pragma unroll
+            for (int s2 = 0; s2 < 3; ++s2) {
+                const bool ok = hok && tw0 + s2 >= 0 && tw0 + s2 < g.Wi;
+                const uint32_t off = base + (uint32_t)((r * g.Wi + s2) * g.Ci) * 4u;
+#pragma unroll
+                for (int c = 0; c < CI16; ++c)
+                    xin[r * 3 + s2][c] = __builtin_bit_cast(f32x4, load16(rin, ok ? off + c * 64u : kOutOfRange));
+            }
+        }
+    };
+    auto finish = [&](const f32x4 (&xin)[TAPS][CI16], int grp) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+            for (int c = 0; c < CI16; ++c)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wreg[t][c][e], xin[t][c][e], acc, 0, 0, 0);
+        const int m = grp * 16 + px;
+        if (m < g.M) {
+            float* dst = out + (size_t)m * g.Co + cg * 16 + 4 * kq;
+            if (g.accum) {
+                const f32x4 old = *(const f32x4*)dst;
+                acc += old;
+            }
+            *(f32x4*)dst = acc;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            s0[e] += acc[e];
+            s1[e] += acc[e] * acc[e];
+        }
+    };
+
+    // DEPTH register sets: the pixels of the next DEPTH - 1 groups are in flight while one is multiplied
+    constexpr int DEPTH = CI16 == 1 ? 4 : 2;
+    const int stride_g = gridDim.x * PW;
+    f32x4 xr[DEPTH][TAPS][CI16];
+    int grp = blockIdx.x * PW + pw;
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d)
+        if (grp + d * stride_g < groups) gather(xr[d], grp + d * stride_g);  // all conditions here are wave-uniform
+    while (grp < groups) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            if (grp < groups) {
+                finish(xr[d], grp);
+                if (grp + DEPTH * stride_g < groups) gather(xr[d], grp + DEPTH * stride_g);
+            }
+            grp += stride_g;
+        }
+    }
+    if (stats) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int off = 1; off < 16; off <<= 1) {
+                s0[e] += __shfl_xor(s0[e], off, 64);
+                s1[e] += __shfl_xor(s1[e], off, 64);
+            }
+        if (px == 0)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                red[wave][4 * kq + e][0] = (double)s0[e];
+                red[wave][4 * kq + e][1] = (double)s1[e];
+            }
+        __syncthreads();
+        if (tid < g.Co) {
+            const int c = tid & 15, cgi = tid >> 4;
+            double a = 0.0, b = 0.0;
+            for (int k = 0; k < PW; ++k) {
+                a += red[k * cgs + cgi][c][0];
+                b += red[k * cgs + cgi][c][1];
+            }
+            double* dst = stats + ((int64_t)blockIdx.x * g.Co + tid) * 2;
             dst[0] = a;
             dst[1] = b;
         }
@@ -837,7 +983,8 @@ int run_gather(const GatherGeom& g, const void* in, const void* w, void* out, hi
     }
     {
         ProfScope ps(tile_name<TL, VEC, false>(), flops, 0);
-        DSP_LAUNCH(ps, kern, dim3((unsigned)tiles), dim3(kThreads), TL::LDS_BYTES, st, (const T*)in, (const T*)w, (T*)out, g);
+        DSP_LAUNCH(ps, kern, dim3((unsigned)tiles, g.in1 ? 2 : 1), dim3(kThreads), TL::LDS_BYTES, st, (const T*)in,
+                   (const T*)w, (T*)out, g);
     }
     DSP_HIP(hipGetLastError());
     return DSP_OK;
@@ -875,10 +1022,41 @@ int select_gather_tile(const GatherGeom& g, int* bm)
     return 6;
 }
 
+// The register-resident-filter kernel: fp32, 3x3, 16 gathered channels, 16 or 32 output channels, no
+// dilation, 16-byte aligned activations.  (The kernel also handles 32 gathered channels, but there
+// the per-wave filter load outweighs the saved LDS traffic and the tiled kernel is faster.)
+template <typename T>
+bool direct_eligible(const GatherGeom& g, const void* in, const void* out)
+{
+    return sizeof(T) == 4 && g.R == 3 && g.S == 3 && g.idil == 1 && g.Ci == 16 && (g.Co == 16 || g.Co == 32) &&
+           ((uintptr_t)in % 16) == 0 && ((uintptr_t)out % 16) == 0;
+}
+
+// Workgroups of the direct kernel: two per compute unit unless there are fewer pixel groups.
+inline int direct_grid(const GatherGeom& g)
+{
+    const int per_block = 4 / (g.Co / 16);
+    const int blocks = ceil_div(ceil_div(g.M, 16), per_block);
+    return blocks < 512 ? blocks : 512;
+}
+
 template <typename T>
 int dispatch_gather(GatherGeom g, bool accum, const void* in, const void* w, void* out, hipStream_t st, double flops)
 {
     constexpr int E = 16 / (int)sizeof(T);
+    if (direct_eligible<T>(g, in, out)) {
+        g.accum = accum ? 1 : 0;
+        const dim3 grid(direct_grid(g), g.in1 ? 2 : 1);
+        ProfScope ps(g.Ci == 16 ? "conv3x3_direct<fp32,ci16>" : "conv3x3_direct<fp32,ci32>", flops, 0);
+        if (g.Ci == 16)
+            DSP_LAUNCH(ps, conv3x3_direct_f32_kernel<1>, grid, dim3(kThreads), 0, st, (const float*)in, (const float*)w,
+                       (float*)out, g);
+        else
+            DSP_LAUNCH(ps, conv3x3_direct_f32_kernel<2>, grid, dim3(kThreads), 0, st, (const float*)in, (const float*)w,
+                       (float*)out, g);
+        DSP_HIP(hipGetLastError());
+        return DSP_OK;
+    }
     constexpr int KB = sizeof(T) == 2 ? 128 : 64;  // bytes of k per LDS row: 64 bf16 / 16 floats
     // 16-byte gathers need channel runs of E elements, 16-byte aligned bases and tap masks of 16 bits
     // (tap masks hold up to 32 taps; larger filters take the generic path)
@@ -1057,7 +1235,7 @@ int check_shape(const ConvShape& c)
 
 static GatherGeom forward_geom(const ConvShape& c)
 {
-    GatherGeom g{c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.pad, c.stride, 1, 0, 0, 0, 0, nullptr};
+    GatherGeom g{c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.pad, c.stride, 1, 0, 0, 0, 0, nullptr, nullptr, nullptr, nullptr};
     g.M = c.N * c.Ho * c.Wo;
     g.Kdim = c.R * c.S * c.Cin;
     return g;
@@ -1066,18 +1244,34 @@ static GatherGeom forward_geom(const ConvShape& c)
 int conv_forward_row_tiles(int dtype, const ConvShape& c)
 {
     const GatherGeom g = forward_geom(c);
+    if (dtype == DSP_FP32 && direct_eligible<float>(g, nullptr, nullptr)) return direct_grid(g);
     int bm;
     if (dtype == DSP_BF16) select_gather_tile<bf16_t>(g, &bm); else select_gather_tile<float>(g, &bm);
     return ceil_div(g.M, bm);
 }
 
 int launch_conv_forward(int dtype, const ConvShape& c, const void* x, const void* w, void* y, hipStream_t st,
-                        double* column_sums)
+                        double* column_sums, const ConvForwardTwin* twin)
 {
     DSP_TRY(check_shape(c));
     GatherGeom g = forward_geom(c);
     g.stats = column_sums;
-    const double flops = 2.0 * conv_macs(c);
+    if (twin) {
+        DSP_REQUIRE(twin->x && twin->y && (twin->column_sums != nullptr) == (column_sums != nullptr), DSP_EINVAL,
+                    "conv forward: incomplete second instance");
+        // both instances must take the same kernel path
+        DSP_REQUIRE(((uintptr_t)x % 16 == 0) == ((uintptr_t)twin->x % 16 == 0) &&
+                        ((uintptr_t)y % 16 == 0) == ((uintptr_t)twin->y % 16 == 0),
+                    DSP_EINVAL, "conv forward: the two instances differ in alignment");
+        g.in1 = twin->x;
+        g.out1 = twin->y;
+        g.stats1 = twin->column_sums;
+    }
+    if (column_sums && dtype == DSP_FP32)
+        // the number of row tiles the caller sized column_sums for assumes aligned tensors
+        DSP_REQUIRE(direct_eligible<float>(g, nullptr, nullptr) == direct_eligible<float>(g, x, y), DSP_EINVAL,
+                    "conv forward with column sums: x and y must be 16-byte aligned");
+    const double flops = 2.0 * conv_macs(c) * (twin ? 2 : 1);
     return dtype == DSP_BF16 ? dispatch_gather<bf16_t>(g, false, x, w, y, st, flops)
                              : dispatch_gather<float>(g, false, x, w, y, st, flops);
 }
@@ -1089,7 +1283,7 @@ int launch_conv_backward_data(int dtype, const ConvShape& c, const void* dy, con
     DSP_REQUIRE(c.stride == 1 || c.stride == 2, DSP_EINVAL, "conv backward-data: stride %d unsupported", c.stride);
     // dx[n,hi,wi,ci] = sum_{r',s',co} dy[n, (hi - (R-1-pad) + r')/stride, ...][co] * wt[ci][r'][s'][co]
     GatherGeom g{c.N, c.Ho, c.Wo, c.Cout, c.H, c.W, c.Cin, c.R, c.S, c.R - 1 - c.pad, c.S - 1 - c.pad, 1, c.stride,
-                 0, 0, 0, 0, nullptr};
+                 0, 0, 0, 0, nullptr, nullptr, nullptr, nullptr};
     g.M = c.N * c.H * c.W;
     g.Kdim = c.R * c.S * c.Cout;
     const double flops = 2.0 * conv_macs(c);

@@ -75,6 +75,13 @@ struct dsp_pipeline {
     float lr = 0, momentum = 0, wd = 0;
     std::vector<hipStream_t> streams;
     std::vector<hipEvent_t> done[2];  // done[tau % 2][k]: block k finished tick tau
+    // Forward streams: a block with m_k > 0 runs forward(a) here while its main stream runs
+    // recompute + backward(a - m_k); the update (main stream) waits for both.
+    std::vector<hipStream_t> fstreams;
+    std::vector<hipEvent_t> fdone[2];  // fdone[tau % 2][k]: block k finished the forward pass of tick tau
+    std::vector<char> fwd_split;       // block k uses its forward stream
+    bool use_twin = true;  // forward(a) and recompute(a - m_k) of a block share their launches (dsp_block_step)
+    bool use_fwd_streams = false;  // measured slower on this GPU: a fifth and sixth stream cost more than the overlap gains
     std::vector<hipEvent_t> join;     // graph capture: branch k joins stream 0
     hipEvent_t in_ready = nullptr, in_copied = nullptr, fork = nullptr;
     std::vector<char*> qring;         // Q_k, k >= 1
@@ -194,8 +201,11 @@ int dsp_pipeline_destroy(dsp_pipeline* pl)
     (void)hipDeviceSynchronize();
     drop_graphs(pl);
     for (hipStream_t s : pl->streams) (void)hipStreamDestroy(s);
-    for (int i = 0; i < 2; ++i)
+    for (hipStream_t s : pl->fstreams) (void)hipStreamDestroy(s);
+    for (int i = 0; i < 2; ++i) {
         for (hipEvent_t e : pl->done[i]) (void)hipEventDestroy(e);
+        for (hipEvent_t e : pl->fdone[i]) (void)hipEventDestroy(e);
+    }
     for (hipEvent_t e : pl->join) (void)hipEventDestroy(e);
     if (pl->in_ready) (void)hipEventDestroy(pl->in_ready);
     if (pl->in_copied) (void)hipEventDestroy(pl->in_copied);
@@ -252,10 +262,14 @@ static int pipeline_build(dsp_pipeline* pl, dsp_block* const* blocks)
         hipStream_t s;
         DSP_HIP(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
         pl->streams.push_back(s);
+        DSP_HIP(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+        pl->fstreams.push_back(s);
         for (int i = 0; i < 2; ++i) {
             hipEvent_t e;
             DSP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
             pl->done[i].push_back(e);
+            DSP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+            pl->fdone[i].push_back(e);
         }
         hipEvent_t e;
         DSP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
@@ -292,6 +306,7 @@ static int pipeline_build(dsp_pipeline* pl, dsp_block* const* blocks)
     DSP_HIP(hipMemset(pl->loss_tmp, 0, 16));
     DSP_HIP(hipDeviceSynchronize());
     DSP_HIP(hipGetDevice(&pl->device));
+    pl->fwd_split.assign(K, 0);
     pl->workers.assign(K, nullptr);
     if (!pl->serial)
         for (int k = 1; k < K; ++k) {
@@ -353,6 +368,22 @@ int dsp_pipeline_set_graph_replay(dsp_pipeline* pl, int32_t enable)
     return DSP_OK;
 }
 
+int dsp_pipeline_set_forward_streams(dsp_pipeline* pl, int32_t enable)
+{
+    DSP_REQUIRE(pl, DSP_EINVAL, "dsp_pipeline_set_forward_streams: null pipeline");
+    DSP_REQUIRE(pl->tau == 0, DSP_ESTATE, "dsp_pipeline_set_forward_streams: the pipeline has already been stepped");
+    pl->use_fwd_streams = enable != 0;
+    return DSP_OK;
+}
+
+int dsp_pipeline_set_twin_launches(dsp_pipeline* pl, int32_t enable)
+{
+    DSP_REQUIRE(pl, DSP_EINVAL, "dsp_pipeline_set_twin_launches: null pipeline");
+    pl->use_twin = enable != 0;
+    drop_graphs(pl);  // recorded ticks contain the other kind of launches
+    return DSP_OK;
+}
+
 int dsp_pipeline_set_launch_threads(dsp_pipeline* pl, int32_t enable)
 {
     DSP_REQUIRE(pl, DSP_EINVAL, "dsp_pipeline_set_launch_threads: null pipeline");
@@ -360,50 +391,124 @@ int dsp_pipeline_set_launch_threads(dsp_pipeline* pl, int32_t enable)
     return DSP_OK;
 }
 
-// Forward / backward / update of block k at tick tau on stream st (what a tick consists of).
-static int block_tick(dsp_pipeline* pl, int k, int64_t tau, hipStream_t st, bool do_fwd, bool do_bwd, bool dry = false)
+// The three parts of block k's tick tau.  Forward of mini-batch a = tau - P_k:
+static int tick_forward(dsp_pipeline* pl, int k, int64_t tau, hipStream_t st, bool dry)
 {
     const int K = pl->K;
     const int64_t a = tau - pl->P[k];
     if (a < 0) return DSP_OK;
     dsp_block* b = pl->blocks[k];
-    const int64_t bb = a - pl->m[k];
-    if (do_fwd) {
-        void* in;
-        DSP_TRY(dsp_block_input_slot(b, a, &in));  // block 0: filled by the data source copy of this tick
-        void* out = nullptr;
-        if (k < K - 1) DSP_TRY(dsp_block_input_slot(pl->blocks[k + 1], a, &out));
-        const int32_t* lab = pl->labels + (size_t)(a % pl->label_slots) * pl->N;
-        const bool last = k == K - 1;
-        DSP_TRY(dsp_block_forward(b, a, in, out, last ? lab : nullptr, last ? pl->loss_tmp : nullptr, st));
-        if (last && !dry) DSP_TRY(launch_record_loss(pl->loss_tmp, pl->losses, pl->loss_count, pl->max_ticks + 1, st));
+    void* in;
+    DSP_TRY(dsp_block_input_slot(b, a, &in));  // block 0: filled by the data source copy of this tick
+    void* out = nullptr;
+    if (k < K - 1) DSP_TRY(dsp_block_input_slot(pl->blocks[k + 1], a, &out));
+    const int32_t* lab = pl->labels + (size_t)(a % pl->label_slots) * pl->N;
+    const bool last = k == K - 1;
+    DSP_TRY(dsp_block_forward(b, a, in, out, last ? lab : nullptr, last ? pl->loss_tmp : nullptr, st));
+    if (last && !dry) DSP_TRY(launch_record_loss(pl->loss_tmp, pl->losses, pl->loss_count, pl->max_ticks + 1, st));
+    return DSP_OK;
+}
+
+// recompute + backward of mini-batch a - m_k (nothing while the pipeline fills):
+static int tick_backward(dsp_pipeline* pl, int k, int64_t tau, hipStream_t st, bool* did)
+{
+    const int K = pl->K;
+    const int64_t bb = tau - pl->P[k] - pl->m[k];
+    *did = bb >= 0;
+    if (bb < 0) return DSP_OK;
+    const void* gout = k < K - 1 ? pl->qring[k + 1] + (size_t)(bb % (1 + pl->q[k + 1])) * pl->qslot_bytes[k + 1] : nullptr;
+    void* gin = k > 0 ? pl->qring[k] + (size_t)(bb % (1 + pl->q[k])) * pl->qslot_bytes[k] : nullptr;
+    return dsp_block_recompute_backward(pl->blocks[k], bb, gout, gin, st);
+}
+
+// Both of the above through dsp_block_step (same results, one launch per layer for the two forward
+// sweeps).  *fused = false if the tick has only one of the two parts; nothing is issued then.
+static int tick_step(dsp_pipeline* pl, int k, int64_t tau, hipStream_t st, bool dry, bool* fused)
+{
+    const int K = pl->K;
+    const int64_t a = tau - pl->P[k], bb = a - pl->m[k];
+    *fused = pl->use_twin && pl->m[k] > 0 && bb >= 0;
+    if (!*fused) return DSP_OK;
+    dsp_block* b = pl->blocks[k];
+    void* in;
+    DSP_TRY(dsp_block_input_slot(b, a, &in));
+    void* out = nullptr;
+    if (k < K - 1) DSP_TRY(dsp_block_input_slot(pl->blocks[k + 1], a, &out));
+    const int32_t* lab = pl->labels + (size_t)(a % pl->label_slots) * pl->N;
+    const bool last = k == K - 1;
+    const void* gout = k < K - 1 ? pl->qring[k + 1] + (size_t)(bb % (1 + pl->q[k + 1])) * pl->qslot_bytes[k + 1] : nullptr;
+    void* gin = k > 0 ? pl->qring[k] + (size_t)(bb % (1 + pl->q[k])) * pl->qslot_bytes[k] : nullptr;
+    DSP_TRY(dsp_block_step(b, a, in, out, last ? lab : nullptr, last ? pl->loss_tmp : nullptr, bb, gout, gin, st));
+    if (last && !dry) DSP_TRY(launch_record_loss(pl->loss_tmp, pl->losses, pl->loss_count, pl->max_ticks + 1, st));
+    return DSP_OK;
+}
+
+// and the update that consumes that gradient.
+static int tick_update(dsp_pipeline* pl, int k, hipStream_t st)
+{
+    return dsp_param_update(pl->blocks[k], pl->lr, pl->momentum, pl->wd, st);
+}
+
+// All of it on one stream.
+static int block_tick(dsp_pipeline* pl, int k, int64_t tau, hipStream_t st, bool do_fwd, bool do_bwd, bool dry = false)
+{
+    if (do_fwd && do_bwd) {
+        bool fused;
+        DSP_TRY(tick_step(pl, k, tau, st, dry, &fused));
+        if (fused) return tick_update(pl, k, st);
     }
-    if (do_bwd && bb >= 0) {
-        const void* gout = k < K - 1 ? pl->qring[k + 1] + (size_t)(bb % (1 + pl->q[k + 1])) * pl->qslot_bytes[k + 1] : nullptr;
-        void* gin = k > 0 ? pl->qring[k] + (size_t)(bb % (1 + pl->q[k])) * pl->qslot_bytes[k] : nullptr;
-        DSP_TRY(dsp_block_recompute_backward(b, bb, gout, gin, st));
-        DSP_TRY(dsp_param_update(b, pl->lr, pl->momentum, pl->wd, st));
+    if (do_fwd) DSP_TRY(tick_forward(pl, k, tau, st, dry));
+    if (do_bwd) {
+        bool did;
+        DSP_TRY(tick_backward(pl, k, tau, st, &did));
+        if (did) DSP_TRY(tick_update(pl, k, st));
     }
     return DSP_OK;
 }
 
-// The chain of block k at tick tau, issued kernel by kernel on the block's own stream.
+// The chain of block k at tick tau, issued kernel by kernel on the block's own stream(s).
 static int run_block_tick(dsp_pipeline* pl, int k, int64_t tau)
 {
     const int K = pl->K;
     const int cur = (int)(tau & 1), prev = cur ^ 1;
-    hipStream_t st = pl->streams[k];
+    const bool split = pl->fwd_split[k] != 0;
+    hipStream_t sb = pl->streams[k];
+    hipStream_t sf = split ? pl->fstreams[k] : sb;
     // Neighbours' previous tick: the slots this block reads were written then or earlier, and
     // the slots it writes were last read then or earlier.  (The labels of the mini-batch the
     // last block sees now were copied on stream 0 P_{K-1} >= K-1 ticks ago, which this chain
     // of waits orders; the label ring has P_{K-1}+K slots so a slot is not refilled too early.)
     if (tau > 0) {
-        if (k > 0) DSP_HIP(hipStreamWaitEvent(st, pl->done[prev][k - 1], 0));
-        if (k < K - 1) DSP_HIP(hipStreamWaitEvent(st, pl->done[prev][k + 1], 0));
+        if (k > 0) DSP_HIP(hipStreamWaitEvent(sb, pl->done[prev][k - 1], 0));
+        if (k < K - 1) DSP_HIP(hipStreamWaitEvent(sb, pl->done[prev][k + 1], 0));
+        if (split) {
+            DSP_HIP(hipStreamWaitEvent(sf, pl->done[prev][k], 0));                       // its own last update
+            if (k > 0) DSP_HIP(hipStreamWaitEvent(sf, pl->fdone[prev][k - 1], 0));        // its input
+            if (k < K - 1) DSP_HIP(hipStreamWaitEvent(sf, pl->done[prev][k + 1], 0));     // the slot its output goes to
+        }
     }
-    if (pl->delay_us[k] > 0) DSP_TRY(launch_spin(pl->delay_us[k], st));
-    DSP_TRY(block_tick(pl, k, tau, st, true, true));
-    DSP_HIP(hipEventRecord(pl->done[cur][k], st));
+    if (split && k == 0) DSP_HIP(hipStreamWaitEvent(sf, pl->in_copied, 0));  // the mini-batch of this tick
+    if (pl->delay_us[k] > 0) {
+        DSP_TRY(launch_spin(pl->delay_us[k], sb));
+        if (split) DSP_TRY(launch_spin(pl->delay_us[k], sf));
+    }
+    if (!split) {
+        DSP_TRY(block_tick(pl, k, tau, sb, true, true));
+        DSP_HIP(hipEventRecord(pl->fdone[cur][k], sb));
+        DSP_HIP(hipEventRecord(pl->done[cur][k], sb));
+        return DSP_OK;
+    }
+    DSP_TRY(tick_forward(pl, k, tau, sf, false));
+    DSP_HIP(hipEventRecord(pl->fdone[cur][k], sf));
+    bool did;
+    DSP_TRY(tick_backward(pl, k, tau, sb, &did));
+    if (did) {
+        if (split) DSP_HIP(hipStreamWaitEvent(sb, pl->fdone[cur][k], 0));  // the forward pass has read the parameters
+        DSP_TRY(tick_update(pl, k, sb));
+    } else if (split) {
+        DSP_HIP(hipStreamWaitEvent(sb, pl->fdone[cur][k], 0));  // keep done[cur][k] meaning "everything of this tick"
+    }
+    DSP_HIP(hipEventRecord(pl->done[cur][k], sb));
     return DSP_OK;
 }
 
@@ -471,6 +576,12 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
     hipStream_t user = (hipStream_t)stream;
     hipStream_t s0 = pl->streams[0];
 
+    if (tau == 0 && pl->use_fwd_streams && !pl->serial)
+        for (int k = 0; k < K; ++k)
+            if (pl->m[k] > 0) {
+                DSP_TRY(dsp_block_enable_forward_lane(pl->blocks[k]));
+                pl->fwd_split[k] = 1;
+            }
     const bool graph_tick = pl->use_graphs && pl->period > 0 && !g_profile_on && tau > pl->fill;
     const int phase = graph_tick ? (int)(tau % pl->period) : 0;
 
@@ -522,7 +633,10 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
             DSP_TRY(rc);
         }
         DSP_HIP(hipGraphLaunch(pl->graphs[phase], s0));
-        for (int k = 0; k < K; ++k) DSP_HIP(hipEventRecord(pl->done[cur][k], s0));
+        for (int k = 0; k < K; ++k) {
+            DSP_HIP(hipEventRecord(pl->done[cur][k], s0));
+            DSP_HIP(hipEventRecord(pl->fdone[cur][k], s0));
+        }
     }
     pl->tau = tau + 1;
 
@@ -531,7 +645,7 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
     if (h_loss) {
         *h_loss = 0.f;
         if (a_last >= 0) {
-            hipStream_t sl = (pl->serial || graph_tick) ? s0 : pl->streams[K - 1];
+            hipStream_t sl = (pl->serial || graph_tick) ? s0 : (pl->fwd_split[K - 1] ? pl->fstreams[K - 1] : pl->streams[K - 1]);
             DSP_HIP(hipStreamSynchronize(sl));
             DSP_HIP(hipMemcpy(h_loss, pl->losses + a_last, 4, hipMemcpyDeviceToHost));
         }
@@ -543,6 +657,7 @@ int dsp_pipeline_sync(dsp_pipeline* pl)
 {
     DSP_REQUIRE(pl, DSP_EINVAL, "dsp_pipeline_sync: null pipeline");
     for (hipStream_t s : pl->streams) DSP_HIP(hipStreamSynchronize(s));
+    for (hipStream_t s : pl->fstreams) DSP_HIP(hipStreamSynchronize(s));
     return DSP_OK;
 }
 

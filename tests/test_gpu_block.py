@@ -280,14 +280,20 @@ def _manual_schedule(cfg, params, batches, dtype):
     ("resnet20", D.DSP_FP32, 12, {"batch": 4, "hw": 8, "p": (2, 2, 0), "m": (6, 3, 0)}),   # p = 2: deeper queues
     ("resnet20", D.DSP_FP32, 12, {"batch": 4, "hw": 8, "p": (1, 1, 0), "m": (7, 3, 1)}),   # q_1 = 3, stale last block
 ], ids=lambda v: v if isinstance(v, str) else None)
-def test_pipeline_equals_manual_fifo_schedule_bit_for_bit(name, dtype, ticks, kw):
+@pytest.mark.parametrize("mode", ["twin", "separate", "forward_streams"])
+def test_pipeline_equals_manual_fifo_schedule_bit_for_bit(name, dtype, ticks, kw, mode):
     """Ring-slot indexing, the fused M/P ring, the Q rings, the label ring and the cross-stream ordering
-    are integer work: the K-stream pipeline must give exactly the bits of a serial FIFO-queue schedule."""
+    are integer work: the K-stream pipeline must give exactly the bits of a serial FIFO-queue schedule
+    issued through the separate forward / recompute_backward / update calls -- whether the pipeline
+    shares the launches of the two forward sweeps of a tick (the default), issues them separately, or
+    runs the forward sweep on a stream of its own."""
     cfg, params, rng = _setup(name, **kw)
     batches = [make_batch(rng, cfg["input"], cfg["classes"]) for _ in range(ticks)]
     ref_losses, ref_params = _manual_schedule(cfg, params, batches, dtype)
     blocks = build_gpu_blocks(cfg, params, dtype)
     pl = D.dsp_pipeline_init(blocks, cfg["p"], cfg["m"], cfg["lr"], cfg["beta"], cfg["wd"], ticks)
+    D.dsp_pipeline_set_twin_launches(pl, mode == "twin")
+    D.dsp_pipeline_set_forward_streams(pl, mode == "forward_streams")
     try:
         for x, y in batches:
             D.dsp_pipeline_step(pl, to_dev(x, dtype), torch.from_numpy(y).cuda())

@@ -23,6 +23,9 @@ SHAPES = [
     (1, 5, 5, 24, 40, 3, 3, 1, 1),      # channel counts that are no power of two
     (4, 13, 13, 16, 16, 3, 3, 2, 1),    # 16 -> 16 channels, stride 2, several slices with a ragged tail
     (2, 11, 11, 16, 16, 1, 1, 1, 0),    # 16 -> 16 channels, 1x1
+    (3, 10, 10, 32, 32, 3, 3, 1, 1),    # 32 -> 32 channels: register-resident filters, two channel groups
+    (2, 9, 9, 32, 16, 3, 3, 1, 1),      # 32 -> 16
+    (33, 32, 32, 16, 16, 3, 3, 1, 1),   # enough pixel groups that each wave walks several of them
 ]
 
 
