@@ -1001,27 +1001,6 @@ constexpr int64_t kEnoughTiles = 384;
 
 inline int64_t tile_count(const GatherGeom& g, int bm, int bn) { return (int64_t)ceil_div(g.M, bm) * ceil_div(g.Co, bn); }
 
-// Largest tile of the channel class that still yields enough workgroups, else the smallest.
-// Returns the tile id used by dispatch_gather and the tile's row count.
-template <typename T>
-int select_gather_tile(const GatherGeom& g, int* bm)
-{
-    if (g.Co <= 16) {
-        if (tile_count(g, 256, 16) >= kEnoughTiles) { *bm = 256; return 0; }
-        *bm = 64;
-        return 1;
-    }
-    if (g.Co <= 32) {
-        if (tile_count(g, 256, 32) >= kEnoughTiles) { *bm = 256; return 2; }
-        *bm = 128;
-        return 3;
-    }
-    if (g.Co % 128 == 0 && tile_count(g, 128, 128) >= kEnoughTiles) { *bm = 128; return 4; }
-    if (tile_count(g, 128, 64) >= kEnoughTiles) { *bm = 128; return 5; }
-    *bm = 64;
-    return 6;
-}
-
 // The register-resident-filter kernel: fp32, 3x3, 16 gathered channels, 16 or 32 output channels, no
 // dilation, 16-byte aligned activations.  (The kernel also handles 32 gathered channels, but there
 // the per-wave filter load outweighs the saved LDS traffic and the tiled kernel is faster.)
@@ -1038,6 +1017,31 @@ inline int direct_grid(const GatherGeom& g)
     const int per_block = 4 / (g.Co / 16);
     const int blocks = ceil_div(ceil_div(g.M, 16), per_block);
     return blocks < 512 ? blocks : 512;
+}
+
+// Largest tile of the channel class that still yields enough workgroups; for small problems (the
+// CIFAR-sized layers) small tiles with long k steps: there the kernel is bound by the latency of the
+// gathers, and what helps is many workgroups with many bytes in flight each.
+// Returns the tile id used by dispatch_gather and the tile's row count.
+template <typename T>
+int select_gather_tile(const GatherGeom& g, int* bm)
+{
+    if (g.Co <= 16) {
+        if (tile_count(g, 256, 16) >= kEnoughTiles) { *bm = 256; return 0; }
+        *bm = 64;
+        return 1;
+    }
+    if (g.Co <= 32) {
+        if (tile_count(g, 256, 32) >= kEnoughTiles) { *bm = 256; return 2; }
+        if (tile_count(g, 128, 32) >= kEnoughTiles) { *bm = 128; return 3; }
+        *bm = 64;
+        return 7;
+    }
+    if (g.Co % 128 == 0 && tile_count(g, 128, 128) >= kEnoughTiles) { *bm = 128; return 4; }
+    if (tile_count(g, 128, 64) >= kEnoughTiles) { *bm = 128; return 5; }
+    if (tile_count(g, 64, 64) >= kEnoughTiles) { *bm = 64; return 6; }
+    *bm = 32;
+    return 8;
 }
 
 template <typename T>
@@ -1057,7 +1061,7 @@ int dispatch_gather(GatherGeom g, bool accum, const void* in, const void* w, voi
         DSP_HIP(hipGetLastError());
         return DSP_OK;
     }
-    constexpr int KB = sizeof(T) == 2 ? 128 : 64;  // bytes of k per LDS row: 64 bf16 / 16 floats
+    constexpr int KB = 128;  // bytes of k per LDS row of the large tiles: 64 bf16 / 32 floats
     // 16-byte gathers need channel runs of E elements, 16-byte aligned bases and tap masks of 16 bits
     // (tap masks hold up to 32 taps; larger filters take the generic path)
     const bool vec = (g.Ci % E) == 0 && ((uintptr_t)in % 16) == 0 && ((uintptr_t)w % 16) == 0 && g.R * g.S <= 32;
@@ -1068,10 +1072,12 @@ int dispatch_gather(GatherGeom g, bool accum, const void* in, const void* w, voi
     case 0: return run_gather_v<Tile<T, 16, 4, 1, 4, 1, 64, 2>>(g, vec, in, w, out, st, flops);
     case 1: return run_gather_v<Tile<T, 16, 4, 1, 1, 1, 64, 2>>(g, vec, in, w, out, st, flops);
     case 2: return run_gather_v<Tile<T, 32, 4, 1, 2, 1, 64, 2>>(g, vec, in, w, out, st, flops);
-    case 3: return run_gather_v<Tile<T, 32, 4, 1, 1, 1, 64, 2>>(g, vec, in, w, out, st, flops);
+    case 3: return run_gather_v<Tile<T, 32, 4, 1, 1, 1, 128, 2>>(g, vec, in, w, out, st, flops);
     case 4: return run_gather_v<Tile<T, 32, 2, 2, 2, 2, KB, 2>>(g, vec, in, w, out, st, flops);
     case 5: return run_gather_v<Tile<T, 32, 2, 2, 2, 1, KB, 2>>(g, vec, in, w, out, st, flops);
-    default: return run_gather_v<Tile<T, 32, 2, 2, 1, 1, KB, 2>>(g, vec, in, w, out, st, flops);
+    case 6: return run_gather_v<Tile<T, 32, 2, 2, 1, 1, KB, 2>>(g, vec, in, w, out, st, flops);
+    case 7: return run_gather_v<Tile<T, 16, 4, 1, 1, 2, 128, 2>>(g, vec, in, w, out, st, flops);
+    default: return run_gather_v<Tile<T, 16, 2, 2, 1, 1, 256, 2>>(g, vec, in, w, out, st, flops);
     }
 }
 
