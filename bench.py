@@ -84,10 +84,11 @@ class Workload:
             D.dsp_pipeline_step(self.pl, x, y)
         else:  # a lone mid-network block fed with an external error gradient
             b, m = self.blocks[0], cfg["m"][0]
-            D.dsp_block_forward(b, self.tick, x, self.out)
             if self.tick - m >= 0:
-                D.dsp_block_recompute_backward(b, self.tick - m, g, self.gin)
+                D.dsp_block_step(b, self.tick, x, self.out, None, None, self.tick - m, g, self.gin)
                 D.dsp_param_update(b, cfg["lr"], cfg["beta"], cfg["wd"])
+            else:
+                D.dsp_block_forward(b, self.tick, x, self.out)
         self.tick += 1
 
     def sync(self):
@@ -136,6 +137,32 @@ def cpu_baseline(name, batch, seconds):
                       % (steady, fill, name, cfg["input"][0])}
 
 
+def hbm_traffic(workload, dtype_name, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload, or None.
+
+    The summary holds one line "TRAFFIC <kernel> <fetch bytes> <write bytes>" per kernel: FETCH_SIZE and
+    WRITE_SIZE per dispatch, each scaled by what the same counter reads for a copy kernel of known size.
+    """
+    path = os.path.join(ROOT, "profiles", "rocprofv3_pmc_hbm_traffic_%s_%s_pipeline_tick.txt" % (workload, dtype_name))
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) == 4 and f[0] == "TRAFFIC" and f[1] == kernel:
+            return float(f[2]) + float(f[3])
+    return None
+
+
+def calibration_copy(torch):
+    """A plain copy of known size (64 MiB read, 64 MiB written), outside the timed region: the reference
+    that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters when this script runs under --pmc."""
+    src = torch.ones(16 << 20, device="cuda", dtype=torch.float32)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -149,6 +176,7 @@ def main():
         print("bench.py: no GPU", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    calibration_copy(torch)
     total_ticks = a.warmup + a.steps + a.profile_steps + 4
     w = Workload(a.workload, a.dtype, a.batch, total_ticks)
     for _ in range(a.warmup):
@@ -188,13 +216,13 @@ def main():
         if dom["unit_kind"] == "flop":
             ach = dom["units"] / (dom["ms"] * 1e-3) / 1e12
             roof = {"bound": "mfma", "kernel": dom["name"], "achieved": round(ach, 3), "peak": peak, "unit": "TFLOP/s",
-                    "frac": round(ach / peak, 4), "traffic": None,
+                    "frac": round(ach / peak, 4), "traffic": hbm_traffic(a.workload, w.dtype_name, dom["name"]),
                     "avg_launch_us": round(1e3 * dom["ms"] / dom["launches"], 2),
                     "flop_per_launch": dom["units"] / dom["launches"]}
         else:
             ach = dom["units"] / (dom["ms"] * 1e-3) / 1e9
             roof = {"bound": "hbm", "kernel": dom["name"], "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None,
+                    "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": hbm_traffic(a.workload, w.dtype_name, dom["name"]),
                     "avg_launch_us": round(1e3 * dom["ms"] / dom["launches"], 2),
                     "bytes_per_launch": dom["units"] / dom["launches"]}
     w.close()

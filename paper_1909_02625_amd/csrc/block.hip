@@ -17,6 +17,7 @@
 #include <map>
 #include <new>
 #include <string>
+#include <mutex>
 #include <vector>
 
 #include "common.h"
@@ -53,8 +54,11 @@ struct ProfAgg {
 std::vector<ProfAgg> g_prof_result;
 }  // namespace
 
+std::mutex g_prof_mu;  // launches come from one host thread per block
+
 void ProfScope::begin(const char* name, double units, int unit_kind)
 {
+    std::lock_guard<std::mutex> lock(g_prof_mu);
     if (g_prof_recs.size() >= g_prof_capacity) return;  // profile full: later launches go untimed
     const size_t slot = g_prof_recs.size();
     g_prof_recs.push_back({name, units, unit_kind});

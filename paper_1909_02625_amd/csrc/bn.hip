@@ -114,24 +114,33 @@ __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__
     const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
     const int64_t r_end = r_begin + rows_per_block < M ? r_begin + rows_per_block : M;
     if (active) {
-        for (int64_t r = r_begin + rlane; r < r_end; r += L.rl) {
-            float xv[VW];
-            VecIO<T, VW>::load(x + r * C + c0, xv);
-            if (MODE == 0) {
+        // U rows per trip with all their loads issued before the first add: the loop is bound by load
+        // latency, not by bandwidth, unless several rows are in flight per thread
+        constexpr int U = 4;
+        for (int64_t r = r_begin + rlane; r < r_end; r += (int64_t)U * L.rl) {
+            float xv[U][VW], gv[U][VW], yv[U][VW];
 #pragma unroll
-                for (int i = 0; i < VW; ++i) {
-                    s0[i] += (double)xv[i];
-                    s1[i] += (double)xv[i] * (double)xv[i];
+            for (int u = 0; u < U; ++u) {
+                const int64_t ru = r + (int64_t)u * L.rl;
+                if (ru < r_end) {
+                    VecIO<T, VW>::load(x + ru * C + c0, xv[u]);
+                    if (MODE == 1) VecIO<T, VW>::load(dy + ru * C + c0, gv[u]);
+                    if (MODE == 1 && RELU) VecIO<T, VW>::load(y + ru * C + c0, yv[u]);
                 }
-            } else {
-                float gv[VW], yv[VW];
-                VecIO<T, VW>::load(dy + r * C + c0, gv);
-                if (RELU) VecIO<T, VW>::load(y + r * C + c0, yv);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (r + (int64_t)u * L.rl >= r_end) break;
 #pragma unroll
                 for (int i = 0; i < VW; ++i) {
-                    const float dz = (!RELU || yv[i] > 0.f) ? gv[i] : 0.f;
-                    s0[i] += (double)dz;
-                    s1[i] += (double)(dz * ((xv[i] - mu[i]) * is[i]));
+                    if (MODE == 0) {
+                        s0[i] += (double)xv[u][i];
+                        s1[i] += (double)xv[u][i] * (double)xv[u][i];
+                    } else {
+                        const float dz = (!RELU || yv[u][i] > 0.f) ? gv[u][i] : 0.f;
+                        s0[i] += (double)dz;
+                        s1[i] += (double)(dz * ((xv[u][i] - mu[i]) * is[i]));
+                    }
                 }
             }
         }
@@ -285,8 +294,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(const T* __restr
 
 int plan_rows(int64_t M, const RowLayout& L, int* nblk)
 {
-    // every thread should see >= 8 rows; at most kMaxPartialBlocks workgroups
-    int64_t rows = (int64_t)L.rl * 8;
+    // every thread should see >= 4 rows (one trip of the summing loop); at most kMaxPartialBlocks workgroups
+    int64_t rows = (int64_t)L.rl * 4;
     int64_t blocks = (M + rows - 1) / rows;
     if (blocks > kMaxPartialBlocks) {
         blocks = kMaxPartialBlocks;

@@ -74,15 +74,27 @@ __global__ void maxpool_bwd_kernel(const T* __restrict__ dy, const uint8_t* __re
 }
 
 // ---- global average pool ------------------------------------------------------------------------
+// y[n][c] = mean over the HW positions of x[n][.][c].  A workgroup owns one image and up to 256
+// channels; CW threads cover the channels (coalesced rows), 256 / CW thread rows split the positions
+// and are added in row order.
 template <typename T>
-__global__ void gap_fwd_kernel(const T* __restrict__ x, float* __restrict__ y, int N, int HW, int C)
+__global__ __launch_bounds__(kThreads) void gap_fwd_kernel(const T* __restrict__ x, float* __restrict__ y, int N, int HW,
+                                                           int C, int cw)
 {
-    const int i = blockIdx.x * kThreads + threadIdx.x;
-    if (i >= N * C) return;
-    const int n = i / C, c = i % C;
+    __shared__ float red[kThreads];
+    const int n = blockIdx.x, c = blockIdx.y * cw + threadIdx.x % cw, row = threadIdx.x / cw, rows = kThreads / cw;
     float s = 0.f;
-    for (int p = 0; p < HW; ++p) s += to_float<T>(x[((int64_t)n * HW + p) * C + c]);
-    y[i] = s / (float)HW;
+    if (c < C && row < rows) {
+        const T* src = x + (int64_t)n * HW * C + c;
+#pragma unroll 8
+        for (int p = row; p < HW; p += rows) s += to_float<T>(src[(int64_t)p * C]);
+    }
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (row == 0 && c < C) {
+        for (int k = 1; k < rows; ++k) s += red[k * cw + threadIdx.x];
+        y[n * C + c] = s / (float)HW;
+    }
 }
 
 template <typename T, bool ACC>
@@ -98,15 +110,21 @@ __global__ void gap_bwd_kernel(const float* __restrict__ dy, T* __restrict__ dx,
 }
 
 // ---- linear head (fp32) ----------------------------------------------------------------------------
-__global__ void linear_fwd_kernel(const float* __restrict__ x, const float* __restrict__ w,
-                                  const float* __restrict__ bias, float* __restrict__ z, int N, int Cin, int Cout)
+// z[n][j] = sum_c x[n][c] w[j][c] + bias[j]: one wave per output, lanes stride over c, fixed shuffle tree.
+__global__ __launch_bounds__(kThreads) void linear_fwd_kernel(const float* __restrict__ x, const float* __restrict__ w,
+                                                              const float* __restrict__ bias, float* __restrict__ z, int N,
+                                                              int Cin, int Cout)
 {
-    const int i = blockIdx.x * kThreads + threadIdx.x;
-    if (i >= N * Cout) return;
-    const int n = i / Cout, j = i % Cout;
+    const int lane = threadIdx.x & 63;
+    const int64_t o = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (o >= (int64_t)N * Cout) return;
+    const int n = (int)(o / Cout), j = (int)(o % Cout);
     float s = 0.f;
-    for (int c = 0; c < Cin; ++c) s += x[n * Cin + c] * w[j * Cin + c];
-    z[i] = s + bias[j];
+#pragma unroll 4
+    for (int c = lane; c < Cin; c += 64) s += x[n * Cin + c] * w[j * Cin + c];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
+    if (lane == 0) z[o] = s + bias[j];
 }
 
 // dx[n][c] = sum_j dz[n][j] w[j][c]
@@ -121,20 +139,30 @@ __global__ void linear_bwd_x_kernel(const float* __restrict__ dz, const float* _
     dx[i] = s;
 }
 
-// dw[j][c] = sum_n dz[n][j] x[n][c];  dbias[j] = sum_n dz[n][j]
-__global__ void linear_bwd_w_kernel(const float* __restrict__ dz, const float* __restrict__ x, float* __restrict__ dw,
-                                    float* __restrict__ dbias, int N, int Cin, int Cout)
+// dw[j][c] = sum_n dz[n][j] x[n][c];  dbias[j] = sum_n dz[n][j] (column c == Cin).
+// A workgroup owns one j and up to cw columns; 256 / cw thread rows split the samples and are
+// added in row order.
+__global__ __launch_bounds__(kThreads) void linear_bwd_w_kernel(const float* __restrict__ dz, const float* __restrict__ x,
+                                                                float* __restrict__ dw, float* __restrict__ dbias, int N,
+                                                                int Cin, int Cout, int cw)
 {
-    const int i = blockIdx.x * kThreads + threadIdx.x;
-    if (i >= Cout * (Cin + 1)) return;
-    const int j = i / (Cin + 1), c = i % (Cin + 1);
+    __shared__ float red[kThreads];
+    const int j = blockIdx.x, c = blockIdx.y * cw + threadIdx.x % cw, row = threadIdx.x / cw, rows = kThreads / cw;
     float s = 0.f;
-    if (c < Cin) {
-        for (int n = 0; n < N; ++n) s += dz[n * Cout + j] * x[n * Cin + c];
-        dw[j * Cin + c] = s;
-    } else {
-        for (int n = 0; n < N; ++n) s += dz[n * Cout + j];
-        dbias[j] = s;
+    if (c <= Cin && row < rows) {
+        if (c < Cin) {
+#pragma unroll 8
+            for (int n = row; n < N; n += rows) s += dz[n * Cout + j] * x[n * Cin + c];
+        } else {
+#pragma unroll 8
+            for (int n = row; n < N; n += rows) s += dz[n * Cout + j];
+        }
+    }
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (row == 0 && c <= Cin) {
+        for (int k = 1; k < rows; ++k) s += red[k * cw + threadIdx.x];
+        if (c < Cin) dw[j * Cin + c] = s; else dbias[j] = s;
     }
 }
 
@@ -243,13 +271,22 @@ int launch_maxpool_backward(int dtype, const void* dy, const uint8_t* argmax, vo
     return DSP_OK;
 }
 
+// Threads that cover the channel (column) axis of a 256-thread workgroup: a power of two <= 256.
+static int column_threads(int columns)
+{
+    int cw = 1;
+    while (cw < columns && cw < kThreads) cw *= 2;
+    return cw;
+}
+
 int launch_gap_forward(int dtype, const void* x, float* y, int N, int HW, int C, hipStream_t st)
 {
-    const dim3 grid(ceil_div((int64_t)N * C, kThreads));
+    const int cw = column_threads(C);
+    const dim3 grid(N, ceil_div(C, cw));
     if (dtype == DSP_BF16)
-        hipLaunchKernelGGL(gap_fwd_kernel<bf16_t>, grid, dim3(kThreads), 0, st, (const bf16_t*)x, y, N, HW, C);
+        hipLaunchKernelGGL(gap_fwd_kernel<bf16_t>, grid, dim3(kThreads), 0, st, (const bf16_t*)x, y, N, HW, C, cw);
     else
-        hipLaunchKernelGGL(gap_fwd_kernel<float>, grid, dim3(kThreads), 0, st, (const float*)x, y, N, HW, C);
+        hipLaunchKernelGGL(gap_fwd_kernel<float>, grid, dim3(kThreads), 0, st, (const float*)x, y, N, HW, C, cw);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }
@@ -269,8 +306,8 @@ int launch_gap_backward(int dtype, const float* dy, void* dx, bool accumulate, i
 int launch_linear_forward(const float* x, const float* w, const float* bias, float* z, int N, int Cin, int Cout,
                           hipStream_t st)
 {
-    hipLaunchKernelGGL(linear_fwd_kernel, dim3(ceil_div((int64_t)N * Cout, kThreads)), dim3(kThreads), 0, st, x, w, bias,
-                       z, N, Cin, Cout);
+    hipLaunchKernelGGL(linear_fwd_kernel, dim3(ceil_div((int64_t)N * Cout, kThreads / 64)), dim3(kThreads), 0, st, x, w,
+                       bias, z, N, Cin, Cout);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }
@@ -281,8 +318,9 @@ int launch_linear_backward(const float* x, const float* w, const float* dz, floa
     if (dx)
         hipLaunchKernelGGL(linear_bwd_x_kernel, dim3(ceil_div((int64_t)N * Cin, kThreads)), dim3(kThreads), 0, st, dz, w,
                            dx, N, Cin, Cout);
-    hipLaunchKernelGGL(linear_bwd_w_kernel, dim3(ceil_div((int64_t)Cout * (Cin + 1), kThreads)), dim3(kThreads), 0, st,
-                       dz, x, dw, dbias, N, Cin, Cout);
+    const int cw = column_threads(Cin + 1);
+    hipLaunchKernelGGL(linear_bwd_w_kernel, dim3(Cout, ceil_div(Cin + 1, cw)), dim3(kThreads), 0, st, dz, x, dw, dbias, N,
+                       Cin, Cout, cw);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }

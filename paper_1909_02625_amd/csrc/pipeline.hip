@@ -512,14 +512,14 @@ static int run_block_tick(dsp_pipeline* pl, int k, int64_t tau)
     return DSP_OK;
 }
 
-// All K block chains of tick tau: kernel by kernel (one stream and, unless a profile is being taken,
-// one host thread per block), or recorded into a graph capture.
+// All K block chains of tick tau: kernel by kernel (one stream and one host thread per block), or
+// recorded into a graph capture.
 static int issue_tick(dsp_pipeline* pl, int64_t tau, bool capturing)
 {
     const int K = pl->K;
     hipStream_t s0 = pl->streams[0];
     if (!capturing) {
-        const bool threads = pl->use_threads && K > 1 && !g_profile_on;
+        const bool threads = pl->use_threads && K > 1;
         if (threads)
             for (int k = 1; k < K; ++k) {
                 Worker* w = pl->workers[k];
