@@ -184,6 +184,16 @@ __device__ inline u32x4 load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
     return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0));
 }
 
+// Workgroups are handed to the 8 XCDs round-robin by workgroup id, and each XCD has an L2 of its own.
+// Neighbouring tiles share input rows (halo rows, the rows a sweep over the output channels re-reads,
+// the m slice all column tiles of a backward-weight read), so they should meet in one L2: logical
+// tile = the position of this workgroup among the workgroups of its XCD, XCD by XCD.
+__device__ inline unsigned xcd_tile(unsigned b, unsigned nb)
+{
+    const unsigned q = nb / 8, r = nb % 8, xcd = b % 8, idx = b / 8;
+    return xcd * q + (xcd < r ? xcd : r) + idx;
+}
+
 template <typename TL, bool VEC>
 __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typename TL::T* __restrict__ in_,
                                                                     const typename TL::T* __restrict__ wgt,
@@ -201,7 +211,8 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
     const int wave_m = wave / TL::WGN, wave_n = wave % TL::WGN;
     // consecutive workgroups share the same rows of `in` and sweep the output channels
     const int tiles_n = (g.Co + TL::BN - 1) / TL::BN;
-    const int m0 = (blockIdx.x / tiles_n) * TL::BM, n0 = (blockIdx.x % tiles_n) * TL::BN;
+    const unsigned tile = xcd_tile(blockIdx.x, gridDim.x);
+    const int m0 = (tile / tiles_n) * TL::BM, n0 = (tile % tiles_n) * TL::BN;
 
     const int kc = tid % CPR;    // which 16-byte run of the k tile this thread moves
     const int row0 = tid / CPR;  // first tile row it moves; further rows are +ROWS_PER_PASS apart
@@ -427,7 +438,7 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
                 a += sred[(k * TL::BN + c) * 2];
                 b += sred[(k * TL::BN + c) * 2 + 1];
             }
-            double* dst = stats + ((int64_t)(blockIdx.x / tiles_n) * g.Co + n0 + c) * 2;
+            double* dst = stats + ((int64_t)(tile / tiles_n) * g.Co + n0 + c) * 2;
             dst[0] = a;
             dst[1] = b;
         }
@@ -528,7 +539,8 @@ __global__ __launch_bounds__(kThreads) void conv3x3_direct_f32_kernel(const floa
     constexpr int DEPTH = CI16 == 1 ? 4 : 2;
     const int stride_g = gridDim.x * PW;
     f32x4 xr[DEPTH][TAPS][CI16];
-    int grp = blockIdx.x * PW + pw;
+    const unsigned tile = xcd_tile(blockIdx.x, gridDim.x);
+    int grp = tile * PW + pw;
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
         if (grp + d * stride_g < groups) gather(xr[d], grp + d * stride_g);  // all conditions here are wave-uniform
@@ -564,7 +576,7 @@ __global__ __launch_bounds__(kThreads) void conv3x3_direct_f32_kernel(const floa
                 a += red[k * cgs + cgi][c][0];
                 b += red[k * cgs + cgi][c][1];
             }
-            double* dst = stats + ((int64_t)blockIdx.x * g.Co + tid) * 2;
+            double* dst = stats + ((int64_t)tile * g.Co + tid) * 2;
             dst[0] = a;
             dst[1] = b;
         }
@@ -628,9 +640,12 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave / TL::WGN, wave_n = wave % TL::WGN;
     const int tiles_n = (g.Kdim + TL::BN - 1) / TL::BN;
-    const int c0 = (blockIdx.x / tiles_n) * TL::BM;  // first output channel of the tile
-    const int j0 = (blockIdx.x % tiles_n) * TL::BN;  // first (r,s,ci) column of the tile
-    const int m_begin = blockIdx.y * g.m_per_split;
+    // all tiles of one m slice in one L2: the linear workgroup id runs over the tiles first
+    const unsigned lin = xcd_tile(blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y);
+    const unsigned tile = lin % gridDim.x, slice = lin / gridDim.x;
+    const int c0 = (tile / tiles_n) * TL::BM;  // first output channel of the tile
+    const int j0 = (tile % tiles_n) * TL::BN;  // first (r,s,ci) column of the tile
+    const int m_begin = slice * g.m_per_split;
     const int m_end = min(g.M, m_begin + g.m_per_split);
     const int nk = (m_end - m_begin + BKm - 1) / BKm;
 
@@ -816,7 +831,7 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
         }
     }
 
-    float* dst = part + (int64_t)blockIdx.y * g.Co * g.Kdim;
+    float* dst = part + (int64_t)slice * g.Co * g.Kdim;
 #pragma unroll
     for (int i = 0; i < TL::TM; ++i)
 #pragma unroll
