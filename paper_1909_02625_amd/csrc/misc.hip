@@ -246,11 +246,12 @@ int launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* argmax, i
     DSP_REQUIRE(k * k < 255, DSP_EINVAL, "maxpool: window too large");
     const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
     const int64_t total = (int64_t)N * Ho * Wo * C;
+    ProfScope ps("maxpool_fwd", ((double)N * H * W * C + (double)total) * dtype_size(dtype) + (double)total, 1);
     if (dtype == DSP_BF16)
-        hipLaunchKernelGGL(maxpool_fwd_kernel<bf16_t>, dim3(grid_for(total)), dim3(kThreads), 0, st, (const bf16_t*)x,
+        DSP_LAUNCH(ps, maxpool_fwd_kernel<bf16_t>, dim3(grid_for(total)), dim3(kThreads), 0, st, (const bf16_t*)x,
                            (bf16_t*)y, argmax, N, H, W, C, Ho, Wo, k, stride, pad);
     else
-        hipLaunchKernelGGL(maxpool_fwd_kernel<float>, dim3(grid_for(total)), dim3(kThreads), 0, st, (const float*)x,
+        DSP_LAUNCH(ps, maxpool_fwd_kernel<float>, dim3(grid_for(total)), dim3(kThreads), 0, st, (const float*)x,
                            (float*)y, argmax, N, H, W, C, Ho, Wo, k, stride, pad);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
@@ -261,8 +262,9 @@ int launch_maxpool_backward(int dtype, const void* dy, const uint8_t* argmax, vo
 {
     const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
     const int64_t total = (int64_t)N * H * W * C;
+    ProfScope ps("maxpool_bwd", ((double)N * Ho * Wo * C + (double)total * (accumulate ? 2 : 1)) * dtype_size(dtype) + (double)N * Ho * Wo * C, 1);
 #define MP_BWD(T, A)                                                                                            \
-    hipLaunchKernelGGL((maxpool_bwd_kernel<T, A>), dim3(grid_for(total)), dim3(kThreads), 0, st, (const T*)dy, \
+    DSP_LAUNCH(ps, (maxpool_bwd_kernel<T, A>), dim3(grid_for(total)), dim3(kThreads), 0, st, (const T*)dy, \
                        argmax, (T*)dx, N, H, W, C, Ho, Wo, k, stride, pad)
     if (dtype == DSP_BF16) { if (accumulate) MP_BWD(bf16_t, true); else MP_BWD(bf16_t, false); }
     else                   { if (accumulate) MP_BWD(float, true); else MP_BWD(float, false); }
@@ -283,10 +285,11 @@ int launch_gap_forward(int dtype, const void* x, float* y, int N, int HW, int C,
 {
     const int cw = column_threads(C);
     const dim3 grid(N, ceil_div(C, cw));
+    ProfScope ps("gap_fwd", (double)N * HW * C * dtype_size(dtype) + 4.0 * N * C, 1);
     if (dtype == DSP_BF16)
-        hipLaunchKernelGGL(gap_fwd_kernel<bf16_t>, grid, dim3(kThreads), 0, st, (const bf16_t*)x, y, N, HW, C, cw);
+        DSP_LAUNCH(ps, gap_fwd_kernel<bf16_t>, grid, dim3(kThreads), 0, st, (const bf16_t*)x, y, N, HW, C, cw);
     else
-        hipLaunchKernelGGL(gap_fwd_kernel<float>, grid, dim3(kThreads), 0, st, (const float*)x, y, N, HW, C, cw);
+        DSP_LAUNCH(ps, gap_fwd_kernel<float>, grid, dim3(kThreads), 0, st, (const float*)x, y, N, HW, C, cw);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }
@@ -294,8 +297,9 @@ int launch_gap_forward(int dtype, const void* x, float* y, int N, int HW, int C,
 int launch_gap_backward(int dtype, const float* dy, void* dx, bool accumulate, int N, int HW, int C, hipStream_t st)
 {
     const int64_t total = (int64_t)N * HW * C;
+    ProfScope ps("gap_bwd", (double)total * dtype_size(dtype) * (accumulate ? 2 : 1) + 4.0 * N * C, 1);
 #define GAP_BWD(T, A) \
-    hipLaunchKernelGGL((gap_bwd_kernel<T, A>), dim3(grid_for(total)), dim3(kThreads), 0, st, dy, (T*)dx, N, HW, C)
+    DSP_LAUNCH(ps, (gap_bwd_kernel<T, A>), dim3(grid_for(total)), dim3(kThreads), 0, st, dy, (T*)dx, N, HW, C)
     if (dtype == DSP_BF16) { if (accumulate) GAP_BWD(bf16_t, true); else GAP_BWD(bf16_t, false); }
     else                   { if (accumulate) GAP_BWD(float, true); else GAP_BWD(float, false); }
 #undef GAP_BWD
@@ -306,7 +310,8 @@ int launch_gap_backward(int dtype, const float* dy, void* dx, bool accumulate, i
 int launch_linear_forward(const float* x, const float* w, const float* bias, float* z, int N, int Cin, int Cout,
                           hipStream_t st)
 {
-    hipLaunchKernelGGL(linear_fwd_kernel, dim3(ceil_div((int64_t)N * Cout, kThreads / 64)), dim3(kThreads), 0, st, x, w,
+    ProfScope ps("linear_fwd", 4.0 * ((double)N * Cin + (double)Cout * Cin + (double)N * Cout), 1);
+    DSP_LAUNCH(ps, linear_fwd_kernel, dim3(ceil_div((int64_t)N * Cout, kThreads / 64)), dim3(kThreads), 0, st, x, w,
                        bias, z, N, Cin, Cout);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
@@ -315,11 +320,14 @@ int launch_linear_forward(const float* x, const float* w, const float* bias, flo
 int launch_linear_backward(const float* x, const float* w, const float* dz, float* dx, float* dw, float* dbias,
                            int N, int Cin, int Cout, hipStream_t st)
 {
-    if (dx)
-        hipLaunchKernelGGL(linear_bwd_x_kernel, dim3(ceil_div((int64_t)N * Cin, kThreads)), dim3(kThreads), 0, st, dz, w,
-                           dx, N, Cin, Cout);
+    if (dx) {
+        ProfScope ps("linear_bwd_x", 4.0 * ((double)N * Cin + (double)Cout * Cin + (double)N * Cout), 1);
+        DSP_LAUNCH(ps, linear_bwd_x_kernel, dim3(ceil_div((int64_t)N * Cin, kThreads)), dim3(kThreads), 0, st, dz, w,
+                   dx, N, Cin, Cout);
+    }
     const int cw = column_threads(Cin + 1);
-    hipLaunchKernelGGL(linear_bwd_w_kernel, dim3(Cout, ceil_div(Cin + 1, cw)), dim3(kThreads), 0, st, dz, x, dw, dbias, N,
+    ProfScope ps("linear_bwd_w", 4.0 * ((double)N * Cin + (double)Cout * Cin + (double)N * Cout), 1);
+    DSP_LAUNCH(ps, linear_bwd_w_kernel, dim3(Cout, ceil_div(Cin + 1, cw)), dim3(kThreads), 0, st, dz, x, dw, dbias, N,
                        Cin, Cout, cw);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
@@ -329,8 +337,12 @@ int launch_softmax_ce(const float* z, const int32_t* labels, float* loss, float*
                       hipStream_t st)
 {
     DSP_REQUIRE(z && labels && loss && dz && row_loss && N > 0 && C > 0, DSP_EINVAL, "softmax_ce: null buffer or empty shape");
-    hipLaunchKernelGGL(softmax_ce_rows_kernel, dim3(N), dim3(64), 0, st, z, labels, row_loss, dz, N, C);
-    hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(64), 0, st, (const float*)row_loss, loss, N);
+    {
+        ProfScope ps("softmax_ce_rows", 8.0 * (double)N * C, 1);
+        DSP_LAUNCH(ps, softmax_ce_rows_kernel, dim3(N), dim3(64), 0, st, z, labels, row_loss, dz, N, C);
+    }
+    ProfScope ps("loss_mean", 4.0 * (double)N, 1);
+    DSP_LAUNCH(ps, mean_kernel, dim3(1), dim3(64), 0, st, (const float*)row_loss, loss, N);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }
@@ -371,7 +383,8 @@ int launch_refresh_shadows(int dtype, const float* x, const int32_t* tmap, void*
 
 int launch_record_loss(const float* loss, float* history, int32_t* counter, int64_t capacity, hipStream_t st)
 {
-    hipLaunchKernelGGL(record_loss_kernel, dim3(1), dim3(1), 0, st, loss, history, counter, (long long)capacity);
+    ProfScope ps("record_loss", 12.0, 1);
+    DSP_LAUNCH(ps, record_loss_kernel, dim3(1), dim3(1), 0, st, loss, history, counter, (long long)capacity);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }
