@@ -157,7 +157,9 @@ __device__ inline void zero_acc(typename Mma<typename TL::T, TL::MT>::Acc (&acc)
 struct GatherGeom {
     int N, Hi, Wi, Ci, Ho, Wo, Co, R, S, pad_h, pad_w, ostride, idil;
     int M, Kdim;
-    int accum;    // add to `out` instead of overwriting it
+    int ci_shift;  // log2(Ci) if Ci is a power of two, else -1
+    int s_inv;     // 65536 / S + 1: tap / S == (tap * s_inv) >> 16 for tap < 4096
+    int accum;     // add to `out` instead of overwriting it
     int out_vec;  // `out` rows can be written as whole 16-byte runs
     // if set: per row tile, the column sums {sum y, sum y^2} of the values as stored, [row tile][Co][2];
     // lets the batch norm that consumes `out` skip its own pass over the tensor
@@ -194,7 +196,7 @@ __device__ inline unsigned xcd_tile(unsigned b, unsigned nb)
     return xcd * q + (xcd < r ? xcd : r) + idx;
 }
 
-template <typename TL, bool VEC>
+template <typename TL, bool VEC, bool DIL>
 __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typename TL::T* __restrict__ in_,
                                                                     const typename TL::T* __restrict__ wgt,
                                                                     typename TL::T* __restrict__ out_, GatherGeom g)
@@ -216,8 +218,10 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
 
     const int kc = tid % CPR;    // which 16-byte run of the k tile this thread moves
     const int row0 = tid / CPR;  // first tile row it moves; further rows are +ROWS_PER_PASS apart
-    const bool dil = g.idil == 2;
-    const bool masked = VEC && !dil;  // plain vector path: per-row tap masks
+    // backward-data of a stride-2 convolution: fixed at compile time on the vector path, a run-time
+    // test on the element-wise path
+    const bool dil = VEC ? DIL : g.idil == 2;
+    constexpr bool masked = VEC && !DIL;  // plain vector path: per-row tap masks
 
     // Per-row gather state of the A operand (byte offsets modulo 2^32; tensors are < 4 GB, checked on the host).
     //   masked:    a_off = byte offset of pixel (ho*ostride - pad_h, wo*ostride - pad_w) of the row's image
@@ -256,15 +260,26 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
     const __amdgpu_buffer_rsrc_t rin = make_rsrc(in, (uint32_t)g.N * g.Hi * g.Wi * g.Ci * SZ);
     const __amdgpu_buffer_rsrc_t rw = make_rsrc(wgt, (uint32_t)g.Co * g.Kdim * SZ);
 
-    // k position of this thread's run: element kk = (kr*S + ks)*Ci + kci
-    int kk = kc * E, kr = 0, ks = 0, kci = kc * E;
-    while (kci >= g.Ci) {
-        kci -= g.Ci;
-        if (++ks == g.S) { ks = 0; ++kr; }
-    }
-
-    u32x4 ra[TL::A_PER], rb[TL::B_PER];
+    // k position of this thread's run in k tile kt: element kk = kt*BK + kc*E = (kr*S + ks)*Ci + kci
     const T zero = from_float<T>(0.f);
+    struct KPos {
+        int kk, kr, ks, kci;
+    };
+    auto k_position = [&](int kt) -> KPos {
+        KPos p;
+        p.kk = kt * TL::BK + kc * E;
+        int tap;
+        if (g.ci_shift >= 0) {
+            tap = p.kk >> g.ci_shift;
+            p.kci = p.kk & (g.Ci - 1);
+        } else {
+            tap = p.kk / g.Ci;
+            p.kci = p.kk - tap * g.Ci;
+        }
+        p.kr = (tap * g.s_inv) >> 16;
+        p.ks = tap - p.kr * g.S;
+        return p;
+    };
 
     // byte offset of tap (r, s), channel ci of the row described by (off, aux), or kOutOfRange  [unmasked rows]
     auto tap_offset = [&](uint32_t off, uint32_t aux, int r, int s, int ci) -> uint32_t {
@@ -279,12 +294,14 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
         return ok ? off + (uint32_t)((th * g.Wi + tw) * g.Ci + ci) * SZ : kOutOfRange;
     };
 
-    auto load_tiles = [&]() {
+    // global -> registers: the runs of k tile kt (zeros past the end of k, for padding taps and rows past M)
+    auto load_tiles = [&](int kt, u32x4 (&ra)[TL::A_PER], u32x4 (&rb)[TL::B_PER]) {
+        const KPos p = k_position(kt);
         if (VEC) {
-            const bool k_ok = kk < g.Kdim;
+            const bool k_ok = p.kk < g.Kdim;
             if (!dil) {
-                const uint32_t tap_off = (uint32_t)((kr * g.Wi + ks) * g.Ci + kci) * SZ;
-                const int tap = kr * g.S + ks;
+                const uint32_t tap_off = (uint32_t)((p.kr * g.Wi + p.ks) * g.Ci + p.kci) * SZ;
+                const int tap = p.kr * g.S + p.ks;
 #pragma unroll
                 for (int i = 0; i < TL::A_PER; ++i) {
                     const bool ok = k_ok && ((a_aux[i] >> tap) & 1u) != 0;
@@ -293,9 +310,9 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
             } else {
 #pragma unroll
                 for (int i = 0; i < TL::A_PER; ++i)
-                    ra[i] = load16(rin, k_ok ? tap_offset(a_off[i], a_aux[i], kr, ks, kci) : kOutOfRange);
+                    ra[i] = load16(rin, k_ok ? tap_offset(a_off[i], a_aux[i], p.kr, p.ks, p.kci) : kOutOfRange);
             }
-            const uint32_t kkb = (uint32_t)kk * SZ;
+            const uint32_t kkb = (uint32_t)p.kk * SZ;
 #pragma unroll
             for (int i = 0; i < TL::B_PER; ++i)
                 rb[i] = load16(rw, (k_ok && b_off[i] != kOutOfRange) ? b_off[i] + kkb : kOutOfRange);
@@ -305,7 +322,7 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
             for (int i = 0; i < TL::A_PER; ++i) {
                 alignas(16) T tmp[E];
                 for (int e = 0; e < E; ++e) {
-                    const int k = kk + e;
+                    const int k = p.kk + e;
                     const int tap = k / g.Ci, ci = k % g.Ci;
                     const uint32_t o = k < g.Kdim ? tap_offset(a_off[i], a_aux[i], tap / g.S, tap % g.S, ci) : kOutOfRange;
                     tmp[e] = o != kOutOfRange ? in[o / SZ] : zero;
@@ -316,31 +333,24 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
             for (int i = 0; i < TL::B_PER; ++i) {
                 alignas(16) T tmp[E];
                 for (int e = 0; e < E; ++e)
-                    tmp[e] = (b_off[i] != kOutOfRange && kk + e < g.Kdim) ? wgt[b_off[i] / SZ + kk + e] : zero;
+                    tmp[e] = (b_off[i] != kOutOfRange && p.kk + e < g.Kdim) ? wgt[b_off[i] / SZ + p.kk + e] : zero;
                 rb[i] = *(const u32x4*)tmp;
             }
         }
     };
-    auto advance_k = [&]() {
-        kk += TL::BK;
-        kci += TL::BK;
-        while (kci >= g.Ci) {
-            kci -= g.Ci;
-            if (++ks == g.S) { ks = 0; ++kr; }
-        }
-    };
-    auto store_tiles = [&](int buf) {
+    // registers -> LDS stage `buf`
+    auto store_tiles = [&](int buf, const u32x4 (&ra)[TL::A_PER], const u32x4 (&rb)[TL::B_PER]) {
         char* sA = smem + buf * TL::STAGE_BYTES;
         char* sB = sA + TL::BM * TL::ROWB;
 #pragma unroll
         for (int i = 0; i < TL::A_PER; ++i) {
             const int row = row0 + i * ROWS_PER_PASS;
-            if (row < TL::BM) *(u32x4*)(sA + row * TL::ROWB + kc * 16) = ra[i];
+            if (TL::A_CHUNKS % kThreads == 0 || row < TL::BM) *(u32x4*)(sA + row * TL::ROWB + kc * 16) = ra[i];
         }
 #pragma unroll
         for (int i = 0; i < TL::B_PER; ++i) {
             const int row = row0 + i * ROWS_PER_PASS;
-            if (row < TL::BN) *(u32x4*)(sB + row * TL::ROWB + kc * 16) = rb[i];
+            if (TL::B_CHUNKS % kThreads == 0 || row < TL::BN) *(u32x4*)(sB + row * TL::ROWB + kc * 16) = rb[i];
         }
     };
 
@@ -348,30 +358,34 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
     zero_acc<TL>(acc);
 
     const int nk = (g.Kdim + TL::BK - 1) / TL::BK;
-    load_tiles();
+    u32x4 ra0[TL::A_PER], rb0[TL::B_PER];
     if (TL::STAGES == 2) {
-        store_tiles(0);
+        // Two LDS stages and two register sets: while k tile kt is multiplied out of one LDS stage, tile
+        // kt+1 moves from registers into the other stage and the gathers of tile kt+2 are in flight, so
+        // a gather has two multiply phases to arrive.  (Loads past the last tile read zeros and are dropped.)
+        u32x4 ra1[TL::A_PER], rb1[TL::B_PER];
+        load_tiles(0, ra0, rb0);
+        store_tiles(0, ra0, rb0);
+        load_tiles(1, ra0, rb0);
         __syncthreads();
-        for (int kt = 0; kt < nk; ++kt) {
-            const int cur = kt & 1;
-            if (kt + 1 < nk) {
-                advance_k();
-                load_tiles();
-            }
-            mma_tile<TL>(smem + cur * TL::STAGE_BYTES, smem + cur * TL::STAGE_BYTES + TL::BM * TL::ROWB, wave_m, wave_n,
-                         lane, acc);
-            if (kt + 1 < nk) store_tiles(cur ^ 1);
+        for (int kt = 0; kt < nk; kt += 2) {
+            load_tiles(kt + 2, ra1, rb1);
+            mma_tile<TL>(smem, smem + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
+            store_tiles(1, ra0, rb0);
+            __syncthreads();
+            if (kt + 1 >= nk) break;
+            load_tiles(kt + 3, ra0, rb0);
+            mma_tile<TL>(smem + TL::STAGE_BYTES, smem + TL::STAGE_BYTES + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
+            store_tiles(0, ra1, rb1);
             __syncthreads();
         }
     } else {
+        load_tiles(0, ra0, rb0);
         for (int kt = 0; kt < nk; ++kt) {
             if (kt > 0) __syncthreads();  // every wave has finished reading the previous tile
-            store_tiles(0);
+            store_tiles(0, ra0, rb0);
             __syncthreads();
-            if (kt + 1 < nk) {  // the next tile's global loads fly while this one is multiplied
-                advance_k();
-                load_tiles();
-            }
+            if (kt + 1 < nk) load_tiles(kt + 1, ra0, rb0);  // the next tile's gathers fly while this one is multiplied
             mma_tile<TL>(smem, smem + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
         }
         __syncthreads();
@@ -984,13 +998,13 @@ const char* tile_name()
     return name.text;
 }
 
-template <typename TL, bool VEC>
+template <typename TL, bool VEC, bool DIL>
 int run_gather(const GatherGeom& g, const void* in, const void* w, void* out, hipStream_t st, double flops)
 {
     typedef typename TL::T T;
     const int64_t tiles = (int64_t)ceil_div(g.M, TL::BM) * ceil_div(g.Co, TL::BN);
     DSP_REQUIRE(tiles > 0 && tiles < (1ll << 31), DSP_EINVAL, "conv: bad tile count");
-    auto kern = conv_gather_gemm_kernel<TL, VEC>;
+    auto kern = conv_gather_gemm_kernel<TL, VEC, DIL>;
     static std::atomic<bool> attr_done{false};
     if (!attr_done && TL::LDS_BYTES > 48 * 1024) {
         DSP_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES));
@@ -1008,7 +1022,9 @@ int run_gather(const GatherGeom& g, const void* in, const void* w, void* out, hi
 template <typename TL>
 int run_gather_v(const GatherGeom& g, bool vec, const void* in, const void* w, void* out, hipStream_t st, double flops)
 {
-    return vec ? run_gather<TL, true>(g, in, w, out, st, flops) : run_gather<TL, false>(g, in, w, out, st, flops);
+    // the element-wise path handles dilation with run-time tests; the vector path has a kernel of its own for it
+    if (!vec) return run_gather<TL, false, false>(g, in, w, out, st, flops);
+    return g.idil == 2 ? run_gather<TL, true, true>(g, in, w, out, st, flops) : run_gather<TL, true, false>(g, in, w, out, st, flops);
 }
 
 // Enough workgroups to put more than one on each of the 256 compute units.
@@ -1254,12 +1270,25 @@ int check_shape(const ConvShape& c)
 
 }  // namespace
 
+// Geometry of a gather-GEMM: tensor `in` (N x Hi x Wi x Ci) gathered into output rows over N x Ho x Wo.
+static GatherGeom make_geom(int N, int Hi, int Wi, int Ci, int Ho, int Wo, int Co, int R, int S, int pad_h, int pad_w,
+                            int ostride, int idil)
+{
+    GatherGeom g{};
+    g.N = N; g.Hi = Hi; g.Wi = Wi; g.Ci = Ci; g.Ho = Ho; g.Wo = Wo; g.Co = Co; g.R = R; g.S = S;
+    g.pad_h = pad_h; g.pad_w = pad_w; g.ostride = ostride; g.idil = idil;
+    g.M = N * Ho * Wo;
+    g.Kdim = R * S * Ci;
+    g.ci_shift = -1;
+    for (int b = 0; b < 31; ++b)
+        if ((1 << b) == Ci) g.ci_shift = b;
+    g.s_inv = 65536 / S + 1;
+    return g;
+}
+
 static GatherGeom forward_geom(const ConvShape& c)
 {
-    GatherGeom g{c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.pad, c.stride, 1, 0, 0, 0, 0, nullptr, nullptr, nullptr, nullptr};
-    g.M = c.N * c.Ho * c.Wo;
-    g.Kdim = c.R * c.S * c.Cin;
-    return g;
+    return make_geom(c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.pad, c.stride, 1);
 }
 
 int conv_forward_row_tiles(int dtype, const ConvShape& c)
@@ -1303,10 +1332,7 @@ int launch_conv_backward_data(int dtype, const ConvShape& c, const void* dy, con
     DSP_TRY(check_shape(c));
     DSP_REQUIRE(c.stride == 1 || c.stride == 2, DSP_EINVAL, "conv backward-data: stride %d unsupported", c.stride);
     // dx[n,hi,wi,ci] = sum_{r',s',co} dy[n, (hi - (R-1-pad) + r')/stride, ...][co] * wt[ci][r'][s'][co]
-    GatherGeom g{c.N, c.Ho, c.Wo, c.Cout, c.H, c.W, c.Cin, c.R, c.S, c.R - 1 - c.pad, c.S - 1 - c.pad, 1, c.stride,
-                 0, 0, 0, 0, nullptr, nullptr, nullptr, nullptr};
-    g.M = c.N * c.H * c.W;
-    g.Kdim = c.R * c.S * c.Cout;
+    GatherGeom g = make_geom(c.N, c.Ho, c.Wo, c.Cout, c.H, c.W, c.Cin, c.R, c.S, c.R - 1 - c.pad, c.S - 1 - c.pad, 1, c.stride);
     const double flops = 2.0 * conv_macs(c);
     return dtype == DSP_BF16 ? dispatch_gather<bf16_t>(g, accumulate, dy, wt, dx, st, flops)
                              : dispatch_gather<float>(g, accumulate, dy, wt, dx, st, flops);
