@@ -19,50 +19,6 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kMaxPartialBlocks = 512;
 
-template <typename T, int VW>
-struct VecIO;
-
-template <>
-struct VecIO<float, 4> {
-    __device__ static inline void load(const float* p, float (&v)[4])
-    {
-        const float4 t = *(const float4*)p;
-        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-    }
-    __device__ static inline void store(float* p, const float (&v)[4]) { *(float4*)p = make_float4(v[0], v[1], v[2], v[3]); }
-};
-template <>
-struct VecIO<float, 1> {
-    __device__ static inline void load(const float* p, float (&v)[1]) { v[0] = *p; }
-    __device__ static inline void store(float* p, const float (&v)[1]) { *p = v[0]; }
-};
-template <>
-struct VecIO<bf16_t, 8> {
-    __device__ static inline void load(const bf16_t* p, float (&v)[8])
-    {
-        const uint4 t = *(const uint4*)p;
-        const uint32_t w[4] = {t.x, t.y, t.z, t.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            v[2 * i] = __uint_as_float(w[i] << 16);
-            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-        }
-    }
-    __device__ static inline void store(bf16_t* p, const float (&v)[8])
-    {
-        uint32_t w[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            w[i] = (uint32_t)float_to_bf16(v[2 * i]).bits | ((uint32_t)float_to_bf16(v[2 * i + 1]).bits << 16);
-        *(uint4*)p = make_uint4(w[0], w[1], w[2], w[3]);
-    }
-};
-template <>
-struct VecIO<bf16_t, 1> {
-    __device__ static inline void load(const bf16_t* p, float (&v)[1]) { v[0] = bf16_to_float(*p); }
-    __device__ static inline void store(bf16_t* p, const float (&v)[1]) { *p = float_to_bf16(v[0]); }
-};
-
 // Layout of a workgroup over x[M][C]: CV channel vectors per row, RL row lanes.
 struct RowLayout {
     int cv;   // channel vectors per row (C / VW)

@@ -980,6 +980,33 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
     }
 }
 
+// The same sum for few slices (<= 8): there the tree above would leave most thread rows idle, so each
+// thread adds the slices of 4 consecutive elements in ascending order.
+template <int VW>
+__global__ __launch_bounds__(256) void wgrad_reduce_few_kernel(const float* __restrict__ part, float* __restrict__ dw,
+                                                               int n, int splits)
+{
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * VW;
+    if (i >= n) return;
+    float s[VW];
+#pragma unroll
+    for (int v = 0; v < VW; ++v) s[v] = 0.f;
+    for (int k = 0; k < splits; ++k) {
+        const float* src = part + (int64_t)k * n + i;
+        if (VW == 4) {
+            const f32x4 t = *(const f32x4*)src;
+#pragma unroll
+            for (int v = 0; v < VW; ++v) s[v] += t[v];
+        } else {
+            s[0] += src[0];
+        }
+    }
+    if (VW == 4)
+        *(f32x4*)(dw + i) = f32x4{s[0], s[1], s[2], s[3]};
+    else
+        dw[i] = s[0];
+}
+
 // ---- host-side dispatch -------------------------------------------------------------------------
 struct KernelName {
     char text[96];
@@ -1227,7 +1254,14 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
     DSP_TRY(rc);
     if (splits > 1) {
         ProfScope ps("wgrad_reduce", (double)n * (splits + 1) * 4.0, 1);
-        if (n % 4 == 0 && ((uintptr_t)ws % 16) == 0)
+        const bool v4 = n % 4 == 0 && ((uintptr_t)ws % 16) == 0 && ((uintptr_t)dw % 16) == 0;
+        if (splits <= 8 && v4)
+            DSP_LAUNCH(ps, wgrad_reduce_few_kernel<4>, dim3(ceil_div(n / 4, 256)), dim3(256), 0, st, (const float*)ws, dw,
+                       (int)n, splits);
+        else if (splits <= 8)
+            DSP_LAUNCH(ps, wgrad_reduce_few_kernel<1>, dim3(ceil_div(n, 256)), dim3(256), 0, st, (const float*)ws, dw, (int)n,
+                       splits);
+        else if (n % 4 == 0 && ((uintptr_t)ws % 16) == 0)
             DSP_LAUNCH(ps, wgrad_reduce_kernel<4>, dim3(ceil_div(n, 32)), dim3(256), 0, st, (const float*)ws, dw, (int)n,
                        splits);
         else

@@ -17,44 +17,65 @@ inline int grid_for(int64_t n, int cap = 256 * 32)
 
 // ---- max pool ------------------------------------------------------------------------------------
 // Window scan in row-major order, strict ">" so the first maximum wins; argmax keeps r*k+s.
-template <typename T>
-__global__ void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, uint8_t* __restrict__ arg, int N, int H,
-                                   int W, int C, int Ho, int Wo, int k, int stride, int pad)
+// A thread owns VW consecutive channels of one output pixel (one 16-byte run per tap when VW > 1).
+template <typename T, int VW>
+__global__ __launch_bounds__(kThreads) void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                               uint8_t* __restrict__ arg, int N, int H, int W, int C,
+                                                               int Ho, int Wo, int k, int stride, int pad)
 {
-    const int64_t total = (int64_t)N * Ho * Wo * C;
+    const int cv = C / VW;
+    const int64_t total = (int64_t)N * Ho * Wo * cv;
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
-        const int c = (int)(i % C);
-        int64_t t = i / C;
+        const int c = (int)(i % cv) * VW;
+        int64_t t = i / cv;
         const int wo = (int)(t % Wo);
         t /= Wo;
         const int ho = (int)(t % Ho), n = (int)(t / Ho);
-        float best = -INFINITY;
-        int a = 255;
+        float best[VW];
+        int a[VW];
+#pragma unroll
+        for (int v = 0; v < VW; ++v) {
+            best[v] = -INFINITY;
+            a[v] = 255;
+        }
         for (int r = 0; r < k; ++r)
             for (int s = 0; s < k; ++s) {
                 const int hi = ho * stride + r - pad, wi = wo * stride + s - pad;
                 if (hi < 0 || hi >= H || wi < 0 || wi >= W) continue;
-                const float v = to_float<T>(x[(((int64_t)n * H + hi) * W + wi) * C + c]);
-                if (v > best) { best = v; a = r * k + s; }
+                float xv[VW];
+                VecIO<T, VW>::load(x + (((int64_t)n * H + hi) * W + wi) * C + c, xv);
+#pragma unroll
+                for (int v = 0; v < VW; ++v)
+                    if (xv[v] > best[v]) {
+                        best[v] = xv[v];
+                        a[v] = r * k + s;
+                    }
             }
-        y[i] = from_float<T>(best);
-        if (arg) arg[i] = (uint8_t)a;
+        const int64_t o = (((int64_t)n * Ho + ho) * Wo + wo) * C + c;
+        VecIO<T, VW>::store(y + o, best);
+        if (arg)
+#pragma unroll
+            for (int v = 0; v < VW; ++v) arg[o + v] = (uint8_t)a[v];
     }
 }
 
 // dx[n,hi,wi,c] (+)= sum of dy over the windows whose recorded argmax is this pixel.
-template <typename T, bool ACC>
-__global__ void maxpool_bwd_kernel(const T* __restrict__ dy, const uint8_t* __restrict__ arg, T* __restrict__ dx, int N,
-                                   int H, int W, int C, int Ho, int Wo, int k, int stride, int pad)
+template <typename T, int VW, bool ACC>
+__global__ __launch_bounds__(kThreads) void maxpool_bwd_kernel(const T* __restrict__ dy, const uint8_t* __restrict__ arg,
+                                                               T* __restrict__ dx, int N, int H, int W, int C, int Ho,
+                                                               int Wo, int k, int stride, int pad)
 {
-    const int64_t total = (int64_t)N * H * W * C;
+    const int cv = C / VW;
+    const int64_t total = (int64_t)N * H * W * cv;
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
-        const int c = (int)(i % C);
-        int64_t t = i / C;
+        const int c = (int)(i % cv) * VW;
+        int64_t t = i / cv;
         const int wi = (int)(t % W);
         t /= W;
         const int hi = (int)(t % H), n = (int)(t / H);
-        float s = 0.f;
+        float s[VW];
+#pragma unroll
+        for (int v = 0; v < VW; ++v) s[v] = 0.f;
         for (int r = 0; r < k; ++r) {
             const int hn = hi + pad - r;
             if (hn < 0 || hn % stride) continue;
@@ -66,14 +87,24 @@ __global__ void maxpool_bwd_kernel(const T* __restrict__ dy, const uint8_t* __re
                 const int wo = wn / stride;
                 if (wo >= Wo) continue;
                 const int64_t o = (((int64_t)n * Ho + ho) * Wo + wo) * C + c;
-                if (arg[o] == r * k + q) s += to_float<T>(dy[o]);
+                float gv[VW];
+                VecIO<T, VW>::load(dy + o, gv);
+#pragma unroll
+                for (int v = 0; v < VW; ++v)
+                    if (arg[o + v] == r * k + q) s[v] += gv[v];
             }
         }
-        dx[i] = from_float<T>(ACC ? to_float<T>(dx[i]) + s : s);
+        const int64_t o = (((int64_t)n * H + hi) * W + wi) * C + c;
+        if (ACC) {
+            float old[VW];
+            VecIO<T, VW>::load(dx + o, old);
+#pragma unroll
+            for (int v = 0; v < VW; ++v) s[v] += old[v];
+        }
+        VecIO<T, VW>::store(dx + o, s);
     }
 }
 
-// ---- global average pool ------------------------------------------------------------------------
 // y[n][c] = mean over the HW positions of x[n][.][c].  A workgroup owns one image and up to 256
 // channels; CW threads cover the channels (coalesced rows), 256 / CW thread rows split the positions
 // and are added in row order.
@@ -245,14 +276,16 @@ int launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* argmax, i
 {
     DSP_REQUIRE(k * k < 255, DSP_EINVAL, "maxpool: window too large");
     const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
-    const int64_t total = (int64_t)N * Ho * Wo * C;
-    ProfScope ps("maxpool_fwd", ((double)N * H * W * C + (double)total) * dtype_size(dtype) + (double)total, 1);
-    if (dtype == DSP_BF16)
-        DSP_LAUNCH(ps, maxpool_fwd_kernel<bf16_t>, dim3(grid_for(total)), dim3(kThreads), 0, st, (const bf16_t*)x,
-                           (bf16_t*)y, argmax, N, H, W, C, Ho, Wo, k, stride, pad);
-    else
-        DSP_LAUNCH(ps, maxpool_fwd_kernel<float>, dim3(grid_for(total)), dim3(kThreads), 0, st, (const float*)x,
-                           (float*)y, argmax, N, H, W, C, Ho, Wo, k, stride, pad);
+    const int vw = dtype == DSP_BF16 ? 8 : 4;
+    const bool vec = C % vw == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)y % 16) == 0;
+    const int64_t total = (int64_t)N * Ho * Wo * (vec ? C / vw : C);
+    ProfScope ps("maxpool_fwd", ((double)N * H * W * C + (double)N * Ho * Wo * C) * dtype_size(dtype) + (double)N * Ho * Wo * C, 1);
+#define MP_FWD(T, V) \
+    DSP_LAUNCH(ps, (maxpool_fwd_kernel<T, V>), dim3(grid_for(total)), dim3(kThreads), 0, st, (const T*)x, (T*)y, argmax, N, \
+               H, W, C, Ho, Wo, k, stride, pad)
+    if (dtype == DSP_BF16) { if (vec) MP_FWD(bf16_t, 8); else MP_FWD(bf16_t, 1); }
+    else                   { if (vec) MP_FWD(float, 4); else MP_FWD(float, 1); }
+#undef MP_FWD
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }
@@ -261,13 +294,21 @@ int launch_maxpool_backward(int dtype, const void* dy, const uint8_t* argmax, vo
                             int H, int W, int C, int k, int stride, int pad, hipStream_t st)
 {
     const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
-    const int64_t total = (int64_t)N * H * W * C;
-    ProfScope ps("maxpool_bwd", ((double)N * Ho * Wo * C + (double)total * (accumulate ? 2 : 1)) * dtype_size(dtype) + (double)N * Ho * Wo * C, 1);
-#define MP_BWD(T, A)                                                                                            \
-    DSP_LAUNCH(ps, (maxpool_bwd_kernel<T, A>), dim3(grid_for(total)), dim3(kThreads), 0, st, (const T*)dy, \
-                       argmax, (T*)dx, N, H, W, C, Ho, Wo, k, stride, pad)
-    if (dtype == DSP_BF16) { if (accumulate) MP_BWD(bf16_t, true); else MP_BWD(bf16_t, false); }
-    else                   { if (accumulate) MP_BWD(float, true); else MP_BWD(float, false); }
+    const int vw = dtype == DSP_BF16 ? 8 : 4;
+    const bool vec = C % vw == 0 && ((uintptr_t)dy % 16) == 0 && ((uintptr_t)dx % 16) == 0;
+    const int64_t total = (int64_t)N * H * W * (vec ? C / vw : C);
+    ProfScope ps("maxpool_bwd",
+                 ((double)N * Ho * Wo * C + (double)N * H * W * C * (accumulate ? 2 : 1)) * dtype_size(dtype) + (double)N * Ho * Wo * C, 1);
+#define MP_BWD(T, V, A) \
+    DSP_LAUNCH(ps, (maxpool_bwd_kernel<T, V, A>), dim3(grid_for(total)), dim3(kThreads), 0, st, (const T*)dy, argmax, (T*)dx, \
+               N, H, W, C, Ho, Wo, k, stride, pad)
+    if (dtype == DSP_BF16) {
+        if (vec) { if (accumulate) MP_BWD(bf16_t, 8, true); else MP_BWD(bf16_t, 8, false); }
+        else     { if (accumulate) MP_BWD(bf16_t, 1, true); else MP_BWD(bf16_t, 1, false); }
+    } else {
+        if (vec) { if (accumulate) MP_BWD(float, 4, true); else MP_BWD(float, 4, false); }
+        else     { if (accumulate) MP_BWD(float, 1, true); else MP_BWD(float, 1, false); }
+    }
 #undef MP_BWD
     DSP_HIP(hipGetLastError());
     return DSP_OK;
