@@ -90,6 +90,13 @@ struct Layer {
     // conv: the next layer is a batch norm of this output, so the conv kernel also leaves the per-tile
     // column sums in the block's partial-sum buffer; bn: number of such tiles (0 = sum x itself)
     int sum_tiles = 0;
+    // A conv on the data input whose channel count is no whole 16-byte run (the 3-channel stem): the
+    // input is copied into a channel-padded buffer and the layer runs as a conv over cin_pad channels
+    // (cs describes that padded problem).  Its forward filters live, padded with zeros, in the block's
+    // filter-copy area (this layer needs no backward-data copy), kept up to date by the update kernel.
+    int cin_pad = 0;
+    void* xpad = nullptr;     // padded input of the pass the backward sweep belongs to
+    float* dw_pad = nullptr;  // filter gradient in the padded layout
 };
 
 }  // namespace dsp
@@ -103,6 +110,7 @@ struct ForwardLane {
     std::vector<void*> act;
     std::vector<float*> mean, invstd;
     std::vector<uint8_t*> argmax;
+    std::vector<void*> xpad;
     double* bn_partial = nullptr;
     float* bn_coef = nullptr;
 };
@@ -201,14 +209,23 @@ static int build_graph(dsp_block* b)
         case DSP_OP_CONV:
             DSP_REQUIRE(!s.is_float && s.C == L.d.cin && L.d.cout > 0 && L.d.r > 0 && L.d.s > 0 && L.d.stride > 0 &&
                             L.d.pad >= 0, DSP_EINVAL, "layer %d: conv shape mismatch", i);
-            L.cs = make_conv_shape(s.N, s.H, s.W, L.d.cin, L.d.cout, L.d.r, L.d.s, L.d.stride, L.d.pad);
+        {
+            const int run = 16 / (int)dtype_size(d.dtype);
+            int cin = L.d.cin;
+            if (L.d.in0 < 0 && !d.needs_input_grad && cin % run != 0) {
+                L.cin_pad = (cin + run - 1) / run * run;
+                cin = L.cin_pad;
+            }
+            L.cs = make_conv_shape(s.N, s.H, s.W, cin, L.d.cout, L.d.r, L.d.s, L.d.stride, L.d.pad);
+            if (L.cin_pad) L.cs.cin_real = L.d.cin;
             DSP_REQUIRE(L.cs.Ho > 0 && L.cs.Wo > 0, DSP_EINVAL, "layer %d: empty conv output", i);
             t.C = L.d.cout; t.H = L.cs.Ho; t.W = L.cs.Wo;
             L.p0 = poff;
             poff += (size_t)L.d.cout * L.d.cin * L.d.r * L.d.s;
             L.wt_off = wtoff;
-            wtoff += (size_t)L.d.cout * L.d.cin * L.d.r * L.d.s;
+            wtoff += (size_t)L.d.cout * cin * L.d.r * L.d.s;
             break;
+        }
         case DSP_OP_BN:
             DSP_REQUIRE(!s.is_float && s.C == L.d.cin, DSP_EINVAL, "layer %d: bn channel mismatch", i);
             DSP_REQUIRE(L.d.in1 == -2 || (L.d.in1 >= -1 && L.d.in1 < i), DSP_EINVAL, "layer %d: bad residual", i);
@@ -288,7 +305,9 @@ static int build_graph(dsp_block* b)
                             const size_t lib = L.p0 + (((size_t)co * R + r) * S + s) * Ci + ci;
                             b->perm[lib] = (int32_t)(L.p0 + (((size_t)co * Ci + ci) * R + r) * S + s);
                             decay[lib] = 1;
-                            if (L.in0_grad)
+                            if (L.cin_pad)
+                                tmap[lib] = (int32_t)(L.wt_off + (((size_t)co * R + r) * S + s) * L.cin_pad + ci);
+                            else if (L.in0_grad)
                                 tmap[lib] = (int32_t)(L.wt_off + (((size_t)ci * R + (R - 1 - r)) * S + (S - 1 - s)) * Co + co);
                         }
         } else if (L.d.op == DSP_OP_BN) {
@@ -311,6 +330,7 @@ static int build_graph(dsp_block* b)
     DSP_TRY(dev_alloc(b, (void**)&b->decay, b->nP, &b->param_bytes));
     DSP_TRY(dev_alloc(b, (void**)&b->tmap, b->nP * 4, &b->param_bytes));
     DSP_TRY(dev_alloc(b, &b->wt, b->wt_elems * esz, &b->param_bytes));
+    DSP_HIP(hipMemset(b->wt, 0, b->wt_elems * esz ? b->wt_elems * esz : 16));  // the zero channels of padded filters stay zero
     if (b->dtype == DSP_BF16) DSP_TRY(dev_alloc(b, &b->wf16, b->nP * 2, &b->param_bytes));
     if (b->nP) {
         DSP_HIP(hipMemcpy(b->decay, decay.data(), b->nP, hipMemcpyHostToDevice));
@@ -338,6 +358,10 @@ static int build_graph(dsp_block* b)
             if (L.d.cin > max_c) max_c = L.d.cin;
         }
         if (L.d.op == DSP_OP_MAXPOOL) DSP_TRY(dev_alloc(b, (void**)&L.argmax, t.elems, &b->ws_bytes));
+        if (L.cin_pad) {
+            DSP_TRY(dev_alloc(b, &L.xpad, (size_t)L.cs.N * L.cs.H * L.cs.W * L.cin_pad * esz, &b->ws_bytes));
+            DSP_TRY(dev_alloc(b, (void**)&L.dw_pad, (size_t)L.cs.Cout * L.cs.R * L.cs.S * L.cin_pad * 4, &b->ws_bytes));
+        }
         if (L.d.op == DSP_OP_CONV) {
             const size_t w = conv_backward_weight_workspace(L.cs);
             if (w > ws) ws = w;
@@ -415,10 +439,20 @@ static int run_forward(dsp_block* b, const ForwardPass& P, const ForwardPass* tw
         const int passes = twin ? 2 : 1;
         switch (L.d.op) {
         case DSP_OP_CONV: {
+            auto conv_src = [&](const ForwardPass& p) -> const void* {
+                return L.cin_pad ? (p.lane ? p.lane->xpad[i] : L.xpad) : src_of(p, L.d.in0);
+            };
+            if (L.cin_pad)
+                for (int q = 0; q < passes; ++q) {
+                    const ForwardPass& p = q ? *twin : P;
+                    DSP_TRY(launch_pad_channels(b->dtype, p.in, const_cast<void*>(conv_src(p)),
+                                                (int64_t)L.cs.N * L.cs.H * L.cs.W, L.d.cin, L.cin_pad, st));
+                }
             ConvForwardTwin tw{};
-            if (twin) tw = ConvForwardTwin{src_of(*twin, L.d.in0), act_of(*twin, i), L.sum_tiles > 0 ? bn_buffers(*twin).partial : nullptr};
-            DSP_TRY(launch_conv_forward(b->dtype, L.cs, src_of(P, L.d.in0), weights_for_forward(b, L), act_of(P, i), st,
-                                        L.sum_tiles > 0 ? bn_buffers(P).partial : nullptr, twin ? &tw : nullptr));
+            if (twin) tw = ConvForwardTwin{conv_src(*twin), act_of(*twin, i), L.sum_tiles > 0 ? bn_buffers(*twin).partial : nullptr};
+            DSP_TRY(launch_conv_forward(b->dtype, L.cs, conv_src(P), L.cin_pad ? weights_for_dgrad(b, L) : weights_for_forward(b, L),
+                                        act_of(P, i), st, L.sum_tiles > 0 ? bn_buffers(P).partial : nullptr,
+                                        twin ? &tw : nullptr));
             break;
         }
         case DSP_OP_BN: {
@@ -477,7 +511,12 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
         const void* dy = (i == b->out_idx) ? gout : b->T[i].grad;
         switch (L.d.op) {
         case DSP_OP_CONV:
-            DSP_TRY(launch_conv_backward_weight(b->dtype, L.cs, src, dy, b->g + L.p0, b->wgrad_ws, b->wgrad_ws_bytes, st));
+            if (L.cin_pad) {
+                DSP_TRY(launch_conv_backward_weight(b->dtype, L.cs, L.xpad, dy, L.dw_pad, b->wgrad_ws, b->wgrad_ws_bytes, st));
+                DSP_TRY(launch_unpad_rows(L.dw_pad, b->g + L.p0, (int64_t)L.cs.Cout * L.cs.R * L.cs.S, L.d.cin, L.cin_pad, st));
+            } else {
+                DSP_TRY(launch_conv_backward_weight(b->dtype, L.cs, src, dy, b->g + L.p0, b->wgrad_ws, b->wgrad_ws_bytes, st));
+            }
             if (L.in0_grad)
                 DSP_TRY(launch_conv_backward_data(b->dtype, L.cs, dy, weights_for_dgrad(b, L), grad_of(L.d.in0), L.in0_acc, st));
             break;
@@ -571,6 +610,7 @@ int dsp_block_enable_forward_lane(dsp_block* b)
     ln->mean.assign(n, nullptr);
     ln->invstd.assign(n, nullptr);
     ln->argmax.assign(n, nullptr);
+    ln->xpad.assign(n, nullptr);
     int rc = DSP_OK;
     for (int i = 0; i < n && rc == DSP_OK; ++i) {
         const Layer& L = b->layers[i];
@@ -582,6 +622,8 @@ int dsp_block_enable_forward_lane(dsp_block* b)
             if (rc == DSP_OK) rc = dev_alloc(b, (void**)&ln->invstd[i], (size_t)L.d.cin * 4, &b->ws_bytes);
         }
         if (rc == DSP_OK && L.d.op == DSP_OP_MAXPOOL) rc = dev_alloc(b, (void**)&ln->argmax[i], t.elems, &b->ws_bytes);
+        if (rc == DSP_OK && L.cin_pad)
+            rc = dev_alloc(b, &ln->xpad[i], (size_t)L.cs.N * L.cs.H * L.cs.W * L.cin_pad * dtype_size(b->dtype), &b->ws_bytes);
     }
     if (rc == DSP_OK) rc = dev_alloc(b, (void**)&ln->bn_partial, b->bn_partial_elems * 2 * sizeof(double), &b->ws_bytes);
     if (rc == DSP_OK) rc = dev_alloc(b, (void**)&ln->bn_coef, (size_t)3 * b->bn_max_c * 4, &b->ws_bytes);

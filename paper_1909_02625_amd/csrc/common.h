@@ -98,11 +98,13 @@ inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 // Geometry of one convolution y = conv(x, w): x is N x H x W x Cin (NHWC), y is N x Ho x Wo x Cout.
 struct ConvShape {
     int N, H, W, Cin, Cout, R, S, stride, pad, Ho, Wo;
+    int cin_real;  // > 0: only the first cin_real of the Cin input channels carry data (the rest is zero padding);
+                   // used for counting the useful multiply-accumulates only
 };
 
 inline ConvShape make_conv_shape(int N, int H, int W, int Cin, int Cout, int R, int S, int stride, int pad)
 {
-    ConvShape c{N, H, W, Cin, Cout, R, S, stride, pad, 0, 0};
+    ConvShape c{N, H, W, Cin, Cout, R, S, stride, pad, 0, 0, 0};
     c.Ho = (H + 2 * pad - R) / stride + 1;
     c.Wo = (W + 2 * pad - S) / stride + 1;
     return c;
@@ -181,6 +183,10 @@ int launch_sgd_update(int dtype, float* x, float* v, const float* g, const uint8
 int launch_refresh_shadows(int dtype, const float* x, const int32_t* tmap, void* wf16, void* wt, size_t n,
                            hipStream_t st);
 int launch_spin(int microseconds, hipStream_t st);
+// dst[p][0..Cp) = {src[p][0..C), 0...}: channel padding of an NHWC tensor (pixels rows) up to a whole 16-byte run.
+int launch_pad_channels(int dtype, const void* src, void* dst, int64_t pixels, int C, int Cp, hipStream_t st);
+// dst[row][0..C) = src[row][0..C) for rows of Cp floats: drops the padded channels of a filter gradient.
+int launch_unpad_rows(const float* src, float* dst, int64_t rows, int C, int Cp, hipStream_t st);
 // history[counter[0]] = *loss; counter[0] += 1   (one thread; keeps the loss history index on the device)
 int launch_record_loss(const float* loss, float* history, int32_t* counter, int64_t capacity, hipStream_t st);
 

@@ -228,23 +228,26 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
     //              (may lie before the tensor), a_aux = bit (r*S + s) set iff tap (r, s) falls inside the image
     //   otherwise: a_off = byte offset of the row's image, a_aux = th0 (low half) | tw0 (high half)
     uint32_t a_off[TL::A_PER], a_aux[TL::A_PER];
+    uint32_t a_hi[TL::A_PER];  // masked: taps 32..63 (filters larger than 32 taps, e.g. 7x7)
 #pragma unroll
     for (int i = 0; i < TL::A_PER; ++i) {
         const int row = row0 + i * ROWS_PER_PASS;
         const int m = m0 + row;
         a_off[i] = 0;
+        a_hi[i] = 0;
         a_aux[i] = masked ? 0u : 0x80008000u;  // nothing valid
         if (row < TL::BM && m < g.M) {
             const int wo = m % g.Wo, t = m / g.Wo, ho = t % g.Ho, n = t / g.Ho;
             const int th0 = ho * g.ostride - g.pad_h, tw0 = wo * g.ostride - g.pad_w;
             const uint32_t img = (uint32_t)n * g.Hi * g.Wi * g.Ci * SZ;
             if (masked) {
-                uint32_t mask = 0;
+                uint64_t mask = 0;
                 for (int r = 0; r < g.R; ++r)
                     for (int s = 0; s < g.S; ++s)
-                        mask |= (uint32_t)(th0 + r >= 0 && th0 + r < g.Hi && tw0 + s >= 0 && tw0 + s < g.Wi) << (r * g.S + s);
+                        mask |= (uint64_t)(th0 + r >= 0 && th0 + r < g.Hi && tw0 + s >= 0 && tw0 + s < g.Wi) << (r * g.S + s);
                 a_off[i] = img + (uint32_t)((th0 * g.Wi + tw0) * g.Ci) * SZ;
-                a_aux[i] = mask;
+                a_aux[i] = (uint32_t)mask;
+                a_hi[i] = (uint32_t)(mask >> 32);
             } else {
                 a_off[i] = img;
                 a_aux[i] = ((uint32_t)th0 & 0xffffu) | ((uint32_t)tw0 << 16);
@@ -304,7 +307,8 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
                 const int tap = p.kr * g.S + p.ks;
 #pragma unroll
                 for (int i = 0; i < TL::A_PER; ++i) {
-                    const bool ok = k_ok && ((a_aux[i] >> tap) & 1u) != 0;
+                    const uint32_t bits = tap < 32 ? a_aux[i] >> tap : a_hi[i] >> (tap - 32);
+                    const bool ok = k_ok && (bits & 1u) != 0;
                     ra[i] = load16(rin, ok ? a_off[i] + tap_off : kOutOfRange);
                 }
             } else {
@@ -1120,9 +1124,10 @@ int dispatch_gather(GatherGeom g, bool accum, const void* in, const void* w, voi
         return DSP_OK;
     }
     constexpr int KB = 128;  // bytes of k per LDS row of the large tiles: 64 bf16 / 32 floats
-    // 16-byte gathers need channel runs of E elements, 16-byte aligned bases and tap masks of 16 bits
-    // (tap masks hold up to 32 taps; larger filters take the generic path)
-    const bool vec = (g.Ci % E) == 0 && ((uintptr_t)in % 16) == 0 && ((uintptr_t)w % 16) == 0 && g.R * g.S <= 32;
+    // 16-byte gathers need channel runs of E elements and 16-byte aligned bases; the per-row tap masks
+    // hold up to 64 taps (larger filters, and dilated gathers of more than 32 taps, take the generic path)
+    const bool vec = (g.Ci % E) == 0 && ((uintptr_t)in % 16) == 0 && ((uintptr_t)w % 16) == 0 &&
+                     g.R * g.S <= (g.idil == 2 ? 32 : 64);
     g.accum = accum ? 1 : 0;
     g.out_vec = ((g.Co % E) == 0 && ((uintptr_t)out % 16) == 0) ? 1 : 0;
     int bm;
@@ -1287,7 +1292,7 @@ double conv_macs(const ConvShape& c)
             const int t = o * c.stride - c.pad + s;
             vw += (t >= 0 && t < c.W);
         }
-    return (double)c.N * (double)vh * (double)vw * (double)c.Cin * (double)c.Cout;
+    return (double)c.N * (double)vh * (double)vw * (double)(c.cin_real > 0 ? c.cin_real : c.Cin) * (double)c.Cout;
 }
 
 int check_shape(const ConvShape& c)

@@ -430,6 +430,49 @@ int launch_record_loss(const float* loss, float* history, int32_t* counter, int6
     return DSP_OK;
 }
 
+template <typename T>
+__global__ __launch_bounds__(kThreads) void pad_channels_kernel(const T* __restrict__ src, T* __restrict__ dst,
+                                                                int64_t pixels, int C, int Cp)
+{
+    const int64_t total = pixels * Cp;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
+        const int c = (int)(i % Cp);
+        const int64_t p = i / Cp;
+        dst[i] = c < C ? src[p * C + c] : from_float<T>(0.f);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void unpad_rows_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                              int64_t rows, int C, int Cp)
+{
+    const int64_t total = rows * C;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads)
+        dst[i] = src[(i / C) * Cp + i % C];
+}
+
+int launch_pad_channels(int dtype, const void* src, void* dst, int64_t pixels, int C, int Cp, hipStream_t st)
+{
+    DSP_REQUIRE(src && dst && pixels > 0 && C > 0 && Cp >= C, DSP_EINVAL, "pad_channels: bad argument");
+    ProfScope ps("pad_channels", (double)pixels * (C + Cp) * dtype_size(dtype), 1);
+    if (dtype == DSP_BF16)
+        DSP_LAUNCH(ps, pad_channels_kernel<bf16_t>, dim3(grid_for(pixels * Cp)), dim3(kThreads), 0, st, (const bf16_t*)src,
+                   (bf16_t*)dst, pixels, C, Cp);
+    else
+        DSP_LAUNCH(ps, pad_channels_kernel<float>, dim3(grid_for(pixels * Cp)), dim3(kThreads), 0, st, (const float*)src,
+                   (float*)dst, pixels, C, Cp);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+int launch_unpad_rows(const float* src, float* dst, int64_t rows, int C, int Cp, hipStream_t st)
+{
+    DSP_REQUIRE(src && dst && rows > 0 && C > 0 && Cp >= C, DSP_EINVAL, "unpad_rows: bad argument");
+    ProfScope ps("unpad_rows", (double)rows * C * 8.0, 1);
+    DSP_LAUNCH(ps, unpad_rows_kernel, dim3(grid_for(rows * C)), dim3(kThreads), 0, st, src, dst, rows, C, Cp);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
 int launch_spin(int microseconds, hipStream_t st)
 {
     if (microseconds <= 0) return DSP_OK;

@@ -19,6 +19,7 @@ SHAPES = [
     (4, 14, 14, 32, 128, 1, 1, 1, 0),   # 1x1
     (2, 10, 10, 128, 256, 3, 3, 1, 1),  # wide
     (2, 20, 20, 3, 64, 7, 7, 2, 3),     # stem 7x7/2
+    (2, 20, 20, 8, 64, 7, 7, 2, 3),     # the same with padded channels: 49 taps on the vector path (two mask words)
     (2, 6, 6, 8, 8, 3, 3, 1, 1),        # channel count below the tile width
     (1, 5, 5, 24, 40, 3, 3, 1, 1),      # channel counts that are no power of two
     (4, 13, 13, 16, 16, 3, 3, 2, 1),    # 16 -> 16 channels, stride 2, several slices with a ragged tail
