@@ -372,15 +372,19 @@ __global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typena
         store_tiles(0, ra0, rb0);
         load_tiles(1, ra0, rb0);
         __syncthreads();
-        for (int kt = 0; kt < nk; kt += 2) {
+        int kt = 0;
+        for (; kt + 1 < nk; kt += 2) {  // one loop body, one back edge: the accumulators stay where the MFMAs want them
             load_tiles(kt + 2, ra1, rb1);
             mma_tile<TL>(smem, smem + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
             store_tiles(1, ra0, rb0);
             __syncthreads();
-            if (kt + 1 >= nk) break;
             load_tiles(kt + 3, ra0, rb0);
             mma_tile<TL>(smem + TL::STAGE_BYTES, smem + TL::STAGE_BYTES + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
             store_tiles(0, ra1, rb1);
+            __syncthreads();
+        }
+        if (kt < nk) {  // odd number of k tiles: the last one sits in stage 0
+            mma_tile<TL>(smem, smem + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
             __syncthreads();
         }
     } else {
@@ -771,19 +775,23 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
                 for (int ch = 0; ch < E; ++ch) *(u32x4*)(base + (mt_row[i] + ch) * TL::ROWB + mt_mg[i] * 16) = tr[ch];
             }
         };
-        if (nk > 0) {
-            load_tiles(m_begin);
-            store_tiles(0);
-        }
+        // rows at or past m_end load as zeros, so the loop may fetch (and store into the idle stage) one
+        // tile past the slice: a single loop body with one back edge keeps the accumulators in place
+        load_tiles(m_begin);
+        store_tiles(0);
         __syncthreads();
-        for (int kt = 0; kt < nk; ++kt) {
-            const int cur = kt & 1;
-            if (kt + 1 < nk) load_tiles(m_begin + (kt + 1) * BKm);
-            mma_tile<TL>(smem + cur * TL::STAGE_BYTES, smem + cur * TL::STAGE_BYTES + TL::BM * TL::ROWB, wave_m, wave_n,
-                         lane, acc);
-            if (kt + 1 < nk) store_tiles(cur ^ 1);
+        int kt = 0;
+        for (; kt + 1 < nk; kt += 2) {
+            load_tiles(m_begin + (kt + 1) * BKm);
+            mma_tile<TL>(smem, smem + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
+            store_tiles(1);
+            __syncthreads();
+            load_tiles(m_begin + (kt + 2) * BKm);
+            mma_tile<TL>(smem + TL::STAGE_BYTES, smem + TL::STAGE_BYTES + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
+            store_tiles(0);
             __syncthreads();
         }
+        if (kt < nk) mma_tile<TL>(smem, smem + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
     } else {
         // generic path: element-wise loads and LDS writes
         constexpr int A_CPR = TL::BM / E, B_CPR = TL::BN / E;
