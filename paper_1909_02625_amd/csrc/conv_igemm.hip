@@ -616,7 +616,18 @@ __global__ __launch_bounds__(kThreads) void conv3x3_direct_f32_kernel(const floa
 struct WgradGeom {
     int N, H, W, Ci, Ho, Wo, Co, R, S, pad, stride;
     int M, Kdim, m_per_split;
+    uint32_t wo_mul, wo_sh, ho_mul, ho_sh;  // n / Wo and n / Ho by multiplication (fast_div)
 };
+
+// n / d for n < 2^31 with precomputed mul = floor(2^32 * (2^sh - d) / d) + 1, sh = ceil(log2 d).
+__device__ inline uint32_t fast_div(uint32_t n, uint32_t mul, uint32_t sh) { return (__umulhi(n, mul) + n) >> sh; }
+inline void fast_div_constants(uint32_t d, uint32_t* mul, uint32_t* sh)
+{
+    uint32_t s = 0;
+    while ((1ull << s) < d) ++s;
+    *sh = s;
+    *mul = (uint32_t)(((1ull << 32) * ((1ull << s) - d)) / d + 1);
+}
 
 template <typename T>
 __device__ inline void transpose_micro(const u32x4 (&in)[16 / sizeof(T)], u32x4 (&out)[16 / sizeof(T)]);
@@ -683,14 +694,14 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
         int mt_row[PER];      // LDS row of channel 0 of the micro-tile (B rows follow the BM A rows), -1 = none
         int mt_col[PER];      // global channel / column offset of the 16-byte run (-1: outside the tensor)
         int mt_mg[PER];
-        int px_n[PER], px_h[PER], px_w[PER], tap_r[PER], tap_s[PER];
+        int tap_r[PER], tap_s[PER];
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
             const int c = tid + i * kThreads;
             mt_row[i] = -1;
             mt_col[i] = -1;
             mt_mg[i] = 0;
-            px_n[i] = px_h[i] = px_w[i] = tap_r[i] = tap_s[i] = 0;
+            tap_r[i] = tap_s[i] = 0;
             if (c < NA) {
                 const int mg = c % MG, cg = c / MG;
                 mt_row[i] = cg * E;
@@ -707,11 +718,6 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
                     tap_r[i] = tap / g.S;
                     tap_s[i] = tap % g.S;
                 }
-                const int m = m_begin + mg * E;  // first row of the micro-tile in the first k step
-                px_w[i] = m % g.Wo;
-                const int t = m / g.Wo;
-                px_h[i] = t % g.Ho;
-                px_n[i] = t / g.Ho;
             }
         }
         u32x4 regs[PER][E];
@@ -734,33 +740,48 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
                         off += step;
                     }
                 } else if (c < NA + NB) {
-                    // E consecutive output pixels, one tap: walk along the image row, re-derive on wrap
-                    int n = px_n[i], h = px_h[i], w = px_w[i];
-                    int hi = h * g.stride - g.pad + tap_r[i], wi = w * g.stride - g.pad + tap_s[i];
-                    bool hok = mt_col[i] >= 0 && hi >= 0 && hi < g.H;
-                    uint32_t rowoff = (uint32_t)(((n * g.H + hi) * g.W) * g.Ci + mt_col[i]) * SZ;
+                    // E consecutive output pixels (n, h, w0 + e) of one tap.  They lie in one image row, or in
+                    // two when the run crosses a row end (Wo >= E - 1: at most one crossing); branch-free:
+                    // both rows' base offsets are formed once and every pixel picks its row.
+                    const bool col_ok = mt_col[i] >= 0;
                     const uint32_t pix = (uint32_t)g.Ci * SZ;
+                    const uint32_t tq = fast_div((uint32_t)mfirst, g.wo_mul, g.wo_sh);
+                    const int w0 = mfirst - (int)tq * g.Wo;
+                    const int n0 = (int)fast_div(tq, g.ho_mul, g.ho_sh);
+                    const int h0 = (int)tq - n0 * g.Ho;
+                    if (g.Wo >= E - 1) {
+                        const int hiA = h0 * g.stride - g.pad + tap_r[i];
+                        const bool okA = col_ok && hiA >= 0 && hiA < g.H;
+                        const uint32_t offA = (uint32_t)(((n0 * g.H + hiA) * g.W) * g.Ci + mt_col[i]) * SZ;
+                        const int wiA = w0 * g.stride - g.pad + tap_s[i];
+                        const bool last = h0 + 1 == g.Ho;
+                        const int h1 = last ? 0 : h0 + 1, n1 = n0 + (last ? 1 : 0);
+                        const int hiB = h1 * g.stride - g.pad + tap_r[i];
+                        const bool okB = col_ok && hiB >= 0 && hiB < g.H;
+                        const uint32_t offB = (uint32_t)(((n1 * g.H + hiB) * g.W) * g.Ci + mt_col[i]) * SZ;
+                        const int e_wrap = g.Wo - w0;                               // first pixel of the run in the second row
+                        const int wiB = tap_s[i] - g.pad - e_wrap * g.stride;       // so that wi = wiB + e * stride there
 #pragma unroll
-                    for (int e = 0; e < E; ++e) {
-                        const bool ok = hok && wi >= 0 && wi < g.W && mfirst + e < m_end;
-                        regs[i][e] = load16(rx, ok ? rowoff + (uint32_t)wi * pix : kOutOfRange);
-                        wi += g.stride;
-                        if (++w == g.Wo) {
-                            w = 0;
-                            wi = tap_s[i] - g.pad;
-                            if (++h == g.Ho) { h = 0; ++n; }
-                            hi = h * g.stride - g.pad + tap_r[i];
-                            hok = mt_col[i] >= 0 && hi >= 0 && hi < g.H;
-                            rowoff = (uint32_t)(((n * g.H + hi) * g.W) * g.Ci + mt_col[i]) * SZ;
+                        for (int e = 0; e < E; ++e) {
+                            const bool in_a = e < e_wrap;
+                            const int wi = (in_a ? wiA : wiB) + e * g.stride;
+                            const bool ok = (in_a ? okA : okB) && (unsigned)wi < (unsigned)g.W && mfirst + e < m_end;
+                            regs[i][e] = load16(rx, ok ? (in_a ? offA : offB) + (uint32_t)wi * pix : kOutOfRange);
+                        }
+                    } else {
+                        // rows shorter than the run: walk pixel by pixel
+                        int n = n0, h = h0, w = w0;
+#pragma unroll
+                        for (int e = 0; e < E; ++e) {
+                            const int hi = h * g.stride - g.pad + tap_r[i], wi = w * g.stride - g.pad + tap_s[i];
+                            const bool ok = col_ok && hi >= 0 && hi < g.H && wi >= 0 && wi < g.W && mfirst + e < m_end;
+                            regs[i][e] = load16(rx, ok ? (uint32_t)(((n * g.H + hi) * g.W + wi) * g.Ci + mt_col[i]) * SZ : kOutOfRange);
+                            if (++w == g.Wo) {
+                                w = 0;
+                                if (++h == g.Ho) { h = 0; ++n; }
+                            }
                         }
                     }
-                    // walk this micro-tile's first pixel to the next k step
-                    int wn = px_w[i] + BKm;
-                    while (wn >= g.Wo) {
-                        wn -= g.Wo;
-                        if (++px_h[i] == g.Ho) { px_h[i] = 0; ++px_n[i]; }
-                    }
-                    px_w[i] = wn;
                 }
             }
         };
@@ -1234,9 +1255,11 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
     constexpr int KB = sizeof(T) == 2 ? 128 : 64;
     const int dtype = sizeof(T) == 2 ? DSP_BF16 : DSP_FP32;
     const WgradPlan pl = wgrad_plan(dtype, c);
-    WgradGeom g{c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.stride, 0, 0, 0};
+    WgradGeom g{c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.stride, 0, 0, 0, 0, 0, 0, 0};
     g.M = c.N * c.Ho * c.Wo;
     g.Kdim = c.R * c.S * c.Cin;
+    fast_div_constants((uint32_t)c.Wo, &g.wo_mul, &g.wo_sh);
+    fast_div_constants((uint32_t)c.Ho, &g.ho_mul, &g.ho_sh);
     const bool c16 = wgrad_c16_eligible(dtype, c);
     const int splits = c16 ? wgrad_c16_splits(c, &g.m_per_split) : wgrad_splits(c, pl, &g.m_per_split);
     const size_t n = (size_t)c.Cout * g.Kdim;
