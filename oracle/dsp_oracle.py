@@ -104,6 +104,67 @@ def conv2d_backward_weight(x, dy, w_shape, stride, pad):
     return dw
 
 
+# ---- single output elements of the three convolutions, straight from the definition ------------------
+# For parity checks at sizes where the full fp64 convolution would take minutes: each requested element
+# is one sum over its receptive field (forward / backward-data) or over all output pixels
+# (backward-weight), written independently of the C loops above.
+def conv2d_forward_at(x, w, stride, pad, idx):
+    """y[n, k, ho, wo] for every (n, k, ho, wo) in idx; y = cross-correlation of x (NCHW) with w (KCRS)."""
+    _, _, H, W = x.shape
+    _, _, R, S = w.shape
+    out = np.zeros(len(idx))
+    for i, (n, k, ho, wo) in enumerate(idx):
+        acc = 0.0
+        for r in range(R):
+            hi = ho * stride - pad + r
+            if hi < 0 or hi >= H:
+                continue
+            for s in range(S):
+                wi = wo * stride - pad + s
+                if wi < 0 or wi >= W:
+                    continue
+                acc += float(np.dot(x[n, :, hi, wi].astype(np.float64), w[k, :, r, s].astype(np.float64)))
+        out[i] = acc
+    return out
+
+
+def conv2d_backward_data_at(dy, w, x_shape, stride, pad, idx):
+    """dx[n, c, hi, wi] for every (n, c, hi, wi) in idx: sum over the outputs (k, ho, wo) that x[n, c, hi, wi] fed."""
+    _, _, Ho, Wo = dy.shape
+    _, _, R, S = w.shape
+    out = np.zeros(len(idx))
+    for i, (n, c, hi, wi) in enumerate(idx):
+        acc = 0.0
+        for r in range(R):
+            th = hi + pad - r
+            if th < 0 or th % stride or th // stride >= Ho:
+                continue
+            for s in range(S):
+                tw = wi + pad - s
+                if tw < 0 or tw % stride or tw // stride >= Wo:
+                    continue
+                acc += float(np.dot(dy[n, :, th // stride, tw // stride].astype(np.float64), w[:, c, r, s].astype(np.float64)))
+        out[i] = acc
+    return out
+
+
+def conv2d_backward_weight_at(x, dy, stride, pad, idx):
+    """dw[k, c, r, s] for every (k, c, r, s) in idx: sum over all (n, ho, wo) of dy[n, k, ho, wo] * x[n, c, hi, wi]."""
+    _, _, H, W = x.shape
+    _, _, Ho, Wo = dy.shape
+    out = np.zeros(len(idx))
+    for i, (k, c, r, s) in enumerate(idx):
+        # output pixels whose tap (r, s) falls inside the image
+        ho = np.array([o for o in range(Ho) if 0 <= o * stride - pad + r < H], dtype=np.int64)
+        wo = np.array([o for o in range(Wo) if 0 <= o * stride - pad + s < W], dtype=np.int64)
+        if len(ho) == 0 or len(wo) == 0:
+            continue
+        xs = x[:, c][:, ho * stride - pad + r][:, :, wo * stride - pad + s].astype(np.float64)
+        gs = dy[:, k][:, ho][:, :, wo].astype(np.float64)
+        out[i] = float(np.sum(xs * gs))
+    return out
+
+
 def bn_forward(x, gamma, beta, eps):
     x, gamma, beta = _f64(x), _f64(gamma), _f64(beta)
     N, C, H, W = x.shape

@@ -88,3 +88,80 @@ def test_conv_rejects_bad_arguments():
         D.dsp_conv_backward_data(D.DSP_FP32, x, x, x, 1, 8, 8, 4, 4, 3, 3, 3, 1)  # stride 3 unsupported
     with pytest.raises(D.DSPError):
         D.dsp_conv_backward_weight(D.DSP_FP32, x, x, x, 64, 32, 32, 16, 16, 3, 3, 1, 1, None, 0)  # no workspace
+
+
+# ---- the layer shapes of the benchmark configurations at their full sizes ------------------------------
+# The large tiles (128x128, 128x64, the 128x128 backward-weight tile, the dilated vector kernel) and
+# the launch shapes bench.py times only occur at these sizes, where the full fp64 convolution would take
+# minutes: a sample of output elements is checked, each computed by the oracle from the definition, plus
+# the corners of every tensor (first / last image, channel and pixel: tile and slice tails).
+FULL = [
+    (D.DSP_FP32, 128, 32, 32, 16, 16, 3, 3, 1, 1),     # ResNet-20/56 stage 1 (register-resident filters, streaming wgrad)
+    (D.DSP_FP32, 128, 16, 16, 32, 32, 3, 3, 1, 1),     # stage 2
+    (D.DSP_FP32, 128, 8, 8, 64, 64, 3, 3, 1, 1),       # stage 3
+    (D.DSP_FP32, 128, 32, 32, 16, 32, 3, 3, 2, 1),     # stage transition, stride 2 (dilated backward-data)
+    (D.DSP_BF16, 64, 14, 14, 256, 256, 3, 3, 1, 1),    # ResNet-50 conv4_x 3x3
+    (D.DSP_BF16, 64, 14, 14, 256, 1024, 1, 1, 1, 0),   # its 1x1 expansion
+    (D.DSP_BF16, 64, 14, 14, 1024, 256, 1, 1, 1, 0),   # and reduction
+    (D.DSP_BF16, 256, 28, 28, 128, 128, 3, 3, 1, 1),   # ResNet-18 stage 2 (128x128 tiles)
+    (D.DSP_BF16, 256, 56, 56, 64, 128, 3, 3, 2, 1),    # ResNet-18 stage transition
+    (D.DSP_BF16, 256, 7, 7, 512, 512, 3, 3, 1, 1),     # ResNet-18 stage 4 (7x7 maps: pixel runs cross image rows)
+]
+
+
+def _sample(rng, shape, n):
+    corners = [tuple(0 for _ in shape), tuple(d - 1 for d in shape)]
+    rand = [tuple(int(rng.integers(0, d)) for d in shape) for _ in range(n)]
+    return corners + rand
+
+
+@pytest.mark.parametrize("cfg", FULL, ids=lambda c: ("bf16_" if c[0] == D.DSP_BF16 else "fp32_") + "x".join(map(str, c[1:])))
+def test_conv_full_size_sampled(cfg):
+    dtype, N, H, W, Ci, Co, R, S, st, pd = cfg
+    rng = np.random.default_rng(1000 + Ci * 7 + Co * 3 + H)
+    Ho, Wo = (H + 2 * pd - R) // st + 1, (W + 2 * pd - S) // st + 1
+    x = round_like(rng.standard_normal((N, Ci, H, W), dtype=np.float32), dtype)
+    w = round_like((rng.standard_normal((Co, Ci, R, S)) * np.sqrt(2.0 / (Ci * R * S))).astype(np.float32), dtype)
+    dy = round_like(rng.standard_normal((N, Co, Ho, Wo), dtype=np.float32), dtype)
+    td = torch.bfloat16 if dtype == D.DSP_BF16 else torch.float32
+    d_x, d_dy = to_dev(x, dtype), to_dev(dy, dtype)
+    d_w = torch.from_numpy(np.ascontiguousarray(w.transpose(0, 2, 3, 1))).to("cuda", td)
+    d_wt = torch.from_numpy(np.ascontiguousarray(w[:, :, ::-1, ::-1].transpose(1, 2, 3, 0))).to("cuda", td)
+    # relative to the typical magnitude of the tensor: stored bf16 has 8 mantissa bits, fp32 sums ~1e-6
+    tol = 1e-2 if dtype == D.DSP_BF16 else 1e-4
+
+    d_y = torch.full((N * Ho * Wo * Co,), float("nan"), device="cuda", dtype=td)
+    D.dsp_conv_forward(dtype, d_x, d_w, d_y, N, H, W, Ci, Co, R, S, st, pd)
+    torch.cuda.synchronize()
+    assert not torch.isnan(d_y.float()).any()
+    y = d_y.view(N, Ho, Wo, Co)
+    idx = _sample(rng, (N, Co, Ho, Wo), 48)
+    ref = O.conv2d_forward_at(x, w, st, pd, idx)
+    got = np.array([float(y[n, ho, wo, k]) for (n, k, ho, wo) in idx])
+    scale = max(np.sqrt(np.mean(ref ** 2)), 1e-6)
+    assert np.abs(got - ref).max() < tol * 4 * scale, (np.abs(got - ref).max(), scale)
+
+    d_dx = torch.full((N * H * W * Ci,), float("nan"), device="cuda", dtype=td)
+    D.dsp_conv_backward_data(dtype, d_dy, d_wt, d_dx, N, H, W, Ci, Co, R, S, st, pd, accumulate=False)
+    torch.cuda.synchronize()
+    assert not torch.isnan(d_dx.float()).any()
+    dx = d_dx.view(N, H, W, Ci)
+    idx = _sample(rng, (N, Ci, H, W), 48)
+    ref = O.conv2d_backward_data_at(dy, w, x.shape, st, pd, idx)
+    got = np.array([float(dx[n, hi, wi, c]) for (n, c, hi, wi) in idx])
+    scale = max(np.sqrt(np.mean(ref ** 2)), 1e-6)
+    assert np.abs(got - ref).max() < tol * 4 * scale, (np.abs(got - ref).max(), scale)
+
+    ws_bytes = D.dsp_conv_workspace_bytes(N, H, W, Ci, Co, R, S, st, pd)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    d_dw = torch.full((Co * R * S * Ci,), float("nan"), device="cuda", dtype=torch.float32)
+    D.dsp_conv_backward_weight(dtype, d_x, d_dy, d_dw, N, H, W, Ci, Co, R, S, st, pd, ws, ws_bytes)
+    torch.cuda.synchronize()
+    assert not torch.isnan(d_dw).any()
+    dw = d_dw.view(Co, R, S, Ci)
+    idx = _sample(rng, (Co, Ci, R, S), 24)
+    ref = O.conv2d_backward_weight_at(x, dy, st, pd, idx)
+    got = np.array([float(dw[k, r, s, c]) for (k, c, r, s) in idx])
+    scale = max(np.sqrt(np.mean(ref ** 2)), 1e-6)
+    # fp32 accumulation over N*Ho*Wo products of unit-variance terms
+    assert np.abs(got - ref).max() < 1e-3 * scale, (np.abs(got - ref).max(), scale)

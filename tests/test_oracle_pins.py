@@ -488,3 +488,24 @@ def test_bf16_gradient_reproducibility_floor():
     rel = lambda a, b: np.linalg.norm(a - b) / np.linalg.norm(b)  # noqa: E731
     assert rel(out2, out) < 3e-2
     assert rel(gh2, gh) > 5e-2 and rel(gh2, gh) > 3 * rel(out2, out)
+
+
+@pytest.mark.parametrize("shape", [(2, 5, 9, 8, 4, 3, 3, 1, 1), (3, 4, 10, 10, 6, 3, 3, 2, 1), (2, 3, 12, 11, 5, 7, 7, 2, 3),
+                                   (2, 6, 7, 7, 4, 1, 1, 2, 0)])
+def test_single_element_convolutions_agree_with_the_full_ones(shape):
+    """The per-element definitions used for full-size GPU parity are written independently (numpy slicing)
+    of the C loops; on small problems every element of both must agree."""
+    N, C, H, W, K, R, S, st, pd = shape
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((N, C, H, W))
+    w = rng.standard_normal((K, C, R, S))
+    y = O.conv2d_forward(x, w, st, pd)
+    dy = rng.standard_normal(y.shape)
+    dx = O.conv2d_backward_data(dy, w, x.shape, st, pd)
+    dw = O.conv2d_backward_weight(x, dy, w.shape, st, pd)
+    iy = [tuple(int(v) for v in np.unravel_index(i, y.shape)) for i in range(y.size)]
+    ix = [tuple(int(v) for v in np.unravel_index(i, x.shape)) for i in range(x.size)]
+    iw = [tuple(int(v) for v in np.unravel_index(i, w.shape)) for i in range(w.size)]
+    np.testing.assert_allclose(O.conv2d_forward_at(x, w, st, pd, iy), y.ravel(), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(O.conv2d_backward_data_at(dy, w, x.shape, st, pd, ix), dx.ravel(), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(O.conv2d_backward_weight_at(x, dy, st, pd, iw), dw.ravel(), rtol=1e-11, atol=1e-11)
