@@ -174,6 +174,10 @@ labels_by_batch = {}
     ("resnet50_conv4x", D.DSP_BF16, 5, {"batch": 4, "hw": 14, "norelu": True}),
     ("resnet50_conv4x", D.DSP_BF16, 5, {"batch": 4, "hw": 14}),
     ("resnet20", D.DSP_FP32, 7, {"batch": 4, "hw": 8, "p": (1, 1, 0), "m": (7, 3, 1)}),  # last block stale too
+    # normalisation, shortcut and 1x1 conv kernels at ImageNet-sized maps (M = 401408 rows, 3136 conv tiles
+    # of fused statistics, 512 partial sums per channel): full size, every element compared
+    ("bn_probe", D.DSP_FP32, 3, {"many_decisions": True}),
+    ("bn_probe", D.DSP_BF16, 3, {}),
 ], ids=lambda v: v if isinstance(v, str) else None)
 def test_block_step_teacher_forced(name, dtype, ticks, kw):
     cfg, params, rng = _setup(name, **kw)

@@ -134,6 +134,17 @@ def _resnet50_conv4x():
     return [b.layers]
 
 
+def _bn_probe():
+    """Two 1x1 conv + BN(+ReLU) layers, the second with an identity shortcut from the block input: a cheap
+    block whose normalisation layers can be checked against the oracle at ImageNet-sized feature maps."""
+    b = _B()
+    a = b.conv(-1, 64, 64, 1, 1, pad=0)
+    a = b.bn(a, 64, relu=True)
+    a = b.conv(a, 64, 64, 1, 1, pad=0)
+    b.bn(a, 64, relu=True, res=-1)
+    return [b.layers]
+
+
 # ----------------------------------------------------------------------------- configs
 CONFIGS = {
     # name: blocks, input (N, C, H, W), classes, DSP(p; m), lr, momentum, weight decay, steps, seed, dtype
@@ -147,6 +158,9 @@ CONFIGS = {
     "resnet50_conv4x": dict(blocks=_resnet50_conv4x, input=(64, 512, 28, 28), classes=None, p=(0,), m=(3,),
                             lr=0.01, beta=0.9, wd=0.0, steps=20, seed=3, dtypes=("bf16",), grad_std=0.1,
                             data_input=False),
+    # not one of the paper-shaped workloads: a parity probe for the streaming kernels at large M (tests only)
+    "bn_probe": dict(blocks=_bn_probe, input=(128, 64, 56, 56), classes=None, p=(0,), m=(1,), lr=0.01, beta=0.9,
+                     wd=0.0, steps=3, seed=5, dtypes=("fp32", "bf16"), grad_std=0.1, data_input=False),
     "resnet18": dict(blocks=_resnet18, input=(256, 3, 224, 224), classes=1000, p=(1, 1, 1, 0), m=(6, 4, 2, 0),
                      lr=0.01, beta=0.9, wd=0.0, steps=20, seed=4, dtypes=("bf16",)),
 }
