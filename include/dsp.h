@@ -161,10 +161,20 @@ int dsp_block_step(dsp_block* b, int64_t batch_fwd, const void* d_in, void* d_ou
                    int64_t batch_bwd, const void* d_grad_out, void* d_grad_in, void* stream);
 
 /*
- * Momentum SGD (Eq. (3), s = 0, constant step): v <- momentum * v + (G + weight_decay * x),
- * x <- x - lr * v; weight_decay acts on conv/linear weights only.  Consumes the pending G_{x_k}
- * exactly once (DSP_ESTATE if there is none) and increments the update counter.
+ * Stochastic unified momentum, Eq. (3), for s = 0 (heavy ball) and s = 1 (Nesterov), in velocity
+ * form: with G' = G + weight_decay * x (conv/linear weights only),
+ *     v <- momentum * v + G',   x <- x - lr * v                      (s = 0)
+ *     v <- momentum * v + G',   x <- x - lr * (G' + momentum * v)    (s = 1)
+ * which is the (y, y^s) recursion of Eq. (3) with y^{s,0} = x^0, v^0 = 0 and v^n = -(x^n - x^{n-1}) / lr
+ * for s = 0, v^n = -(y^n - y^{n-1}) / lr for s = 1.
+ * The block remembers the step size of its previous update; when lr differs from it, v is first
+ * multiplied by (previous lr / lr), so that the momentum term stays the difference of iterates that
+ * Eq. (3) prescribes under a learning-rate schedule.  lr = 0 leaves x unchanged (exact for
+ * momentum = 0).  Other values of s need the previous gradient and are refused (DSP_EINVAL).
+ * Consumes the pending G_{x_k} exactly once (DSP_ESTATE if there is none) and increments the
+ * update counter.  dsp_param_update is the s = 0 case.
  */
+int dsp_param_update_sum(dsp_block* b, float lr, float momentum, int32_t s, float weight_decay, void* stream);
 int dsp_param_update(dsp_block* b, float lr, float momentum, float weight_decay, void* stream);
 
 /*
@@ -224,6 +234,12 @@ int dsp_pipeline_destroy(dsp_pipeline* pl);
  */
 int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_labels, float* h_loss,
                       int64_t* loss_batch_id, void* stream);
+
+/*
+ * Step size, momentum constant, s of Eq. (3) (0 or 1) and weight decay used by the updates of all
+ * later ticks (a step learning-rate schedule calls this between steps; dsp_pipeline_init sets s = 0).
+ */
+int dsp_pipeline_set_optimizer(dsp_pipeline* pl, float lr, float momentum, int32_t s, float weight_decay);
 
 /*
  * How the launches of a tick reach the GPU (results are bit-identical in every mode):

@@ -373,6 +373,8 @@ class SUM:
         x^{n+1}   = y^{n+1} + beta (y^{s,n+1} - y^{s,n}),       y^{s,0} = x^0.
 
     s = 0 is heavy-ball momentum SGD (the optimiser of the paper's experiments), beta = 0 is SGD.
+    ``alpha`` may be changed between steps (a learning-rate schedule): the recursion is applied as
+    written, so the momentum term stays the difference of the stored iterates y^s.
     Works on any list of objects supporting + - * (numpy arrays, Fractions).
     """
 
@@ -382,20 +384,23 @@ class SUM:
         self.mask = decay_mask or [True] * len(x0)
         self.n_updates = 0
         self.last_step = None  # x^{n+1} - x^n of the latest update
+        self.last_ys_step = None  # y^{s,n+1} - y^{s,n} of the latest update, and the alpha it was taken with
+        self.last_alpha = None
 
     def step(self, x, G):
-        new, step = [], []
+        new, step, ys_step = [], [], []
         for i, (xi, gi) in enumerate(zip(x, G)):
             if self.wd and self.mask[i]:
                 gi = gi + self.wd * xi
             y = xi - self.alpha * gi
             ys = xi - self.s * self.alpha * gi
             xn = y + self.beta * (ys - self.ys[i])
+            ys_step.append(ys - self.ys[i])
             self.ys[i] = ys
             new.append(xn)
             step.append(xn - xi)
         self.n_updates += 1
-        self.last_step = step
+        self.last_step, self.last_ys_step, self.last_alpha = step, ys_step, self.alpha
         return new
 
 

@@ -15,7 +15,7 @@ __all__ = [
     "dsp_layer_desc", "dsp_block_desc", "make_block_desc",
     "dsp_schedule_validate", "dsp_schedule_index", "dsp_schedule_queue_elems",
     "dsp_block_init", "dsp_block_destroy", "dsp_block_forward", "dsp_block_recompute_backward",
-    "dsp_param_update", "dsp_block_input_slot", "dsp_block_query", "dsp_block_output_shape",
+    "dsp_param_update", "dsp_param_update_sum", "dsp_pipeline_set_optimizer", "dsp_block_input_slot", "dsp_block_query", "dsp_block_output_shape",
     "dsp_block_input_shape", "dsp_block_memory", "dsp_block_get_params", "dsp_block_set_params",
     "dsp_block_get_momentum", "dsp_block_set_momentum", "dsp_block_get_grads",
     "dsp_pipeline_init", "dsp_pipeline_destroy", "dsp_pipeline_step", "dsp_pipeline_set_delay",
@@ -85,6 +85,8 @@ _SIGNATURES = {
     "dsp_block_forward": [_vp, _i64, _vp, _vp, _vp, _vp, _vp],
     "dsp_block_recompute_backward": [_vp, _i64, _vp, _vp, _vp],
     "dsp_param_update": [_vp, _f, _f, _f, _vp],
+    "dsp_param_update_sum": [_vp, _f, _f, _i32, _f, _vp],
+    "dsp_pipeline_set_optimizer": [_vp, _f, _f, _i32, _f],
     "dsp_block_input_slot": [_vp, _i64, C.POINTER(_vp)],
     "dsp_block_query": [_vp, _pi64],
     "dsp_block_output_shape": [_vp, _pi32],
@@ -226,6 +228,14 @@ def dsp_block_step(b, batch_fwd, d_in, d_out=None, d_labels=None, d_loss=None, b
 
 def dsp_param_update(b, lr, momentum, weight_decay=0.0, stream=None):
     check(lib().dsp_param_update(b, lr, momentum, weight_decay, _stream(stream)), "dsp_param_update")
+
+
+def dsp_param_update_sum(b, lr, momentum, s=0, weight_decay=0.0, stream=None):
+    check(lib().dsp_param_update_sum(b, lr, momentum, int(s), weight_decay, _stream(stream)), "dsp_param_update_sum")
+
+
+def dsp_pipeline_set_optimizer(pl, lr, momentum, s=0, weight_decay=0.0):
+    check(lib().dsp_pipeline_set_optimizer(pl, lr, momentum, int(s), weight_decay), "dsp_pipeline_set_optimizer")
 
 
 def dsp_block_input_slot(b, batch_id):

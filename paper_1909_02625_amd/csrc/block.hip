@@ -97,6 +97,7 @@ struct Layer {
     int cin_pad = 0;
     void* xpad = nullptr;     // padded input of the pass the backward sweep belongs to
     float* dw_pad = nullptr;  // filter gradient in the padded layout
+    size_t wg_off = 0, wg_bytes = 0;  // conv: this layer's region of the partial-gradient workspace
 };
 
 }  // namespace dsp
@@ -143,8 +144,10 @@ struct dsp_block {
     float* row_loss = nullptr;
     float* loss_sink = nullptr;
 
-    void* wgrad_ws = nullptr;
+    float last_lr = 0.f;  // step size of the latest update (the velocity is stored in its units)
+    void* wgrad_ws = nullptr;  // per-slice partial weight gradients, one region per conv layer
     size_t wgrad_ws_bytes = 0;
+    WgradReduceSet* wgrad_set = nullptr;  // sums all regions in one launch at the end of the backward sweep
     double* bn_partial = nullptr;
     float* bn_coef = nullptr;
     size_t bn_partial_elems = 0;
@@ -363,12 +366,24 @@ static int build_graph(dsp_block* b)
             DSP_TRY(dev_alloc(b, (void**)&L.dw_pad, (size_t)L.cs.Cout * L.cs.R * L.cs.S * L.cin_pad * 4, &b->ws_bytes));
         }
         if (L.d.op == DSP_OP_CONV) {
-            const size_t w = conv_backward_weight_workspace(L.cs);
-            if (w > ws) ws = w;
+            L.wg_off = ws;
+            L.wg_bytes = (conv_backward_weight_workspace(L.cs) + 255) & ~(size_t)255;
+            ws += L.wg_bytes;
         }
     }
     b->wgrad_ws_bytes = ws;
     DSP_TRY(dev_alloc(b, &b->wgrad_ws, ws, &b->ws_bytes));
+    {
+        std::vector<WgradReduceItem> items;
+        for (Layer& L : b->layers) {
+            if (L.d.op != DSP_OP_CONV) continue;
+            float* dw = L.cin_pad ? L.dw_pad : b->g + L.p0;
+            items.push_back(WgradReduceItem{(const float*)((char*)b->wgrad_ws + L.wg_off), dw,
+                                            (size_t)L.cs.Cout * L.cs.R * L.cs.S * L.cs.Cin,
+                                            conv_backward_weight_slices(b->dtype, L.cs)});
+        }
+        DSP_TRY(wgrad_reduce_set_create(items.data(), (int)items.size(), &b->wgrad_set));
+    }
     size_t partial_elems = (size_t)bn_max_partial_blocks() * max_c;
     for (int i = 0; i + 1 < d.n_layers; ++i) {
         Layer& L = b->layers[i];
@@ -511,12 +526,10 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
         const void* dy = (i == b->out_idx) ? gout : b->T[i].grad;
         switch (L.d.op) {
         case DSP_OP_CONV:
-            if (L.cin_pad) {
-                DSP_TRY(launch_conv_backward_weight(b->dtype, L.cs, L.xpad, dy, L.dw_pad, b->wgrad_ws, b->wgrad_ws_bytes, st));
-                DSP_TRY(launch_unpad_rows(L.dw_pad, b->g + L.p0, (int64_t)L.cs.Cout * L.cs.R * L.cs.S, L.d.cin, L.cin_pad, st));
-            } else {
-                DSP_TRY(launch_conv_backward_weight(b->dtype, L.cs, src, dy, b->g + L.p0, b->wgrad_ws, b->wgrad_ws_bytes, st));
-            }
+            // per-slice partial sums only; they are summed for all layers after the sweep
+            DSP_TRY(launch_conv_backward_weight(b->dtype, L.cs, L.cin_pad ? L.xpad : src, dy,
+                                                L.cin_pad ? L.dw_pad : b->g + L.p0, (char*)b->wgrad_ws + L.wg_off,
+                                                L.wg_bytes, st, /*defer_reduce=*/true));
             if (L.in0_grad)
                 DSP_TRY(launch_conv_backward_data(b->dtype, L.cs, dy, weights_for_dgrad(b, L), grad_of(L.d.in0), L.in0_acc, st));
             break;
@@ -546,6 +559,10 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
             break;
         }
     }
+    DSP_TRY(wgrad_reduce_set_launch(b->wgrad_set, st));
+    for (Layer& L : b->layers)
+        if (L.d.op == DSP_OP_CONV && L.cin_pad)
+            DSP_TRY(launch_unpad_rows(L.dw_pad, b->g + L.p0, (int64_t)L.cs.Cout * L.cs.R * L.cs.S, L.d.cin, L.cin_pad, st));
     return DSP_OK;
 }
 
@@ -592,6 +609,7 @@ int dsp_block_destroy(dsp_block* b)
     if (!b) return DSP_OK;
     (void)hipDeviceSynchronize();
     for (void* p : b->allocs) (void)hipFree(p);
+    wgrad_reduce_set_destroy(b->wgrad_set);
     delete b->fwd_lane;
     delete b;
     return DSP_OK;
@@ -759,16 +777,29 @@ int dsp_block_step(dsp_block* b, int64_t batch_fwd, const void* d_in, void* d_ou
     return DSP_OK;
 }
 
-int dsp_param_update(dsp_block* b, float lr, float momentum, float weight_decay, void* stream)
+int dsp_param_update_sum(dsp_block* b, float lr, float momentum, int32_t s, float weight_decay, void* stream)
 {
     DSP_REQUIRE(b, DSP_EINVAL, "dsp_param_update: null block");
+    DSP_REQUIRE(s == 0 || s == 1, DSP_EINVAL, "dsp_param_update: s = %d (only s = 0 and s = 1 are built)", (int)s);
+    DSP_REQUIRE(lr >= 0.f, DSP_EINVAL, "dsp_param_update: negative step size");
     DSP_REQUIRE(b->pending, DSP_ESTATE, "dsp_param_update: no pending gradient");
     b->pending = false;
     b->version += 1;
+    // the stored velocity is in units of the step size of the update that wrote it
+    float v_scale = 1.f;
+    if (lr > 0.f) {
+        if (b->last_lr > 0.f && b->last_lr != lr) v_scale = b->last_lr / lr;
+        b->last_lr = lr;
+    }
     if (b->dry) return DSP_OK;
     DSP_TRY(launch_sgd_update(b->dtype, b->x, b->v, b->g, b->decay, b->tmap, b->wf16, b->wt, b->nP, lr, momentum,
-                              weight_decay, (hipStream_t)stream));
+                              weight_decay, (hipStream_t)stream, s == 1, v_scale));
     return DSP_OK;
+}
+
+int dsp_param_update(dsp_block* b, float lr, float momentum, float weight_decay, void* stream)
+{
+    return dsp_param_update_sum(b, lr, momentum, 0, weight_decay, stream);
 }
 
 int dsp_block_query(const dsp_block* b, int64_t out[8])

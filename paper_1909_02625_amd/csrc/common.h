@@ -128,8 +128,21 @@ int conv_forward_row_tiles(int dtype, const ConvShape& c);
 int launch_conv_backward_data(int dtype, const ConvShape& c, const void* dy, const void* wt, void* dx,
                               bool accumulate, hipStream_t st);
 // dw[Cout][R][S][Cin] (float) = sum over (n, ho, wo) of dy * x;  ws holds the split partials.
+// defer_reduce: write the per-slice partial sums to ws only; the caller sums them later (for all its layers
+// at once, wgrad_reduce_set_*).  conv_backward_weight_slices = number of slices (1: dw is written directly).
 int launch_conv_backward_weight(int dtype, const ConvShape& c, const void* x, const void* dy, float* dw, void* ws,
-                                size_t ws_bytes, hipStream_t st);
+                                size_t ws_bytes, hipStream_t st, bool defer_reduce = false);
+int conv_backward_weight_slices(int dtype, const ConvShape& c);
+struct WgradReduceItem {
+    const float* partials;  // [slices][n]
+    float* dw;              // [n]
+    size_t n;
+    int slices;
+};
+struct WgradReduceSet;
+int wgrad_reduce_set_create(const WgradReduceItem* items, int n, WgradReduceSet** out);
+int wgrad_reduce_set_launch(const WgradReduceSet* s, hipStream_t st);
+void wgrad_reduce_set_destroy(WgradReduceSet* s);
 size_t conv_backward_weight_workspace(const ConvShape& c);
 
 // ---- batch norm (+ residual + ReLU) launchers (bn.hip) ----------------------------------------
@@ -178,7 +191,8 @@ int launch_softmax_ce(const float* z, const int32_t* labels, float* loss, float*
 // v <- momentum*v + (g + wd*x*[decay]);  x <- x - lr*v;  shadow copies refreshed in the same pass:
 // wf16[i] = bf16(x[i]) if wf16 != nullptr;  wt[tmap[i]] = T(x[i]) where tmap[i] >= 0.
 int launch_sgd_update(int dtype, float* x, float* v, const float* g, const uint8_t* decay, const int32_t* tmap,
-                      void* wf16, void* wt, size_t n, float lr, float momentum, float wd, hipStream_t st);
+                      void* wf16, void* wt, size_t n, float lr, float momentum, float wd, hipStream_t st,
+                      bool nesterov = false, float v_scale = 1.f);
 // Same shadow refresh without an update (after init / set_params).
 int launch_refresh_shadows(int dtype, const float* x, const int32_t* tmap, void* wf16, void* wt, size_t n,
                            hipStream_t st);

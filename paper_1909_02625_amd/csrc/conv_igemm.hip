@@ -19,6 +19,8 @@
 #include <stdio.h>
 
 #include <atomic>
+#include <new>
+#include <vector>
 
 #include "common.h"
 
@@ -1040,6 +1042,78 @@ __global__ __launch_bounds__(256) void wgrad_reduce_few_kernel(const float* __re
         dw[i] = s[0];
 }
 
+// All slice sums of a block's conv layers in ONE launch (the per-layer sums are tiny and the idle gap
+// between two launches costs as much as each of them).  A workgroup looks up its task and then does
+// exactly what the two kernels above do: the tree over 32 elements when the task has more than 8
+// slices, else the flat loop over 1024 elements.
+struct ReduceTask {
+    const float* part;
+    float* dw;
+    int n, splits;
+    int block_begin;  // first workgroup of the task
+};
+
+template <int VW>
+__global__ __launch_bounds__(256) void wgrad_reduce_all_kernel(const ReduceTask* __restrict__ tasks, int n_tasks)
+{
+    constexpr int COLS = 32 / VW, ROWS = 256 / COLS;
+    __shared__ float red[ROWS][33];
+    int p = 0;
+    while (p + 1 < n_tasks && (int)blockIdx.x >= tasks[p + 1].block_begin) ++p;
+    const ReduceTask t = tasks[p];
+    const int blk = (int)blockIdx.x - t.block_begin;
+    const float* __restrict__ part = t.part;
+    const int n = t.n, splits = t.splits;
+    if (splits <= 8) {  // uniform per workgroup
+        const int64_t i = ((int64_t)blk * 256 + threadIdx.x) * VW;
+        if (i >= n) return;
+        float s[VW];
+#pragma unroll
+        for (int v = 0; v < VW; ++v) s[v] = 0.f;
+        for (int k = 0; k < splits; ++k) {
+            const float* src = part + (int64_t)k * n + i;
+            if (VW == 4) {
+                const f32x4 v4 = *(const f32x4*)src;
+#pragma unroll
+                for (int v = 0; v < VW; ++v) s[v] += v4[v];
+            } else {
+                s[0] += src[0];
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < VW; ++v) t.dw[i + v] = s[v];
+        return;
+    }
+    const int cg = threadIdx.x % COLS, row = threadIdx.x / COLS;
+    const int i = blk * 32 + cg * VW;
+    float s[VW];
+#pragma unroll
+    for (int v = 0; v < VW; ++v) s[v] = 0.f;
+    if (i < n) {
+#pragma unroll 4
+        for (int k = row; k < splits; k += ROWS) {
+            const float* src = part + (int64_t)k * n + i;
+            if (VW == 4) {
+                const f32x4 v4 = *(const f32x4*)src;
+#pragma unroll
+                for (int v = 0; v < VW; ++v) s[v] += v4[v];
+            } else {
+                s[0] += src[0];
+            }
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < VW; ++v) red[row][cg * VW + v] = s[v];
+    __syncthreads();
+    const int c = threadIdx.x;
+    if (c < 32 && blk * 32 + c < n) {
+        float acc = red[0][c];
+#pragma unroll 8
+        for (int k = 1; k < ROWS; ++k) acc += red[k][c];
+        t.dw[blk * 32 + c] = acc;
+    }
+}
+
 // ---- host-side dispatch -------------------------------------------------------------------------
 struct KernelName {
     char text[96];
@@ -1249,7 +1323,7 @@ int wgrad_c16_splits(const ConvShape& c, int* m_per_split)
 
 template <typename T>
 int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes,
-                   hipStream_t st, double flops)
+                   hipStream_t st, double flops, bool defer_reduce)
 {
     constexpr int E = 16 / (int)sizeof(T);
     constexpr int KB = sizeof(T) == 2 ? 128 : 64;
@@ -1288,7 +1362,7 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
     default: rc = run_wgrad_v<Tile<T, 32, 2, 2, 1, 1, KB, 2>>(g, splits, vec, x, dy, dst, st, flops); break;
     }
     DSP_TRY(rc);
-    if (splits > 1) {
+    if (splits > 1 && !defer_reduce) {
         ProfScope ps("wgrad_reduce", (double)n * (splits + 1) * 4.0, 1);
         const bool v4 = n % 4 == 0 && ((uintptr_t)ws % 16) == 0 && ((uintptr_t)dw % 16) == 0;
         if (splits <= 8 && v4)
@@ -1422,12 +1496,81 @@ size_t conv_backward_weight_workspace(const ConvShape& c)
 }
 
 int launch_conv_backward_weight(int dtype, const ConvShape& c, const void* x, const void* dy, float* dw, void* ws,
-                                size_t ws_bytes, hipStream_t st)
+                                size_t ws_bytes, hipStream_t st, bool defer_reduce)
 {
     DSP_TRY(check_shape(c));
     const double flops = 2.0 * conv_macs(c);
-    return dtype == DSP_BF16 ? dispatch_wgrad<bf16_t>(c, x, dy, dw, ws, ws_bytes, st, flops)
-                             : dispatch_wgrad<float>(c, x, dy, dw, ws, ws_bytes, st, flops);
+    return dtype == DSP_BF16 ? dispatch_wgrad<bf16_t>(c, x, dy, dw, ws, ws_bytes, st, flops, defer_reduce)
+                             : dispatch_wgrad<float>(c, x, dy, dw, ws, ws_bytes, st, flops, defer_reduce);
+}
+
+int conv_backward_weight_slices(int dtype, const ConvShape& c)
+{
+    // aligned 16-byte tensors assumed (the slicing does not depend on the alignment)
+    int per;
+    if (wgrad_c16_eligible(dtype, c)) return wgrad_c16_splits(c, &per);
+    return wgrad_splits(c, wgrad_plan(dtype, c), &per);
+}
+
+struct WgradReduceSet {
+    ReduceTask* d_tasks = nullptr;
+    int n_tasks = 0, blocks = 0;
+    bool vec4 = true;
+    double bytes = 0;
+};
+
+int wgrad_reduce_set_create(const WgradReduceItem* items, int n, WgradReduceSet** out)
+{
+    DSP_REQUIRE(out && (n == 0 || items), DSP_EINVAL, "wgrad_reduce_set_create: null argument");
+    *out = nullptr;
+    WgradReduceSet* s = new (std::nothrow) WgradReduceSet();
+    DSP_REQUIRE(s, DSP_ENOMEM, "wgrad_reduce_set_create: out of host memory");
+    std::vector<ReduceTask> tasks;
+    for (int i = 0; i < n; ++i) {
+        const WgradReduceItem& it = items[i];
+        if (it.slices <= 1) continue;
+        if (it.n % 4 != 0 || ((uintptr_t)it.partials % 16) != 0 || ((uintptr_t)it.dw % 16) != 0) s->vec4 = false;
+    }
+    for (int i = 0; i < n; ++i) {
+        const WgradReduceItem& it = items[i];
+        if (it.slices <= 1) continue;
+        tasks.push_back(ReduceTask{it.partials, it.dw, (int)it.n, it.slices, s->blocks});
+        const int per_block = it.slices <= 8 ? 256 * (s->vec4 ? 4 : 1) : 32;
+        s->blocks += ceil_div((int64_t)it.n, per_block);
+        s->bytes += (double)it.n * (it.slices + 1) * 4.0;
+    }
+    s->n_tasks = (int)tasks.size();
+    if (s->n_tasks > 0) {
+        if (hipMalloc((void**)&s->d_tasks, tasks.size() * sizeof(ReduceTask)) != hipSuccess ||
+            hipMemcpy(s->d_tasks, tasks.data(), tasks.size() * sizeof(ReduceTask), hipMemcpyHostToDevice) != hipSuccess) {
+            set_error("wgrad_reduce_set_create: device table allocation failed");
+            if (s->d_tasks) (void)hipFree(s->d_tasks);
+            delete s;
+            return DSP_ENOMEM;
+        }
+    }
+    *out = s;
+    return DSP_OK;
+}
+
+void wgrad_reduce_set_destroy(WgradReduceSet* s)
+{
+    if (!s) return;
+    if (s->d_tasks) (void)hipFree(s->d_tasks);
+    delete s;
+}
+
+int wgrad_reduce_set_launch(const WgradReduceSet* s, hipStream_t st)
+{
+    DSP_REQUIRE(s, DSP_EINVAL, "wgrad_reduce_set_launch: null set");
+    if (s->n_tasks == 0) return DSP_OK;
+    ProfScope ps("wgrad_reduce_all", s->bytes, 1);
+    if (s->vec4)
+        DSP_LAUNCH(ps, wgrad_reduce_all_kernel<4>, dim3(s->blocks), dim3(256), 0, st, (const ReduceTask*)s->d_tasks, s->n_tasks);
+    else
+        DSP_LAUNCH(ps, wgrad_reduce_all_kernel<1>, dim3(s->blocks), dim3(256), 0, st, (const ReduceTask*)s->d_tasks, s->n_tasks);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
 }
 
 }  // namespace dsp

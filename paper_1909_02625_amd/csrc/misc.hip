@@ -233,20 +233,25 @@ __global__ __launch_bounds__(64) void mean_kernel(const float* __restrict__ v, f
 }
 
 // ---- momentum SGD + shadow refresh ---------------------------------------------------------------
-template <typename TS, bool UPDATE>
+// Eq. (3) in velocity form: v <- beta v + G, then x <- x - alpha v for s = 0 (v^n = -(x^n - x^{n-1}) / alpha)
+// and x <- x - alpha (G + beta v) for s = 1 (v^n = -(y^n - y^{n-1}) / alpha).
+// v_scale = (previous step size) / (this step size) keeps the form exact across a change of alpha:
+// the momentum term of Eq. (3) is a difference of iterates, not of gradients, so it is not rescaled
+// by the new step size.
+template <typename TS, bool UPDATE, bool NESTEROV = false>
 __global__ void sgd_update_kernel(float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
                                   const uint8_t* __restrict__ decay, const int32_t* __restrict__ tmap,
                                   bf16_t* __restrict__ wf16, TS* __restrict__ wt, size_t n, float lr, float momentum,
-                                  float wd)
+                                  float wd, float v_scale)
 {
     for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (size_t)gridDim.x * kThreads) {
         float xi = x[i];
         if (UPDATE) {
             float gi = g[i];
             if (wd != 0.f && decay[i]) gi += wd * xi;
-            const float vi = momentum * v[i] + gi;
+            const float vi = momentum * (v[i] * v_scale) + gi;
             v[i] = vi;
-            xi -= lr * vi;
+            xi -= lr * (NESTEROV ? gi + momentum * vi : vi);
             x[i] = xi;
         }
         if (wf16) wf16[i] = float_to_bf16(xi);
@@ -389,18 +394,25 @@ int launch_softmax_ce(const float* z, const int32_t* labels, float* loss, float*
 }
 
 int launch_sgd_update(int dtype, float* x, float* v, const float* g, const uint8_t* decay, const int32_t* tmap,
-                      void* wf16, void* wt, size_t n, float lr, float momentum, float wd, hipStream_t st)
+                      void* wf16, void* wt, size_t n, float lr, float momentum, float wd, hipStream_t st, bool nesterov,
+                      float v_scale)
 {
     if (n == 0) return DSP_OK;
     const dim3 grid(grid_for((int64_t)n));
     // read x, v, g, the weight-decay flag and the filter-copy index; write x, v and the shadow copies
     ProfScope ps(dtype == DSP_BF16 ? "sgd_update<bf16 shadows>" : "sgd_update<fp32>", (double)n * 29.0, 1);
-    if (dtype == DSP_BF16)
+    if (dtype == DSP_BF16 && nesterov)
+        DSP_LAUNCH(ps, (sgd_update_kernel<bf16_t, true, true>), grid, dim3(kThreads), 0, st, x, v, g, decay, tmap,
+                   (bf16_t*)wf16, (bf16_t*)wt, n, lr, momentum, wd, v_scale);
+    else if (dtype == DSP_BF16)
         DSP_LAUNCH(ps, (sgd_update_kernel<bf16_t, true>), grid, dim3(kThreads), 0, st, x, v, g, decay, tmap,
-                   (bf16_t*)wf16, (bf16_t*)wt, n, lr, momentum, wd);
+                   (bf16_t*)wf16, (bf16_t*)wt, n, lr, momentum, wd, v_scale);
+    else if (nesterov)
+        DSP_LAUNCH(ps, (sgd_update_kernel<float, true, true>), grid, dim3(kThreads), 0, st, x, v, g, decay, tmap,
+                   (bf16_t*)nullptr, (float*)wt, n, lr, momentum, wd, v_scale);
     else
         DSP_LAUNCH(ps, (sgd_update_kernel<float, true>), grid, dim3(kThreads), 0, st, x, v, g, decay, tmap,
-                   (bf16_t*)nullptr, (float*)wt, n, lr, momentum, wd);
+                   (bf16_t*)nullptr, (float*)wt, n, lr, momentum, wd, v_scale);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }
@@ -413,11 +425,11 @@ int launch_refresh_shadows(int dtype, const float* x, const int32_t* tmap, void*
     if (dtype == DSP_BF16)
         hipLaunchKernelGGL((sgd_update_kernel<bf16_t, false>), grid, dim3(kThreads), 0, st, (float*)x, (float*)nullptr,
                            (const float*)nullptr, (const uint8_t*)nullptr, tmap, (bf16_t*)wf16, (bf16_t*)wt, n, 0.f, 0.f,
-                           0.f);
+                           0.f, 1.f);
     else
         hipLaunchKernelGGL((sgd_update_kernel<float, false>), grid, dim3(kThreads), 0, st, (float*)x, (float*)nullptr,
                            (const float*)nullptr, (const uint8_t*)nullptr, tmap, (bf16_t*)nullptr, (float*)wt, n, 0.f,
-                           0.f, 0.f);
+                           0.f, 0.f, 1.f);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }

@@ -73,6 +73,8 @@ struct dsp_pipeline {
     std::vector<dsp_block*> blocks;
     std::vector<int32_t> p, m, q, P;  // P[k] = sum_{j<k} p_j
     float lr = 0, momentum = 0, wd = 0;
+    int sum_s = 0;        // Eq. (3): 0 heavy ball, 1 Nesterov
+    int eager_ticks = 0;  // ticks to run unrecorded (the update after a step-size change rescales the velocity once)
     std::vector<hipStream_t> streams;
     std::vector<hipEvent_t> done[2];  // done[tau % 2][k]: block k finished tick tau
     // Forward streams: a block with m_k > 0 runs forward(a) here while its main stream runs
@@ -361,6 +363,20 @@ int dsp_pipeline_set_delay(dsp_pipeline* pl, int32_t k, int32_t microseconds)
     return DSP_OK;
 }
 
+int dsp_pipeline_set_optimizer(dsp_pipeline* pl, float lr, float momentum, int32_t s, float weight_decay)
+{
+    DSP_REQUIRE(pl, DSP_EINVAL, "dsp_pipeline_set_optimizer: null pipeline");
+    DSP_REQUIRE(s == 0 || s == 1, DSP_EINVAL, "dsp_pipeline_set_optimizer: s = %d (only s = 0 and s = 1 are built)", (int)s);
+    DSP_REQUIRE(lr >= 0.f, DSP_EINVAL, "dsp_pipeline_set_optimizer: negative step size");
+    pl->lr = lr;
+    pl->momentum = momentum;
+    pl->sum_s = s;
+    pl->wd = weight_decay;
+    drop_graphs(pl);  // recorded ticks hold the old constants
+    pl->eager_ticks = 1;
+    return DSP_OK;
+}
+
 int dsp_pipeline_set_graph_replay(dsp_pipeline* pl, int32_t enable)
 {
     DSP_REQUIRE(pl, DSP_EINVAL, "dsp_pipeline_set_graph_replay: null pipeline");
@@ -446,7 +462,7 @@ static int tick_step(dsp_pipeline* pl, int k, int64_t tau, hipStream_t st, bool 
 // and the update that consumes that gradient.
 static int tick_update(dsp_pipeline* pl, int k, hipStream_t st)
 {
-    return dsp_param_update(pl->blocks[k], pl->lr, pl->momentum, pl->wd, st);
+    return dsp_param_update_sum(pl->blocks[k], pl->lr, pl->momentum, pl->sum_s, pl->wd, st);
 }
 
 // All of it on one stream.
@@ -582,7 +598,8 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
                 DSP_TRY(dsp_block_enable_forward_lane(pl->blocks[k]));
                 pl->fwd_split[k] = 1;
             }
-    const bool graph_tick = pl->use_graphs && pl->period > 0 && !g_profile_on && tau > pl->fill;
+    const bool graph_tick = pl->use_graphs && pl->period > 0 && !g_profile_on && tau > pl->fill && pl->eager_ticks == 0;
+    if (pl->eager_ticks > 0 && tau > pl->fill) pl->eager_ticks -= 1;
     const int phase = graph_tick ? (int)(tau % pl->period) : 0;
 
     // the data source: copy the mini-batch into block 0's ring slot and the labels into the label ring

@@ -180,6 +180,39 @@ def test_sum_matches_torch_sgd_momentum():
         np.testing.assert_allclose(x[0], t.detach().numpy(), rtol=1e-12, atol=1e-14)
 
 
+def test_sum_s1_matches_torch_nesterov():
+    """Eq. (3) with s = 1 is Nesterov's method; torch's SGD(nesterov=True) is the same iteration."""
+    rng = np.random.default_rng(1)
+    x0 = rng.standard_normal(7)
+    t = torch.tensor(x0, dtype=torch.float64, requires_grad=True)
+    topt = torch.optim.SGD([t], lr=0.05, momentum=0.9, nesterov=True)
+    opt, x = O.SUM([x0.copy()], 0.05, 0.9, s=1), [x0.copy()]
+    for _ in range(6):
+        g = rng.standard_normal(7)
+        t.grad = torch.tensor(g)
+        topt.step()
+        x = opt.step(x, [g])
+        np.testing.assert_allclose(x[0], t.detach().numpy(), rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("s", [0, 1])
+def test_sum_step_size_change_keeps_the_iterate_difference(s):
+    """Eq. (3) under a schedule: the momentum term is beta (y^{s,n+1} - y^{s,n}), a difference of iterates.
+    With G^n = 0 the new step size cannot matter: x^{n+1} - x^n = beta (x^n - x^{n-1} + s alpha_{n-1} G^{n-1})."""
+    a0, a1, b = Fraction(1, 3), Fraction(1, 30), Fraction(3, 5)
+    G = [Fraction(v) for v in (2, -1, 5)]
+    opt, xs = O.SUM([Fraction(1)], a0, b, s=s), [Fraction(1)]
+    for g in G:
+        xs.append(opt.step([xs[-1]], [g])[0])
+    opt.alpha = a1
+    xs.append(opt.step([xs[-1]], [Fraction(0)])[0])
+    assert xs[-1] - xs[-2] == b * (xs[-2] - xs[-3] + s * a0 * G[-1])
+    # and one more step with a gradient: the plain step uses the new alpha, the carried term the old iterates
+    g = Fraction(7)
+    x_next = opt.step([xs[-1]], [g])[0]
+    assert x_next - xs[-1] == -a1 * g + b * (xs[-1] - xs[-2] - s * a1 * g)
+
+
 # ----------------------------------------------------------------------------- layers
 CONV_CASES = [(2, 3, 5, 6, 4, 3, 3, 1, 1), (2, 4, 7, 7, 3, 3, 3, 2, 1), (3, 5, 6, 6, 2, 1, 1, 2, 0),
               (1, 2, 9, 8, 3, 7, 7, 2, 3), (2, 3, 4, 4, 5, 1, 1, 1, 0)]
