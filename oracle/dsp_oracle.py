@@ -11,6 +11,7 @@ What follows the paper, and where:
   ``SoftmaxCE`` is L.
 * Section 2, Eq. (2): the chain rule per block -> ``CNNBlock.vjp``.
 * Section 2, Eq. (3): stochastic unified momentum -> ``SUM`` (s = 0 heavy ball, s = 1 Nesterov).
+* Lemma 1 / Section 5.4: DSP gradient against the BP gradient at forward-time parameters -> ``GradientDifference``.
 * Section 3.1: layer-wise staleness = number of parameter updates between the forward and the
   backward use of a block's parameters for one mini-batch.
 * Section 3.2, Eq. (5): the DSP gradient -- block k recomputes f_k on the input it *stored*
@@ -527,6 +528,72 @@ class DSPOracle:
         self.tau += 1
         self.log.append({k: rec[k] for k in ("tau", "fwd", "bwd", "version", "loss", "loss_batch")})
         return rec
+
+
+# --------------------------------------------------------------------------- Lemma 1 / Section 5.4
+def _sumsq(v):
+    return (v * v).sum() if hasattr(v, "sum") else v * v
+
+
+class GradientDifference:
+    """The two gradients Lemma 1 compares, per block and mini-batch (the quantity of Section 5.4).
+
+    For mini-batch b let x_i^{fwd(b)} be block i's parameters when it ran the forward pass of b.
+    * BP gradient: nabla_{x_k} L(F(h_0(b); x_0^{fwd(b)}, ..., x_{K-1}^{fwd(b)}), label(b)), i.e. ordinary
+      backpropagation of batch b through the network frozen at those parameters;
+    * DSP gradient: the G_{x_k} block k formed for b (Eq. (5)), with the parameters of its backward tick.
+    ``tick`` drives the wrapped pipeline and, once block 0 (the last to finish a batch) has formed its
+    gradient of batch b, returns (b, [||DSP_k - BP_k||^2], [||BP_k||^2]) as exact sums of squares.
+    """
+
+    def __init__(self, orc):
+        assert not orc.external_gradient
+        self.orc = orc
+        K = orc.K
+        self.snap = [dict() for _ in range(K)]          # batch -> parameters block k forwarded it with
+        self.data = {}                                  # batch -> (h_0, label)
+        self.dsp = [dict() for _ in range(K)]           # batch -> G_{x_k}
+
+    def bp_gradient(self, b):
+        """Backpropagation of batch b through the blocks frozen at their forward-time parameters."""
+        orc, K = self.orc, self.orc.K
+        live = [blk.param_list() for blk in orc.blocks]
+        try:
+            for k in range(K):
+                orc.blocks[k].set_param_list(self.snap[k][b])
+            h, lab = self.data[b]
+            hs = []
+            for k in range(K):
+                hs.append(h)
+                h, _ = orc.blocks[k].forward(h)
+            _, g = orc.loss.value_and_grad(h, lab)
+            grads = [None] * K
+            for k in reversed(range(K)):
+                g, grads[k] = orc.blocks[k].vjp(hs[k], g)
+        finally:
+            for k in range(K):
+                orc.blocks[k].set_param_list(live[k])
+        return grads
+
+    def tick(self, h0, label):
+        orc, K, tau = self.orc, self.orc.K, self.orc.tau
+        self.data[tau] = (h0, label)
+        before = [[v * 1 for v in blk.param_list()] for blk in orc.blocks]  # a tick's update comes last
+        rec = orc.tick(h0, label)
+        for k in range(K):
+            if rec["fwd"][k] is not None:
+                self.snap[k][rec["fwd"][k]] = before[k]
+            if rec["bwd"][k] is not None:
+                self.dsp[k][rec["bwd"][k]] = rec["g_x"][k]
+        b = rec["bwd"][0]
+        if b is None:
+            return rec, None
+        bp = self.bp_gradient(b)
+        diff = [sum(_sumsq(d - r) for d, r in zip(self.dsp[k].pop(b), bp[k])) for k in range(K)]
+        ref = [sum(_sumsq(r) for r in bp[k]) for k in range(K)]
+        self.last_frozen = [self.snap[k].pop(b) for k in range(K)]  # kept for inspection
+        del self.data[b]
+        return rec, (b, diff, ref)
 
 
 def build_cnn_oracle(cfg, params_per_block, lr=None, beta=None, wd=None, p=None, m=None, eps=1e-5, storage=None):

@@ -132,6 +132,98 @@ def test_mismatched_queue_is_caught():
             orc.tick(n, n)
 
 
+# ----------------------------------------------------------------------------- Lemma 1 / Section 5.4
+def _scalar_pipeline(p, m, lr, beta=0):
+    blocks = [ScalarBlock(Fraction(3, 4), 1), ScalarBlock(Fraction(5, 4), 2), ScalarBlock(Fraction(2, 3), 1)]
+    return O.DSPOracle(blocks, HalfSquare(), p, m, lr, beta)
+
+
+def test_gradient_difference_closed_form_on_scalar_blocks():
+    """f_k = x_k^{n_k} h, L = (h_K - l)^2 / 2.  With x_i^f / x_i^b the parameters block i held at the forward /
+    backward of batch b: BP_k = n_k x_k^{f,n_k-1} h_k (h_K - l) prod_{i>k} (x_i^f)^{n_i} and DSP_k has x^b in
+    place of x^f for the blocks i >= k (its own recompute included); h_k, h_K come from forward parameters."""
+    p, m = (1, 1, 0), (4, 2, 0)
+    orc = _scalar_pipeline(p, m, Fraction(1, 50), Fraction(1, 2))
+    gd = O.GradientDifference(orc)
+    P = [0, 1, 2]
+    powers = [1, 2, 1]
+    hist = []  # hist[tau][k] = parameter of block k at the start of tick tau
+    data = []
+    seen = 0
+    for tau in range(9):  # exact rationals: the digit count multiplies every tick, keep it short
+        hist.append([blk.x[0] for blk in orc.blocks])
+        h0, l = Fraction(tau % 5 + 1, 3), Fraction(7 - tau % 4, 5)
+        data.append((h0, l))
+        _, out = gd.tick(h0, l)
+        if out is None:
+            continue
+        b, diff, ref = out
+        assert b == tau - m[0]
+        xf = [hist[b + P[k]][k] for k in range(3)]
+        xb = [hist[b + P[k] + m[k]][k] for k in range(3)]
+        h = [data[b][0]]
+        for k in range(3):
+            h.append(xf[k] ** powers[k] * h[k])
+        err = h[3] - data[b][1]
+        for k in range(3):
+            def grad(x):
+                g = powers[k] * x[k] ** (powers[k] - 1) * h[k] * err
+                for i in range(k + 1, 3):
+                    g *= x[i] ** powers[i]
+                return g
+            bp, dsp = grad(xf), grad(xf[:k] + xb[k:])
+            assert ref[k] == bp * bp
+            assert diff[k] == (dsp - bp) ** 2
+        assert diff[2] == 0  # the last block is not stale here
+        assert (diff[0] != 0) == (b >= 1)  # batch 0 comes back before any block has made an update
+        seen += 1
+    assert seen == 5
+
+
+def test_gradient_difference_vanishes_without_staleness_or_steps():
+    """All-zero schedule: the DSP gradient is the BP gradient.  Zero step size: parameters never move."""
+    for p, m, lr in (((0, 0, 0), (0, 0, 0), Fraction(1, 10)), ((1, 1, 0), (4, 2, 0), Fraction(0))):
+        gd = O.GradientDifference(_scalar_pipeline(p, m, lr, Fraction(1, 2)))
+        n = 0
+        ticks = 5 if lr else 8  # exact rationals grow with every update
+        for tau in range(ticks):
+            _, out = gd.tick(Fraction(tau + 1, 3), Fraction(2))
+            if out is not None:
+                assert all(d == 0 for d in out[1]) and all(r != 0 for r in out[2])
+                n += 1
+        assert n == ticks - m[0]
+
+
+def test_gradient_difference_on_cnn_blocks_matches_torch_autograd_bp():
+    """The BP side on real layers: torch autograd through the whole network at the snapshot parameters."""
+    cfg = get_config("tiny2")
+    rng = np.random.default_rng(3)
+    params = [perturb_affine(make_params(layers, rng), rng) for layers in cfg["blocks"]]
+    orc = O.build_cnn_oracle(cfg, params)
+    gd = O.GradientDifference(orc)
+    batches, hist, fwd_tick, seen, stale_seen = [], [], {}, 0, False
+    for tau in range(6):
+        x, y = make_batch(rng, cfg["input"], cfg["classes"])
+        batches.append((x, y))
+        hist.append([[v.copy() for v in blk.param_list()] for blk in orc.blocks])
+        rec, out = gd.tick(x, y)
+        for k in range(cfg["K"]):
+            if rec["fwd"][k] is not None:
+                fwd_tick[(k, rec["fwd"][k])] = tau
+        if out is None:
+            continue
+        b, diff, ref = out
+        # the parameters each block held in the tick it forwarded batch b, taken from this test's own history
+        frozen = [hist[fwd_tick[(k, b)]][k] for k in range(cfg["K"])]
+        tot = _torch_bp_sumsq(cfg, params, frozen, *batches[b])
+        for k in range(cfg["K"]):
+            assert abs(tot[k] - ref[k]) <= 1e-9 * max(1.0, ref[k])
+        assert diff[-1] <= 1e-20 * max(1.0, ref[-1])  # the last block of this schedule is not stale
+        stale_seen = stale_seen or diff[0] > 1e-12 * ref[0]
+        seen += 1
+    assert seen >= 3 and stale_seen
+
+
 # ----------------------------------------------------------------------------- update rule
 def test_sum_constant_gradient_closed_form():
     """Heavy ball with a constant gradient g: x^n - x^{n+1} = alpha g (1 - beta^{n+1}) / (1 - beta)."""
@@ -399,6 +491,17 @@ def _torch_net(cfg, params):
 
     leaves = [t for blk in tp for d in blk for t in d.values()]
     return run, leaves, tp
+
+
+def _torch_bp_sumsq(cfg, template, frozen, x, y):
+    """Sum of squares of torch autograd's parameter gradients per block; frozen[k] = flat parameter list."""
+    params = []
+    for blk, flat in zip(template, frozen):
+        it = iter(flat)
+        params.append([{key: next(it) for key in d} for d in blk])
+    run, leaves, tp = _torch_net(cfg, params)
+    run(torch.tensor(x, dtype=torch.float64), torch.tensor(y, dtype=torch.long)).backward()
+    return [sum(float((t.grad ** 2).sum()) for d in blk for t in d.values()) for blk in tp]
 
 
 @pytest.mark.parametrize("name,batch,hw", [("tiny2", 4, 8), ("resnet20", 4, 8), ("resnet18", 2, 64)])
