@@ -242,6 +242,28 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
 int dsp_pipeline_set_optimizer(dsp_pipeline* pl, float lr, float momentum, int32_t s, float weight_decay);
 
 /*
+ * Gradient-difference diagnostic (Lemma 1; the quantity plotted in Section 5.4).  `probe` is a second
+ * pipeline over K blocks of the same architecture, built with the all-zero schedule (ordinary
+ * backpropagation), step size 0 and max_ticks >= pl's; it stays owned by the caller and must outlive
+ * pl's last step.  Call once, before the first step of either pipeline.  From then on every
+ * dsp_pipeline_step(pl) (labels required) additionally
+ *   - keeps, per block, the parameters it runs the forward pass of mini-batch a = tau - P_k with,
+ *   - keeps the DSP gradient G_{x_k} of mini-batch b_k = a - m_k,
+ *   - and, once block 0 has formed its gradient of mini-batch b (the last block to do so), loads the
+ *     kept forward-time parameters of b into the probe blocks, back-propagates h_0(b) through them and
+ *     forms, per block, sum (G^DSP_{x_k} - G^BP_{x_k})^2 and sum (G^BP_{x_k})^2 in fp64.
+ * The step then synchronises all streams several times and never replays graphs: a diagnostic mode,
+ * not a timed path.  Costs device memory for (1 + m_0 - P_k) parameter copies and
+ * (1 + m_0 - P_k - m_k) gradient copies per block.
+ */
+int dsp_pipeline_attach_gradient_probe(dsp_pipeline* pl, dsp_pipeline* probe);
+/*
+ * Result of the latest step: *batch_id = the mini-batch evaluated (-1: none yet, while block 0 has no
+ * gradient), diff_sumsq[K] and bp_sumsq[K] (host) as defined above.
+ */
+int dsp_pipeline_gradient_difference(dsp_pipeline* pl, int64_t* batch_id, double* diff_sumsq, double* bp_sumsq);
+
+/*
  * How the launches of a tick reach the GPU (results are bit-identical in every mode):
  *  - launch threads (default on): the chain of block k >= 1 is issued by a host thread of its own while
  *    the caller's thread issues block 0; the call returns when every chain has been enqueued.

@@ -15,7 +15,8 @@ __all__ = [
     "dsp_layer_desc", "dsp_block_desc", "make_block_desc",
     "dsp_schedule_validate", "dsp_schedule_index", "dsp_schedule_queue_elems",
     "dsp_block_init", "dsp_block_destroy", "dsp_block_forward", "dsp_block_recompute_backward",
-    "dsp_param_update", "dsp_param_update_sum", "dsp_pipeline_set_optimizer", "dsp_block_input_slot", "dsp_block_query", "dsp_block_output_shape",
+    "dsp_param_update", "dsp_param_update_sum", "dsp_pipeline_set_optimizer", "dsp_block_input_slot",
+    "dsp_pipeline_attach_gradient_probe", "dsp_pipeline_gradient_difference", "dsp_block_query", "dsp_block_output_shape",
     "dsp_block_input_shape", "dsp_block_memory", "dsp_block_get_params", "dsp_block_set_params",
     "dsp_block_get_momentum", "dsp_block_set_momentum", "dsp_block_get_grads",
     "dsp_pipeline_init", "dsp_pipeline_destroy", "dsp_pipeline_step", "dsp_pipeline_set_delay",
@@ -87,6 +88,8 @@ _SIGNATURES = {
     "dsp_param_update": [_vp, _f, _f, _f, _vp],
     "dsp_param_update_sum": [_vp, _f, _f, _i32, _f, _vp],
     "dsp_pipeline_set_optimizer": [_vp, _f, _f, _i32, _f],
+    "dsp_pipeline_attach_gradient_probe": [_vp, _vp],
+    "dsp_pipeline_gradient_difference": [_vp, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)],
     "dsp_block_input_slot": [_vp, _i64, C.POINTER(_vp)],
     "dsp_block_query": [_vp, _pi64],
     "dsp_block_output_shape": [_vp, _pi32],
@@ -236,6 +239,18 @@ def dsp_param_update_sum(b, lr, momentum, s=0, weight_decay=0.0, stream=None):
 
 def dsp_pipeline_set_optimizer(pl, lr, momentum, s=0, weight_decay=0.0):
     check(lib().dsp_pipeline_set_optimizer(pl, lr, momentum, int(s), weight_decay), "dsp_pipeline_set_optimizer")
+
+
+def dsp_pipeline_attach_gradient_probe(pl, probe):
+    check(lib().dsp_pipeline_attach_gradient_probe(pl, probe), "dsp_pipeline_attach_gradient_probe")
+
+
+def dsp_pipeline_gradient_difference(pl, K):
+    """(batch_id, diff_sumsq[K], bp_sumsq[K]) of the latest step; batch_id = -1 while there is none."""
+    bid = C.c_int64(-1)
+    diff, ref = (C.c_double * K)(), (C.c_double * K)()
+    check(lib().dsp_pipeline_gradient_difference(pl, C.byref(bid), diff, ref), "dsp_pipeline_gradient_difference")
+    return bid.value, np.array(diff[:], np.float64), np.array(ref[:], np.float64)
 
 
 def dsp_block_input_slot(b, batch_id):

@@ -568,6 +568,15 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
 
 void block_set_dry(dsp_block* b, bool dry) { b->dry = dry; }
 
+BlockArrays block_arrays(dsp_block* b) { return BlockArrays{b->x, b->g, b->nP}; }
+
+int block_load_params_device(dsp_block* b, const float* d_src, hipStream_t st)
+{
+    if (b->nP == 0) return DSP_OK;
+    DSP_HIP(hipMemcpyAsync(b->x, d_src, b->nP * 4, hipMemcpyDeviceToDevice, st));
+    return launch_refresh_shadows(b->dtype, b->x, b->tmap, b->wf16, b->wt, b->nP, st);
+}
+
 }  // namespace dsp
 
 // ================================================================================================

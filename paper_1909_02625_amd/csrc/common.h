@@ -17,6 +17,17 @@ namespace dsp {
 // counter) but launch nothing: the pipeline replays the launches of that tick from a HIP graph.
 void block_set_dry(dsp_block* b, bool dry);
 
+// The block's flat fp32 parameter and gradient arrays (library layout) and their length.
+struct BlockArrays {
+    float* x;
+    float* g;
+    size_t n;
+};
+BlockArrays block_arrays(dsp_block* b);
+// Overwrites the parameters with n floats in the library layout (device memory) and refreshes the
+// storage-type copies the kernels read; ordered on st.
+int block_load_params_device(dsp_block* b, const float* d_src, hipStream_t st);
+
 // ---- error plumbing ---------------------------------------------------------------------------
 void set_error(const char* fmt, ...);
 
@@ -190,6 +201,9 @@ int launch_softmax_ce(const float* z, const int32_t* labels, float* loss, float*
                       int C, hipStream_t st);
 // v <- momentum*v + (g + wd*x*[decay]);  x <- x - lr*v;  shadow copies refreshed in the same pass:
 // wf16[i] = bf16(x[i]) if wf16 != nullptr;  wt[tmap[i]] = T(x[i]) where tmap[i] >= 0.
+// out[0] = sum (a_i - b_i)^2, out[1] = sum b_i^2 in fp64, same order every run; partial: 2 * kDiffSumsqBlocks doubles.
+constexpr int kDiffSumsqBlocks = 256;
+int launch_diff_sumsq(const float* a, const float* b, size_t n, double* partial, double* out, hipStream_t st);
 int launch_sgd_update(int dtype, float* x, float* v, const float* g, const uint8_t* decay, const int32_t* tmap,
                       void* wf16, void* wt, size_t n, float lr, float momentum, float wd, hipStream_t st,
                       bool nesterov = false, float v_scale = 1.f);

@@ -3,6 +3,8 @@
 // the matrix cores; they are written as coalesced NHWC streams.
 #include "common.h"
 
+#include <algorithm>
+
 namespace dsp {
 namespace {
 
@@ -260,6 +262,46 @@ __global__ void sgd_update_kernel(float* __restrict__ x, float* __restrict__ v, 
     }
 }
 
+// ---- sums of squares of a - b and of b (gradient-difference diagnostic), fixed summation order -----
+__global__ __launch_bounds__(256) void diff_sumsq_partial_kernel(const float* __restrict__ a, const float* __restrict__ b,
+                                                                 size_t n, double* __restrict__ partial)
+{
+    __shared__ double red[2][256];
+    double sd = 0.0, sb = 0.0;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        const double bi = (double)b[i], d = (double)a[i] - bi;
+        sd += d * d;
+        sb += bi * bi;
+    }
+    red[0][threadIdx.x] = sd;
+    red[1][threadIdx.x] = sb;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+            red[0][threadIdx.x] += red[0][threadIdx.x + w];
+            red[1][threadIdx.x] += red[1][threadIdx.x + w];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        partial[2 * blockIdx.x] = red[0][0];
+        partial[2 * blockIdx.x + 1] = red[1][0];
+    }
+}
+
+__global__ __launch_bounds__(64) void diff_sumsq_final_kernel(const double* __restrict__ partial, int nblk,
+                                                             double* __restrict__ out)
+{
+    if (threadIdx.x != 0) return;
+    double sd = 0.0, sb = 0.0;
+    for (int i = 0; i < nblk; ++i) {
+        sd += partial[2 * i];
+        sb += partial[2 * i + 1];
+    }
+    out[0] = sd;
+    out[1] = sb;
+}
+
 __global__ void record_loss_kernel(const float* __restrict__ loss, float* __restrict__ history, int32_t* counter,
                                    long long capacity)
 {
@@ -430,6 +472,15 @@ int launch_refresh_shadows(int dtype, const float* x, const int32_t* tmap, void*
         hipLaunchKernelGGL((sgd_update_kernel<float, false>), grid, dim3(kThreads), 0, st, (float*)x, (float*)nullptr,
                            (const float*)nullptr, (const uint8_t*)nullptr, tmap, (bf16_t*)nullptr, (float*)wt, n, 0.f,
                            0.f, 0.f, 1.f);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+int launch_diff_sumsq(const float* a, const float* b, size_t n, double* partial, double* out, hipStream_t st)
+{
+    const int nblk = (int)std::max<size_t>(1, std::min<size_t>(kDiffSumsqBlocks, (n + 255) / 256));
+    hipLaunchKernelGGL(diff_sumsq_partial_kernel, dim3(nblk), dim3(256), 0, st, a, b, n, partial);
+    hipLaunchKernelGGL(diff_sumsq_final_kernel, dim3(1), dim3(64), 0, st, (const double*)partial, nblk, out);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }

@@ -107,6 +107,17 @@ struct dsp_pipeline {
     int period = 0;      // ticks after which every ring is back in the same position (0: too long, no graphs)
     int64_t fill = 0;    // first tick at which every block runs forward, backward and update
     std::vector<hipGraphExec_t> graphs;
+    // Gradient-difference diagnostic (Lemma 1, Section 5.4): a second, all-zero-schedule pipeline over
+    // blocks of the same architecture re-runs each mini-batch as ordinary backpropagation at the
+    // parameters every block held when it ran the forward pass of that mini-batch.
+    dsp_pipeline* probe = nullptr;
+    std::vector<float*> xsnap, gstash;      // per block: rings of parameter snapshots / DSP gradients, by mini-batch
+    std::vector<int> xsnap_n, gstash_n;     // their entry counts
+    int32_t* probe_labels = nullptr;        // labels of the last 1 + m_0 mini-batches
+    double* probe_partial = nullptr;
+    double* probe_out = nullptr;            // [K][2]
+    int64_t probe_batch = -1;               // mini-batch of the latest result
+    std::vector<double> probe_diff, probe_ref;
 };
 
 static int run_block_tick(dsp_pipeline* pl, int k, int64_t tau);
@@ -377,6 +388,55 @@ int dsp_pipeline_set_optimizer(dsp_pipeline* pl, float lr, float momentum, int32
     return DSP_OK;
 }
 
+int dsp_pipeline_attach_gradient_probe(dsp_pipeline* pl, dsp_pipeline* probe)
+{
+    DSP_REQUIRE(pl && probe && pl != probe, DSP_EINVAL, "dsp_pipeline_attach_gradient_probe: bad argument");
+    DSP_REQUIRE(pl->tau == 0 && probe->tau == 0 && !pl->probe, DSP_ESTATE,
+                "dsp_pipeline_attach_gradient_probe: must be called once, before the first step of either pipeline");
+    DSP_REQUIRE(!pl->serial && pl->K >= 2, DSP_EINVAL, "dsp_pipeline_attach_gradient_probe: the pipeline has no staleness to measure");
+    DSP_REQUIRE(probe->serial && probe->K == pl->K && probe->N == pl->N && probe->in_bytes == pl->in_bytes, DSP_EINVAL,
+                "dsp_pipeline_attach_gradient_probe: the probe must be an all-zero-schedule pipeline over the same K blocks");
+    DSP_REQUIRE(probe->lr == 0.f, DSP_EINVAL, "dsp_pipeline_attach_gradient_probe: the probe must have step size 0");
+    DSP_REQUIRE(probe->max_ticks >= pl->max_ticks, DSP_EINVAL, "dsp_pipeline_attach_gradient_probe: probe max_ticks too small");
+    const int K = pl->K;
+    for (int k = 0; k < K; ++k)
+        DSP_REQUIRE(block_arrays(pl->blocks[k]).n == block_arrays(probe->blocks[k]).n, DSP_EINVAL,
+                    "dsp_pipeline_attach_gradient_probe: block %d has another parameter count in the probe", k);
+    // block 0 is the last to finish a mini-batch: b forwarded at tick b + P_k is needed until tick b + m_0
+    const int horizon = pl->m[0];
+    pl->xsnap.assign(K, nullptr);
+    pl->gstash.assign(K, nullptr);
+    pl->xsnap_n.assign(K, 0);
+    pl->gstash_n.assign(K, 0);
+    for (int k = 0; k < K; ++k) {
+        const size_t n = block_arrays(pl->blocks[k]).n;
+        pl->xsnap_n[k] = horizon - pl->P[k] + 1;
+        pl->gstash_n[k] = horizon - pl->P[k] - pl->m[k] + 1;
+        DSP_REQUIRE(pl->xsnap_n[k] >= 1 && pl->gstash_n[k] >= 1, DSP_EINVAL, "dsp_pipeline_attach_gradient_probe: schedule");
+        DSP_TRY(pl_alloc(pl, (void**)&pl->xsnap[k], n * 4 * pl->xsnap_n[k]));
+        DSP_TRY(pl_alloc(pl, (void**)&pl->gstash[k], n * 4 * pl->gstash_n[k]));
+    }
+    DSP_TRY(pl_alloc(pl, (void**)&pl->probe_labels, (size_t)pl->N * 4 * (horizon + 1)));
+    DSP_TRY(pl_alloc(pl, (void**)&pl->probe_partial, sizeof(double) * 2 * kDiffSumsqBlocks));
+    DSP_TRY(pl_alloc(pl, (void**)&pl->probe_out, sizeof(double) * 2 * K));
+    pl->probe_diff.assign(K, 0.0);
+    pl->probe_ref.assign(K, 0.0);
+    pl->probe = probe;
+    return DSP_OK;
+}
+
+int dsp_pipeline_gradient_difference(dsp_pipeline* pl, int64_t* batch_id, double* diff_sumsq, double* bp_sumsq)
+{
+    DSP_REQUIRE(pl && batch_id && diff_sumsq && bp_sumsq, DSP_EINVAL, "dsp_pipeline_gradient_difference: null argument");
+    DSP_REQUIRE(pl->probe, DSP_ESTATE, "dsp_pipeline_gradient_difference: no probe attached");
+    *batch_id = pl->probe_batch;
+    for (int k = 0; k < pl->K; ++k) {
+        diff_sumsq[k] = pl->probe_batch >= 0 ? pl->probe_diff[k] : 0.0;
+        bp_sumsq[k] = pl->probe_batch >= 0 ? pl->probe_ref[k] : 0.0;
+    }
+    return DSP_OK;
+}
+
 int dsp_pipeline_set_graph_replay(dsp_pipeline* pl, int32_t enable)
 {
     DSP_REQUIRE(pl, DSP_EINVAL, "dsp_pipeline_set_graph_replay: null pipeline");
@@ -581,6 +641,63 @@ static int issue_tick(dsp_pipeline* pl, int64_t tau, bool capturing)
     return DSP_OK;
 }
 
+// Gradient-difference diagnostic, part 1: before tick tau is issued, keep the parameters every block is
+// about to run the forward pass of mini-batch tau - P_k with (the tick's update comes last) and the labels.
+static int probe_before_tick(dsp_pipeline* pl, int64_t tau, const int32_t* d_labels, hipStream_t user)
+{
+    DSP_REQUIRE(d_labels, DSP_EINVAL, "dsp_pipeline_step: the gradient probe needs labels");
+    DSP_TRY(dsp_pipeline_sync(pl));
+    DSP_HIP(hipStreamSynchronize(user));
+    for (int k = 0; k < pl->K; ++k) {
+        const int64_t a = tau - pl->P[k];
+        if (a < 0) continue;
+        const BlockArrays A = block_arrays(pl->blocks[k]);
+        DSP_HIP(hipMemcpy(pl->xsnap[k] + (size_t)(a % pl->xsnap_n[k]) * A.n, A.x, A.n * 4, hipMemcpyDeviceToDevice));
+    }
+    DSP_HIP(hipMemcpy(pl->probe_labels + (size_t)(tau % (pl->m[0] + 1)) * pl->N, d_labels, (size_t)pl->N * 4,
+                      hipMemcpyDeviceToDevice));
+    return DSP_OK;
+}
+
+// Part 2: after tick tau, keep the DSP gradients it formed; block 0's is the last one of its mini-batch b,
+// which is then re-run as ordinary backpropagation through the probe blocks at the kept parameters.
+static int probe_after_tick(dsp_pipeline* pl, int64_t tau)
+{
+    const int K = pl->K;
+    DSP_TRY(dsp_pipeline_sync(pl));
+    for (int k = 0; k < K; ++k) {
+        const int64_t bb = tau - pl->P[k] - pl->m[k];
+        if (bb < 0) continue;
+        const BlockArrays A = block_arrays(pl->blocks[k]);
+        DSP_HIP(hipMemcpy(pl->gstash[k] + (size_t)(bb % pl->gstash_n[k]) * A.n, A.g, A.n * 4, hipMemcpyDeviceToDevice));
+    }
+    const int64_t b = tau - pl->m[0];
+    if (b < 0) return DSP_OK;
+    dsp_pipeline* pr = pl->probe;
+    for (int k = 0; k < K; ++k) {
+        const BlockArrays A = block_arrays(pr->blocks[k]);
+        DSP_TRY(block_load_params_device(pr->blocks[k], pl->xsnap[k] + (size_t)(b % pl->xsnap_n[k]) * A.n, nullptr));
+    }
+    DSP_HIP(hipDeviceSynchronize());
+    void* slot0;
+    DSP_TRY(dsp_block_input_slot(pl->blocks[0], b, &slot0));  // still holds h_0(b): block 0 just recomputed from it
+    DSP_TRY(dsp_pipeline_step(pr, slot0, pl->probe_labels + (size_t)(b % (pl->m[0] + 1)) * pl->N, nullptr, nullptr, nullptr));
+    DSP_TRY(dsp_pipeline_sync(pr));
+    for (int k = 0; k < K; ++k) {
+        const BlockArrays A = block_arrays(pr->blocks[k]);
+        DSP_TRY(launch_diff_sumsq(pl->gstash[k] + (size_t)(b % pl->gstash_n[k]) * A.n, A.g, A.n, pl->probe_partial,
+                                  pl->probe_out + 2 * k, nullptr));
+    }
+    std::vector<double> out(2 * K);
+    DSP_HIP(hipMemcpy(out.data(), pl->probe_out, sizeof(double) * 2 * K, hipMemcpyDeviceToHost));
+    for (int k = 0; k < K; ++k) {
+        pl->probe_diff[k] = out[2 * k];
+        pl->probe_ref[k] = out[2 * k + 1];
+    }
+    pl->probe_batch = b;
+    return DSP_OK;
+}
+
 int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_labels, float* h_loss,
                       int64_t* loss_batch_id, void* stream)
 {
@@ -598,7 +715,9 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
                 DSP_TRY(dsp_block_enable_forward_lane(pl->blocks[k]));
                 pl->fwd_split[k] = 1;
             }
-    const bool graph_tick = pl->use_graphs && pl->period > 0 && !g_profile_on && tau > pl->fill && pl->eager_ticks == 0;
+    if (pl->probe) DSP_TRY(probe_before_tick(pl, tau, d_labels, user));
+    const bool graph_tick = pl->use_graphs && pl->period > 0 && !g_profile_on && tau > pl->fill && pl->eager_ticks == 0 &&
+                            !pl->probe;
     if (pl->eager_ticks > 0 && tau > pl->fill) pl->eager_ticks -= 1;
     const int phase = graph_tick ? (int)(tau % pl->period) : 0;
 
@@ -656,6 +775,7 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
         }
     }
     pl->tau = tau + 1;
+    if (pl->probe) DSP_TRY(probe_after_tick(pl, tau));
 
     const int64_t a_last = tau - pl->P[K - 1];
     if (loss_batch_id) *loss_batch_id = a_last >= 0 ? a_last : -1;

@@ -379,6 +379,83 @@ def test_pipeline_loss_trajectory(name, dtype, ticks, kw, rtol):
         assert rel_err(final[k], _flat(orc.blocks[k].param_list())) < (rtol if rtol <= 1e-3 else 0.25)
 
 
+@pytest.mark.parametrize("name,dtype,ticks,kw,rtol", [
+    ("tiny2", D.DSP_FP32, 16, {"perturb": True}, 2e-2),
+    ("resnet20", D.DSP_FP32, 10, {}, 2e-2),   # configs[1] at full size
+    ("resnet20", D.DSP_BF16, 9, {}, None),    # bf16: invariants only
+], ids=lambda v: v if isinstance(v, str) else None)
+def test_gradient_difference_probe(name, dtype, ticks, kw, rtol):
+    """Lemma 1 / Section 5.4: ||G^DSP_{x_k} - G^BP_{x_k}|| per block, free-running, against the oracle's
+    GradientDifference on the same batches.  The quantity is a difference of two nearby gradients, each
+    exact to ~1e-6 in fp32, on trajectories that agree to ~1e-3, hence the 2e-2 bound on its norm."""
+    cfg, params, rng = _setup(name, **kw)
+    K, p, m = cfg["K"], cfg["p"], cfg["m"]
+    blocks = build_gpu_blocks(cfg, params, dtype)
+    probes = build_gpu_blocks(cfg, params, dtype, p=[0] * K, m=[0] * K)
+    pl = D.dsp_pipeline_init(blocks, p, m, cfg["lr"], cfg["beta"], cfg["wd"], ticks)
+    pr = D.dsp_pipeline_init(probes, [0] * K, [0] * K, 0.0, 0.0, 0.0, ticks)
+    D.dsp_pipeline_attach_gradient_probe(pl, pr)
+    gd = O.GradientDifference(O.build_cnn_oracle(cfg, params)) if rtol is not None else None
+    seen = 0
+    try:
+        for tau in range(ticks):
+            x, y = make_batch(rng, cfg["input"], cfg["classes"])
+            x = round_like(x, dtype)
+            D.dsp_pipeline_step(pl, to_dev(x, dtype), torch.from_numpy(y).cuda(), want_loss=False)
+            bid, diff, ref = D.dsp_pipeline_gradient_difference(pl, K)
+            assert bid == (tau - m[0] if tau >= m[0] else -1)
+            out = gd.tick(x, y)[1] if gd else None
+            if bid < 0:
+                assert out is None
+                continue
+            seen += 1
+            assert np.all(ref > 0)
+            if m[K - 1] == 0:
+                # the last block is not stale: same input, same parameters, same kernels -> the same bits
+                assert diff[K - 1] == 0.0
+            if bid == 0:
+                # mini-batch 0 returns to every block before that block's first update
+                assert np.all(diff == 0.0)
+            else:
+                assert np.all(diff[:K - 1] > 0)
+            if out is not None:
+                ob, odiff, oref = out
+                assert ob == bid
+                np.testing.assert_allclose(np.sqrt(ref), np.sqrt(np.asarray(oref, np.float64)), rtol=1e-3)
+                for k in range(K):
+                    if odiff[k] > 0:
+                        assert abs(np.sqrt(diff[k]) - np.sqrt(odiff[k])) <= rtol * np.sqrt(odiff[k]), (tau, k, diff[k], odiff[k])
+                    else:
+                        assert diff[k] <= 1e-10 * ref[k]
+        assert seen == ticks - m[0] and seen >= 3
+    finally:
+        D.dsp_pipeline_destroy(pl)
+        D.dsp_pipeline_destroy(pr)
+        destroy_blocks(blocks)
+        destroy_blocks(probes)
+
+
+def test_gradient_probe_is_refused_when_it_cannot_work():
+    cfg, params, rng = _setup("tiny2")
+    K = cfg["K"]
+    blocks = build_gpu_blocks(cfg, params, D.DSP_FP32)
+    probes = build_gpu_blocks(cfg, params, D.DSP_FP32, p=[0] * K, m=[0] * K)
+    pl = D.dsp_pipeline_init(blocks, cfg["p"], cfg["m"], cfg["lr"], cfg["beta"], cfg["wd"], 8)
+    moving = D.dsp_pipeline_init(probes, [0] * K, [0] * K, 0.1, 0.0, 0.0, 8)
+    try:
+        with pytest.raises(D.DSPError):
+            D.dsp_pipeline_attach_gradient_probe(pl, moving)   # a probe that would update its parameters
+        with pytest.raises(D.DSPError):
+            D.dsp_pipeline_attach_gradient_probe(moving, pl)   # nothing stale to measure / wrong roles
+        with pytest.raises(D.DSPError):
+            D.dsp_pipeline_gradient_difference(pl, K)          # no probe attached
+    finally:
+        D.dsp_pipeline_destroy(pl)
+        D.dsp_pipeline_destroy(moving)
+        destroy_blocks(blocks)
+        destroy_blocks(probes)
+
+
 def test_graph_replay_equals_kernel_by_kernel_issue():
     """Ticks replayed from HIP graphs (with the program's own synchronisations and host reads in between)
     give the bits of the same ticks issued kernel by kernel."""
