@@ -894,6 +894,159 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
         }
 }
 
+// bf16 backward-weight for the 64- and 128-wide tiles without any register transpose.  Both operands go
+// into LDS exactly as they lie in memory (rows = m, 16-byte channel runs); the MFMA operand layout
+// (lane = channel, 8 consecutive m per lane) is produced by the LDS transpose read: in each group of 16
+// lanes, lane i receives as element f the element (i % 4) of the 8 bytes that lane 4 f + i / 4 addressed.
+// So the 16 lanes address rows m0 .. m0+3 (lane / 4), 4 channels each (lane % 4), and come away with
+// 4 consecutive m of 16 channels; two such reads make one 8-element operand.  LDS rows are not padded:
+// within every 256-byte line the 16-byte chunk index is XORed with 4 * (line % 4), which spreads the
+// four rows of a read over all banks.
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+// Byte offset of 16-byte chunk `chunk` of row `row` in an unpadded tile whose rows are `row_bytes` long.
+__device__ inline int swizzled_chunk(int row, int chunk, int row_bytes)
+{
+    const int lin = row * row_bytes + chunk * 16;
+    const int line = lin >> 8, cl = (lin >> 4) & 15;
+    return (line << 8) + ((cl ^ ((line & 3) << 2)) << 4);
+}
+
+__device__ inline u32x2 lds_read_tr16(const char* p)
+{
+    return __builtin_bit_cast(
+        u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(p)));
+}
+
+template <typename TL>
+__global__ __launch_bounds__(kThreads) void conv_wgrad_tr_kernel(const bf16_t* __restrict__ x,
+                                                                 const bf16_t* __restrict__ dy,
+                                                                 float* __restrict__ part, WgradGeom g)
+{
+    typedef bf16_t T;
+    constexpr int BM = TL::BM, BN = TL::BN, BKm = TL::BK;
+    static_assert(sizeof(typename TL::T) == 2 && TL::MT == 32 && BKm == 64, "bf16, 32x32x16 MFMA, 64 rows of m per LDS tile");
+    static_assert((BM == 64 || BM == 128) && (BN == 64 || BN == 128), "tile widths the swizzle is laid out for");
+    constexpr int RA = BM * 2, RB = BN * 2;         // LDS row bytes of the two operands
+    constexpr int A_BYTES = BKm * RA, STAGE = BKm * (RA + RB);
+    constexpr int CA = BM / 8, CB = BN / 8;         // 16-byte chunks per row
+    constexpr int PA = BKm * CA / kThreads, PB = BKm * CB / kThreads;
+    constexpr int RSA = kThreads / CA, RSB = kThreads / CB;  // row step between a thread's chunks
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_m = wave / TL::WGN, wave_n = wave % TL::WGN;
+    const int tiles_n = (g.Kdim + BN - 1) / BN;
+    const unsigned lin = xcd_tile(blockIdx.y * gridDim.x + blockIdx.x, gridDim.x * gridDim.y);
+    const unsigned tile = lin % gridDim.x, slice = lin / gridDim.x;
+    const int c0 = (tile / tiles_n) * BM;
+    const int j0 = (tile % tiles_n) * BN;
+    const int m_begin = slice * g.m_per_split;
+    const int m_end = min(g.M, m_begin + g.m_per_split);
+    const int nk = (m_end - m_begin + BKm - 1) / BKm;
+
+    typename Mma<T, 32>::Acc acc[TL::TM][TL::TN];
+    zero_acc<TL>(acc);
+
+    // loader: this thread's chunk column is fixed, its rows are row0 + i * RS
+    const int a_chunk = tid % CA, a_row0 = tid / CA;
+    const int b_chunk = tid % CB, b_row0 = tid / CB;
+    const bool a_ok = c0 + a_chunk * 8 < g.Co;
+    const int jb = j0 + b_chunk * 8;
+    const bool b_ok = jb < g.Kdim;
+    const int tap = b_ok ? jb / g.Ci : 0, b_ci = b_ok ? jb % g.Ci : 0;
+    const int tap_r = tap / g.S, tap_s = tap % g.S;
+    const __amdgpu_buffer_rsrc_t rdy = make_rsrc(dy, (uint32_t)g.M * g.Co * 2u);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)g.N * g.H * g.W * g.Ci * 2u);
+    u32x4 ra[PA], rb[PB];
+    auto load_tiles = [&](int mb) {
+#pragma unroll
+        for (int i = 0; i < PA; ++i) {
+            const int m = mb + a_row0 + i * RSA;
+            ra[i] = load16(rdy, (a_ok && m < m_end) ? (uint32_t)(m * g.Co + c0 + a_chunk * 8) * 2u : kOutOfRange);
+        }
+#pragma unroll
+        for (int i = 0; i < PB; ++i) {
+            const int m = mb + b_row0 + i * RSB;
+            const uint32_t tq = fast_div((uint32_t)m, g.wo_mul, g.wo_sh);
+            const int wo = m - (int)tq * g.Wo;
+            const int n = (int)fast_div(tq, g.ho_mul, g.ho_sh);
+            const int ho = (int)tq - n * g.Ho;
+            const int hi = ho * g.stride - g.pad + tap_r, wi = wo * g.stride - g.pad + tap_s;
+            const bool ok = b_ok && m < m_end && (unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W;
+            rb[i] = load16(rx, ok ? (uint32_t)(((n * g.H + hi) * g.W + wi) * g.Ci + b_ci) * 2u : kOutOfRange);
+        }
+    };
+    auto store_tiles = [&](int buf) {
+        char* sA = smem + buf * STAGE;
+        char* sB = sA + A_BYTES;
+#pragma unroll
+        for (int i = 0; i < PA; ++i) *(u32x4*)(sA + swizzled_chunk(a_row0 + i * RSA, a_chunk, RA)) = ra[i];
+#pragma unroll
+        for (int i = 0; i < PB; ++i) *(u32x4*)(sB + swizzled_chunk(b_row0 + i * RSB, b_chunk, RB)) = rb[i];
+    };
+    // operand reads: 16-lane group = (channel half cs, m half kg); lane j of it addresses row j / 4, channels 4 (j % 4)
+    const int j16 = lane & 15, cs = (lane >> 4) & 1, kg = lane >> 5;
+    const int frag_row = 8 * kg + (j16 >> 2);            // + 16 * ks + 4 * h
+    const int frag_chunk = cs * 2 + ((j16 & 3) >> 1);    // + 4 * (32-wide tile index)
+    const int frag_half = (j16 & 1) * 8;
+    auto mma = [&](const char* sA, const char* sB) {
+#pragma unroll
+        for (int ks = 0; ks < BKm / 16; ++ks) {
+            u32x4 a[TL::TM], b[TL::TN];
+#pragma unroll
+            for (int i = 0; i < TL::TM; ++i) {
+                const int ch = (wave_m * TL::TM + i) * 4 + frag_chunk;
+                const u32x2 lo = lds_read_tr16(sA + swizzled_chunk(16 * ks + frag_row, ch, RA) + frag_half);
+                const u32x2 hi = lds_read_tr16(sA + swizzled_chunk(16 * ks + 4 + frag_row, ch, RA) + frag_half);
+                a[i] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            }
+#pragma unroll
+            for (int jn = 0; jn < TL::TN; ++jn) {
+                const int ch = (wave_n * TL::TN + jn) * 4 + frag_chunk;
+                const u32x2 lo = lds_read_tr16(sB + swizzled_chunk(16 * ks + frag_row, ch, RB) + frag_half);
+                const u32x2 hi = lds_read_tr16(sB + swizzled_chunk(16 * ks + 4 + frag_row, ch, RB) + frag_half);
+                b[jn] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            }
+#pragma unroll
+            for (int i = 0; i < TL::TM; ++i)
+#pragma unroll
+                for (int jn = 0; jn < TL::TN; ++jn) Mma<T, 32>::run(a[i], b[jn], acc[i][jn]);
+        }
+    };
+    // rows at or past m_end load as zeros, so the loop may fetch (and store into the idle stage) one tile
+    // past the slice: a single loop body with one back edge keeps the accumulators in place
+    load_tiles(m_begin);
+    store_tiles(0);
+    __syncthreads();
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+        load_tiles(m_begin + (kt + 1) * BKm);
+        mma(smem, smem + A_BYTES);
+        store_tiles(1);
+        __syncthreads();
+        load_tiles(m_begin + (kt + 2) * BKm);
+        mma(smem + STAGE, smem + STAGE + A_BYTES);
+        store_tiles(0);
+        __syncthreads();
+    }
+    if (kt < nk) mma(smem, smem + A_BYTES);
+
+    float* dst = part + (int64_t)slice * g.Co * g.Kdim;
+#pragma unroll
+    for (int i = 0; i < TL::TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < TL::TN; ++jn) {
+            const int col = j0 + (wave_n * TL::TN + jn) * 32 + lane % 32;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int co = c0 + (wave_m * TL::TM + i) * 32 + acc_row<32>(lane, e);
+                if (co < g.Co && col < g.Kdim) dst[(int64_t)co * g.Kdim + col] = acc[i][jn][e];
+            }
+        }
+}
+
 // Backward-weight of an fp32 layer with 16 input and 16 output channels.  The GEMM output is only
 // 16 x (R*S*16), so LDS tiling buys nothing: each wave streams its own output pixels straight from
 // global memory into the 16x16x4 MFMA operand layout (lane = (pixel % 4) * 16 + channel, one
@@ -1266,11 +1419,39 @@ int run_wgrad(const WgradGeom& g, int splits, const void* x, const void* dy, flo
     return DSP_OK;
 }
 
+// The transpose-read kernel serves bf16 tiles of 64 or 128 channels/columns.
+template <typename TL>
+constexpr bool kWgradTr = sizeof(typename TL::T) == 2 && TL::MT == 32 && (TL::BM == 64 || TL::BM == 128) &&
+                          (TL::BN == 64 || TL::BN == 128) && TL::BK == 64;
+
+template <typename TL>
+int run_wgrad_tr(const WgradGeom& g, int splits, const void* x, const void* dy, float* dst, hipStream_t st, double flops)
+{
+    if constexpr (kWgradTr<TL>) {
+        constexpr int LDS = 2 * TL::BK * (TL::BM + TL::BN) * 2;
+        const int tiles = ceil_div(g.Co, TL::BM) * ceil_div(g.Kdim, TL::BN);
+        auto kern = conv_wgrad_tr_kernel<TL>;
+        static std::atomic<bool> attr_done{false};
+        if (!attr_done && LDS > 48 * 1024) {
+            DSP_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
+            attr_done = true;
+        }
+        {
+            ProfScope ps(tile_name<TL, true, true>(), flops, 0);
+            DSP_LAUNCH(ps, kern, dim3(tiles, splits), dim3(kThreads), LDS, st, (const bf16_t*)x, (const bf16_t*)dy, dst, g);
+        }
+        DSP_HIP(hipGetLastError());
+        return DSP_OK;
+    } else {
+        return run_wgrad<TL, true>(g, splits, x, dy, dst, st, flops);
+    }
+}
+
 template <typename TL>
 int run_wgrad_v(const WgradGeom& g, int splits, bool vec, const void* x, const void* dy, float* dst, hipStream_t st,
                 double flops)
 {
-    return vec ? run_wgrad<TL, true>(g, splits, x, dy, dst, st, flops) : run_wgrad<TL, false>(g, splits, x, dy, dst, st, flops);
+    return vec ? run_wgrad_tr<TL>(g, splits, x, dy, dst, st, flops) : run_wgrad<TL, false>(g, splits, x, dy, dst, st, flops);
 }
 
 // Tile of the backward-weight GEMM (output Cout x R*S*Cin) and the m extent of one LDS tile.
