@@ -60,7 +60,9 @@ def _teacher_forced(cfg, params, rng, dtype, ticks):
     # oracle alone: 1 ulp on 0.01% of a block's inputs moves its G_h by ~25% over 18 ReLU layers).
     # So: the forward output and, for ReLU-free blocks, the gradients are held to 2e-2; gradients through
     # n ReLU layers are held to 6e-2 * sqrt(n) in bf16.
-    n_relu = [sum(1 for L in layers if L["op"] == "bn" and L["relu"]) for layers in cfg["blocks"]]
+    # A max pool is a branch decision of the same kind (which window element receives the gradient), and in bf16
+    # the two largest values of a window are within one ulp of each other about as often, so it counts as a layer.
+    n_relu = [sum(1 for L in layers if (L["op"] == "bn" and L["relu"]) or L["op"] == "maxpool") for layers in cfg["blocks"]]
     gtol = [(6e-2 * np.sqrt(n) if (dtype == D.DSP_BF16 and n) else tol) for n in n_relu]
     orc = O.build_cnn_oracle(cfg, params, storage="bf16" if dtype == D.DSP_BF16 else None)
     # fp32: a pre-activation within a few dozen fp32 ulps of zero (relative to the terms it is summed from; the
@@ -197,6 +199,9 @@ labels_by_batch = {}
     # of fused statistics, 512 partial sums per channel): full size, every element compared
     ("bn_probe", D.DSP_FP32, 3, {"many_decisions": True}),
     ("bn_probe", D.DSP_BF16, 3, {}),
+    # VGG-19 with batch norm (2x2 max pools inside the blocks, 512-channel layers on 4x4 and 2x2 maps)
+    ("vgg19", D.DSP_FP32, 7, {"batch": 4, "perturb": True, "many_decisions": True}),
+    ("vgg19", D.DSP_BF16, 7, {"batch": 16, "perturb": True}),   # 2x2 maps: BN over 4 * batch values per channel
     # Eq. (3) beyond the constant-step heavy ball: Nesterov (s = 1), weight decay, a step schedule that drops
     # the step size twice while every block carries momentum
     ("resnet20", D.DSP_FP32, 9, {"batch": 8, "hw": 16, "perturb": True, "sum_s": 1, "wd": 5e-4,
@@ -361,6 +366,7 @@ def test_pipeline_equals_manual_fifo_schedule_bit_for_bit(name, dtype, ticks, kw
     ("resnet20", D.DSP_FP32, 16, {"batch": 16, "hw": 16}, 2e-2),
     ("resnet56", D.DSP_FP32, 11, {"batch": 16, "hw": 16}, 2e-2),   # short: the gap to the oracle triples per tick here
     ("resnet20", D.DSP_FP32, 12, {}, 1e-3),                  # configs[1] at full size (first 12 of its 50 steps)
+    ("vgg19", D.DSP_FP32, 8, {"batch": 32}, 2e-2),
 ], ids=lambda v: v if isinstance(v, str) else None)
 def test_pipeline_loss_trajectory(name, dtype, ticks, kw, rtol):
     cfg, params, rng = _setup(name, **kw)

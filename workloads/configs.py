@@ -12,8 +12,9 @@ A block of the split CNN is a list of layer dicts.  Layer ``i`` produces tensor
 
 The architectures are the ones the benchmark configurations name in words:
 CIFAR-style ResNets (3 stages, widths 16/32/64, post-activation basic blocks,
-1x1 stride-2 projection shortcuts), a ResNet-18-style ImageNet net, and the
-conv4_x stage of a bottleneck ResNet-50 (stride on the 3x3).  The schedules are
+1x1 stride-2 projection shortcuts), a ResNet-18-style ImageNet net, the
+conv4_x stage of a bottleneck ResNet-50 (stride on the 3x3), and VGG-19 with
+batch norm for 32x32 inputs.  The schedules are
 the first rows of the paper's accuracy table for each K:
 DSP(1,0;2,0), DSP(1,1,0;4,2,0), DSP(1,1,1,0;6,4,2,0).
 """
@@ -134,6 +135,27 @@ def _resnet50_conv4x():
     return [b.layers]
 
 
+def _vgg19(classes=10, cuts=(6, 10)):
+    """VGG-19 with batch norm for 32x32 inputs (16 conv layers, a 2x2 max pool after layers 2, 4, 8, 12, 16, then
+    global average pool + one linear layer); ``cuts`` = index of the first conv layer of each later DSP block."""
+    plan = [64, 64, "M", 128, 128, "M", 256, 256, 256, 256, "M", 512, 512, 512, 512, "M", 512, 512, 512, 512, "M"]
+    blocks, b, src, cin, n_conv = [], _B(), -1, 3, 0
+    for item in plan:
+        if item == "M":
+            src = b.add(op="maxpool", **{"in": src}, k=2, stride=2, pad=0)
+            continue
+        if n_conv in cuts:
+            blocks.append(b.layers)
+            b, src = _B(), -1
+        src = b.conv(src, cin, item, 3)
+        src = b.bn(src, item)
+        cin = item
+        n_conv += 1
+    b.head(src, cin, classes)
+    blocks.append(b.layers)
+    return blocks
+
+
 def _bn_probe():
     """Two 1x1 conv + BN(+ReLU) layers, the second with an identity shortcut from the block input: a cheap
     block whose normalisation layers can be checked against the oracle at ImageNet-sized feature maps."""
@@ -158,6 +180,9 @@ CONFIGS = {
     "resnet50_conv4x": dict(blocks=_resnet50_conv4x, input=(64, 512, 28, 28), classes=None, p=(0,), m=(3,),
                             lr=0.01, beta=0.9, wd=0.0, steps=20, seed=3, dtypes=("bf16",), grad_std=0.1,
                             data_input=False),
+    # one of the further networks the paper's speed-up table names (CIFAR, K = 3)
+    "vgg19": dict(blocks=_vgg19, input=(128, 3, 32, 32), classes=10, p=(1, 1, 0), m=(4, 2, 0), lr=0.01, beta=0.9,
+                  wd=0.0, steps=50, seed=6, dtypes=("fp32", "bf16")),
     # not one of the paper-shaped workloads: a parity probe for the streaming kernels at large M (tests only)
     "bn_probe": dict(blocks=_bn_probe, input=(128, 64, 56, 56), classes=None, p=(0,), m=(1,), lr=0.01, beta=0.9,
                      wd=0.0, steps=3, seed=5, dtypes=("fp32", "bf16"), grad_std=0.1, data_input=False),
