@@ -128,58 +128,88 @@ __device__ inline double wave_sum(double v)
     return v;
 }
 
-// One wave per channel merges the partials.  Forward: mean, invstd, coef = {scale, shift}.
+// Merging the partials.  The partials of a conv epilogue can be thousands of rows (one per row tile), so a
+// workgroup of kMergeLanes x 4 threads takes 4 channels and reads whole 64-byte row segments, up to 8 loads
+// in flight per thread and added in row order; then a fixed tree over the row lanes.  Returns the two sums
+// of channel blockIdx.x * 4 + (threadIdx.x & 3) to the threads of row lane 0.
+constexpr int kMergeLanes = 64;
+typedef __attribute__((ext_vector_type(2))) double f64x2;
+__device__ inline void merge_partials(const double* __restrict__ part, int nblk, int C, double (&red)[kMergeLanes][4][2],
+                                      double* sa, double* sb)
+{
+    const int cq = threadIdx.x & 3, r = threadIdx.x >> 2;
+    const int c = blockIdx.x * 4 + cq;
+    double a = 0.0, b = 0.0;
+    if (c < C)
+        for (int k0 = r; k0 < nblk; k0 += kMergeLanes * 8) {
+            f64x2 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int k = k0 + kMergeLanes * u;
+                v[u] = k < nblk ? *(const f64x2*)(part + ((int64_t)k * C + c) * 2) : f64x2{0.0, 0.0};
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                a += v[u][0];
+                b += v[u][1];
+            }
+        }
+    red[r][cq][0] = a;
+    red[r][cq][1] = b;
+    __syncthreads();
+    for (int w = kMergeLanes / 2; w > 0; w >>= 1) {
+        if (r < w) {
+            red[r][cq][0] += red[r + w][cq][0];
+            red[r][cq][1] += red[r + w][cq][1];
+        }
+        __syncthreads();
+    }
+    *sa = red[0][cq][0];
+    *sb = red[0][cq][1];
+}
+
+// Forward: mean, invstd, coef = {scale, shift}.
 struct BnStatOut {
     const double* part;
     float *mean, *invstd, *coef;
 };
-__global__ __launch_bounds__(64) void bn_fwd_finalize_kernel(BnStatOut o0, BnStatOut o1, int nblk, int C, double inv_M,
-                                                             float eps, const float* __restrict__ gamma,
-                                                             const float* __restrict__ beta)
+__global__ __launch_bounds__(kMergeLanes * 4) void bn_fwd_finalize_kernel(BnStatOut o0, BnStatOut o1, int nblk, int C,
+                                                                          double inv_M, float eps,
+                                                                          const float* __restrict__ gamma,
+                                                                          const float* __restrict__ beta)
 {
+    __shared__ double red[kMergeLanes][4][2];
     const BnStatOut o = blockIdx.y ? o1 : o0;
-    const double* __restrict__ part = o.part;
-    float* __restrict__ mean = o.mean;
-    float* __restrict__ invstd = o.invstd;
-    float* __restrict__ coef = o.coef;
-    const int c = blockIdx.x, lane = threadIdx.x;
-    double a = 0.0, b = 0.0;
-    for (int k = lane; k < nblk; k += 64) {
-        a += part[((int64_t)k * C + c) * 2];
-        b += part[((int64_t)k * C + c) * 2 + 1];
-    }
-    a = wave_sum(a);
-    b = wave_sum(b);
-    if (lane == 0) {
+    double a, b;
+    merge_partials(o.part, nblk, C, red, &a, &b);
+    const int c = blockIdx.x * 4 + (threadIdx.x & 3);
+    if ((threadIdx.x >> 2) == 0 && c < C) {
         const double mu = a * inv_M;
         double var = b * inv_M - mu * mu;
         if (var < 0.0) var = 0.0;
         const double is = 1.0 / sqrt(var + (double)eps);
-        mean[c] = (float)mu;
-        invstd[c] = (float)is;
+        o.mean[c] = (float)mu;
+        o.invstd[c] = (float)is;
         const double sc = (double)gamma[c] * is;
-        coef[c] = (float)sc;
-        coef[C + c] = (float)((double)beta[c] - mu * sc);
+        o.coef[c] = (float)sc;
+        o.coef[C + c] = (float)((double)beta[c] - mu * sc);
     }
 }
 
 // Backward: dgamma, dbeta and dx = c1*dz - c2*x + c0 with
 // c1 = gamma*invstd, c2 = c1*invstd*dgamma/M, c0 = c2*mean - c1*dbeta/M.
-__global__ __launch_bounds__(64) void bn_bwd_finalize_kernel(const double* __restrict__ part, int nblk, int C,
-                                                             double inv_M, const float* __restrict__ gamma,
-                                                             const float* __restrict__ mean,
-                                                             const float* __restrict__ invstd, float* __restrict__ dgamma,
-                                                             float* __restrict__ dbeta, float* __restrict__ coef)
+__global__ __launch_bounds__(kMergeLanes * 4) void bn_bwd_finalize_kernel(const double* __restrict__ part, int nblk, int C,
+                                                                          double inv_M, const float* __restrict__ gamma,
+                                                                          const float* __restrict__ mean,
+                                                                          const float* __restrict__ invstd,
+                                                                          float* __restrict__ dgamma,
+                                                                          float* __restrict__ dbeta, float* __restrict__ coef)
 {
-    const int c = blockIdx.x, lane = threadIdx.x;
-    double a = 0.0, b = 0.0;
-    for (int k = lane; k < nblk; k += 64) {
-        a += part[((int64_t)k * C + c) * 2];
-        b += part[((int64_t)k * C + c) * 2 + 1];
-    }
-    a = wave_sum(a);
-    b = wave_sum(b);
-    if (lane == 0) {
+    __shared__ double red[kMergeLanes][4][2];
+    double a, b;
+    merge_partials(part, nblk, C, red, &a, &b);
+    const int c = blockIdx.x * 4 + (threadIdx.x & 3);
+    if ((threadIdx.x >> 2) == 0 && c < C) {
         dbeta[c] = (float)a;
         dgamma[c] = (float)b;
         const double c1 = (double)gamma[c] * (double)invstd[c];
@@ -291,8 +321,8 @@ int bn_forward_t(const void* x, const void* res, void* y, const float* gamma, co
         const BnStatOut o0{buf.partial, buf.mean, buf.invstd, buf.coef};
         const BnStatOut o1 = tw ? BnStatOut{tw->buf.partial, tw->buf.mean, tw->buf.invstd, tw->buf.coef} : o0;
         ProfScope ps("bn_fwd_finalize", (double)nblk * C * 16.0 * ni, 1);
-        DSP_LAUNCH(ps, bn_fwd_finalize_kernel, dim3(C, ni), dim3(64), 0, st, o0, o1, nblk, C, 1.0 / (double)M, eps, gamma,
-                   beta);
+        DSP_LAUNCH(ps, bn_fwd_finalize_kernel, dim3(ceil_div(C, 4), ni), dim3(kMergeLanes * 4), 0, st, o0, o1, nblk, C,
+                   1.0 / (double)M, eps, gamma, beta);
     }
     const int64_t nvec = M * (C / VW);
     const dim3 ag(apply_grid(nvec), ni);
@@ -328,7 +358,7 @@ int bn_backward_t(const void* dy, const void* x, const void* y, void* dx, void* 
     }
     {
         ProfScope ps("bn_bwd_finalize", (double)nblk * C * 16.0, 1);
-        DSP_LAUNCH(ps, bn_bwd_finalize_kernel, dim3(C), dim3(64), 0, st, (const double*)buf.partial, nblk, C,
+        DSP_LAUNCH(ps, bn_bwd_finalize_kernel, dim3(ceil_div(C, 4)), dim3(kMergeLanes * 4), 0, st, (const double*)buf.partial, nblk, C,
                    1.0 / (double)M, gamma, (const float*)buf.mean, (const float*)buf.invstd, dgamma, dbeta, buf.coef);
     }
     const int64_t nvec = M * (C / VW);
