@@ -505,6 +505,22 @@ __global__ __launch_bounds__(kThreads) void pad_channels_kernel(const T* __restr
     }
 }
 
+// The common case: the padded pixel is one 16-byte run (4 floats / 8 bf16).  One thread per pixel: scalar loads of
+// neighbouring pixels coalesce, the store is a whole run.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void pad_channels_run_kernel(const T* __restrict__ src, T* __restrict__ dst,
+                                                                    int64_t pixels, int C)
+{
+    constexpr int CP = 16 / (int)sizeof(T);
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+    for (int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x; p < pixels; p += (int64_t)gridDim.x * kThreads) {
+        alignas(16) T v[CP];
+#pragma unroll
+        for (int c = 0; c < CP; ++c) v[c] = c < C ? src[p * C + c] : from_float<T>(0.f);
+        *(u32x4*)(dst + p * CP) = *(const u32x4*)v;
+    }
+}
+
 __global__ __launch_bounds__(kThreads) void unpad_rows_kernel(const float* __restrict__ src, float* __restrict__ dst,
                                                               int64_t rows, int C, int Cp)
 {
@@ -517,6 +533,16 @@ int launch_pad_channels(int dtype, const void* src, void* dst, int64_t pixels, i
 {
     DSP_REQUIRE(src && dst && pixels > 0 && C > 0 && Cp >= C, DSP_EINVAL, "pad_channels: bad argument");
     ProfScope ps("pad_channels", (double)pixels * (C + Cp) * dtype_size(dtype), 1);
+    if (Cp * dtype_size(dtype) == 16 && ((uintptr_t)dst % 16) == 0) {
+        if (dtype == DSP_BF16)
+            DSP_LAUNCH(ps, pad_channels_run_kernel<bf16_t>, dim3(grid_for(pixels)), dim3(kThreads), 0, st,
+                       (const bf16_t*)src, (bf16_t*)dst, pixels, C);
+        else
+            DSP_LAUNCH(ps, pad_channels_run_kernel<float>, dim3(grid_for(pixels)), dim3(kThreads), 0, st, (const float*)src,
+                       (float*)dst, pixels, C);
+        DSP_HIP(hipGetLastError());
+        return DSP_OK;
+    }
     if (dtype == DSP_BF16)
         DSP_LAUNCH(ps, pad_channels_kernel<bf16_t>, dim3(grid_for(pixels * Cp)), dim3(kThreads), 0, st, (const bf16_t*)src,
                    (bf16_t*)dst, pixels, C, Cp);
