@@ -1356,6 +1356,7 @@ int select_gather_tile(const GatherGeom& g, int* bm)
         return 7;
     }
     if (g.Co % 128 == 0 && tile_count(g, 128, 128) >= kEnoughTiles) { *bm = 128; return 4; }
+    if (sizeof(T) == 2 && g.Co == 64 && tile_count(g, 256, 64) >= kEnoughTiles) { *bm = 256; return 10; }
     if (tile_count(g, 128, 64) >= kEnoughTiles) { *bm = 128; return 5; }
     if (tile_count(g, 64, 64) >= kEnoughTiles) { *bm = 64; return 6; }
     *bm = 32;
@@ -1396,6 +1397,7 @@ int dispatch_gather(GatherGeom g, bool accum, const void* in, const void* w, voi
     case 5: return run_gather_v<Tile<T, 32, 2, 2, 2, 1, KB, 2>>(g, vec, in, w, out, st, flops);
     case 6: return run_gather_v<Tile<T, 32, 2, 2, 1, 1, KB, 2>>(g, vec, in, w, out, st, flops);
     case 7: return run_gather_v<Tile<T, 16, 4, 1, 1, 2, 128, 2>>(g, vec, in, w, out, st, flops);
+    case 10: return run_gather_v<Tile<T, 32, 4, 1, 2, 2, 64, 2>>(g, vec, in, w, out, st, flops);
     default: return run_gather_v<Tile<T, 16, 2, 2, 1, 1, 256, 2>>(g, vec, in, w, out, st, flops);
     }
 }
