@@ -115,6 +115,8 @@ struct Tile {
     static constexpr int EPI_BYTES = BM * EPI_ROWB;
     static constexpr int STATS_BYTES = kThreads * 2 * (int)sizeof(double);  // column-sum scratch behind the staged tile
     static constexpr int LDS_BYTES = cmax(LOAD_BYTES, EPI_BYTES + STATS_BYTES);
+    // waves per SIMD the register allocation aims for (the LDS footprint allows as many workgroups)
+    static constexpr int MIN_WAVES = (sizeof(T) == 2 && BM == 128 && BN == 128 && BKB == 64) ? 3 : 1;
     static_assert(BKB % KSB == 0 && kThreads % CPR == 0 && (STAGES == 1 || STAGES == 2), "tile shape");
     static_assert(kThreads % BN == 0 && EPI_BYTES % 8 == 0, "column sums: whole row groups, aligned scratch");
 };
@@ -199,7 +201,7 @@ __device__ inline unsigned xcd_tile(unsigned b, unsigned nb)
 }
 
 template <typename TL, bool VEC, bool DIL>
-__global__ __launch_bounds__(kThreads) void conv_gather_gemm_kernel(const typename TL::T* __restrict__ in_,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MIN_WAVES))) void conv_gather_gemm_kernel(const typename TL::T* __restrict__ in_,
                                                                     const typename TL::T* __restrict__ wgt,
                                                                     typename TL::T* __restrict__ out_, GatherGeom g)
 {
@@ -1393,7 +1395,11 @@ int dispatch_gather(GatherGeom g, bool accum, const void* in, const void* w, voi
     case 1: return run_gather_v<Tile<T, 16, 4, 1, 1, 1, 64, 2>>(g, vec, in, w, out, st, flops);
     case 2: return run_gather_v<Tile<T, 32, 4, 1, 2, 1, 64, 2>>(g, vec, in, w, out, st, flops);
     case 3: return run_gather_v<Tile<T, 32, 4, 1, 1, 1, 128, 2>>(g, vec, in, w, out, st, flops);
-    case 4: return run_gather_v<Tile<T, 32, 2, 2, 2, 2, KB, 2>>(g, vec, in, w, out, st, flops);
+    case 4:
+        // short contractions (1x1 filters over few channels) of bf16: 32-deep k steps and three workgroups per
+        // compute unit; the two-tile prologue is half as long and the epilogues of more workgroups overlap
+        if (sizeof(T) == 2 && g.Kdim <= 512) return run_gather_v<Tile<T, 32, 2, 2, 2, 2, 64, 2>>(g, vec, in, w, out, st, flops);
+        return run_gather_v<Tile<T, 32, 2, 2, 2, 2, KB, 2>>(g, vec, in, w, out, st, flops);
     case 5: return run_gather_v<Tile<T, 32, 2, 2, 2, 1, KB, 2>>(g, vec, in, w, out, st, flops);
     case 6: return run_gather_v<Tile<T, 32, 2, 2, 1, 1, KB, 2>>(g, vec, in, w, out, st, flops);
     case 7: return run_gather_v<Tile<T, 16, 4, 1, 1, 2, 128, 2>>(g, vec, in, w, out, st, flops);
