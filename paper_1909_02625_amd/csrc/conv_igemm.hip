@@ -1172,6 +1172,29 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
 
 // The same sum for few slices (<= 8): there the tree above would leave most thread rows idle, so each
 // thread adds the slices of 4 consecutive elements in ascending order.
+// s[v] += part[k * n + v] for k = 0 .. splits-1 in that order, 8 loads in flight.
+template <int VW>
+__device__ inline void flat_slice_sum(const float* __restrict__ src0, int n, int splits, float (&s)[VW])
+{
+    for (int k0 = 0; k0 < splits; k0 += 8) {
+        f32x4 t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float* src = src0 + (int64_t)(k0 + u) * n;
+            if (k0 + u < splits) {
+                if (VW == 4) t[u] = *(const f32x4*)src; else t[u] = f32x4{src[0], 0.f, 0.f, 0.f};
+            } else {
+                t[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (k0 + u < splits)
+#pragma unroll
+                for (int v = 0; v < VW; ++v) s[v] += t[u][v];
+    }
+}
+
 template <int VW>
 __global__ __launch_bounds__(256) void wgrad_reduce_few_kernel(const float* __restrict__ part, float* __restrict__ dw,
                                                                int n, int splits)
@@ -1181,31 +1204,27 @@ __global__ __launch_bounds__(256) void wgrad_reduce_few_kernel(const float* __re
     float s[VW];
 #pragma unroll
     for (int v = 0; v < VW; ++v) s[v] = 0.f;
-    for (int k = 0; k < splits; ++k) {
-        const float* src = part + (int64_t)k * n + i;
-        if (VW == 4) {
-            const f32x4 t = *(const f32x4*)src;
-#pragma unroll
-            for (int v = 0; v < VW; ++v) s[v] += t[v];
-        } else {
-            s[0] += src[0];
-        }
-    }
+    flat_slice_sum<VW>(part + i, n, splits, s);
     if (VW == 4)
         *(f32x4*)(dw + i) = f32x4{s[0], s[1], s[2], s[3]};
     else
         dw[i] = s[0];
 }
 
+// The flat loop (one thread adds the slices of its 4 elements in ascending order) is used when there are
+// few slices, and also whenever the gradient is long enough for its 1024-element workgroups to fill the
+// chip: it reads whole 4 KiB runs of every slice, where the tree reads 128-byte pieces.
+inline bool wgrad_reduce_flat(size_t n, int splits) { return splits <= 8 || n >= 65536; }
+
 // All slice sums of a block's conv layers in ONE launch (the per-layer sums are tiny and the idle gap
 // between two launches costs as much as each of them).  A workgroup looks up its task and then does
-// exactly what the two kernels above do: the tree over 32 elements when the task has more than 8
-// slices, else the flat loop over 1024 elements.
+// exactly what the two kernels above do: the flat loop over 1024 elements or the tree over 32.
 struct ReduceTask {
     const float* part;
     float* dw;
     int n, splits;
     int block_begin;  // first workgroup of the task
+    int flat;         // flat loop over 1024 elements per workgroup, else the tree over 32
 };
 
 template <int VW>
@@ -1219,24 +1238,17 @@ __global__ __launch_bounds__(256) void wgrad_reduce_all_kernel(const ReduceTask*
     const int blk = (int)blockIdx.x - t.block_begin;
     const float* __restrict__ part = t.part;
     const int n = t.n, splits = t.splits;
-    if (splits <= 8) {  // uniform per workgroup
+    if (t.flat) {  // uniform per workgroup
         const int64_t i = ((int64_t)blk * 256 + threadIdx.x) * VW;
         if (i >= n) return;
         float s[VW];
 #pragma unroll
         for (int v = 0; v < VW; ++v) s[v] = 0.f;
-        for (int k = 0; k < splits; ++k) {
-            const float* src = part + (int64_t)k * n + i;
-            if (VW == 4) {
-                const f32x4 v4 = *(const f32x4*)src;
-#pragma unroll
-                for (int v = 0; v < VW; ++v) s[v] += v4[v];
-            } else {
-                s[0] += src[0];
-            }
-        }
-#pragma unroll
-        for (int v = 0; v < VW; ++v) t.dw[i + v] = s[v];
+        flat_slice_sum<VW>(part + i, n, splits, s);
+        if (VW == 4)
+            *(f32x4*)(t.dw + i) = f32x4{s[0], s[1], s[2], s[3]};
+        else
+            t.dw[i] = s[0];
         return;
     }
     const int cg = threadIdx.x % COLS, row = threadIdx.x / COLS;
@@ -1554,10 +1566,11 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
     if (splits > 1 && !defer_reduce) {
         ProfScope ps("wgrad_reduce", (double)n * (splits + 1) * 4.0, 1);
         const bool v4 = n % 4 == 0 && ((uintptr_t)ws % 16) == 0 && ((uintptr_t)dw % 16) == 0;
-        if (splits <= 8 && v4)
+        const bool flat = wgrad_reduce_flat(n, splits);
+        if (flat && v4)
             DSP_LAUNCH(ps, wgrad_reduce_few_kernel<4>, dim3(ceil_div(n / 4, 256)), dim3(256), 0, st, (const float*)ws, dw,
                        (int)n, splits);
-        else if (splits <= 8)
+        else if (flat)
             DSP_LAUNCH(ps, wgrad_reduce_few_kernel<1>, dim3(ceil_div(n, 256)), dim3(256), 0, st, (const float*)ws, dw, (int)n,
                        splits);
         else if (n % 4 == 0 && ((uintptr_t)ws % 16) == 0)
@@ -1723,8 +1736,9 @@ int wgrad_reduce_set_create(const WgradReduceItem* items, int n, WgradReduceSet*
     for (int i = 0; i < n; ++i) {
         const WgradReduceItem& it = items[i];
         if (it.slices <= 1) continue;
-        tasks.push_back(ReduceTask{it.partials, it.dw, (int)it.n, it.slices, s->blocks});
-        const int per_block = it.slices <= 8 ? 256 * (s->vec4 ? 4 : 1) : 32;
+        const bool flat = wgrad_reduce_flat(it.n, it.slices);
+        tasks.push_back(ReduceTask{it.partials, it.dw, (int)it.n, it.slices, s->blocks, flat ? 1 : 0});
+        const int per_block = flat ? 256 * (s->vec4 ? 4 : 1) : 32;
         s->blocks += ceil_div((int64_t)it.n, per_block);
         s->bytes += (double)it.n * (it.slices + 1) * 4.0;
     }
