@@ -1343,12 +1343,13 @@ bool direct_eligible(const GatherGeom& g, const void* in, const void* out)
            ((uintptr_t)in % 16) == 0 && ((uintptr_t)out % 16) == 0;
 }
 
-// Workgroups of the direct kernel: two per compute unit unless there are fewer pixel groups.
+// Workgroups of the direct kernel: one per compute unit unless there are fewer pixel groups (measured in the
+// three-stream pipeline: 256 beats 128, 192, 384, 512 and 1024).
 inline int direct_grid(const GatherGeom& g)
 {
     const int per_block = 4 / (g.Co / 16);
     const int blocks = ceil_div(ceil_div(g.M, 16), per_block);
-    return blocks < 512 ? blocks : 512;
+    return blocks < 256 ? blocks : 256;
 }
 
 // Largest tile of the channel class that still yields enough workgroups; for small problems (the
