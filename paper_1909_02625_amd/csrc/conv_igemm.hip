@@ -1495,7 +1495,10 @@ int wgrad_splits(const ConvShape& c, const WgradPlan& pl, int* m_per_split)
 {
     const int64_t M = (int64_t)c.N * c.Ho * c.Wo, Kdim = (int64_t)c.R * c.S * c.Cin;
     const int tiles = ceil_div(c.Cout, pl.bm) * ceil_div(Kdim, pl.bn);
-    int want = 512 / tiles;  // rounded down: one workgroup too many costs a whole second round
+    // two workgroups per compute unit, one for small problems (below ~1 GMAC, the CIFAR-sized layers: measured in
+    // the three-stream pipeline); rounded down: one workgroup too many costs a whole second round
+    const int target = (double)M * (double)Kdim * (double)c.Cout < 1e9 ? 256 : 512;
+    int want = target / tiles;
     const int max_by_len = (int)((M + 8 * pl.bk - 1) / (8 * pl.bk));
     if (want > max_by_len) want = max_by_len;
     if (want < 1) want = 1;
