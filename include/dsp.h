@@ -58,14 +58,15 @@ typedef enum dsp_op {
     DSP_OP_MAXPOOL = 2,   /* r x r window, stride, pad (-inf padding, first maximum wins) */
     DSP_OP_GAP = 3,       /* global average pool over H, W */
     DSP_OP_LINEAR = 4,    /* z = W h + c */
-    DSP_OP_SOFTMAX_CE = 5 /* L = mean over the batch of -log softmax(z)[label]; last block only */
+    DSP_OP_SOFTMAX_CE = 5, /* L = mean over the batch of -log softmax(z)[label]; last block only */
+    DSP_OP_ADD = 6         /* y = in0 + in1, two feature maps of one shape (shortcut of a pre-activation unit) */
 } dsp_op;
 
 /* One layer of a block.  Layer i produces tensor i; in0 = -1 names the block input h_k. */
 typedef struct dsp_layer_desc {
     int32_t op;     /* dsp_op */
     int32_t in0;    /* producer of the input: layer index, or -1 for the block input */
-    int32_t in1;    /* BN only: tensor added after normalisation (residual), or -2 for none */
+    int32_t in1;    /* BN: tensor added after normalisation (residual), or -2 for none; ADD: the second operand */
     int32_t cin;    /* conv/linear input channels; BN channels */
     int32_t cout;   /* conv/linear output channels */
     int32_t r, s;   /* conv filter height/width; maxpool window (r) */

@@ -293,6 +293,9 @@ class CNNBlock:
                 y = rnd(np.maximum(z, 0.0) if L["relu"] else z)
                 T.append(y)
                 aux.append((mean, invstd, y, knife))
+            elif op == "add":  # element-wise sum of two feature maps (the shortcut of a pre-activation unit)
+                T.append(rnd(x + src(L["res"])))
+                aux.append(None)
             elif op == "maxpool":
                 y, arg = maxpool_forward(x, L["k"], L["stride"], L["pad"])
                 T.append(y)
@@ -347,6 +350,9 @@ class CNNBlock:
                 dx, dg, db = bn_backward(g, x, prm["gamma"], mean, invstd)
                 grads[i]["gamma"], grads[i]["beta"] = dg, db
                 add(L["in"], dx)
+            elif op == "add":
+                add(L["res"], g)
+                add(L["in"], g)
             elif op == "maxpool":
                 add(L["in"], maxpool_backward(g, aux[i], x.shape))
             elif op == "gap":

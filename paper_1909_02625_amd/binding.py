@@ -29,7 +29,7 @@ __all__ = [
 ]
 
 DSP_FP32, DSP_BF16 = 0, 1
-_OPS = {"conv": 0, "bn": 1, "maxpool": 2, "gap": 3, "linear": 4, "softmax_ce": 5}
+_OPS = {"conv": 0, "bn": 1, "maxpool": 2, "gap": 3, "linear": 4, "softmax_ce": 5, "add": 6}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -173,7 +173,7 @@ def make_block_desc(layers, in_shape, dtype, k, K, m_k, p_prev=0, needs_input_gr
         d.r, d.s = L.get("r", L.get("k", 0)), L.get("s", L.get("k", 0))
         d.stride, d.pad = L.get("stride", 1), L.get("pad", 0)
         d.relu = int(bool(L.get("relu", False)))
-        if L["op"] == "bn" and L.get("res") is not None:
+        if L["op"] in ("bn", "add") and L.get("res") is not None:
             d.in1 = L["res"]
     n, c, h, w = in_shape
     desc = dsp_block_desc(len(layers), arr, n, c, h, w, dtype, k, K, m_k, p_prev, int(bool(needs_input_grad)), bn_eps)

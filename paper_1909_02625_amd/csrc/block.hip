@@ -241,6 +241,13 @@ static int build_graph(dsp_block* b)
             L.p0 = poff; L.p1 = poff + s.C;
             poff += 2 * (size_t)s.C;
             break;
+        case DSP_OP_ADD: {
+            DSP_REQUIRE(!s.is_float && L.d.in1 >= -1 && L.d.in1 < i, DSP_EINVAL, "layer %d: add needs two earlier feature maps", i);
+            const Tensor& r = L.d.in1 < 0 ? b->input : b->T[L.d.in1];
+            DSP_REQUIRE(!r.is_float && r.C == s.C && r.H == s.H && r.W == s.W, DSP_EINVAL, "layer %d: add shape mismatch", i);
+            t.C = s.C; t.H = s.H; t.W = s.W;
+            break;
+        }
         case DSP_OP_MAXPOOL:
             DSP_REQUIRE(!s.is_float && L.d.r > 0 && L.d.stride > 0 && L.d.pad >= 0 && L.d.pad < L.d.r, DSP_EINVAL,
                         "layer %d: bad maxpool", i);
@@ -284,7 +291,7 @@ static int build_graph(dsp_block* b)
         if (i != b->out_idx) DSP_REQUIRE(written[i + 1], DSP_EINVAL, "layer %d: output is never used", i);
         L.in0_grad = !(L.d.in0 < 0 && !d.needs_input_grad);
         if (L.in0_grad) { L.in0_acc = written[L.d.in0 + 1]; written[L.d.in0 + 1] = 1; }
-        if (L.d.op == DSP_OP_BN && L.d.in1 != -2) {
+        if ((L.d.op == DSP_OP_BN && L.d.in1 != -2) || L.d.op == DSP_OP_ADD) {
             L.in1_grad = !(L.d.in1 < 0 && !d.needs_input_grad);
             if (L.in1_grad) { L.in1_acc = written[L.d.in1 + 1]; written[L.d.in1 + 1] = 1; }
         } else {
@@ -480,6 +487,13 @@ static int run_forward(dsp_block* b, const ForwardPass& P, const ForwardPass* tw
                                       L.d.relu != 0, bn_buffers(P), st, L.sum_tiles, twin ? &tw : nullptr));
             break;
         }
+        case DSP_OP_ADD:
+            for (int q = 0; q < passes; ++q) {
+                const ForwardPass& p = q ? *twin : P;
+                DSP_TRY(launch_add_forward(b->dtype, src_of(p, L.d.in0), src_of(p, L.d.in1), act_of(p, i),
+                                           (int64_t)s.N * s.H * s.W * s.C, st));
+            }
+            break;
         case DSP_OP_MAXPOOL:
             for (int q = 0; q < passes; ++q) {
                 const ForwardPass& p = q ? *twin : P;
@@ -540,6 +554,13 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
             DSP_TRY(launch_bn_backward(b->dtype, dy, src, b->T[i].act, grad_of(L.d.in0), dres, L.in1_acc, L.in0_acc,
                                        b->x + L.p0, b->g + L.p0, b->g + L.p1, (int64_t)s.N * s.H * s.W, s.C,
                                        L.d.relu != 0, buf, st));
+            break;
+        }
+        case DSP_OP_ADD: {
+            // in0 then in1, the order in which the overwrite / accumulate flags were decided
+            const int64_t n_el = (int64_t)s.N * s.H * s.W * s.C;
+            if (L.in0_grad) DSP_TRY(launch_grad_pass(b->dtype, dy, grad_of(L.d.in0), n_el, L.in0_acc, st));
+            if (L.in1_grad) DSP_TRY(launch_grad_pass(b->dtype, dy, grad_of(L.d.in1), n_el, L.in1_acc, st));
             break;
         }
         case DSP_OP_MAXPOOL:

@@ -505,6 +505,37 @@ __global__ __launch_bounds__(kThreads) void pad_channels_kernel(const T* __restr
     }
 }
 
+// ---- element-wise sum of two feature maps and its backward (the gradient passes to both operands) ----
+template <typename T, int VW>
+__global__ __launch_bounds__(kThreads) void add_fwd_kernel(const T* __restrict__ a, const T* __restrict__ b,
+                                                           T* __restrict__ y, int64_t nvec)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * kThreads) {
+        float va[VW], vb[VW];
+        VecIO<T, VW>::load(a + i * VW, va);
+        VecIO<T, VW>::load(b + i * VW, vb);
+#pragma unroll
+        for (int v = 0; v < VW; ++v) va[v] += vb[v];
+        VecIO<T, VW>::store(y + i * VW, va);
+    }
+}
+
+template <typename T, int VW, bool ACC>
+__global__ __launch_bounds__(kThreads) void grad_pass_kernel(const T* __restrict__ dy, T* __restrict__ dx, int64_t nvec)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * kThreads) {
+        float v[VW];
+        VecIO<T, VW>::load(dy + i * VW, v);
+        if (ACC) {
+            float o[VW];
+            VecIO<T, VW>::load(dx + i * VW, o);
+#pragma unroll
+            for (int k = 0; k < VW; ++k) v[k] += o[k];
+        }
+        VecIO<T, VW>::store(dx + i * VW, v);
+    }
+}
+
 // The common case: the padded pixel is one 16-byte run (4 floats / 8 bf16).  One thread per pixel: scalar loads of
 // neighbouring pixels coalesce, the store is a whole run.
 template <typename T>
@@ -527,6 +558,51 @@ __global__ __launch_bounds__(kThreads) void unpad_rows_kernel(const float* __res
     const int64_t total = rows * C;
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads)
         dst[i] = src[(i / C) * Cp + i % C];
+}
+
+template <typename T>
+static int add_forward_t(const void* a, const void* b, void* y, int64_t n, hipStream_t st)
+{
+    constexpr int VW = 16 / (int)sizeof(T);
+    ProfScope ps("add_fwd", (double)n * 3.0 * sizeof(T), 1);
+    const bool vec = n % VW == 0 && ((uintptr_t)a % 16) == 0 && ((uintptr_t)b % 16) == 0 && ((uintptr_t)y % 16) == 0;
+    if (vec)
+        DSP_LAUNCH(ps, (add_fwd_kernel<T, VW>), dim3(grid_for(n / VW)), dim3(kThreads), 0, st, (const T*)a, (const T*)b,
+                   (T*)y, n / VW);
+    else
+        DSP_LAUNCH(ps, (add_fwd_kernel<T, 1>), dim3(grid_for(n)), dim3(kThreads), 0, st, (const T*)a, (const T*)b, (T*)y, n);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+int launch_add_forward(int dtype, const void* a, const void* b, void* y, int64_t n, hipStream_t st)
+{
+    DSP_REQUIRE(a && b && y && n > 0, DSP_EINVAL, "add: bad argument");
+    return dtype == DSP_BF16 ? add_forward_t<bf16_t>(a, b, y, n, st) : add_forward_t<float>(a, b, y, n, st);
+}
+
+template <typename T>
+static int grad_pass_t(const void* dy, void* dx, int64_t n, bool accumulate, hipStream_t st)
+{
+    constexpr int VW = 16 / (int)sizeof(T);
+    ProfScope ps("add_bwd", (double)n * (accumulate ? 3.0 : 2.0) * sizeof(T), 1);
+    const bool vec = n % VW == 0 && ((uintptr_t)dy % 16) == 0 && ((uintptr_t)dx % 16) == 0;
+#define GRAD_PASS(V, A, CNT) \
+    DSP_LAUNCH(ps, (grad_pass_kernel<T, V, A>), dim3(grid_for(CNT)), dim3(kThreads), 0, st, (const T*)dy, (T*)dx, (int64_t)(CNT))
+    if (vec) {
+        if (accumulate) GRAD_PASS(VW, true, n / VW); else GRAD_PASS(VW, false, n / VW);
+    } else {
+        if (accumulate) GRAD_PASS(1, true, n); else GRAD_PASS(1, false, n);
+    }
+#undef GRAD_PASS
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+int launch_grad_pass(int dtype, const void* dy, void* dx, int64_t n, bool accumulate, hipStream_t st)
+{
+    DSP_REQUIRE(dy && dx && n > 0, DSP_EINVAL, "add backward: bad argument");
+    return dtype == DSP_BF16 ? grad_pass_t<bf16_t>(dy, dx, n, accumulate, st) : grad_pass_t<float>(dy, dx, n, accumulate, st);
 }
 
 int launch_pad_channels(int dtype, const void* src, void* dst, int64_t pixels, int C, int Cp, hipStream_t st)

@@ -64,6 +64,12 @@ def _teacher_forced(cfg, params, rng, dtype, ticks):
     # the two largest values of a window are within one ulp of each other about as often, so it counts as a layer.
     n_relu = [sum(1 for L in layers if (L["op"] == "bn" and L["relu"]) or L["op"] == "maxpool") for layers in cfg["blocks"]]
     gtol = [(6e-2 * np.sqrt(n) if (dtype == D.DSP_BF16 and n) else tol) for n in n_relu]
+    # bf16 forward output: every stored feature map is rounded on both sides, and where the fp32 and the fp64
+    # value straddle a rounding boundary the two stored values differ by a whole ulp (~4e-3 relative); these
+    # differences add in quadrature over the n maps of a block: 4e-3 * sqrt(n), which exceeds the 2e-2 of the
+    # usual ~20-layer blocks only for the 128-layer blocks of the pre-activation net.
+    n_maps = [sum(1 for L in layers if L["op"] in ("conv", "bn", "add", "maxpool")) for layers in cfg["blocks"]]
+    otol = [max(tol, 4e-3 * np.sqrt(n)) if dtype == D.DSP_BF16 else tol for n in n_maps]
     orc = O.build_cnn_oracle(cfg, params, storage="bf16" if dtype == D.DSP_BF16 else None)
     # fp32: a pre-activation within a few dozen fp32 ulps of zero (relative to the terms it is summed from; the
     # conv sum feeding it carries the rounding of 144-576 products and may itself be a cancellation)
@@ -122,7 +128,7 @@ def _teacher_forced(cfg, params, rng, dtype, ticks):
                 torch.cuda.synchronize()
                 e = rel_err(from_dev(d_out, oshape), rec["out"][k])
                 worst["out"] = max(worst.get("out", 0), e)
-                assert e < tol, ("h_out", tau, k, e)
+                assert e < otol[k], ("h_out", tau, k, e)
                 if has_loss:
                     assert abs(d_loss.item() - rec["loss"]) < tol * max(1.0, abs(rec["loss"])), (tau, d_loss.item(), rec["loss"])
                 bb = rec["bwd"][k]
@@ -202,6 +208,9 @@ labels_by_batch = {}
     # VGG-19 with batch norm (2x2 max pools inside the blocks, 512-channel layers on 4x4 and 2x2 maps)
     ("vgg19", D.DSP_FP32, 7, {"batch": 4, "perturb": True, "many_decisions": True}),
     ("vgg19", D.DSP_BF16, 7, {"batch": 16, "perturb": True}),   # 2x2 maps: BN over 4 * batch values per channel
+    # pre-activation bottleneck ResNet-164 (element-wise add layers, BN directly on a block input, 128 layers per block)
+    ("resnet164", D.DSP_FP32, 7, {"batch": 4, "hw": 16, "perturb": True, "many_decisions": True}),
+    ("resnet164", D.DSP_BF16, 7, {"batch": 8, "hw": 16, "perturb": True}),
     # Eq. (3) beyond the constant-step heavy ball: Nesterov (s = 1), weight decay, a step schedule that drops
     # the step size twice while every block carries momentum
     ("resnet20", D.DSP_FP32, 9, {"batch": 8, "hw": 16, "perturb": True, "sum_s": 1, "wd": 5e-4,

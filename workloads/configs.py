@@ -5,6 +5,7 @@ A block of the split CNN is a list of layer dicts.  Layer ``i`` produces tensor
 
   conv        cin, cout, r, s, stride, pad           (cross-correlation, no bias)
   bn          c, res (tensor index, -1, or None), relu   y = [relu](BN(x) [+ res])
+  add         res (tensor index or -1)               y = x + res
   maxpool     k, stride, pad
   gap         global average pool over H, W
   linear      cin, cout                              z = W h + c
@@ -13,8 +14,8 @@ A block of the split CNN is a list of layer dicts.  Layer ``i`` produces tensor
 The architectures are the ones the benchmark configurations name in words:
 CIFAR-style ResNets (3 stages, widths 16/32/64, post-activation basic blocks,
 1x1 stride-2 projection shortcuts), a ResNet-18-style ImageNet net, the
-conv4_x stage of a bottleneck ResNet-50 (stride on the 3x3), and VGG-19 with
-batch norm for 32x32 inputs.  The schedules are
+conv4_x stage of a bottleneck ResNet-50 (stride on the 3x3), VGG-19 with
+batch norm for 32x32 inputs, and the pre-activation bottleneck ResNet-164.  The schedules are
 the first rows of the paper's accuracy table for each K:
 DSP(1,0;2,0), DSP(1,1,0;4,2,0), DSP(1,1,1,0;6,4,2,0).
 """
@@ -65,6 +66,18 @@ class _B:
             sc = src
         return self.bn(a, cout, relu=True, res=sc)
 
+    def preact_bottleneck(self, src, cin, mid, cout, stride):
+        """Pre-activation bottleneck unit: BN-ReLU-conv three times, the shortcut added to the last conv's output;
+        a unit that changes shape takes its 1x1 projection shortcut from the first activation."""
+        t = self.bn(src, cin, relu=True)
+        a = self.conv(t, cin, mid, 1, 1, pad=0)
+        a = self.bn(a, mid, relu=True)
+        a = self.conv(a, mid, mid, 3, stride)
+        a = self.bn(a, mid, relu=True)
+        a = self.conv(a, mid, cout, 1, 1, pad=0)
+        sc = self.conv(t, cin, cout, 1, stride, pad=0) if (stride != 1 or cin != cout) else src
+        return self.add(op="add", **{"in": a}, res=sc)
+
     def head(self, src, c, classes):
         a = self.add(op="gap", **{"in": src})
         a = self.add(op="linear", **{"in": a}, cin=c, cout=classes)
@@ -103,6 +116,31 @@ def _resnet_cifar(per_block_units, classes, widths=(16, 32, 64), units_per_stage
         pos += cnt
         if bi == len(per_block_units) - 1:
             b.head(src, widths[-1], classes)
+        blocks.append(b.layers)
+    return blocks
+
+
+def _preact_resnet_cifar(per_block_units, classes, units_per_stage=18, widths=(16, 32, 64)):
+    """Pre-activation bottleneck ResNet for 32x32 inputs (ResNet-164 with 18 units per stage): 3x3 stem conv,
+    three stages of bottleneck units with 4x expansion, final BN-ReLU, global average pool, linear."""
+    seq, cin = [], widths[0]
+    for si, w in enumerate(widths):
+        for u in range(units_per_stage):
+            seq.append((cin, w, 4 * w, 2 if (si > 0 and u == 0) else 1))
+            cin = 4 * w
+    assert sum(per_block_units) == len(seq)
+    blocks, pos = [], 0
+    for bi, cnt in enumerate(per_block_units):
+        b = _B()
+        src = -1
+        if bi == 0:
+            src = b.conv(-1, 3, widths[0], 3)
+        for (ci, mid, co, st) in seq[pos:pos + cnt]:
+            src = b.preact_bottleneck(src, ci, mid, co, st)
+        pos += cnt
+        if bi == len(per_block_units) - 1:
+            src = b.bn(src, 4 * widths[-1], relu=True)
+            b.head(src, 4 * widths[-1], classes)
         blocks.append(b.layers)
     return blocks
 
@@ -183,6 +221,9 @@ CONFIGS = {
     # one of the further networks the paper's speed-up table names (CIFAR, K = 3)
     "vgg19": dict(blocks=_vgg19, input=(128, 3, 32, 32), classes=10, p=(1, 1, 0), m=(4, 2, 0), lr=0.01, beta=0.9,
                   wd=0.0, steps=50, seed=6, dtypes=("fp32", "bf16")),
+    # the network of the paper's gradient-difference and straggler experiments (CIFAR, K = 3)
+    "resnet164": dict(blocks=lambda: _preact_resnet_cifar((18, 18, 18), 10), input=(128, 3, 32, 32), classes=10,
+                      p=(1, 1, 0), m=(4, 2, 0), lr=0.01, beta=0.9, wd=0.0, steps=50, seed=7, dtypes=("fp32", "bf16")),
     # not one of the paper-shaped workloads: a parity probe for the streaming kernels at large M (tests only)
     "bn_probe": dict(blocks=_bn_probe, input=(128, 64, 56, 56), classes=None, p=(0,), m=(1,), lr=0.01, beta=0.9,
                      wd=0.0, steps=3, seed=5, dtypes=("fp32", "bf16"), grad_std=0.1, data_input=False),
@@ -227,6 +268,9 @@ def infer_shapes(layers, in_shape):
             assert s[1] == L["c"]
             if L["res"] is not None:
                 assert sh(L["res"]) == s, (sh(L["res"]), s)
+            shapes.append(s)
+        elif op == "add":
+            assert sh(L["res"]) == s, (sh(L["res"]), s)
             shapes.append(s)
         elif op == "maxpool":
             n, c, h, w = s
