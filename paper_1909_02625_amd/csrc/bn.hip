@@ -50,7 +50,7 @@ __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__
         x = x1;
         part = part1;
     }
-    __shared__ double red[kThreads][2];
+    __shared__ double red[kThreads][VW][2];
     const int tid = threadIdx.x;
     const int cvi = blockIdx.y * L.cvb + tid % L.cvb;
     const int rlane = tid / L.cvb;
@@ -101,31 +101,34 @@ __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__
             }
         }
     }
-    // combine the row lanes of each channel vector (fixed order), one channel of the vector at a time
+    // combine the row lanes of each channel vector: a fixed tree over the row lanes, all channels of the vector at once
 #pragma unroll
     for (int i = 0; i < VW; ++i) {
-        red[tid][0] = s0[i];
-        red[tid][1] = s1[i];
-        __syncthreads();
-        if (active && rlane == 0) {
-            double a = 0.0, b = 0.0;
-            for (int k = 0; k < L.rl; ++k) {
-                a += red[k * L.cvb + tid][0];
-                b += red[k * L.cvb + tid][1];
+        red[tid][i][0] = s0[i];
+        red[tid][i][1] = s1[i];
+    }
+    __syncthreads();
+    int w = 1;
+    while (w < L.rl) w <<= 1;
+    for (w >>= 1; w > 0; w >>= 1) {
+        if (active && rlane < w && rlane + w < L.rl) {
+            const int other = tid + w * L.cvb;
+#pragma unroll
+            for (int i = 0; i < VW; ++i) {
+                red[tid][i][0] += red[other][i][0];
+                red[tid][i][1] += red[other][i][1];
             }
-            double* dst = part + ((int64_t)blockIdx.x * C + c0 + i) * 2;
-            dst[0] = a;
-            dst[1] = b;
         }
         __syncthreads();
     }
-}
-
-__device__ inline double wave_sum(double v)
-{
+    if (active && rlane == 0) {
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-    return v;
+        for (int i = 0; i < VW; ++i) {
+            double* dst = part + ((int64_t)blockIdx.x * C + c0 + i) * 2;
+            dst[0] = red[tid][i][0];
+            dst[1] = red[tid][i][1];
+        }
+    }
 }
 
 // Merging the partials.  The partials of a conv epilogue can be thousands of rows (one per row tile), so a
