@@ -1481,11 +1481,12 @@ struct WgradPlan {
 };
 WgradPlan wgrad_plan(int dtype, const ConvShape& c)
 {
-    const int bk = dtype == DSP_BF16 ? 64 : 16;
+    // m rows per LDS tile: 128 bytes of k per row; the large fp32 tile keeps 64 (measured: VGG-19's layers)
+    const int bk = dtype == DSP_BF16 ? 64 : 32;
     const int64_t kdim = (int64_t)c.R * c.S * c.Cin;
     if (c.Cout <= 16) return {16, 64, bk, 0};
     if (c.Cout <= 32) return {32, 128, bk, 1};
-    if (c.Cout >= 128 && kdim >= 512) return {128, 128, bk, 3};
+    if (c.Cout >= 128 && kdim >= 512) return {128, 128, dtype == DSP_BF16 ? 64 : 16, 3};
     return {64, 64, bk, 2};
 }
 
@@ -1531,7 +1532,7 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
                    hipStream_t st, double flops, bool defer_reduce)
 {
     constexpr int E = 16 / (int)sizeof(T);
-    constexpr int KB = sizeof(T) == 2 ? 128 : 64;
+    constexpr int KB = 128;
     const int dtype = sizeof(T) == 2 ? DSP_BF16 : DSP_FP32;
     const WgradPlan pl = wgrad_plan(dtype, c);
     WgradGeom g{c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.stride, 0, 0, 0, 0, 0, 0, 0};
@@ -1563,7 +1564,7 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
     switch (pl.id) {
     case 0: rc = run_wgrad_v<Tile<T, 16, 1, 4, 1, 1, KB, 2>>(g, splits, vec, x, dy, dst, st, flops); break;
     case 1: rc = run_wgrad_v<Tile<T, 32, 1, 4, 1, 1, KB, 2>>(g, splits, vec, x, dy, dst, st, flops); break;
-    case 3: rc = run_wgrad_v<Tile<T, 32, 2, 2, 2, 2, KB, 2>>(g, splits, vec, x, dy, dst, st, flops); break;
+    case 3: rc = run_wgrad_v<Tile<T, 32, 2, 2, 2, 2, (sizeof(T) == 2 ? 128 : 64), 2>>(g, splits, vec, x, dy, dst, st, flops); break;
     default: rc = run_wgrad_v<Tile<T, 32, 2, 2, 1, 1, KB, 2>>(g, splits, vec, x, dy, dst, st, flops); break;
     }
     DSP_TRY(rc);
