@@ -557,10 +557,17 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
             break;
         }
         case DSP_OP_ADD: {
-            // in0 then in1, the order in which the overwrite / accumulate flags were decided
+            // both operands in one launch (dy is read once); the same tensor on both sides would need in0 before
+            // in1, the order in which the overwrite / accumulate flags were decided, so it takes two launches
             const int64_t n_el = (int64_t)s.N * s.H * s.W * s.C;
-            if (L.in0_grad) DSP_TRY(launch_grad_pass(b->dtype, dy, grad_of(L.d.in0), n_el, L.in0_acc, st));
-            if (L.in1_grad) DSP_TRY(launch_grad_pass(b->dtype, dy, grad_of(L.d.in1), n_el, L.in1_acc, st));
+            void* d0 = L.in0_grad ? grad_of(L.d.in0) : nullptr;
+            void* d1 = L.in1_grad ? grad_of(L.d.in1) : nullptr;
+            if (d0 && d1 && d0 != d1) {
+                DSP_TRY(launch_grad_pass(b->dtype, dy, d0, L.in0_acc, d1, L.in1_acc, n_el, st));
+            } else {
+                if (d0) DSP_TRY(launch_grad_pass(b->dtype, dy, d0, L.in0_acc, nullptr, false, n_el, st));
+                if (d1) DSP_TRY(launch_grad_pass(b->dtype, dy, d1, L.in1_acc, nullptr, false, n_el, st));
+            }
             break;
         }
         case DSP_OP_MAXPOOL:

@@ -212,9 +212,9 @@ int launch_refresh_shadows(int dtype, const float* x, const int32_t* tmap, void*
                            hipStream_t st);
 int launch_spin(int microseconds, hipStream_t st);
 // dst[p][0..Cp) = {src[p][0..C), 0...}: channel padding of an NHWC tensor (pixels rows) up to a whole 16-byte run.
-// y = a + b over n elements; dx = dy or dx += dy (the backward of the sum, once per operand)
+// y = a + b over n elements; backward of the sum: dx0 (and dx1, unless null) = dy or += dy, one read of dy
 int launch_add_forward(int dtype, const void* a, const void* b, void* y, int64_t n, hipStream_t st);
-int launch_grad_pass(int dtype, const void* dy, void* dx, int64_t n, bool accumulate, hipStream_t st);
+int launch_grad_pass(int dtype, const void* dy, void* dx0, bool acc0, void* dx1, bool acc1, int64_t n, hipStream_t st);
 int launch_pad_channels(int dtype, const void* src, void* dst, int64_t pixels, int C, int Cp, hipStream_t st);
 // dst[row][0..C) = src[row][0..C) for rows of Cp floats: drops the padded channels of a filter gradient.
 int launch_unpad_rows(const float* src, float* dst, int64_t rows, int C, int Cp, hipStream_t st);

@@ -520,19 +520,29 @@ __global__ __launch_bounds__(kThreads) void add_fwd_kernel(const T* __restrict__
     }
 }
 
-template <typename T, int VW, bool ACC>
-__global__ __launch_bounds__(kThreads) void grad_pass_kernel(const T* __restrict__ dy, T* __restrict__ dx, int64_t nvec)
+// dx0 (and dx1, if given) = dy, or += dy where the buffer already holds another consumer's contribution
+template <typename T, int VW>
+__global__ __launch_bounds__(kThreads) void grad_pass_kernel(const T* __restrict__ dy, T* __restrict__ dx0, int acc0,
+                                                             T* __restrict__ dx1, int acc1, int64_t nvec)
 {
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * kThreads) {
         float v[VW];
         VecIO<T, VW>::load(dy + i * VW, v);
-        if (ACC) {
-            float o[VW];
-            VecIO<T, VW>::load(dx + i * VW, o);
 #pragma unroll
-            for (int k = 0; k < VW; ++k) v[k] += o[k];
+        for (int t = 0; t < 2; ++t) {
+            T* dx = t ? dx1 : dx0;
+            if (!dx) continue;
+            float o[VW];
+            if (t ? acc1 : acc0) {
+                VecIO<T, VW>::load(dx + i * VW, o);
+#pragma unroll
+                for (int k = 0; k < VW; ++k) o[k] += v[k];
+            } else {
+#pragma unroll
+                for (int k = 0; k < VW; ++k) o[k] = v[k];
+            }
+            VecIO<T, VW>::store(dx + i * VW, o);
         }
-        VecIO<T, VW>::store(dx + i * VW, v);
     }
 }
 
@@ -582,27 +592,27 @@ int launch_add_forward(int dtype, const void* a, const void* b, void* y, int64_t
 }
 
 template <typename T>
-static int grad_pass_t(const void* dy, void* dx, int64_t n, bool accumulate, hipStream_t st)
+static int grad_pass_t(const void* dy, void* dx0, bool acc0, void* dx1, bool acc1, int64_t n, hipStream_t st)
 {
     constexpr int VW = 16 / (int)sizeof(T);
-    ProfScope ps("add_bwd", (double)n * (accumulate ? 3.0 : 2.0) * sizeof(T), 1);
-    const bool vec = n % VW == 0 && ((uintptr_t)dy % 16) == 0 && ((uintptr_t)dx % 16) == 0;
-#define GRAD_PASS(V, A, CNT) \
-    DSP_LAUNCH(ps, (grad_pass_kernel<T, V, A>), dim3(grid_for(CNT)), dim3(kThreads), 0, st, (const T*)dy, (T*)dx, (int64_t)(CNT))
-    if (vec) {
-        if (accumulate) GRAD_PASS(VW, true, n / VW); else GRAD_PASS(VW, false, n / VW);
-    } else {
-        if (accumulate) GRAD_PASS(1, true, n); else GRAD_PASS(1, false, n);
-    }
-#undef GRAD_PASS
+    const int passes = 1 + (acc0 ? 1 : 0) + (dx1 ? 1 + (acc1 ? 1 : 0) : 0);
+    ProfScope ps("add_bwd", (double)n * (1.0 + passes) * sizeof(T), 1);
+    const bool vec = n % VW == 0 && ((uintptr_t)dy % 16) == 0 && ((uintptr_t)dx0 % 16) == 0 && ((uintptr_t)dx1 % 16) == 0;
+    if (vec)
+        DSP_LAUNCH(ps, (grad_pass_kernel<T, VW>), dim3(grid_for(n / VW)), dim3(kThreads), 0, st, (const T*)dy, (T*)dx0,
+                   (int)acc0, (T*)dx1, (int)acc1, n / VW);
+    else
+        DSP_LAUNCH(ps, (grad_pass_kernel<T, 1>), dim3(grid_for(n)), dim3(kThreads), 0, st, (const T*)dy, (T*)dx0, (int)acc0,
+                   (T*)dx1, (int)acc1, n);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }
 
-int launch_grad_pass(int dtype, const void* dy, void* dx, int64_t n, bool accumulate, hipStream_t st)
+int launch_grad_pass(int dtype, const void* dy, void* dx0, bool acc0, void* dx1, bool acc1, int64_t n, hipStream_t st)
 {
-    DSP_REQUIRE(dy && dx && n > 0, DSP_EINVAL, "add backward: bad argument");
-    return dtype == DSP_BF16 ? grad_pass_t<bf16_t>(dy, dx, n, accumulate, st) : grad_pass_t<float>(dy, dx, n, accumulate, st);
+    DSP_REQUIRE(dy && dx0 && n > 0 && dx0 != dx1, DSP_EINVAL, "add backward: bad argument");
+    return dtype == DSP_BF16 ? grad_pass_t<bf16_t>(dy, dx0, acc0, dx1, acc1, n, st)
+                             : grad_pass_t<float>(dy, dx0, acc0, dx1, acc1, n, st);
 }
 
 int launch_pad_channels(int dtype, const void* src, void* dst, int64_t pixels, int C, int Cp, hipStream_t st)
