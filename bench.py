@@ -3,7 +3,7 @@
 
 A "step" is one pipeline tick: every block of DSP(p; m) runs forward(a), recompute+backward(b) and
 its momentum-SGD update on its own HIP stream, on synthetic inputs that are already resident in
-HBM.  Prints ONE JSON line (see README for the fields).
+HBM.  Prints ONE JSON line (the fields are described in the README).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet20|resnet56|resnet18|resnet50_conv4x|vgg19|resnet164|tiny2]
 """
