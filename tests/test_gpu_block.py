@@ -450,6 +450,21 @@ def test_gradient_difference_probe(name, dtype, ticks, kw, rtol):
         destroy_blocks(probes)
 
 
+def test_pipeline_optimizer_arguments_are_checked():
+    cfg, params, rng = _setup("tiny2")
+    blocks = build_gpu_blocks(cfg, params, D.DSP_FP32)
+    pl = D.dsp_pipeline_init(blocks, cfg["p"], cfg["m"], cfg["lr"], cfg["beta"], cfg["wd"], 4)
+    try:
+        with pytest.raises(D.DSPError):
+            D.dsp_pipeline_set_optimizer(pl, 0.1, 0.9, s=3)
+        with pytest.raises(D.DSPError):
+            D.dsp_pipeline_set_optimizer(pl, -1.0, 0.9)
+        D.dsp_pipeline_set_optimizer(pl, 0.05, 0.8, s=1, weight_decay=1e-4)
+    finally:
+        D.dsp_pipeline_destroy(pl)
+        destroy_blocks(blocks)
+
+
 def test_gradient_probe_is_refused_when_it_cannot_work():
     cfg, params, rng = _setup("tiny2")
     K = cfg["K"]
@@ -563,6 +578,12 @@ def test_call_order_is_enforced():
         D.dsp_block_recompute_backward(b, 0, g)
         with pytest.raises(D.DSPError):
             D.dsp_block_forward(b, 3, x, out)            # update still pending
+        with pytest.raises(D.DSPError) as e:
+            D.dsp_param_update_sum(b, 0.1, 0.9, s=2)     # only s = 0 and s = 1 of Eq. (3) are built
+        assert e.value.status == 1
+        with pytest.raises(D.DSPError):
+            D.dsp_param_update_sum(b, -0.1, 0.9, s=1)    # negative step size
+        assert D.dsp_block_query(b)["pending"] == 1      # the refused calls consumed nothing
         D.dsp_param_update(b, 0.1, 0.9)
         D.dsp_block_forward(b, 3, x, out)
         q = D.dsp_block_query(b)
