@@ -1484,6 +1484,12 @@ WgradPlan wgrad_plan(int dtype, const ConvShape& c)
     // m rows per LDS tile: 128 bytes of k per row; the large fp32 tile keeps 64 (measured: VGG-19's layers)
     const int bk = dtype == DSP_BF16 ? 64 : 32;
     const int64_t kdim = (int64_t)c.R * c.S * c.Cin;
+    if (dtype == DSP_BF16) {
+        // bf16 has the transpose-read kernel only for 64- and 128-wide tiles; narrow layers run on the 64x64 one
+        // (the idle MFMA rows cost less than the register transposes of the narrow tiles)
+        if (c.Cout >= 128 && kdim >= 512) return {128, 128, bk, 3};
+        return {64, 64, bk, 2};
+    }
     if (c.Cout <= 16) return {16, 64, bk, 0};
     if (c.Cout <= 32) return {32, 128, bk, 1};
     if (c.Cout >= 128 && kdim >= 512) return {128, 128, dtype == DSP_BF16 ? 64 : 16, 3};
