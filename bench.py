@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--batch", type=int, default=None, help="override the mini-batch size (not the headline number)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the CPU-oracle baseline leg (0 = skip)")
     ap.add_argument("--profile-steps", type=int, default=10)
+    ap.add_argument("--straggler", type=int, nargs=2, metavar=("BLOCK", "MICROSECONDS"), default=None,
+                    help="straggler emulation: block BLOCK's stream idles this long before its work in every tick "
+                         "(not the headline number)")
     return ap.parse_args()
 
 
@@ -179,6 +182,10 @@ def main():
     calibration_copy(torch)
     total_ticks = a.warmup + a.steps + a.profile_steps + 4
     w = Workload(a.workload, a.dtype, a.batch, total_ticks)
+    if a.straggler is not None:
+        if w.pl is None:
+            sys.exit("bench.py: --straggler needs a pipeline of several blocks")
+        w.D.dsp_pipeline_set_delay(w.pl, a.straggler[0], a.straggler[1])
     for _ in range(a.warmup):
         w.step()
     w.sync()
@@ -240,7 +247,8 @@ def main():
         "config": {"workload": "%s: DSP(%s;%s), K=%d blocks on %d HIP streams, batch %d x %dx%dx%d, one pipeline tick per step"
                                % (a.workload, ",".join(map(str, cfg["p"])), ",".join(map(str, cfg["m"])), cfg["K"],
                                   cfg["K"], cfg["input"][0], cfg["input"][1], cfg["input"][2], cfg["input"][3]),
-                   "lr": cfg["lr"], "momentum": cfg["beta"]},
+                   "lr": cfg["lr"], "momentum": cfg["beta"],
+                   **({"straggler": {"block": a.straggler[0], "microseconds": a.straggler[1]}} if a.straggler else {})},
         "conv_mfma_util_pct": None if conv_util is None else round(conv_util, 3),
         # sum of all kernel durations of a tick (over the K streams); K * ms_per_step minus this is stream idle time
         "kernel_time_ms_per_step": None if not table else round(sum(k["ms"] for k in table) / a.profile_steps, 4),
