@@ -36,13 +36,23 @@ def parse():
     ap.add_argument("--straggler", type=int, nargs=2, metavar=("BLOCK", "MICROSECONDS"), default=None,
                     help="straggler emulation: block BLOCK's stream idles this long before its work in every tick "
                          "(not the headline number)")
+    ap.add_argument("--schedule", default=None, metavar="P;M",
+                    help='another DSP(p; m) for the workload\'s K blocks, e.g. "2,2,0;6,3,0" (not the headline number)')
+    ap.add_argument("--spare", type=int, default=0,
+                    help="spare entries in every queue between two blocks: lets neighbouring blocks drift apart by more "
+                         "than one tick (results are unchanged)")
+    ap.add_argument("--random-stragglers", type=float, nargs="+", metavar="PERCENT", default=None,
+                    help="after the timed ticks, one more series of --steps ticks per value: in every tick each block "
+                         "independently, with probability 1/3, first idles PERCENT %% of the undisturbed tick time "
+                         "(robustness experiment of Section 6); reported next to the headline number")
+    ap.add_argument("--straggler-seed", type=int, default=0)
     return ap.parse_args()
 
 
 class Workload:
     """Library objects + resident synthetic inputs for one configuration."""
 
-    def __init__(self, name, dtype_name, batch, max_ticks):
+    def __init__(self, name, dtype_name, batch, max_ticks, schedule=None, spare=0):
         import numpy as np
         import torch
 
@@ -53,11 +63,16 @@ class Workload:
 
         self.D, self.torch = D, torch
         self.cfg = cfg = get_config(name, batch=batch)
+        if schedule is not None:
+            ps, ms = schedule.split(";")
+            cfg["p"], cfg["m"] = tuple(int(v) for v in ps.split(",")), tuple(int(v) for v in ms.split(","))
+            if len(cfg["p"]) != cfg["K"] or len(cfg["m"]) != cfg["K"]:
+                sys.exit("bench.py: --schedule needs %d values of p and of m" % cfg["K"])
         self.dtype_name = dtype_name or cfg["dtypes"][0]
         self.dtype = D.DSP_BF16 if self.dtype_name == "bf16" else D.DSP_FP32
         rng = np.random.default_rng(cfg["seed"])
         self.params = [make_params(layers, rng) for layers in cfg["blocks"]]
-        self.blocks = build_gpu_blocks(cfg, self.params, self.dtype)
+        self.blocks = build_gpu_blocks(cfg, self.params, self.dtype, spare=spare)
         self.shapes = block_shapes(cfg)
         self.N = cfg["input"][0]
         self.external = cfg.get("classes") is None
@@ -180,8 +195,8 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     calibration_copy(torch)
-    total_ticks = a.warmup + a.steps + a.profile_steps + 4
-    w = Workload(a.workload, a.dtype, a.batch, total_ticks)
+    total_ticks = a.warmup + a.steps * (1 + len(a.random_stragglers or [])) + a.profile_steps + 4
+    w = Workload(a.workload, a.dtype, a.batch, total_ticks, a.schedule, a.spare)
     if a.straggler is not None:
         if w.pl is None:
             sys.exit("bench.py: --straggler needs a pipeline of several blocks")
@@ -232,6 +247,33 @@ def main():
                     "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": hbm_traffic(a.workload, w.dtype_name, dom["name"]),
                     "avg_launch_us": round(1e3 * dom["ms"] / dom["launches"], 2),
                     "bytes_per_launch": dom["units"] / dom["launches"]}
+    # Section 6 (robustness): the same ticks with blocks that are late at random
+    stragglers = None
+    if a.random_stragglers:
+        import numpy as np
+        if w.pl is None:
+            sys.exit("bench.py: --random-stragglers needs a pipeline of several blocks")
+        stragglers = []
+        for pct in a.random_stragglers:
+            srng = np.random.default_rng(a.straggler_seed)
+            delay_us = int(round(ms * 1e3 * pct / 100.0))
+            hits = 0
+            w.sync()
+            ts = time.perf_counter()
+            for _ in range(a.steps):
+                for k in range(w.cfg["K"]):
+                    late = srng.random() < 1.0 / 3.0
+                    hits += int(late)
+                    D.dsp_pipeline_set_delay(w.pl, k, delay_us if late else 0)
+                w.step()
+            w.sync()
+            te = time.perf_counter()
+            ms_s = (te - ts) * 1e3 / a.steps
+            stragglers.append({"block_slow_down_pct": pct, "delay_us": delay_us, "probability": "1/3 per block and tick",
+                               "delayed_block_ticks": hits, "ms_per_step": round(ms_s, 4),
+                               "slow_down_pct": round(100.0 * (ms_s / ms - 1.0), 2)})
+        for k in range(w.cfg["K"]):
+            D.dsp_pipeline_set_delay(w.pl, k, 0)
     w.close()
 
     base = None
@@ -248,7 +290,9 @@ def main():
                                % (a.workload, ",".join(map(str, cfg["p"])), ",".join(map(str, cfg["m"])), cfg["K"],
                                   cfg["K"], cfg["input"][0], cfg["input"][1], cfg["input"][2], cfg["input"][3]),
                    "lr": cfg["lr"], "momentum": cfg["beta"],
-                   **({"straggler": {"block": a.straggler[0], "microseconds": a.straggler[1]}} if a.straggler else {})},
+                   **({"straggler": {"block": a.straggler[0], "microseconds": a.straggler[1]}} if a.straggler else {}),
+                   **({"spare_queue_entries": a.spare} if a.spare else {})},
+        **({"random_stragglers": stragglers} if stragglers else {}),
         "conv_mfma_util_pct": None if conv_util is None else round(conv_util, 3),
         # sum of all kernel durations of a tick (over the K streams); K * ms_per_step minus this is stream idle time
         "kernel_time_ms_per_step": None if not table else round(sum(k["ms"] for k in table) / a.profile_steps, 4),

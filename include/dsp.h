@@ -23,8 +23,12 @@
  *     average pool (N x C) and the loss are always float.
  *   - Parameters cross the boundary on the HOST as float in "layer order": for each layer in
  *     turn, conv: w[cout][cin][r][s]; bn: gamma[c], beta[c]; linear: W[cout][cin], c[cout].
- *   - The library allocates device memory only in the *_init calls; the step calls launch
- *     kernels asynchronously on the given stream and allocate nothing.
+ *   - The library allocates device memory only in the *_init calls and in
+ *     dsp_pipeline_attach_gradient_probe / dsp_pipeline_set_forward_streams (first step after it);
+ *     the step calls launch kernels asynchronously on the given stream and allocate nothing.
+ *   - Arguments are checked before anything is launched: DSP_EINVAL and DSP_ESTATE leave the
+ *     object as it was.  DSP_EHIP or DSP_ENOMEM out of a step call may have launched part of the
+ *     step: the object's contents are then unspecified and it should be destroyed.
  *   - Objects are not thread-safe; calls on one block must be issued in pipeline order
  *     (forward, then recompute_backward, then param_update) or DSP_ESTATE is returned.
  */
@@ -85,7 +89,9 @@ typedef struct dsp_block_desc {
     int32_t m_k;              /* layer-wise staleness: the stored-input queue M_k has 1+m_k entries */
     int32_t p_prev;           /* p_{k-1} (0 for a stand-alone block): the output queue P_{k-1} of the block
                                  below is fused into M_k, which then has 1+m_k+p_prev entries, so the
-                                 producer writes h_k straight into its slot (no copy between queues) */
+                                 producer writes h_k straight into its slot (no copy between queues).
+                                 p_prev = p_{k-1} + spare gives the queue `spare` entries of slack
+                                 (see dsp_pipeline_init); results do not depend on it */
     int32_t needs_input_grad; /* 0 for the block that reads the data h_0 (q_0 = 0): G_{h_0} is not formed */
     float bn_eps;
 } dsp_block_desc;
@@ -117,6 +123,18 @@ int dsp_schedule_index(int32_t K, const int32_t* p, const int32_t* m, int32_t k,
  * space O(L + sum_k (m_k + p_k + q_k))): sum_k (1+m_k+p_{k-1}) |h_k| + (1+q_k) |h_k| [k >= 1]. */
 int dsp_schedule_queue_elems(int32_t K, const int32_t* p, const int32_t* m, const int64_t* h_elems,
                              int64_t* total);
+
+/*
+ * Cross-block ordering of DSP(p; m) when the queues between blocks k-1 and k hold spare[k] entries
+ * beyond the minimum (spare may be NULL = all 0; spare[0] must be 0; each 0..64): block k may start
+ * tick tau once block k-1 has finished tick tau - wait_down[k] and block k+1 tick tau - wait_up[k]
+ * (0 = no such neighbour, or an all-zero schedule), where wait_down[k] = min(p_{k-1}, 1 + spare[k])
+ * and wait_up[k] = min(q_{k+1}, 1 + spare[k+1]): the nearer of the tick that wrote what the block
+ * reads and the tick that last read what it overwrites.  *label_slots (may be NULL) = mini-batches
+ * of labels a data source feeding block 0 must keep for the last block.  Host only.
+ */
+int dsp_schedule_waits(int32_t K, const int32_t* p, const int32_t* m, const int32_t* spare, int32_t* wait_down,
+                       int32_t* wait_up, int32_t* label_slots);
 
 /* ---- one block (Section 2 Eq. (1)-(3), Section 3.2 Eq. (5)) ------------------------------ */
 
@@ -218,6 +236,14 @@ int dsp_block_get_grads(dsp_block* b, float* h_dst, size_t n);
  * Wires K blocks (built with matching k, K, m_k, p_prev = p_{k-1}) into DSP(p; m): one stream per
  * block, gradient rings Q_k of 1+q_k entries, a label ring, a loss history of max_ticks floats.
  * The blocks stay owned by the caller and must outlive the pipeline.
+ * Spare queue entries: a block k >= 1 built with p_prev = p_{k-1} + spare_k (0 <= spare_k <= 64) has
+ * spare_k more ring entries than the schedule needs; Q_k then gets spare_k more as well, and the two
+ * blocks k-1 and k may drift apart by more than one tick (block k-1 waits for tick
+ * tau - min(q_k, 1+spare_k) of block k, block k for tick tau - min(p_{k-1}, 1+spare_k) of block k-1)
+ * instead of running in lockstep: the slack that the FIFO queues of Section 6 ("Robustness") give a
+ * block whose neighbour is late.  Which mini-batch meets which parameters depends on the tick number
+ * only, so every result is bit-identical with and without spare entries.  A smaller ring, or a larger
+ * one in block 0: DSP_EINVAL.
  */
 int dsp_pipeline_init(int32_t K, dsp_block* const* blocks, const int32_t* p, const int32_t* m, float lr,
                       float momentum, float weight_decay, int64_t max_ticks, dsp_pipeline** out);
@@ -227,7 +253,8 @@ int dsp_pipeline_destroy(dsp_pipeline* pl);
  * One tick: feeds mini-batch number tau (d_batch: NHWC block-0 input, d_labels: int32[N], both
  * ready on `stream`); every block k with a >= 0 runs forward(a), then, if b >= 0,
  * recompute_backward(b) and its update, on its own stream.  Blocks never depend on each other
- * inside a tick; across ticks each stream waits for its neighbours' previous tick.  On return
+ * inside a tick; across ticks each stream waits for its neighbours' previous tick (an earlier one
+ * where the queues have spare entries, see dsp_pipeline_init).  On return
  * `stream` is ordered after the copies of d_batch/d_labels, so the caller may refill them.
  * If h_loss != NULL the call blocks until the loss of this tick is known and returns it with
  * its mini-batch id (*loss_batch_id = -1 while the pipeline fills); pass NULL to stay asynchronous
@@ -277,7 +304,7 @@ int dsp_pipeline_set_graph_replay(dsp_pipeline* pl, int32_t enable);
  *  - forward streams (default off): a block with m_k > 0 runs the forward pass of the current
  *    mini-batch on a second stream, concurrently with the recompute + backward of the stale one
  *    (dsp_block_enable_forward_lane); the update waits for both.  Must be set before the first
- *    dsp_pipeline_step (DSP_ESTATE afterwards).
+ *    dsp_pipeline_step (DSP_ESTATE afterwards); not available with spare queue entries (DSP_EINVAL).
  */
 int dsp_pipeline_set_forward_streams(dsp_pipeline* pl, int32_t enable);
 /*
@@ -287,7 +314,8 @@ int dsp_pipeline_set_forward_streams(dsp_pipeline* pl, int32_t enable);
  *    between steps.
  */
 int dsp_pipeline_set_twin_launches(dsp_pipeline* pl, int32_t enable);
-/* Straggler emulation: block k's stream spins for `microseconds` before its work in every tick. */
+/* Straggler emulation: block k's stream spins for `microseconds` before its work in every later tick
+ * (0 <= microseconds <= 1000000; may be changed between steps at no cost unless graph replay is on). */
 int dsp_pipeline_set_delay(dsp_pipeline* pl, int32_t k, int32_t microseconds);
 /* Waits for all K streams. */
 int dsp_pipeline_sync(dsp_pipeline* pl);

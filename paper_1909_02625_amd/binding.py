@@ -13,7 +13,7 @@ import numpy as np
 __all__ = [
     "DSP_FP32", "DSP_BF16", "DSPError", "lib", "lib_path", "check",
     "dsp_layer_desc", "dsp_block_desc", "make_block_desc",
-    "dsp_schedule_validate", "dsp_schedule_index", "dsp_schedule_queue_elems",
+    "dsp_schedule_validate", "dsp_schedule_index", "dsp_schedule_queue_elems", "dsp_schedule_waits",
     "dsp_block_init", "dsp_block_destroy", "dsp_block_forward", "dsp_block_recompute_backward",
     "dsp_param_update", "dsp_param_update_sum", "dsp_pipeline_set_optimizer", "dsp_block_input_slot",
     "dsp_pipeline_attach_gradient_probe", "dsp_pipeline_gradient_difference", "dsp_block_query", "dsp_block_output_shape",
@@ -81,6 +81,7 @@ _SIGNATURES = {
     "dsp_schedule_validate": [_i32, _pi32, _pi32, _pi32],
     "dsp_schedule_index": [_i32, _pi32, _pi32, _i32, _i64, _pi64],
     "dsp_schedule_queue_elems": [_i32, _pi32, _pi32, _pi64, _pi64],
+    "dsp_schedule_waits": [_i32, _pi32, _pi32, _pi32, _pi32, _pi32, _pi32],
     "dsp_block_init": [C.POINTER(dsp_block_desc), _pf, _sz, C.POINTER(_vp)],
     "dsp_block_destroy": [_vp],
     "dsp_block_forward": [_vp, _i64, _vp, _vp, _vp, _vp, _vp],
@@ -199,6 +200,15 @@ def dsp_schedule_queue_elems(p, m, h_elems):
     arr = (C.c_int64 * len(h_elems))(*h_elems)
     check(lib().dsp_schedule_queue_elems(len(m), _i32arr(p), _i32arr(m), arr, C.byref(tot)), "dsp_schedule_queue_elems")
     return tot.value
+
+
+def dsp_schedule_waits(p, m, spare=None):
+    """Returns (wait_down[K], wait_up[K], label_slots)."""
+    K = len(m)
+    dn, up, lab = (C.c_int32 * K)(), (C.c_int32 * K)(), C.c_int32()
+    check(lib().dsp_schedule_waits(K, _i32arr(p), _i32arr(m), None if spare is None else _i32arr(spare), dn, up,
+                                   C.byref(lab)), "dsp_schedule_waits")
+    return list(dn), list(up), lab.value
 
 
 # ---- block -----------------------------------------------------------------------------------------

@@ -5,14 +5,21 @@
 // (block k-1 writes h_k straight into the slot block k will read p_{k-1} ticks later and again,
 // for the backward, m_k ticks after that); Q_k is a ring of 1+q_k gradient slots owned here.
 // Which mini-batch a block touches depends only on the tick number, so results do not depend
-// on timing; streams only have to respect "a slot is written one tick or more before it is
-// read, and read before it is rewritten", which waiting for both neighbours' previous tick gives.
+// on timing; streams only have to respect "a slot is written before it is read, and read before
+// it is rewritten".  With rings of exactly those sizes a slot is rewritten one tick after its last
+// read, so every block waits for both neighbours' previous tick.  Blocks built with spare ring
+// entries (p_prev larger than p_{k-1}) give the queues between two blocks that much slack: the
+// producer may then run 1+spare ticks ahead of the consumer's last read, the consumer needs what the
+// producer wrote p_{k-1} (activations) or q_k (gradients) ticks ago, and each block waits for the
+// nearer of the two per neighbour -- a block that is late for a tick no longer holds up the others
+// at once (the role Section 6 of the paper gives to the FIFO queues under stragglers).
 //
-// Steady-state ticks are launch-bound on small layers (hundreds of kernels of a few microseconds),
-// so once the pipeline is full each tick is captured into a HIP graph -- one per phase of the ring
-// rotation, lcm(ring sizes) of them -- with the K block chains as parallel branches, and later
-// ticks of the same phase replay that graph with a single launch while the blocks' host-side
-// state is advanced without launching.
+// Steady-state ticks are launch-bound on small layers (hundreds of kernels of a few microseconds).
+// By default the K chains are issued kernel by kernel from K host threads.  Optionally
+// (dsp_pipeline_set_graph_replay) each tick of a full pipeline is captured into a HIP graph -- one
+// per phase of the ring rotation, lcm(ring sizes) of them -- with the K block chains as parallel
+// branches, and later ticks of the same phase replay that graph with a single launch while the
+// blocks' host-side state is advanced without launching.
 #include <condition_variable>
 #include <mutex>
 #include <new>
@@ -76,7 +83,11 @@ struct dsp_pipeline {
     int sum_s = 0;        // Eq. (3): 0 heavy ball, 1 Nesterov
     int eager_ticks = 0;  // ticks to run unrecorded (the update after a step-size change rescales the velocity once)
     std::vector<hipStream_t> streams;
-    std::vector<hipEvent_t> done[2];  // done[tau % 2][k]: block k finished tick tau
+    std::vector<int32_t> spare;       // spare[k], k >= 1: entries beyond the minimum in the two queues between blocks k-1 and k
+    std::vector<int32_t> qn;          // entries of Q_k = 1 + q_k + spare[k]
+    std::vector<int32_t> wait_dn, wait_up;  // block k waits for tick tau - wait_dn[k] of block k-1 and tau - wait_up[k] of block k+1
+    int ev_depth = 2;                 // ticks of history the done events keep (1 + the longest wait distance)
+    std::vector<std::vector<hipEvent_t>> done;  // done[tau % ev_depth][k]: block k finished tick tau
     // Forward streams: a block with m_k > 0 runs forward(a) here while its main stream runs
     // recompute + backward(a - m_k); the update (main stream) waits for both.
     std::vector<hipStream_t> fstreams;
@@ -159,8 +170,11 @@ static void stop_workers(dsp_pipeline* pl)
 
 static void drop_graphs(dsp_pipeline* pl)
 {
+    bool synced = false;
     for (hipGraphExec_t& g : pl->graphs)
         if (g) {
+            if (!synced) (void)hipDeviceSynchronize();  // a replay of it may still be running
+            synced = true;
             (void)hipGraphExecDestroy(g);
             g = nullptr;
         }
@@ -207,6 +221,31 @@ int dsp_schedule_queue_elems(int32_t K, const int32_t* p, const int32_t* m, cons
     return DSP_OK;
 }
 
+int dsp_schedule_waits(int32_t K, const int32_t* p, const int32_t* m, const int32_t* spare, int32_t* wait_down,
+                       int32_t* wait_up, int32_t* label_slots)
+{
+    std::vector<int32_t> q(K > 0 ? K : 1);
+    DSP_TRY(validate_schedule(K, p, m, q.data()));
+    DSP_REQUIRE(wait_down && wait_up, DSP_EINVAL, "dsp_schedule_waits: null argument");
+    DSP_REQUIRE(!spare || spare[0] == 0, DSP_EINVAL, "dsp_schedule_waits: block 0 has no queue below it (spare[0] must be 0)");
+    // The nearer of "what I read was written then" (p_{k-1} ticks ago by the block below, q_{k+1} by the
+    // block above) and "what I overwrite was last read then" (1 + spare ticks ago).
+    int64_t labels = K, P = 0;
+    for (int k = 0; k < K; ++k) {
+        const int sk = spare ? spare[k] : 0, su = (spare && k < K - 1) ? spare[k + 1] : 0;
+        DSP_REQUIRE(sk >= 0 && sk <= 64, DSP_EINVAL, "dsp_schedule_waits: spare[%d] = %d outside 0..64", k, sk);
+        wait_down[k] = (k > 0 && p[k - 1] > 0) ? std::min(p[k - 1], 1 + sk) : 0;
+        wait_up[k] = (k < K - 1 && q[k + 1] > 0) ? std::min(q[k + 1], 1 + su) : 0;
+        labels += sk;
+        if (k < K - 1) P += p[k];
+    }
+    // Labels copied at tick tau are read by the last block P_{K-1} ticks later; the copy of tick tau runs
+    // after block 0's tick tau-1, hence after the last block's tick tau - 1 - (sum of the upward waits),
+    // which is tick tau - K - (all spare entries) or later.
+    if (label_slots) *label_slots = (int32_t)(P + labels);
+    return DSP_OK;
+}
+
 int dsp_pipeline_destroy(dsp_pipeline* pl)
 {
     if (!pl) return DSP_OK;
@@ -215,10 +254,10 @@ int dsp_pipeline_destroy(dsp_pipeline* pl)
     drop_graphs(pl);
     for (hipStream_t s : pl->streams) (void)hipStreamDestroy(s);
     for (hipStream_t s : pl->fstreams) (void)hipStreamDestroy(s);
-    for (int i = 0; i < 2; ++i) {
-        for (hipEvent_t e : pl->done[i]) (void)hipEventDestroy(e);
+    for (auto& row : pl->done)
+        for (hipEvent_t e : row) (void)hipEventDestroy(e);
+    for (int i = 0; i < 2; ++i)
         for (hipEvent_t e : pl->fdone[i]) (void)hipEventDestroy(e);
-    }
     for (hipEvent_t e : pl->join) (void)hipEventDestroy(e);
     if (pl->in_ready) (void)hipEventDestroy(pl->in_ready);
     if (pl->in_copied) (void)hipEventDestroy(pl->in_copied);
@@ -260,27 +299,41 @@ static int pipeline_build(dsp_pipeline* pl, dsp_block* const* blocks)
         DSP_TRY(dsp_block_output_shape(b, prev_out));
         DSP_TRY(dsp_block_query(b, info));
         const int want = 1 + pl->m[k] + (k > 0 ? pl->p[k - 1] : 0);
-        DSP_REQUIRE(info[3] == want, DSP_EINVAL, "dsp_pipeline_init: block %d has a ring of %lld entries, DSP(p;m) needs %d",
-                    k, (long long)info[3], want);
+        DSP_REQUIRE(k > 0 ? info[3] >= want : info[3] == want, DSP_EINVAL,
+                    "dsp_pipeline_init: block %d has a ring of %lld entries, DSP(p;m) needs %d%s", k, (long long)info[3], want,
+                    k > 0 ? " or more" : "");
+        DSP_REQUIRE(info[3] - want <= 64, DSP_EINVAL, "dsp_pipeline_init: block %d has more than 64 spare ring entries", k);
         DSP_REQUIRE(info[1] == 0 && info[2] == 0, DSP_ESTATE, "dsp_pipeline_init: block %d has already been stepped", k);
         pl->blocks.push_back(b);
-        period = std::lcm(period, (int64_t)want);
+        pl->spare[k] = (int32_t)(info[3] - want);
+        pl->qn[k] = k > 0 ? 1 + pl->q[k] + pl->spare[k] : 1;
+        period = std::lcm(period, (int64_t)info[3]);
         period = std::lcm(period, (int64_t)(1 + pl->m[k]));  // the last block's loss-gradient ring
-        if (k > 0) period = std::lcm(period, (int64_t)(1 + pl->q[k]));
+        if (k > 0) period = std::lcm(period, (int64_t)pl->qn[k]);
         if (period > kMaxGraphs) period = kMaxGraphs + 1;
         const int64_t full = pl->P[k] + pl->m[k];
         if (full > pl->fill) pl->fill = full;
     }
+    // How far back each block has to look at its neighbours (an all-zero schedule runs on one stream and
+    // never waits), and how many mini-batches of labels are kept.
+    int32_t label_slots = 1;
+    DSP_TRY(dsp_schedule_waits(K, pl->p.data(), pl->m.data(), pl->spare.data(), pl->wait_dn.data(), pl->wait_up.data(),
+                               &label_slots));
+    for (int k = 0; k < K; ++k) pl->ev_depth = std::max(pl->ev_depth, 1 + std::max(pl->wait_dn[k], pl->wait_up[k]));
+    pl->done.assign(pl->ev_depth, std::vector<hipEvent_t>());
     for (int k = 0; k < K; ++k) {
         hipStream_t s;
         DSP_HIP(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
         pl->streams.push_back(s);
         DSP_HIP(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
         pl->fstreams.push_back(s);
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < pl->ev_depth; ++i) {
             hipEvent_t e;
             DSP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
             pl->done[i].push_back(e);
+        }
+        for (int i = 0; i < 2; ++i) {
+            hipEvent_t e;
             DSP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
             pl->fdone[i].push_back(e);
         }
@@ -299,11 +352,11 @@ static int pipeline_build(dsp_pipeline* pl, dsp_block* const* blocks)
         size_t bytes = (size_t)shape[0] * shape[1] * shape[2] * shape[3] * 4;  // upper bound (fp32)
         bytes = (bytes + 255) / 256 * 256;
         void* ptr;
-        DSP_TRY(pl_alloc(pl, &ptr, bytes * (1 + pl->q[k])));
+        DSP_TRY(pl_alloc(pl, &ptr, bytes * pl->qn[k]));
         pl->qring[k] = (char*)ptr;
         pl->qslot_bytes[k] = bytes;
     }
-    pl->label_slots = pl->P[K - 1] + K;
+    pl->label_slots = label_slots;
     period = std::lcm(period, (int64_t)pl->label_slots);
     pl->period = (pl->serial || period > kMaxGraphs) ? 0 : (int)period;
     pl->graphs.assign(pl->period, nullptr);
@@ -353,6 +406,10 @@ int dsp_pipeline_init(int32_t K, dsp_block* const* blocks, const int32_t* p, con
     pl->wd = weight_decay;
     pl->max_ticks = max_ticks;
     pl->delay_us.assign(K, 0);
+    pl->spare.assign(K, 0);
+    pl->qn.assign(K, 1);
+    pl->wait_dn.assign(K, 1);
+    pl->wait_up.assign(K, 1);
     const int rc = pipeline_build(pl, blocks);
     if (rc != DSP_OK) {
         dsp_pipeline_destroy(pl);
@@ -366,10 +423,7 @@ int dsp_pipeline_set_delay(dsp_pipeline* pl, int32_t k, int32_t microseconds)
 {
     DSP_REQUIRE(pl && k >= 0 && k < pl->K && microseconds >= 0 && microseconds <= 1000000, DSP_EINVAL,
                 "dsp_pipeline_set_delay: bad argument");
-    if (pl->delay_us[k] != microseconds) {
-        DSP_HIP(hipDeviceSynchronize());
-        drop_graphs(pl);  // the delay kernel is part of the captured ticks
-    }
+    if (pl->delay_us[k] != microseconds) drop_graphs(pl);  // the delay kernel is part of the captured ticks
     pl->delay_us[k] = microseconds;
     return DSP_OK;
 }
@@ -448,6 +502,8 @@ int dsp_pipeline_set_forward_streams(dsp_pipeline* pl, int32_t enable)
 {
     DSP_REQUIRE(pl, DSP_EINVAL, "dsp_pipeline_set_forward_streams: null pipeline");
     DSP_REQUIRE(pl->tau == 0, DSP_ESTATE, "dsp_pipeline_set_forward_streams: the pipeline has already been stepped");
+    DSP_REQUIRE(!enable || pl->ev_depth == 2, DSP_EINVAL,
+                "dsp_pipeline_set_forward_streams: not with spare queue entries (its waits are one tick deep)");
     pl->use_fwd_streams = enable != 0;
     return DSP_OK;
 }
@@ -492,8 +548,8 @@ static int tick_backward(dsp_pipeline* pl, int k, int64_t tau, hipStream_t st, b
     const int64_t bb = tau - pl->P[k] - pl->m[k];
     *did = bb >= 0;
     if (bb < 0) return DSP_OK;
-    const void* gout = k < K - 1 ? pl->qring[k + 1] + (size_t)(bb % (1 + pl->q[k + 1])) * pl->qslot_bytes[k + 1] : nullptr;
-    void* gin = k > 0 ? pl->qring[k] + (size_t)(bb % (1 + pl->q[k])) * pl->qslot_bytes[k] : nullptr;
+    const void* gout = k < K - 1 ? pl->qring[k + 1] + (size_t)(bb % pl->qn[k + 1]) * pl->qslot_bytes[k + 1] : nullptr;
+    void* gin = k > 0 ? pl->qring[k] + (size_t)(bb % pl->qn[k]) * pl->qslot_bytes[k] : nullptr;
     return dsp_block_recompute_backward(pl->blocks[k], bb, gout, gin, st);
 }
 
@@ -512,8 +568,8 @@ static int tick_step(dsp_pipeline* pl, int k, int64_t tau, hipStream_t st, bool 
     if (k < K - 1) DSP_TRY(dsp_block_input_slot(pl->blocks[k + 1], a, &out));
     const int32_t* lab = pl->labels + (size_t)(a % pl->label_slots) * pl->N;
     const bool last = k == K - 1;
-    const void* gout = k < K - 1 ? pl->qring[k + 1] + (size_t)(bb % (1 + pl->q[k + 1])) * pl->qslot_bytes[k + 1] : nullptr;
-    void* gin = k > 0 ? pl->qring[k] + (size_t)(bb % (1 + pl->q[k])) * pl->qslot_bytes[k] : nullptr;
+    const void* gout = k < K - 1 ? pl->qring[k + 1] + (size_t)(bb % pl->qn[k + 1]) * pl->qslot_bytes[k + 1] : nullptr;
+    void* gin = k > 0 ? pl->qring[k] + (size_t)(bb % pl->qn[k]) * pl->qslot_bytes[k] : nullptr;
     DSP_TRY(dsp_block_step(b, a, in, out, last ? lab : nullptr, last ? pl->loss_tmp : nullptr, bb, gout, gin, st));
     if (last && !dry) DSP_TRY(launch_record_loss(pl->loss_tmp, pl->losses, pl->loss_count, pl->max_ticks + 1, st));
     return DSP_OK;
@@ -546,20 +602,24 @@ static int block_tick(dsp_pipeline* pl, int k, int64_t tau, hipStream_t st, bool
 static int run_block_tick(dsp_pipeline* pl, int k, int64_t tau)
 {
     const int K = pl->K;
-    const int cur = (int)(tau & 1), prev = cur ^ 1;
+    const int R = pl->ev_depth;
+    const int cur = (int)(tau % R), prev = (int)((tau + R - 1) % R);
+    const int fcur = (int)(tau & 1), fprev = fcur ^ 1;
     const bool split = pl->fwd_split[k] != 0;
     hipStream_t sb = pl->streams[k];
     hipStream_t sf = split ? pl->fstreams[k] : sb;
-    // Neighbours' previous tick: the slots this block reads were written then or earlier, and
-    // the slots it writes were last read then or earlier.  (The labels of the mini-batch the
+    // The neighbours' tick wait_dn / wait_up back (the previous tick unless the queues have spare
+    // entries): the slots this block reads were written then or earlier, and the slots it writes
+    // were last read then or earlier.  Every host thread has issued that tick (ticks are issued
+    // one at a time), so its event already stands for it.  (The labels of the mini-batch the
     // last block sees now were copied on stream 0 P_{K-1} >= K-1 ticks ago, which this chain
-    // of waits orders; the label ring has P_{K-1}+K slots so a slot is not refilled too early.)
+    // of waits orders; the label ring is long enough that a slot is not refilled too early.)
+    if (k > 0 && pl->wait_dn[k] > 0 && tau >= pl->wait_dn[k]) DSP_HIP(hipStreamWaitEvent(sb, pl->done[(tau - pl->wait_dn[k]) % R][k - 1], 0));
+    if (k < K - 1 && pl->wait_up[k] > 0 && tau >= pl->wait_up[k]) DSP_HIP(hipStreamWaitEvent(sb, pl->done[(tau - pl->wait_up[k]) % R][k + 1], 0));
     if (tau > 0) {
-        if (k > 0) DSP_HIP(hipStreamWaitEvent(sb, pl->done[prev][k - 1], 0));
-        if (k < K - 1) DSP_HIP(hipStreamWaitEvent(sb, pl->done[prev][k + 1], 0));
         if (split) {
             DSP_HIP(hipStreamWaitEvent(sf, pl->done[prev][k], 0));                       // its own last update
-            if (k > 0) DSP_HIP(hipStreamWaitEvent(sf, pl->fdone[prev][k - 1], 0));        // its input
+            if (k > 0) DSP_HIP(hipStreamWaitEvent(sf, pl->fdone[fprev][k - 1], 0));       // its input
             if (k < K - 1) DSP_HIP(hipStreamWaitEvent(sf, pl->done[prev][k + 1], 0));     // the slot its output goes to
         }
     }
@@ -570,19 +630,19 @@ static int run_block_tick(dsp_pipeline* pl, int k, int64_t tau)
     }
     if (!split) {
         DSP_TRY(block_tick(pl, k, tau, sb, true, true));
-        DSP_HIP(hipEventRecord(pl->fdone[cur][k], sb));
+        DSP_HIP(hipEventRecord(pl->fdone[fcur][k], sb));
         DSP_HIP(hipEventRecord(pl->done[cur][k], sb));
         return DSP_OK;
     }
     DSP_TRY(tick_forward(pl, k, tau, sf, false));
-    DSP_HIP(hipEventRecord(pl->fdone[cur][k], sf));
+    DSP_HIP(hipEventRecord(pl->fdone[fcur][k], sf));
     bool did;
     DSP_TRY(tick_backward(pl, k, tau, sb, &did));
     if (did) {
-        if (split) DSP_HIP(hipStreamWaitEvent(sb, pl->fdone[cur][k], 0));  // the forward pass has read the parameters
+        if (split) DSP_HIP(hipStreamWaitEvent(sb, pl->fdone[fcur][k], 0));  // the forward pass has read the parameters
         DSP_TRY(tick_update(pl, k, sb));
     } else if (split) {
-        DSP_HIP(hipStreamWaitEvent(sb, pl->fdone[cur][k], 0));  // keep done[cur][k] meaning "everything of this tick"
+        DSP_HIP(hipStreamWaitEvent(sb, pl->fdone[fcur][k], 0));  // keep done[cur][k] meaning "everything of this tick"
     }
     DSP_HIP(hipEventRecord(pl->done[cur][k], sb));
     return DSP_OK;
@@ -705,7 +765,8 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
     DSP_REQUIRE(pl->tau < pl->max_ticks, DSP_ESTATE, "dsp_pipeline_step: max_ticks (%lld) reached", (long long)pl->max_ticks);
     const int K = pl->K;
     const int64_t tau = pl->tau;
-    const int cur = (int)(tau & 1), prev = cur ^ 1;
+    const int R = pl->ev_depth;
+    const int cur = (int)(tau % R), prev = (int)((tau + R - 1) % R);
     hipStream_t user = (hipStream_t)stream;
     hipStream_t s0 = pl->streams[0];
 
@@ -726,9 +787,12 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
     DSP_HIP(hipStreamWaitEvent(s0, pl->in_ready, 0));
     if (tau > 0 && !pl->serial) {
         // block 0's slot for this tick is free (its own earlier ticks ran on this stream); a graph tick
-        // additionally starts only after every stream has finished the previous tick
-        for (int k = 1; k < K; ++k)
-            if (graph_tick || k == 1) DSP_HIP(hipStreamWaitEvent(s0, pl->done[prev][k], 0));
+        // starts only after every stream has finished the previous tick, any other after the tick of block 1
+        // that block 0 is about to wait for anyway
+        if (graph_tick)
+            for (int k = 1; k < K; ++k) DSP_HIP(hipStreamWaitEvent(s0, pl->done[prev][k], 0));
+        else if (K > 1 && pl->wait_up[0] > 0 && tau >= pl->wait_up[0])
+            DSP_HIP(hipStreamWaitEvent(s0, pl->done[(tau - pl->wait_up[0]) % R][1], 0));
     }
     void* slot0;
     DSP_TRY(dsp_block_input_slot(pl->blocks[0], tau, &slot0));
@@ -752,6 +816,7 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
             DSP_HIP(hipStreamBeginCapture(s0, hipStreamCaptureModeRelaxed));
             const int rc = issue_tick(pl, tau, true);
             const hipError_t e = hipStreamEndCapture(s0, &graph);
+            if (rc != DSP_OK && graph) (void)hipGraphDestroy(graph);
             DSP_TRY(rc);
             DSP_REQUIRE(e == hipSuccess && graph, DSP_EHIP, "dsp_pipeline_step: graph capture failed: %s", hipGetErrorString(e));
             hipGraphExec_t exec = nullptr;
@@ -771,7 +836,7 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
         DSP_HIP(hipGraphLaunch(pl->graphs[phase], s0));
         for (int k = 0; k < K; ++k) {
             DSP_HIP(hipEventRecord(pl->done[cur][k], s0));
-            DSP_HIP(hipEventRecord(pl->fdone[cur][k], s0));
+            DSP_HIP(hipEventRecord(pl->fdone[tau & 1][k], s0));
         }
     }
     pl->tau = tau + 1;

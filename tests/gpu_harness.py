@@ -54,8 +54,9 @@ def block_shapes(cfg):
     return shapes
 
 
-def build_gpu_blocks(cfg, params, dtype, p=None, m=None, standalone=False):
-    """One library block per config block; rings sized for DSP(p; m) (p_prev = 0 when stand-alone)."""
+def build_gpu_blocks(cfg, params, dtype, p=None, m=None, standalone=False, spare=0):
+    """One library block per config block; rings sized for DSP(p; m) (p_prev = 0 when stand-alone) plus
+    ``spare`` entries of slack in every queue between two blocks."""
     p = list(cfg["p"] if p is None else p)
     m = list(cfg["m"] if m is None else m)
     K = len(cfg["blocks"])
@@ -64,7 +65,7 @@ def build_gpu_blocks(cfg, params, dtype, p=None, m=None, standalone=False):
     for k, layers in enumerate(cfg["blocks"]):
         first = k == 0 and cfg.get("data_input", True)
         desc, keep = D.make_block_desc(layers, shapes[k], dtype, k, K, m[k],
-                                       p_prev=0 if (standalone or k == 0) else p[k - 1],
+                                       p_prev=0 if (standalone or k == 0) else p[k - 1] + spare,
                                        needs_input_grad=not first)
         blocks.append(D.dsp_block_init(desc, flatten_params(layers, params[k])))
         del keep

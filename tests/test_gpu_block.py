@@ -362,6 +362,52 @@ def test_pipeline_equals_manual_fifo_schedule_bit_for_bit(name, dtype, ticks, kw
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("name,dtype,ticks,kw,spare,graphs", [
+    ("tiny2", D.DSP_FP32, 30, {}, 1, False),
+    ("resnet20", D.DSP_FP32, 30, {"batch": 8, "hw": 16}, 3, False),
+    ("resnet20", D.DSP_FP32, 20, {"batch": 4, "hw": 8, "p": (2, 2, 0), "m": (6, 3, 0)}, 2, False),    # waits 2 down, 1 up
+    ("resnet20", D.DSP_FP32, 26, {"batch": 4, "hw": 8, "p": (3, 3, 0), "m": (10, 5, 0)}, 4, False),   # q = 2: waits 3 down, 2 up
+    ("resnet20", D.DSP_FP32, 20, {"batch": 4, "hw": 8, "p": (1, 1, 0), "m": (7, 3, 1)}, 2, False),    # q_1 = 3, stale last block
+    ("resnet56", D.DSP_BF16, 16, {"batch": 8, "hw": 16}, 2, False),
+    ("resnet20", D.DSP_FP32, 60, {"batch": 4, "hw": 8, "p": (2, 2, 0), "m": (6, 3, 0)}, 1, True),     # ring period 60 with the spare entry
+], ids=lambda v: v if isinstance(v, str) else None)
+def test_spare_queue_entries_and_random_stragglers_change_no_bit(name, dtype, ticks, kw, spare, graphs):
+    """Section 6 (robustness): with spare entries in the queues between blocks a block that is late for a
+    tick does not hold the others up at once.  Which mini-batch meets which parameters is fixed by the
+    tick number, so the losses and the final parameters must be exactly those of the serial FIFO-queue
+    schedule however the streams drift: here every tick delays a random subset of the blocks by up to
+    a few hundred microseconds (several times the work of a tick at these sizes)."""
+    cfg, params, rng = _setup(name, **kw)
+    batches = [make_batch(rng, cfg["input"], cfg["classes"]) for _ in range(ticks)]
+    ref_losses, ref_params = _manual_schedule(cfg, params, batches, dtype)
+    blocks = build_gpu_blocks(cfg, params, dtype, spare=spare)
+    pl = D.dsp_pipeline_init(blocks, cfg["p"], cfg["m"], cfg["lr"], cfg["beta"], cfg["wd"], ticks)
+    D.dsp_pipeline_set_graph_replay(pl, graphs)
+    drng = np.random.default_rng(1234)
+    try:
+        for k, b in enumerate(blocks):
+            want = 1 + cfg["m"][k] + (cfg["p"][k - 1] + spare if k else 0)
+            assert D.dsp_block_query(b)["ring_entries"] == want
+        dn, up, _ = D.dsp_schedule_waits(cfg["p"], cfg["m"], [0] + [spare] * (cfg["K"] - 1))
+        if max(dn + up) > 1:  # the forward-stream mode orders its two streams per block by the previous tick only
+            with pytest.raises(D.DSPError):
+                D.dsp_pipeline_set_forward_streams(pl, True)
+        for x, y in batches:
+            if not graphs:  # a changed delay drops the recorded graphs
+                for k in range(cfg["K"]):
+                    D.dsp_pipeline_set_delay(pl, k, int(drng.integers(50, 400)) if drng.random() < 1 / 3 else 0)
+            D.dsp_pipeline_step(pl, to_dev(x, dtype), torch.from_numpy(y).cuda())
+        got = D.dsp_pipeline_losses(pl)
+        prm = [D.dsp_block_get_params(b) for b in blocks]
+    finally:
+        D.dsp_pipeline_destroy(pl)
+        destroy_blocks(blocks)
+    assert len(got) == len(ref_losses) == ticks - sum(cfg["p"])
+    assert np.array_equal(got, ref_losses)
+    for a, b in zip(prm, ref_params):
+        assert np.array_equal(a, b)
+
+
 # Free-running trajectories.  A ReLU pre-activation within a few fp32 ulps of zero takes either branch;
 # on small tensors one such decision moves that step's gradient by ~1/sqrt(elements), i.e. by far more
 # than 1e-3, so the 1e-3 bound on the loss trajectory is checked at the configurations' real sizes

@@ -107,3 +107,128 @@ def test_make_block_desc_marshalling():
     assert ops[0] == 0 and ops[1] == 1
     res = [keep[i].in1 for i in range(desc.n_layers) if keep[i].op == 1]
     assert -2 in res and any(r >= -1 for r in res)
+
+
+def _drift_simulation(p, m, spare, wait_dn, wait_up, label_slots, ticks, rng):
+    """Lets K blocks run their ticks as intervals [start, end] on a common clock in a random order that only
+    obeys "block k starts tick tau after block k-1 has ended tick tau - wait_dn[k] and block k+1 has ended
+    tick tau - wait_up[k]" and its own stream order, with blocks stalling at random.  Every queue access of a
+    tick may happen anywhere inside its interval.  Returns the list of hazards found: a read whose value was
+    written by a tick that had not ended before the reader's tick started, or whose slot is rewritten by a
+    tick that started before the reader's tick ended."""
+    K = len(m)
+    q = O.queue_lengths(p, m)
+    P = [sum(p[:k]) for k in range(K)]
+    ring = [1 + m[k] + (p[k - 1] + spare[k] if k else 0) for k in range(K)]
+    qn = [1 + q[k] + spare[k] for k in range(K)]
+    started, ended, clock = [0] * K, [0] * K, 0
+    span = {}
+    stall = [0] * K
+    while min(ended) < ticks:
+        moves = []
+        for k in range(K):
+            if started[k] > ended[k]:
+                if stall[k] == 0:
+                    moves.append(("end", k))
+            elif started[k] < ticks:
+                tau = started[k]
+                dn_ok = k == 0 or wait_dn[k] == 0 or tau < wait_dn[k] or ended[k - 1] > tau - wait_dn[k]
+                up_ok = k == K - 1 or wait_up[k] == 0 or tau < wait_up[k] or ended[k + 1] > tau - wait_up[k]
+                if dn_ok and up_ok:
+                    moves.append(("start", k))
+        clock += 1
+        if not moves:
+            assert any(stall), "the waits deadlock: %r" % ((started, ended),)
+        for k in range(K):
+            stall[k] = max(0, stall[k] - 1)
+        if not moves:
+            continue
+        kind, k = moves[rng.integers(len(moves))]
+        if kind == "start":
+            span[(k, started[k])] = [clock, None]
+            started[k] += 1
+            if rng.random() < 0.2:
+                stall[k] = int(rng.integers(1, 12 * K))   # this tick takes many times longer than the others'
+        else:
+            span[(k, ended[k])][1] = clock
+            ended[k] += 1
+    # the accesses of every tick, per shared resource (a queue between two blocks, or the label ring)
+    writes, reads = {}, []   # (resource, slot) -> [(batch, tick key)], and (resource, slot, batch, tick key)
+    for k in range(K):
+        for tau in range(ticks):
+            a, key = tau - P[k], (k, tau)
+            b = a - m[k] if a >= 0 else -1
+            if k == 0:
+                writes.setdefault(("labels", tau % label_slots), []).append((tau, key))
+            if a >= 0:
+                if k > 0:
+                    reads.append((("act", k), a % ring[k], a, key))
+                if k < K - 1:
+                    writes.setdefault((("act", k + 1), a % ring[k + 1]), []).append((a, key))
+                else:
+                    reads.append(("labels", a % label_slots, a, key))
+            if b >= 0:
+                if k > 0:
+                    reads.append((("act", k), b % ring[k], b, key))
+                    writes.setdefault((("grad", k), b % qn[k]), []).append((b, key))
+                if k < K - 1:
+                    reads.append((("grad", k + 1), b % qn[k + 1], b, key))
+    hazards = []
+    for res, slot, batch, key in reads:
+        ws = writes.get((res, slot), [])
+        mine = [w for w in ws if w[0] == batch]
+        if len(mine) != 1:
+            hazards.append(("never written", res, batch, key))
+            continue
+        if not span[mine[0][1]][1] < span[key][0]:
+            hazards.append(("read before written", res, batch, key))
+        for wb, wkey in ws:
+            if wb > batch and not span[wkey][0] > span[key][1]:
+                hazards.append(("rewritten before read", res, batch, key, wb))
+    return hazards
+
+
+@pytest.mark.parametrize("p,m,spare", [
+    ((1, 1, 0), (4, 2, 0), (0, 0, 0)), ((1, 1, 0), (4, 2, 0), (0, 2, 2)), ((2, 2, 0), (6, 3, 0), (0, 1, 3)),
+    ((3, 3, 0), (10, 5, 0), (0, 4, 4)), ((3, 3, 0), (10, 5, 0), (0, 0, 1)), ((1, 1, 0), (7, 3, 1), (0, 2, 0)),
+    ((2, 1, 3, 0), (12, 8, 4, 0), (0, 3, 0, 5)), ((1, 0), (2, 0), (0, 6)),
+])
+def test_wait_distances_keep_every_queue_access_ordered_however_the_blocks_drift(p, m, spare):
+    """Section 3.3 / Section 6 (robustness): with spare queue entries the blocks may drift apart; the wait
+    distances the library derives must still order every read after its write and before the slot's next
+    write, never deadlock, and be the loosest that do (one tick more in either direction gives a hazard)."""
+    K = len(m)
+    q = O.queue_lengths(p, m)
+    dn, up, labels = D.dsp_schedule_waits(p, m, spare)
+    assert dn == [0] + [min(p[k - 1], 1 + spare[k]) for k in range(1, K)]
+    assert up == [min(q[k + 1], 1 + spare[k + 1]) for k in range(K - 1)] + [0]
+    rng = np.random.default_rng(99)
+    for trial in range(12):
+        assert _drift_simulation(p, m, spare, dn, up, labels, 60, rng) == []
+    # teeth: looking one tick further back on any single edge lets some interleaving break an access
+    for k in range(K):
+        for which in ("dn", "up"):
+            if (which == "dn" and k == 0) or (which == "up" and k == K - 1):
+                continue
+            d2, u2 = list(dn), list(up)
+            (d2 if which == "dn" else u2)[k] += 1
+            found = False
+            for trial in range(40):
+                try:
+                    found = found or bool(_drift_simulation(p, m, spare, d2, u2, labels, 60, rng))
+                except AssertionError:
+                    found = True
+                if found:
+                    break
+            assert found, (which, k)
+    # the label ring (sufficient, not always the minimum) must at least span the forward lag of the last block
+    assert sum(p) + 1 <= labels <= sum(p) + K + sum(spare)
+
+
+def test_schedule_waits_arguments():
+    assert D.dsp_schedule_waits((0, 0, 0), (0, 0, 0)) == ([0, 0, 0], [0, 0, 0], 3)
+    assert D.dsp_schedule_waits((1, 1, 0), (4, 2, 0)) == ([0, 1, 1], [1, 1, 0], 5)
+    with pytest.raises(D.DSPError):
+        D.dsp_schedule_waits((1, 1, 0), (4, 2, 0), (1, 0, 0))    # block 0 has no queue below it
+    with pytest.raises(D.DSPError):
+        D.dsp_schedule_waits((1, 1, 0), (4, 2, 0), (0, 65, 0))
