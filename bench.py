@@ -5,7 +5,7 @@ A "step" is one pipeline tick: every block of DSP(p; m) runs forward(a), recompu
 its momentum-SGD update on its own HIP stream, on synthetic inputs that are already resident in
 HBM.  Prints ONE JSON line (the fields are described in the README).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet20|resnet56|resnet18|resnet50_conv4x|vgg19|resnet164|tiny2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet20|resnet56|resnet18|resnet50_conv4x|vgg19|resnet164|resnet1001|tiny2]
 """
 from __future__ import annotations
 
@@ -57,7 +57,7 @@ class Workload:
         import torch
 
         import paper_1909_02625_amd as D
-        from tests.gpu_harness import block_shapes, build_gpu_blocks, round_like, to_dev
+        from paper_1909_02625_amd.marshal import block_shapes, build_gpu_blocks, round_like, to_dev
         from workloads import get_config, make_batch, make_params
         from workloads.gen import make_error_gradient
 
@@ -115,7 +115,7 @@ class Workload:
         self.torch.cuda.synchronize()
 
     def close(self):
-        from tests.gpu_harness import destroy_blocks
+        from paper_1909_02625_amd.marshal import destroy_blocks
         if self.pl is not None:
             self.D.dsp_pipeline_destroy(self.pl)
         destroy_blocks(self.blocks)

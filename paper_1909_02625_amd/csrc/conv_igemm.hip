@@ -1232,8 +1232,11 @@ __global__ __launch_bounds__(256) void wgrad_reduce_all_kernel(const ReduceTask*
 {
     constexpr int COLS = 32 / VW, ROWS = 256 / COLS;
     __shared__ float red[ROWS][33];
-    int p = 0;
-    while (p + 1 < n_tasks && (int)blockIdx.x >= tasks[p + 1].block_begin) ++p;
+    int p = 0, hi = n_tasks;  // last task whose first workgroup is not after this one (block_begin ascends)
+    while (hi - p > 1) {
+        const int mid = (p + hi) >> 1;
+        if ((int)blockIdx.x >= tasks[mid].block_begin) p = mid; else hi = mid;
+    }
     const ReduceTask t = tasks[p];
     const int blk = (int)blockIdx.x - t.block_begin;
     const float* __restrict__ part = t.part;

@@ -24,7 +24,7 @@ def trace(workload, dtype_name, ticks, lr, batch=None):
     import torch
 
     import paper_1909_02625_amd as D
-    from tests.gpu_harness import build_gpu_blocks, destroy_blocks, round_like, to_dev
+    from paper_1909_02625_amd.marshal import build_gpu_blocks, destroy_blocks, round_like, to_dev
     from workloads import get_config, make_batch, make_params
 
     cfg = get_config(workload, batch=batch)

@@ -1,77 +1,13 @@
-"""Marshalling helpers shared by the GPU parity tests, the smoke check and the benchmark:
-numpy NCHW fp32/fp64 <-> torch device tensors in NHWC, and construction of library blocks /
-oracle blocks from one workload config.  No arithmetic of the method lives here."""
+"""Helpers of the GPU parity tests: the package's marshalling functions plus the error norm the tests use."""
 from __future__ import annotations
 
 import numpy as np
-import torch
 
-import paper_1909_02625_amd as D
-from workloads import flatten_params
-from workloads.configs import block_output_shape
-
-
-def torch_dtype(dtype):
-    return torch.bfloat16 if dtype == D.DSP_BF16 else torch.float32
-
-
-def to_dev(a, dtype, feature_map=True):
-    """numpy NCHW (or N x C) -> contiguous NHWC device tensor in the block storage type."""
-    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
-    if t.dim() == 4:
-        t = t.permute(0, 2, 3, 1).contiguous()
-    td = torch_dtype(dtype) if (feature_map and t.dim() == 4) else torch.float32
-    return t.to(device="cuda", dtype=td).contiguous()
-
-
-def from_dev(t, shape):
-    """device NHWC tensor (flat or shaped) -> numpy fp64 in NCHW ``shape`` (or N x C)."""
-    h = t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
-    if len(shape) == 4:
-        n, c, hh, ww = shape
-        return h.reshape(n, hh, ww, c).transpose(0, 3, 1, 2).copy()
-    return h.reshape(shape)
-
-
-def round_like(a, dtype):
-    """What the storage type keeps of fp32 values (bf16 round-to-nearest-even), as fp32 numpy."""
-    if dtype == D.DSP_BF16:
-        return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(torch.bfloat16).to(torch.float32).numpy()
-    return np.asarray(a, np.float32)
+from paper_1909_02625_amd.marshal import (block_shapes, build_gpu_blocks, destroy_blocks, from_dev, round_like,  # noqa: F401
+                                          to_dev, torch_dtype)
 
 
 def rel_err(a, b):
     a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
     nb = np.linalg.norm(b.ravel())
     return float(np.linalg.norm((a - b).ravel()) / (nb if nb > 0 else 1.0))
-
-
-def block_shapes(cfg):
-    """Input shape of every block and the final output shape."""
-    shapes = [tuple(cfg["input"])]
-    for layers in cfg["blocks"]:
-        shapes.append(tuple(block_output_shape(layers, shapes[-1])))
-    return shapes
-
-
-def build_gpu_blocks(cfg, params, dtype, p=None, m=None, standalone=False, spare=0):
-    """One library block per config block; rings sized for DSP(p; m) (p_prev = 0 when stand-alone) plus
-    ``spare`` entries of slack in every queue between two blocks."""
-    p = list(cfg["p"] if p is None else p)
-    m = list(cfg["m"] if m is None else m)
-    K = len(cfg["blocks"])
-    shapes = block_shapes(cfg)
-    blocks = []
-    for k, layers in enumerate(cfg["blocks"]):
-        first = k == 0 and cfg.get("data_input", True)
-        desc, keep = D.make_block_desc(layers, shapes[k], dtype, k, K, m[k],
-                                       p_prev=0 if (standalone or k == 0) else p[k - 1] + spare,
-                                       needs_input_grad=not first)
-        blocks.append(D.dsp_block_init(desc, flatten_params(layers, params[k])))
-        del keep
-    return blocks
-
-
-def destroy_blocks(blocks):
-    for b in blocks:
-        D.dsp_block_destroy(b)

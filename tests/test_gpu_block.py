@@ -211,6 +211,8 @@ labels_by_batch = {}
     # pre-activation bottleneck ResNet-164 (element-wise add layers, BN directly on a block input, 128 layers per block)
     ("resnet164", D.DSP_FP32, 7, {"batch": 4, "hw": 16, "perturb": True, "many_decisions": True}),
     ("resnet164", D.DSP_BF16, 7, {"batch": 8, "hw": 16, "perturb": True}),
+    # ResNet-1001 (same unit as ResNet-164; 387-915 layers per block, K = 4), every block twice through its update
+    ("resnet1001", D.DSP_FP32, 9, {"batch": 4, "hw": 8, "perturb": True, "many_decisions": True}),
     # Eq. (3) beyond the constant-step heavy ball: Nesterov (s = 1), weight decay, a step schedule that drops
     # the step size twice while every block carries momentum
     ("resnet20", D.DSP_FP32, 9, {"batch": 8, "hw": 16, "perturb": True, "sum_s": 1, "wd": 5e-4,
@@ -333,6 +335,7 @@ def _manual_schedule(cfg, params, batches, dtype):
     ("resnet18", D.DSP_BF16, 12, {"batch": 4, "hw": 64}),
     ("resnet20", D.DSP_FP32, 12, {"batch": 4, "hw": 8, "p": (2, 2, 0), "m": (6, 3, 0)}),   # p = 2: deeper queues
     ("resnet20", D.DSP_FP32, 12, {"batch": 4, "hw": 8, "p": (1, 1, 0), "m": (7, 3, 1)}),   # q_1 = 3, stale last block
+    ("resnet1001", D.DSP_BF16, 10, {"batch": 2, "hw": 8}),                                 # K = 4, up to 915 layers per block
 ], ids=lambda v: v if isinstance(v, str) else None)
 @pytest.mark.parametrize("mode", ["twin", "separate", "forward_streams"])
 def test_pipeline_equals_manual_fifo_schedule_bit_for_bit(name, dtype, ticks, kw, mode):
