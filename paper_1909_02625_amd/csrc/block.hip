@@ -395,7 +395,16 @@ static int build_graph(dsp_block* b)
     for (int i = 0; i + 1 < d.n_layers; ++i) {
         Layer& L = b->layers[i];
         Layer& nx = b->layers[i + 1];
-        if (L.d.op != DSP_OP_CONV || nx.d.op != DSP_OP_BN || nx.d.in0 != i) continue;
+        if (nx.d.op != DSP_OP_BN || nx.d.in0 != i) continue;
+        if (L.d.op == DSP_OP_ADD) {
+            // the sum layer of a pre-activation unit also leaves the column sums of its output for the next unit's BN
+            const Tensor& t = b->T[i];
+            L.sum_tiles = nx.sum_tiles = add_stats_blocks(b->dtype, (int64_t)t.N * t.H * t.W, t.C);
+            const size_t e = (size_t)L.sum_tiles * t.C;
+            if (e > partial_elems) partial_elems = e;
+            continue;
+        }
+        if (L.d.op != DSP_OP_CONV) continue;
         L.sum_tiles = nx.sum_tiles = conv_forward_row_tiles(b->dtype, L.cs);
         const size_t e = (size_t)L.sum_tiles * L.d.cout;
         if (e > partial_elems) partial_elems = e;
@@ -488,6 +497,13 @@ static int run_forward(dsp_block* b, const ForwardPass& P, const ForwardPass* tw
             break;
         }
         case DSP_OP_ADD:
+            if (L.sum_tiles > 0) {  // the next layer is a batch norm on this sum: leave its column sums as well
+                AddStatsTwin tw{};
+                if (twin) tw = AddStatsTwin{src_of(*twin, L.d.in0), src_of(*twin, L.d.in1), act_of(*twin, i), bn_buffers(*twin).partial};
+                DSP_TRY(launch_add_forward_stats(b->dtype, src_of(P, L.d.in0), src_of(P, L.d.in1), act_of(P, i),
+                                                 (int64_t)s.N * s.H * s.W, s.C, bn_buffers(P).partial, st, twin ? &tw : nullptr));
+                break;
+            }
             for (int q = 0; q < passes; ++q) {
                 const ForwardPass& p = q ? *twin : P;
                 DSP_TRY(launch_add_forward(b->dtype, src_of(p, L.d.in0), src_of(p, L.d.in1), act_of(p, i),

@@ -37,18 +37,32 @@ inline RowLayout make_layout(int C, int VW)
 // ---- per-channel sums ---------------------------------------------------------------------------
 // MODE 0: s0 = sum x, s1 = sum x^2.
 // MODE 1: dz = dy * [y > 0] (if RELU); s0 = sum dz, s1 = sum dz * (x - mean) * invstd.
+// MODE 2: out = x + dy as stored (the element-wise sum of two feature maps); s0 = sum out, s1 = sum out^2:
+//         the sum layer together with the statistics pass of the batch norm that reads it.
 // part[blockIdx.x][c][2]; blockIdx.y walks channel groups when C/VW > 256.
+template <typename T>
+struct AddOut {
+    T* out;        // MODE 2: the sum
+    const T* b1;   // second instance: the other operand and the sum
+    T* out1;
+};
 template <typename T, int VW, int MODE, bool RELU>
 __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__ x, const T* __restrict__ dy,
                                                            const T* __restrict__ y, const float* __restrict__ mean,
                                                            const float* __restrict__ invstd, double* __restrict__ part,
                                                            int64_t M, int C, RowLayout L, int rows_per_block,
-                                                           const T* __restrict__ x1, double* __restrict__ part1)
+                                                           const T* __restrict__ x1, double* __restrict__ part1,
+                                                           AddOut<T> add)
 {
     // blockIdx.z = 1: the second instance of a twin launch (other tensor, same shape)
+    T* __restrict__ out = add.out;
     if (blockIdx.z) {
         x = x1;
         part = part1;
+        if (MODE == 2) {
+            dy = add.b1;
+            out = add.out1;
+        }
     }
     __shared__ double red[kThreads][VW][2];
     const int tid = threadIdx.x;
@@ -80,7 +94,7 @@ __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__
                 const int64_t ru = r + (int64_t)u * L.rl;
                 if (ru < r_end) {
                     VecIO<T, VW>::load(x + ru * C + c0, xv[u]);
-                    if (MODE == 1) VecIO<T, VW>::load(dy + ru * C + c0, gv[u]);
+                    if (MODE >= 1) VecIO<T, VW>::load(dy + ru * C + c0, gv[u]);
                     if (MODE == 1 && RELU) VecIO<T, VW>::load(y + ru * C + c0, yv[u]);
                 }
             }
@@ -89,7 +103,8 @@ __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__
                 if (r + (int64_t)u * L.rl >= r_end) break;
 #pragma unroll
                 for (int i = 0; i < VW; ++i) {
-                    if (MODE == 0) {
+                    if (MODE == 2) xv[u][i] = to_float<T>(from_float<T>(xv[u][i] + gv[u][i]));  // the value as stored
+                    if (MODE == 0 || MODE == 2) {
                         s0[i] += (double)xv[u][i];
                         s1[i] += (double)xv[u][i] * (double)xv[u][i];
                     } else {
@@ -98,6 +113,7 @@ __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__
                         s1[i] += (double)(dz * ((xv[u][i] - mu[i]) * is[i]));
                     }
                 }
+                if (MODE == 2) VecIO<T, VW>::store(out + (r + (int64_t)u * L.rl) * C + c0, xv[u]);
             }
         }
     }
@@ -318,7 +334,7 @@ int bn_forward_t(const void* x, const void* res, void* y, const float* gamma, co
         ProfScope ps(sizeof(T) == 2 ? "bn_stats<bf16>" : "bn_stats<fp32>", tensor_bytes, 1);
         DSP_LAUNCH(ps, (bn_sums_kernel<T, VW, 0, false>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)nullptr,
                    (const T*)nullptr, (const float*)nullptr, (const float*)nullptr, buf.partial, M, C, L, rows,
-                   (const T*)(tw ? tw->x : nullptr), tw ? tw->buf.partial : nullptr);
+                   (const T*)(tw ? tw->x : nullptr), tw ? tw->buf.partial : nullptr, AddOut<T>{});
     }
     {
         const BnStatOut o0{buf.partial, buf.mean, buf.invstd, buf.coef};
@@ -357,7 +373,7 @@ int bn_backward_t(const void* dy, const void* x, const void* y, void* dx, void* 
         ProfScope ps(sizeof(T) == 2 ? "bn_bwd_reduce<bf16>" : "bn_bwd_reduce<fp32>", tensor_bytes * (RELU ? 3 : 2), 1);
         DSP_LAUNCH(ps, (bn_sums_kernel<T, VW, 1, RELU>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)dy,
                    (const T*)y, (const float*)buf.mean, (const float*)buf.invstd, buf.partial, M, C, L, rows,
-                   (const T*)nullptr, (double*)nullptr);
+                   (const T*)nullptr, (double*)nullptr, AddOut<T>{});
     }
     {
         ProfScope ps("bn_bwd_finalize", (double)nblk * C * 16.0, 1);
@@ -386,6 +402,46 @@ int bn_backward_t(const void* dy, const void* x, const void* y, void* dx, void* 
 }  // namespace
 
 int bn_max_partial_blocks() { return kMaxPartialBlocks; }
+
+template <typename T, int VW>
+int add_stats_t(const void* a, const void* b, void* y, int64_t M, int C, double* partial, hipStream_t st,
+                const AddStatsTwin* tw)
+{
+    const RowLayout L = make_layout(C, VW);
+    int nblk;
+    const int rows = plan_rows(M, L, &nblk);
+    const unsigned ni = tw ? 2 : 1;
+    const dim3 grid(nblk, ceil_div(L.cv, L.cvb), ni);
+    ProfScope ps("add_fwd_stats", (double)M * C * sizeof(T) * 3.0 * ni, 1);
+    DSP_LAUNCH(ps, (bn_sums_kernel<T, VW, 2, false>), grid, dim3(kThreads), 0, st, (const T*)a, (const T*)b, (const T*)nullptr,
+               (const float*)nullptr, (const float*)nullptr, partial, M, C, L, rows, (const T*)(tw ? tw->a : nullptr),
+               tw ? tw->partial : nullptr, (AddOut<T>{(T*)y, (const T*)(tw ? tw->b : nullptr), (T*)(tw ? tw->y : nullptr)}));
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+static bool add_stats_vec(int dtype, int C) { return C % (dtype == DSP_BF16 ? 8 : 4) == 0; }
+
+int add_stats_blocks(int dtype, int64_t M, int C)
+{
+    const int vw = add_stats_vec(dtype, C) ? (dtype == DSP_BF16 ? 8 : 4) : 1;
+    int nblk;
+    (void)plan_rows(M, make_layout(C, vw), &nblk);
+    return nblk;
+}
+
+int launch_add_forward_stats(int dtype, const void* a, const void* b, void* y, int64_t M, int C, double* partial,
+                             hipStream_t st, const AddStatsTwin* twin)
+{
+    DSP_REQUIRE(a && b && y && partial && M > 0 && C > 0, DSP_EINVAL, "add + statistics: bad argument");
+    if (twin) DSP_REQUIRE(twin->a && twin->b && twin->y && twin->partial, DSP_EINVAL, "add + statistics: incomplete second instance");
+    if (dtype == DSP_BF16) {
+        if (add_stats_vec(dtype, C)) return add_stats_t<bf16_t, 8>(a, b, y, M, C, partial, st, twin);
+        return add_stats_t<bf16_t, 1>(a, b, y, M, C, partial, st, twin);
+    }
+    if (add_stats_vec(dtype, C)) return add_stats_t<float, 4>(a, b, y, M, C, partial, st, twin);
+    return add_stats_t<float, 1>(a, b, y, M, C, partial, st, twin);
+}
 
 int launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
                       float eps, int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed,

@@ -178,6 +178,18 @@ struct BnForwardTwin {
 int launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
                       float eps, int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed = 0,
                       const BnForwardTwin* twin = nullptr);
+// y = a + b over [M][C] (as launch_add_forward) and, in the same pass, the per-block column sums {sum y, sum y^2}
+// of the stored values in partial[add_stats_blocks()][C][2]: exactly what launch_bn_forward(y, ...) would compute
+// first, so the batch norm that reads y is called with presummed = add_stats_blocks().  twin: a second instance.
+struct AddStatsTwin {
+    const void* a;
+    const void* b;
+    void* y;
+    double* partial;
+};
+int add_stats_blocks(int dtype, int64_t M, int C);
+int launch_add_forward_stats(int dtype, const void* a, const void* b, void* y, int64_t M, int C, double* partial,
+                             hipStream_t st, const AddStatsTwin* twin = nullptr);
 // Backward of the map above given dy and the saved x, y, mean, invstd:
 // dz = dy * [y > 0]; dres (+)= dz; dgamma, dbeta; dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M).
 int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, void* dx, void* dres,
