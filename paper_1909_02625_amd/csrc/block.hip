@@ -87,6 +87,11 @@ struct Layer {
     bool in1_grad = true;
     bool in0_acc = false;  // add to (true) or overwrite (false) the gradient buffer of in0
     bool in1_acc = false;
+    // add: this operand's gradient is not copied -- its only other consumer, a batch norm, adds the sum's
+    // gradient itself (dx_add_from of that layer), or the operand has no other consumer and its producer
+    // reads the sum's gradient directly (grad_alias of the block)
+    bool in0_skip = false, in1_skip = false;
+    int dx_add_from = -1;  // bn: layer whose output gradient is added to this layer's input gradient
     // conv: the next layer is a batch norm of this output, so the conv kernel also leaves the per-tile
     // column sums in the block's partial-sum buffer; bn: number of such tiles (0 = sum x itself)
     int sum_tiles = 0;
@@ -156,6 +161,7 @@ struct dsp_block {
 
     size_t ring_bytes = 0, ws_bytes = 0, param_bytes = 0;
     std::vector<void*> allocs;
+    std::vector<int> grad_alias;  // per tensor: the sum layer whose output gradient is also this tensor's (-1: its own buffer)
 
     int64_t version = 0, next_fwd = 0, next_bwd = 0;
     bool pending = false;
@@ -299,6 +305,43 @@ static int build_graph(dsp_block* b)
         }
     }
     if (d.needs_input_grad) DSP_REQUIRE(written[0], DSP_EINVAL, "block: the input never reaches a layer");
+
+    // The backward of a sum hands its gradient to both operands unchanged.  Two cases need no copy:
+    // the operand has no other consumer (its producer reads the sum's gradient in place), or its only
+    // other consumer is an earlier batch norm reading it as in0, which then forms
+    // (its own input gradient) + (the sum's gradient) in one pass instead of accumulating onto a copy.
+    b->grad_alias.assign(d.n_layers, -1);
+    {
+        std::vector<std::vector<std::pair<int, int>>> consumers(d.n_layers + 1);  // tensor t+1 -> (layer, operand)
+        for (int i = 0; i < d.n_layers; ++i) {
+            const Layer& L = b->layers[i];
+            if (L.d.op == DSP_OP_SOFTMAX_CE) continue;
+            consumers[L.d.in0 + 1].push_back({i, 0});
+            if ((L.d.op == DSP_OP_BN && L.d.in1 != -2) || L.d.op == DSP_OP_ADD) consumers[L.d.in1 + 1].push_back({i, 1});
+        }
+        for (int i = 0; i < d.n_layers; ++i) {
+            Layer& L = b->layers[i];
+            if (L.d.op != DSP_OP_ADD || L.d.in0 == L.d.in1) continue;
+            for (int o = 0; o < 2; ++o) {
+                const int t = o ? L.d.in1 : L.d.in0;
+                const bool has_grad = o ? L.in1_grad : L.in0_grad, acc = o ? L.in1_acc : L.in0_acc;
+                if (!has_grad || acc || t == b->out_idx) continue;
+                const auto& cs = consumers[t + 1];
+                if (cs.size() == 1 && t >= 0) {
+                    b->grad_alias[t] = i;
+                    (o ? L.in1_skip : L.in0_skip) = true;
+                } else if (cs.size() == 2) {
+                    const std::pair<int, int> other = cs[0].first == i ? cs[1] : cs[0];
+                    Layer& J = b->layers[other.first];
+                    if (J.d.op == DSP_OP_BN && other.second == 0 && other.first < i && J.in0_grad && J.in0_acc &&
+                        J.dx_add_from < 0) {
+                        J.dx_add_from = i;
+                        (o ? L.in1_skip : L.in0_skip) = true;
+                    }
+                }
+            }
+        }
+    }
 
     // parameter index maps
     b->perm.resize(b->nP);
@@ -553,7 +596,9 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
         if (L.d.op == DSP_OP_SOFTMAX_CE) continue;
         const Tensor& s = L.d.in0 < 0 ? b->input : b->T[L.d.in0];
         const void* src = L.d.in0 < 0 ? in : b->T[L.d.in0].act;
-        const void* dy = (i == b->out_idx) ? gout : b->T[i].grad;
+        int dyt = i;  // the buffer that holds the gradient of this layer's output
+        while (dyt != b->out_idx && b->grad_alias[dyt] >= 0) dyt = b->grad_alias[dyt];
+        const void* dy = (dyt == b->out_idx) ? gout : b->T[dyt].grad;
         switch (L.d.op) {
         case DSP_OP_CONV:
             // per-slice partial sums only; they are summed for all layers after the sweep
@@ -567,17 +612,23 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
             BnBuffers buf{b->bn_partial, L.mean, L.invstd, b->bn_coef};
             void* dres = L.in1_grad ? grad_of(L.d.in1) : nullptr;
             DSP_REQUIRE(L.in0_grad, DSP_EINVAL, "bn directly on the data input is not supported");
+            const void* dx_add = nullptr;
+            if (L.dx_add_from >= 0) {
+                int t = L.dx_add_from;
+                while (t != b->out_idx && b->grad_alias[t] >= 0) t = b->grad_alias[t];
+                dx_add = (t == b->out_idx) ? gout : b->T[t].grad;
+            }
             DSP_TRY(launch_bn_backward(b->dtype, dy, src, b->T[i].act, grad_of(L.d.in0), dres, L.in1_acc, L.in0_acc,
                                        b->x + L.p0, b->g + L.p0, b->g + L.p1, (int64_t)s.N * s.H * s.W, s.C,
-                                       L.d.relu != 0, buf, st));
+                                       L.d.relu != 0, buf, st, dx_add));
             break;
         }
         case DSP_OP_ADD: {
             // both operands in one launch (dy is read once); the same tensor on both sides would need in0 before
             // in1, the order in which the overwrite / accumulate flags were decided, so it takes two launches
             const int64_t n_el = (int64_t)s.N * s.H * s.W * s.C;
-            void* d0 = L.in0_grad ? grad_of(L.d.in0) : nullptr;
-            void* d1 = L.in1_grad ? grad_of(L.d.in1) : nullptr;
+            void* d0 = (L.in0_grad && !L.in0_skip) ? grad_of(L.d.in0) : nullptr;
+            void* d1 = (L.in1_grad && !L.in1_skip) ? grad_of(L.d.in1) : nullptr;
             if (d0 && d1 && d0 != d1) {
                 DSP_TRY(launch_grad_pass(b->dtype, dy, d0, L.in0_acc, d1, L.in1_acc, n_el, st));
             } else {

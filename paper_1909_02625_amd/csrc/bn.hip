@@ -270,10 +270,11 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_apply_kernel(BnApplyIo io0, B
     }
 }
 
-// dz = dy*[y>0];  dx (+)= c1*dz - c2*x + c0;  dres (+)= dz
+// dz = dy*[y>0];  dx = [dx_prev +] c1*dz - c2*x + c0;  dres (+)= dz.  dx_prev is dx itself (accumulate in place)
+// or another tensor's gradient that reaches the same input (the shortcut of a pre-activation unit).
 template <typename T, int VW, bool RELU, bool HAS_RES, bool RES_ACC, bool DX_ACC>
 __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(const T* __restrict__ dy, const T* __restrict__ x,
-                                                                const T* __restrict__ y, T* __restrict__ dx,
+                                                                const T* __restrict__ y, T* dx, const T* dx_prev,
                                                                 T* __restrict__ dres, const float* __restrict__ coef,
                                                                 int64_t nvec, int C, int cv)
 {
@@ -283,7 +284,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(const T* __restr
         VecIO<T, VW>::load(dy + i * VW, gv);
         VecIO<T, VW>::load(x + i * VW, xv);
         if (RELU) VecIO<T, VW>::load(y + i * VW, yv);
-        if (DX_ACC) VecIO<T, VW>::load(dx + i * VW, ov);
+        if (DX_ACC) VecIO<T, VW>::load(dx_prev + i * VW, ov);
         if (HAS_RES && RES_ACC) VecIO<T, VW>::load(dres + i * VW, rv);
 #pragma unroll
         for (int k = 0; k < VW; ++k) {
@@ -362,7 +363,8 @@ int bn_forward_t(const void* x, const void* res, void* y, const float* gamma, co
 
 template <typename T, int VW, bool RELU>
 int bn_backward_t(const void* dy, const void* x, const void* y, void* dx, void* dres, bool racc, bool xacc,
-                  const float* gamma, float* dgamma, float* dbeta, int64_t M, int C, const BnBuffers& buf, hipStream_t st)
+                  const float* gamma, float* dgamma, float* dbeta, int64_t M, int C, const BnBuffers& buf, hipStream_t st,
+                  const void* dx_prev)
 {
     const RowLayout L = make_layout(C, VW);
     int nblk;
@@ -387,7 +389,7 @@ int bn_backward_t(const void* dy, const void* x, const void* y, void* dx, void* 
                  tensor_bytes * (2 + (RELU ? 1 : 0) + 1 + (xacc ? 1 : 0) + (dres ? 1 + (racc ? 1 : 0) : 0)), 1);
 #define BN_BAPPLY(H, RA, XA)                                                                                   \
     DSP_LAUNCH(ps, (bn_bwd_apply_kernel<T, VW, RELU, H, RA, XA>), ag, dim3(kThreads), 0, st, (const T*)dy,    \
-               (const T*)x, (const T*)y, (T*)dx, (T*)dres, (const float*)buf.coef, nvec, C, L.cv)
+               (const T*)x, (const T*)y, (T*)dx, (const T*)dx_prev, (T*)dres, (const float*)buf.coef, nvec, C, L.cv)
     if (dres) {
         if (racc) { if (xacc) BN_BAPPLY(true, true, true); else BN_BAPPLY(true, true, false); }
         else      { if (xacc) BN_BAPPLY(true, false, true); else BN_BAPPLY(true, false, false); }
@@ -461,14 +463,16 @@ int launch_bn_forward(int dtype, const void* x, const void* res, void* y, const 
 
 int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, void* dx, void* dres,
                        bool dres_accumulate, bool dx_accumulate, const float* gamma, float* dgamma, float* dbeta,
-                       int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st)
+                       int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, const void* dx_add)
 {
     DSP_REQUIRE(M > 0 && C > 0, DSP_EINVAL, "bn: bad shape");
+    const void* dx_prev = dx_add ? dx_add : dx;
+    if (dx_add) dx_accumulate = true;
 #define BN_BWD(T, VW)                                                                                              \
     (relu ? bn_backward_t<T, VW, true>(dy, x, y, dx, dres, dres_accumulate, dx_accumulate, gamma, dgamma, dbeta, M, \
-                                       C, buf, st)                                                                 \
+                                       C, buf, st, dx_prev)                                                        \
           : bn_backward_t<T, VW, false>(dy, x, y, dx, dres, dres_accumulate, dx_accumulate, gamma, dgamma, dbeta,  \
-                                        M, C, buf, st))
+                                        M, C, buf, st, dx_prev))
     if (dtype == DSP_BF16) {
         if (C % 8 == 0) return BN_BWD(bf16_t, 8);
         return BN_BWD(bf16_t, 1);

@@ -192,9 +192,11 @@ int launch_add_forward_stats(int dtype, const void* a, const void* b, void* y, i
                              hipStream_t st, const AddStatsTwin* twin = nullptr);
 // Backward of the map above given dy and the saved x, y, mean, invstd:
 // dz = dy * [y > 0]; dres (+)= dz; dgamma, dbeta; dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M).
+// dx_add != nullptr: dx = dx_add + (the above) -- the gradient another consumer of the same input left in a
+// buffer of its own (then dx_accumulate is ignored).
 int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, void* dx, void* dres,
                        bool dres_accumulate, bool dx_accumulate, const float* gamma, float* dgamma, float* dbeta,
-                       int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st);
+                       int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, const void* dx_add = nullptr);
 
 // ---- small layers and the update (misc.hip) ---------------------------------------------------
 int launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* argmax, int N, int H, int W, int C, int k,
