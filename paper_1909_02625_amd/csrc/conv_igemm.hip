@@ -31,6 +31,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kThreads = 256;
 
@@ -91,6 +92,36 @@ __device__ inline int acc_row(int lane, int j)
 
 constexpr int cmax(int a, int b) { return a > b ? a : b; }
 
+// Four consecutive elements of T as one 8-byte (bf16) or 16-byte (fp32) register run.
+template <typename T>
+struct Run4;
+template <>
+struct Run4<bf16_t> {
+    typedef u32x2 V;
+    __device__ static inline V pack(float a, float b, float c, float d)
+    {
+        return V{(uint32_t)float_to_bf16(a).bits | ((uint32_t)float_to_bf16(b).bits << 16),
+                 (uint32_t)float_to_bf16(c).bits | ((uint32_t)float_to_bf16(d).bits << 16)};
+    }
+    __device__ static inline void unpack(V v, float (&f)[4])
+    {
+        const uint32_t lo = v.x, hi = v.y;
+        f[0] = __uint_as_float(lo << 16);
+        f[1] = __uint_as_float(lo & 0xffff0000u);
+        f[2] = __uint_as_float(hi << 16);
+        f[3] = __uint_as_float(hi & 0xffff0000u);
+    }
+};
+template <>
+struct Run4<float> {
+    typedef f32x4 V;
+    __device__ static inline V pack(float a, float b, float c, float d) { return V{a, b, c, d}; }
+    __device__ static inline void unpack(V v, float (&f)[4])
+    {
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+};
+
 // ---- tile configuration -----------------------------------------------------------------------
 template <typename T_, int MT_, int WGM_, int WGN_, int TM_, int TN_, int BKB_, int STAGES_>
 struct Tile {
@@ -117,11 +148,17 @@ struct Tile {
     static constexpr int LDS_BYTES = cmax(LOAD_BYTES, EPI_BYTES + STATS_BYTES);
     // waves per SIMD the register allocation aims for (the LDS footprint allows as many workgroups)
     static constexpr int MIN_WAVES = (sizeof(T) == 2 && BM == 128 && BN == 128 && BKB == 64) ? 3 : 1;
+    // forward / backward-data accumulate the transposed tile on the 32x32 MFMA (16 registers per lane = four
+    // runs of 4 consecutive output channels, staged with four vector stores instead of sixteen element stores)
+    static constexpr bool SWAP = MT == 32;
     static_assert(BKB % KSB == 0 && kThreads % CPR == 0 && (STAGES == 1 || STAGES == 2), "tile shape");
     static_assert(kThreads % BN == 0 && EPI_BYTES % 8 == 0, "column sums: whole row groups, aligned scratch");
 };
 
-template <typename TL>
+// SWAP = false: acc[i][j] holds rows of A against columns of B (register e of a lane = row acc_row(lane, e),
+// column lane % MT).  SWAP = true: the transposed tile (row = the B row acc_row(lane, e), column = the A row
+// lane % MT), so that a lane holds runs of 4 consecutive B rows for one A row.
+template <typename TL, bool SWAP = false>
 __device__ inline void mma_tile(const char* sA, const char* sB, int wave_m, int wave_n, int lane,
                                 typename Mma<typename TL::T, TL::MT>::Acc (&acc)[TL::TM][TL::TN])
 {
@@ -139,7 +176,12 @@ __device__ inline void mma_tile(const char* sA, const char* sB, int wave_m, int 
 #pragma unroll
         for (int i = 0; i < TL::TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TL::TN; ++j) Mma<typename TL::T, MT>::run(a[i], b[j], acc[i][j]);
+            for (int j = 0; j < TL::TN; ++j) {
+                if (SWAP)
+                    Mma<typename TL::T, MT>::run(b[j], a[i], acc[i][j]);
+                else
+                    Mma<typename TL::T, MT>::run(a[i], b[j], acc[i][j]);
+            }
     }
 }
 
@@ -379,16 +421,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
         int kt = 0;
         for (; kt + 1 < nk; kt += 2) {  // one loop body, one back edge: the accumulators stay where the MFMAs want them
             load_tiles(kt + 2, ra1, rb1);
-            mma_tile<TL>(smem, smem + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
+            mma_tile<TL, TL::SWAP>(smem, smem + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
             store_tiles(1, ra0, rb0);
             __syncthreads();
             load_tiles(kt + 3, ra0, rb0);
-            mma_tile<TL>(smem + TL::STAGE_BYTES, smem + TL::STAGE_BYTES + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
+            mma_tile<TL, TL::SWAP>(smem + TL::STAGE_BYTES, smem + TL::STAGE_BYTES + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
             store_tiles(0, ra1, rb1);
             __syncthreads();
         }
         if (kt < nk) {  // odd number of k tiles: the last one sits in stage 0
-            mma_tile<TL>(smem, smem + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
+            mma_tile<TL, TL::SWAP>(smem, smem + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
             __syncthreads();
         }
     } else {
@@ -398,37 +440,69 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
             store_tiles(0, ra0, rb0);
             __syncthreads();
             if (kt + 1 < nk) load_tiles(kt + 1, ra0, rb0);  // the next tile's gathers fly while this one is multiplied
-            mma_tile<TL>(smem, smem + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
+            mma_tile<TL, TL::SWAP>(smem, smem + TL::BM * TL::ROWB, wave_m, wave_n, lane, acc);
         }
         __syncthreads();
     }
 
     // ---- epilogue: (optionally add the old values,) stage the tile in LDS, store 16-byte runs ----
     constexpr int kAcc = Mma<T, TL::MT>::kAcc;
-    if (g.accum) {
+    if constexpr (TL::SWAP) {
+        // The accumulators hold the transposed tile: a lane has, for output row lane % MT of its block, runs of
+        // 4 consecutive output channels (registers 4q .. 4q+3), which go to LDS as one 8- or 16-byte store.
+        typedef typename Run4<T>::V RunV;
 #pragma unroll
         for (int i = 0; i < TL::TM; ++i)
 #pragma unroll
             for (int j = 0; j < TL::TN; ++j) {
-                const int col = n0 + (wave_n * TL::TN + j) * TL::MT + lane % TL::MT;
+                const int lrow = (wave_m * TL::TM + i) * TL::MT + lane % TL::MT;
+                const int m = m0 + lrow;
+#pragma unroll
+                for (int q = 0; q < kAcc / 4; ++q) {
+                    const int lcol = (wave_n * TL::TN + j) * TL::MT + acc_row<TL::MT>(lane, 4 * q);
+                    const int col = n0 + lcol;
+                    if (g.accum && m < g.M) {
+                        if (g.out_vec && col + 4 <= g.Co) {
+                            float o[4];
+                            Run4<T>::unpack(*(const RunV*)(out + (int64_t)m * g.Co + col), o);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += o[e];
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (col + e < g.Co) acc[i][j][4 * q + e] += to_float<T>(out[(int64_t)m * g.Co + col + e]);
+                        }
+                    }
+                    *(RunV*)(smem + lrow * TL::EPI_ROWB + lcol * (int)sizeof(T)) =
+                        Run4<T>::pack(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                }
+            }
+    } else {
+        if (g.accum) {
+#pragma unroll
+            for (int i = 0; i < TL::TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TL::TN; ++j) {
+                    const int col = n0 + (wave_n * TL::TN + j) * TL::MT + lane % TL::MT;
+#pragma unroll
+                    for (int e = 0; e < kAcc; ++e) {
+                        const int m = m0 + (wave_m * TL::TM + i) * TL::MT + acc_row<TL::MT>(lane, e);
+                        if (m < g.M && col < g.Co) acc[i][j][e] += to_float<T>(out[(int64_t)m * g.Co + col]);
+                    }
+                }
+        }
+#pragma unroll
+        for (int i = 0; i < TL::TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TL::TN; ++j) {
+                const int lcol = (wave_n * TL::TN + j) * TL::MT + lane % TL::MT;
 #pragma unroll
                 for (int e = 0; e < kAcc; ++e) {
-                    const int m = m0 + (wave_m * TL::TM + i) * TL::MT + acc_row<TL::MT>(lane, e);
-                    if (m < g.M && col < g.Co) acc[i][j][e] += to_float<T>(out[(int64_t)m * g.Co + col]);
+                    const int lrow = (wave_m * TL::TM + i) * TL::MT + acc_row<TL::MT>(lane, e);
+                    *(T*)(smem + lrow * TL::EPI_ROWB + lcol * (int)sizeof(T)) = from_float<T>(acc[i][j][e]);
                 }
             }
     }
-#pragma unroll
-    for (int i = 0; i < TL::TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TL::TN; ++j) {
-            const int lcol = (wave_n * TL::TN + j) * TL::MT + lane % TL::MT;
-#pragma unroll
-            for (int e = 0; e < kAcc; ++e) {
-                const int lrow = (wave_m * TL::TM + i) * TL::MT + acc_row<TL::MT>(lane, e);
-                *(T*)(smem + lrow * TL::EPI_ROWB + lcol * (int)sizeof(T)) = from_float<T>(acc[i][j][e]);
-            }
-        }
     __syncthreads();
     constexpr int OCPR = TL::BN / E;  // 16-byte runs per tile row
     for (int c = tid; c < TL::BM * OCPR; c += kThreads) {
@@ -905,7 +979,6 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
 // within every 256-byte line the 16-byte chunk index is XORed with 4 * (line % 4), which spreads the
 // four rows of a read over all banks.
 typedef short short4v __attribute__((ext_vector_type(4)));
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 // Byte offset of 16-byte chunk `chunk` of row `row` in an unpadded tile whose rows are `row_bytes` long.
 __device__ inline int swizzled_chunk(int row, int chunk, int row_bytes)
