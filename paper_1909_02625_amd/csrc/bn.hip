@@ -64,7 +64,7 @@ __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__
             out = add.out1;
         }
     }
-    __shared__ double red[kThreads][VW][2];
+    __shared__ double red[VW][kThreads][2];  // one 16-byte pair per thread and channel, neighbouring lanes side by side: no bank conflicts
     const int tid = threadIdx.x;
     const int cvi = blockIdx.y * L.cvb + tid % L.cvb;
     const int rlane = tid / L.cvb;
@@ -120,8 +120,8 @@ __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__
     // combine the row lanes of each channel vector: a fixed tree over the row lanes, all channels of the vector at once
 #pragma unroll
     for (int i = 0; i < VW; ++i) {
-        red[tid][i][0] = s0[i];
-        red[tid][i][1] = s1[i];
+        red[i][tid][0] = s0[i];
+        red[i][tid][1] = s1[i];
     }
     __syncthreads();
     int w = 1;
@@ -131,8 +131,8 @@ __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__
             const int other = tid + w * L.cvb;
 #pragma unroll
             for (int i = 0; i < VW; ++i) {
-                red[tid][i][0] += red[other][i][0];
-                red[tid][i][1] += red[other][i][1];
+                red[i][tid][0] += red[i][other][0];
+                red[i][tid][1] += red[i][other][1];
             }
         }
         __syncthreads();
@@ -141,8 +141,8 @@ __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__
 #pragma unroll
         for (int i = 0; i < VW; ++i) {
             double* dst = part + ((int64_t)blockIdx.x * C + c0 + i) * 2;
-            dst[0] = red[tid][i][0];
-            dst[1] = red[tid][i][1];
+            dst[0] = red[i][tid][0];
+            dst[1] = red[i][tid][1];
         }
     }
 }
