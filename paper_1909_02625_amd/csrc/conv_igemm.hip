@@ -100,8 +100,7 @@ struct Run4<bf16_t> {
     typedef u32x2 V;
     __device__ static inline V pack(float a, float b, float c, float d)
     {
-        return V{(uint32_t)float_to_bf16(a).bits | ((uint32_t)float_to_bf16(b).bits << 16),
-                 (uint32_t)float_to_bf16(c).bits | ((uint32_t)float_to_bf16(d).bits << 16)};
+        return V{pack_bf16x2(a, b), pack_bf16x2(c, d)};
     }
     __device__ static inline void unpack(V v, float (&f)[4])
     {
