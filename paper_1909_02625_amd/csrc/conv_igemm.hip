@@ -199,11 +199,22 @@ __device__ inline void zero_acc(typename Mma<typename TL::T, TL::MT>::Acc (&acc)
 // The gathered tensor `in` is N x Hi x Wi x Ci; output rows m = (n, ho, wo) over N x Ho x Wo.
 // Tap (r, s) of output pixel (ho, wo) reads position t = o*ostride - pad + tap; with idil = 2
 // (backward-data of a stride-2 conv) only even t exist and they map to source pixel t/2.
+// n / d for n < 2^31 with precomputed mul = floor(2^32 * (2^sh - d) / d) + 1, sh = ceil(log2 d).
+__device__ inline uint32_t fast_div(uint32_t n, uint32_t mul, uint32_t sh) { return (__umulhi(n, mul) + n) >> sh; }
+inline void fast_div_constants(uint32_t d, uint32_t* mul, uint32_t* sh)
+{
+    uint32_t s = 0;
+    while ((1ull << s) < d) ++s;
+    *sh = s;
+    *mul = (uint32_t)(((1ull << 32) * ((1ull << s) - d)) / d + 1);
+}
+
 struct GatherGeom {
     int N, Hi, Wi, Ci, Ho, Wo, Co, R, S, pad_h, pad_w, ostride, idil;
     int M, Kdim;
     int ci_shift;  // log2(Ci) if Ci is a power of two, else -1
     int s_inv;     // 65536 / S + 1: tap / S == (tap * s_inv) >> 16 for tap < 4096
+    uint32_t wo_mul, wo_sh, ho_mul, ho_sh;  // m / Wo and (m / Wo) / Ho by multiplication (fast_div)
     int accum;     // add to `out` instead of overwriting it
     int out_vec;  // `out` rows can be written as whole 16-byte runs
     // if set: per row tile, the column sums {sum y, sum y^2} of the values as stored, [row tile][Co][2];
@@ -282,14 +293,17 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
         a_hi[i] = 0;
         a_aux[i] = masked ? 0u : 0x80008000u;  // nothing valid
         if (row < TL::BM && m < g.M) {
-            const int wo = m % g.Wo, t = m / g.Wo, ho = t % g.Ho, n = t / g.Ho;
+            const int t = (int)fast_div((uint32_t)m, g.wo_mul, g.wo_sh), wo = m - t * g.Wo;
+            const int n = (int)fast_div((uint32_t)t, g.ho_mul, g.ho_sh), ho = t - n * g.Ho;
             const int th0 = ho * g.ostride - g.pad_h, tw0 = wo * g.ostride - g.pad_w;
             const uint32_t img = (uint32_t)n * g.Hi * g.Wi * g.Ci * SZ;
             if (masked) {
+                // taps s in [s_lo, s_hi) of a filter row fall inside the image; the same bits for every valid row r
+                const int s_lo = tw0 < 0 ? -tw0 : 0, s_hi = g.Wi - tw0 < g.S ? g.Wi - tw0 : g.S;
+                const uint64_t cols = s_hi > s_lo ? ((1ull << s_hi) - 1) & ~((1ull << s_lo) - 1) : 0ull;
                 uint64_t mask = 0;
                 for (int r = 0; r < g.R; ++r)
-                    for (int s = 0; s < g.S; ++s)
-                        mask |= (uint64_t)(th0 + r >= 0 && th0 + r < g.Hi && tw0 + s >= 0 && tw0 + s < g.Wi) << (r * g.S + s);
+                    if (th0 + r >= 0 && th0 + r < g.Hi) mask |= cols << (r * g.S);
                 a_off[i] = img + (uint32_t)((th0 * g.Wi + tw0) * g.Ci) * SZ;
                 a_aux[i] = (uint32_t)mask;
                 a_hi[i] = (uint32_t)(mask >> 32);
@@ -593,7 +607,8 @@ __global__ __launch_bounds__(kThreads) void conv3x3_direct_f32_kernel(const floa
     auto gather = [&](f32x4 (&xin)[TAPS][CI16], int grp) {
         const int m = grp * 16 + px;
         const bool live = grp < groups && m < g.M;
-        const int wo = m % g.Wo, tq = m / g.Wo, ho = tq % g.Ho, n = tq / g.Ho;
+        const int tq = (int)fast_div((uint32_t)m, g.wo_mul, g.wo_sh), wo = m - tq * g.Wo;
+        const int n = (int)fast_div((uint32_t)tq, g.ho_mul, g.ho_sh), ho = tq - n * g.Ho;
         const int th0 = ho * g.ostride - g.pad_h, tw0 = wo * g.ostride - g.pad_w;
         const uint32_t base = (uint32_t)(((n * g.Hi + th0) * g.Wi + tw0) * g.Ci + 4 * kq) * 4u;
 #pragma unroll
@@ -695,16 +710,6 @@ struct WgradGeom {
     int M, Kdim, m_per_split;
     uint32_t wo_mul, wo_sh, ho_mul, ho_sh;  // n / Wo and n / Ho by multiplication (fast_div)
 };
-
-// n / d for n < 2^31 with precomputed mul = floor(2^32 * (2^sh - d) / d) + 1, sh = ceil(log2 d).
-__device__ inline uint32_t fast_div(uint32_t n, uint32_t mul, uint32_t sh) { return (__umulhi(n, mul) + n) >> sh; }
-inline void fast_div_constants(uint32_t d, uint32_t* mul, uint32_t* sh)
-{
-    uint32_t s = 0;
-    while ((1ull << s) < d) ++s;
-    *sh = s;
-    *mul = (uint32_t)(((1ull << 32) * ((1ull << s) - d)) / d + 1);
-}
 
 template <typename T>
 __device__ inline void transpose_micro(const u32x4 (&in)[16 / sizeof(T)], u32x4 (&out)[16 / sizeof(T)]);
@@ -1716,6 +1721,8 @@ static GatherGeom make_geom(int N, int Hi, int Wi, int Ci, int Ho, int Wo, int C
     for (int b = 0; b < 31; ++b)
         if ((1 << b) == Ci) g.ci_shift = b;
     g.s_inv = 65536 / S + 1;
+    fast_div_constants((uint32_t)Wo, &g.wo_mul, &g.wo_sh);
+    fast_div_constants((uint32_t)Ho, &g.ho_mul, &g.ho_sh);
     return g;
 }
 
