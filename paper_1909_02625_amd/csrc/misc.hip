@@ -25,14 +25,15 @@ __global__ __launch_bounds__(kThreads) void maxpool_fwd_kernel(const T* __restri
                                                                uint8_t* __restrict__ arg, int N, int H, int W, int C,
                                                                int Ho, int Wo, int k, int stride, int pad)
 {
-    const int cv = C / VW;
-    const int64_t total = (int64_t)N * Ho * Wo * cv;
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
-        const int c = (int)(i % cv) * VW;
-        int64_t t = i / cv;
-        const int wo = (int)(t % Wo);
-        t /= Wo;
-        const int ho = (int)(t % Ho), n = (int)(t / Ho);
+    // element counts are below 2^31 (checked by the launcher): 32-bit index arithmetic
+    const uint32_t cv = (uint32_t)(C / VW);
+    const uint32_t total = (uint32_t)N * Ho * Wo * cv;
+    for (uint32_t i = blockIdx.x * kThreads + threadIdx.x; i < total; i += gridDim.x * kThreads) {
+        uint32_t t = i / cv;
+        const int c = (int)(i - t * cv) * VW;
+        const uint32_t t2 = t / (uint32_t)Wo;
+        const int wo = (int)(t - t2 * Wo);
+        const int n = (int)(t2 / (uint32_t)Ho), ho = (int)(t2 - (uint32_t)n * Ho);
         float best[VW];
         int a[VW];
 #pragma unroll
@@ -67,27 +68,30 @@ __global__ __launch_bounds__(kThreads) void maxpool_bwd_kernel(const T* __restri
                                                                T* __restrict__ dx, int N, int H, int W, int C, int Ho,
                                                                int Wo, int k, int stride, int pad)
 {
-    const int cv = C / VW;
-    const int64_t total = (int64_t)N * H * W * cv;
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
-        const int c = (int)(i % cv) * VW;
-        int64_t t = i / cv;
-        const int wi = (int)(t % W);
-        t /= W;
-        const int hi = (int)(t % H), n = (int)(t / H);
+    // element counts are below 2^31 (checked by the launcher): 32-bit index arithmetic
+    const uint32_t cv = (uint32_t)(C / VW);
+    const uint32_t total = (uint32_t)N * H * W * cv;
+    for (uint32_t i = blockIdx.x * kThreads + threadIdx.x; i < total; i += gridDim.x * kThreads) {
+        uint32_t t = i / cv;
+        const int c = (int)(i - t * cv) * VW;
+        const uint32_t t2 = t / (uint32_t)W;
+        const int wi = (int)(t - t2 * W);
+        const int n = (int)(t2 / (uint32_t)H), hi = (int)(t2 - (uint32_t)n * H);
         float s[VW];
 #pragma unroll
         for (int v = 0; v < VW; ++v) s[v] = 0.f;
-        for (int r = 0; r < k; ++r) {
-            const int hn = hi + pad - r;
-            if (hn < 0 || hn % stride) continue;
-            const int ho = hn / stride;
-            if (ho >= Ho) continue;
-            for (int q = 0; q < k; ++q) {
-                const int wn = wi + pad - q;
-                if (wn < 0 || wn % stride) continue;
-                const int wo = wn / stride;
-                if (wo >= Wo) continue;
+        // windows (ho, wo) that contain this pixel: tap r = hi + pad - ho*stride in [0, k), same for columns;
+        // walked with r and q ascending (ho and wo descending), the order the sums have always been taken in
+        const int hn = hi + pad, wn = wi + pad;
+        int ho_hi = (int)((uint32_t)hn / (uint32_t)stride), wo_hi = (int)((uint32_t)wn / (uint32_t)stride);
+        const int ho_lo = hn - k + 1 > 0 ? (int)((uint32_t)(hn - k + stride) / (uint32_t)stride) : 0;
+        const int wo_lo = wn - k + 1 > 0 ? (int)((uint32_t)(wn - k + stride) / (uint32_t)stride) : 0;
+        if (ho_hi > Ho - 1) ho_hi = Ho - 1;
+        if (wo_hi > Wo - 1) wo_hi = Wo - 1;
+        for (int ho = ho_hi; ho >= ho_lo; --ho) {
+            const int r = hn - ho * stride;
+            for (int wo = wo_hi; wo >= wo_lo; --wo) {
+                const int q = wn - wo * stride;
                 const int64_t o = (((int64_t)n * Ho + ho) * Wo + wo) * C + c;
                 float gv[VW];
                 VecIO<T, VW>::load(dy + o, gv);
@@ -324,6 +328,7 @@ int launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* argmax, i
                            int stride, int pad, hipStream_t st)
 {
     DSP_REQUIRE(k * k < 255, DSP_EINVAL, "maxpool: window too large");
+    DSP_REQUIRE((int64_t)N * H * W * C < (1ll << 31), DSP_EINVAL, "maxpool: tensors of 2^31 elements or more are not supported");
     const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
     const int vw = dtype == DSP_BF16 ? 8 : 4;
     const bool vec = C % vw == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)y % 16) == 0;
@@ -342,6 +347,7 @@ int launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* argmax, i
 int launch_maxpool_backward(int dtype, const void* dy, const uint8_t* argmax, void* dx, bool accumulate, int N,
                             int H, int W, int C, int k, int stride, int pad, hipStream_t st)
 {
+    DSP_REQUIRE((int64_t)N * H * W * C < (1ll << 31), DSP_EINVAL, "maxpool: tensors of 2^31 elements or more are not supported");
     const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
     const int vw = dtype == DSP_BF16 ? 8 : 4;
     const bool vec = C % vw == 0 && ((uintptr_t)dy % 16) == 0 && ((uintptr_t)dx % 16) == 0;
