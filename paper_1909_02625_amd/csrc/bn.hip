@@ -254,8 +254,12 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_apply_kernel(BnApplyIo io0, B
     const T* __restrict__ res = (const T*)io.res;
     T* __restrict__ y = (T*)io.y;
     const float* __restrict__ coef = io.coef;
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * kThreads) {
-        const int c0 = (int)(i % cv) * VW;
+    // channel vector of element i = i mod cv, carried along the grid-stride loop instead of divided out each trip
+    const uint32_t step = gridDim.x * kThreads, step_c = step % (uint32_t)cv;
+    uint32_t cvi = (blockIdx.x * kThreads + threadIdx.x) % (uint32_t)cv;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec;
+         i += step, cvi = cvi + step_c >= (uint32_t)cv ? cvi + step_c - (uint32_t)cv : cvi + step_c) {
+        const int c0 = (int)cvi * VW;
         float xv[VW], rv[VW], ov[VW];
         VecIO<T, VW>::load(x + i * VW, xv);
         if (HAS_RES) VecIO<T, VW>::load(res + i * VW, rv);
@@ -278,8 +282,12 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(const T* __restr
                                                                 T* __restrict__ dres, const float* __restrict__ coef,
                                                                 int64_t nvec, int C, int cv)
 {
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * kThreads) {
-        const int c0 = (int)(i % cv) * VW;
+    // channel vector of element i = i mod cv, carried along the grid-stride loop instead of divided out each trip
+    const uint32_t step = gridDim.x * kThreads, step_c = step % (uint32_t)cv;
+    uint32_t cvi = (blockIdx.x * kThreads + threadIdx.x) % (uint32_t)cv;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < nvec;
+         i += step, cvi = cvi + step_c >= (uint32_t)cv ? cvi + step_c - (uint32_t)cv : cvi + step_c) {
+        const int c0 = (int)cvi * VW;
         float gv[VW], xv[VW], yv[VW], ov[VW], rv[VW];
         VecIO<T, VW>::load(dy + i * VW, gv);
         VecIO<T, VW>::load(x + i * VW, xv);
