@@ -147,21 +147,34 @@ __global__ void gap_bwd_kernel(const float* __restrict__ dy, T* __restrict__ dx,
 }
 
 // ---- linear head (fp32) ----------------------------------------------------------------------------
-// z[n][j] = sum_c x[n][c] w[j][c] + bias[j]: one wave per output, lanes stride over c, fixed shuffle tree.
+// z[n][j] = sum_c x[n][c] w[j][c] + bias[j]: lanes stride over c, fixed shuffle tree per output.
+constexpr int kLinearJ = 8;
 __global__ __launch_bounds__(kThreads) void linear_fwd_kernel(const float* __restrict__ x, const float* __restrict__ w,
                                                               const float* __restrict__ bias, float* __restrict__ z, int N,
                                                               int Cin, int Cout)
 {
-    const int lane = threadIdx.x & 63;
-    const int64_t o = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
-    if (o >= (int64_t)N * Cout) return;
-    const int n = (int)(o / Cout), j = (int)(o % Cout);
-    float s = 0.f;
-#pragma unroll 4
-    for (int c = lane; c < Cin; c += 64) s += x[n * Cin + c] * w[j * Cin + c];
+    // a wave forms kLinearJ outputs of one sample (x[n] is read once for all of them), the four waves of a
+    // workgroup take four samples against the same rows of w; each output is summed as before: lane-strided
+    // partial sums over c, then a shuffle tree
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int jblocks = (Cout + kLinearJ - 1) / kLinearJ;
+    const int j0 = (int)(blockIdx.x % jblocks) * kLinearJ, n = (int)(blockIdx.x / jblocks) * (kThreads / 64) + wave;
+    if (n >= N) return;
+    float s[kLinearJ];
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off, 64);
-    if (lane == 0) z[o] = s + bias[j];
+    for (int q = 0; q < kLinearJ; ++q) s[q] = 0.f;
+    for (int c = lane; c < Cin; c += 64) {
+        const float xv = x[n * Cin + c];
+#pragma unroll
+        for (int q = 0; q < kLinearJ; ++q)
+            if (j0 + q < Cout) s[q] += xv * w[(j0 + q) * Cin + c];
+    }
+#pragma unroll
+    for (int q = 0; q < kLinearJ; ++q) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s[q] += __shfl_down(s[q], off, 64);
+        if (lane == 0 && j0 + q < Cout) z[n * Cout + j0 + q] = s[q] + bias[j0 + q];
+    }
 }
 
 // dx[n][c] = sum_j dz[n][j] w[j][c]
@@ -407,7 +420,7 @@ int launch_linear_forward(const float* x, const float* w, const float* bias, flo
                           hipStream_t st)
 {
     ProfScope ps("linear_fwd", 4.0 * ((double)N * Cin + (double)Cout * Cin + (double)N * Cout), 1);
-    DSP_LAUNCH(ps, linear_fwd_kernel, dim3(ceil_div((int64_t)N * Cout, kThreads / 64)), dim3(kThreads), 0, st, x, w,
+    DSP_LAUNCH(ps, linear_fwd_kernel, dim3(ceil_div(Cout, kLinearJ) * ceil_div(N, kThreads / 64)), dim3(kThreads), 0, st, x, w,
                        bias, z, N, Cin, Cout);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
