@@ -343,6 +343,21 @@ int dsp_conv_backward_weight(int32_t dtype, const void* d_x, const void* d_dy, f
 int dsp_conv_workspace_bytes(int32_t N, int32_t H, int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s,
                              int32_t stride, int32_t pad, size_t* bytes);
 
+/*
+ * dsp_conv_backward_weight for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * kernels and bits as dsp_conv_backward_weight, but the split-reduction partials live in a fixed buffer
+ * inside the loaded library (dsp_conv_backward_weight_static_bytes() bytes, 16 MiB, held on every GPU the
+ * library runs on until the process ends); the call allocates nothing.  A layer whose partials
+ * (dsp_conv_workspace_bytes) exceed that size is refused with DSP_EINVAL before anything is launched.
+ * All calls on one GPU share the buffer: calls that overlap in time on one GPU (two streams, two threads)
+ * race and must be ordered by the caller.  Nothing in the buffer has to start at zero, so it is never cleared.
+ */
+int dsp_conv_backward_weight_static(int32_t dtype, const void* d_x, const void* d_dy, float* d_dw, int32_t N, int32_t H,
+                                    int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride,
+                                    int32_t pad, void* stream);
+int dsp_conv_backward_weight_static_bytes(size_t* bytes);
+
 /* ---- in-situ kernel timing (measurement support) ------------------------------------------------ */
 
 /*

@@ -24,6 +24,7 @@ __all__ = [
     "dsp_block_enable_forward_lane", "dsp_block_step", "dsp_pipeline_set_twin_launches",
     "dsp_pipeline_sync", "dsp_pipeline_losses", "dsp_pipeline_ticks",
     "dsp_conv_forward", "dsp_conv_backward_data", "dsp_conv_backward_weight", "dsp_conv_workspace_bytes",
+    "dsp_conv_backward_weight_static", "dsp_conv_backward_weight_static_bytes",
     "dsp_profile_start", "dsp_profile_stop", "dsp_profile_get",
     "dsp_strerror", "dsp_last_error", "EXPORTED_SYMBOLS",
 ]
@@ -118,6 +119,8 @@ _SIGNATURES = {
     "dsp_conv_backward_data": [_i32, _vp, _vp, _vp] + [_i32] * 10 + [_vp],
     "dsp_conv_backward_weight": [_i32, _vp, _vp, _vp] + [_i32] * 9 + [_vp, _sz, _vp],
     "dsp_conv_workspace_bytes": [_i32] * 9 + [C.POINTER(_sz)],
+    "dsp_conv_backward_weight_static": [_i32, _vp, _vp, _vp] + [_i32] * 9 + [_vp],
+    "dsp_conv_backward_weight_static_bytes": [C.POINTER(_sz)],
     "dsp_profile_start": [_i32],
     "dsp_profile_stop": [_pi32],
     "dsp_profile_get": [_i32, C.c_char_p, _sz, _pi64, C.POINTER(C.c_double), C.POINTER(C.c_double), _pi32],
@@ -412,6 +415,17 @@ def dsp_conv_backward_weight(dtype, d_x, d_dy, d_dw, N, H, W, cin, cout, r, s, s
 def dsp_conv_workspace_bytes(N, H, W, cin, cout, r, s, stride, pad):
     out = C.c_size_t()
     check(lib().dsp_conv_workspace_bytes(N, H, W, cin, cout, r, s, stride, pad, C.byref(out)), "dsp_conv_workspace_bytes")
+    return out.value
+
+
+def dsp_conv_backward_weight_static(dtype, d_x, d_dy, d_dw, N, H, W, cin, cout, r, s, stride, pad, stream=None):
+    check(lib().dsp_conv_backward_weight_static(dtype, _ptr(d_x), _ptr(d_dy), _ptr(d_dw), N, H, W, cin, cout, r, s, stride, pad,
+                                                _stream(stream)), "dsp_conv_backward_weight_static")
+
+
+def dsp_conv_backward_weight_static_bytes():
+    out = C.c_size_t()
+    check(lib().dsp_conv_backward_weight_static_bytes(C.byref(out)), "dsp_conv_backward_weight_static_bytes")
     return out.value
 
 

@@ -1871,3 +1871,62 @@ int wgrad_reduce_set_launch(const WgradReduceSet* s, hipStream_t st)
 }
 
 }  // namespace dsp
+
+// ---- backward-weight for callers that cannot allocate ---------------------------------------------
+// The split-reduction partials of dsp_conv_backward_weight normally live in a caller-provided workspace.
+// This variant keeps them in a fixed array inside the loaded code object instead, so the call needs no
+// allocation at all.  In host code the array's name is only a handle for the symbol: its device address is
+// asked for once per device (each GPU holds its own copy) and that pointer is what the kernels get.
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+constexpr int kMaxScratchDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+void* g_scratch_ptr[kMaxScratchDevices] = {};
+std::atomic<bool> g_scratch_known[kMaxScratchDevices] = {};
+
+// Device address of the current device's copy of `scratch` (looked up on the first call per device).
+int static_scratch(void** out)
+{
+    int dev = -1;
+    DSP_HIP(hipGetDevice(&dev));
+    DSP_REQUIRE(dev >= 0 && dev < kMaxScratchDevices, DSP_EINVAL, "static scratch: device index %d out of range", dev);
+    if (!g_scratch_known[dev].load(std::memory_order_acquire)) {
+        void* p = nullptr;
+        DSP_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        DSP_REQUIRE(p != nullptr, DSP_EHIP, "static scratch: the symbol has no device address");
+        g_scratch_ptr[dev] = p;  // every thread that gets here stores the same address
+        g_scratch_known[dev].store(true, std::memory_order_release);
+    }
+    *out = g_scratch_ptr[dev];
+    return DSP_OK;
+}
+}  // namespace
+
+extern "C" int dsp_conv_backward_weight_static_bytes(size_t* bytes)
+{
+    DSP_REQUIRE(bytes, DSP_EINVAL, "dsp_conv_backward_weight_static_bytes: null argument");
+    *bytes = kStaticScratchBytes;
+    return DSP_OK;
+}
+
+extern "C" int dsp_conv_backward_weight_static(int32_t dtype, const void* d_x, const void* d_dy, float* d_dw, int32_t N,
+                                               int32_t H, int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s,
+                                               int32_t stride, int32_t pad, void* stream)
+{
+    using namespace dsp;
+    DSP_REQUIRE(d_x && d_dy && d_dw && (dtype == DSP_FP32 || dtype == DSP_BF16), DSP_EINVAL,
+                "dsp_conv_backward_weight_static: bad argument");
+    DSP_REQUIRE(N > 0 && H > 0 && W > 0 && cin > 0 && cout > 0 && r > 0 && s > 0 && stride > 0 && pad >= 0, DSP_EINVAL,
+                "dsp_conv_backward_weight_static: bad shape");
+    const ConvShape c = make_conv_shape(N, H, W, cin, cout, r, s, stride, pad);
+    DSP_REQUIRE(c.Ho > 0 && c.Wo > 0, DSP_EINVAL, "dsp_conv_backward_weight_static: empty output");
+    const size_t need = conv_backward_weight_workspace(c);
+    DSP_REQUIRE(need <= kStaticScratchBytes, DSP_EINVAL,
+                "dsp_conv_backward_weight_static: this layer needs %zu bytes of partial sums, the built-in buffer holds %zu; "
+                "use dsp_conv_backward_weight with a workspace",
+                need, kStaticScratchBytes);
+    void* ws = nullptr;
+    DSP_TRY(static_scratch(&ws));
+    // every partial the reduction reads is written by this call's first kernel: nothing has to start at zero
+    return launch_conv_backward_weight(dtype, c, d_x, d_dy, d_dw, ws, kStaticScratchBytes, (hipStream_t)stream);
+}
