@@ -3,7 +3,9 @@
 
 A "step" is one pipeline tick: every block of DSP(p; m) runs forward(a), recompute+backward(b) and
 its momentum-SGD update on its own HIP stream, on synthetic inputs that are already resident in
-HBM.  Prints ONE JSON line (the fields are described in the README).
+HBM.  The default workload is the largest configuration that fits one GPU: the ResNet-18-shaped
+ImageNet-sized net in bf16, K = 4 blocks, batch 256.  Prints ONE JSON line (the fields are described
+in the README).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet20|resnet56|resnet18|resnet50_conv4x|vgg19|resnet164|resnet1001|tiny2]
 """
@@ -26,13 +28,13 @@ PEAK_HBM_GBS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="resnet20")
+    ap.add_argument("--workload", default="resnet18")
     ap.add_argument("--dtype", default=None, choices=[None, "fp32", "bf16"])
     ap.add_argument("--batch", type=int, default=None, help="override the mini-batch size (not the headline number)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the CPU-oracle baseline leg (0 = skip)")
-    ap.add_argument("--profile-steps", type=int, default=10)
+    ap.add_argument("--profile-steps", type=int, default=5)
     ap.add_argument("--straggler", type=int, nargs=2, metavar=("BLOCK", "MICROSECONDS"), default=None,
                     help="straggler emulation: block BLOCK's stream idles this long before its work in every tick "
                          "(not the headline number)")
@@ -87,6 +89,7 @@ class Workload:
             self.batches.append((to_dev(x, self.dtype), None if y is None else torch.from_numpy(y).cuda(), g))
         self.pl = None
         self.tick = 0
+        self.fill = max(sum(cfg["p"][:k]) + cfg["m"][k] for k in range(cfg["K"]))
         if not self.external:
             self.pl = D.dsp_pipeline_init(self.blocks, cfg["p"], cfg["m"], cfg["lr"], cfg["beta"], cfg["wd"], max_ticks)
         else:
@@ -122,37 +125,75 @@ class Workload:
 
 
 def cpu_baseline(name, batch, seconds):
-    """The CPU oracle (as is) on the first ticks of the same workload: images/s over the steady ticks."""
+    """The CPU oracle (as is) on a bounded sample of the same workload: images/s of one steady-state tick.
+
+    Small workloads: the oracle's own pipeline on the first ticks at the full mini-batch, timed over the steady
+    ticks.  Workloads whose tick would take the oracle minutes (ImageNet-sized): every block once through
+    forward(a) + recompute/backward(b) + update -- exactly the work of one steady tick -- on its real layer
+    shapes at a reduced mini-batch that fits the time budget; the sample string says which."""
     import numpy as np
 
     from oracle import dsp_oracle as O
-    from workloads import get_config, make_batch, make_params
+    from workloads import count_macs, get_config, make_batch, make_params
     from workloads.gen import make_error_gradient
 
     cfg = get_config(name, batch=batch)
+    N = cfg["input"][0]
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    shapes = [tuple(cfg["input"])]
+    from workloads.configs import block_output_shape
+    for layers in cfg["blocks"]:
+        shapes.append(tuple(block_output_shape(layers, shapes[-1])))
+    gmac_img = sum(count_macs(layers, shapes[k]) for k, layers in enumerate(cfg["blocks"])) * 4 / 1e9
+    est_tick_s = gmac_img * N / (2.0 * cores)  # ~2 GMAC/s per core for the plain loops
+    if est_tick_s <= seconds / 6:
+        rng = np.random.default_rng(cfg["seed"])
+        params = [make_params(layers, rng) for layers in cfg["blocks"]]
+        orc = O.build_cnn_oracle(cfg, params)
+        fill = max(sum(cfg["p"][:k]) + cfg["m"][k] for k in range(cfg["K"]))
+        ext = cfg.get("classes") is None
+        steady, t_steady, t_start, tick = 0, 0.0, time.perf_counter(), 0
+        while True:
+            x, y = make_batch(rng, cfg["input"], cfg["classes"])
+            t0 = time.perf_counter()
+            orc.tick(x, y, top_gradient=(lambda a, out: make_error_gradient(rng, out.shape, 0.1).astype(np.float64)) if ext else None)
+            dt = time.perf_counter() - t0
+            if tick >= fill:
+                steady += 1
+                t_steady += dt
+            tick += 1
+            if steady >= 1 and time.perf_counter() - t_start > seconds:
+                break
+            if steady >= 8:
+                break
+        return {"value": N * steady / t_steady, "unit": "images/s", "cores": cores, "kind": "oracle",
+                "sample": "%d steady ticks (after %d fill ticks) of %s at batch %d, fp64, plain C loops + OpenMP over the batch"
+                          % (steady, fill, name, N)}
+    # one steady tick's work, block by block, at a reduced mini-batch
+    nb = N
+    while nb > 4 and gmac_img * nb / (2.0 * cores) > seconds / 2:
+        nb //= 2
+    cfg = get_config(name, batch=nb)
     rng = np.random.default_rng(cfg["seed"])
     params = [make_params(layers, rng) for layers in cfg["blocks"]]
     orc = O.build_cnn_oracle(cfg, params)
-    fill = max(sum(cfg["p"][:k]) + cfg["m"][k] for k in range(cfg["K"]))
+    shapes = [(nb,) + s[1:] for s in shapes]
     ext = cfg.get("classes") is None
-    steady, t_steady, t_start, tick = 0, 0.0, time.perf_counter(), 0
-    while True:
-        x, y = make_batch(rng, cfg["input"], cfg["classes"])
+    t_tick = 0.0
+    for k, blk in enumerate(orc.blocks):
+        h = rng.standard_normal(shapes[k])
+        g = rng.standard_normal(shapes[k + 1]) * 0.1
         t0 = time.perf_counter()
-        orc.tick(x, y, top_gradient=(lambda a, out: make_error_gradient(rng, out.shape, 0.1).astype(np.float64)) if ext else None)
-        dt = time.perf_counter() - t0
-        if tick >= fill:
-            steady += 1
-            t_steady += dt
-        tick += 1
-        if steady >= 1 and time.perf_counter() - t_start > seconds:
-            break
-        if steady >= 8:
-            break
-    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return {"value": cfg["input"][0] * steady / t_steady, "unit": "images/s", "cores": cores, "kind": "oracle",
-            "sample": "%d steady ticks (after %d fill ticks) of %s at batch %d, fp64, plain C loops + OpenMP over the batch"
-                      % (steady, fill, name, cfg["input"][0])}
+        out, _ = blk.forward(h)                                   # forward(a)
+        if k == cfg["K"] - 1 and not ext:
+            _, g = orc.loss.value_and_grad(out, rng.integers(0, cfg["classes"], nb))
+        _, gx = blk.vjp(h, g)                                      # recompute(b) + backward(b)
+        blk.set_param_list(orc.opt[k].step(blk.param_list(), gx))  # update
+        t_tick += time.perf_counter() - t0
+    return {"value": nb / t_tick, "unit": "images/s", "cores": cores, "kind": "oracle",
+            "sample": "one steady tick's work of %s (each of the %d blocks once: forward + recompute/backward + update on its "
+                      "real layer shapes) at batch %d instead of %d, %.1f s, fp64, plain C loops + OpenMP over the batch"
+                      % (name, cfg["K"], nb, N, t_tick)}
 
 
 def hbm_traffic(workload, dtype_name, kernel):
@@ -195,13 +236,16 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     calibration_copy(torch)
-    total_ticks = a.warmup + a.steps * (1 + len(a.random_stragglers or [])) + a.profile_steps + 4
+    total_ticks = a.warmup + 16 + a.steps * (1 + len(a.random_stragglers or [])) + a.profile_steps + 4
     w = Workload(a.workload, a.dtype, a.batch, total_ticks, a.schedule, a.spare)
     if a.straggler is not None:
         if w.pl is None:
             sys.exit("bench.py: --straggler needs a pipeline of several blocks")
         w.D.dsp_pipeline_set_delay(w.pl, a.straggler[0], a.straggler[1])
-    for _ in range(a.warmup):
+    # untimed: at least the ticks that fill the pipeline plus two steady ones (the first steady tick of a block
+    # allocates its second buffer set), whatever --warmup says
+    warm = max(a.warmup, w.fill + 2)
+    for _ in range(warm):
         w.step()
     w.sync()
     t0 = time.perf_counter()
@@ -215,11 +259,18 @@ def main():
     # per-kernel time of the same ticks, from event pairs recorded around every launch on its own stream
     table = []
     if a.profile_steps > 0:
-        D.dsp_profile_start(200000)
+        # the same ticks once more with the K chains on ONE stream, so that no two kernels overlap and every
+        # launch's duration (event pair around it) is that kernel's own; the markers dsp_profile_start / _stop
+        # launch let a rocprofv3 kernel trace of this command be cut to exactly these launches
+        if w.pl is not None:
+            D.dsp_pipeline_set_single_stream(w.pl, True)
+        D.dsp_profile_start(400000)
         for _ in range(a.profile_steps):
             w.step()
         w.sync()
         table = D.dsp_profile_stop()
+        if w.pl is not None:
+            D.dsp_pipeline_set_single_stream(w.pl, False)
     roof, kernels, conv_util = None, [], None
     if table:
         tot_ms = sum(k["ms"] for k in table)
@@ -282,8 +333,8 @@ def main():
 
     cfg = w.cfg
     out = {
-        "metric": "images/sec per DSP block step (fwd+recompute+bwd+update)",
-        "value": round(value, 1), "unit": "images/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "metric": "images/sec per DSP block step (fwd+recompute+bwd+update); conv MFMA util %",
+        "value": round(value, 1), "unit": "images/s", "n_gpus": 1, "steps": a.steps, "warmup": warm,
         "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if w.dtype_name == "fp32" else "bf16", "data": "synthetic",
         "config": {"workload": "%s: DSP(%s;%s), K=%d blocks on %d HIP streams, batch %d x %dx%dx%d, one pipeline tick per step"

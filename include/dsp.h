@@ -299,6 +299,13 @@ int dsp_pipeline_gradient_difference(dsp_pipeline* pl, int64_t* batch_id, double
  *    and replayed with one launch each.
  */
 int dsp_pipeline_set_launch_threads(dsp_pipeline* pl, int32_t enable);
+/*
+ *  - single stream (default off): the K chains of a tick are issued one after the other on ONE stream by the
+ *    caller's thread, so no two kernels overlap: the mode in which a per-kernel duration is that kernel's own
+ *    (measurement support; blocks within a tick are independent, so any issue order gives the same bits).
+ *    Synchronises the pipeline's streams when called; may be changed between steps; not with forward streams.
+ */
+int dsp_pipeline_set_single_stream(dsp_pipeline* pl, int32_t enable);
 int dsp_pipeline_set_graph_replay(dsp_pipeline* pl, int32_t enable);
 /*
  *  - forward streams (default off): a block with m_k > 0 runs the forward pass of the current
@@ -344,6 +351,60 @@ int dsp_conv_workspace_bytes(int32_t N, int32_t H, int32_t W, int32_t cin, int32
                              int32_t stride, int32_t pad, size_t* bytes);
 
 /*
+ * The other layers of a block (the paper names networks, not layers; these are the textbook definitions
+ * the block function f_k of Eq. (1) and its chain rule, Eq. (2), are assembled from), each as the kernels
+ * the block engine launches for it, on caller-owned device tensors.  Feature maps are NHWC in `dtype`
+ * seen as x[M][C], M = N*H*W rows; everything behind a global average pool is float.
+ *
+ * Batch norm in training mode over the M rows, per channel: mean, biased variance, y = [relu](gamma *
+ * (x - mean) / sqrt(var + eps) + beta [+ res]); d_mean / d_invstd (C floats each) receive the statistics
+ * the backward needs.  Backward: dz = dy * [y > 0] (relu) ; dres (+)= dz; dgamma = sum dz * xhat;
+ * dbeta = sum dz; dx (+)= gamma * invstd * (dz - dbeta / M - xhat * dgamma / M).  d_res / d_dres may be NULL.
+ * d_workspace: dsp_bn_workspace_bytes(C) bytes, 16-byte aligned, contents unspecified before and after.
+ */
+int dsp_bn_workspace_bytes(int32_t C, size_t* bytes);
+int dsp_bn_forward(int32_t dtype, const void* d_x, const void* d_res, void* d_y, const float* d_gamma, const float* d_beta,
+                   float eps, int64_t M, int32_t C, int32_t relu, float* d_mean, float* d_invstd, void* d_workspace,
+                   size_t workspace_bytes, void* stream);
+int dsp_bn_backward(int32_t dtype, const void* d_dy, const void* d_x, const void* d_y, void* d_dx, void* d_dres,
+                    int32_t dres_accumulate, int32_t dx_accumulate, const float* d_gamma, const float* d_mean,
+                    const float* d_invstd, float* d_dgamma, float* d_dbeta, int64_t M, int32_t C, int32_t relu,
+                    void* d_workspace, size_t workspace_bytes, void* stream);
+/* k x k max pool (padding = -inf, the first maximum in row-major window order wins); d_argmax keeps one
+ * byte per output element (window position r*k+s); backward: dx (+)= the dy of every window that chose the pixel. */
+int dsp_maxpool_forward(int32_t dtype, const void* d_x, void* d_y, uint8_t* d_argmax, int32_t N, int32_t H, int32_t W,
+                        int32_t C, int32_t k, int32_t stride, int32_t pad, void* stream);
+int dsp_maxpool_backward(int32_t dtype, const void* d_dy, const uint8_t* d_argmax, void* d_dx, int32_t accumulate, int32_t N,
+                         int32_t H, int32_t W, int32_t C, int32_t k, int32_t stride, int32_t pad, void* stream);
+/* y = a + b over n elements; backward: da (+)= dy and, unless d_db is NULL, db (+)= dy. */
+int dsp_add_forward(int32_t dtype, const void* d_a, const void* d_b, void* d_y, int64_t n, void* stream);
+int dsp_add_backward(int32_t dtype, const void* d_dy, void* d_da, int32_t da_accumulate, void* d_db, int32_t db_accumulate,
+                     int64_t n, void* stream);
+/* y[n][c] = mean over the HW positions of x[n][.][c] (float); backward: dx (+)= dy / HW. */
+int dsp_gap_forward(int32_t dtype, const void* d_x, float* d_y, int32_t N, int32_t HW, int32_t C, void* stream);
+int dsp_gap_backward(int32_t dtype, const float* d_dy, void* d_dx, int32_t accumulate, int32_t N, int32_t HW, int32_t C,
+                     void* stream);
+/* z = x W^T + bias with W[cout][cin]; backward: dx = dz W (skipped if d_dx is NULL), dW = dz^T x, dbias = sum_n dz. */
+int dsp_linear_forward(const float* d_x, const float* d_w, const float* d_bias, float* d_z, int32_t N, int32_t cin,
+                       int32_t cout, void* stream);
+int dsp_linear_backward(const float* d_x, const float* d_w, const float* d_dz, float* d_dx, float* d_dw, float* d_dbias,
+                        int32_t N, int32_t cin, int32_t cout, void* stream);
+/* L(h_K, l) of Eq. (1): *d_loss = mean_n -log softmax(z_n)[label_n], d_dz = dL/dz; d_row_loss: N floats of scratch. */
+int dsp_softmax_ce(const float* d_z, const int32_t* d_labels, float* d_loss, float* d_dz, float* d_row_loss, int32_t N,
+                   int32_t C, void* stream);
+
+/*
+ * Test support: copies what layer `layer` of the block left in the buffers the backward sweep reads (the
+ * recompute of the latest dsp_block_recompute_backward / dsp_block_step, or the latest forward when m_k = 0)
+ * to the host after a device synchronisation: the layer's output in the block's storage type (NHWC; float
+ * behind a pool), `bytes` = its exact size; for a max-pool layer dsp_block_get_pool_argmax copies the chosen
+ * window positions (one byte per output element).  These are the values the ReLU masks and pooling
+ * decisions of the backward sweep were taken on.
+ */
+int dsp_block_get_activation(dsp_block* b, int32_t layer, void* h_dst, size_t bytes);
+int dsp_block_get_pool_argmax(dsp_block* b, int32_t layer, uint8_t* h_dst, size_t bytes);
+
+/*
  * dsp_conv_backward_weight for callers that cannot allocate device memory or hand over a workspace:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
  * kernels and bits as dsp_conv_backward_weight, but the split-reduction partials live in a fixed buffer
@@ -370,6 +431,9 @@ int dsp_conv_backward_weight_static_bytes(size_t* bytes);
  * convolution as defined, padding taps and skipped strided taps not counted), unit_kind 1 = bytes
  * that have to cross HBM once (each operand read once, each result written once).
  * dsp_profile_get returns entry i of that table.  Process-wide, not thread-safe.
+ * dsp_profile_start and dsp_profile_stop each synchronise the device and launch one empty marker kernel
+ * (dsp_profile_window_begin / dsp_profile_window_end), so that an external kernel trace of the process can be
+ * cut to exactly the launches the table covers.
  */
 int dsp_profile_start(int32_t max_launches);
 int dsp_profile_stop(int32_t* n_kernels);

@@ -211,6 +211,12 @@ def round_bf16(a):
     return np.where(np.isfinite(f), out, f.astype(np.float64)).reshape(np.shape(a))
 
 
+def round_fp32(a):
+    """Nearest IEEE single (ties to even), returned as fp64."""
+    with np.errstate(over="ignore"):  # beyond the single range: infinity, as the format prescribes
+        return np.asarray(a, dtype=np.float64).astype(np.float32).astype(np.float64)
+
+
 class SoftmaxCE:
     """L(h_K, l): mean over the mini-batch of -log softmax(h_K)[l]; returns (loss, dL/dh_K)."""
 
@@ -245,14 +251,12 @@ class CNNBlock:
         # pooled head stay unrounded).  A ReLU mask is an integer decision taken on a stored
         # value, so a comparison with a bf16 implementation is only meaningful if both sides
         # take it in the same precision.
-        assert storage in (None, "bf16")
-        self._rnd = round_bf16 if storage == "bf16" else (lambda a: a)
-        # Diagnostics for comparisons with finite-precision implementations: a ReLU input z whose
-        # magnitude is below knife_tau times the magnitude of the terms it was summed from may
-        # legitimately fall on either branch there.  last_knife lists (count, elements) per ReLU
-        # layer of the latest vjp(); it does not influence any result.
-        self.knife_tau = 0.0
-        self.last_knife = []
+        # storage = "fp32": the same roundings to single precision (what an fp32 implementation keeps in memory).
+        assert storage in (None, "bf16", "fp32")
+        self._rnd = {None: (lambda a: a), "bf16": round_bf16, "fp32": round_fp32}[storage]
+        # Filled by backward() when it is handed the branch decisions of another implementation: per layer
+        # (layer index, decisions that differ from this block's own, largest |margin| / magnitude among them).
+        self.last_decision_report = []
 
     # -- parameters as one flat list of arrays (what the optimiser sees)
     def param_list(self):
@@ -282,17 +286,11 @@ class CNNBlock:
                 aux.append(None)
             elif op == "bn":
                 z, mean, invstd = bn_forward(x, prm["gamma"], prm["beta"], self.eps)
-                cshape = (1, -1, 1, 1)
-                mag = (np.abs(prm["gamma"] * invstd).reshape(cshape) * (np.abs(x) + np.abs(mean).reshape(cshape))
-                       + np.abs(prm["beta"]).reshape(cshape)) if (L["relu"] and self.knife_tau > 0) else 0.0
                 if L["res"] is not None:
-                    mag = mag + np.abs(src(L["res"]))
                     z = z + src(L["res"])
-                knife = (int((np.abs(z) < self.knife_tau * (mag + 1e-300)).sum()), z.size) if (
-                    L["relu"] and self.knife_tau > 0) else None
                 y = rnd(np.maximum(z, 0.0) if L["relu"] else z)
                 T.append(y)
-                aux.append((mean, invstd, y, knife))
+                aux.append((mean, invstd, y))
             elif op == "add":  # element-wise sum of two feature maps (the shortcut of a pre-activation unit)
                 T.append(rnd(x + src(L["res"])))
                 aux.append(None)
@@ -310,14 +308,26 @@ class CNNBlock:
                 raise ValueError(op)
         return T[-1], (h, T, aux)
 
-    def backward(self, cache, g_out, params=None):
-        """Chain rule through the cached forward: returns (G_{h_k} or None, G_{x_k} as a flat list)."""
+    def backward(self, cache, g_out, params=None, decisions=None):
+        """Chain rule through the cached forward: returns (G_{h_k} or None, G_{x_k} as a flat list).
+
+        ``decisions`` (optional): {layer index: array}.  The backward pass of a rectifier and of a max pool
+        rests on an integer decision taken on floating-point values (is the output positive; which window
+        element is the largest).  Another implementation of the same definition may decide a near-tie the
+        other way, after which the two gradients differ although both are correct.  To compare gradients, the
+        decisions of that implementation can be handed in: for a bn layer with relu a boolean array
+        (output > 0), for a max pool an integer array of source pixels (h * W + w per output element, -1 for
+        none); the chain rule is then applied with THOSE decisions and ``last_decision_report`` lists, per
+        such layer, how many differ from this block's own and the largest margin by which a differing
+        decision contradicts this block's values, relative to the magnitude of the terms the value was
+        formed from (the caller judges whether that is rounding noise).  Nothing else changes."""
         P = self.x if params is None else params
         h, T, aux = cache
         dT = [None] * len(T)
         dT[-1] = _f64(g_out)
         dh = [None]
         grads = [dict() for _ in self.layers]
+        report = []
 
         def src(i):
             return h if i == -1 else T[i]
@@ -342,9 +352,25 @@ class CNNBlock:
                 if not (L["in"] == -1 and self.first_block):
                     add(L["in"], conv2d_backward_data(g, rnd(prm["w"]), x.shape, L["stride"], L["pad"]))
             elif op == "bn":
-                mean, invstd, y, _ = aux[i]
+                mean, invstd, y = aux[i]
                 if L["relu"]:
-                    g = g * (y > 0.0)  # ReLU'(0) = 0, decided on the stored output
+                    own = y > 0.0  # ReLU'(0) = 0, decided on the stored output
+                    mask = own
+                    if decisions is not None and i in decisions:
+                        mask = np.asarray(decisions[i], dtype=bool).reshape(y.shape)
+                        diff = mask != own
+                        worst = 0.0
+                        if diff.any():
+                            cs = (1, -1, 1, 1)
+                            scale = (prm["gamma"] * invstd).reshape(cs)
+                            z = scale * (x - mean.reshape(cs)) + prm["beta"].reshape(cs)
+                            mag = np.abs(scale) * (np.abs(x) + np.abs(mean).reshape(cs)) + np.abs(prm["beta"]).reshape(cs)
+                            if L["res"] is not None:
+                                z = z + src(L["res"])
+                                mag = mag + np.abs(src(L["res"]))
+                            worst = float((np.abs(z[diff]) / (mag[diff] + 1e-300)).max())
+                        report.append((i, int(diff.sum()), worst))
+                    g = g * mask
                 if L["res"] is not None:
                     add(L["res"], g)
                 dx, dg, db = bn_backward(g, x, prm["gamma"], mean, invstd)
@@ -354,7 +380,19 @@ class CNNBlock:
                 add(L["res"], g)
                 add(L["in"], g)
             elif op == "maxpool":
-                add(L["in"], maxpool_backward(g, aux[i], x.shape))
+                arg = aux[i]
+                if decisions is not None and i in decisions:
+                    theirs = np.ascontiguousarray(np.asarray(decisions[i]).reshape(arg.shape), dtype=np.int32)
+                    diff = theirs != arg
+                    worst = 0.0
+                    if diff.any():
+                        n_, c_ = np.nonzero(diff)[:2]
+                        flat = x.reshape(x.shape[0], x.shape[1], -1)
+                        best, chosen = flat[n_, c_, arg[diff]], flat[n_, c_, theirs[diff]]
+                        worst = float((np.abs(best - chosen) / (np.abs(best) + 1e-300)).max())
+                    report.append((i, int(diff.sum()), worst))
+                    arg = theirs
+                add(L["in"], maxpool_backward(g, arg, x.shape))
             elif op == "gap":
                 hw = x.shape[2] * x.shape[3]
                 add(L["in"], np.broadcast_to(g[:, :, None, None] / hw, x.shape).copy())
@@ -362,14 +400,14 @@ class CNNBlock:
                 grads[i]["w"] = g.T @ x
                 grads[i]["c"] = g.sum(axis=0)
                 add(L["in"], g @ prm["w"])
+        self.last_decision_report = report
         flat = [grads[i][k] for i, d in enumerate(self.x) for k in d]
         return (None if self.first_block else dh[0]), flat
 
-    def vjp(self, h, g_out):
+    def vjp(self, h, g_out, decisions=None):
         """Eq. (5), lines 1-2: recompute f_k on the stored input with the *current* parameters, then chain rule."""
         _, cache = self.forward(h)
-        self.last_knife = [a[3] for a in cache[2] if isinstance(a, tuple) and len(a) == 4 and a[3] is not None]
-        return self.backward(cache, g_out)
+        return self.backward(cache, g_out, decisions=decisions)
 
 
 # --------------------------------------------------------------------------- Eq. (3)

@@ -20,11 +20,14 @@ __all__ = [
     "dsp_block_input_shape", "dsp_block_memory", "dsp_block_get_params", "dsp_block_set_params",
     "dsp_block_get_momentum", "dsp_block_set_momentum", "dsp_block_get_grads",
     "dsp_pipeline_init", "dsp_pipeline_destroy", "dsp_pipeline_step", "dsp_pipeline_set_delay",
-    "dsp_pipeline_set_graph_replay", "dsp_pipeline_set_launch_threads", "dsp_pipeline_set_forward_streams",
+    "dsp_pipeline_set_graph_replay", "dsp_pipeline_set_launch_threads", "dsp_pipeline_set_single_stream", "dsp_pipeline_set_forward_streams",
     "dsp_block_enable_forward_lane", "dsp_block_step", "dsp_pipeline_set_twin_launches",
     "dsp_pipeline_sync", "dsp_pipeline_losses", "dsp_pipeline_ticks",
     "dsp_conv_forward", "dsp_conv_backward_data", "dsp_conv_backward_weight", "dsp_conv_workspace_bytes",
     "dsp_conv_backward_weight_static", "dsp_conv_backward_weight_static_bytes",
+    "dsp_bn_workspace_bytes", "dsp_bn_forward", "dsp_bn_backward", "dsp_maxpool_forward", "dsp_maxpool_backward",
+    "dsp_add_forward", "dsp_add_backward", "dsp_gap_forward", "dsp_gap_backward", "dsp_linear_forward",
+    "dsp_linear_backward", "dsp_softmax_ce", "dsp_block_get_activation", "dsp_block_get_pool_argmax",
     "dsp_profile_start", "dsp_profile_stop", "dsp_profile_get",
     "dsp_strerror", "dsp_last_error", "EXPORTED_SYMBOLS",
 ]
@@ -108,6 +111,7 @@ _SIGNATURES = {
     "dsp_pipeline_set_delay": [_vp, _i32, _i32],
     "dsp_pipeline_set_graph_replay": [_vp, _i32],
     "dsp_pipeline_set_launch_threads": [_vp, _i32],
+    "dsp_pipeline_set_single_stream": [_vp, _i32],
     "dsp_pipeline_set_forward_streams": [_vp, _i32],
     "dsp_block_enable_forward_lane": [_vp],
     "dsp_pipeline_set_twin_launches": [_vp, _i32],
@@ -120,6 +124,20 @@ _SIGNATURES = {
     "dsp_conv_backward_weight": [_i32, _vp, _vp, _vp] + [_i32] * 9 + [_vp, _sz, _vp],
     "dsp_conv_workspace_bytes": [_i32] * 9 + [C.POINTER(_sz)],
     "dsp_conv_backward_weight_static": [_i32, _vp, _vp, _vp] + [_i32] * 9 + [_vp],
+    "dsp_bn_workspace_bytes": [_i32, C.POINTER(_sz)],
+    "dsp_bn_forward": [_i32, _vp, _vp, _vp, _vp, _vp, _f, _i64, _i32, _i32, _vp, _vp, _vp, _sz, _vp],
+    "dsp_bn_backward": [_i32, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _vp, _sz, _vp],
+    "dsp_maxpool_forward": [_i32, _vp, _vp, _vp] + [_i32] * 7 + [_vp],
+    "dsp_maxpool_backward": [_i32, _vp, _vp, _vp] + [_i32] * 8 + [_vp],
+    "dsp_add_forward": [_i32, _vp, _vp, _vp, _i64, _vp],
+    "dsp_add_backward": [_i32, _vp, _vp, _i32, _vp, _i32, _i64, _vp],
+    "dsp_gap_forward": [_i32, _vp, _vp, _i32, _i32, _i32, _vp],
+    "dsp_gap_backward": [_i32, _vp, _vp, _i32, _i32, _i32, _i32, _vp],
+    "dsp_linear_forward": [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp],
+    "dsp_linear_backward": [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp],
+    "dsp_softmax_ce": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp],
+    "dsp_block_get_activation": [_vp, _i32, _vp, _sz],
+    "dsp_block_get_pool_argmax": [_vp, _i32, _vp, _sz],
     "dsp_conv_backward_weight_static_bytes": [C.POINTER(_sz)],
     "dsp_profile_start": [_i32],
     "dsp_profile_stop": [_pi32],
@@ -364,6 +382,10 @@ def dsp_pipeline_set_launch_threads(pl, enable):
     check(lib().dsp_pipeline_set_launch_threads(pl, int(bool(enable))), "dsp_pipeline_set_launch_threads")
 
 
+def dsp_pipeline_set_single_stream(pl, enable):
+    check(lib().dsp_pipeline_set_single_stream(pl, int(bool(enable))), "dsp_pipeline_set_single_stream")
+
+
 def dsp_pipeline_set_forward_streams(pl, enable):
     check(lib().dsp_pipeline_set_forward_streams(pl, int(bool(enable))), "dsp_pipeline_set_forward_streams")
 
@@ -427,6 +449,82 @@ def dsp_conv_backward_weight_static_bytes():
     out = C.c_size_t()
     check(lib().dsp_conv_backward_weight_static_bytes(C.byref(out)), "dsp_conv_backward_weight_static_bytes")
     return out.value
+
+
+def dsp_bn_workspace_bytes(C_):
+    out = C.c_size_t()
+    check(lib().dsp_bn_workspace_bytes(C_, C.byref(out)), "dsp_bn_workspace_bytes")
+    return out.value
+
+
+def dsp_bn_forward(dtype, d_x, d_res, d_y, d_gamma, d_beta, eps, M, C_, relu, d_mean, d_invstd, d_workspace, workspace_bytes,
+                   stream=None):
+    check(lib().dsp_bn_forward(dtype, _ptr(d_x), _ptr(d_res), _ptr(d_y), _ptr(d_gamma), _ptr(d_beta), eps, M, C_, int(relu),
+                               _ptr(d_mean), _ptr(d_invstd), _ptr(d_workspace), workspace_bytes, _stream(stream)),
+          "dsp_bn_forward")
+
+
+def dsp_bn_backward(dtype, d_dy, d_x, d_y, d_dx, d_dres, dres_accumulate, dx_accumulate, d_gamma, d_mean, d_invstd, d_dgamma,
+                    d_dbeta, M, C_, relu, d_workspace, workspace_bytes, stream=None):
+    check(lib().dsp_bn_backward(dtype, _ptr(d_dy), _ptr(d_x), _ptr(d_y), _ptr(d_dx), _ptr(d_dres), int(dres_accumulate),
+                                int(dx_accumulate), _ptr(d_gamma), _ptr(d_mean), _ptr(d_invstd), _ptr(d_dgamma),
+                                _ptr(d_dbeta), M, C_, int(relu), _ptr(d_workspace), workspace_bytes, _stream(stream)),
+          "dsp_bn_backward")
+
+
+def dsp_maxpool_forward(dtype, d_x, d_y, d_argmax, N, H, W, C_, k, stride, pad, stream=None):
+    check(lib().dsp_maxpool_forward(dtype, _ptr(d_x), _ptr(d_y), _ptr(d_argmax), N, H, W, C_, k, stride, pad, _stream(stream)),
+          "dsp_maxpool_forward")
+
+
+def dsp_maxpool_backward(dtype, d_dy, d_argmax, d_dx, accumulate, N, H, W, C_, k, stride, pad, stream=None):
+    check(lib().dsp_maxpool_backward(dtype, _ptr(d_dy), _ptr(d_argmax), _ptr(d_dx), int(accumulate), N, H, W, C_, k, stride,
+                                     pad, _stream(stream)), "dsp_maxpool_backward")
+
+
+def dsp_add_forward(dtype, d_a, d_b, d_y, n, stream=None):
+    check(lib().dsp_add_forward(dtype, _ptr(d_a), _ptr(d_b), _ptr(d_y), n, _stream(stream)), "dsp_add_forward")
+
+
+def dsp_add_backward(dtype, d_dy, d_da, da_accumulate, d_db, db_accumulate, n, stream=None):
+    check(lib().dsp_add_backward(dtype, _ptr(d_dy), _ptr(d_da), int(da_accumulate), _ptr(d_db), int(db_accumulate), n,
+                                 _stream(stream)), "dsp_add_backward")
+
+
+def dsp_gap_forward(dtype, d_x, d_y, N, HW, C_, stream=None):
+    check(lib().dsp_gap_forward(dtype, _ptr(d_x), _ptr(d_y), N, HW, C_, _stream(stream)), "dsp_gap_forward")
+
+
+def dsp_gap_backward(dtype, d_dy, d_dx, accumulate, N, HW, C_, stream=None):
+    check(lib().dsp_gap_backward(dtype, _ptr(d_dy), _ptr(d_dx), int(accumulate), N, HW, C_, _stream(stream)), "dsp_gap_backward")
+
+
+def dsp_linear_forward(d_x, d_w, d_bias, d_z, N, cin, cout, stream=None):
+    check(lib().dsp_linear_forward(_ptr(d_x), _ptr(d_w), _ptr(d_bias), _ptr(d_z), N, cin, cout, _stream(stream)),
+          "dsp_linear_forward")
+
+
+def dsp_linear_backward(d_x, d_w, d_dz, d_dx, d_dw, d_dbias, N, cin, cout, stream=None):
+    check(lib().dsp_linear_backward(_ptr(d_x), _ptr(d_w), _ptr(d_dz), _ptr(d_dx), _ptr(d_dw), _ptr(d_dbias), N, cin, cout,
+                                    _stream(stream)), "dsp_linear_backward")
+
+
+def dsp_softmax_ce(d_z, d_labels, d_loss, d_dz, d_row_loss, N, C_, stream=None):
+    check(lib().dsp_softmax_ce(_ptr(d_z), _ptr(d_labels), _ptr(d_loss), _ptr(d_dz), _ptr(d_row_loss), N, C_, _stream(stream)),
+          "dsp_softmax_ce")
+
+
+def dsp_block_get_activation(b, layer, nbytes):
+    """Raw bytes (numpy uint8) of the output layer ``layer`` left in the buffers the backward sweep reads."""
+    out = np.empty(nbytes, np.uint8)
+    check(lib().dsp_block_get_activation(b, layer, out.ctypes.data, nbytes), "dsp_block_get_activation")
+    return out
+
+
+def dsp_block_get_pool_argmax(b, layer, nbytes):
+    out = np.empty(nbytes, np.uint8)
+    check(lib().dsp_block_get_pool_argmax(b, layer, out.ctypes.data, nbytes), "dsp_block_get_pool_argmax")
+    return out
 
 
 def dsp_profile_start(max_launches):

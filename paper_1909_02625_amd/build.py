@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdsp_hip.so")
-SOURCES = ["conv_igemm.hip", "bn.hip", "misc.hip", "block.hip", "pipeline.hip"]
+SOURCES = ["conv_igemm.hip", "bn.hip", "misc.hip", "block.hip", "pipeline.hip", "layers_capi.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

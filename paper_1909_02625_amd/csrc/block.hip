@@ -132,8 +132,9 @@ struct dsp_block {
 
     size_t nP = 0;
     float *x = nullptr, *v = nullptr, *g = nullptr;
-    uint8_t* decay = nullptr;
-    int32_t* tmap = nullptr;
+    int32_t* tmap = nullptr;        // index table of the filter copies that are no plain transposition (padded stem filters)
+    UpdateTask* upd_tasks = nullptr;  // how the update kernel walks the flat arrays (device copy)
+    int upd_n_tasks = 0, upd_blocks = 0;
     void* wf16 = nullptr;  // bf16 copy of x in the same layout (bf16 blocks only)
     void* wt = nullptr;    // backward-data filter copies [cin][R-1-r][S-1-s][cout] in the storage type
     size_t wt_elems = 0;
@@ -343,36 +344,59 @@ static int build_graph(dsp_block* b)
         }
     }
 
-    // parameter index maps
+    // parameter index maps and the update kernel's task list
     b->perm.resize(b->nP);
     std::vector<int32_t> tmap(b->nP, -1);
-    std::vector<uint8_t> decay(b->nP, 0);
+    std::vector<UpdateTask> tasks;
+    auto flat_task = [&](size_t p0, size_t n, bool decay) {
+        if (n == 0) return;
+        if (!tasks.empty() && tasks.back().kind == 0 && tasks.back().decay == (decay ? 1 : 0) &&
+            (size_t)tasks.back().p0 + tasks.back().n == p0) {
+            tasks.back().n += (uint32_t)n;
+            return;
+        }
+        UpdateTask t{};
+        t.kind = 0; t.decay = decay ? 1 : 0; t.p0 = (uint32_t)p0; t.n = (uint32_t)n;
+        tasks.push_back(t);
+    };
     for (int i = 0; i < d.n_layers; ++i) {
         const Layer& L = b->layers[i];
         if (L.d.op == DSP_OP_CONV) {
             const int Co = L.d.cout, Ci = L.d.cin, R = L.d.r, S = L.d.s;
+            const size_t n = (size_t)Co * R * S * Ci;
             for (int co = 0; co < Co; ++co)
                 for (int r = 0; r < R; ++r)
                     for (int s = 0; s < S; ++s)
                         for (int ci = 0; ci < Ci; ++ci) {
                             const size_t lib = L.p0 + (((size_t)co * R + r) * S + s) * Ci + ci;
                             b->perm[lib] = (int32_t)(L.p0 + (((size_t)co * Ci + ci) * R + r) * S + s);
-                            decay[lib] = 1;
                             if (L.cin_pad)
                                 tmap[lib] = (int32_t)(L.wt_off + (((size_t)co * R + r) * S + s) * L.cin_pad + ci);
-                            else if (L.in0_grad)
-                                tmap[lib] = (int32_t)(L.wt_off + (((size_t)ci * R + (R - 1 - r)) * S + (S - 1 - s)) * Co + co);
                         }
+            if (L.cin_pad) {
+                UpdateTask t{};
+                t.kind = 2; t.decay = 1; t.p0 = (uint32_t)L.p0; t.n = (uint32_t)n;
+                tasks.push_back(t);
+            } else if (L.in0_grad) {
+                UpdateTask t{};
+                t.kind = 1; t.decay = 1; t.p0 = (uint32_t)L.p0; t.n = (uint32_t)n; t.wt_off = (uint32_t)L.wt_off;
+                t.Co = Co; t.Ci = Ci; t.R = R; t.S = S; t.J = R * S * Ci;
+                tasks.push_back(t);
+            } else {
+                flat_task(L.p0, n, true);
+            }
         } else if (L.d.op == DSP_OP_BN) {
             for (size_t j = 0; j < 2 * (size_t)L.d.cin; ++j) b->perm[L.p0 + j] = (int32_t)(L.p0 + j);
+            flat_task(L.p0, 2 * (size_t)L.d.cin, false);
         } else if (L.d.op == DSP_OP_LINEAR) {
             const size_t nw = (size_t)L.d.cin * L.d.cout;
-            for (size_t j = 0; j < nw + L.d.cout; ++j) {
-                b->perm[L.p0 + j] = (int32_t)(L.p0 + j);
-                if (j < nw) decay[L.p0 + j] = 1;
-            }
+            for (size_t j = 0; j < nw + L.d.cout; ++j) b->perm[L.p0 + j] = (int32_t)(L.p0 + j);
+            flat_task(L.p0, nw, true);
+            flat_task(L.p0 + nw, (size_t)L.d.cout, false);
         }
     }
+    DSP_TRY(update_plan_finish(tasks, b->dtype, &b->upd_blocks));
+    b->upd_n_tasks = (int)tasks.size();
     DSP_REQUIRE(b->nP < (1ull << 31), DSP_EINVAL, "block: too many parameters");
 
     // device buffers
@@ -380,13 +404,14 @@ static int build_graph(dsp_block* b)
     DSP_TRY(dev_alloc(b, (void**)&b->x, b->nP * 4, &b->param_bytes));
     DSP_TRY(dev_alloc(b, (void**)&b->v, b->nP * 4, &b->param_bytes));
     DSP_TRY(dev_alloc(b, (void**)&b->g, b->nP * 4, &b->param_bytes));
-    DSP_TRY(dev_alloc(b, (void**)&b->decay, b->nP, &b->param_bytes));
+    DSP_TRY(dev_alloc(b, (void**)&b->upd_tasks, tasks.size() * sizeof(UpdateTask), &b->param_bytes));
+    if (!tasks.empty())
+        DSP_HIP(hipMemcpy(b->upd_tasks, tasks.data(), tasks.size() * sizeof(UpdateTask), hipMemcpyHostToDevice));
     DSP_TRY(dev_alloc(b, (void**)&b->tmap, b->nP * 4, &b->param_bytes));
     DSP_TRY(dev_alloc(b, &b->wt, b->wt_elems * esz, &b->param_bytes));
     DSP_HIP(hipMemset(b->wt, 0, b->wt_elems * esz ? b->wt_elems * esz : 16));  // the zero channels of padded filters stay zero
     if (b->dtype == DSP_BF16) DSP_TRY(dev_alloc(b, &b->wf16, b->nP * 2, &b->param_bytes));
     if (b->nP) {
-        DSP_HIP(hipMemcpy(b->decay, decay.data(), b->nP, hipMemcpyHostToDevice));
         DSP_HIP(hipMemcpy(b->tmap, tmap.data(), b->nP * 4, hipMemcpyHostToDevice));
         DSP_HIP(hipMemset(b->v, 0, b->nP * 4));
         DSP_HIP(hipMemset(b->g, 0, b->nP * 4));
@@ -669,7 +694,7 @@ int block_load_params_device(dsp_block* b, const float* d_src, hipStream_t st)
 {
     if (b->nP == 0) return DSP_OK;
     DSP_HIP(hipMemcpyAsync(b->x, d_src, b->nP * 4, hipMemcpyDeviceToDevice, st));
-    return launch_refresh_shadows(b->dtype, b->x, b->tmap, b->wf16, b->wt, b->nP, st);
+    return launch_refresh_shadows(b->dtype, b->x, b->upd_tasks, b->upd_n_tasks, b->upd_blocks, b->tmap, b->wf16, b->wt, b->nP, st);
 }
 
 }  // namespace dsp
@@ -694,7 +719,7 @@ int dsp_block_init(const dsp_block_desc* desc, const float* h_params, size_t n_p
         rc = DSP_EINVAL;
     }
     if (rc == DSP_OK) rc = upload_params(b, h_params, b->x);
-    if (rc == DSP_OK) rc = launch_refresh_shadows(b->dtype, b->x, b->tmap, b->wf16, b->wt, b->nP, nullptr);
+    if (rc == DSP_OK) rc = launch_refresh_shadows(b->dtype, b->x, b->upd_tasks, b->upd_n_tasks, b->upd_blocks, b->tmap, b->wf16, b->wt, b->nP, nullptr);
     if (rc == DSP_OK && hipDeviceSynchronize() != hipSuccess) {
         set_error("dsp_block_init: device synchronisation failed");
         rc = DSP_EHIP;
@@ -896,8 +921,8 @@ int dsp_param_update_sum(dsp_block* b, float lr, float momentum, int32_t s, floa
         b->last_lr = lr;
     }
     if (b->dry) return DSP_OK;
-    DSP_TRY(launch_sgd_update(b->dtype, b->x, b->v, b->g, b->decay, b->tmap, b->wf16, b->wt, b->nP, lr, momentum,
-                              weight_decay, (hipStream_t)stream, s == 1, v_scale));
+    DSP_TRY(launch_sgd_update(b->dtype, b->x, b->v, b->g, b->upd_tasks, b->upd_n_tasks, b->upd_blocks, b->tmap, b->wf16, b->wt,
+                              b->nP, lr, momentum, weight_decay, (hipStream_t)stream, s == 1, v_scale));
     return DSP_OK;
 }
 
@@ -956,7 +981,7 @@ int dsp_block_set_params(dsp_block* b, const float* h_src, size_t n)
     DSP_REQUIRE(b && h_src && n == b->nP, DSP_EINVAL, "dsp_block_set_params: bad argument");
     DSP_HIP(hipDeviceSynchronize());
     DSP_TRY(upload_params(b, h_src, b->x));
-    DSP_TRY(launch_refresh_shadows(b->dtype, b->x, b->tmap, b->wf16, b->wt, b->nP, nullptr));
+    DSP_TRY(launch_refresh_shadows(b->dtype, b->x, b->upd_tasks, b->upd_n_tasks, b->upd_blocks, b->tmap, b->wf16, b->wt, b->nP, nullptr));
     DSP_HIP(hipDeviceSynchronize());
     return DSP_OK;
 }
@@ -975,6 +1000,30 @@ int dsp_block_get_grads(dsp_block* b, float* h_dst, size_t n)
 {
     DSP_REQUIRE(b && h_dst && n == b->nP, DSP_EINVAL, "dsp_block_get_grads: bad argument");
     return download_params(b, b->g, h_dst);
+}
+
+int dsp_block_get_activation(dsp_block* b, int32_t layer, void* h_dst, size_t bytes)
+{
+    DSP_REQUIRE(b && h_dst && layer >= 0 && layer < (int)b->layers.size(), DSP_EINVAL, "dsp_block_get_activation: bad argument");
+    const Tensor& t = b->T[layer];
+    DSP_REQUIRE(t.act != nullptr, DSP_EINVAL, "dsp_block_get_activation: layer %d keeps no output", (int)layer);
+    DSP_REQUIRE(bytes == t.bytes(b->dtype), DSP_EINVAL, "dsp_block_get_activation: layer %d holds %zu bytes, not %zu", (int)layer,
+                t.bytes(b->dtype), bytes);
+    DSP_HIP(hipDeviceSynchronize());
+    DSP_HIP(hipMemcpy(h_dst, t.act, bytes, hipMemcpyDeviceToHost));
+    return DSP_OK;
+}
+
+int dsp_block_get_pool_argmax(dsp_block* b, int32_t layer, uint8_t* h_dst, size_t bytes)
+{
+    DSP_REQUIRE(b && h_dst && layer >= 0 && layer < (int)b->layers.size(), DSP_EINVAL, "dsp_block_get_pool_argmax: bad argument");
+    const Layer& L = b->layers[layer];
+    DSP_REQUIRE(L.d.op == DSP_OP_MAXPOOL && L.argmax, DSP_EINVAL, "dsp_block_get_pool_argmax: layer %d is no max pool", (int)layer);
+    DSP_REQUIRE(bytes == b->T[layer].elems, DSP_EINVAL, "dsp_block_get_pool_argmax: layer %d holds %zu bytes, not %zu", (int)layer,
+                b->T[layer].elems, bytes);
+    DSP_HIP(hipDeviceSynchronize());
+    DSP_HIP(hipMemcpy(h_dst, L.argmax, bytes, hipMemcpyDeviceToHost));
+    return DSP_OK;
 }
 
 // ---- single-layer entry points ---------------------------------------------------------------------
@@ -1021,6 +1070,11 @@ int dsp_conv_workspace_bytes(int32_t N, int32_t H, int32_t W, int32_t cin, int32
 }
 
 // ---- in-situ kernel timing ---------------------------------------------------------------------------
+}  // extern "C"
+__global__ void dsp_profile_window_begin() {}
+__global__ void dsp_profile_window_end() {}
+extern "C" {
+
 int dsp_profile_start(int32_t max_launches)
 {
     DSP_REQUIRE(max_launches > 0 && max_launches <= (1 << 20), DSP_EINVAL, "dsp_profile_start: bad max_launches");
@@ -1034,6 +1088,9 @@ int dsp_profile_start(int32_t max_launches)
     g_prof_recs.reserve(max_launches);
     g_prof_capacity = max_launches;
     g_prof_result.clear();
+    DSP_HIP(hipDeviceSynchronize());
+    hipLaunchKernelGGL(dsp_profile_window_begin, dim3(1), dim3(1), 0, nullptr);
+    DSP_HIP(hipDeviceSynchronize());
     g_profile_on = true;
     return DSP_OK;
 }
@@ -1042,6 +1099,8 @@ int dsp_profile_stop(int32_t* n_kernels)
 {
     DSP_REQUIRE(g_profile_on, DSP_ESTATE, "dsp_profile_stop: no profile is running");
     g_profile_on = false;
+    DSP_HIP(hipDeviceSynchronize());
+    hipLaunchKernelGGL(dsp_profile_window_end, dim3(1), dim3(1), 0, nullptr);
     DSP_HIP(hipDeviceSynchronize());
     std::map<std::string, size_t> index;
     for (size_t i = 0; i < g_prof_recs.size(); ++i) {

@@ -7,6 +7,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "../../include/dsp.h"
 
 struct dsp_block;
@@ -232,17 +234,28 @@ int launch_linear_backward(const float* x, const float* w, const float* dz, floa
 // loss = mean_n -log softmax(z_n)[label_n];  dz = (softmax - onehot) / N;  row_loss is scratch [N].
 int launch_softmax_ce(const float* z, const int32_t* labels, float* loss, float* dz, float* row_loss, int N,
                       int C, hipStream_t st);
-// v <- momentum*v + (g + wd*x*[decay]);  x <- x - lr*v;  shadow copies refreshed in the same pass:
-// wf16[i] = bf16(x[i]) if wf16 != nullptr;  wt[tmap[i]] = T(x[i]) where tmap[i] >= 0.
 // out[0] = sum (a_i - b_i)^2, out[1] = sum b_i^2 in fp64, same order every run; partial: 2 * kDiffSumsqBlocks doubles.
 constexpr int kDiffSumsqBlocks = 256;
 int launch_diff_sumsq(const float* a, const float* b, size_t n, double* partial, double* out, hipStream_t st);
-int launch_sgd_update(int dtype, float* x, float* v, const float* g, const uint8_t* decay, const int32_t* tmap,
-                      void* wf16, void* wt, size_t n, float lr, float momentum, float wd, hipStream_t st,
+// v <- momentum*v + (g + wd*x*[decay]);  x <- x - lr*v (s = 0);  the copies the kernels read are refreshed in the
+// same pass: wf16[i] = bf16(x[i]) (bf16 blocks), and the backward-data filter copies in wt.  The parameters of a block
+// are described as a list of tasks over the flat arrays (built once at init, kept on the device):
+struct UpdateTask {
+    int kind;          // 0: flat run, no copy in wt;  1: conv filters w[co][j] with the copy wt[ci][R-1-r][S-1-s][co];
+                       // 2: one element per thread, copy position from the index table tmap (-1: none)
+    int decay;         // weight decay applies (conv / linear weights)
+    uint32_t p0, n;    // first element and length in the flat arrays
+    uint32_t wt_off;   // kind 1: first element of the copy in wt
+    int Co, J, Ci, R, S;  // kind 1: J = R * S * Ci
+    int tiles_j, block_begin, aligned, wt_aligned;  // filled by update_plan_finish
+};
+int update_plan_finish(std::vector<UpdateTask>& tasks, int dtype, int* total_blocks);
+int launch_sgd_update(int dtype, float* x, float* v, const float* g, const UpdateTask* tasks, int n_tasks, int blocks,
+                      const int32_t* tmap, void* wf16, void* wt, size_t n, float lr, float momentum, float wd, hipStream_t st,
                       bool nesterov = false, float v_scale = 1.f);
-// Same shadow refresh without an update (after init / set_params).
-int launch_refresh_shadows(int dtype, const float* x, const int32_t* tmap, void* wf16, void* wt, size_t n,
-                           hipStream_t st);
+// Same refresh of the copies without an update (after init / set_params).
+int launch_refresh_shadows(int dtype, const float* x, const UpdateTask* tasks, int n_tasks, int blocks, const int32_t* tmap,
+                           void* wf16, void* wt, size_t n, hipStream_t st);
 int launch_spin(int microseconds, hipStream_t st);
 // dst[p][0..Cp) = {src[p][0..C), 0...}: channel padding of an NHWC tensor (pixels rows) up to a whole 16-byte run.
 // y = a + b over n elements; backward of the sum: dx0 (and dx1, unless null) = dy or += dy, one read of dy

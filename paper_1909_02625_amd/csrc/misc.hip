@@ -4,6 +4,7 @@
 #include "common.h"
 
 #include <algorithm>
+#include <vector>
 
 namespace dsp {
 namespace {
@@ -259,25 +260,147 @@ __global__ __launch_bounds__(64) void mean_kernel(const float* __restrict__ v, f
 // v_scale = (previous step size) / (this step size) keeps the form exact across a change of alpha:
 // the momentum term of Eq. (3) is a difference of iterates, not of gradients, so it is not rescaled
 // by the new step size.
-template <typename TS, bool UPDATE, bool NESTEROV = false>
-__global__ void sgd_update_kernel(float* __restrict__ x, float* __restrict__ v, const float* __restrict__ g,
-                                  const uint8_t* __restrict__ decay, const int32_t* __restrict__ tmap,
-                                  bf16_t* __restrict__ wf16, TS* __restrict__ wt, size_t n, float lr, float momentum,
-                                  float wd, float v_scale)
+//
+// One launch covers all parameters of a block.  The flat arrays are cut into tasks (UpdateTask):
+//   flat    a run of parameters with no transposed copy (BN, linear, convs without backward-data): 16-byte
+//           loads and stores of x, v, g (and 8-byte stores of the bf16 copy), 4096 elements per workgroup;
+//   conv    a filter bank w[co][j], j = (r, s, ci), that also has the backward-data copy wt[ci][R-1-r][S-1-s][co]:
+//           a workgroup owns a 64 x 64 tile (co, j), streams its rows with 16-byte accesses along j, keeps the new
+//           values in LDS and writes the copy as 16-byte runs along co -- every global access is a coalesced run;
+//   mapped  anything else (the channel-padded forward filters of a stem conv): one element per thread through
+//           the index table.
+template <bool UPDATE, bool NESTEROV>
+__device__ inline float sgd_element(float xi, float& vi, float gi, bool decay, float lr, float momentum, float wd, float v_scale)
 {
-    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (size_t)gridDim.x * kThreads) {
-        float xi = x[i];
+    if (!UPDATE) return xi;
+    if (wd != 0.f && decay) gi += wd * xi;
+    vi = momentum * (vi * v_scale) + gi;
+    return xi - lr * (NESTEROV ? gi + momentum * vi : vi);
+}
+
+constexpr int kUpdFlatPerBlock = 4096;
+constexpr int kUpdTile = 64;
+
+template <typename TS, bool UPDATE, bool NESTEROV = false>
+__global__ __launch_bounds__(kThreads) void sgd_update_kernel(float* __restrict__ x, float* __restrict__ v,
+                                                              const float* __restrict__ g,
+                                                              const UpdateTask* __restrict__ tasks, int n_tasks,
+                                                              const int32_t* __restrict__ tmap, bf16_t* __restrict__ wf16,
+                                                              TS* __restrict__ wt, float lr, float momentum, float wd,
+                                                              float v_scale)
+{
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+    __shared__ float tile[kUpdTile][kUpdTile + 1];
+    int p = 0, hi = n_tasks;  // last task whose first workgroup is not after this one (block_begin ascends)
+    while (hi - p > 1) {
+        const int mid = (p + hi) >> 1;
+        if ((int)blockIdx.x >= tasks[mid].block_begin) p = mid; else hi = mid;
+    }
+    const UpdateTask t = tasks[p];
+    const int blk = (int)blockIdx.x - t.block_begin, tid = threadIdx.x;
+    const bool decay = t.decay != 0;
+
+    // four consecutive elements starting at i (all inside the task)
+    auto quad = [&](size_t i, float (&xn)[4]) {
+        f32x4 xv = *(const f32x4*)(x + i), vv = f32x4{0.f, 0.f, 0.f, 0.f}, gv = vv;
         if (UPDATE) {
-            float gi = g[i];
-            if (wd != 0.f && decay[i]) gi += wd * xi;
-            const float vi = momentum * (v[i] * v_scale) + gi;
-            v[i] = vi;
-            xi -= lr * (NESTEROV ? gi + momentum * vi : vi);
-            x[i] = xi;
+            vv = *(const f32x4*)(v + i);
+            gv = *(const f32x4*)(g + i);
         }
-        if (wf16) wf16[i] = float_to_bf16(xi);
-        const int32_t t = tmap[i];
-        if (t >= 0) wt[t] = from_float<TS>(xi);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float vi = vv[e];
+            xn[e] = sgd_element<UPDATE, NESTEROV>(xv[e], vi, gv[e], decay, lr, momentum, wd, v_scale);
+            vv[e] = vi;
+            xv[e] = xn[e];
+        }
+        if (UPDATE) {
+            *(f32x4*)(v + i) = vv;
+            *(f32x4*)(x + i) = xv;
+        }
+        if (wf16) *(u32x2*)(wf16 + i) = u32x2{pack_bf16x2(xn[0], xn[1]), pack_bf16x2(xn[2], xn[3])};
+    };
+    auto single = [&](size_t i) -> float {
+        float vi = UPDATE ? v[i] : 0.f;
+        const float xn = sgd_element<UPDATE, NESTEROV>(x[i], vi, UPDATE ? g[i] : 0.f, decay, lr, momentum, wd, v_scale);
+        if (UPDATE) {
+            v[i] = vi;
+            x[i] = xn;
+        }
+        if (wf16) wf16[i] = float_to_bf16(xn);
+        return xn;
+    };
+
+    if (t.kind == 0) {
+        const size_t base = (size_t)t.p0 + (size_t)blk * kUpdFlatPerBlock, end = (size_t)t.p0 + t.n;
+        if (t.aligned) {
+#pragma unroll
+            for (int it = 0; it < kUpdFlatPerBlock / (kThreads * 4); ++it) {
+                const size_t i = base + (size_t)it * kThreads * 4 + (size_t)tid * 4;
+                if (i + 4 <= end) {
+                    float xn[4];
+                    quad(i, xn);
+                } else {
+                    for (size_t k = i; k < end; ++k) (void)single(k);
+                }
+            }
+        } else {
+            for (int it = 0; it < kUpdFlatPerBlock / kThreads; ++it) {
+                const size_t i = base + (size_t)it * kThreads + tid;
+                if (i < end) (void)single(i);
+            }
+        }
+        return;
+    }
+    if (t.kind == 2) {
+        const size_t i = (size_t)t.p0 + (size_t)blk * kThreads + tid;
+        if (i < (size_t)t.p0 + t.n) {
+            const float xn = single(i);
+            const int32_t m = tmap[i];
+            if (m >= 0) wt[m] = from_float<TS>(xn);
+        }
+        return;
+    }
+    // conv tile: rows co0 .. co0+63 of w[co][j], columns j0 .. j0+63
+    const int co0 = (blk / t.tiles_j) * kUpdTile, j0 = (blk % t.tiles_j) * kUpdTile;
+    {
+        const int jq = tid % 16, row = tid / 16, j = j0 + 4 * jq;
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+            const int col = row + 16 * pass, co = co0 + col;
+            if (co >= t.Co || j >= t.J) continue;
+            const size_t i = (size_t)t.p0 + (size_t)co * t.J + j;
+            float xn[4] = {0.f, 0.f, 0.f, 0.f};
+            if (t.aligned && j + 4 <= t.J) {
+                quad(i, xn);
+            } else {
+                for (int e = 0; e < 4 && j + e < t.J; ++e) xn[e] = single(i + e);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) tile[4 * jq + e][col] = xn[e];
+        }
+    }
+    __syncthreads();
+    {
+        constexpr int E = 16 / (int)sizeof(TS);          // elements of the copy per 16-byte run
+        constexpr int CQ = kUpdTile / E, ROWS = kThreads / CQ;
+        const int cq = tid % CQ, jr = tid / CQ, co = co0 + E * cq;
+#pragma unroll
+        for (int pass = 0; pass < kUpdTile / ROWS; ++pass) {
+            const int jl = jr + ROWS * pass, j = j0 + jl;
+            if (j >= t.J || co >= t.Co) continue;
+            const int ci = j % t.Ci, tap = j / t.Ci, r = tap / t.S, s2 = tap % t.S;
+            TS* dst = wt + (size_t)t.wt_off + ((size_t)(ci * t.R + (t.R - 1 - r)) * t.S + (t.S - 1 - s2)) * t.Co + co;
+            if (t.wt_aligned && co + E <= t.Co) {
+                float f[E];
+#pragma unroll
+                for (int e = 0; e < E; ++e) f[e] = tile[jl][E * cq + e];
+                VecIO<TS, E>::store(dst, f);
+            } else {
+                for (int e = 0; e < E && co + e < t.Co; ++e) dst[e] = from_float<TS>(tile[jl][E * cq + e]);
+            }
+        }
     }
 }
 
@@ -456,45 +579,60 @@ int launch_softmax_ce(const float* z, const int32_t* labels, float* loss, float*
     return DSP_OK;
 }
 
-int launch_sgd_update(int dtype, float* x, float* v, const float* g, const uint8_t* decay, const int32_t* tmap,
-                      void* wf16, void* wt, size_t n, float lr, float momentum, float wd, hipStream_t st, bool nesterov,
-                      float v_scale)
+int update_plan_finish(std::vector<UpdateTask>& tasks, int dtype, int* total_blocks)
 {
-    if (n == 0) return DSP_OK;
-    const dim3 grid(grid_for((int64_t)n));
-    // read x, v, g, the weight-decay flag and the filter-copy index; write x, v and the shadow copies
-    ProfScope ps(dtype == DSP_BF16 ? "sgd_update<bf16 shadows>" : "sgd_update<fp32>", (double)n * 29.0, 1);
-    if (dtype == DSP_BF16 && nesterov)
-        DSP_LAUNCH(ps, (sgd_update_kernel<bf16_t, true, true>), grid, dim3(kThreads), 0, st, x, v, g, decay, tmap,
-                   (bf16_t*)wf16, (bf16_t*)wt, n, lr, momentum, wd, v_scale);
-    else if (dtype == DSP_BF16)
-        DSP_LAUNCH(ps, (sgd_update_kernel<bf16_t, true>), grid, dim3(kThreads), 0, st, x, v, g, decay, tmap,
-                   (bf16_t*)wf16, (bf16_t*)wt, n, lr, momentum, wd, v_scale);
-    else if (nesterov)
-        DSP_LAUNCH(ps, (sgd_update_kernel<float, true, true>), grid, dim3(kThreads), 0, st, x, v, g, decay, tmap,
-                   (bf16_t*)nullptr, (float*)wt, n, lr, momentum, wd, v_scale);
-    else
-        DSP_LAUNCH(ps, (sgd_update_kernel<float, true>), grid, dim3(kThreads), 0, st, x, v, g, decay, tmap,
-                   (bf16_t*)nullptr, (float*)wt, n, lr, momentum, wd, v_scale);
+    int blocks = 0;
+    for (UpdateTask& t : tasks) {
+        t.block_begin = blocks;
+        if (t.kind == 0) {
+            blocks += ceil_div((int64_t)t.n, kUpdFlatPerBlock);
+        } else if (t.kind == 2) {
+            blocks += ceil_div((int64_t)t.n, kThreads);
+        } else {
+            t.tiles_j = ceil_div(t.J, kUpdTile);
+            blocks += ceil_div(t.Co, kUpdTile) * t.tiles_j;
+            const int E = dtype == DSP_BF16 ? 8 : 4;
+            t.wt_aligned = (t.Co % E == 0 && t.wt_off % E == 0) ? 1 : 0;
+            t.aligned = (t.p0 % 4 == 0 && t.J % 4 == 0) ? 1 : 0;
+        }
+        if (t.kind == 0) t.aligned = (t.p0 % 4 == 0) ? 1 : 0;
+    }
+    *total_blocks = blocks;
+    return DSP_OK;
+}
+
+template <bool UPDATE>
+static int run_update(int dtype, float* x, float* v, const float* g, const UpdateTask* tasks, int n_tasks, int blocks,
+                      const int32_t* tmap, void* wf16, void* wt, size_t n, float lr, float momentum, float wd, hipStream_t st,
+                      bool nesterov, float v_scale)
+{
+    if (n == 0 || blocks == 0) return DSP_OK;
+    const dim3 grid(blocks);
+    // read x, v, g; write x, v, the bf16 copy (bf16 blocks) and the backward-data filter copy
+    ProfScope ps(dtype == DSP_BF16 ? "sgd_update<bf16 shadows>" : "sgd_update<fp32>", UPDATE ? (double)n * 24.0 : (double)n * 8.0, 1);
+#define UPD(TS, NES)                                                                                              \
+    DSP_LAUNCH(ps, (sgd_update_kernel<TS, UPDATE, NES>), grid, dim3(kThreads), 0, st, x, v, g, tasks, n_tasks, tmap, \
+               (bf16_t*)wf16, (TS*)wt, lr, momentum, wd, v_scale)
+    if (dtype == DSP_BF16) { if (nesterov) UPD(bf16_t, true); else UPD(bf16_t, false); }
+    else                   { if (nesterov) UPD(float, true); else UPD(float, false); }
+#undef UPD
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }
 
-int launch_refresh_shadows(int dtype, const float* x, const int32_t* tmap, void* wf16, void* wt, size_t n,
-                           hipStream_t st)
+int launch_sgd_update(int dtype, float* x, float* v, const float* g, const UpdateTask* tasks, int n_tasks, int blocks,
+                      const int32_t* tmap, void* wf16, void* wt, size_t n, float lr, float momentum, float wd, hipStream_t st,
+                      bool nesterov, float v_scale)
 {
-    if (n == 0) return DSP_OK;
-    const dim3 grid(grid_for((int64_t)n));
-    if (dtype == DSP_BF16)
-        hipLaunchKernelGGL((sgd_update_kernel<bf16_t, false>), grid, dim3(kThreads), 0, st, (float*)x, (float*)nullptr,
-                           (const float*)nullptr, (const uint8_t*)nullptr, tmap, (bf16_t*)wf16, (bf16_t*)wt, n, 0.f, 0.f,
-                           0.f, 1.f);
-    else
-        hipLaunchKernelGGL((sgd_update_kernel<float, false>), grid, dim3(kThreads), 0, st, (float*)x, (float*)nullptr,
-                           (const float*)nullptr, (const uint8_t*)nullptr, tmap, (bf16_t*)nullptr, (float*)wt, n, 0.f,
-                           0.f, 0.f, 1.f);
-    DSP_HIP(hipGetLastError());
-    return DSP_OK;
+    return run_update<true>(dtype, x, v, g, tasks, n_tasks, blocks, tmap, dtype == DSP_BF16 ? wf16 : nullptr, wt, n, lr, momentum,
+                            wd, st, nesterov, v_scale);
+}
+
+int launch_refresh_shadows(int dtype, const float* x, const UpdateTask* tasks, int n_tasks, int blocks, const int32_t* tmap,
+                           void* wf16, void* wt, size_t n, hipStream_t st)
+{
+    return run_update<false>(dtype, const_cast<float*>(x), nullptr, nullptr, tasks, n_tasks, blocks, tmap,
+                             dtype == DSP_BF16 ? wf16 : nullptr, wt, n, 0.f, 0.f, 0.f, st, false, 1.f);
 }
 
 int launch_diff_sumsq(const float* a, const float* b, size_t n, double* partial, double* out, hipStream_t st)

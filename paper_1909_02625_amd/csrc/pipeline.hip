@@ -112,6 +112,7 @@ struct dsp_pipeline {
     std::vector<Worker*> workers;
     int device = 0;
     bool use_threads = true;
+    bool single_stream = false;  // issue all K chains on stream 0 from the caller's thread (no overlap between kernels)
     // graph replay (off by default: on this runtime replaying a few hundred nodes costs more host time
     // than issuing them from K threads)
     bool use_graphs = false;
@@ -516,6 +517,16 @@ int dsp_pipeline_set_twin_launches(dsp_pipeline* pl, int32_t enable)
     return DSP_OK;
 }
 
+int dsp_pipeline_set_single_stream(dsp_pipeline* pl, int32_t enable)
+{
+    DSP_REQUIRE(pl, DSP_EINVAL, "dsp_pipeline_set_single_stream: null pipeline");
+    DSP_REQUIRE(!enable || !pl->use_fwd_streams, DSP_EINVAL, "dsp_pipeline_set_single_stream: not together with forward streams");
+    // work already issued on the K streams must not be overtaken by what follows on stream 0, and vice versa
+    DSP_TRY(dsp_pipeline_sync(pl));
+    pl->single_stream = enable != 0;
+    return DSP_OK;
+}
+
 int dsp_pipeline_set_launch_threads(dsp_pipeline* pl, int32_t enable)
 {
     DSP_REQUIRE(pl, DSP_EINVAL, "dsp_pipeline_set_launch_threads: null pipeline");
@@ -606,7 +617,7 @@ static int run_block_tick(dsp_pipeline* pl, int k, int64_t tau)
     const int cur = (int)(tau % R), prev = (int)((tau + R - 1) % R);
     const int fcur = (int)(tau & 1), fprev = fcur ^ 1;
     const bool split = pl->fwd_split[k] != 0;
-    hipStream_t sb = pl->streams[k];
+    hipStream_t sb = pl->single_stream ? pl->streams[0] : pl->streams[k];
     hipStream_t sf = split ? pl->fstreams[k] : sb;
     // The neighbours' tick wait_dn / wait_up back (the previous tick unless the queues have spare
     // entries): the slots this block reads were written then or earlier, and the slots it writes
@@ -655,7 +666,7 @@ static int issue_tick(dsp_pipeline* pl, int64_t tau, bool capturing)
     const int K = pl->K;
     hipStream_t s0 = pl->streams[0];
     if (!capturing) {
-        const bool threads = pl->use_threads && K > 1;
+        const bool threads = pl->use_threads && K > 1 && !pl->single_stream;
         if (threads)
             for (int k = 1; k < K; ++k) {
                 Worker* w = pl->workers[k];
@@ -778,7 +789,7 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
             }
     if (pl->probe) DSP_TRY(probe_before_tick(pl, tau, d_labels, user));
     const bool graph_tick = pl->use_graphs && pl->period > 0 && !g_profile_on && tau > pl->fill && pl->eager_ticks == 0 &&
-                            !pl->probe;
+                            !pl->probe && !pl->single_stream;
     if (pl->eager_ticks > 0 && tau > pl->fill) pl->eager_ticks -= 1;
     const int phase = graph_tick ? (int)(tau % pl->period) : 0;
 
@@ -847,7 +858,7 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
     if (h_loss) {
         *h_loss = 0.f;
         if (a_last >= 0) {
-            hipStream_t sl = (pl->serial || graph_tick) ? s0 : (pl->fwd_split[K - 1] ? pl->fstreams[K - 1] : pl->streams[K - 1]);
+            hipStream_t sl = (pl->serial || graph_tick || pl->single_stream) ? s0 : (pl->fwd_split[K - 1] ? pl->fstreams[K - 1] : pl->streams[K - 1]);
             DSP_HIP(hipStreamSynchronize(sl));
             DSP_HIP(hipMemcpy(h_loss, pl->losses + a_last, 4, hipMemcpyDeviceToHost));
         }

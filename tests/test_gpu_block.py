@@ -10,8 +10,8 @@ import torch
 
 import paper_1909_02625_amd as D
 from oracle import dsp_oracle as O
-from tests.gpu_harness import (block_shapes, build_gpu_blocks, destroy_blocks, from_dev, rel_err, round_like,
-                               to_dev, torch_dtype)
+from tests.gpu_harness import (block_shapes, build_gpu_blocks, destroy_blocks, from_dev, gpu_decisions, rel_err,
+                               round_like, to_dev, torch_dtype)
 from workloads import flatten_params, get_config, make_batch, make_params
 from workloads.gen import make_error_gradient, perturb_affine
 
@@ -24,10 +24,9 @@ def _flat(arrs):
     return np.concatenate([np.asarray(a, np.float64).ravel() for a in arrs]) if arrs else np.zeros(0)
 
 
-def _setup(name, batch=None, hw=None, perturb=False, p=None, m=None, lr=None, norelu=False, many_decisions=False,
-           sum_s=0, lr_drops=None, wd=None):
+def _setup(name, batch=None, hw=None, perturb=False, p=None, m=None, lr=None, norelu=False, sum_s=0, lr_drops=None,
+           wd=None):
     cfg = get_config(name, batch=batch, hw=hw)
-    cfg["many_decisions"] = many_decisions
     cfg["sum_s"] = sum_s                # s of Eq. (3)
     cfg["lr_drops"] = lr_drops or {}    # step schedule: from tick t on the step size is multiplied by lr_drops[t]
     if wd is not None:
@@ -48,44 +47,41 @@ def _setup(name, batch=None, hw=None, perturb=False, p=None, m=None, lr=None, no
     return cfg, params, rng
 
 
+# Branch decisions (is a rectifier's output positive; which element of a pooling window is the largest) are integer
+# results of floating-point values.  The library takes them on ITS stored activations; the reference gradient is
+# the oracle's chain rule applied with those same decisions (both sides decide in the kernel's precision), after
+# checking every decision against the layer definition on the library's own stored inputs (gpu_decisions).  With
+# the decisions shared, gradients are held to the plain per-step tolerance.
+
+
 def _teacher_forced(cfg, params, rng, dtype, ticks):
+    import copy
     tol = TOL[dtype]
     K = cfg["K"]
-    # bf16: a 1-ulp difference in a stored activation (fp32 vs fp64 accumulation landing on either side
-    # of a bf16 rounding boundary) perturbs its whole receptive field by ~1e-3 of a standard deviation,
-    # and about that fraction f of the pre-activations then takes the other ReLU branch.  Every ReLU layer
-    # therefore adds an independent relative difference of about sqrt(2 f) ~ 4-6e-2 to the gradients of
-    # ANY two bf16 implementations that are not bit-identical; it does not shrink with tensor size
-    # (tests/test_oracle_pins.py::test_bf16_gradient_reproducibility_floor shows the same jump inside the
-    # oracle alone: 1 ulp on 0.01% of a block's inputs moves its G_h by ~25% over 18 ReLU layers).
-    # So: the forward output and, for ReLU-free blocks, the gradients are held to 2e-2; gradients through
-    # n ReLU layers are held to 6e-2 * sqrt(n) in bf16.
-    # A max pool is a branch decision of the same kind (which window element receives the gradient), and in bf16
-    # the two largest values of a window are within one ulp of each other about as often, so it counts as a layer.
-    n_relu = [sum(1 for L in layers if (L["op"] == "bn" and L["relu"]) or L["op"] == "maxpool") for layers in cfg["blocks"]]
-    gtol = [(6e-2 * np.sqrt(n) if (dtype == D.DSP_BF16 and n) else tol) for n in n_relu]
-    # bf16 forward output: every stored feature map is rounded on both sides, and where the fp32 and the fp64
-    # value straddle a rounding boundary the two stored values differ by a whole ulp (~4e-3 relative); these
-    # differences add in quadrature over the n maps of a block: 4e-3 * sqrt(n), which exceeds the 2e-2 of the
-    # usual ~20-layer blocks only for the 128-layer blocks of the pre-activation net.
+    # bf16: every stored feature map is rounded on both sides, and where the fp32 and the fp64 value straddle a
+    # rounding boundary the two stored values differ by a whole ulp (2^-8 relative, rms ~4e-3 over a tensor when it
+    # happens everywhere); these independent differences add in quadrature over the n stored maps of a block:
+    # 5e-3 * sqrt(n) (measured: up to 4.6e-2 at stored map 124 of a 128-layer block), which exceeds 2e-2 only for blocks of more than 16 stored maps (ResNet-56, the bottleneck stage, the
+    # 128-layer blocks of the pre-activation nets).  The same bound holds for the gradients once the branch
+    # decisions are shared.
     n_maps = [sum(1 for L in layers if L["op"] in ("conv", "bn", "add", "maxpool")) for layers in cfg["blocks"]]
-    otol = [max(tol, 4e-3 * np.sqrt(n)) if dtype == D.DSP_BF16 else tol for n in n_maps]
-    orc = O.build_cnn_oracle(cfg, params, storage="bf16" if dtype == D.DSP_BF16 else None)
-    # fp32: a pre-activation within a few dozen fp32 ulps of zero (relative to the terms it is summed from; the
-    # conv sum feeding it carries the rounding of 144-576 products and may itself be a cancellation)
-    # may fall on the other ReLU branch in fp32 than in fp64; such a step has no unique gradient.  The
-    # oracle counts these knife-edge decisions and the gradient bound of that one step is widened by the
-    # largest change they could make: 4 * sqrt(sum_layers knife_l / (n_l / 2)).
-    for ob in orc.blocks:
-        ob.knife_tau = 3e-6 if dtype == D.DSP_FP32 else 0.0
+    btol = [max(tol, 5e-3 * np.sqrt(n)) if dtype == D.DSP_BF16 else tol for n in n_maps]
+    storage = "bf16" if dtype == D.DSP_BF16 else None
+    orc = O.build_cnn_oracle(cfg, params, storage=storage)
+    chk = [O.CNNBlock(layers, prm, first_block=(k == 0 and cfg.get("data_input", True)), storage=storage)
+           for k, (layers, prm) in enumerate(zip(cfg["blocks"], params))]
     for o in orc.opt:
         o.s = cfg.get("sum_s", 0)
     lr_now = cfg["lr"]
-    n_widened = n_steps = 0
+    n_steps = 0
     blocks = build_gpu_blocks(cfg, params, dtype, standalone=True)
     shapes = block_shapes(cfg)
     ext = cfg.get("classes") is None
-    worst = {}
+    worst = {"near_tie_decisions": 0, "decisions_unlike_oracle": 0}
+
+    def note(key, e):
+        worst[key] = max(worst.get(key, 0.0), e)
+
     try:
         for tau in range(ticks):
             x, y = make_batch(rng, cfg["input"], cfg["classes"])
@@ -96,23 +92,24 @@ def _teacher_forced(cfg, params, rng, dtype, ticks):
                 gtop[a] = round_like(make_error_gradient(rng, out.shape, cfg.get("grad_std", 0.1)), dtype)
                 return gtop[a].astype(np.float64)
 
-            before = [_flat(b.param_list()) for b in orc.blocks]
+            before = [[a.copy() for a in b.param_list()] for b in orc.blocks]
             # the library's velocity: -(x^n - x^{n-1}) / alpha for s = 0, -(y^n - y^{n-1}) / alpha for s = 1
             # (alpha = step size of that update)
             def velocity(o):
                 return -_flat(o.last_ys_step if o.s == 1 else o.last_step) / o.last_alpha
 
-            vel = [velocity(o) if o.last_step is not None else np.zeros_like(before[k]) for k, o in enumerate(orc.opt)]
+            vel = [velocity(o) if o.last_step is not None else np.zeros_like(_flat(before[k])) for k, o in enumerate(orc.opt)]
             lr_now *= cfg.get("lr_drops", {}).get(tau, 1.0)
             for o in orc.opt:
                 o.alpha = lr_now
+            opt_before = [copy.deepcopy(o) for o in orc.opt]
             rec = orc.tick(x, y, top_gradient=top_gradient if ext else None)
             for k in range(K):
                 a = rec["fwd"][k]
                 if a is None:
                     continue
                 b = blocks[k]
-                D.dsp_block_set_params(b, before[k])
+                D.dsp_block_set_params(b, _flat(before[k]))
                 D.dsp_block_set_momentum(b, vel[k])
                 last = k == K - 1
                 has_loss = last and not ext
@@ -127,8 +124,8 @@ def _teacher_forced(cfg, params, rng, dtype, ticks):
                 D.dsp_block_forward(b, a, d_in, d_out, d_lab, d_loss)
                 torch.cuda.synchronize()
                 e = rel_err(from_dev(d_out, oshape), rec["out"][k])
-                worst["out"] = max(worst.get("out", 0), e)
-                assert e < otol[k], ("h_out", tau, k, e)
+                note("out", e)
+                assert e < btol[k], ("h_out", tau, k, e)
                 if has_loss:
                     assert abs(d_loss.item() - rec["loss"]) < tol * max(1.0, abs(rec["loss"])), (tau, d_loss.item(), rec["loss"])
                 bb = rec["bwd"][k]
@@ -137,49 +134,54 @@ def _teacher_forced(cfg, params, rng, dtype, ticks):
                 if bb is None:
                     continue
                 assert q["slot_of_next_bwd"] == bb % q["ring_entries"]
-                knife = orc.blocks[k].last_knife
-                gt = gtol[k]
                 n_steps += 1
-                if any(c for c, _ in knife):
-                    gt += 4.0 * float(np.sqrt(sum(c / (n / 2) for c, n in knife)))
-                    n_widened += 1
                 d_gout = None if has_loss else to_dev(rec["g_out"][k], dtype)
                 ishape = shapes[k]
                 d_gin = torch.full((int(np.prod(ishape)),), float("nan"), device="cuda", dtype=torch_dtype(dtype))
                 D.dsp_block_recompute_backward(b, bb, d_gout, d_gin)
                 torch.cuda.synchronize()
-                if rec["g_in"][k] is not None:
-                    e = rel_err(from_dev(d_gin, ishape), rec["g_in"][k])
-                    if gt == gtol[k]:
-                        worst["g_in"] = max(worst.get("g_in", 0), e)
-                    assert e < gt, ("G_h", tau, k, e)
-                gx_ref = _flat(rec["g_x"][k])
-                e = rel_err(D.dsp_block_get_grads(b), gx_ref)
-                if gt == gtol[k]:
-                    worst["g_x"] = max(worst.get("g_x", 0), e)
-                assert e < gt, ("G_x", tau, k, e)
+                # the oracle's chain rule at the same parameters, with the decisions the library took
+                layers = [L for L in cfg["blocks"][k] if L["op"] != "softmax_ce"]
+                chk[k].set_param_list([v.copy() for v in before[k]])
+                dec, acts, near_ties, margin = gpu_decisions(D, O, b, layers, ishape, dtype, rec["h_in_bwd"][k], chk[k].x)
+                worst["near_tie_decisions"] += near_ties
+                note("near_tie_margin", margin)
+                _, cache = chk[k].forward(rec["h_in_bwd"][k])
+                for i, act in acts.items():   # layer-wise: every rectified map the library recomputed
+                    e = rel_err(act, cache[1][i])
+                    note("act", e)
+                    assert e < btol[k], ("recomputed activation", tau, k, i, e)
+                g_h_ref, g_x_ref = chk[k].backward(cache, rec["g_out"][k], decisions=dec)
+                worst["decisions_unlike_oracle"] += sum(n for _, n, _ in chk[k].last_decision_report)
+                if g_h_ref is not None:
+                    e = rel_err(from_dev(d_gin, ishape), g_h_ref)
+                    note("g_in", e)
+                    assert e < btol[k], ("G_h", tau, k, e)
+                e = rel_err(D.dsp_block_get_grads(b), _flat(g_x_ref))
+                note("g_x", e)
+                assert e < btol[k], ("G_x", tau, k, e)
                 if cfg.get("sum_s", 0) == 0 and not cfg.get("lr_drops"):
                     D.dsp_param_update(b, lr_now, cfg["beta"], cfg["wd"])
                 else:
                     D.dsp_param_update_sum(b, lr_now, cfg["beta"], cfg["sum_s"], cfg["wd"])
                 torch.cuda.synchronize()
-                after = _flat(orc.blocks[k].param_list())
+                # Eq. (3) from the same state with the reference gradient of THIS comparison
+                after = _flat(opt_before[k].step(before[k], g_x_ref))
+                bflat = _flat(before[k])
                 e = rel_err(D.dsp_block_get_params(b), after)
-                # x may be off by the storage tolerance plus the allowed gradient difference times the step taken
-                step_share = float(np.linalg.norm(after - before[k]) / np.linalg.norm(after))
-                assert e < tol + (gt if gt > tol else 0.0) * step_share, ("x", tau, k, e)
-                # the update itself (x_new - x_old) must match too, not just x
-                e = rel_err(D.dsp_block_get_params(b).astype(np.float64) - before[k].astype(np.float32), after - before[k])
-                worst["dx"] = max(worst.get("dx", 0), e)
-                assert e < max(gt, 2e-3), ("step", tau, k, e)
-                e = rel_err(D.dsp_block_get_momentum(b), velocity(orc.opt[k]))
-                assert e < gt, ("v", tau, k, e)
-                assert D.dsp_block_query(b)["version"] == orc.opt[k].n_updates
+                note("x", e)
+                assert e < tol, ("x", tau, k, e)
+                # the update itself (x_new - x_old) must match too, not just x (x_old as the library holds it: fp32)
+                e = rel_err(D.dsp_block_get_params(b).astype(np.float64) - bflat.astype(np.float32), after - bflat)
+                note("dx", e)
+                assert e < max(btol[k], 2e-3), ("step", tau, k, e)
+                e = rel_err(D.dsp_block_get_momentum(b), velocity(opt_before[k]))
+                note("v", e)
+                assert e < btol[k], ("v", tau, k, e)
+                assert D.dsp_block_query(b)["version"] == orc.opt[k].n_updates == opt_before[k].n_updates
     finally:
         destroy_blocks(blocks)
-    worst["steps"], worst["steps_with_knife_edge_relu"] = n_steps, n_widened
-    if not cfg.get("many_decisions"):
-        assert n_widened <= max(1, n_steps // 2), "too many steps ran on the widened bound"
+    worst["steps"] = n_steps
     return worst
 
 
@@ -193,26 +195,26 @@ labels_by_batch = {}
     ("resnet20", D.DSP_BF16, 8, {"batch": 8, "hw": 16, "perturb": True}),
     ("resnet20", D.DSP_BF16, 8, {"batch": 8, "hw": 16, "perturb": True, "norelu": True}),
     ("resnet56", D.DSP_FP32, 9, {"batch": 4, "hw": 16}),
+    ("resnet56", D.DSP_BF16, 9, {"batch": 8, "hw": 16, "perturb": True}),
     ("resnet18", D.DSP_BF16, 8, {"batch": 4, "hw": 64, "perturb": True}),
     ("resnet18", D.DSP_FP32, 8, {"batch": 2, "hw": 64}),
-    # ~1.5e6 ReLU decisions per step: nearly every step holds a knife-edge one, so every step of this case
-    # is checked against the widened (few-percent) bound; the ReLU-free case below is the tight one
-    ("resnet50_conv4x", D.DSP_FP32, 5, {"batch": 4, "hw": 14, "many_decisions": True}),
+    # ~1.5e6 ReLU decisions per step: in fp32 nearly every step holds one that falls the other way than in fp64
+    ("resnet50_conv4x", D.DSP_FP32, 5, {"batch": 4, "hw": 14}),
     ("resnet50_conv4x", D.DSP_BF16, 5, {"batch": 4, "hw": 14, "norelu": True}),
-    ("resnet50_conv4x", D.DSP_BF16, 5, {"batch": 4, "hw": 14}),
+    ("resnet50_conv4x", D.DSP_BF16, 20, {"batch": 4, "hw": 14}),   # configs[3]: all 20 steps (17 updates), batch 4 of 64
     ("resnet20", D.DSP_FP32, 7, {"batch": 4, "hw": 8, "p": (1, 1, 0), "m": (7, 3, 1)}),  # last block stale too
     # normalisation, shortcut and 1x1 conv kernels at ImageNet-sized maps (M = 401408 rows, 3136 conv tiles
     # of fused statistics, 512 partial sums per channel): full size, every element compared
-    ("bn_probe", D.DSP_FP32, 3, {"many_decisions": True}),
+    ("bn_probe", D.DSP_FP32, 3, {}),
     ("bn_probe", D.DSP_BF16, 3, {}),
     # VGG-19 with batch norm (2x2 max pools inside the blocks, 512-channel layers on 4x4 and 2x2 maps)
-    ("vgg19", D.DSP_FP32, 7, {"batch": 4, "perturb": True, "many_decisions": True}),
+    ("vgg19", D.DSP_FP32, 7, {"batch": 4, "perturb": True}),
     ("vgg19", D.DSP_BF16, 7, {"batch": 16, "perturb": True}),   # 2x2 maps: BN over 4 * batch values per channel
     # pre-activation bottleneck ResNet-164 (element-wise add layers, BN directly on a block input, 128 layers per block)
-    ("resnet164", D.DSP_FP32, 7, {"batch": 4, "hw": 16, "perturb": True, "many_decisions": True}),
+    ("resnet164", D.DSP_FP32, 7, {"batch": 4, "hw": 16, "perturb": True}),
     ("resnet164", D.DSP_BF16, 7, {"batch": 8, "hw": 16, "perturb": True}),
     # ResNet-1001 (same unit as ResNet-164; 387-915 layers per block, K = 4), every block twice through its update
-    ("resnet1001", D.DSP_FP32, 9, {"batch": 4, "hw": 8, "perturb": True, "many_decisions": True}),
+    ("resnet1001", D.DSP_FP32, 9, {"batch": 4, "hw": 8, "perturb": True}),
     # Eq. (3) beyond the constant-step heavy ball: Nesterov (s = 1), weight decay, a step schedule that drops
     # the step size twice while every block carries momentum
     ("resnet20", D.DSP_FP32, 9, {"batch": 8, "hw": 16, "perturb": True, "sum_s": 1, "wd": 5e-4,
@@ -411,36 +413,130 @@ def test_spare_queue_entries_and_random_stragglers_change_no_bit(name, dtype, ti
         assert np.array_equal(a, b)
 
 
-# Free-running trajectories.  A ReLU pre-activation within a few fp32 ulps of zero takes either branch;
-# on small tensors one such decision moves that step's gradient by ~1/sqrt(elements), i.e. by far more
-# than 1e-3, so the 1e-3 bound on the loss trajectory is checked at the configurations' real sizes
-# (where those decisions average out) and the shrunken variants get a looser bound.
-@pytest.mark.parametrize("name,dtype,ticks,kw,rtol", [
-    ("tiny2", D.DSP_FP32, 4, {}, 1e-3),                      # configs[0]: 4 steps -> losses of batches 0,1,2
-    ("tiny2", D.DSP_FP32, 24, {"perturb": True}, 1e-3),
+# Free-running trajectories against the oracle run in the same process.  The DSP recursion amplifies rounding
+# differences from tick to tick (tests/test_oracle_pins.py::test_trajectories_of_the_oracle_itself_drift_apart), so
+# each case also runs the ORACLE twice more with nothing changed but rounding (every stored tensor rounded to the
+# compared storage type / initial parameters moved by one fp32 ulp) and bounds the library's distance from the
+# oracle by max(1e-3, ENVELOPE_FACTOR x the largest distance between oracle runs so far): on the losses tick by tick
+# and on the final parameters.
+ENVELOPE_FACTOR = 4.0
+
+
+def _oracle_spread(cfg, params, rng_state, dtype, ticks, ref_losses, ref_orc):
+    from workloads.gen import perturb_one_ulp
+    bf16 = dtype == D.DSP_BF16
+    gaps, pgap = [], np.zeros(cfg["K"])
+    for variant in (0, 1):
+        prm = perturb_one_ulp(params, 101 + variant) if (bf16 or variant) else params
+        storage = "bf16" if bf16 else ("fp32" if variant == 0 else None)
+        orc = O.build_cnn_oracle(cfg, prm, storage=storage)
+        for o in orc.opt:
+            o.s = cfg.get("sum_s", 0)
+        rng = np.random.default_rng(0)
+        rng.bit_generator.state = rng_state
+        lr_now, losses = cfg["lr"], []
+        for tau in range(ticks):
+            x, y = make_batch(rng, cfg["input"], cfg["classes"])
+            if tau in cfg.get("lr_drops", {}):
+                lr_now *= cfg["lr_drops"][tau]
+                for o in orc.opt:
+                    o.alpha = lr_now
+            rec = orc.tick(round_like(x, dtype), y)
+            if rec["loss"] is not None:
+                losses.append(rec["loss"])
+        gaps.append(np.abs(np.array(losses) - ref_losses) / np.abs(ref_losses))
+        for k in range(cfg["K"]):
+            pgap[k] = max(pgap[k], rel_err(_flat(orc.blocks[k].param_list()), _flat(ref_orc.blocks[k].param_list())))
+    return np.maximum.accumulate(np.maximum(gaps[0], gaps[1])), pgap
+
+
+@pytest.mark.parametrize("name,dtype,ticks,kw", [
+    ("tiny2", D.DSP_FP32, 4, {}),                      # configs[0]: 4 steps -> losses of batches 0,1,2
+    ("tiny2", D.DSP_FP32, 24, {"perturb": True}),
     # Nesterov + weight decay + two drops of the step size while the pipeline runs
-    ("tiny2", D.DSP_FP32, 24, {"perturb": True, "sum_s": 1, "wd": 5e-4, "lr_drops": {9: 0.1, 16: 0.1}}, 1e-3),
-    ("tiny2", D.DSP_FP32, 24, {"perturb": True, "lr_drops": {9: 0.1, 16: 0.1}}, 1e-3),
-    ("resnet20", D.DSP_FP32, 16, {"batch": 16, "hw": 16}, 2e-2),
-    ("resnet56", D.DSP_FP32, 11, {"batch": 16, "hw": 16}, 2e-2),   # short: the gap to the oracle triples per tick here
-    ("resnet20", D.DSP_FP32, 12, {}, 1e-3),                  # configs[1] at full size (first 12 of its 50 steps)
-    ("vgg19", D.DSP_FP32, 6, {"batch": 32}, 2e-2),          # short: 2x2 maps with 128 values per channel diverge fast
+    ("tiny2", D.DSP_FP32, 24, {"perturb": True, "sum_s": 1, "wd": 5e-4, "lr_drops": {9: 0.1, 16: 0.1}}),
+    ("tiny2", D.DSP_FP32, 24, {"perturb": True, "lr_drops": {9: 0.1, 16: 0.1}}),
+    ("resnet20", D.DSP_FP32, 16, {"batch": 16, "hw": 16}),
+    ("resnet20", D.DSP_BF16, 16, {"batch": 16, "hw": 16}),
+    ("resnet56", D.DSP_FP32, 14, {"batch": 16, "hw": 16}),
+    ("vgg19", D.DSP_FP32, 8, {"batch": 32}),
 ], ids=lambda v: v if isinstance(v, str) else None)
-def test_pipeline_loss_trajectory(name, dtype, ticks, kw, rtol):
+def test_pipeline_loss_trajectory(name, dtype, ticks, kw):
     cfg, params, rng = _setup(name, **kw)
-    ref, got, final, versions, orc = _free_running(cfg, params, rng, dtype, ticks, rtol=rtol)
+    state = rng.bit_generator.state
+    ref, got, final, versions, orc = _free_running(cfg, params, rng, dtype, ticks, rtol=1.0)
     assert len(got) == len(ref) == ticks - sum(cfg["p"])
-    np.testing.assert_allclose(got, ref, rtol=rtol)
+    env, pgap = _oracle_spread(cfg, params, state, dtype, ticks, ref, orc)
+    err = np.abs(got - ref) / np.abs(ref)
+    print(name, "max loss err %.2e, oracle-vs-oracle envelope at the end %.2e; parameter gaps of the oracle runs" % (err.max(), env[-1]), pgap)
+    assert np.all(err <= np.maximum(1e-3, ENVELOPE_FACTOR * env)), (err, env)
     # update counts: block k has made max(0, ticks - P_k - m_k) updates
     P = np.concatenate([[0], np.cumsum(cfg["p"])[:-1]])
     assert versions == [max(0, ticks - int(P[k]) - cfg["m"][k]) for k in range(cfg["K"])]
     assert versions == [o.n_updates for o in orc.opt]
-    # Final parameters: at full size to the trajectory tolerance.  The shrunken variants are chaotic at
-    # this scale -- two runs of the fp64 oracle whose inputs differ by one fp32 ulp end 14 ticks later
-    # with parameters 1-7 % apart (ReLU decisions on tiny tensors) -- so there the bound only catches
-    # gross errors; step-exactness is what the teacher-forced tests check.
     for k in range(cfg["K"]):
-        assert rel_err(final[k], _flat(orc.blocks[k].param_list())) < (rtol if rtol <= 1e-3 else 0.25)
+        assert rel_err(final[k], _flat(orc.blocks[k].param_list())) < max(1e-3, ENVELOPE_FACTOR * pgap[k])
+
+
+def _stored_trajectory(fname):
+    """Oracle losses per tick and the running envelope of the gaps between perturbed oracle runs (see
+    tests/golden/make_trajectory_spread.py, which wrote the file calling only the oracle)."""
+    import os
+    loss, env, e = [], [], 0.0
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", fname)):
+        if line.startswith("#"):
+            continue
+        _, batch, a, gb, gc = line.split()
+        if int(batch) < 0:
+            continue
+        e = max(e, float(gb), float(gc))
+        loss.append(float(a))
+        env.append(e)
+    return np.array(loss), np.array(env)
+
+
+# The free-running loss trajectory over ALL configured steps of the benchmark configurations, against oracle
+# trajectories stored under tests/golden/ (the oracle needs minutes for them).  The recursion amplifies rounding
+# differences tick by tick (a rectifier that falls the other way changes the next parameters, hence every later
+# decision): two runs of the ORACLE ITSELF that differ only by rounding (stored tensors rounded to fp32, or initial
+# parameters moved by one fp32 ulp) drift apart by the gaps stored next to the losses.  The bound per tick is
+# therefore max(1e-3, ENVELOPE_FACTOR x the largest gap between oracle runs up to that tick); 1e-3 alone holds for
+# as long as the oracle's own runs stay within 1e-3 / ENVELOPE_FACTOR of each other.
+
+
+@pytest.mark.parametrize("fname,name,dtype,kw,delay_us", [
+    ("trajectory_resnet20_fp32.txt", "resnet20", D.DSP_FP32, {}, 0),                               # configs[1], 50 steps
+    ("trajectory_resnet56_fp32.txt", "resnet56", D.DSP_FP32, {}, 0),                               # configs[2], 50 steps
+    ("trajectory_resnet56_bf16.txt", "resnet56", D.DSP_BF16, {}, 0),
+    # configs[4] at reduced size (the oracle cannot afford 224 x 224 x 256), 20 steps, block 1 delayed in every tick
+    ("trajectory_resnet18_bf16_b32_hw64.txt", "resnet18", D.DSP_BF16, {"batch": 32, "hw": 64}, 1500),
+], ids=lambda v: v if isinstance(v, str) else None)
+def test_pipeline_loss_trajectory_over_the_configured_steps(fname, name, dtype, kw, delay_us):
+    ref, env = _stored_trajectory(fname)
+    cfg, params, rng = _setup(name, **kw)
+    ticks = cfg["steps"]
+    assert len(ref) == ticks - sum(cfg["p"])
+    blocks = build_gpu_blocks(cfg, params, dtype)
+    pl = D.dsp_pipeline_init(blocks, cfg["p"], cfg["m"], cfg["lr"], cfg["beta"], cfg["wd"], ticks)
+    if delay_us:
+        D.dsp_pipeline_set_delay(pl, 1, delay_us)
+    try:
+        for _ in range(ticks):
+            x, y = make_batch(rng, cfg["input"], cfg["classes"])
+            D.dsp_pipeline_step(pl, to_dev(round_like(x, dtype), dtype), torch.from_numpy(y).cuda())
+        got = D.dsp_pipeline_losses(pl).astype(np.float64)
+    finally:
+        D.dsp_pipeline_destroy(pl)
+        destroy_blocks(blocks)
+    err = np.abs(got - ref) / np.abs(ref)
+    bound = np.maximum(1e-3, ENVELOPE_FACTOR * env)
+    print(fname, "ticks within 1e-3:", int((err <= 1e-3).sum()), "of", len(err), "max err %.2e" % err.max(),
+          "oracle-vs-oracle envelope at the end %.2e" % env[-1])
+    assert np.all(err <= bound), (np.nonzero(err > bound)[0], err, bound)
+    # while the oracle's own runs agree to 1e-3 / ENVELOPE_FACTOR the plain 1e-3 criterion is what was checked
+    # (in bf16 two oracle runs whose initial parameters differ by one fp32 ulp are ~1e-3 apart from the first loss on)
+    n_strict = int((ENVELOPE_FACTOR * env <= 1e-3).sum())
+    assert np.all(err[:n_strict] <= 1e-3) and (n_strict >= 4 or dtype == D.DSP_BF16)
 
 
 @pytest.mark.parametrize("name,dtype,ticks,kw,rtol", [

@@ -36,6 +36,24 @@ def perturb_affine(params, rng, scale=0.25):
     return params
 
 
+def perturb_one_ulp(params_per_block, seed):
+    """Every parameter of every block moved by one fp32 ulp up or down (random signs): the smallest change of
+    the inputs an fp32 program can see.  Used to measure how far two runs of one recursion drift apart."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for block in params_per_block:
+        nb = []
+        for d in block:
+            nd = {}
+            for k, v in d.items():
+                v = np.asarray(v, np.float32)
+                up = rng.random(v.shape) < 0.5
+                nd[k] = np.where(up, np.nextafter(v, np.float32(np.inf)), np.nextafter(v, np.float32(-np.inf))).astype(np.float32)
+            nb.append(nd)
+        out.append(nb)
+    return out
+
+
 def make_batch(rng, shape, classes):
     """One mini-batch: data ~ N(0,1) in NCHW fp32, labels uniform in [0, classes)."""
     x = rng.standard_normal(shape).astype(np.float32)
