@@ -558,6 +558,269 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
     }
 }
 
+// ---- bf16 gather-GEMM fed by direct global -> LDS loads ---------------------------------------------
+// For bf16 layers whose gathered channel count is a multiple of 64 (every 64-element k tile then lies inside one
+// filter tap) the operands need no detour through registers: `buffer_load ... lds` moves 16 bytes per lane from
+// memory straight into LDS.  A load instruction of one wave fills 1 KB of LDS contiguously (lane l -> bytes
+// 16 l .. 16 l + 15), i.e. 8 tile rows of 128 bytes, so rows cannot be padded; instead the 16-byte chunk c of row R
+// is kept at position c ^ ((R >> 1) & 7) of its row -- the lane that owns position p of row R simply fetches chunk
+// p ^ ((R >> 1) & 7) -- which spreads the 16 rows a group of 16 lanes reads over all 64 banks.  Three LDS stages:
+// while k tile t is multiplied, tile t+1 has landed or is landing and the loads of tile t+2 are issued, so a
+// gather has two multiply phases to arrive and no vector register or LDS-write instruction is spent on it.
+// A 256-thread workgroup owns BM x BN outputs (256 x 128: each of the 2 x 2 waves a 128 x 64 sub-tile = 4 x 2
+// MFMA tiles of 32 x 32, 6 LDS operand reads per 8 MFMAs).  Per k tile the tap and the channel offset are uniform,
+// so a lane's address is (row base + uniform tap offset) or "out of range" (padding tap / row past M: the buffer
+// load then writes zeros).
+template <int BM_, int BN_, int WGM_, int WGN_, int BKB_, int STAGES_, int WAVES_ = 1>
+struct DmaTile {
+    static constexpr int WAVES = WAVES_;  // waves per SIMD the register allocation aims for (workgroups per compute unit)
+    static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_, STAGES = STAGES_;
+    static_assert(WGM * WGN == 4, "four waves per workgroup");
+    static constexpr int TM = BM / (WGM * 32), TN = BN / (WGN * 32);
+    static constexpr int ROWB = BKB_;                      // bytes of k per row: 64 or 32 bf16
+    static constexpr int BK = ROWB / 2;
+    static constexpr int CPR = ROWB / 16;                  // 16-byte chunks per row
+    static constexpr int RPG = 1024 / ROWB;                // rows per 1 KB load instruction
+    static constexpr int NKS = ROWB / 32;                  // MFMA k steps (16 elements) per tile
+    static constexpr int A_G = BM / RPG / 4, B_G = BN / RPG / 4;  // load instructions per wave and tile
+    static constexpr int STAGE_BYTES = (BM + BN) * ROWB;
+    static constexpr int EPI_ROWB = BN * 2 + 16;
+    static constexpr int EPI_BYTES = BM * EPI_ROWB;
+    static constexpr int STATS_BYTES = kThreads * 2 * (int)sizeof(double);
+    static constexpr int LDS_BYTES = cmax(STAGES * STAGE_BYTES, EPI_BYTES + STATS_BYTES);
+    static_assert((ROWB == 128 || ROWB == 64) && BM % (4 * RPG) == 0 && BN % (4 * RPG) == 0 && kThreads % BN == 0 &&
+                      STAGES >= 3 && LDS_BYTES <= 160 * 1024, "tile shape");
+    // chunk c of row R sits at position c ^ swz(R) of its row: the 16 rows a group of 16 lanes reads (same c) then
+    // fall on 16 different 16-byte bank groups of the 64 banks
+    __device__ static inline int swz(int R) { return ROWB == 128 ? (R >> 1) & 7 : (R >> 2) & 3; }
+};
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+__device__ inline void dma16(__amdgpu_buffer_rsrc_t r, char* lds_wave_base, uint32_t byte_off)
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr_t)lds_wave_base, 16, (int)byte_off, 0, 0, 0);
+}
+
+template <typename TL>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::WAVES, TL::WAVES))) void conv_dma_gemm_kernel(
+    const bf16_t* __restrict__ in_, const bf16_t* __restrict__ wgt, bf16_t* __restrict__ out_, GatherGeom g)
+{
+    typedef bf16_t T;
+    constexpr int BM = TL::BM, BN = TL::BN, TM = TL::TM, TN = TL::TN, NKS = TL::NKS, ST = TL::STAGES;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const T* __restrict__ in = blockIdx.y ? (const T*)g.in1 : in_;
+    T* __restrict__ out = blockIdx.y ? (T*)g.out1 : out_;
+    double* stats = blockIdx.y ? g.stats1 : g.stats;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_m = wave / TL::WGN, wave_n = wave % TL::WGN;
+    const int tiles_n = (g.Co + BN - 1) / BN;
+    const unsigned tile = xcd_tile(blockIdx.x, gridDim.x);
+    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+
+    // loader state: this lane owns position (lane % CPR) of row (lane / CPR) of each 1 KB row group of its wave
+    const int lrow = lane / TL::CPR, lpos = lane % TL::CPR;
+    uint32_t a_base[TL::A_G], a_mask[TL::A_G], b_base[TL::B_G];
+#pragma unroll
+    for (int i = 0; i < TL::A_G; ++i) {
+        const int row = (wave * TL::A_G + i) * TL::RPG + lrow, m = m0 + row;
+        const uint32_t chunk = (uint32_t)(lpos ^ TL::swz(row));
+        a_base[i] = 0;
+        a_mask[i] = 0;
+        if (m < g.M) {
+            const int t = (int)fast_div((uint32_t)m, g.wo_mul, g.wo_sh), wo = m - t * g.Wo;
+            const int n = (int)fast_div((uint32_t)t, g.ho_mul, g.ho_sh), ho = t - n * g.Ho;
+            const int th0 = ho * g.ostride - g.pad_h, tw0 = wo * g.ostride - g.pad_w;
+            const int s_lo = tw0 < 0 ? -tw0 : 0, s_hi = g.Wi - tw0 < g.S ? g.Wi - tw0 : g.S;
+            const uint32_t cols = s_hi > s_lo ? ((1u << s_hi) - 1) & ~((1u << s_lo) - 1) : 0u;
+            uint32_t mask = 0;
+            for (int r = 0; r < g.R; ++r)
+                if (th0 + r >= 0 && th0 + r < g.Hi) mask |= cols << (r * g.S);
+            a_mask[i] = mask;
+            a_base[i] = (uint32_t)n * g.Hi * g.Wi * g.Ci * 2u + (uint32_t)((th0 * g.Wi + tw0) * g.Ci) * 2u + chunk * 16u;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < TL::B_G; ++i) {
+        const int row = (wave * TL::B_G + i) * TL::RPG + lrow, co = n0 + row;
+        const uint32_t chunk = (uint32_t)(lpos ^ TL::swz(row));
+        b_base[i] = co < g.Co ? (uint32_t)(co * g.Kdim) * 2u + chunk * 16u : kOutOfRange;
+    }
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc(in, (uint32_t)g.N * g.Hi * g.Wi * g.Ci * 2u);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(wgt, (uint32_t)g.Co * g.Kdim * 2u);
+
+    const int nk = g.Kdim / TL::BK;
+    const int tiles_per_tap = g.Ci / TL::BK;
+    // position of the k tile whose loads are issued next (all uniform)
+    int l_kt = 0, l_tap = 0, l_r = 0, l_s = 0, l_c = 0;
+    auto issue_loads = [&](int stage) {
+        char* sA = smem + stage * TL::STAGE_BYTES + wave * (TL::A_G * 1024);
+        char* sB = smem + stage * TL::STAGE_BYTES + BM * TL::ROWB + wave * (TL::B_G * 1024);
+        const bool live = l_kt < nk;
+        const uint32_t tap_off = (uint32_t)((l_r * g.Wi + l_s) * g.Ci + l_c * TL::BK) * 2u;
+        const uint32_t tap_bit = live ? (1u << l_tap) : 0u;
+#pragma unroll
+        for (int i = 0; i < TL::A_G; ++i)
+            dma16(rin, sA + i * 1024, (a_mask[i] & tap_bit) ? a_base[i] + tap_off : kOutOfRange);
+        const uint32_t kb = (uint32_t)l_kt * (uint32_t)TL::ROWB;
+#pragma unroll
+        for (int i = 0; i < TL::B_G; ++i)
+            dma16(rw, sB + i * 1024, (live && b_base[i] != kOutOfRange) ? b_base[i] + kb : kOutOfRange);
+        ++l_kt;
+        if (++l_c == tiles_per_tap) {
+            l_c = 0;
+            ++l_tap;
+            if (++l_s == g.S) {
+                l_s = 0;
+                ++l_r;
+            }
+        }
+    };
+
+    typename Mma<T, 32>::Acc acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // operand reads: lane (frow, fg) takes row frow of every 32-row MFMA block and the 16-byte k chunk 2 ks + fg
+    const int frow = lane & 31, fg = lane >> 5, swl = TL::swz(frow);
+    int koff[NKS];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) koff[ks] = ((2 * ks + fg) ^ swl) << 4;
+    const int a_row_off = (wave_m * TM * 32 + frow) * TL::ROWB;
+    const int b_row_off = BM * TL::ROWB + (wave_n * TN * 32 + frow) * TL::ROWB;
+    auto read_frags = [&](const char* s, int ks, u32x4 (&a)[TM], u32x4 (&b)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[i] = *(const u32x4*)(s + a_row_off + i * 32 * TL::ROWB + koff[ks]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[j] = *(const u32x4*)(s + b_row_off + j * 32 * TL::ROWB + koff[ks]);
+    };
+    auto mfmas = [&](const u32x4 (&a)[TM], const u32x4 (&b)[TN]) {
+        __builtin_amdgcn_sched_barrier(0);  // the reads of the next step are issued before this step's MFMAs, not among them
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) Mma<T, 32>::run(b[j], a[i], acc[i][j]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // Synchronisation by hand (__syncthreads() would make every wave wait for ALL its outstanding loads at every
+    // barrier).  ST stages: tiles kt .. kt + ST - 2 are in LDS or on their way, tile kt + ST - 1 is issued during
+    // tile kt.  One barrier per k tile, in the MIDDLE of the tile's k steps: by then the loads of tile kt + 1 have
+    // landed -- each wave waits until only its loads of the later tiles are outstanding, the barrier makes them
+    // visible to all -- and every wave has finished reading tile kt - 1, whose stage the loads issued right after
+    // the barrier overwrite.  The operands of a tile's first k step are read during the last k step of the tile
+    // before, so no wave meets the barrier and a burst of LDS reads at the same moment.
+    constexpr int LOADS = TL::A_G + TL::B_G;      // loads one wave issues per k tile
+    constexpr int AHEAD = (ST - 3) * LOADS;       // loads that may stay outstanding at the barrier
+#pragma unroll
+    for (int t = 0; t < ST - 1; ++t) issue_loads(t);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((ST - 2) * LOADS) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    u32x4 fa[2][TM], fb[2][TN];
+    read_frags(smem, 0, fa[0], fb[0]);
+    int st = 0;
+    for (int kt = 0; kt < nk; ++kt) {
+        const char* s = smem + st * TL::STAGE_BYTES;
+        int st1 = st + 1;
+        if (st1 == ST) st1 = 0;
+        int stl = st - 1;        // the stage of tile kt - 1 = the stage of tile kt + ST - 1
+        if (stl < 0) stl = ST - 1;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            if (ks + 1 < NKS)
+                read_frags(s, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+            else
+                read_frags(smem + st1 * TL::STAGE_BYTES, 0, fa[0], fb[0]);
+            mfmas(fa[ks & 1], fb[ks & 1]);
+            if (ks == NKS / 2 - 1) {
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(AHEAD) : "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                issue_loads(stl);   // tile kt + ST - 1 (zeros past the end) replaces tile kt - 1
+            }
+        }
+        st = st1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the zero loads past the end must not land in the staged output tile
+    __syncthreads();
+
+    // ---- epilogue: the accumulators hold the transposed tile (a lane has, for output row lane % 32 of its block,
+    // runs of 4 consecutive output channels); stage it in LDS, then store 16-byte runs ----
+    typedef typename Run4<T>::V RunV;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int lr = (wave_m * TM + i) * 32 + (lane & 31);
+            const int m = m0 + lr;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int lcol = (wave_n * TN + j) * 32 + acc_row<32>(lane, 4 * q);
+                const int col = n0 + lcol;
+                if (g.accum && m < g.M) {
+                    if (g.out_vec && col + 4 <= g.Co) {
+                        float o[4];
+                        Run4<T>::unpack(*(const RunV*)(out + (int64_t)m * g.Co + col), o);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += o[e];
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col + e < g.Co) acc[i][j][4 * q + e] += to_float<T>(out[(int64_t)m * g.Co + col + e]);
+                    }
+                }
+                *(RunV*)(smem + lr * TL::EPI_ROWB + lcol * 2) =
+                    Run4<T>::pack(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            }
+        }
+    __syncthreads();
+    constexpr int OCPR = BN / 8;  // 16-byte runs per tile row
+    for (int c = tid; c < BM * OCPR; c += kThreads) {
+        const int lr = c / OCPR, cc = (c % OCPR) * 8;
+        const int m = m0 + lr, col = n0 + cc;
+        if (m >= g.M || col >= g.Co) continue;
+        const char* src = smem + lr * TL::EPI_ROWB + cc * 2;
+        T* dst = out + (int64_t)m * g.Co + col;
+        if (g.out_vec && col + 8 <= g.Co) {
+            *(u32x4*)dst = *(const u32x4*)src;
+        } else {
+            for (int e = 0; e < 8 && col + e < g.Co; ++e) dst[e] = ((const T*)src)[e];
+        }
+    }
+    if (stats) {
+        // column sums of the staged tile (rows past M hold zeros): thread = (row group, column)
+        constexpr int G = kThreads / BN;
+        const int c = tid % BN, rg = tid / BN;
+        float s0 = 0.f, s1 = 0.f;
+        for (int r = rg; r < BM; r += G) {
+            const float v = to_float<T>(*(const T*)(smem + r * TL::EPI_ROWB + c * 2));
+            s0 += v;
+            s1 += v * v;
+        }
+        double* sred = (double*)(smem + TL::EPI_BYTES);
+        sred[(rg * BN + c) * 2] = (double)s0;
+        sred[(rg * BN + c) * 2 + 1] = (double)s1;
+        __syncthreads();
+        if (rg == 0 && n0 + c < g.Co) {
+            double a = 0.0, b = 0.0;
+#pragma unroll
+            for (int k = 0; k < G; ++k) {
+                a += sred[(k * BN + c) * 2];
+                b += sred[(k * BN + c) * 2 + 1];
+            }
+            double* dst = stats + ((int64_t)(tile / tiles_n) * g.Co + n0 + c) * 2;
+            dst[0] = a;
+            dst[1] = b;
+        }
+    }
+}
+
 // ---- fp32 3x3 convolutions with 16 or 32 channels on both sides ----------------------------------
 // With so few channels the whole filter bank of 16 output channels fits in registers (9 * Ci / 16
 // 16-byte runs per lane), so no operand needs LDS: the MFMA computes y^T, D[co][pixel] with
@@ -1436,9 +1699,26 @@ inline int direct_grid(const GatherGeom& g)
 // CIFAR-sized layers) small tiles with long k steps: there the kernel is bound by the latency of the
 // gathers, and what helps is many workgroups with many bytes in flight each.
 // Returns the tile id used by dispatch_gather and the tile's row count.
+// The direct-to-LDS kernel: bf16, gathered channels a multiple of 64 (a k tile never straddles two taps), at most 32
+// taps (one mask word per row), no dilation, whole 128-wide column tiles, enough 256-row tiles for the chip, and a
+// long contraction (K >= 2304: with one workgroup per compute unit nothing overlaps a tile's prologue and epilogue,
+// which only long k loops amortise; measured: 3x3 layers of 256 / 512 channels gain 5-10 %, 128-channel ones lose 20 %).
+template <typename T>
+bool dma_wide(const GatherGeom& g)  // 256 x 256 tiles (half the LDS operand reads per MFMA) where enough of them exist
+{
+    return g.Co % 256 == 0 && tile_count(g, 256, 256) >= 192;
+}
+template <typename T>
+bool dma_eligible(const GatherGeom& g)
+{
+    return sizeof(T) == 2 && g.Ci % 64 == 0 && g.R * g.S <= 32 && g.idil == 1 && g.Co % 128 == 0 && g.Kdim >= 2304 &&
+           (tile_count(g, 256, 128) >= 192 || dma_wide<T>(g));
+}
+
 template <typename T>
 int select_gather_tile(const GatherGeom& g, int* bm)
 {
+    if (dma_eligible<T>(g)) { *bm = 256; return 20; }
     if (g.Co <= 16) {
         // (bf16 always takes the 64-row tile: measured in the four-stream resnet56 pipeline)
         if (sizeof(T) == 4 && tile_count(g, 256, 16) >= kEnoughTiles) { *bm = 256; return 0; }
@@ -1457,6 +1737,31 @@ int select_gather_tile(const GatherGeom& g, int* bm)
     if (tile_count(g, 64, 64) >= kEnoughTiles) { *bm = 64; return 6; }
     *bm = 32;
     return 8;
+}
+
+template <typename TL>
+int run_dma(const GatherGeom& g, const void* in, const void* w, void* out, hipStream_t st, double flops)
+{
+    const int64_t tiles = (int64_t)ceil_div(g.M, TL::BM) * ceil_div(g.Co, TL::BN);
+    DSP_REQUIRE(tiles > 0 && tiles < (1ll << 31), DSP_EINVAL, "conv: bad tile count");
+    auto kern = conv_dma_gemm_kernel<TL>;
+    static std::atomic<bool> attr_done{false};
+    if (!attr_done) {
+        DSP_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES));
+        attr_done = true;
+    }
+    static const KernelName name = [] {
+        KernelName k;
+        snprintf(k.text, sizeof(k.text), "conv_dma_gemm<bf16,mfma32,BM%d,BN%d,BK%d>", TL::BM, TL::BN, TL::BK);
+        return k;
+    }();
+    {
+        ProfScope ps(name.text, flops, 0);
+        DSP_LAUNCH(ps, kern, dim3((unsigned)tiles, g.in1 ? 2 : 1), dim3(kThreads), TL::LDS_BYTES, st, (const bf16_t*)in,
+                   (const bf16_t*)w, (bf16_t*)out, g);
+    }
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
 }
 
 template <typename T>
@@ -1484,7 +1789,24 @@ int dispatch_gather(GatherGeom g, bool accum, const void* in, const void* w, voi
     g.accum = accum ? 1 : 0;
     g.out_vec = ((g.Co % E) == 0 && ((uintptr_t)out % 16) == 0) ? 1 : 0;
     int bm;
-    switch (select_gather_tile<T>(g, &bm)) {
+    int id = select_gather_tile<T>(g, &bm);
+    if (id == 20) {
+        const bool aligned = vec && ((uintptr_t)g.in1 % 16) == 0 && ((uintptr_t)g.out1 % 16) == 0;
+        if (aligned && g.out_vec) {
+            if (dma_wide<T>(g)) return run_dma<DmaTile<256, 256, 2, 2, 64, 4>>(g, in, w, out, st, flops);
+            return run_dma<DmaTile<256, 128, 2, 2, 128, 3>>(g, in, w, out, st, flops);
+        }
+        // unaligned tensors (single-layer calls only) take the register-staged tiles; their row tiles differ
+        DSP_REQUIRE(g.stats == nullptr, DSP_EINVAL, "conv forward with column sums: x, w and y must be 16-byte aligned");
+        id = -1;
+    }
+    if (id < 0) {
+        if (g.Co % 128 == 0 && tile_count(g, 128, 128) >= kEnoughTiles) id = 4;
+        else if (tile_count(g, 128, 64) >= kEnoughTiles) id = 5;
+        else if (tile_count(g, 64, 64) >= kEnoughTiles) id = 6;
+        else id = 8;
+    }
+    switch (id) {
     case 0: return run_gather_v<Tile<T, 16, 4, 1, 4, 1, 64, 2>>(g, vec, in, w, out, st, flops);
     case 1: return run_gather_v<Tile<T, 16, 4, 1, 1, 1, 64, 2>>(g, vec, in, w, out, st, flops);
     case 2: return run_gather_v<Tile<T, 32, 4, 1, 2, 1, 64, 2>>(g, vec, in, w, out, st, flops);

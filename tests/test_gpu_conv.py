@@ -105,7 +105,10 @@ FULL = [
     (D.DSP_BF16, 64, 14, 14, 1024, 256, 1, 1, 1, 0),   # and reduction
     (D.DSP_BF16, 256, 28, 28, 128, 128, 3, 3, 1, 1),   # ResNet-18 stage 2 (128x128 tiles)
     (D.DSP_BF16, 256, 56, 56, 64, 128, 3, 3, 2, 1),    # ResNet-18 stage transition
-    (D.DSP_BF16, 256, 7, 7, 512, 512, 3, 3, 1, 1),     # ResNet-18 stage 4 (7x7 maps: pixel runs cross image rows)
+    (D.DSP_BF16, 256, 7, 7, 512, 512, 3, 3, 1, 1),     # ResNet-18 stage 4 (7x7 maps: pixel runs cross image rows; direct-to-LDS 256x128 tiles)
+    (D.DSP_BF16, 256, 14, 14, 256, 256, 3, 3, 1, 1),   # ResNet-18 stage 3 (direct-to-LDS 256x256 tiles)
+    (D.DSP_BF16, 250, 14, 14, 256, 256, 3, 3, 1, 1),   # the same with a ragged last row tile (M = 49000)
+    (D.DSP_BF16, 125, 14, 14, 256, 384, 3, 3, 1, 1),   # direct-to-LDS 256x128 tiles, three column tiles, ragged rows
 ]
 
 
