@@ -336,7 +336,10 @@ int dsp_pipeline_ticks(const dsp_pipeline* pl, int64_t* ticks);
 /*
  * Convolution kernels on NHWC device tensors of type `dtype`; filters in the library's layout:
  * d_w  = w[cout][r][s][cin] (forward / backward-weight), d_wt = w[cin][R-1-r][S-1-s][cout]
- * (backward-data).  dsp_conv_workspace_bytes() sizes d_workspace for backward-weight (split
+ * (backward-data, stride 1).  Backward-data of a stride-2 layer runs as four dense problems, one per parity
+ * class (hi % 2, wi % 2) of the input pixel, and takes d_wt class by class: classes in the order (0,0), (0,1),
+ * (1,0), (1,1); class (ph, pw) holds [cin][j][l][cout] for the taps r' = r0 + 2 j, s' = s0 + 2 l of the flipped
+ * filter w[cin][r'][s'][cout], r0 = (R-1-pad - ph) mod 2, s0 = (S-1-pad - pw) mod 2 (the same elements, reordered).  dsp_conv_workspace_bytes() sizes d_workspace for backward-weight (split
  * reduction partials).  accumulate != 0 adds into d_dx instead of overwriting.
  */
 int dsp_conv_forward(int32_t dtype, const void* d_x, const void* d_w, void* d_y, int32_t N, int32_t H, int32_t W,

@@ -134,6 +134,7 @@ struct dsp_block {
     float *x = nullptr, *v = nullptr, *g = nullptr;
     int32_t* tmap = nullptr;        // index table of the filter copies that are no plain transposition (padded stem filters)
     UpdateTask* upd_tasks = nullptr;  // how the update kernel walks the flat arrays (device copy)
+    int32_t* tap_tab = nullptr;       // per conv layer and tap: where that tap's filters sit in the backward-data copy
     int upd_n_tasks = 0, upd_blocks = 0;
     void* wf16 = nullptr;  // bf16 copy of x in the same layout (bf16 blocks only)
     void* wt = nullptr;    // backward-data filter copies [cin][R-1-r][S-1-s][cout] in the storage type
@@ -348,6 +349,7 @@ static int build_graph(dsp_block* b)
     b->perm.resize(b->nP);
     std::vector<int32_t> tmap(b->nP, -1);
     std::vector<UpdateTask> tasks;
+    std::vector<int32_t> tap_tab;
     auto flat_task = [&](size_t p0, size_t n, bool decay) {
         if (n == 0) return;
         if (!tasks.empty() && tasks.back().kind == 0 && tasks.back().decay == (decay ? 1 : 0) &&
@@ -381,6 +383,24 @@ static int build_graph(dsp_block* b)
                 UpdateTask t{};
                 t.kind = 1; t.decay = 1; t.p0 = (uint32_t)L.p0; t.n = (uint32_t)n; t.wt_off = (uint32_t)L.wt_off;
                 t.Co = Co; t.Ci = Ci; t.R = R; t.S = S; t.J = R * S * Ci;
+                t.tap_tab = (int)tap_tab.size();
+                DgradClass cls[4];
+                if (L.d.stride == 2) dgrad_classes(L.cs, cls);
+                for (int r = 0; r < R; ++r)
+                    for (int s = 0; s < S; ++s) {
+                        const int rf = R - 1 - r, sf = S - 1 - s;  // tap of the flipped filter
+                        if (L.d.stride == 2) {
+                            const int padh = R - 1 - L.d.pad, padw = S - 1 - L.d.pad;
+                            const int ph = ((padh - rf) % 2 + 2) % 2, pw = ((padw - sf) % 2 + 2) % 2;
+                            const DgradClass& k = cls[ph * 2 + pw];
+                            const int jj = (rf - k.r0) / 2, ll = (sf - k.s0) / 2;
+                            tap_tab.push_back((int32_t)(k.wt_off + ((size_t)jj * k.Sc + ll) * Co));
+                            tap_tab.push_back((int32_t)((size_t)k.Rc * k.Sc * Co));
+                        } else {
+                            tap_tab.push_back((int32_t)(((size_t)rf * S + sf) * Co));
+                            tap_tab.push_back((int32_t)((size_t)R * S * Co));
+                        }
+                    }
                 tasks.push_back(t);
             } else {
                 flat_task(L.p0, n, true);
@@ -407,6 +427,9 @@ static int build_graph(dsp_block* b)
     DSP_TRY(dev_alloc(b, (void**)&b->upd_tasks, tasks.size() * sizeof(UpdateTask), &b->param_bytes));
     if (!tasks.empty())
         DSP_HIP(hipMemcpy(b->upd_tasks, tasks.data(), tasks.size() * sizeof(UpdateTask), hipMemcpyHostToDevice));
+    DSP_TRY(dev_alloc(b, (void**)&b->tap_tab, tap_tab.size() * sizeof(int32_t), &b->param_bytes));
+    if (!tap_tab.empty())
+        DSP_HIP(hipMemcpy(b->tap_tab, tap_tab.data(), tap_tab.size() * sizeof(int32_t), hipMemcpyHostToDevice));
     DSP_TRY(dev_alloc(b, (void**)&b->tmap, b->nP * 4, &b->param_bytes));
     DSP_TRY(dev_alloc(b, &b->wt, b->wt_elems * esz, &b->param_bytes));
     DSP_HIP(hipMemset(b->wt, 0, b->wt_elems * esz ? b->wt_elems * esz : 16));  // the zero channels of padded filters stay zero
@@ -694,7 +717,7 @@ int block_load_params_device(dsp_block* b, const float* d_src, hipStream_t st)
 {
     if (b->nP == 0) return DSP_OK;
     DSP_HIP(hipMemcpyAsync(b->x, d_src, b->nP * 4, hipMemcpyDeviceToDevice, st));
-    return launch_refresh_shadows(b->dtype, b->x, b->upd_tasks, b->upd_n_tasks, b->upd_blocks, b->tmap, b->wf16, b->wt, b->nP, st);
+    return launch_refresh_shadows(b->dtype, b->x, b->upd_tasks, b->upd_n_tasks, b->upd_blocks, b->tmap, b->tap_tab, b->wf16, b->wt, b->nP, st);
 }
 
 }  // namespace dsp
@@ -719,7 +742,7 @@ int dsp_block_init(const dsp_block_desc* desc, const float* h_params, size_t n_p
         rc = DSP_EINVAL;
     }
     if (rc == DSP_OK) rc = upload_params(b, h_params, b->x);
-    if (rc == DSP_OK) rc = launch_refresh_shadows(b->dtype, b->x, b->upd_tasks, b->upd_n_tasks, b->upd_blocks, b->tmap, b->wf16, b->wt, b->nP, nullptr);
+    if (rc == DSP_OK) rc = launch_refresh_shadows(b->dtype, b->x, b->upd_tasks, b->upd_n_tasks, b->upd_blocks, b->tmap, b->tap_tab, b->wf16, b->wt, b->nP, nullptr);
     if (rc == DSP_OK && hipDeviceSynchronize() != hipSuccess) {
         set_error("dsp_block_init: device synchronisation failed");
         rc = DSP_EHIP;
@@ -921,7 +944,7 @@ int dsp_param_update_sum(dsp_block* b, float lr, float momentum, int32_t s, floa
         b->last_lr = lr;
     }
     if (b->dry) return DSP_OK;
-    DSP_TRY(launch_sgd_update(b->dtype, b->x, b->v, b->g, b->upd_tasks, b->upd_n_tasks, b->upd_blocks, b->tmap, b->wf16, b->wt,
+    DSP_TRY(launch_sgd_update(b->dtype, b->x, b->v, b->g, b->upd_tasks, b->upd_n_tasks, b->upd_blocks, b->tmap, b->tap_tab, b->wf16, b->wt,
                               b->nP, lr, momentum, weight_decay, (hipStream_t)stream, s == 1, v_scale));
     return DSP_OK;
 }
@@ -981,7 +1004,7 @@ int dsp_block_set_params(dsp_block* b, const float* h_src, size_t n)
     DSP_REQUIRE(b && h_src && n == b->nP, DSP_EINVAL, "dsp_block_set_params: bad argument");
     DSP_HIP(hipDeviceSynchronize());
     DSP_TRY(upload_params(b, h_src, b->x));
-    DSP_TRY(launch_refresh_shadows(b->dtype, b->x, b->upd_tasks, b->upd_n_tasks, b->upd_blocks, b->tmap, b->wf16, b->wt, b->nP, nullptr));
+    DSP_TRY(launch_refresh_shadows(b->dtype, b->x, b->upd_tasks, b->upd_n_tasks, b->upd_blocks, b->tmap, b->tap_tab, b->wf16, b->wt, b->nP, nullptr));
     DSP_HIP(hipDeviceSynchronize());
     return DSP_OK;
 }

@@ -156,7 +156,17 @@ struct ConvForwardTwin {
 int launch_conv_forward(int dtype, const ConvShape& c, const void* x, const void* w, void* y, hipStream_t st,
                         double* column_sums = nullptr, const ConvForwardTwin* twin = nullptr);
 int conv_forward_row_tiles(int dtype, const ConvShape& c);
-// dx (+)= conv^T(dy, w);  wt in [Cin][R-1-r][S-1-s][Cout].
+// dx (+)= conv^T(dy, w);  wt in [Cin][R-1-r][S-1-s][Cout] for stride 1.  For stride 2 the copy is stored class by
+// class (dgrad_classes): class (hi % 2, wi % 2) of the input pixels uses the taps r' = r0 + 2 j, s' = s0 + 2 l of the
+// flipped filter, kept as [Cin][j][l][Cout] at element offset wt_off; the classes follow each other.
+struct DgradClass {
+    int Rc, Sc;        // taps of the class per direction (0: no tap reaches these pixels)
+    int r0, s0;        // its first tap of the flipped filter
+    int off_h, off_w;  // class pixel (a, b) reads source pixels (a + off_h + j, b + off_w + l)
+    int Hc, Wc;        // pixels of the class per direction
+    size_t wt_off;     // first element of its filters in the copy
+};
+void dgrad_classes(const ConvShape& c, DgradClass (&cls)[4]);
 int launch_conv_backward_data(int dtype, const ConvShape& c, const void* dy, const void* wt, void* dx,
                               bool accumulate, hipStream_t st);
 // dw[Cout][R][S][Cin] (float) = sum over (n, ho, wo) of dy * x;  ws holds the split partials.
@@ -247,15 +257,17 @@ struct UpdateTask {
     uint32_t p0, n;    // first element and length in the flat arrays
     uint32_t wt_off;   // kind 1: first element of the copy in wt
     int Co, J, Ci, R, S;  // kind 1: J = R * S * Ci
+    int tap_tab;          // kind 1: first entry of this layer in the tap table: per tap (r * S + s) the element offset of
+                          // (ci = 0, co = 0) of that tap inside the copy and the stride between consecutive ci
     int tiles_j, block_begin, aligned, wt_aligned;  // filled by update_plan_finish
 };
 int update_plan_finish(std::vector<UpdateTask>& tasks, int dtype, int* total_blocks);
 int launch_sgd_update(int dtype, float* x, float* v, const float* g, const UpdateTask* tasks, int n_tasks, int blocks,
-                      const int32_t* tmap, void* wf16, void* wt, size_t n, float lr, float momentum, float wd, hipStream_t st,
-                      bool nesterov = false, float v_scale = 1.f);
+                      const int32_t* tmap, const int32_t* tap_tab, void* wf16, void* wt, size_t n, float lr, float momentum,
+                      float wd, hipStream_t st, bool nesterov = false, float v_scale = 1.f);
 // Same refresh of the copies without an update (after init / set_params).
 int launch_refresh_shadows(int dtype, const float* x, const UpdateTask* tasks, int n_tasks, int blocks, const int32_t* tmap,
-                           void* wf16, void* wt, size_t n, hipStream_t st);
+                           const int32_t* tap_tab, void* wf16, void* wt, size_t n, hipStream_t st);
 int launch_spin(int microseconds, hipStream_t st);
 // dst[p][0..Cp) = {src[p][0..C), 0...}: channel padding of an NHWC tensor (pixels rows) up to a whole 16-byte run.
 // y = a + b over n elements; backward of the sum: dx0 (and dx1, unless null) = dy or += dy, one read of dy

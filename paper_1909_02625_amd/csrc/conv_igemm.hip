@@ -217,6 +217,10 @@ struct GatherGeom {
     uint32_t wo_mul, wo_sh, ho_mul, ho_sh;  // m / Wo and (m / Wo) / Ho by multiplication (fast_div)
     int accum;     // add to `out` instead of overwriting it
     int out_vec;  // `out` rows can be written as whole 16-byte runs
+    // Output row of tile row m = (n, ho, wo): pixel (n, ho * oh_mul + oh_off, wo * ow_mul + ow_off) of an N x OH x OW
+    // map; oh_mul = 0 means the rows are simply consecutive (the usual case).  Backward-data of a stride-2
+    // convolution runs as four dense problems, one per parity class of the input pixel, each writing its own pixels.
+    int oh_mul, ow_mul, oh_off, ow_off, OH, OW;
     // if set: per row tile, the column sums {sum y, sum y^2} of the values as stored, [row tile][Co][2];
     // lets the batch norm that consumes `out` skip its own pass over the tensor
     double* stats;
@@ -240,6 +244,15 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes
 __device__ inline u32x4 load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off)
 {
     return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0));
+}
+
+// Row of `out` that tile row m is written to (see GatherGeom::oh_mul).
+__device__ inline int64_t out_row(const GatherGeom& g, int m)
+{
+    if (g.oh_mul == 0) return m;
+    const int t = (int)fast_div((uint32_t)m, g.wo_mul, g.wo_sh), wo = m - t * g.Wo;
+    const int n = (int)fast_div((uint32_t)t, g.ho_mul, g.ho_sh), ho = t - n * g.Ho;
+    return ((int64_t)n * g.OH + ho * g.oh_mul + g.oh_off) * g.OW + wo * g.ow_mul + g.ow_off;
 }
 
 // Workgroups are handed to the 8 XCDs round-robin by workgroup id, and each XCD has an L2 of its own.
@@ -475,15 +488,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
                     const int lcol = (wave_n * TL::TN + j) * TL::MT + acc_row<TL::MT>(lane, 4 * q);
                     const int col = n0 + lcol;
                     if (g.accum && m < g.M) {
+                        const T* old = out + out_row(g, m) * g.Co + col;
                         if (g.out_vec && col + 4 <= g.Co) {
                             float o[4];
-                            Run4<T>::unpack(*(const RunV*)(out + (int64_t)m * g.Co + col), o);
+                            Run4<T>::unpack(*(const RunV*)old, o);
 #pragma unroll
                             for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += o[e];
                         } else {
 #pragma unroll
                             for (int e = 0; e < 4; ++e)
-                                if (col + e < g.Co) acc[i][j][4 * q + e] += to_float<T>(out[(int64_t)m * g.Co + col + e]);
+                                if (col + e < g.Co) acc[i][j][4 * q + e] += to_float<T>(old[e]);
                         }
                     }
                     *(RunV*)(smem + lrow * TL::EPI_ROWB + lcol * (int)sizeof(T)) =
@@ -500,7 +514,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
 #pragma unroll
                     for (int e = 0; e < kAcc; ++e) {
                         const int m = m0 + (wave_m * TL::TM + i) * TL::MT + acc_row<TL::MT>(lane, e);
-                        if (m < g.M && col < g.Co) acc[i][j][e] += to_float<T>(out[(int64_t)m * g.Co + col]);
+                        if (m < g.M && col < g.Co) acc[i][j][e] += to_float<T>(out[out_row(g, m) * g.Co + col]);
                     }
                 }
         }
@@ -523,7 +537,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
         const int m = m0 + lrow, col = n0 + cc;
         if (m >= g.M || col >= g.Co) continue;
         const char* src = smem + lrow * TL::EPI_ROWB + cc * (int)sizeof(T);
-        T* dst = out + (int64_t)m * g.Co + col;
+        T* dst = out + out_row(g, m) * g.Co + col;
         if (g.out_vec && col + E <= g.Co) {
             *(u32x4*)dst = *(const u32x4*)src;
         } else {
@@ -1666,9 +1680,9 @@ int run_gather(const GatherGeom& g, const void* in, const void* w, void* out, hi
 template <typename TL>
 int run_gather_v(const GatherGeom& g, bool vec, const void* in, const void* w, void* out, hipStream_t st, double flops)
 {
-    // the element-wise path handles dilation with run-time tests; the vector path has a kernel of its own for it
+    // (backward-data of strided layers arrives here as dense per-parity-class problems, so no launch dilates)
     if (!vec) return run_gather<TL, false, false>(g, in, w, out, st, flops);
-    return g.idil == 2 ? run_gather<TL, true, true>(g, in, w, out, st, flops) : run_gather<TL, true, false>(g, in, w, out, st, flops);
+    return run_gather<TL, true, false>(g, in, w, out, st, flops);
 }
 
 // Enough workgroups to put more than one on each of the 256 compute units.
@@ -1711,7 +1725,7 @@ bool dma_wide(const GatherGeom& g)  // 256 x 256 tiles (half the LDS operand rea
 template <typename T>
 bool dma_eligible(const GatherGeom& g)
 {
-    return sizeof(T) == 2 && g.Ci % 64 == 0 && g.R * g.S <= 32 && g.idil == 1 && g.Co % 128 == 0 && g.Kdim >= 2304 &&
+    return sizeof(T) == 2 && g.Ci % 64 == 0 && g.R * g.S <= 32 && g.idil == 1 && g.oh_mul == 0 && g.Co % 128 == 0 && g.Kdim >= 2304 &&
            (tile_count(g, 256, 128) >= 192 || dma_wide<T>(g));
 }
 
@@ -2088,16 +2102,63 @@ int launch_conv_forward(int dtype, const ConvShape& c, const void* x, const void
                              : dispatch_gather<float>(g, false, x, w, y, st, flops);
 }
 
+void dgrad_classes(const ConvShape& c, DgradClass (&cls)[4])
+{
+    // dx[hi] sums dy[(hi - padh + r') / stride] * wt[r'] over the taps r' of the flipped filter for which the division
+    // is exact.  For stride 2 that fixes the parity of r' by the parity of hi: class ph takes r' = r0, r0 + 2, ...
+    // and reads the source rows a + off + j for its a-th pixel -- a dense stride-1 problem.
+    const int padh = c.R - 1 - c.pad, padw = c.S - 1 - c.pad;
+    size_t off = 0;
+    for (int ph = 0; ph < 2; ++ph)
+        for (int pw = 0; pw < 2; ++pw) {
+            DgradClass& k = cls[ph * 2 + pw];
+            k.r0 = ((padh - ph) % 2 + 2) % 2;
+            k.s0 = ((padw - pw) % 2 + 2) % 2;
+            k.Rc = k.r0 < c.R ? (c.R - k.r0 + 1) / 2 : 0;
+            k.Sc = k.s0 < c.S ? (c.S - k.s0 + 1) / 2 : 0;
+            k.off_h = (ph - padh + k.r0) / 2;   // exact: the numerator is even
+            k.off_w = (pw - padw + k.s0) / 2;
+            k.Hc = (c.H - ph + 1) / 2;
+            k.Wc = (c.W - pw + 1) / 2;
+            k.wt_off = off;
+            off += (size_t)c.Cin * k.Rc * k.Sc * c.Cout;
+        }
+}
+
 int launch_conv_backward_data(int dtype, const ConvShape& c, const void* dy, const void* wt, void* dx,
                               bool accumulate, hipStream_t st)
 {
     DSP_TRY(check_shape(c));
     DSP_REQUIRE(c.stride == 1 || c.stride == 2, DSP_EINVAL, "conv backward-data: stride %d unsupported", c.stride);
-    // dx[n,hi,wi,ci] = sum_{r',s',co} dy[n, (hi - (R-1-pad) + r')/stride, ...][co] * wt[ci][r'][s'][co]
-    GatherGeom g = make_geom(c.N, c.Ho, c.Wo, c.Cout, c.H, c.W, c.Cin, c.R, c.S, c.R - 1 - c.pad, c.S - 1 - c.pad, 1, c.stride);
     const double flops = 2.0 * conv_macs(c);
-    return dtype == DSP_BF16 ? dispatch_gather<bf16_t>(g, accumulate, dy, wt, dx, st, flops)
-                             : dispatch_gather<float>(g, accumulate, dy, wt, dx, st, flops);
+    if (c.stride == 1) {
+        // dx[n,hi,wi,ci] = sum_{r',s',co} dy[n, hi - (R-1-pad) + r', ...][co] * wt[ci][r'][s'][co]
+        GatherGeom g = make_geom(c.N, c.Ho, c.Wo, c.Cout, c.H, c.W, c.Cin, c.R, c.S, c.R - 1 - c.pad, c.S - 1 - c.pad, 1, 1);
+        return dtype == DSP_BF16 ? dispatch_gather<bf16_t>(g, accumulate, dy, wt, dx, st, flops)
+                                 : dispatch_gather<float>(g, accumulate, dy, wt, dx, st, flops);
+    }
+    // stride 2: one dense problem per parity class of the input pixel (hi % 2, wi % 2); together they perform exactly
+    // the multiply-accumulates of the definition (none on the zeros between the strided gradient's pixels)
+    DgradClass cls[4];
+    dgrad_classes(c, cls);
+    double taps = 0;
+    for (const DgradClass& k : cls) taps += (double)k.Rc * k.Sc * k.Hc * k.Wc;
+    for (int q = 0; q < 4; ++q) {
+        const DgradClass& k = cls[q];
+        if (k.Hc == 0 || k.Wc == 0) continue;
+        const bool empty = k.Rc == 0 || k.Sc == 0;  // no tap reaches these pixels: their gradient is zero
+        if (empty && accumulate) continue;
+        GatherGeom g = make_geom(c.N, c.Ho, c.Wo, c.Cout, k.Hc, k.Wc, c.Cin, empty ? 1 : k.Rc, empty ? 1 : k.Sc, -k.off_h,
+                                 -k.off_w, 1, 1);
+        if (empty) g.Kdim = 0;
+        g.oh_mul = 2; g.ow_mul = 2; g.oh_off = q >> 1; g.ow_off = q & 1; g.OH = c.H; g.OW = c.W;
+        const size_t esz = dtype_size(dtype);
+        const void* wq = (const char*)wt + k.wt_off * esz;
+        const double fq = taps > 0 ? flops * ((double)k.Rc * k.Sc * k.Hc * k.Wc / taps) : 0.0;
+        DSP_TRY(dtype == DSP_BF16 ? dispatch_gather<bf16_t>(g, accumulate, dy, wq, dx, st, fq)
+                                  : dispatch_gather<float>(g, accumulate, dy, wq, dx, st, fq));
+    }
+    return DSP_OK;
 }
 
 size_t conv_backward_weight_workspace(const ConvShape& c)

@@ -285,7 +285,8 @@ template <typename TS, bool UPDATE, bool NESTEROV = false>
 __global__ __launch_bounds__(kThreads) void sgd_update_kernel(float* __restrict__ x, float* __restrict__ v,
                                                               const float* __restrict__ g,
                                                               const UpdateTask* __restrict__ tasks, int n_tasks,
-                                                              const int32_t* __restrict__ tmap, bf16_t* __restrict__ wf16,
+                                                              const int32_t* __restrict__ tmap,
+                                                              const int32_t* __restrict__ tap_tab, bf16_t* __restrict__ wf16,
                                                               TS* __restrict__ wt, float lr, float momentum, float wd,
                                                               float v_scale)
 {
@@ -390,8 +391,8 @@ __global__ __launch_bounds__(kThreads) void sgd_update_kernel(float* __restrict_
         for (int pass = 0; pass < kUpdTile / ROWS; ++pass) {
             const int jl = jr + ROWS * pass, j = j0 + jl;
             if (j >= t.J || co >= t.Co) continue;
-            const int ci = j % t.Ci, tap = j / t.Ci, r = tap / t.S, s2 = tap % t.S;
-            TS* dst = wt + (size_t)t.wt_off + ((size_t)(ci * t.R + (t.R - 1 - r)) * t.S + (t.S - 1 - s2)) * t.Co + co;
+            const int ci = j % t.Ci, tap = j / t.Ci;
+            TS* dst = wt + (size_t)t.wt_off + (size_t)tap_tab[t.tap_tab + 2 * tap] + (size_t)ci * tap_tab[t.tap_tab + 2 * tap + 1] + co;
             if (t.wt_aligned && co + E <= t.Co) {
                 float f[E];
 #pragma unroll
@@ -592,7 +593,7 @@ int update_plan_finish(std::vector<UpdateTask>& tasks, int dtype, int* total_blo
             t.tiles_j = ceil_div(t.J, kUpdTile);
             blocks += ceil_div(t.Co, kUpdTile) * t.tiles_j;
             const int E = dtype == DSP_BF16 ? 8 : 4;
-            t.wt_aligned = (t.Co % E == 0 && t.wt_off % E == 0) ? 1 : 0;
+            t.wt_aligned = (t.Co % E == 0 && t.wt_off % E == 0) ? 1 : 0;  // every tap base and ci stride is a multiple of Co
             t.aligned = (t.p0 % 4 == 0 && t.J % 4 == 0) ? 1 : 0;
         }
         if (t.kind == 0) t.aligned = (t.p0 % 4 == 0) ? 1 : 0;
@@ -603,8 +604,8 @@ int update_plan_finish(std::vector<UpdateTask>& tasks, int dtype, int* total_blo
 
 template <bool UPDATE>
 static int run_update(int dtype, float* x, float* v, const float* g, const UpdateTask* tasks, int n_tasks, int blocks,
-                      const int32_t* tmap, void* wf16, void* wt, size_t n, float lr, float momentum, float wd, hipStream_t st,
-                      bool nesterov, float v_scale)
+                      const int32_t* tmap, const int32_t* tap_tab, void* wf16, void* wt, size_t n, float lr, float momentum,
+                      float wd, hipStream_t st, bool nesterov, float v_scale)
 {
     if (n == 0 || blocks == 0) return DSP_OK;
     const dim3 grid(blocks);
@@ -612,7 +613,7 @@ static int run_update(int dtype, float* x, float* v, const float* g, const Updat
     ProfScope ps(dtype == DSP_BF16 ? "sgd_update<bf16 shadows>" : "sgd_update<fp32>", UPDATE ? (double)n * 24.0 : (double)n * 8.0, 1);
 #define UPD(TS, NES)                                                                                              \
     DSP_LAUNCH(ps, (sgd_update_kernel<TS, UPDATE, NES>), grid, dim3(kThreads), 0, st, x, v, g, tasks, n_tasks, tmap, \
-               (bf16_t*)wf16, (TS*)wt, lr, momentum, wd, v_scale)
+               tap_tab, (bf16_t*)wf16, (TS*)wt, lr, momentum, wd, v_scale)
     if (dtype == DSP_BF16) { if (nesterov) UPD(bf16_t, true); else UPD(bf16_t, false); }
     else                   { if (nesterov) UPD(float, true); else UPD(float, false); }
 #undef UPD
@@ -621,17 +622,17 @@ static int run_update(int dtype, float* x, float* v, const float* g, const Updat
 }
 
 int launch_sgd_update(int dtype, float* x, float* v, const float* g, const UpdateTask* tasks, int n_tasks, int blocks,
-                      const int32_t* tmap, void* wf16, void* wt, size_t n, float lr, float momentum, float wd, hipStream_t st,
-                      bool nesterov, float v_scale)
+                      const int32_t* tmap, const int32_t* tap_tab, void* wf16, void* wt, size_t n, float lr, float momentum,
+                      float wd, hipStream_t st, bool nesterov, float v_scale)
 {
-    return run_update<true>(dtype, x, v, g, tasks, n_tasks, blocks, tmap, dtype == DSP_BF16 ? wf16 : nullptr, wt, n, lr, momentum,
-                            wd, st, nesterov, v_scale);
+    return run_update<true>(dtype, x, v, g, tasks, n_tasks, blocks, tmap, tap_tab, dtype == DSP_BF16 ? wf16 : nullptr, wt, n, lr,
+                            momentum, wd, st, nesterov, v_scale);
 }
 
 int launch_refresh_shadows(int dtype, const float* x, const UpdateTask* tasks, int n_tasks, int blocks, const int32_t* tmap,
-                           void* wf16, void* wt, size_t n, hipStream_t st)
+                           const int32_t* tap_tab, void* wf16, void* wt, size_t n, hipStream_t st)
 {
-    return run_update<false>(dtype, const_cast<float*>(x), nullptr, nullptr, tasks, n_tasks, blocks, tmap,
+    return run_update<false>(dtype, const_cast<float*>(x), nullptr, nullptr, tasks, n_tasks, blocks, tmap, tap_tab,
                              dtype == DSP_BF16 ? wf16 : nullptr, wt, n, 0.f, 0.f, 0.f, st, false, 1.f);
 }
 

@@ -5,7 +5,7 @@ import torch
 
 import paper_1909_02625_amd as D
 from oracle import dsp_oracle as O
-from tests.gpu_harness import from_dev, rel_err, round_like, to_dev
+from tests.gpu_harness import dgrad_filter_copy, from_dev, rel_err, round_like, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -27,6 +27,10 @@ SHAPES = [
     (3, 10, 10, 32, 32, 3, 3, 1, 1),    # 32 -> 32 channels: register-resident filters, two channel groups
     (2, 9, 9, 32, 16, 3, 3, 1, 1),      # 32 -> 16
     (33, 32, 32, 16, 16, 3, 3, 1, 1),   # enough pixel groups that each wave walks several of them
+    (3, 11, 9, 16, 24, 3, 3, 2, 1),     # stride 2 on odd map sides: the four parity classes have different sizes
+    (2, 12, 12, 32, 64, 1, 1, 2, 0),    # 1x1 stride 2: three of the four classes receive no gradient at all
+    (2, 9, 9, 8, 16, 2, 2, 2, 0),       # 2x2 stride 2 without padding: one tap per class
+    (2, 14, 14, 8, 8, 5, 5, 2, 2),      # 5x5 stride 2: classes of 3x3, 3x2, 2x3 and 2x2 taps
 ]
 
 
@@ -49,7 +53,7 @@ def test_conv_forward_dgrad_wgrad(shape, dtype):
     td = torch.bfloat16 if dtype == D.DSP_BF16 else torch.float32
     d_x, d_dy = to_dev(x, dtype), to_dev(dy, dtype)
     d_w = torch.from_numpy(w.transpose(0, 2, 3, 1).copy()).to("cuda", td)                      # [co][r][s][ci]
-    d_wt = torch.from_numpy(w[:, :, ::-1, ::-1].transpose(1, 2, 3, 0).copy()).to("cuda", td)   # [ci][R-1-r][S-1-s][co]
+    d_wt = torch.from_numpy(dgrad_filter_copy(w, st, pd)).to("cuda", td)   # [ci][R-1-r][S-1-s][co] (stride 2: by parity class)
     d_y = torch.full((N * y_ref.shape[2] * y_ref.shape[3] * Co,), float("nan"), device="cuda", dtype=td)
     D.dsp_conv_forward(dtype, d_x, d_w, d_y, N, H, W, Ci, Co, R, S, st, pd)
     torch.cuda.synchronize()
@@ -129,7 +133,7 @@ def test_conv_full_size_sampled(cfg):
     td = torch.bfloat16 if dtype == D.DSP_BF16 else torch.float32
     d_x, d_dy = to_dev(x, dtype), to_dev(dy, dtype)
     d_w = torch.from_numpy(np.ascontiguousarray(w.transpose(0, 2, 3, 1))).to("cuda", td)
-    d_wt = torch.from_numpy(np.ascontiguousarray(w[:, :, ::-1, ::-1].transpose(1, 2, 3, 0))).to("cuda", td)
+    d_wt = torch.from_numpy(dgrad_filter_copy(w, st, pd)).to("cuda", td)
     # relative to the typical magnitude of the tensor: stored bf16 has 8 mantissa bits, fp32 sums ~1e-6
     tol = 1e-2 if dtype == D.DSP_BF16 else 1e-4
 
