@@ -77,6 +77,9 @@ typedef struct dsp_layer_desc {
     int32_t stride; /* conv/maxpool stride */
     int32_t pad;    /* conv/maxpool padding */
     int32_t relu;   /* BN only: apply ReLU after (BN + residual) */
+    int32_t groups; /* conv only: > 1 makes it a grouped convolution (aggregated transforms of ResNeXt): group g maps
+                       input channels [g cin/groups, (g+1) cin/groups) to output channels [g cout/groups, ...) with
+                       filters [cout][r][s][cin/groups]; 0 and 1 both mean an ordinary convolution */
 } dsp_layer_desc;
 
 /* One block of the split CNN and its place in DSP(p; m). */
@@ -352,6 +355,27 @@ int dsp_conv_backward_weight(int32_t dtype, const void* d_x, const void* d_dy, f
                              int32_t pad, void* d_workspace, size_t workspace_bytes, void* stream);
 int dsp_conv_workspace_bytes(int32_t N, int32_t H, int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s,
                              int32_t stride, int32_t pad, size_t* bytes);
+
+/*
+ * The same three kernels for a grouped convolution (the aggregated transforms of ResNeXt-29, one of the networks of
+ * the paper's speed-up table): `groups` divides cin and cout; group g maps input channels [g cin/groups,
+ * (g+1) cin/groups) to output channels [g cout/groups, (g+1) cout/groups).  Tensors keep all cin (cout) channels per
+ * pixel.  d_w = w[cout][r][s][cin/groups] (the output channel selects the group); d_wt (stride 1) =
+ * w[g cin/groups + ci][R-1-r][S-1-s][co within the group]: cin rows of r*s*cout/groups elements; for stride 2 the
+ * same class-by-class order as above with these rows and runs.  d_dw has the layout of d_w.  groups = 1 is the
+ * ordinary convolution.  Errors: DSP_EINVAL if groups does not divide the channel counts, else as above.
+ */
+int dsp_grouped_conv_forward(int32_t dtype, const void* d_x, const void* d_w, void* d_y, int32_t N, int32_t H, int32_t W,
+                             int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride, int32_t pad, int32_t groups,
+                             void* stream);
+int dsp_grouped_conv_backward_data(int32_t dtype, const void* d_dy, const void* d_wt, void* d_dx, int32_t N, int32_t H,
+                                   int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride, int32_t pad,
+                                   int32_t groups, int32_t accumulate, void* stream);
+int dsp_grouped_conv_backward_weight(int32_t dtype, const void* d_x, const void* d_dy, float* d_dw, int32_t N, int32_t H,
+                                     int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride, int32_t pad,
+                                     int32_t groups, void* d_workspace, size_t workspace_bytes, void* stream);
+int dsp_grouped_conv_workspace_bytes(int32_t N, int32_t H, int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s,
+                                     int32_t stride, int32_t pad, int32_t groups, size_t* bytes);
 
 /*
  * The other layers of a block (the paper names networks, not layers; these are the textbook definitions

@@ -76,8 +76,19 @@ def _f64(a):
 
 
 # --------------------------------------------------------------------------- layers (fp64, NCHW)
-def conv2d_forward(x, w, stride, pad):
+def _per_group(groups, x_channels, w):
+    """Channel ranges of a grouped convolution: group g maps input channels [g Ci, (g+1) Ci) to output channels
+    [g Co, (g+1) Co) with the filters w[g Co : (g+1) Co] (shape Co_total x Ci x R x S)."""
+    K, Ci = w.shape[0], w.shape[1]
+    assert x_channels == Ci * groups and K % groups == 0, (x_channels, w.shape, groups)
+    Co = K // groups
+    return [(slice(g * Ci, (g + 1) * Ci), slice(g * Co, (g + 1) * Co)) for g in range(groups)]
+
+
+def conv2d_forward(x, w, stride, pad, groups=1):
     x, w = _f64(x), _f64(w)
+    if groups > 1:  # every group is an ordinary convolution of its own channel range
+        return np.concatenate([conv2d_forward(x[:, ci], w[co], stride, pad) for ci, co in _per_group(groups, x.shape[1], w)], axis=1)
     N, C, H, W = x.shape
     K, C2, R, S = w.shape
     assert C == C2
@@ -87,8 +98,12 @@ def conv2d_forward(x, w, stride, pad):
     return y
 
 
-def conv2d_backward_data(dy, w, x_shape, stride, pad):
+def conv2d_backward_data(dy, w, x_shape, stride, pad, groups=1):
     dy, w = _f64(dy), _f64(w)
+    if groups > 1:
+        N, C, H, W = x_shape
+        return np.concatenate([conv2d_backward_data(dy[:, co], w[co], (N, C // groups, H, W), stride, pad)
+                               for ci, co in _per_group(groups, C, w)], axis=1)
     N, C, H, W = x_shape
     K, _, R, S = w.shape
     dx = np.empty(x_shape)
@@ -96,8 +111,12 @@ def conv2d_backward_data(dy, w, x_shape, stride, pad):
     return dx
 
 
-def conv2d_backward_weight(x, dy, w_shape, stride, pad):
+def conv2d_backward_weight(x, dy, w_shape, stride, pad, groups=1):
     x, dy = _f64(x), _f64(dy)
+    if groups > 1:
+        K, Ci, R, S = w_shape
+        rng = [(slice(g * Ci, (g + 1) * Ci), slice(g * (K // groups), (g + 1) * (K // groups))) for g in range(groups)]
+        return np.concatenate([conv2d_backward_weight(x[:, ci], dy[:, co], (K // groups, Ci, R, S), stride, pad) for ci, co in rng], axis=0)
     N, C, H, W = x.shape
     K, _, R, S = w_shape
     dw = np.empty(w_shape)
@@ -109,12 +128,14 @@ def conv2d_backward_weight(x, dy, w_shape, stride, pad):
 # For parity checks at sizes where the full fp64 convolution would take minutes: each requested element
 # is one sum over its receptive field (forward / backward-data) or over all output pixels
 # (backward-weight), written independently of the C loops above.
-def conv2d_forward_at(x, w, stride, pad, idx):
-    """y[n, k, ho, wo] for every (n, k, ho, wo) in idx; y = cross-correlation of x (NCHW) with w (KCRS)."""
+def conv2d_forward_at(x, w, stride, pad, idx, groups=1):
+    """y[n, k, ho, wo] for every (n, k, ho, wo) in idx; y = cross-correlation of x (NCHW) with w (KCRS); with groups,
+    output channel k sees only the input channels of its group."""
     _, _, H, W = x.shape
-    _, _, R, S = w.shape
+    K, Ci, R, S = w.shape
     out = np.zeros(len(idx))
     for i, (n, k, ho, wo) in enumerate(idx):
+        c0 = (k // (K // groups)) * Ci
         acc = 0.0
         for r in range(R):
             hi = ho * stride - pad + r
@@ -124,17 +145,21 @@ def conv2d_forward_at(x, w, stride, pad, idx):
                 wi = wo * stride - pad + s
                 if wi < 0 or wi >= W:
                     continue
-                acc += float(np.dot(x[n, :, hi, wi].astype(np.float64), w[k, :, r, s].astype(np.float64)))
+                acc += float(np.dot(x[n, c0:c0 + Ci, hi, wi].astype(np.float64), w[k, :, r, s].astype(np.float64)))
         out[i] = acc
     return out
 
 
-def conv2d_backward_data_at(dy, w, x_shape, stride, pad, idx):
-    """dx[n, c, hi, wi] for every (n, c, hi, wi) in idx: sum over the outputs (k, ho, wo) that x[n, c, hi, wi] fed."""
+def conv2d_backward_data_at(dy, w, x_shape, stride, pad, idx, groups=1):
+    """dx[n, c, hi, wi] for every (n, c, hi, wi) in idx: sum over the outputs (k, ho, wo) that x[n, c, hi, wi] fed
+    (with groups: the output channels of the group of c)."""
     _, _, Ho, Wo = dy.shape
-    _, _, R, S = w.shape
+    K, Ci, R, S = w.shape
+    Co = K // groups
     out = np.zeros(len(idx))
     for i, (n, c, hi, wi) in enumerate(idx):
+        g, cl = c // Ci, c % Ci
+        ks = slice(g * Co, (g + 1) * Co)
         acc = 0.0
         for r in range(R):
             th = hi + pad - r
@@ -144,17 +169,19 @@ def conv2d_backward_data_at(dy, w, x_shape, stride, pad, idx):
                 tw = wi + pad - s
                 if tw < 0 or tw % stride or tw // stride >= Wo:
                     continue
-                acc += float(np.dot(dy[n, :, th // stride, tw // stride].astype(np.float64), w[:, c, r, s].astype(np.float64)))
+                acc += float(np.dot(dy[n, ks, th // stride, tw // stride].astype(np.float64), w[ks, cl, r, s].astype(np.float64)))
         out[i] = acc
     return out
 
 
-def conv2d_backward_weight_at(x, dy, stride, pad, idx):
-    """dw[k, c, r, s] for every (k, c, r, s) in idx: sum over all (n, ho, wo) of dy[n, k, ho, wo] * x[n, c, hi, wi]."""
-    _, _, H, W = x.shape
-    _, _, Ho, Wo = dy.shape
+def conv2d_backward_weight_at(x, dy, stride, pad, idx, groups=1):
+    """dw[k, c, r, s] for every (k, c, r, s) in idx: sum over all (n, ho, wo) of dy[n, k, ho, wo] * x[n, c, hi, wi]
+    (with groups, c counts inside the group of k: the input channel is (k // (K / groups)) * (C / groups) + c)."""
+    _, C, H, W = x.shape
+    _, K, Ho, Wo = dy.shape
     out = np.zeros(len(idx))
     for i, (k, c, r, s) in enumerate(idx):
+        c = (k // (K // groups)) * (C // groups) + c
         # output pixels whose tap (r, s) falls inside the image
         ho = np.array([o for o in range(Ho) if 0 <= o * stride - pad + r < H], dtype=np.int64)
         wo = np.array([o for o in range(Wo) if 0 <= o * stride - pad + s < W], dtype=np.int64)
@@ -282,7 +309,7 @@ class CNNBlock:
             x = src(L["in"])
             op = L["op"]
             if op == "conv":
-                T.append(rnd(conv2d_forward(x, rnd(prm["w"]), L["stride"], L["pad"])))
+                T.append(rnd(conv2d_forward(x, rnd(prm["w"]), L["stride"], L["pad"], L.get("groups", 1))))
                 aux.append(None)
             elif op == "bn":
                 z, mean, invstd = bn_forward(x, prm["gamma"], prm["beta"], self.eps)
@@ -348,9 +375,9 @@ class CNNBlock:
             x = src(L["in"])
             op = L["op"]
             if op == "conv":
-                grads[i]["w"] = conv2d_backward_weight(x, g, prm["w"].shape, L["stride"], L["pad"])
+                grads[i]["w"] = conv2d_backward_weight(x, g, prm["w"].shape, L["stride"], L["pad"], L.get("groups", 1))
                 if not (L["in"] == -1 and self.first_block):
-                    add(L["in"], conv2d_backward_data(g, rnd(prm["w"]), x.shape, L["stride"], L["pad"]))
+                    add(L["in"], conv2d_backward_data(g, rnd(prm["w"]), x.shape, L["stride"], L["pad"], L.get("groups", 1)))
             elif op == "bn":
                 mean, invstd, y = aux[i]
                 if L["relu"]:

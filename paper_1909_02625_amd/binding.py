@@ -24,6 +24,8 @@ __all__ = [
     "dsp_block_enable_forward_lane", "dsp_block_step", "dsp_pipeline_set_twin_launches",
     "dsp_pipeline_sync", "dsp_pipeline_losses", "dsp_pipeline_ticks",
     "dsp_conv_forward", "dsp_conv_backward_data", "dsp_conv_backward_weight", "dsp_conv_workspace_bytes",
+    "dsp_grouped_conv_forward", "dsp_grouped_conv_backward_data", "dsp_grouped_conv_backward_weight",
+    "dsp_grouped_conv_workspace_bytes",
     "dsp_conv_backward_weight_static", "dsp_conv_backward_weight_static_bytes",
     "dsp_bn_workspace_bytes", "dsp_bn_forward", "dsp_bn_backward", "dsp_maxpool_forward", "dsp_maxpool_backward",
     "dsp_add_forward", "dsp_add_backward", "dsp_gap_forward", "dsp_gap_backward", "dsp_linear_forward",
@@ -47,7 +49,7 @@ class DSPError(RuntimeError):
 
 
 class dsp_layer_desc(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("op", "in0", "in1", "cin", "cout", "r", "s", "stride", "pad", "relu")]
+    _fields_ = [(n, C.c_int32) for n in ("op", "in0", "in1", "cin", "cout", "r", "s", "stride", "pad", "relu", "groups")]
 
 
 class dsp_block_desc(C.Structure):
@@ -123,6 +125,10 @@ _SIGNATURES = {
     "dsp_conv_backward_data": [_i32, _vp, _vp, _vp] + [_i32] * 10 + [_vp],
     "dsp_conv_backward_weight": [_i32, _vp, _vp, _vp] + [_i32] * 9 + [_vp, _sz, _vp],
     "dsp_conv_workspace_bytes": [_i32] * 9 + [C.POINTER(_sz)],
+    "dsp_grouped_conv_forward": [_i32, _vp, _vp, _vp] + [_i32] * 10 + [_vp],
+    "dsp_grouped_conv_backward_data": [_i32, _vp, _vp, _vp] + [_i32] * 11 + [_vp],
+    "dsp_grouped_conv_backward_weight": [_i32, _vp, _vp, _vp] + [_i32] * 10 + [_vp, _sz, _vp],
+    "dsp_grouped_conv_workspace_bytes": [_i32] * 10 + [C.POINTER(_sz)],
     "dsp_conv_backward_weight_static": [_i32, _vp, _vp, _vp] + [_i32] * 9 + [_vp],
     "dsp_bn_workspace_bytes": [_i32, C.POINTER(_sz)],
     "dsp_bn_forward": [_i32, _vp, _vp, _vp, _vp, _vp, _f, _i64, _i32, _i32, _vp, _vp, _vp, _sz, _vp],
@@ -195,6 +201,7 @@ def make_block_desc(layers, in_shape, dtype, k, K, m_k, p_prev=0, needs_input_gr
         d.r, d.s = L.get("r", L.get("k", 0)), L.get("s", L.get("k", 0))
         d.stride, d.pad = L.get("stride", 1), L.get("pad", 0)
         d.relu = int(bool(L.get("relu", False)))
+        d.groups = int(L.get("groups", 1))
         if L["op"] in ("bn", "add") and L.get("res") is not None:
             d.in1 = L["res"]
     n, c, h, w = in_shape
@@ -418,6 +425,31 @@ def dsp_pipeline_ticks(pl):
 
 
 # ---- single layers ---------------------------------------------------------------------------------
+def dsp_grouped_conv_forward(dtype, d_x, d_w, d_y, N, H, W, cin, cout, r, s, stride, pad, groups, stream=None):
+    check(lib().dsp_grouped_conv_forward(dtype, _ptr(d_x), _ptr(d_w), _ptr(d_y), N, H, W, cin, cout, r, s, stride, pad, groups,
+                                         _stream(stream)), "dsp_grouped_conv_forward")
+
+
+def dsp_grouped_conv_backward_data(dtype, d_dy, d_wt, d_dx, N, H, W, cin, cout, r, s, stride, pad, groups, accumulate=False,
+                                   stream=None):
+    check(lib().dsp_grouped_conv_backward_data(dtype, _ptr(d_dy), _ptr(d_wt), _ptr(d_dx), N, H, W, cin, cout, r, s, stride, pad,
+                                               groups, int(accumulate), _stream(stream)), "dsp_grouped_conv_backward_data")
+
+
+def dsp_grouped_conv_backward_weight(dtype, d_x, d_dy, d_dw, N, H, W, cin, cout, r, s, stride, pad, groups, d_workspace,
+                                     workspace_bytes, stream=None):
+    check(lib().dsp_grouped_conv_backward_weight(dtype, _ptr(d_x), _ptr(d_dy), _ptr(d_dw), N, H, W, cin, cout, r, s, stride, pad,
+                                                 groups, _ptr(d_workspace), workspace_bytes, _stream(stream)),
+          "dsp_grouped_conv_backward_weight")
+
+
+def dsp_grouped_conv_workspace_bytes(N, H, W, cin, cout, r, s, stride, pad, groups):
+    out = C.c_size_t()
+    check(lib().dsp_grouped_conv_workspace_bytes(N, H, W, cin, cout, r, s, stride, pad, groups, C.byref(out)),
+          "dsp_grouped_conv_workspace_bytes")
+    return out.value
+
+
 def dsp_conv_forward(dtype, d_x, d_w, d_y, N, H, W, cin, cout, r, s, stride, pad, stream=None):
     check(lib().dsp_conv_forward(dtype, _ptr(d_x), _ptr(d_w), _ptr(d_y), N, H, W, cin, cout, r, s, stride, pad,
                                  _stream(stream)), "dsp_conv_forward")

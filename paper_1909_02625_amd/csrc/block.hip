@@ -220,21 +220,25 @@ static int build_graph(dsp_block* b)
         case DSP_OP_CONV:
             DSP_REQUIRE(!s.is_float && s.C == L.d.cin && L.d.cout > 0 && L.d.r > 0 && L.d.s > 0 && L.d.stride > 0 &&
                             L.d.pad >= 0, DSP_EINVAL, "layer %d: conv shape mismatch", i);
+            DSP_REQUIRE(L.d.groups >= 0 && L.d.groups < 65536 && L.d.cin % (L.d.groups > 1 ? L.d.groups : 1) == 0 &&
+                            L.d.cout % (L.d.groups > 1 ? L.d.groups : 1) == 0,
+                        DSP_EINVAL, "layer %d: %d groups do not divide the channels", i, L.d.groups);
         {
             const int run = 16 / (int)dtype_size(d.dtype);
+            const int G = L.d.groups > 1 ? L.d.groups : 1;
             int cin = L.d.cin;
-            if (L.d.in0 < 0 && !d.needs_input_grad && cin % run != 0) {
+            if (L.d.in0 < 0 && !d.needs_input_grad && cin % run != 0 && G == 1) {
                 L.cin_pad = (cin + run - 1) / run * run;
                 cin = L.cin_pad;
             }
-            L.cs = make_conv_shape(s.N, s.H, s.W, cin, L.d.cout, L.d.r, L.d.s, L.d.stride, L.d.pad);
+            L.cs = make_conv_shape(s.N, s.H, s.W, cin, L.d.cout, L.d.r, L.d.s, L.d.stride, L.d.pad, G);
             if (L.cin_pad) L.cs.cin_real = L.d.cin;
             DSP_REQUIRE(L.cs.Ho > 0 && L.cs.Wo > 0, DSP_EINVAL, "layer %d: empty conv output", i);
             t.C = L.d.cout; t.H = L.cs.Ho; t.W = L.cs.Wo;
             L.p0 = poff;
-            poff += (size_t)L.d.cout * L.d.cin * L.d.r * L.d.s;
+            poff += (size_t)L.d.cout * (L.d.cin / G) * L.d.r * L.d.s;
             L.wt_off = wtoff;
-            wtoff += (size_t)L.d.cout * cin * L.d.r * L.d.s;
+            wtoff += (size_t)L.d.cout * (cin / G) * L.d.r * L.d.s;
             break;
         }
         case DSP_OP_BN:
@@ -364,7 +368,8 @@ static int build_graph(dsp_block* b)
     for (int i = 0; i < d.n_layers; ++i) {
         const Layer& L = b->layers[i];
         if (L.d.op == DSP_OP_CONV) {
-            const int Co = L.d.cout, Ci = L.d.cin, R = L.d.r, S = L.d.s;
+            const int G = conv_groups(L.cs), Cog = L.d.cout / G;
+            const int Co = L.d.cout, Ci = L.d.cin / G, R = L.d.r, S = L.d.s;  // Ci: input channels of one group
             const size_t n = (size_t)Co * R * S * Ci;
             for (int co = 0; co < Co; ++co)
                 for (int r = 0; r < R; ++r)
@@ -382,7 +387,7 @@ static int build_graph(dsp_block* b)
             } else if (L.in0_grad) {
                 UpdateTask t{};
                 t.kind = 1; t.decay = 1; t.p0 = (uint32_t)L.p0; t.n = (uint32_t)n; t.wt_off = (uint32_t)L.wt_off;
-                t.Co = Co; t.Ci = Ci; t.R = R; t.S = S; t.J = R * S * Ci;
+                t.Co = Co; t.Ci = Ci; t.R = R; t.S = S; t.J = R * S * Ci; t.Cog = Cog;
                 t.tap_tab = (int)tap_tab.size();
                 DgradClass cls[4];
                 if (L.d.stride == 2) dgrad_classes(L.cs, cls);
@@ -394,11 +399,11 @@ static int build_graph(dsp_block* b)
                             const int ph = ((padh - rf) % 2 + 2) % 2, pw = ((padw - sf) % 2 + 2) % 2;
                             const DgradClass& k = cls[ph * 2 + pw];
                             const int jj = (rf - k.r0) / 2, ll = (sf - k.s0) / 2;
-                            tap_tab.push_back((int32_t)(k.wt_off + ((size_t)jj * k.Sc + ll) * Co));
-                            tap_tab.push_back((int32_t)((size_t)k.Rc * k.Sc * Co));
+                            tap_tab.push_back((int32_t)(k.wt_off + ((size_t)jj * k.Sc + ll) * Cog));
+                            tap_tab.push_back((int32_t)((size_t)k.Rc * k.Sc * Cog));
                         } else {
-                            tap_tab.push_back((int32_t)(((size_t)rf * S + sf) * Co));
-                            tap_tab.push_back((int32_t)((size_t)R * S * Co));
+                            tap_tab.push_back((int32_t)(((size_t)rf * S + sf) * Cog));
+                            tap_tab.push_back((int32_t)((size_t)R * S * Cog));
                         }
                     }
                 tasks.push_back(t);
@@ -477,7 +482,7 @@ static int build_graph(dsp_block* b)
             if (L.d.op != DSP_OP_CONV) continue;
             float* dw = L.cin_pad ? L.dw_pad : b->g + L.p0;
             items.push_back(WgradReduceItem{(const float*)((char*)b->wgrad_ws + L.wg_off), dw,
-                                            (size_t)L.cs.Cout * L.cs.R * L.cs.S * L.cs.Cin,
+                                            (size_t)L.cs.Cout * L.cs.R * L.cs.S * (L.cs.Cin / conv_groups(L.cs)),
                                             conv_backward_weight_slices(b->dtype, L.cs)});
         }
         DSP_TRY(wgrad_reduce_set_create(items.data(), (int)items.size(), &b->wgrad_set));
@@ -1050,46 +1055,76 @@ int dsp_block_get_pool_argmax(dsp_block* b, int32_t layer, uint8_t* h_dst, size_
 }
 
 // ---- single-layer entry points ---------------------------------------------------------------------
+int dsp_grouped_conv_forward(int32_t dtype, const void* d_x, const void* d_w, void* d_y, int32_t N, int32_t H, int32_t W,
+                             int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride, int32_t pad, int32_t groups,
+                             void* stream)
+{
+    DSP_REQUIRE(d_x && d_w && d_y && (dtype == DSP_FP32 || dtype == DSP_BF16), DSP_EINVAL, "dsp_conv_forward: bad argument");
+    DSP_REQUIRE(N > 0 && H > 0 && W > 0 && cin > 0 && cout > 0 && r > 0 && s > 0 && stride > 0 && pad >= 0 && groups > 0,
+                DSP_EINVAL, "dsp_conv_forward: bad shape");
+    return launch_conv_forward(dtype, make_conv_shape(N, H, W, cin, cout, r, s, stride, pad, groups), d_x, d_w, d_y,
+                               (hipStream_t)stream);
+}
+
+int dsp_grouped_conv_backward_data(int32_t dtype, const void* d_dy, const void* d_wt, void* d_dx, int32_t N, int32_t H,
+                                   int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride, int32_t pad,
+                                   int32_t groups, int32_t accumulate, void* stream)
+{
+    DSP_REQUIRE(d_dy && d_wt && d_dx && (dtype == DSP_FP32 || dtype == DSP_BF16), DSP_EINVAL, "dsp_conv_backward_data: bad argument");
+    DSP_REQUIRE(N > 0 && H > 0 && W > 0 && cin > 0 && cout > 0 && r > 0 && s > 0 && stride > 0 && pad >= 0 && groups > 0,
+                DSP_EINVAL, "dsp_conv_backward_data: bad shape");
+    return launch_conv_backward_data(dtype, make_conv_shape(N, H, W, cin, cout, r, s, stride, pad, groups), d_dy, d_wt, d_dx,
+                                     accumulate != 0, (hipStream_t)stream);
+}
+
+int dsp_grouped_conv_backward_weight(int32_t dtype, const void* d_x, const void* d_dy, float* d_dw, int32_t N, int32_t H,
+                                     int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride, int32_t pad,
+                                     int32_t groups, void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    DSP_REQUIRE(d_x && d_dy && d_dw && (dtype == DSP_FP32 || dtype == DSP_BF16), DSP_EINVAL, "dsp_conv_backward_weight: bad argument");
+    DSP_REQUIRE(N > 0 && H > 0 && W > 0 && cin > 0 && cout > 0 && r > 0 && s > 0 && stride > 0 && pad >= 0 && groups > 0,
+                DSP_EINVAL, "dsp_conv_backward_weight: bad shape");
+    return launch_conv_backward_weight(dtype, make_conv_shape(N, H, W, cin, cout, r, s, stride, pad, groups), d_x, d_dy, d_dw,
+                                       d_workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int dsp_grouped_conv_workspace_bytes(int32_t N, int32_t H, int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s,
+                                     int32_t stride, int32_t pad, int32_t groups, size_t* bytes)
+{
+    DSP_REQUIRE(bytes && N > 0 && H > 0 && W > 0 && cin > 0 && cout > 0 && r > 0 && s > 0 && stride > 0 && pad >= 0 &&
+                    groups > 0 && cin % groups == 0 && cout % groups == 0,
+                DSP_EINVAL, "dsp_conv_workspace_bytes: bad argument");
+    const ConvShape c = make_conv_shape(N, H, W, cin, cout, r, s, stride, pad, groups);
+    DSP_REQUIRE(c.Ho > 0 && c.Wo > 0, DSP_EINVAL, "dsp_conv_workspace_bytes: empty output");
+    *bytes = conv_backward_weight_workspace(c);
+    return DSP_OK;
+}
+
 int dsp_conv_forward(int32_t dtype, const void* d_x, const void* d_w, void* d_y, int32_t N, int32_t H, int32_t W,
                      int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride, int32_t pad, void* stream)
 {
-    DSP_REQUIRE(d_x && d_w && d_y && (dtype == DSP_FP32 || dtype == DSP_BF16), DSP_EINVAL, "dsp_conv_forward: bad argument");
-    DSP_REQUIRE(N > 0 && H > 0 && W > 0 && cin > 0 && cout > 0 && r > 0 && s > 0 && stride > 0 && pad >= 0, DSP_EINVAL,
-                "dsp_conv_forward: bad shape");
-    return launch_conv_forward(dtype, make_conv_shape(N, H, W, cin, cout, r, s, stride, pad), d_x, d_w, d_y, (hipStream_t)stream);
+    return dsp_grouped_conv_forward(dtype, d_x, d_w, d_y, N, H, W, cin, cout, r, s, stride, pad, 1, stream);
 }
 
 int dsp_conv_backward_data(int32_t dtype, const void* d_dy, const void* d_wt, void* d_dx, int32_t N, int32_t H,
                            int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride, int32_t pad,
                            int32_t accumulate, void* stream)
 {
-    DSP_REQUIRE(d_dy && d_wt && d_dx && (dtype == DSP_FP32 || dtype == DSP_BF16), DSP_EINVAL, "dsp_conv_backward_data: bad argument");
-    DSP_REQUIRE(N > 0 && H > 0 && W > 0 && cin > 0 && cout > 0 && r > 0 && s > 0 && stride > 0 && pad >= 0, DSP_EINVAL,
-                "dsp_conv_backward_data: bad shape");
-    return launch_conv_backward_data(dtype, make_conv_shape(N, H, W, cin, cout, r, s, stride, pad), d_dy, d_wt, d_dx,
-                                     accumulate != 0, (hipStream_t)stream);
+    return dsp_grouped_conv_backward_data(dtype, d_dy, d_wt, d_dx, N, H, W, cin, cout, r, s, stride, pad, 1, accumulate, stream);
 }
 
 int dsp_conv_backward_weight(int32_t dtype, const void* d_x, const void* d_dy, float* d_dw, int32_t N, int32_t H,
                              int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s, int32_t stride, int32_t pad,
                              void* d_workspace, size_t workspace_bytes, void* stream)
 {
-    DSP_REQUIRE(d_x && d_dy && d_dw && (dtype == DSP_FP32 || dtype == DSP_BF16), DSP_EINVAL, "dsp_conv_backward_weight: bad argument");
-    DSP_REQUIRE(N > 0 && H > 0 && W > 0 && cin > 0 && cout > 0 && r > 0 && s > 0 && stride > 0 && pad >= 0, DSP_EINVAL,
-                "dsp_conv_backward_weight: bad shape");
-    return launch_conv_backward_weight(dtype, make_conv_shape(N, H, W, cin, cout, r, s, stride, pad), d_x, d_dy, d_dw,
-                                       d_workspace, workspace_bytes, (hipStream_t)stream);
+    return dsp_grouped_conv_backward_weight(dtype, d_x, d_dy, d_dw, N, H, W, cin, cout, r, s, stride, pad, 1, d_workspace,
+                                            workspace_bytes, stream);
 }
 
 int dsp_conv_workspace_bytes(int32_t N, int32_t H, int32_t W, int32_t cin, int32_t cout, int32_t r, int32_t s,
                              int32_t stride, int32_t pad, size_t* bytes)
 {
-    DSP_REQUIRE(bytes && N > 0 && H > 0 && W > 0 && cin > 0 && cout > 0 && r > 0 && s > 0 && stride > 0 && pad >= 0,
-                DSP_EINVAL, "dsp_conv_workspace_bytes: bad argument");
-    const ConvShape c = make_conv_shape(N, H, W, cin, cout, r, s, stride, pad);
-    DSP_REQUIRE(c.Ho > 0 && c.Wo > 0, DSP_EINVAL, "dsp_conv_workspace_bytes: empty output");
-    *bytes = conv_backward_weight_workspace(c);
-    return DSP_OK;
+    return dsp_grouped_conv_workspace_bytes(N, H, W, cin, cout, r, s, stride, pad, 1, bytes);
 }
 
 // ---- in-situ kernel timing ---------------------------------------------------------------------------

@@ -132,11 +132,15 @@ struct ConvShape {
     int N, H, W, Cin, Cout, R, S, stride, pad, Ho, Wo;
     int cin_real;  // > 0: only the first cin_real of the Cin input channels carry data (the rest is zero padding);
                    // used for counting the useful multiply-accumulates only
+    int groups;    // > 1: grouped convolution -- group g maps input channels [g Cin/groups, (g+1) Cin/groups) to output
+                   // channels [g Cout/groups, (g+1) Cout/groups); filters [Cout][R][S][Cin/groups].  0 and 1: ungrouped.
 };
 
-inline ConvShape make_conv_shape(int N, int H, int W, int Cin, int Cout, int R, int S, int stride, int pad)
+inline int conv_groups(const ConvShape& c) { return c.groups > 1 ? c.groups : 1; }
+
+inline ConvShape make_conv_shape(int N, int H, int W, int Cin, int Cout, int R, int S, int stride, int pad, int groups = 1)
 {
-    ConvShape c{N, H, W, Cin, Cout, R, S, stride, pad, 0, 0, 0};
+    ConvShape c{N, H, W, Cin, Cout, R, S, stride, pad, 0, 0, 0, groups};
     c.Ho = (H + 2 * pad - R) / stride + 1;
     c.Wo = (W + 2 * pad - S) / stride + 1;
     return c;
@@ -256,7 +260,9 @@ struct UpdateTask {
     int decay;         // weight decay applies (conv / linear weights)
     uint32_t p0, n;    // first element and length in the flat arrays
     uint32_t wt_off;   // kind 1: first element of the copy in wt
-    int Co, J, Ci, R, S;  // kind 1: J = R * S * Ci
+    int Co, J, Ci, R, S;  // kind 1: J = R * S * Ci (Ci: input channels of one group)
+    int Cog;              // kind 1: output channels per group (= Co for an ordinary convolution); the copy of a
+                          // grouped layer is wt[group * Ci + ci][..taps..][co within the group]
     int tap_tab;          // kind 1: first entry of this layer in the tap table: per tap (r * S + s) the element offset of
                           // (ci = 0, co = 0) of that tap inside the copy and the stride between consecutive ci
     int tiles_j, block_begin, aligned, wt_aligned;  // filled by update_plan_finish

@@ -212,6 +212,10 @@ inline void fast_div_constants(uint32_t d, uint32_t* mul, uint32_t* sh)
 struct GatherGeom {
     int N, Hi, Wi, Ci, Ho, Wo, Co, R, S, pad_h, pad_w, ostride, idil;
     int M, Kdim;
+    // Grouped convolution: Ci and Co above are the channels of ONE group (they shape the GEMM: Kdim = R*S*Ci, Co
+    // columns); a pixel of `in` holds Cis = groups * Ci channels and a row of `out` Cos = groups * Co.  The group
+    // is the launch's blockIdx.z.  Ungrouped: groups = 1, Cis = Ci, Cos = Co.
+    int groups, Cis, Cos;
     int ci_shift;  // log2(Ci) if Ci is a power of two, else -1
     int s_inv;     // 65536 / S + 1: tap / S == (tap * s_inv) >> 16 for tap < 4096
     uint32_t wo_mul, wo_sh, ho_mul, ho_sh;  // m / Wo and (m / Wo) / Ho by multiplication (fast_div)
@@ -284,6 +288,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
     const int tiles_n = (g.Co + TL::BN - 1) / TL::BN;
     const unsigned tile = xcd_tile(blockIdx.x, gridDim.x);
     const int m0 = (tile / tiles_n) * TL::BM, n0 = (tile % tiles_n) * TL::BN;
+    // grouped convolution: this workgroup's group reads channels [in_c0, in_c0 + Ci) of rows Cis wide and writes
+    // channels [out_c0, out_c0 + Co) of rows Cos wide, with the filters of output channels out_c0 ..
+    const int in_c0 = blockIdx.z * g.Ci, out_c0 = blockIdx.z * g.Co;
 
     const int kc = tid % CPR;    // which 16-byte run of the k tile this thread moves
     const int row0 = tid / CPR;  // first tile row it moves; further rows are +ROWS_PER_PASS apart
@@ -309,7 +316,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
             const int t = (int)fast_div((uint32_t)m, g.wo_mul, g.wo_sh), wo = m - t * g.Wo;
             const int n = (int)fast_div((uint32_t)t, g.ho_mul, g.ho_sh), ho = t - n * g.Ho;
             const int th0 = ho * g.ostride - g.pad_h, tw0 = wo * g.ostride - g.pad_w;
-            const uint32_t img = (uint32_t)n * g.Hi * g.Wi * g.Ci * SZ;
+            const uint32_t img = ((uint32_t)n * g.Hi * g.Wi * g.Cis + in_c0) * SZ;
             if (masked) {
                 // taps s in [s_lo, s_hi) of a filter row fall inside the image; the same bits for every valid row r
                 const int s_lo = tw0 < 0 ? -tw0 : 0, s_hi = g.Wi - tw0 < g.S ? g.Wi - tw0 : g.S;
@@ -317,7 +324,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
                 uint64_t mask = 0;
                 for (int r = 0; r < g.R; ++r)
                     if (th0 + r >= 0 && th0 + r < g.Hi) mask |= cols << (r * g.S);
-                a_off[i] = img + (uint32_t)((th0 * g.Wi + tw0) * g.Ci) * SZ;
+                a_off[i] = img + (uint32_t)((th0 * g.Wi + tw0) * g.Cis) * SZ;
                 a_aux[i] = (uint32_t)mask;
                 a_hi[i] = (uint32_t)(mask >> 32);
             } else {
@@ -330,10 +337,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
 #pragma unroll
     for (int i = 0; i < TL::B_PER; ++i) {
         const int row = row0 + i * ROWS_PER_PASS, co = n0 + row;
-        b_off[i] = (row < TL::BN && co < g.Co) ? (uint32_t)(co * g.Kdim) * SZ : kOutOfRange;
+        b_off[i] = (row < TL::BN && co < g.Co) ? (uint32_t)((out_c0 + co) * g.Kdim) * SZ : kOutOfRange;
     }
-    const __amdgpu_buffer_rsrc_t rin = make_rsrc(in, (uint32_t)g.N * g.Hi * g.Wi * g.Ci * SZ);
-    const __amdgpu_buffer_rsrc_t rw = make_rsrc(wgt, (uint32_t)g.Co * g.Kdim * SZ);
+    const __amdgpu_buffer_rsrc_t rin = make_rsrc(in, (uint32_t)g.N * g.Hi * g.Wi * g.Cis * SZ);
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(wgt, (uint32_t)gridDim.z * g.Co * g.Kdim * SZ);
 
     // k position of this thread's run in k tile kt: element kk = kt*BK + kc*E = (kr*S + ks)*Ci + kci
     const T zero = from_float<T>(0.f);
@@ -366,7 +373,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
             tw >>= 1;
         }
         ok = ok && th < g.Hi && tw < g.Wi;
-        return ok ? off + (uint32_t)((th * g.Wi + tw) * g.Ci + ci) * SZ : kOutOfRange;
+        return ok ? off + (uint32_t)((th * g.Wi + tw) * g.Cis + ci) * SZ : kOutOfRange;
     };
 
     // global -> registers: the runs of k tile kt (zeros past the end of k, for padding taps and rows past M)
@@ -375,7 +382,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
         if (VEC) {
             const bool k_ok = p.kk < g.Kdim;
             if (!dil) {
-                const uint32_t tap_off = (uint32_t)((p.kr * g.Wi + p.ks) * g.Ci + p.kci) * SZ;
+                const uint32_t tap_off = (uint32_t)((p.kr * g.Wi + p.ks) * g.Cis + p.kci) * SZ;
                 const int tap = p.kr * g.S + p.ks;
 #pragma unroll
                 for (int i = 0; i < TL::A_PER; ++i) {
@@ -488,7 +495,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
                     const int lcol = (wave_n * TL::TN + j) * TL::MT + acc_row<TL::MT>(lane, 4 * q);
                     const int col = n0 + lcol;
                     if (g.accum && m < g.M) {
-                        const T* old = out + out_row(g, m) * g.Co + col;
+                        const T* old = out + out_row(g, m) * g.Cos + out_c0 + col;
                         if (g.out_vec && col + 4 <= g.Co) {
                             float o[4];
                             Run4<T>::unpack(*(const RunV*)old, o);
@@ -514,7 +521,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
 #pragma unroll
                     for (int e = 0; e < kAcc; ++e) {
                         const int m = m0 + (wave_m * TL::TM + i) * TL::MT + acc_row<TL::MT>(lane, e);
-                        if (m < g.M && col < g.Co) acc[i][j][e] += to_float<T>(out[out_row(g, m) * g.Co + col]);
+                        if (m < g.M && col < g.Co) acc[i][j][e] += to_float<T>(out[out_row(g, m) * g.Cos + out_c0 + col]);
                     }
                 }
         }
@@ -537,7 +544,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
         const int m = m0 + lrow, col = n0 + cc;
         if (m >= g.M || col >= g.Co) continue;
         const char* src = smem + lrow * TL::EPI_ROWB + cc * (int)sizeof(T);
-        T* dst = out + out_row(g, m) * g.Co + col;
+        T* dst = out + out_row(g, m) * g.Cos + out_c0 + col;
         if (g.out_vec && col + E <= g.Co) {
             *(u32x4*)dst = *(const u32x4*)src;
         } else {
@@ -565,7 +572,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::MI
                 a += sred[(k * TL::BN + c) * 2];
                 b += sred[(k * TL::BN + c) * 2 + 1];
             }
-            double* dst = stats + ((int64_t)(tile / tiles_n) * g.Co + n0 + c) * 2;
+            double* dst = stats + ((int64_t)(tile / tiles_n) * g.Cos + out_c0 + n0 + c) * 2;
             dst[0] = a;
             dst[1] = b;
         }
@@ -985,6 +992,9 @@ __global__ __launch_bounds__(kThreads) void conv3x3_direct_f32_kernel(const floa
 struct WgradGeom {
     int N, H, W, Ci, Ho, Wo, Co, R, S, pad, stride;
     int M, Kdim, m_per_split;
+    // Grouped convolution: Ci and Co are the channels of ONE group (blockIdx.z); a pixel of x holds Cis = groups * Ci
+    // channels and a row of dy Cos = groups * Co; the filter gradient has groups * Co rows of Kdim = R*S*Ci columns.
+    int groups, Cis, Cos;
     uint32_t wo_mul, wo_sh, ho_mul, ho_sh;  // n / Wo and n / Ho by multiplication (fast_div)
 };
 
@@ -1040,6 +1050,8 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
     const int m_begin = slice * g.m_per_split;
     const int m_end = min(g.M, m_begin + g.m_per_split);
     const int nk = (m_end - m_begin + BKm - 1) / BKm;
+    // grouped convolution (blockIdx.z = group): dy columns dy_c0 .. of rows Cos wide, x channels x_c0 .. of pixels Cis wide
+    const int dy_c0 = blockIdx.z * g.Co, x_c0 = blockIdx.z * g.Ci;
 
     typename Mma<T, TL::MT>::Acc acc[TL::TM][TL::TN];
     zero_acc<TL>(acc);
@@ -1082,8 +1094,8 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
         u32x4 regs[PER][E];
 
         constexpr uint32_t SZ = sizeof(T);
-        const __amdgpu_buffer_rsrc_t rdy = make_rsrc(dy, (uint32_t)g.M * g.Co * SZ);
-        const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)g.N * g.H * g.W * g.Ci * SZ);
+        const __amdgpu_buffer_rsrc_t rdy = make_rsrc(dy, (uint32_t)g.M * g.Cos * SZ);
+        const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)g.N * g.H * g.W * g.Cis * SZ);
         auto load_tiles = [&](int mb) {
 #pragma unroll
             for (int i = 0; i < PER; ++i) {
@@ -1091,8 +1103,8 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
                 const int mfirst = mb + mt_mg[i] * E;
                 if (c < NA) {
                     // E consecutive rows of dy: offsets Co apart; out-of-range rows read as zeros
-                    uint32_t off = mt_col[i] >= 0 ? (uint32_t)(mfirst * g.Co + mt_col[i]) * SZ : kOutOfRange;
-                    const uint32_t step = (uint32_t)g.Co * SZ;
+                    uint32_t off = mt_col[i] >= 0 ? (uint32_t)(mfirst * g.Cos + dy_c0 + mt_col[i]) * SZ : kOutOfRange;
+                    const uint32_t step = (uint32_t)g.Cos * SZ;
 #pragma unroll
                     for (int e = 0; e < E; ++e) {
                         regs[i][e] = load16(rdy, (mt_col[i] >= 0 && mfirst + e < m_end) ? off : kOutOfRange);
@@ -1103,7 +1115,7 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
                     // two when the run crosses a row end (Wo >= E - 1: at most one crossing); branch-free:
                     // both rows' base offsets are formed once and every pixel picks its row.
                     const bool col_ok = mt_col[i] >= 0;
-                    const uint32_t pix = (uint32_t)g.Ci * SZ;
+                    const uint32_t pix = (uint32_t)g.Cis * SZ;
                     const uint32_t tq = fast_div((uint32_t)mfirst, g.wo_mul, g.wo_sh);
                     const int w0 = mfirst - (int)tq * g.Wo;
                     const int n0 = (int)fast_div(tq, g.ho_mul, g.ho_sh);
@@ -1111,13 +1123,13 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
                     if (g.Wo >= E - 1) {
                         const int hiA = h0 * g.stride - g.pad + tap_r[i];
                         const bool okA = col_ok && hiA >= 0 && hiA < g.H;
-                        const uint32_t offA = (uint32_t)(((n0 * g.H + hiA) * g.W) * g.Ci + mt_col[i]) * SZ;
+                        const uint32_t offA = (uint32_t)(((n0 * g.H + hiA) * g.W) * g.Cis + x_c0 + mt_col[i]) * SZ;
                         const int wiA = w0 * g.stride - g.pad + tap_s[i];
                         const bool last = h0 + 1 == g.Ho;
                         const int h1 = last ? 0 : h0 + 1, n1 = n0 + (last ? 1 : 0);
                         const int hiB = h1 * g.stride - g.pad + tap_r[i];
                         const bool okB = col_ok && hiB >= 0 && hiB < g.H;
-                        const uint32_t offB = (uint32_t)(((n1 * g.H + hiB) * g.W) * g.Ci + mt_col[i]) * SZ;
+                        const uint32_t offB = (uint32_t)(((n1 * g.H + hiB) * g.W) * g.Cis + x_c0 + mt_col[i]) * SZ;
                         const int e_wrap = g.Wo - w0;                               // first pixel of the run in the second row
                         const int wiB = tap_s[i] - g.pad - e_wrap * g.stride;       // so that wi = wiB + e * stride there
 #pragma unroll
@@ -1134,7 +1146,7 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
                         for (int e = 0; e < E; ++e) {
                             const int hi = h * g.stride - g.pad + tap_r[i], wi = w * g.stride - g.pad + tap_s[i];
                             const bool ok = col_ok && hi >= 0 && hi < g.H && wi >= 0 && wi < g.W && mfirst + e < m_end;
-                            regs[i][e] = load16(rx, ok ? (uint32_t)(((n * g.H + hi) * g.W + wi) * g.Ci + mt_col[i]) * SZ : kOutOfRange);
+                            regs[i][e] = load16(rx, ok ? (uint32_t)(((n * g.H + hi) * g.W + wi) * g.Cis + x_c0 + mt_col[i]) * SZ : kOutOfRange);
                             if (++w == g.Wo) {
                                 w = 0;
                                 if (++h == g.Ho) { h = 0; ++n; }
@@ -1186,7 +1198,7 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
                 const int c = tid + i * kThreads, mrow = c / A_CPR, cc = (c % A_CPR) * E;
                 const int m = mb + mrow, co = c0 + cc;
                 const bool ok = c < A_CH && m < m_end;
-                for (int e = 0; e < E; ++e) ra[i][e] = (ok && co + e < g.Co) ? dy[(int64_t)m * g.Co + co + e] : zero;
+                for (int e = 0; e < E; ++e) ra[i][e] = (ok && co + e < g.Co) ? dy[(int64_t)m * g.Cos + dy_c0 + co + e] : zero;
             }
 #pragma unroll
             for (int i = 0; i < B_PER; ++i) {
@@ -1199,7 +1211,7 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
                     const int tap = je / g.Ci, ci = je % g.Ci, r = tap / g.S, s = tap % g.S;
                     const int hi = ho * g.stride - g.pad + r, wi = wo * g.stride - g.pad + s;
                     rb[i][e] = (ok && je < g.Kdim && hi >= 0 && hi < g.H && wi >= 0 && wi < g.W)
-                                   ? x[(((int64_t)n * g.H + hi) * g.W + wi) * g.Ci + ci]
+                                   ? x[(((int64_t)n * g.H + hi) * g.W + wi) * g.Cis + x_c0 + ci]
                                    : zero;
                 }
             }
@@ -1237,7 +1249,7 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const typename TL:
         }
     }
 
-    float* dst = part + (int64_t)slice * g.Co * g.Kdim;
+    float* dst = part + ((int64_t)slice * gridDim.z * g.Co + dy_c0) * g.Kdim;
 #pragma unroll
     for (int i = 0; i < TL::TM; ++i)
 #pragma unroll
@@ -1301,6 +1313,8 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_tr_kernel(const bf16_t* _
     const int m_begin = slice * g.m_per_split;
     const int m_end = min(g.M, m_begin + g.m_per_split);
     const int nk = (m_end - m_begin + BKm - 1) / BKm;
+    // grouped convolution (blockIdx.z = group): dy columns dy_c0 .. of rows Cos wide, x channels x_c0 .. of pixels Cis wide
+    const int dy_c0 = blockIdx.z * g.Co, x_c0 = blockIdx.z * g.Ci;
 
     typename Mma<T, 32>::Acc acc[TL::TM][TL::TN];
     zero_acc<TL>(acc);
@@ -1313,14 +1327,14 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_tr_kernel(const bf16_t* _
     const bool b_ok = jb < g.Kdim;
     const int tap = b_ok ? jb / g.Ci : 0, b_ci = b_ok ? jb % g.Ci : 0;
     const int tap_r = tap / g.S, tap_s = tap % g.S;
-    const __amdgpu_buffer_rsrc_t rdy = make_rsrc(dy, (uint32_t)g.M * g.Co * 2u);
-    const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)g.N * g.H * g.W * g.Ci * 2u);
+    const __amdgpu_buffer_rsrc_t rdy = make_rsrc(dy, (uint32_t)g.M * g.Cos * 2u);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)g.N * g.H * g.W * g.Cis * 2u);
     u32x4 ra[PA], rb[PB];
     auto load_tiles = [&](int mb) {
 #pragma unroll
         for (int i = 0; i < PA; ++i) {
             const int m = mb + a_row0 + i * RSA;
-            ra[i] = load16(rdy, (a_ok && m < m_end) ? (uint32_t)(m * g.Co + c0 + a_chunk * 8) * 2u : kOutOfRange);
+            ra[i] = load16(rdy, (a_ok && m < m_end) ? (uint32_t)(m * g.Cos + dy_c0 + c0 + a_chunk * 8) * 2u : kOutOfRange);
         }
 #pragma unroll
         for (int i = 0; i < PB; ++i) {
@@ -1331,7 +1345,7 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_tr_kernel(const bf16_t* _
             const int ho = (int)tq - n * g.Ho;
             const int hi = ho * g.stride - g.pad + tap_r, wi = wo * g.stride - g.pad + tap_s;
             const bool ok = b_ok && m < m_end && (unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W;
-            rb[i] = load16(rx, ok ? (uint32_t)(((n * g.H + hi) * g.W + wi) * g.Ci + b_ci) * 2u : kOutOfRange);
+            rb[i] = load16(rx, ok ? (uint32_t)(((n * g.H + hi) * g.W + wi) * g.Cis + x_c0 + b_ci) * 2u : kOutOfRange);
         }
     };
     auto store_tiles = [&](int buf) {
@@ -1389,7 +1403,7 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_tr_kernel(const bf16_t* _
     }
     if (kt < nk) mma(smem, smem + A_BYTES);
 
-    float* dst = part + (int64_t)slice * g.Co * g.Kdim;
+    float* dst = part + ((int64_t)slice * gridDim.z * g.Co + dy_c0) * g.Kdim;
 #pragma unroll
     for (int i = 0; i < TL::TM; ++i)
 #pragma unroll
@@ -1670,8 +1684,8 @@ int run_gather(const GatherGeom& g, const void* in, const void* w, void* out, hi
     }
     {
         ProfScope ps(tile_name<TL, VEC, false>(), flops, 0);
-        DSP_LAUNCH(ps, kern, dim3((unsigned)tiles, g.in1 ? 2 : 1), dim3(kThreads), TL::LDS_BYTES, st, (const T*)in,
-                   (const T*)w, (T*)out, g);
+        DSP_LAUNCH(ps, kern, dim3((unsigned)tiles, g.in1 ? 2 : 1, (unsigned)g.groups), dim3(kThreads), TL::LDS_BYTES, st,
+                   (const T*)in, (const T*)w, (T*)out, g);
     }
     DSP_HIP(hipGetLastError());
     return DSP_OK;
@@ -1688,7 +1702,10 @@ int run_gather_v(const GatherGeom& g, bool vec, const void* in, const void* w, v
 // Enough workgroups to put more than one on each of the 256 compute units.
 constexpr int64_t kEnoughTiles = 384;
 
-inline int64_t tile_count(const GatherGeom& g, int bm, int bn) { return (int64_t)ceil_div(g.M, bm) * ceil_div(g.Co, bn); }
+inline int64_t tile_count(const GatherGeom& g, int bm, int bn)
+{
+    return (int64_t)ceil_div(g.M, bm) * ceil_div(g.Co, bn) * g.groups;
+}
 
 // The register-resident-filter kernel: fp32, 3x3, 16 gathered channels, 16 or 32 output channels, no
 // dilation, 16-byte aligned activations.  (The kernel also handles 32 gathered channels, but there
@@ -1696,7 +1713,7 @@ inline int64_t tile_count(const GatherGeom& g, int bm, int bn) { return (int64_t
 template <typename T>
 bool direct_eligible(const GatherGeom& g, const void* in, const void* out)
 {
-    return sizeof(T) == 4 && g.R == 3 && g.S == 3 && g.idil == 1 && g.Ci == 16 && (g.Co == 16 || g.Co == 32) &&
+    return sizeof(T) == 4 && g.groups == 1 && g.R == 3 && g.S == 3 && g.idil == 1 && g.Ci == 16 && (g.Co == 16 || g.Co == 32) &&
            ((uintptr_t)in % 16) == 0 && ((uintptr_t)out % 16) == 0;
 }
 
@@ -1725,7 +1742,7 @@ bool dma_wide(const GatherGeom& g)  // 256 x 256 tiles (half the LDS operand rea
 template <typename T>
 bool dma_eligible(const GatherGeom& g)
 {
-    return sizeof(T) == 2 && g.Ci % 64 == 0 && g.R * g.S <= 32 && g.idil == 1 && g.oh_mul == 0 && g.Co % 128 == 0 && g.Kdim >= 2304 &&
+    return sizeof(T) == 2 && g.groups == 1 && g.Ci % 64 == 0 && g.R * g.S <= 32 && g.idil == 1 && g.oh_mul == 0 && g.Co % 128 == 0 && g.Kdim >= 2304 &&
            (tile_count(g, 256, 128) >= 192 || dma_wide<T>(g));
 }
 
@@ -1851,7 +1868,7 @@ int run_wgrad(const WgradGeom& g, int splits, const void* x, const void* dy, flo
     }
     {
         ProfScope ps(tile_name<TL, VEC, true>(), flops, 0);
-        DSP_LAUNCH(ps, kern, dim3(tiles, splits), dim3(kThreads), TL::LOAD_BYTES, st, (const T*)x, (const T*)dy, dst, g);
+        DSP_LAUNCH(ps, kern, dim3(tiles, splits, g.groups), dim3(kThreads), TL::LOAD_BYTES, st, (const T*)x, (const T*)dy, dst, g);
     }
     DSP_HIP(hipGetLastError());
     return DSP_OK;
@@ -1876,7 +1893,7 @@ int run_wgrad_tr(const WgradGeom& g, int splits, const void* x, const void* dy, 
         }
         {
             ProfScope ps(tile_name<TL, true, true>(), flops, 0);
-            DSP_LAUNCH(ps, kern, dim3(tiles, splits), dim3(kThreads), LDS, st, (const bf16_t*)x, (const bf16_t*)dy, dst, g);
+            DSP_LAUNCH(ps, kern, dim3(tiles, splits, g.groups), dim3(kThreads), LDS, st, (const bf16_t*)x, (const bf16_t*)dy, dst, g);
         }
         DSP_HIP(hipGetLastError());
         return DSP_OK;
@@ -1896,8 +1913,19 @@ int run_wgrad_v(const WgradGeom& g, int splits, bool vec, const void* x, const v
 struct WgradPlan {
     int bm, bn, bk, id;
 };
-WgradPlan wgrad_plan(int dtype, const ConvShape& c)
+// One group of a grouped convolution as a convolution of its own (the shape the GEMM tiles are chosen for).
+ConvShape one_group(const ConvShape& c)
 {
+    ConvShape o = c;
+    o.Cin = c.Cin / conv_groups(c);
+    o.Cout = c.Cout / conv_groups(c);
+    o.groups = 1;
+    return o;
+}
+
+WgradPlan wgrad_plan(int dtype, const ConvShape& cc)
+{
+    const ConvShape c = one_group(cc);
     // m rows per LDS tile: 128 bytes of k per row; the large fp32 tile keeps 64 (measured: VGG-19's layers)
     const int bk = dtype == DSP_BF16 ? 64 : 32;
     const int64_t kdim = (int64_t)c.R * c.S * c.Cin;
@@ -1915,13 +1943,14 @@ WgradPlan wgrad_plan(int dtype, const ConvShape& c)
 
 // Slices of the (n, ho, wo) range: about two workgroups per compute unit, each slice a whole number
 // of LDS tiles and at least 8 of them.
-int wgrad_splits(const ConvShape& c, const WgradPlan& pl, int* m_per_split)
+int wgrad_splits(const ConvShape& cc, const WgradPlan& pl, int* m_per_split)
 {
+    const ConvShape c = one_group(cc);
     const int64_t M = (int64_t)c.N * c.Ho * c.Wo, Kdim = (int64_t)c.R * c.S * c.Cin;
-    const int tiles = ceil_div(c.Cout, pl.bm) * ceil_div(Kdim, pl.bn);
+    const int tiles = ceil_div(c.Cout, pl.bm) * ceil_div(Kdim, pl.bn) * conv_groups(cc);
     // two workgroups per compute unit, one for small problems (below ~1 GMAC, the CIFAR-sized layers: measured in
     // the three-stream pipeline); rounded down: one workgroup too many costs a whole second round
-    const int target = (double)M * (double)Kdim * (double)c.Cout < 1e9 ? 256 : 512;
+    const int target = (double)M * (double)Kdim * (double)cc.Cout < 1e9 ? 256 : 512;
     int want = target / tiles;
     const int max_by_len = (int)((M + 8 * pl.bk - 1) / (8 * pl.bk));
     if (want > max_by_len) want = max_by_len;
@@ -1936,7 +1965,8 @@ int wgrad_splits(const ConvShape& c, const WgradPlan& pl, int* m_per_split)
 // The register-streaming kernel serves fp32 layers with 16 -> 16 channels and 3x3 or 1x1 filters.
 bool wgrad_c16_eligible(int dtype, const ConvShape& c)
 {
-    return dtype == DSP_FP32 && c.Cin == 16 && c.Cout == 16 && ((c.R == 3 && c.S == 3) || (c.R == 1 && c.S == 1));
+    return dtype == DSP_FP32 && conv_groups(c) == 1 && c.Cin == 16 && c.Cout == 16 &&
+           ((c.R == 3 && c.S == 3) || (c.R == 1 && c.S == 1));
 }
 
 // About two workgroups per compute unit; a slice is a multiple of the 16 pixels one step covers.
@@ -1958,9 +1988,13 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
     constexpr int KB = 128;
     const int dtype = sizeof(T) == 2 ? DSP_BF16 : DSP_FP32;
     const WgradPlan pl = wgrad_plan(dtype, c);
-    WgradGeom g{c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.stride, 0, 0, 0, 0, 0, 0, 0};
+    const int G = conv_groups(c);
+    WgradGeom g{};
+    g.N = c.N; g.H = c.H; g.W = c.W; g.Ci = c.Cin / G; g.Ho = c.Ho; g.Wo = c.Wo; g.Co = c.Cout / G; g.R = c.R; g.S = c.S;
+    g.pad = c.pad; g.stride = c.stride;
+    g.groups = G; g.Cis = c.Cin; g.Cos = c.Cout;
     g.M = c.N * c.Ho * c.Wo;
-    g.Kdim = c.R * c.S * c.Cin;
+    g.Kdim = c.R * c.S * g.Ci;
     fast_div_constants((uint32_t)c.Wo, &g.wo_mul, &g.wo_sh);
     fast_div_constants((uint32_t)c.Ho, &g.ho_mul, &g.ho_sh);
     const bool c16 = wgrad_c16_eligible(dtype, c);
@@ -1972,7 +2006,7 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
                     "conv backward-weight: workspace too small (%zu < %zu)", ws_bytes, n * splits * sizeof(float));
         dst = (float*)ws;
     }
-    const bool vec = (c.Cin % E) == 0 && (c.Cout % E) == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)dy % 16) == 0;
+    const bool vec = (g.Ci % E) == 0 && (g.Co % E) == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)dy % 16) == 0;
     int rc;
     if (c16) {
         ProfScope ps(c.R == 3 ? "conv_wgrad_c16<fp32,3x3>" : "conv_wgrad_c16<fp32,1x1>", flops, 0);
@@ -2027,7 +2061,7 @@ double conv_macs(const ConvShape& c)
             const int t = o * c.stride - c.pad + s;
             vw += (t >= 0 && t < c.W);
         }
-    return (double)c.N * (double)vh * (double)vw * (double)(c.cin_real > 0 ? c.cin_real : c.Cin) * (double)c.Cout;
+    return (double)c.N * (double)vh * (double)vw * (double)(c.cin_real > 0 ? c.cin_real : c.Cin / conv_groups(c)) * (double)c.Cout;
 }
 
 int check_shape(const ConvShape& c)
@@ -2036,8 +2070,10 @@ int check_shape(const ConvShape& c)
                     c.pad >= 0 && c.Ho > 0 && c.Wo > 0,
                 DSP_EINVAL, "conv: bad shape");
     DSP_REQUIRE(c.H < 32000 && c.W < 32000, DSP_EINVAL, "conv: image side too large");
+    DSP_REQUIRE(c.groups >= 0 && c.groups < 65536 && c.Cin % conv_groups(c) == 0 && c.Cout % conv_groups(c) == 0, DSP_EINVAL,
+                "conv: %d groups do not divide %d input and %d output channels", c.groups, c.Cin, c.Cout);
     DSP_REQUIRE((int64_t)c.N * c.H * c.W * c.Cin < (1ll << 30) && (int64_t)c.N * c.Ho * c.Wo * c.Cout < (1ll << 30) &&
-                    (int64_t)c.R * c.S * c.Cin * c.Cout < (1ll << 30),
+                    (int64_t)c.R * c.S * (c.Cin / conv_groups(c)) * c.Cout < (1ll << 30),
                 DSP_EINVAL, "conv: tensor too large for 32-bit byte offsets (2^30 elements per tensor at most)");
     return DSP_OK;
 }
@@ -2053,6 +2089,7 @@ static GatherGeom make_geom(int N, int Hi, int Wi, int Ci, int Ho, int Wo, int C
     g.pad_h = pad_h; g.pad_w = pad_w; g.ostride = ostride; g.idil = idil;
     g.M = N * Ho * Wo;
     g.Kdim = R * S * Ci;
+    g.groups = 1; g.Cis = Ci; g.Cos = Co;
     g.ci_shift = -1;
     for (int b = 0; b < 31; ++b)
         if ((1 << b) == Ci) g.ci_shift = b;
@@ -2062,9 +2099,20 @@ static GatherGeom make_geom(int N, int Hi, int Wi, int Ci, int Ho, int Wo, int C
     return g;
 }
 
+// `in` pixels hold in_channels, `out` rows out_channels; every group gathers and produces its share of them.
+static void set_groups(GatherGeom& g, int groups, int in_channels, int out_channels)
+{
+    g.groups = groups;
+    g.Cis = in_channels;
+    g.Cos = out_channels;
+}
+
 static GatherGeom forward_geom(const ConvShape& c)
 {
-    return make_geom(c.N, c.H, c.W, c.Cin, c.Ho, c.Wo, c.Cout, c.R, c.S, c.pad, c.pad, c.stride, 1);
+    const int G = conv_groups(c);
+    GatherGeom g = make_geom(c.N, c.H, c.W, c.Cin / G, c.Ho, c.Wo, c.Cout / G, c.R, c.S, c.pad, c.pad, c.stride, 1);
+    set_groups(g, G, c.Cin, c.Cout);
+    return g;
 }
 
 int conv_forward_row_tiles(int dtype, const ConvShape& c)
@@ -2121,7 +2169,7 @@ void dgrad_classes(const ConvShape& c, DgradClass (&cls)[4])
             k.Hc = (c.H - ph + 1) / 2;
             k.Wc = (c.W - pw + 1) / 2;
             k.wt_off = off;
-            off += (size_t)c.Cin * k.Rc * k.Sc * c.Cout;
+            off += (size_t)c.Cin * k.Rc * k.Sc * (c.Cout / conv_groups(c));
         }
 }
 
@@ -2131,9 +2179,11 @@ int launch_conv_backward_data(int dtype, const ConvShape& c, const void* dy, con
     DSP_TRY(check_shape(c));
     DSP_REQUIRE(c.stride == 1 || c.stride == 2, DSP_EINVAL, "conv backward-data: stride %d unsupported", c.stride);
     const double flops = 2.0 * conv_macs(c);
+    const int G = conv_groups(c), Cig = c.Cin / G, Cog = c.Cout / G;  // a group gathers its Cog gradient channels
     if (c.stride == 1) {
         // dx[n,hi,wi,ci] = sum_{r',s',co} dy[n, hi - (R-1-pad) + r', ...][co] * wt[ci][r'][s'][co]
-        GatherGeom g = make_geom(c.N, c.Ho, c.Wo, c.Cout, c.H, c.W, c.Cin, c.R, c.S, c.R - 1 - c.pad, c.S - 1 - c.pad, 1, 1);
+        GatherGeom g = make_geom(c.N, c.Ho, c.Wo, Cog, c.H, c.W, Cig, c.R, c.S, c.R - 1 - c.pad, c.S - 1 - c.pad, 1, 1);
+        set_groups(g, G, c.Cout, c.Cin);
         return dtype == DSP_BF16 ? dispatch_gather<bf16_t>(g, accumulate, dy, wt, dx, st, flops)
                                  : dispatch_gather<float>(g, accumulate, dy, wt, dx, st, flops);
     }
@@ -2148,8 +2198,9 @@ int launch_conv_backward_data(int dtype, const ConvShape& c, const void* dy, con
         if (k.Hc == 0 || k.Wc == 0) continue;
         const bool empty = k.Rc == 0 || k.Sc == 0;  // no tap reaches these pixels: their gradient is zero
         if (empty && accumulate) continue;
-        GatherGeom g = make_geom(c.N, c.Ho, c.Wo, c.Cout, k.Hc, k.Wc, c.Cin, empty ? 1 : k.Rc, empty ? 1 : k.Sc, -k.off_h,
+        GatherGeom g = make_geom(c.N, c.Ho, c.Wo, Cog, k.Hc, k.Wc, Cig, empty ? 1 : k.Rc, empty ? 1 : k.Sc, -k.off_h,
                                  -k.off_w, 1, 1);
+        set_groups(g, G, c.Cout, c.Cin);
         if (empty) g.Kdim = 0;
         g.oh_mul = 2; g.ow_mul = 2; g.oh_off = q >> 1; g.ow_off = q & 1; g.OH = c.H; g.OW = c.W;
         const size_t esz = dtype_size(dtype);
@@ -2168,7 +2219,7 @@ size_t conv_backward_weight_workspace(const ConvShape& c)
         const WgradPlan pl = wgrad_plan(dtype, c);
         int per;
         const int splits = wgrad_c16_eligible(dtype, c) ? wgrad_c16_splits(c, &per) : wgrad_splits(c, pl, &per);
-        const size_t b = splits > 1 ? (size_t)splits * c.Cout * c.R * c.S * c.Cin * sizeof(float) : 0;
+        const size_t b = splits > 1 ? (size_t)splits * c.Cout * c.R * c.S * (c.Cin / conv_groups(c)) * sizeof(float) : 0;
         if (b > worst) worst = b;
     }
     return worst;

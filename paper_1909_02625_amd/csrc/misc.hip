@@ -392,14 +392,22 @@ __global__ __launch_bounds__(kThreads) void sgd_update_kernel(float* __restrict_
             const int jl = jr + ROWS * pass, j = j0 + jl;
             if (j >= t.J || co >= t.Co) continue;
             const int ci = j % t.Ci, tap = j / t.Ci;
-            TS* dst = wt + (size_t)t.wt_off + (size_t)tap_tab[t.tap_tab + 2 * tap] + (size_t)ci * tap_tab[t.tap_tab + 2 * tap + 1] + co;
+            // (grouped layers: the copy's rows are the input channels of all groups, its runs one group's output channels)
+            const int grp = co / t.Cog;
+            TS* dst = wt + (size_t)t.wt_off + (size_t)tap_tab[t.tap_tab + 2 * tap] +
+                      (size_t)(grp * t.Ci + ci) * tap_tab[t.tap_tab + 2 * tap + 1] + (co - grp * t.Cog);
             if (t.wt_aligned && co + E <= t.Co) {
                 float f[E];
 #pragma unroll
                 for (int e = 0; e < E; ++e) f[e] = tile[jl][E * cq + e];
                 VecIO<TS, E>::store(dst, f);
             } else {
-                for (int e = 0; e < E && co + e < t.Co; ++e) dst[e] = from_float<TS>(tile[jl][E * cq + e]);
+                for (int e = 0; e < E && co + e < t.Co; ++e) {
+                    const int ge = (co + e) / t.Cog;
+                    wt[(size_t)t.wt_off + (size_t)tap_tab[t.tap_tab + 2 * tap] +
+                       (size_t)(ge * t.Ci + ci) * tap_tab[t.tap_tab + 2 * tap + 1] + (co + e - ge * t.Cog)] =
+                        from_float<TS>(tile[jl][E * cq + e]);
+                }
             }
         }
     }
@@ -593,7 +601,7 @@ int update_plan_finish(std::vector<UpdateTask>& tasks, int dtype, int* total_blo
             t.tiles_j = ceil_div(t.J, kUpdTile);
             blocks += ceil_div(t.Co, kUpdTile) * t.tiles_j;
             const int E = dtype == DSP_BF16 ? 8 : 4;
-            t.wt_aligned = (t.Co % E == 0 && t.wt_off % E == 0) ? 1 : 0;  // every tap base and ci stride is a multiple of Co
+            t.wt_aligned = (t.Cog % E == 0 && t.wt_off % E == 0) ? 1 : 0;  // every tap base and ci stride is a multiple of Cog
             t.aligned = (t.p0 % 4 == 0 && t.J % 4 == 0) ? 1 : 0;
         }
         if (t.kind == 0) t.aligned = (t.p0 % 4 == 0) ? 1 : 0;

@@ -13,11 +13,14 @@ def rel_err(a, b):
     return float(np.linalg.norm((a - b).ravel()) / (nb if nb > 0 else 1.0))
 
 
-def dgrad_filter_copy(w, stride, pad):
-    """The filter copy dsp_conv_backward_data reads, from w[cout][cin][r][s]: the flipped filter
-    wf[cin][R-1-r][S-1-s][cout]; for stride 2 stored class by class of the input-pixel parity (hi % 2, wi % 2),
-    class (ph, pw) keeping the taps r' = r0, r0 + 2, ... and s' = s0, s0 + 2, ... with r0 = (R-1-pad - ph) mod 2."""
-    wf = np.ascontiguousarray(w[:, :, ::-1, ::-1].transpose(1, 2, 3, 0))
+def dgrad_filter_copy(w, stride, pad, groups=1):
+    """The filter copy dsp_conv_backward_data reads, from w[cout][cin / groups][r][s]: the flipped filter
+    wf[cin][R-1-r][S-1-s][cout / groups] (row g cin/groups + ci holds the output channels of group g); for stride 2
+    stored class by class of the input-pixel parity (hi % 2, wi % 2), class (ph, pw) keeping the taps r' = r0,
+    r0 + 2, ... and s' = s0, s0 + 2, ... with r0 = (R-1-pad - ph) mod 2."""
+    co = w.shape[0] // groups
+    wf = np.concatenate([np.ascontiguousarray(w[g * co:(g + 1) * co, :, ::-1, ::-1].transpose(1, 2, 3, 0))
+                         for g in range(groups)], axis=0)
     if stride == 1:
         return wf.ravel()
     R, S = w.shape[2], w.shape[3]

@@ -215,6 +215,9 @@ labels_by_batch = {}
     ("resnet164", D.DSP_BF16, 7, {"batch": 8, "hw": 16, "perturb": True}),
     # ResNet-1001 (same unit as ResNet-164; 387-915 layers per block, K = 4), every block twice through its update
     ("resnet1001", D.DSP_FP32, 9, {"batch": 4, "hw": 8, "perturb": True}),
+    # ResNeXt-29 (8 x 64d): grouped 3x3 convolutions of 512 / 1024 / 2048 channels, stride-2 grouped layers
+    ("resnext29", D.DSP_FP32, 11, {"batch": 4, "hw": 8}),
+    ("resnext29", D.DSP_BF16, 11, {"batch": 4, "hw": 8, "perturb": True}),
     # Eq. (3) beyond the constant-step heavy ball: Nesterov (s = 1), weight decay, a step schedule that drops
     # the step size twice while every block carries momentum
     ("resnet20", D.DSP_FP32, 9, {"batch": 8, "hw": 16, "perturb": True, "sum_s": 1, "wd": 5e-4,

@@ -84,6 +84,61 @@ def test_conv_forward_dgrad_wgrad(shape, dtype):
     assert torch.equal(d_dw, d_dw2)
 
 
+# (N, H, W, Cin, Cout, R, S, stride, pad, groups)
+GROUPED = [
+    (3, 9, 9, 32, 48, 3, 3, 1, 1, 4),       # 8 -> 12 channels per group: bf16 rows of the output are no whole 16-byte runs
+    (2, 12, 12, 64, 64, 3, 3, 2, 1, 8),     # stride 2 (parity classes per group)
+    (2, 8, 8, 128, 128, 3, 3, 1, 1, 2),     # 64 -> 64 per group
+    (2, 6, 6, 12, 6, 1, 1, 1, 0, 3),        # 4 -> 2 per group: element-wise paths
+    (2, 7, 7, 16, 16, 3, 3, 1, 1, 16),      # depthwise
+    (2, 10, 10, 512, 512, 3, 3, 1, 1, 8),   # ResNeXt-29 (8 x 64d) stage 1
+    (1, 9, 9, 256, 256, 3, 3, 2, 1, 8),     # 32 -> 32 per group, stride 2, odd sides
+    (5, 6, 6, 24, 64, 1, 1, 1, 0, 2),       # 12 -> 32 per group
+]
+
+
+@pytest.mark.parametrize("dtype", [D.DSP_FP32, D.DSP_BF16], ids=["fp32", "bf16"])
+@pytest.mark.parametrize("shape", GROUPED, ids=lambda s: "x".join(map(str, s)))
+def test_grouped_conv_forward_dgrad_wgrad(shape, dtype):
+    """The three kernels on grouped convolutions against the oracle's (one ordinary convolution per group); tensors start
+    as NaN so that a channel a group forgot to write shows."""
+    N, H, W, Ci, Co, R, S, st, pd, G = shape
+    rng = np.random.default_rng(hash(shape) % 2**32)
+    x = round_like(rng.standard_normal((N, Ci, H, W)), dtype)
+    w = round_like(rng.standard_normal((Co, Ci // G, R, S)) * np.sqrt(2.0 * G / (Ci * R * S)), dtype)
+    y_ref = O.conv2d_forward(x, w, st, pd, G)
+    dy = round_like(rng.standard_normal(y_ref.shape), dtype)
+    dx_ref = O.conv2d_backward_data(dy, w, x.shape, st, pd, G)
+    dw_ref = O.conv2d_backward_weight(x, dy, w.shape, st, pd, G)
+
+    td = torch.bfloat16 if dtype == D.DSP_BF16 else torch.float32
+    d_x, d_dy = to_dev(x, dtype), to_dev(dy, dtype)
+    d_w = torch.from_numpy(w.transpose(0, 2, 3, 1).copy()).to("cuda", td)         # [co][r][s][ci within the group]
+    d_wt = torch.from_numpy(dgrad_filter_copy(w, st, pd, G)).to("cuda", td)
+    d_y = torch.full((N * y_ref.shape[2] * y_ref.shape[3] * Co,), float("nan"), device="cuda", dtype=td)
+    D.dsp_grouped_conv_forward(dtype, d_x, d_w, d_y, N, H, W, Ci, Co, R, S, st, pd, G)
+    torch.cuda.synchronize()
+    assert rel_err(from_dev(d_y, y_ref.shape), y_ref) < _tol(dtype)
+
+    d_dx = torch.full((N * H * W * Ci,), float("nan"), device="cuda", dtype=td)
+    D.dsp_grouped_conv_backward_data(dtype, d_dy, d_wt, d_dx, N, H, W, Ci, Co, R, S, st, pd, G, accumulate=False)
+    torch.cuda.synchronize()
+    assert rel_err(from_dev(d_dx, x.shape), dx_ref) < _tol(dtype)
+    D.dsp_grouped_conv_backward_data(dtype, d_dy, d_wt, d_dx, N, H, W, Ci, Co, R, S, st, pd, G, accumulate=True)
+    torch.cuda.synchronize()
+    assert rel_err(from_dev(d_dx, x.shape), 2 * dx_ref) < _tol(dtype)
+
+    ws_bytes = D.dsp_grouped_conv_workspace_bytes(N, H, W, Ci, Co, R, S, st, pd, G)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    d_dw = torch.full((Co * R * S * (Ci // G),), float("nan"), device="cuda", dtype=torch.float32)
+    D.dsp_grouped_conv_backward_weight(dtype, d_x, d_dy, d_dw, N, H, W, Ci, Co, R, S, st, pd, G, ws, ws_bytes)
+    torch.cuda.synchronize()
+    dw = d_dw.cpu().numpy().astype(np.float64).reshape(Co, R, S, Ci // G).transpose(0, 3, 1, 2)
+    assert rel_err(dw, dw_ref) < _tol(dtype)
+    with pytest.raises(D.DSPError):
+        D.dsp_grouped_conv_forward(dtype, d_x, d_w, d_y, N, H, W, Ci, Co, R, S, st, pd, 5 if G != 5 else 7)  # 5 divides no case
+
+
 def test_conv_rejects_bad_arguments():
     x = torch.zeros(16, device="cuda")
     with pytest.raises(D.DSPError):
@@ -113,6 +168,9 @@ FULL = [
     (D.DSP_BF16, 256, 14, 14, 256, 256, 3, 3, 1, 1),   # ResNet-18 stage 3 (direct-to-LDS 256x256 tiles)
     (D.DSP_BF16, 250, 14, 14, 256, 256, 3, 3, 1, 1),   # the same with a ragged last row tile (M = 49000)
     (D.DSP_BF16, 125, 14, 14, 256, 384, 3, 3, 1, 1),   # direct-to-LDS 256x128 tiles, three column tiles, ragged rows
+    (D.DSP_BF16, 128, 32, 32, 512, 512, 3, 3, 1, 1, 8),   # ResNeXt-29 (8 x 64d) stage 1: 8 groups of 64 -> 64
+    (D.DSP_BF16, 128, 32, 32, 1024, 1024, 3, 3, 2, 1, 8), # stage 2 entry: 128 -> 128 per group, stride 2
+    (D.DSP_FP32, 64, 8, 8, 2048, 2048, 3, 3, 1, 1, 8),    # stage 3: 256 -> 256 per group
 ]
 
 
@@ -124,50 +182,51 @@ def _sample(rng, shape, n):
 
 @pytest.mark.parametrize("cfg", FULL, ids=lambda c: ("bf16_" if c[0] == D.DSP_BF16 else "fp32_") + "x".join(map(str, c[1:])))
 def test_conv_full_size_sampled(cfg):
-    dtype, N, H, W, Ci, Co, R, S, st, pd = cfg
+    dtype, N, H, W, Ci, Co, R, S, st, pd = cfg[:10]
+    G = cfg[10] if len(cfg) > 10 else 1
     rng = np.random.default_rng(1000 + Ci * 7 + Co * 3 + H)
     Ho, Wo = (H + 2 * pd - R) // st + 1, (W + 2 * pd - S) // st + 1
     x = round_like(rng.standard_normal((N, Ci, H, W), dtype=np.float32), dtype)
-    w = round_like((rng.standard_normal((Co, Ci, R, S)) * np.sqrt(2.0 / (Ci * R * S))).astype(np.float32), dtype)
+    w = round_like((rng.standard_normal((Co, Ci // G, R, S)) * np.sqrt(2.0 * G / (Ci * R * S))).astype(np.float32), dtype)
     dy = round_like(rng.standard_normal((N, Co, Ho, Wo), dtype=np.float32), dtype)
     td = torch.bfloat16 if dtype == D.DSP_BF16 else torch.float32
     d_x, d_dy = to_dev(x, dtype), to_dev(dy, dtype)
     d_w = torch.from_numpy(np.ascontiguousarray(w.transpose(0, 2, 3, 1))).to("cuda", td)
-    d_wt = torch.from_numpy(dgrad_filter_copy(w, st, pd)).to("cuda", td)
+    d_wt = torch.from_numpy(dgrad_filter_copy(w, st, pd, G)).to("cuda", td)
     # relative to the typical magnitude of the tensor: stored bf16 has 8 mantissa bits, fp32 sums ~1e-6
     tol = 1e-2 if dtype == D.DSP_BF16 else 1e-4
 
     d_y = torch.full((N * Ho * Wo * Co,), float("nan"), device="cuda", dtype=td)
-    D.dsp_conv_forward(dtype, d_x, d_w, d_y, N, H, W, Ci, Co, R, S, st, pd)
+    D.dsp_grouped_conv_forward(dtype, d_x, d_w, d_y, N, H, W, Ci, Co, R, S, st, pd, G)
     torch.cuda.synchronize()
     assert not torch.isnan(d_y.float()).any()
     y = d_y.view(N, Ho, Wo, Co)
     idx = _sample(rng, (N, Co, Ho, Wo), 48)
-    ref = O.conv2d_forward_at(x, w, st, pd, idx)
+    ref = O.conv2d_forward_at(x, w, st, pd, idx, G)
     got = np.array([float(y[n, ho, wo, k]) for (n, k, ho, wo) in idx])
     scale = max(np.sqrt(np.mean(ref ** 2)), 1e-6)
     assert np.abs(got - ref).max() < tol * 4 * scale, (np.abs(got - ref).max(), scale)
 
     d_dx = torch.full((N * H * W * Ci,), float("nan"), device="cuda", dtype=td)
-    D.dsp_conv_backward_data(dtype, d_dy, d_wt, d_dx, N, H, W, Ci, Co, R, S, st, pd, accumulate=False)
+    D.dsp_grouped_conv_backward_data(dtype, d_dy, d_wt, d_dx, N, H, W, Ci, Co, R, S, st, pd, G, accumulate=False)
     torch.cuda.synchronize()
     assert not torch.isnan(d_dx.float()).any()
     dx = d_dx.view(N, H, W, Ci)
     idx = _sample(rng, (N, Ci, H, W), 48)
-    ref = O.conv2d_backward_data_at(dy, w, x.shape, st, pd, idx)
+    ref = O.conv2d_backward_data_at(dy, w, x.shape, st, pd, idx, G)
     got = np.array([float(dx[n, hi, wi, c]) for (n, c, hi, wi) in idx])
     scale = max(np.sqrt(np.mean(ref ** 2)), 1e-6)
     assert np.abs(got - ref).max() < tol * 4 * scale, (np.abs(got - ref).max(), scale)
 
-    ws_bytes = D.dsp_conv_workspace_bytes(N, H, W, Ci, Co, R, S, st, pd)
+    ws_bytes = D.dsp_grouped_conv_workspace_bytes(N, H, W, Ci, Co, R, S, st, pd, G)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
-    d_dw = torch.full((Co * R * S * Ci,), float("nan"), device="cuda", dtype=torch.float32)
-    D.dsp_conv_backward_weight(dtype, d_x, d_dy, d_dw, N, H, W, Ci, Co, R, S, st, pd, ws, ws_bytes)
+    d_dw = torch.full((Co * R * S * (Ci // G),), float("nan"), device="cuda", dtype=torch.float32)
+    D.dsp_grouped_conv_backward_weight(dtype, d_x, d_dy, d_dw, N, H, W, Ci, Co, R, S, st, pd, G, ws, ws_bytes)
     torch.cuda.synchronize()
     assert not torch.isnan(d_dw).any()
-    dw = d_dw.view(Co, R, S, Ci)
-    idx = _sample(rng, (Co, Ci, R, S), 24)
-    ref = O.conv2d_backward_weight_at(x, dy, st, pd, idx)
+    dw = d_dw.view(Co, R, S, Ci // G)
+    idx = _sample(rng, (Co, Ci // G, R, S), 24)
+    ref = O.conv2d_backward_weight_at(x, dy, st, pd, idx, G)
     got = np.array([float(dw[k, r, s, c]) for (k, c, r, s) in idx])
     scale = max(np.sqrt(np.mean(ref ** 2)), 1e-6)
     # fp32 accumulation over N*Ho*Wo products of unit-variance terms

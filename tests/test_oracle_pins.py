@@ -330,6 +330,34 @@ def test_conv_matches_torch_and_adjoints(N, C, H, W, K, R, S, st, pd):
     assert abs(float((O.conv2d_forward(x, w2, st, pd) * g).sum()) - float((w2 * dw).sum())) < 1e-9
 
 
+@pytest.mark.parametrize("N,C,H,W,K,R,S,st,pd,G", [(2, 8, 7, 6, 12, 3, 3, 1, 1, 4), (3, 6, 9, 9, 6, 3, 3, 2, 1, 2),
+                                                   (2, 6, 5, 5, 6, 1, 1, 1, 0, 6), (1, 4, 8, 7, 8, 5, 5, 2, 2, 2)])
+def test_grouped_conv_is_the_block_diagonal_dense_conv(N, C, H, W, K, R, S, st, pd, G):
+    """A grouped convolution equals the dense one whose filter bank is zero outside the diagonal channel blocks; its
+    two gradients are those of the dense problem (the filter gradient restricted to the blocks).  Also against
+    torch's ``groups=`` and the adjoint identities with arbitrary second arguments."""
+    rng = np.random.default_rng(40 + G)
+    Ci, Co = C // G, K // G
+    x, w = rng.standard_normal((N, C, H, W)), rng.standard_normal((K, Ci, R, S))
+    dense = np.zeros((K, C, R, S))
+    for g in range(G):
+        dense[g * Co:(g + 1) * Co, g * Ci:(g + 1) * Ci] = w[g * Co:(g + 1) * Co]
+    y = O.conv2d_forward(x, w, st, pd, G)
+    np.testing.assert_allclose(y, O.conv2d_forward(x, dense, st, pd), rtol=1e-13, atol=1e-13)
+    yt = torch.nn.functional.conv2d(torch.tensor(x), torch.tensor(w), stride=st, padding=pd, groups=G).numpy()
+    np.testing.assert_allclose(y, yt, rtol=1e-12, atol=1e-12)
+    gy = rng.standard_normal(y.shape)
+    dx = O.conv2d_backward_data(gy, w, x.shape, st, pd, G)
+    dw = O.conv2d_backward_weight(x, gy, w.shape, st, pd, G)
+    np.testing.assert_allclose(dx, O.conv2d_backward_data(gy, dense, x.shape, st, pd), rtol=1e-12, atol=1e-12)
+    dwd = O.conv2d_backward_weight(x, gy, dense.shape, st, pd)
+    for g in range(G):
+        np.testing.assert_allclose(dw[g * Co:(g + 1) * Co], dwd[g * Co:(g + 1) * Co, g * Ci:(g + 1) * Ci], rtol=1e-12, atol=1e-12)
+    x2, w2 = rng.standard_normal(x.shape), rng.standard_normal(w.shape)
+    assert abs(float((O.conv2d_forward(x2, w, st, pd, G) * gy).sum()) - float((x2 * dx).sum())) < 1e-9
+    assert abs(float((O.conv2d_forward(x, w2, st, pd, G) * gy).sum()) - float((w2 * dw).sum())) < 1e-9
+
+
 def test_conv_1x1_is_matmul_and_delta_is_shift():
     rng = np.random.default_rng(2)
     x, w = rng.standard_normal((2, 5, 4, 3)), rng.standard_normal((6, 5, 1, 1))
@@ -414,7 +442,8 @@ def _block_in_shape(cfg, k):
 
 @pytest.mark.parametrize("name,k,batch,hw", [("tiny2", 0, 2, 6), ("tiny2", 1, 2, 6), ("resnet20", 1, 2, 8),
                                              ("resnet18", 0, 2, 16), ("resnet50_conv4x", 0, 2, 4),
-                                             ("resnet164", 1, 2, 8), ("vgg19", 1, 2, 32)])
+                                             ("resnet164", 1, 2, 8), ("vgg19", 1, 2, 32), ("resnext_tiny", 0, 2, 8),
+                                             ("resnext_tiny", 1, 2, 8)])
 def test_block_vjp_finite_differences(name, k, batch, hw):
     """Central differences in fp64 on s(x_k, h_k) = <f_k(h_k; x_k), G> for a fixed random G: this is
     exactly what lines 1-2 of Eq. (5) define.  Probes a few coordinates of every parameter tensor and of h_k."""
@@ -473,7 +502,7 @@ def _torch_net(cfg, params):
             for L, p in zip(layers, prm):
                 xin = src(L["in"])
                 if L["op"] == "conv":
-                    T.append(F.conv2d(xin, p["w"], stride=L["stride"], padding=L["pad"]))
+                    T.append(F.conv2d(xin, p["w"], stride=L["stride"], padding=L["pad"], groups=L.get("groups", 1)))
                 elif L["op"] == "bn":
                     z = F.batch_norm(xin, None, None, p["gamma"], p["beta"], training=True, eps=1e-5)
                     if L["res"] is not None:
@@ -510,7 +539,7 @@ def _torch_bp_sumsq(cfg, template, frozen, x, y):
 @pytest.mark.parametrize("name,batch,hw,loose", [("tiny2", 4, 8, 1), ("resnet20", 4, 8, 1), ("resnet18", 2, 64, 1),
                                                  # 164 layers amplify the fp64 rounding differences of two evaluation
                                                  # orders about a thousandfold more than 18 do (gradients still agree to 1e-4: no formula differs)
-                                                 ("resnet164", 4, 16, 1000), ("vgg19", 2, 32, 1)])
+                                                 ("resnet164", 4, 16, 1000), ("vgg19", 2, 32, 1), ("resnext_tiny", 4, 8, 1)])
 def test_zero_staleness_equals_backprop_sgd(name, batch, hw, loose):
     """Section 3.1 remark (a): with Delta t_k = 0 DSP is backpropagation; step for step against
     torch.autograd + torch.optim.SGD(momentum) in fp64 on the same net, data and initial parameters."""
@@ -633,24 +662,25 @@ def test_bf16_gradient_reproducibility_floor():
 
 
 @pytest.mark.parametrize("shape", [(2, 5, 9, 8, 4, 3, 3, 1, 1), (3, 4, 10, 10, 6, 3, 3, 2, 1), (2, 3, 12, 11, 5, 7, 7, 2, 3),
-                                   (2, 6, 7, 7, 4, 1, 1, 2, 0)])
+                                   (2, 6, 7, 7, 4, 1, 1, 2, 0), (2, 6, 7, 8, 9, 3, 3, 1, 1, 3), (2, 8, 9, 9, 4, 3, 3, 2, 1, 2)])
 def test_single_element_convolutions_agree_with_the_full_ones(shape):
     """The per-element definitions used for full-size GPU parity are written independently (numpy slicing)
     of the C loops; on small problems every element of both must agree."""
-    N, C, H, W, K, R, S, st, pd = shape
+    N, C, H, W, K, R, S, st, pd = shape[:9]
+    G = shape[9] if len(shape) > 9 else 1
     rng = np.random.default_rng(11)
     x = rng.standard_normal((N, C, H, W))
-    w = rng.standard_normal((K, C, R, S))
-    y = O.conv2d_forward(x, w, st, pd)
+    w = rng.standard_normal((K, C // G, R, S))
+    y = O.conv2d_forward(x, w, st, pd, G)
     dy = rng.standard_normal(y.shape)
-    dx = O.conv2d_backward_data(dy, w, x.shape, st, pd)
-    dw = O.conv2d_backward_weight(x, dy, w.shape, st, pd)
+    dx = O.conv2d_backward_data(dy, w, x.shape, st, pd, G)
+    dw = O.conv2d_backward_weight(x, dy, w.shape, st, pd, G)
     iy = [tuple(int(v) for v in np.unravel_index(i, y.shape)) for i in range(y.size)]
     ix = [tuple(int(v) for v in np.unravel_index(i, x.shape)) for i in range(x.size)]
     iw = [tuple(int(v) for v in np.unravel_index(i, w.shape)) for i in range(w.size)]
-    np.testing.assert_allclose(O.conv2d_forward_at(x, w, st, pd, iy), y.ravel(), rtol=1e-12, atol=1e-12)
-    np.testing.assert_allclose(O.conv2d_backward_data_at(dy, w, x.shape, st, pd, ix), dx.ravel(), rtol=1e-12, atol=1e-12)
-    np.testing.assert_allclose(O.conv2d_backward_weight_at(x, dy, st, pd, iw), dw.ravel(), rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(O.conv2d_forward_at(x, w, st, pd, iy, G), y.ravel(), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(O.conv2d_backward_data_at(dy, w, x.shape, st, pd, ix, G), dx.ravel(), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(O.conv2d_backward_weight_at(x, dy, st, pd, iw, G), dw.ravel(), rtol=1e-11, atol=1e-11)
 
 
 # ----------------------------------------------------------------------------- bf16 storage mode, decisions handed in

@@ -3,7 +3,8 @@
 A block of the split CNN is a list of layer dicts.  Layer ``i`` produces tensor
 ``i``; ``"in": -1`` names the block input h_k.  Ops:
 
-  conv        cin, cout, r, s, stride, pad           (cross-correlation, no bias)
+  conv        cin, cout, r, s, stride, pad [, groups]  (cross-correlation, no bias; ``groups`` > 1: group g maps input
+              channels [g cin/groups, (g+1) cin/groups) to output channels [g cout/groups, (g+1) cout/groups))
   bn          c, res (tensor index, -1, or None), relu   y = [relu](BN(x) [+ res])
   add         res (tensor index or -1)               y = x + res
   maxpool     k, stride, pad
@@ -35,9 +36,25 @@ class _B:
         self.layers.append(kw)
         return len(self.layers) - 1
 
-    def conv(self, src, cin, cout, k, stride=1, pad=None):
+    def conv(self, src, cin, cout, k, stride=1, pad=None, groups=1):
         pad = (k // 2) if pad is None else pad
-        return self.add(op="conv", **{"in": src}, cin=cin, cout=cout, r=k, s=k, stride=stride, pad=pad)
+        kw = {"groups": groups} if groups > 1 else {}
+        return self.add(op="conv", **{"in": src}, cin=cin, cout=cout, r=k, s=k, stride=stride, pad=pad, **kw)
+
+    def resnext_unit(self, src, cin, width, cout, stride, cardinality):
+        """Aggregated-transform bottleneck: 1x1 -> grouped 3x3 (``cardinality`` groups) -> 1x1, each followed by batch
+        norm, projection shortcut (1x1 conv + BN) when the shape changes, ReLU after the sum."""
+        a = self.conv(src, cin, width, 1, 1, pad=0)
+        a = self.bn(a, width, relu=True)
+        a = self.conv(a, width, width, 3, stride, groups=cardinality)
+        a = self.bn(a, width, relu=True)
+        a = self.conv(a, width, cout, 1, 1, pad=0)
+        if stride != 1 or cin != cout:
+            sc = self.conv(src, cin, cout, 1, stride, pad=0)
+            sc = self.bn(sc, cout, relu=False)
+        else:
+            sc = src
+        return self.bn(a, cout, relu=True, res=sc)
 
     def bn(self, src, c, relu=True, res=None):
         return self.add(op="bn", **{"in": src}, c=c, relu=relu, res=res)
@@ -145,6 +162,33 @@ def _preact_resnet_cifar(per_block_units, classes, units_per_stage=18, widths=(1
     return blocks
 
 
+def _resnext29(per_block_units, classes=10, cardinality=8, base_width=64, units_per_stage=3, out0=256):
+    """ResNeXt-29 (cardinality x base_width d, e.g. 8 x 64d) for 32x32 inputs: 3x3 stem of 64 channels, three stages of
+    three aggregated bottleneck units (grouped 3x3 of width cardinality * base_width * 2^stage, outputs 256 / 512 /
+    1024 channels), global average pool, linear.  ``per_block_units``: units per DSP block."""
+    seq, cin = [], 64
+    for si in range(3):
+        width, cout = cardinality * base_width * 2 ** si, out0 * 2 ** si
+        for u in range(units_per_stage):
+            seq.append((cin, width, cout, 2 if (si > 0 and u == 0) else 1))
+            cin = cout
+    assert sum(per_block_units) == len(seq)
+    blocks, pos = [], 0
+    for bi, cnt in enumerate(per_block_units):
+        b = _B()
+        src = -1
+        if bi == 0:
+            src = b.conv(-1, 3, 64, 3)
+            src = b.bn(src, 64)
+        for (ci, wd, co, st) in seq[pos:pos + cnt]:
+            src = b.resnext_unit(src, ci, wd, co, st, cardinality)
+        pos += cnt
+        if bi == len(per_block_units) - 1:
+            b.head(src, seq[-1][2], classes)
+        blocks.append(b.layers)
+    return blocks
+
+
 def _resnet18(classes=1000):
     widths = (64, 128, 256, 512)
     blocks = []
@@ -229,6 +273,13 @@ CONFIGS = {
     "resnet1001": dict(blocks=lambda: _preact_resnet_cifar((70, 70, 95, 98), 100, units_per_stage=111),
                        input=(128, 3, 32, 32), classes=100, p=(1, 1, 1, 0), m=(6, 4, 2, 0), lr=0.01, beta=0.9, wd=0.0,
                        steps=20, seed=8, dtypes=("fp32", "bf16")),
+    # ResNeXt-29 (8 x 64d), the grouped-convolution network of the paper's speed-up table (CIFAR-10, K = 4, batch 128)
+    "resnext29": dict(blocks=lambda: _resnext29((2, 2, 2, 3)), input=(128, 3, 32, 32), classes=10, p=(1, 1, 1, 0),
+                      m=(6, 4, 2, 0), lr=0.01, beta=0.9, wd=0.0, steps=20, seed=9, dtypes=("bf16", "fp32")),
+    # the same graph with narrow channels, for finite differences and torch-autograd checks of the oracle (tests only)
+    "resnext_tiny": dict(blocks=lambda: _resnext29((1, 2), cardinality=2, base_width=4, units_per_stage=1, out0=16),
+                         input=(8, 3, 16, 16), classes=10, p=(1, 0), m=(2, 0), lr=0.01, beta=0.9, wd=0.0, steps=4, seed=10,
+                         dtypes=("fp32",)),
     # not one of the paper-shaped workloads: a parity probe for the streaming kernels at large M (tests only)
     "bn_probe": dict(blocks=_bn_probe, input=(128, 64, 56, 56), classes=None, p=(0,), m=(1,), lr=0.01, beta=0.9,
                      wd=0.0, steps=3, seed=5, dtypes=("fp32", "bf16"), grad_std=0.1, data_input=False),
@@ -308,7 +359,7 @@ def param_shapes(layers):
     out = []
     for L in layers:
         if L["op"] == "conv":
-            out.append([("w", (L["cout"], L["cin"], L["r"], L["s"]))])
+            out.append([("w", (L["cout"], L["cin"] // L.get("groups", 1), L["r"], L["s"]))])
         elif L["op"] == "bn":
             out.append([("gamma", (L["c"],)), ("beta", (L["c"],))])
         elif L["op"] == "linear":
@@ -324,7 +375,7 @@ def count_macs(layers, in_shape):
     macs = 0
     for L, s in zip(layers, shapes):
         if L["op"] == "conv":
-            macs += s[1] * s[2] * s[3] * L["cin"] * L["r"] * L["s"]
+            macs += s[1] * s[2] * s[3] * (L["cin"] // L.get("groups", 1)) * L["r"] * L["s"]
         elif L["op"] == "linear":
             macs += L["cin"] * L["cout"]
     return macs
