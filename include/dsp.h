@@ -108,7 +108,10 @@ typedef struct dsp_pipeline dsp_pipeline;
  * Validates DSP(p; m) and writes q_k = m_{k-1} - p_{k-1} - m_k (q_0 = 0) into q[K].
  * Accepted: p_k > 0 for k < K-1, p_{K-1} = 0, m_k > 0 for k < K-1, m_{K-1} >= 0 (the paper's own
  * schedules end in m = 0), q_k > 0 for k >= 1; or the all-zero schedule, which is ordinary
- * backpropagation (Section 3.1, remark a).  Anything else: DSP_EINVAL.
+ * backpropagation (Section 3.1, remark a; with K blocks: the model-parallel BP of Section 6); or every
+ * p_k = 0 with m_k > 0 for k < K-1 and q_k > 0: forward-locked, stale backward passes -- with
+ * m_k = K-1-k the schedule of the features-replay comparison of Section 6 (the pipeline then orders the
+ * forward passes of a tick block after block).  Anything else: DSP_EINVAL.
  */
 int dsp_schedule_validate(int32_t K, const int32_t* p, const int32_t* m, int32_t* q);
 

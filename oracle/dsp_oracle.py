@@ -481,7 +481,10 @@ def queue_lengths(p, m):
     """Appendix A: q_0 = 0, q_k = m_{k-1} - p_{k-1} - m_k; validates the schedule.
 
     Accepted: (i) the all-zero schedule = ordinary backpropagation (Section 3.1, remark a);
-    (ii) p_k > 0 for k < K-1, p_{K-1} = 0, m_k > 0 for k < K-1, m_{K-1} >= 0, q_k > 0 for k >= 1.
+    (ii) p_k > 0 for k < K-1, p_{K-1} = 0, m_k > 0 for k < K-1, m_{K-1} >= 0, q_k > 0 for k >= 1;
+    (iii) every p_k = 0 with m_k > 0 for k < K-1 and q_k > 0: no output queue delays anything, so a mini-batch
+    runs forward through all blocks within one tick (forward locking) while the backward passes stay stale --
+    with m_k = K-1-k this is the schedule of the features-replay comparison of Section 6 (q_k = 1).
     """
     K = len(m)
     if len(p) != K:
@@ -490,8 +493,8 @@ def queue_lengths(p, m):
         return [0] * K
     if p[K - 1] != 0:
         raise ValueError("p_{K-1} must be 0")
-    if any(v <= 0 for v in p[:K - 1]):
-        raise ValueError("p_k must be > 0 for k < K-1")
+    if any(v <= 0 for v in p[:K - 1]) and any(v != 0 for v in p):
+        raise ValueError("p_k must be > 0 for k < K-1 (or every p_k = 0)")
     if any(v <= 0 for v in m[:K - 1]) or m[K - 1] < 0:
         raise ValueError("m_k must be > 0 for k < K-1 and >= 0 for the last block")
     q = [0] + [m[k - 1] - p[k - 1] - m[k] for k in range(1, K)]

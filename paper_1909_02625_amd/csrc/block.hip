@@ -912,8 +912,16 @@ int dsp_block_recompute_backward(dsp_block* b, int64_t batch_id, const void* d_g
 int dsp_block_step(dsp_block* b, int64_t batch_fwd, const void* d_in, void* d_out, const int32_t* d_labels, float* d_loss,
                    int64_t batch_bwd, const void* d_grad_out, void* d_grad_in, void* stream)
 {
+    return block_step_event(b, batch_fwd, d_in, d_out, d_labels, d_loss, batch_bwd, d_grad_out, d_grad_in, (hipStream_t)stream,
+                            nullptr);
+}
+
+}  // extern "C"
+
+int dsp::block_step_event(dsp_block* b, int64_t batch_fwd, const void* d_in, void* d_out, const int32_t* d_labels, float* d_loss,
+                     int64_t batch_bwd, const void* d_grad_out, void* d_grad_in, hipStream_t st, hipEvent_t after_forward)
+{
     DSP_REQUIRE(b && d_in, DSP_EINVAL, "dsp_block_step: null argument");
-    hipStream_t st = (hipStream_t)stream;
     if (b->desc.m_k > 0 && !b->fwd_lane && !b->dry) DSP_TRY(dsp_block_enable_forward_lane(b));
     ForwardCall fc;
     BackwardCall bc;
@@ -930,9 +938,12 @@ int dsp_block_step(dsp_block* b, int64_t batch_fwd, const void* d_in, void* d_ou
         const ForwardPass recompute{nullptr, bc.slot, nullptr};
         DSP_TRY(run_forward(b, ForwardPass{b->fwd_lane, fc.slot, d_out}, &recompute, d_labels, fc.loss, fc.dz, st));
     }
+    if (after_forward) DSP_HIP(hipEventRecord(after_forward, st));
     DSP_TRY(run_backward(b, bc.slot, bc.gout, d_grad_in, st));
     return DSP_OK;
 }
+
+extern "C" {
 
 int dsp_param_update_sum(dsp_block* b, float lr, float momentum, int32_t s, float weight_decay, void* stream)
 {

@@ -18,6 +18,10 @@ namespace dsp {
 // While a block is "dry" its step calls check and advance the host-side state (batch ids, update
 // counter) but launch nothing: the pipeline replays the launches of that tick from a HIP graph.
 void block_set_dry(dsp_block* b, bool dry);
+// dsp_block_step that records `after_forward` (if not null) on the stream once the forward sweeps are issued, i.e.
+// when the block's output for the block above is complete, before the backward sweep.
+int block_step_event(dsp_block* b, int64_t batch_fwd, const void* d_in, void* d_out, const int32_t* d_labels, float* d_loss,
+                     int64_t batch_bwd, const void* d_grad_out, void* d_grad_in, hipStream_t st, hipEvent_t after_forward);
 
 // The block's flat fp32 parameter and gradient arrays (library layout) and their length.
 struct BlockArrays {

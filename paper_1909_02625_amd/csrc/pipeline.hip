@@ -20,7 +20,9 @@
 // per phase of the ring rotation, lcm(ring sizes) of them -- with the K block chains as parallel
 // branches, and later ticks of the same phase replay that graph with a single launch while the
 // blocks' host-side state is advanced without launching.
+#include <atomic>
 #include <condition_variable>
+#include <memory>
 #include <mutex>
 #include <new>
 #include <numeric>
@@ -46,8 +48,12 @@ int validate_schedule(int K, const int32_t* p, const int32_t* m, int32_t* q)
     }
     DSP_REQUIRE(p[K - 1] == 0, DSP_EINVAL, "schedule: p_{K-1} must be 0");
     DSP_REQUIRE(m[K - 1] >= 0, DSP_EINVAL, "schedule: m_{K-1} must be >= 0");
+    // all p_k = 0 with stale backward passes: the forward-locked schedule of the features-replay comparison
+    // (Section 6); otherwise every p_k below the last block must be positive (Appendix A)
+    bool locked = true;
+    for (int k = 0; k < K; ++k) locked = locked && p[k] == 0;
     for (int k = 0; k < K - 1; ++k) {
-        DSP_REQUIRE(p[k] > 0, DSP_EINVAL, "schedule: p_%d must be > 0", k);
+        DSP_REQUIRE(locked || p[k] > 0, DSP_EINVAL, "schedule: p_%d must be > 0 (or every p_k = 0)", k);
         DSP_REQUIRE(m[k] > 0, DSP_EINVAL, "schedule: m_%d must be > 0", k);
     }
     for (int k = 1; k < K; ++k) {
@@ -77,6 +83,11 @@ struct Worker {
 struct dsp_pipeline {
     int K = 0;
     bool serial = false;  // all-zero schedule: ordinary backpropagation, one stream
+    // every p_k = 0 but the backward passes are stale (the features-replay schedule): the forward passes of a tick
+    // form one chain through the blocks (block k+1 reads what block k wrote in the same tick); recompute, backward and
+    // update of the K blocks still run side by side
+    bool fwd_locked = false;
+    std::unique_ptr<std::atomic<int64_t>[]> fwd_issued;  // fwd_issued[k] = ticks whose forward-done event block k has recorded
     std::vector<dsp_block*> blocks;
     std::vector<int32_t> p, m, q, P;  // P[k] = sum_{j<k} p_j
     float lr = 0, momentum = 0, wd = 0;
@@ -359,7 +370,7 @@ static int pipeline_build(dsp_pipeline* pl, dsp_block* const* blocks)
     }
     pl->label_slots = label_slots;
     period = std::lcm(period, (int64_t)pl->label_slots);
-    pl->period = (pl->serial || period > kMaxGraphs) ? 0 : (int)period;
+    pl->period = (pl->serial || pl->fwd_locked || period > kMaxGraphs) ? 0 : (int)period;
     pl->graphs.assign(pl->period, nullptr);
     void* ptr;
     DSP_TRY(pl_alloc(pl, &ptr, (size_t)pl->label_slots * pl->N * 4));
@@ -402,6 +413,10 @@ int dsp_pipeline_init(int32_t K, dsp_block* const* blocks, const int32_t* p, con
     pl->serial = true;
     for (int k = 0; k < K; ++k) pl->serial = pl->serial && p[k] == 0 && m[k] == 0;
     if (K == 1) pl->serial = false;
+    pl->fwd_locked = !pl->serial && K > 1;
+    for (int k = 0; k < K; ++k) pl->fwd_locked = pl->fwd_locked && p[k] == 0;
+    pl->fwd_issued.reset(new std::atomic<int64_t>[K]);
+    for (int k = 0; k < K; ++k) pl->fwd_issued[k].store(0);
     pl->lr = lr;
     pl->momentum = momentum;
     pl->wd = weight_decay;
@@ -505,6 +520,7 @@ int dsp_pipeline_set_forward_streams(dsp_pipeline* pl, int32_t enable)
     DSP_REQUIRE(pl->tau == 0, DSP_ESTATE, "dsp_pipeline_set_forward_streams: the pipeline has already been stepped");
     DSP_REQUIRE(!enable || pl->ev_depth == 2, DSP_EINVAL,
                 "dsp_pipeline_set_forward_streams: not with spare queue entries (its waits are one tick deep)");
+    DSP_REQUIRE(!enable || !pl->fwd_locked, DSP_EINVAL, "dsp_pipeline_set_forward_streams: not with a forward-locked schedule");
     pl->use_fwd_streams = enable != 0;
     return DSP_OK;
 }
@@ -566,7 +582,7 @@ static int tick_backward(dsp_pipeline* pl, int k, int64_t tau, hipStream_t st, b
 
 // Both of the above through dsp_block_step (same results, one launch per layer for the two forward
 // sweeps).  *fused = false if the tick has only one of the two parts; nothing is issued then.
-static int tick_step(dsp_pipeline* pl, int k, int64_t tau, hipStream_t st, bool dry, bool* fused)
+static int tick_step(dsp_pipeline* pl, int k, int64_t tau, hipStream_t st, bool dry, bool* fused, hipEvent_t after_forward = nullptr)
 {
     const int K = pl->K;
     const int64_t a = tau - pl->P[k], bb = a - pl->m[k];
@@ -581,7 +597,7 @@ static int tick_step(dsp_pipeline* pl, int k, int64_t tau, hipStream_t st, bool 
     const bool last = k == K - 1;
     const void* gout = k < K - 1 ? pl->qring[k + 1] + (size_t)(bb % pl->qn[k + 1]) * pl->qslot_bytes[k + 1] : nullptr;
     void* gin = k > 0 ? pl->qring[k] + (size_t)(bb % pl->qn[k]) * pl->qslot_bytes[k] : nullptr;
-    DSP_TRY(dsp_block_step(b, a, in, out, last ? lab : nullptr, last ? pl->loss_tmp : nullptr, bb, gout, gin, st));
+    DSP_TRY(block_step_event(b, a, in, out, last ? lab : nullptr, last ? pl->loss_tmp : nullptr, bb, gout, gin, st, after_forward));
     if (last && !dry) DSP_TRY(launch_record_loss(pl->loss_tmp, pl->losses, pl->loss_count, pl->max_ticks + 1, st));
     return DSP_OK;
 }
@@ -638,6 +654,34 @@ static int run_block_tick(dsp_pipeline* pl, int k, int64_t tau)
     if (pl->delay_us[k] > 0) {
         DSP_TRY(launch_spin(pl->delay_us[k], sb));
         if (split) DSP_TRY(launch_spin(pl->delay_us[k], sf));
+    }
+    if (pl->fwd_locked) {
+        // This tick's forward pass of the block below produced the input (and, being later on that stream than its
+        // previous tick, also stands for everything this block overwrites having been read).  Its host thread
+        // records that event some time during this tick: wait until it has.
+        if (k > 0) {
+            while (pl->fwd_issued[k - 1].load(std::memory_order_acquire) <= tau) std::this_thread::yield();
+            DSP_HIP(hipStreamWaitEvent(sb, pl->fdone[fcur][k - 1], 0));
+        }
+        bool fused = false;
+        int rc = tick_step(pl, k, tau, sb, false, &fused, pl->fdone[fcur][k]);
+        if (rc == DSP_OK && fused) {
+            pl->fwd_issued[k].store(tau + 1, std::memory_order_release);
+            rc = tick_update(pl, k, sb);
+        } else if (rc == DSP_OK) {
+            rc = tick_forward(pl, k, tau, sb, false);
+            if (rc == DSP_OK && hipEventRecord(pl->fdone[fcur][k], sb) != hipSuccess) rc = DSP_EHIP;
+            pl->fwd_issued[k].store(tau + 1, std::memory_order_release);
+            bool did = false;
+            if (rc == DSP_OK) rc = tick_backward(pl, k, tau, sb, &did);
+            if (rc == DSP_OK && did) rc = tick_update(pl, k, sb);
+        }
+        if (rc != DSP_OK) {
+            pl->fwd_issued[k].store(tau + 1, std::memory_order_release);  // never leave the block above spinning
+            return rc;
+        }
+        DSP_HIP(hipEventRecord(pl->done[cur][k], sb));
+        return DSP_OK;
     }
     if (!split) {
         DSP_TRY(block_tick(pl, k, tau, sb, true, true));
@@ -815,8 +859,12 @@ int dsp_pipeline_step(dsp_pipeline* pl, const void* d_batch, const int32_t* d_la
     DSP_HIP(hipStreamWaitEvent(user, pl->in_copied, 0));
 
     if (pl->serial) {
-        // ordinary backpropagation: forward up the chain, backward down the chain, one stream
-        for (int k = 0; k < K; ++k) DSP_TRY(block_tick(pl, k, tau, s0, true, false));
+        // ordinary backpropagation: forward up the chain, backward down the chain, one stream (a delayed block
+        // holds the whole chain up, as a slow device does in model-parallel backpropagation)
+        for (int k = 0; k < K; ++k) {
+            if (pl->delay_us[k] > 0) DSP_TRY(launch_spin(pl->delay_us[k], s0));
+            DSP_TRY(block_tick(pl, k, tau, s0, true, false));
+        }
         for (int k = K - 1; k >= 0; --k) DSP_TRY(block_tick(pl, k, tau, s0, false, true));
     } else if (!graph_tick) {
         DSP_TRY(issue_tick(pl, tau, false));

@@ -341,6 +341,11 @@ def _manual_schedule(cfg, params, batches, dtype):
     ("resnet20", D.DSP_FP32, 12, {"batch": 4, "hw": 8, "p": (2, 2, 0), "m": (6, 3, 0)}),   # p = 2: deeper queues
     ("resnet20", D.DSP_FP32, 12, {"batch": 4, "hw": 8, "p": (1, 1, 0), "m": (7, 3, 1)}),   # q_1 = 3, stale last block
     ("resnet1001", D.DSP_BF16, 10, {"batch": 2, "hw": 8}),                                 # K = 4, up to 915 layers per block
+    # forward-locked schedules (every p_k = 0; m_k = K-1-k is the features-replay comparison of Section 6): block k+1
+    # reads in the same tick what block k wrote
+    ("resnet20", D.DSP_FP32, 14, {"batch": 4, "hw": 8, "p": (0, 0, 0), "m": (2, 1, 0)}),
+    ("resnet56", D.DSP_BF16, 12, {"batch": 8, "hw": 16, "p": (0, 0, 0, 0), "m": (3, 2, 1, 0)}),
+    ("resnet20", D.DSP_FP32, 14, {"batch": 4, "hw": 8, "p": (0, 0, 0), "m": (5, 2, 1)}),   # q_1 = 3, stale last block
 ], ids=lambda v: v if isinstance(v, str) else None)
 @pytest.mark.parametrize("mode", ["twin", "separate", "forward_streams"])
 def test_pipeline_equals_manual_fifo_schedule_bit_for_bit(name, dtype, ticks, kw, mode):
@@ -355,8 +360,12 @@ def test_pipeline_equals_manual_fifo_schedule_bit_for_bit(name, dtype, ticks, kw
     blocks = build_gpu_blocks(cfg, params, dtype)
     pl = D.dsp_pipeline_init(blocks, cfg["p"], cfg["m"], cfg["lr"], cfg["beta"], cfg["wd"], ticks)
     D.dsp_pipeline_set_twin_launches(pl, mode == "twin")
-    D.dsp_pipeline_set_forward_streams(pl, mode == "forward_streams")
     try:
+        if mode == "forward_streams" and not any(cfg["p"]):
+            with pytest.raises(D.DSPError):   # a forward-locked schedule has no use for forward streams
+                D.dsp_pipeline_set_forward_streams(pl, True)
+        else:
+            D.dsp_pipeline_set_forward_streams(pl, mode == "forward_streams")
         for x, y in batches:
             D.dsp_pipeline_step(pl, to_dev(x, dtype), torch.from_numpy(y).cuda())
         got = D.dsp_pipeline_losses(pl)
@@ -377,6 +386,7 @@ def test_pipeline_equals_manual_fifo_schedule_bit_for_bit(name, dtype, ticks, kw
     ("resnet20", D.DSP_FP32, 26, {"batch": 4, "hw": 8, "p": (3, 3, 0), "m": (10, 5, 0)}, 4, False),   # q = 2: waits 3 down, 2 up
     ("resnet20", D.DSP_FP32, 20, {"batch": 4, "hw": 8, "p": (1, 1, 0), "m": (7, 3, 1)}, 2, False),    # q_1 = 3, stale last block
     ("resnet56", D.DSP_BF16, 16, {"batch": 8, "hw": 16}, 2, False),
+    ("resnet20", D.DSP_FP32, 20, {"batch": 4, "hw": 8, "p": (0, 0, 0), "m": (2, 1, 0)}, 1, False),    # forward-locked
     ("resnet20", D.DSP_FP32, 60, {"batch": 4, "hw": 8, "p": (2, 2, 0), "m": (6, 3, 0)}, 1, True),     # ring period 60 with the spare entry
 ], ids=lambda v: v if isinstance(v, str) else None)
 def test_spare_queue_entries_and_random_stragglers_change_no_bit(name, dtype, ticks, kw, spare, graphs):
@@ -463,6 +473,10 @@ def _oracle_spread(cfg, params, rng_state, dtype, ticks, ref_losses, ref_orc):
     ("resnet20", D.DSP_BF16, 16, {"batch": 16, "hw": 16}),
     ("resnet56", D.DSP_FP32, 14, {"batch": 16, "hw": 16}),
     ("vgg19", D.DSP_FP32, 8, {"batch": 32}),
+    # the features-replay schedule (every block updates from tick 2 on, so the rounding differences start to grow
+    # earlier than under DSP(1,1,0;4,2,0): 10 ticks stay inside the band)
+    ("resnet20", D.DSP_FP32, 10, {"batch": 16, "hw": 16, "p": (0, 0, 0), "m": (2, 1, 0)}),
+    ("resnext29", D.DSP_BF16, 12, {"batch": 4, "hw": 8}),
 ], ids=lambda v: v if isinstance(v, str) else None)
 def test_pipeline_loss_trajectory(name, dtype, ticks, kw):
     cfg, params, rng = _setup(name, **kw)

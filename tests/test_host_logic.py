@@ -44,8 +44,9 @@ def test_schedule_validate_matches_paper_tuples(p, m, q):
     assert D.dsp_schedule_validate(p, m) == list(q) == O.queue_lengths(p, m)
 
 
-@pytest.mark.parametrize("p,m", [((1, 0), (1, 0)), ((2, 0), (2, 0)), ((1, 1, 0), (2, 2, 0)), ((0, 0), (2, 0)),
-                                 ((1, 0), (0, 0)), ((1, 1, 0), (4, 4, 0)), ((1, 0), (2, -1))])
+@pytest.mark.parametrize("p,m", [((1, 0), (1, 0)), ((2, 0), (2, 0)), ((1, 1, 0), (2, 2, 0)), ((0, 1, 0), (4, 2, 0)),
+                                 ((1, 0), (0, 0)), ((1, 1, 0), (4, 4, 0)), ((1, 0), (2, -1)), ((0, 0, 0), (1, 1, 0)),
+                                 ((0, 0, 0), (2, 0, 0))])
 def test_schedule_rejects_what_the_oracle_rejects(p, m):
     with pytest.raises(ValueError):
         O.queue_lengths(p, m)
@@ -54,7 +55,9 @@ def test_schedule_rejects_what_the_oracle_rejects(p, m):
 
 
 @pytest.mark.parametrize("p,m,_q", PAPER_TUPLES + [((1, 0), (2, 0), None), ((1, 1, 0), (7, 3, 1), None),
-                                                   ((2, 1, 3, 0), (12, 8, 4, 0), None), ((0, 0, 0), (0, 0, 0), None)])
+                                                   ((2, 1, 3, 0), (12, 8, 4, 0), None), ((0, 0, 0), (0, 0, 0), None),
+                                                   ((0, 0, 0), (2, 1, 0), None), ((0, 0, 0, 0), (3, 2, 1, 0), None),
+                                                   ((0, 0), (2, 0), None), ((0, 0, 0), (5, 2, 1), None)])
 def test_closed_form_index_equals_fifo_simulation(p, m, _q):
     """Brute force: the oracle pushes tagged items through real queues for 64 ticks; the library's closed
     form must name the same forward batch, backward batch and update count for every block and tick, and

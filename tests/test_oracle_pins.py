@@ -75,8 +75,9 @@ def test_paper_tuples_validate(p, m, q):
     assert O.queue_lengths(p, m) == list(q)
 
 
-@pytest.mark.parametrize("p,m", [((1, 0), (1, 0)), ((2, 0), (2, 0)), ((1, 1, 0), (2, 2, 0)), ((0, 0), (2, 0)),
-                                 ((1, 1), (2, 0)), ((1, 0), (0, 0)), ((1, 1, 0), (4, 4, 0))])
+@pytest.mark.parametrize("p,m", [((1, 0), (1, 0)), ((2, 0), (2, 0)), ((1, 1, 0), (2, 2, 0)), ((0, 1, 0), (4, 2, 0)),
+                                 ((1, 1), (2, 0)), ((1, 0), (0, 0)), ((1, 1, 0), (4, 4, 0)), ((0, 0, 0), (1, 1, 0)),
+                                 ((0, 0, 0), (2, 0, 0))])
 def test_invalid_schedules_rejected(p, m):
     with pytest.raises(ValueError):
         O.queue_lengths(p, m)
@@ -91,7 +92,28 @@ def _run_counting(p, m, ticks):
     return blocks, orc
 
 
-@pytest.mark.parametrize("p,m,_q", PAPER_TUPLES + [((1, 0), (2, 0), None), ((1, 1, 0), (7, 3, 1), None)])
+FORWARD_LOCKED = [((0, 0), (1, 0), (0, 1)), ((0, 0, 0), (2, 1, 0), (0, 1, 1)), ((0, 0, 0, 0), (3, 2, 1, 0), (0, 1, 1, 1)),
+                  ((0, 0), (2, 0), (0, 2)), ((0, 0, 0), (5, 2, 1), (0, 3, 1))]
+
+
+@pytest.mark.parametrize("p,m,q", FORWARD_LOCKED)
+def test_forward_locked_schedules(p, m, q):
+    """Every p_k = 0 (Section 6's features-replay comparison when m_k = K-1-k): each tick one mini-batch runs
+    forward through ALL blocks, block k's backward pass handles the mini-batch of m_k ticks ago with parameters
+    that have seen exactly m_k more updates, and the error gradient spends q_k = m_{k-1} - m_k ticks in Q_k."""
+    assert O.queue_lengths(p, m) == list(q)
+    K = len(p)
+    blocks, orc = _run_counting(p, m, 40)
+    for rec in orc.log:
+        tau = rec["tau"]
+        assert rec["fwd"] == [tau] * K and rec["loss_batch"] == tau
+        assert rec["bwd"] == [tau - m[k] if tau >= m[k] else None for k in range(K)]
+    for k in range(K):
+        for n, vb in blocks[k].bwd_version.items():
+            assert vb - blocks[k].fwd_version[n] == (m[k] if n >= m[k] else n)
+
+
+@pytest.mark.parametrize("p,m,_q", PAPER_TUPLES + [((1, 0), (2, 0), None), ((1, 1, 0), (7, 3, 1), None)] + FORWARD_LOCKED)
 def test_fifo_timeline_and_staleness(p, m, _q):
     """Real queues reproduce: forward batch tau - sum_{j<k} p_j, backward batch a - m_k, and the
     layer-wise staleness (Section 3.1; proof of Theorem 1: exactly Delta t_k = m_k updates lie
