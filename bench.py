@@ -347,7 +347,7 @@ def main():
         "conv_mfma_util_pct": None if conv_util is None else round(conv_util, 3),
         # sum of all kernel durations of a tick (over the K streams); K * ms_per_step minus this is stream idle time
         "kernel_time_ms_per_step": None if not table else round(sum(k["ms"] for k in table) / a.profile_steps, 4),
-        "roofline": roof, "cpu_baseline": base, "kernels": kernels[:12],
+        "library_build_id": D.dsp_build_id(), "roofline": roof, "cpu_baseline": base, "kernels": kernels[:12],
     }
     print(json.dumps(out))
 

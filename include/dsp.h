@@ -194,8 +194,12 @@ int dsp_block_step(dsp_block* b, int64_t batch_fwd, const void* d_in, void* d_ou
  * for s = 0, v^n = -(y^n - y^{n-1}) / lr for s = 1.
  * The block remembers the step size of its previous update; when lr differs from it, v is first
  * multiplied by (previous lr / lr), so that the momentum term stays the difference of iterates that
- * Eq. (3) prescribes under a learning-rate schedule.  lr = 0 leaves x unchanged (exact for
- * momentum = 0).  Other values of s need the previous gradient and are refused (DSP_EINVAL).
+ * Eq. (3) prescribes under a learning-rate schedule.  lr = 0 leaves x unchanged, which is what Eq. (3)
+ * gives as long as no momentum is carried (momentum = 0, or no update with lr > 0 so far: the probe
+ * pipeline of dsp_pipeline_attach_gradient_probe); a step of size 0 AFTER updates with lr > 0 and
+ * momentum != 0 would still have to move x by momentum * (x^n - x^{n-1}), which the velocity form cannot
+ * express, and is refused (DSP_EINVAL, nothing consumed).  Other values of s need the previous gradient
+ * and are refused (DSP_EINVAL).
  * Consumes the pending G_{x_k} exactly once (DSP_ESTATE if there is none) and increments the
  * update counter.  dsp_param_update is the s = 0 case.
  */
@@ -473,6 +477,9 @@ int dsp_profile_get(int32_t i, char* name, size_t name_len, int64_t* launches, d
 const char* dsp_strerror(int status);
 /* Text of the most recent failure on this thread ("" if none). */
 const char* dsp_last_error(void);
+/* Identifies the sources this binary was built from (a hash over csrc/ and this header, set by the build
+ * script); the Python binding refuses to load a binary whose id differs from the sources next to it. */
+const char* dsp_build_id(void);
 
 #ifdef __cplusplus
 }

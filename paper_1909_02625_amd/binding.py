@@ -31,7 +31,7 @@ __all__ = [
     "dsp_add_forward", "dsp_add_backward", "dsp_gap_forward", "dsp_gap_backward", "dsp_linear_forward",
     "dsp_linear_backward", "dsp_softmax_ce", "dsp_block_get_activation", "dsp_block_get_pool_argmax",
     "dsp_profile_start", "dsp_profile_stop", "dsp_profile_get",
-    "dsp_strerror", "dsp_last_error", "EXPORTED_SYMBOLS",
+    "dsp_strerror", "dsp_last_error", "dsp_build_id", "EXPORTED_SYMBOLS",
 ]
 
 DSP_FP32, DSP_BF16 = 0, 1
@@ -77,6 +77,12 @@ def lib():
             _build.build(force=True)
         _LIB = C.CDLL(path)
         _declare(_LIB)
+        from . import build as _build
+        have, want = _LIB.dsp_build_id().decode(), _build.source_hash()
+        if have != want:
+            _LIB = None
+            raise RuntimeError("%s was built from other sources (id %s, csrc/ + include/dsp.h now hash to %s): rebuild it "
+                               "with `python -m paper_1909_02625_amd.build`" % (path, have, want))
     return _LIB
 
 
@@ -149,7 +155,7 @@ _SIGNATURES = {
     "dsp_profile_stop": [_pi32],
     "dsp_profile_get": [_i32, C.c_char_p, _sz, _pi64, C.POINTER(C.c_double), C.POINTER(C.c_double), _pi32],
 }
-EXPORTED_SYMBOLS = sorted(list(_SIGNATURES) + ["dsp_strerror", "dsp_last_error"])
+EXPORTED_SYMBOLS = sorted(list(_SIGNATURES) + ["dsp_strerror", "dsp_last_error", "dsp_build_id"])
 
 
 def _declare(L):
@@ -161,6 +167,8 @@ def _declare(L):
     L.dsp_strerror.restype = C.c_char_p
     L.dsp_last_error.argtypes = []
     L.dsp_last_error.restype = C.c_char_p
+    L.dsp_build_id.argtypes = []
+    L.dsp_build_id.restype = C.c_char_p
 
 
 def check(status, where):
@@ -585,3 +593,7 @@ def dsp_strerror(status):
 
 def dsp_last_error():
     return lib().dsp_last_error().decode()
+
+
+def dsp_build_id():
+    return lib().dsp_build_id().decode()

@@ -27,9 +27,20 @@ def is_stale():
     return any(os.path.getmtime(f) > t for f in _deps())
 
 
+def source_hash():
+    """Hash over everything the library is built from (csrc/*, include/dsp.h): the id the binary reports through
+    dsp_build_id(), so that a binary older than the sources next to it is recognised whatever the file times say."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(_deps()):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
 def _compile(src):
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC] + FLAGS + ['-DDSP_BUILD_ID="%s"' % source_hash(), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

@@ -951,6 +951,9 @@ int dsp_param_update_sum(dsp_block* b, float lr, float momentum, int32_t s, floa
     DSP_REQUIRE(s == 0 || s == 1, DSP_EINVAL, "dsp_param_update: s = %d (only s = 0 and s = 1 are built)", (int)s);
     DSP_REQUIRE(lr >= 0.f, DSP_EINVAL, "dsp_param_update: negative step size");
     DSP_REQUIRE(b->pending, DSP_ESTATE, "dsp_param_update: no pending gradient");
+    DSP_REQUIRE(!(lr == 0.f && momentum != 0.f && b->last_lr > 0.f), DSP_EINVAL,
+                "dsp_param_update: step size 0 after updates that carry momentum (Eq. (3) would still move x by "
+                "momentum * (x^n - x^{n-1}); the velocity form cannot)");
     b->pending = false;
     b->version += 1;
     // the stored velocity is in units of the step size of the update that wrote it
@@ -1217,5 +1220,10 @@ const char* dsp_strerror(int status)
 }
 
 const char* dsp_last_error(void) { return dsp::g_err; }
+
+#ifndef DSP_BUILD_ID
+#define DSP_BUILD_ID "unknown"
+#endif
+const char* dsp_build_id(void) { return DSP_BUILD_ID; }
 
 }  // extern "C"

@@ -750,6 +750,15 @@ def test_call_order_is_enforced():
         D.dsp_block_forward(b, 3, x, out)
         q = D.dsp_block_query(b)
         assert q["version"] == 1 and q["next_bwd"] == 1 and q["fwd_version_of_next_bwd"] == 0
+        # a step of size 0 while momentum is carried: Eq. (3) would still move x by beta (x^n - x^{n-1}), which the
+        # velocity form cannot express -> refused, nothing consumed; without momentum it is the identity and allowed
+        D.dsp_block_recompute_backward(b, 1, g)
+        before = D.dsp_block_get_params(b)
+        with pytest.raises(D.DSPError) as e:
+            D.dsp_param_update(b, 0.0, 0.9)
+        assert e.value.status == 1 and D.dsp_block_query(b)["pending"] == 1
+        D.dsp_param_update(b, 0.0, 0.0)
+        assert np.array_equal(D.dsp_block_get_params(b), before) and D.dsp_block_query(b)["version"] == 2
         torch.cuda.synchronize()
     finally:
         destroy_blocks(blocks)

@@ -31,6 +31,12 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(D, n), n
 
 
+def test_loaded_library_was_built_from_these_sources():
+    """The binary carries a hash of csrc/ and include/dsp.h; the binding refuses one built from other sources."""
+    from paper_1909_02625_amd import build
+    assert D.dsp_build_id() == build.source_hash() and len(D.dsp_build_id()) == 16
+
+
 def test_strerror_and_status_codes():
     assert D.dsp_strerror(0) == "ok"
     assert "order" in D.dsp_strerror(2)
