@@ -27,13 +27,24 @@ a queue of length 1+n releases its oldest item once it holds 1+n items, i.e. it 
 ticks; inside one tick a block runs forward(a), then recompute+backward(b) with the same
 parameters, then its update; ticks in which no gradient has arrived make no update; the
 last block may have m = 0 (the paper's own configurations do); all m = p = 0 is ordinary
-backpropagation; Q_k holds the gradients block k emits for block k-1; the mini-batch loss is
-the mean over the batch; weight decay, if any, is added to the gradient of weight tensors only.
+backpropagation; every p = 0 with stale backward passes is the forward-locked schedule of the
+features-replay comparison (Section 6); Q_k holds the gradients block k emits for block k-1; the
+mini-batch loss is the mean over the batch; weight decay, if any, is added to the gradient of weight
+tensors only; a grouped convolution (ResNeXt) is one ordinary convolution per group of channels.
 
-Parity pins (see tests): exact rational worked example, finite differences, adjoint
-identities, torch-autograd + SGD for the zero-staleness case, closed forms for BN /
-softmax / momentum.  The loss trajectory on the synthetic CNN workloads has no pin other
-than those (parity unpinned beyond them: the paper prints no numbers for synthetic data).
+Two modes beside plain fp64 serve the comparison with a kernel that stores tensors in a narrower
+type: ``storage="bf16"`` / ``"fp32"`` round every stored feature map, gradient map and filter where
+the C ABI says they are stored (arithmetic stays fp64), and ``CNNBlock.backward(decisions=...)``
+applies the chain rule with given rectifier masks / pooling choices instead of its own (a branch
+decision is an integer taken on a stored value; both sides must take it in the same precision).
+
+Parity pins (tests/test_oracle_pins.py): exact rational worked examples (the DSP recursion; the bf16
+storage mode with every rounding point written out), finite differences, adjoint identities,
+grouped = block-diagonal dense convolution, torch's conv2d / autograd / SGD (also Nesterov) for the
+zero-staleness case, closed forms for BN / softmax / momentum / the gradient difference, queue
+timelines incl. the forward-locked tuples.  No function of this module is without a pin.  The loss
+trajectory on the synthetic CNN workloads has no reference other than this oracle (parity unpinned
+beyond its pins: the paper prints no numbers for synthetic data).
 """
 from __future__ import annotations
 
