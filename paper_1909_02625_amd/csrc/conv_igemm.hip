@@ -842,6 +842,250 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::WA
     }
 }
 
+// ---- bf16 3x3 / stride 1 / pad 1 convolutions with 64 channels on both sides, filters held in registers ----
+// The contraction is 576 long and only 64 wide, so the whole filter bank (64 x 576 bf16 = 72 KB) fits the register
+// files of a workgroup's four waves: each wave keeps ALL of it as MFMA operand fragments (36 k steps x 2 blocks of 32
+// output channels x 4 registers = 288 registers per lane, one wave per SIMD) for the life of a persistent workgroup,
+// and LDS only carries the pixels.  Those are not staged as an im2col tile either: the input rows a tile of 256
+// consecutive output pixels needs (its image rows plus one above and below, one zero column left and right) go into LDS
+// ONCE, as they lie in memory, and the fragment of tap (r, s) is read at the shifted address -- the nine-fold
+// expansion happens in the LDS read.  Per k step a wave reads 2 fragments for 4 MFMAs (64 B/clk per compute unit,
+// against 128 for the register-staged 256x64 tile, which is what bound that tile).  The rows of the NEXT tile are
+// fetched into registers before the k loop and written to the other patch buffer during its last steps (15 16-byte
+// chunks per lane).  (Direct global -> LDS loads were built first and measured: a wave's LDS reads queue behind its
+// own outstanding direct loads, so the k loop stood still until the next tile had landed.)
+//   patch pixel pp = prow * 64 + pcol (rows of 64 pixels; 51 <= W <= 62, so a tile touches at most 8 flat rows) holds
+//   input pixel (flat row R0 + prow, column pcol - 1), flat row = n * H + h; its 128 bytes keep the 16-byte chunk c
+//   at position c ^ ((pcol >> 1) & 7), so that the 16 consecutive pixels a group of 16 lanes reads (same c) fall on
+//   16 different bank groups.  Lane tid moves position tid & 7 of the columns (tid >> 3) and (tid >> 3) + 32 of every
+//   row: its two column offsets are fixed, the row offset is uniform, so a fetch costs two vector instructions.
+// A tap row that belongs to another image (h + r - 1 outside [0, H)) is a per-lane matter (the same flat row is data
+// for one output row and padding for the next image's): such lanes read from a 512-byte zero region instead.
+// The MFMA computes the transposed tile (filters as the first operand), so a lane ends up with runs of 4 consecutive
+// output channels of one pixel; the tile is staged through the patch buffer just multiplied and stored as 16-byte
+// runs, with the column sums for a following batch norm taken from the staged values.
+struct C64Args {
+    int buf_bytes;       // bytes of one patch buffer (>= kC64Chunks * 4 KB and >= the staged output tile + column-sum scratch)
+    int tiles;           // row tiles of 256 output pixels per problem instance
+    int total_tiles;     // tiles x (1 or 2 instances)
+    int tiles_per_wg;    // consecutive tiles one workgroup walks (neighbouring tiles share input rows: same L2, soon after)
+};
+constexpr int kC64Zero = 512;    // zero region at the start of LDS
+constexpr int kC64EpiRowB = 64 * 2 + 16;
+constexpr int kC64Chunks = 16;   // 16-byte chunks of a patch per lane: 8 rows of 64 pixels
+constexpr int kC64Pitch = 64;    // pixels per patch row
+
+// Barrier for phases that only exchange data through LDS stores: waits for this wave's LDS operations, not for its
+// outstanding vector-memory operations (the next tile's loads and the previous tile's stores stay in flight).
+__device__ inline void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <bool ACCUM>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void conv3x3_c64_bf16_kernel(
+    const bf16_t* __restrict__ in_, const bf16_t* __restrict__ wgt, bf16_t* __restrict__ out_, GatherGeom g, C64Args a)
+{
+    typedef bf16_t T;
+    constexpr int BM = 256, C = 64, NKS = 36, NCH = kC64Chunks, WR0 = NKS - NCH;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int frow = lane & 31, fg = lane >> 5;
+    const int W = g.Wi, H = g.Hi;
+    constexpr int W2 = kC64Pitch;
+
+    // the filter bank as first-operand fragments: lane (frow, fg) holds, for output channel 32 j + frow, the
+    // k elements 16 t + 8 fg .. + 7
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(wgt, (uint32_t)(C * 9 * C) * 2u);
+    u32x4 wf[NKS][2];
+#pragma unroll
+    for (int t = 0; t < NKS; ++t)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) wf[t][j] = load16(rw, (uint32_t)(((32 * j + frow) * (9 * C)) + 16 * t + 8 * fg) * 2u);
+    // the filters are complete before the tile loop starts (otherwise the compiler keeps counting on their loads inside
+    // the loop, and its waits there would also drain the prefetch of the next tile)
+#pragma unroll
+    for (int t = 0; t < NKS; ++t)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) asm volatile("" ::"v"(wf[t][j]));
+
+    if (tid < kC64Zero / 16) *(u32x4*)(smem + tid * 16) = u32x4{0u, 0u, 0u, 0u};
+    const uint32_t in_bytes = (uint32_t)g.N * H * W * C * 2u;
+    const __amdgpu_buffer_rsrc_t rin0 = make_rsrc(in_, in_bytes);
+    const __amdgpu_buffer_rsrc_t rin1 = make_rsrc(g.in1 ? g.in1 : in_, in_bytes);
+
+    const int t_begin = blockIdx.x * a.tiles_per_wg;
+    const int t_end = min(a.total_tiles, t_begin + a.tiles_per_wg);
+
+    // the input rows of tile t, 16 chunks per lane: chunk i = position tid & 7 of patch pixel (row i >> 1, column
+    // (tid >> 3) + 32 (i & 1)); zeros for the border columns, for rows outside the tensor and past the rows the tile touches
+    uint32_t col_off[2];
+    bool col_ok[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int pcol = (tid >> 3) + 32 * h, wi = pcol - 1;
+        col_ok[h] = wi >= 0 && wi < W;
+        col_off[h] = (uint32_t)(wi * C + ((tid & 7) ^ ((pcol >> 1) & 7)) * 8) * 2u;
+    }
+    auto fetch_patch = [&](int t, u32x4 (&pre)[NCH]) {
+        const int inst = t >= a.tiles ? 1 : 0;
+        const int m0 = (t - inst * a.tiles) * BM;
+        const int tq = (int)fast_div((uint32_t)m0, g.wo_mul, g.wo_sh);  // flat output row of the tile's first pixel
+        const int m_last = min(m0 + BM, g.M) - 1;
+        const int R0 = tq - 1;
+        const int rows = (int)fast_div((uint32_t)m_last, g.wo_mul, g.wo_sh) - tq + 3;  // the rows this tile touches
+        const __amdgpu_buffer_rsrc_t rin = inst ? rin1 : rin0;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int prow = i >> 1, row = R0 + prow;
+            const bool row_ok = prow < rows && row >= 0 && row < g.N * H;   // uniform
+            const uint32_t row_off = (uint32_t)(row * W * C) * 2u;           // uniform
+            pre[i] = load16(rin, (row_ok && col_ok[i & 1]) ? row_off + col_off[i & 1] : kOutOfRange);
+        }
+    };
+
+    u32x4 pre[NCH];
+    if (t_begin < t_end) {
+        fetch_patch(t_begin, pre);
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) *(u32x4*)(smem + kC64Zero + (tid + kThreads * i) * 16) = pre[i];
+    }
+    int cur = 0;
+    for (int t = t_begin; t < t_end; ++t) {
+        const int inst = t >= a.tiles ? 1 : 0;
+        const int row_tile = t - inst * a.tiles;
+        const int m0 = row_tile * BM;
+        T* __restrict__ out = inst ? (T*)g.out1 : out_;
+        double* stats = inst ? g.stats1 : g.stats;
+        const int R0 = (int)fast_div((uint32_t)m0, g.wo_mul, g.wo_sh) - 1;
+        char* patch = smem + kC64Zero + cur * a.buf_bytes;
+        char* next_patch = smem + kC64Zero + (cur ^ 1) * a.buf_bytes;
+        const bool has_next = t + 1 < t_end;
+
+        // this tile's rows are in LDS (written by all waves during the previous tile, or just above), and every wave is
+        // past the previous tile's epilogue, whose staging area this tile's prefetch will overwrite
+        lds_barrier();
+        if (has_next) fetch_patch(t + 1, pre);
+
+        // per lane and 32-pixel block: LDS address of tap row r (or the zero region), swizzle keys of the three tap columns
+        uint32_t base_r[2][3], keyf[2][3];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int m = m0 + wave * 64 + i * 32 + frow;
+            const int tq = (int)fast_div((uint32_t)m, g.wo_mul, g.wo_sh), wo = m - tq * W;
+            const int n = (int)fast_div((uint32_t)tq, g.ho_mul, g.ho_sh), ho = tq - n * H;
+            const uint32_t pix0 = (uint32_t)(((tq - R0 - 1) * W2 + wo) * 128);  // tap (0, 0): flat row tq - 1, patch column wo
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                const bool ok = m < g.M && ho + r - 1 >= 0 && ho + r - 1 < H;
+                base_r[i][r] = ok ? (uint32_t)(kC64Zero + cur * a.buf_bytes) + pix0 + (uint32_t)(r * W2 * 128) : 0u;
+            }
+#pragma unroll
+            for (int s2 = 0; s2 < 3; ++s2) keyf[i][s2] = (uint32_t)(((((wo + s2) >> 1) & 7) ^ fg) << 4);
+        }
+        auto read_frag = [&](int ks, u32x4 (&f)[2]) {
+            const int tap = ks >> 2, r = tap / 3, s2 = tap - 3 * r;
+            const uint32_t cx = (uint32_t)((2 * (ks & 3)) << 4);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) f[i] = *(const u32x4*)(smem + (base_r[i][r] + (keyf[i][s2] ^ cx)) + s2 * 128);
+        };
+
+        typename Mma<T, 32>::Acc acc[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+        u32x4 fa[2][2];
+        read_frag(0, fa[0]);
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            if (ks + 1 < NKS) read_frag(ks + 1, fa[(ks + 1) & 1]);
+            // the next tile's rows move from registers to the other patch buffer during the last steps
+            if (ks >= WR0 && has_next) *(u32x4*)(next_patch + (tid + kThreads * (ks - WR0)) * 16) = pre[ks - WR0];
+            __builtin_amdgcn_sched_barrier(0);  // the next step's fragment reads go out before this step's MFMAs
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) Mma<T, 32>::run(wf[ks][j], fa[ks & 1][i], acc[i][j]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        lds_barrier();  // every wave has finished reading the patch: it becomes the staging area of the output tile
+
+        typedef typename Run4<T>::V RunV;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int lr = wave * 64 + i * 32 + frow;
+                const int m = m0 + lr;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = j * 32 + acc_row<32>(lane, 4 * q);
+                    if (ACCUM && m < g.M) {
+                        float o[4];
+                        Run4<T>::unpack(*(const RunV*)(out + (int64_t)m * C + col), o);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += o[e];
+                    }
+                    *(RunV*)(patch + lr * kC64EpiRowB + col * 2) =
+                        Run4<T>::pack(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                }
+            }
+        lds_barrier();
+        {
+            // thread = (row tid >> 3 of each group of 32 rows, 16-byte run tid & 7): all eight reads first, then the stores
+            const int cc = (tid & 7) * 8, lr0 = tid >> 3;
+            u32x4 v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = *(const u32x4*)(patch + (lr0 + 32 * k) * kC64EpiRowB + cc * 2);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int m = m0 + lr0 + 32 * k;
+                if (m < g.M) *(u32x4*)(out + (int64_t)m * C + cc) = v[k];
+            }
+            if (stats) {
+                // column sums of the staged tile (rows past M hold zeros) from the same registers: this thread's 8 rows
+                // of its 8 channels, then the 32 row groups per channel in a fixed order
+                float s0[8], s1[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s0[e] = s1[e] = 0.f;
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float lo = __uint_as_float(v[k][e] << 16), hi = __uint_as_float(v[k][e] & 0xffff0000u);
+                        s0[2 * e] += lo;
+                        s1[2 * e] += lo * lo;
+                        s0[2 * e + 1] += hi;
+                        s1[2 * e + 1] += hi * hi;
+                    }
+                float* sred = (float*)(patch + BM * kC64EpiRowB);  // [32 row groups][64 channels][2]
+#pragma unroll
+                for (int e = 0; e < 8; e += 2)
+                    *(f32x4*)(sred + (lr0 * 64 + cc + e) * 2) = f32x4{s0[e], s1[e], s0[e + 1], s1[e + 1]};
+                lds_barrier();
+                if (tid < 64) {
+                    double sa = 0.0, sb = 0.0;
+#pragma unroll 8
+                    for (int k = 0; k < 32; ++k) {
+                        sa += (double)sred[(k * 64 + tid) * 2];
+                        sb += (double)sred[(k * 64 + tid) * 2 + 1];
+                    }
+                    double* dst = stats + ((int64_t)row_tile * C + tid) * 2;
+                    dst[0] = sa;
+                    dst[1] = sb;
+                }
+            }
+        }
+        cur ^= 1;
+    }
+}
+
 // ---- fp32 3x3 convolutions with 16 or 32 channels on both sides ----------------------------------
 // With so few channels the whole filter bank of 16 output channels fits in registers (9 * Ci / 16
 // 16-byte runs per lane), so no operand needs LDS: the MFMA computes y^T, D[co][pixel] with
@@ -1746,9 +1990,26 @@ bool dma_eligible(const GatherGeom& g)
            (tile_count(g, 256, 128) >= 192 || dma_wide<T>(g));
 }
 
+// The register-resident-filter kernel: bf16, 3x3 / stride 1 / pad 1, 64 channels on both sides, no groups, rows wide
+// enough to fill the chip, and image rows of 51 .. 62 pixels (the input rows of a 256-pixel tile are kept as 8 x 64 pixels).
+inline int c64_buf_bytes()
+{
+    const int patch = kC64Chunks * kThreads * 16;
+    const int epi = 256 * kC64EpiRowB + 32 * 64 * 2 * (int)sizeof(float);
+    return (patch > epi ? patch : epi + 1023) / 1024 * 1024;
+}
+template <typename T>
+bool c64_eligible(const GatherGeom& g)
+{
+    return sizeof(T) == 2 && g.groups == 1 && g.Ci == 64 && g.Co == 64 && g.R == 3 && g.S == 3 && g.ostride == 1 && g.idil == 1 &&
+           g.pad_h == 1 && g.pad_w == 1 && g.Hi == g.Ho && g.Wi == g.Wo && g.oh_mul == 0 && g.M >= 256 * 256 &&
+           g.Wi + 2 <= kC64Pitch && 4 + 254 / g.Wi <= kC64Chunks / 2;  // rows of the patch: 64 pixels wide, at most 8
+}
+
 template <typename T>
 int select_gather_tile(const GatherGeom& g, int* bm)
 {
+    if (c64_eligible<T>(g)) { *bm = 256; return 21; }
     if (dma_eligible<T>(g)) { *bm = 256; return 20; }
     if (g.Co <= 16) {
         // (bf16 always takes the 64-row tile: measured in the four-stream resnet56 pipeline)
@@ -1795,6 +2056,31 @@ int run_dma(const GatherGeom& g, const void* in, const void* w, void* out, hipSt
     return DSP_OK;
 }
 
+int run_c64(const GatherGeom& g, const void* in, const void* w, void* out, hipStream_t st, double flops)
+{
+    C64Args a{};
+    a.buf_bytes = c64_buf_bytes();
+    a.tiles = ceil_div(g.M, 256);
+    a.total_tiles = a.tiles * (g.in1 ? 2 : 1);
+    const int wgs = a.total_tiles < 256 ? a.total_tiles : 256;  // one persistent workgroup per compute unit
+    a.tiles_per_wg = ceil_div(a.total_tiles, wgs);
+    const int grid = ceil_div(a.total_tiles, a.tiles_per_wg);
+    const int lds = kC64Zero + 2 * a.buf_bytes;
+    auto kern = g.accum ? conv3x3_c64_bf16_kernel<true> : conv3x3_c64_bf16_kernel<false>;
+    static std::atomic<bool> attr_done{false};
+    if (!attr_done) {
+        DSP_HIP(hipFuncSetAttribute((const void*)conv3x3_c64_bf16_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        DSP_HIP(hipFuncSetAttribute((const void*)conv3x3_c64_bf16_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        attr_done = true;
+    }
+    {
+        ProfScope ps("conv3x3_c64<bf16,filters in registers>", flops, 0);
+        DSP_LAUNCH(ps, kern, dim3((unsigned)grid), dim3(kThreads), lds, st, (const bf16_t*)in, (const bf16_t*)w, (bf16_t*)out, g, a);
+    }
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
 template <typename T>
 int dispatch_gather(GatherGeom g, bool accum, const void* in, const void* w, void* out, hipStream_t st, double flops)
 {
@@ -1821,6 +2107,12 @@ int dispatch_gather(GatherGeom g, bool accum, const void* in, const void* w, voi
     g.out_vec = ((g.Co % E) == 0 && ((uintptr_t)out % 16) == 0) ? 1 : 0;
     int bm;
     int id = select_gather_tile<T>(g, &bm);
+    if (id == 21) {
+        const bool aligned = vec && g.out_vec && ((uintptr_t)g.in1 % 16) == 0 && ((uintptr_t)g.out1 % 16) == 0;
+        if (aligned) return run_c64(g, in, w, out, st, flops);
+        // unaligned tensors (single-layer calls only) take the register-staged tiles; their row tiles are the same 256
+        id = 10;
+    }
     if (id == 20) {
         const bool aligned = vec && ((uintptr_t)g.in1 % 16) == 0 && ((uintptr_t)g.out1 % 16) == 0;
         if (aligned && g.out_vec) {

@@ -31,6 +31,12 @@ SHAPES = [
     (2, 12, 12, 32, 64, 1, 1, 2, 0),    # 1x1 stride 2: three of the four classes receive no gradient at all
     (2, 9, 9, 8, 16, 2, 2, 2, 0),       # 2x2 stride 2 without padding: one tap per class
     (2, 14, 14, 8, 8, 5, 5, 2, 2),      # 5x5 stride 2: classes of 3x3, 3x2, 2x3 and 2x2 taps
+    # 64 -> 64 channels, 3x3: in bf16 the filters-in-registers kernel (persistent workgroups walking 256-pixel tiles,
+    # input rows staged once in LDS); every element compared, M = 65856 with a ragged last tile of 64 pixels
+    (21, 56, 56, 64, 64, 3, 3, 1, 1),
+    (30, 52, 51, 64, 64, 3, 3, 1, 1),   # the shortest rows that kernel takes (a tile touches 8 input rows), H != W, odd W, M = 79560
+    (20, 60, 62, 64, 64, 3, 3, 1, 1),   # the longest (patch rows of 64 pixels are full)
+    (65, 32, 32, 64, 64, 3, 3, 1, 1),   # rows too short for it: the register-staged 256x64 tile at a large M
 ]
 
 
@@ -168,6 +174,7 @@ FULL = [
     (D.DSP_BF16, 256, 14, 14, 256, 256, 3, 3, 1, 1),   # ResNet-18 stage 3 (direct-to-LDS 256x256 tiles)
     (D.DSP_BF16, 250, 14, 14, 256, 256, 3, 3, 1, 1),   # the same with a ragged last row tile (M = 49000)
     (D.DSP_BF16, 125, 14, 14, 256, 384, 3, 3, 1, 1),   # direct-to-LDS 256x128 tiles, three column tiles, ragged rows
+    (D.DSP_BF16, 256, 56, 56, 64, 64, 3, 3, 1, 1),     # ResNet-18 stage 1 (filters in registers, 3136 tiles on 256 workgroups)
     (D.DSP_BF16, 128, 32, 32, 512, 512, 3, 3, 1, 1, 8),   # ResNeXt-29 (8 x 64d) stage 1: 8 groups of 64 -> 64
     (D.DSP_BF16, 128, 32, 32, 1024, 1024, 3, 3, 2, 1, 8), # stage 2 entry: 128 -> 128 per group, stride 2
     (D.DSP_FP32, 64, 8, 8, 2048, 2048, 3, 3, 1, 1, 8),    # stage 3: 256 -> 256 per group

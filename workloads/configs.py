@@ -249,6 +249,17 @@ def _bn_probe():
     return [b.layers]
 
 
+def _c64_probe():
+    """One ResNet-18 stage-1 basic block (two 3x3 convolutions of 64 channels, identity shortcut): a block whose
+    convolutions are large enough for the persistent filters-in-registers kernel, small enough for the oracle."""
+    b = _B()
+    a = b.conv(-1, 64, 64, 3)
+    a = b.bn(a, 64, relu=True)
+    a = b.conv(a, 64, 64, 3)
+    b.bn(a, 64, relu=True, res=-1)
+    return [b.layers]
+
+
 # ----------------------------------------------------------------------------- configs
 CONFIGS = {
     # name: blocks, input (N, C, H, W), classes, DSP(p; m), lr, momentum, weight decay, steps, seed, dtype
@@ -283,6 +294,10 @@ CONFIGS = {
     # not one of the paper-shaped workloads: a parity probe for the streaming kernels at large M (tests only)
     "bn_probe": dict(blocks=_bn_probe, input=(128, 64, 56, 56), classes=None, p=(0,), m=(1,), lr=0.01, beta=0.9,
                      wd=0.0, steps=3, seed=5, dtypes=("fp32", "bf16"), grad_std=0.1, data_input=False),
+    # the same for the convolution kernel that only large 64-channel 3x3 layers take (M = 65856 rows: 258 tiles, the last
+    # one ragged; forward + recompute in one launch, fused batch-norm sums, accumulating backward-data)
+    "c64_probe": dict(blocks=_c64_probe, input=(21, 64, 56, 56), classes=None, p=(0,), m=(1,), lr=0.01, beta=0.9,
+                      wd=0.0, steps=3, seed=6, dtypes=("bf16",), grad_std=0.1, data_input=False),
     "resnet18": dict(blocks=_resnet18, input=(256, 3, 224, 224), classes=1000, p=(1, 1, 1, 0), m=(6, 4, 2, 0),
                      lr=0.01, beta=0.9, wd=0.0, steps=20, seed=4, dtypes=("bf16",)),
 }
