@@ -99,7 +99,14 @@ struct Layer {
     // input is copied into a channel-padded buffer and the layer runs as a conv over cin_pad channels
     // (cs describes that padded problem).  Its forward filters live, padded with zeros, in the block's
     // filter-copy area (this layer needs no backward-data copy), kept up to date by the update kernel.
+    // A 7x7 / stride 2 / pad 3 stem on even-sized images runs in space-to-depth form instead (s2d): the 2x2 cells of
+    // the input become 4 * cin channels (padded to cin_pad) of a half-size image, on which the layer is a 4x4 / stride
+    // 1 convolution with padding 2 above / left and 1 below / right -- tap r of the 7x7 filter is tap (r - 3) >> 1
+    // (+ 2) and cell row (r - 3) & 1 -- i.e. 4 * 4 * cin_pad = 256 multiplications per output instead of
+    // 7 * 7 * 8 = 392 of the channel-padded form, and half the bytes of padded input.
     int cin_pad = 0;
+    bool s2d = false;
+    int in_h = 0, in_w = 0;   // s2d: size of the layer's real input
     void* xpad = nullptr;     // padded input of the pass the backward sweep belongs to
     float* dw_pad = nullptr;  // filter gradient in the padded layout
     size_t wg_off = 0, wg_bytes = 0;  // conv: this layer's region of the partial-gradient workspace
@@ -228,17 +235,29 @@ static int build_graph(dsp_block* b)
             const int G = L.d.groups > 1 ? L.d.groups : 1;
             int cin = L.d.cin;
             if (L.d.in0 < 0 && !d.needs_input_grad && cin % run != 0 && G == 1) {
-                L.cin_pad = (cin + run - 1) / run * run;
+                L.s2d = L.d.r == 7 && L.d.s == 7 && L.d.stride == 2 && L.d.pad == 3 && s.H % 2 == 0 && s.W % 2 == 0 &&
+                        s.H >= 8 && s.W >= 8 && 4 * cin <= 16;
+                L.cin_pad = ((L.s2d ? 4 * cin : cin) + run - 1) / run * run;
                 cin = L.cin_pad;
             }
-            L.cs = make_conv_shape(s.N, s.H, s.W, cin, L.d.cout, L.d.r, L.d.s, L.d.stride, L.d.pad, G);
-            if (L.cin_pad) L.cs.cin_real = L.d.cin;
+            if (L.s2d) {
+                const ConvShape real = make_conv_shape(s.N, s.H, s.W, L.d.cin, L.d.cout, 7, 7, 2, 3);
+                L.in_h = s.H;
+                L.in_w = s.W;
+                L.cs = make_conv_shape(s.N, s.H / 2, s.W / 2, cin, L.d.cout, 4, 4, 1, 2);
+                L.cs.Ho = real.Ho;   // = H / 2: one row / column of padding less below / right than above / left
+                L.cs.Wo = real.Wo;
+                L.cs.macs = conv_useful_macs(real);
+            } else {
+                L.cs = make_conv_shape(s.N, s.H, s.W, cin, L.d.cout, L.d.r, L.d.s, L.d.stride, L.d.pad, G);
+                if (L.cin_pad) L.cs.cin_real = L.d.cin;
+            }
             DSP_REQUIRE(L.cs.Ho > 0 && L.cs.Wo > 0, DSP_EINVAL, "layer %d: empty conv output", i);
             t.C = L.d.cout; t.H = L.cs.Ho; t.W = L.cs.Wo;
             L.p0 = poff;
             poff += (size_t)L.d.cout * (L.d.cin / G) * L.d.r * L.d.s;
             L.wt_off = wtoff;
-            wtoff += (size_t)L.d.cout * (cin / G) * L.d.r * L.d.s;
+            wtoff += (size_t)L.d.cout * (cin / G) * L.cs.R * L.cs.S;
             break;
         }
         case DSP_OP_BN:
@@ -377,7 +396,11 @@ static int build_graph(dsp_block* b)
                         for (int ci = 0; ci < Ci; ++ci) {
                             const size_t lib = L.p0 + (((size_t)co * R + r) * S + s) * Ci + ci;
                             b->perm[lib] = (int32_t)(L.p0 + (((size_t)co * Ci + ci) * R + r) * S + s);
-                            if (L.cin_pad)
+                            if (L.s2d) {
+                                const int ur = r - 3, us = s - 3;  // offsets from the centre tap; >> and & floor towards -inf
+                                const int ta = (ur >> 1) + 2, tb = (us >> 1) + 2, cell = (ur & 1) * 2 + (us & 1);
+                                tmap[lib] = (int32_t)(L.wt_off + (((size_t)co * 4 + ta) * 4 + tb) * L.cin_pad + cell * Ci + ci);
+                            } else if (L.cin_pad)
                                 tmap[lib] = (int32_t)(L.wt_off + (((size_t)co * R + r) * S + s) * L.cin_pad + ci);
                         }
             if (L.cin_pad) {
@@ -572,8 +595,12 @@ static int run_forward(dsp_block* b, const ForwardPass& P, const ForwardPass* tw
             if (L.cin_pad)
                 for (int q = 0; q < passes; ++q) {
                     const ForwardPass& p = q ? *twin : P;
-                    DSP_TRY(launch_pad_channels(b->dtype, p.in, const_cast<void*>(conv_src(p)),
-                                                (int64_t)L.cs.N * L.cs.H * L.cs.W, L.d.cin, L.cin_pad, st));
+                    if (L.s2d)
+                        DSP_TRY(launch_space_to_depth2(b->dtype, p.in, const_cast<void*>(conv_src(p)), L.cs.N, L.in_h, L.in_w,
+                                                       L.d.cin, L.cin_pad, st));
+                    else
+                        DSP_TRY(launch_pad_channels(b->dtype, p.in, const_cast<void*>(conv_src(p)),
+                                                    (int64_t)L.cs.N * L.cs.H * L.cs.W, L.d.cin, L.cin_pad, st));
                 }
             ConvForwardTwin tw{};
             if (twin) tw = ConvForwardTwin{conv_src(*twin), act_of(*twin, i), L.sum_tiles > 0 ? bn_buffers(*twin).partial : nullptr};
@@ -710,7 +737,8 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
     DSP_TRY(wgrad_reduce_set_launch(b->wgrad_set, st));
     for (Layer& L : b->layers)
         if (L.d.op == DSP_OP_CONV && L.cin_pad)
-            DSP_TRY(launch_unpad_rows(L.dw_pad, b->g + L.p0, (int64_t)L.cs.Cout * L.cs.R * L.cs.S, L.d.cin, L.cin_pad, st));
+            DSP_TRY(launch_gather_f32(L.dw_pad, b->tmap + L.p0, (int32_t)L.wt_off, b->g + L.p0,
+                                      (int64_t)L.d.cout * L.d.r * L.d.s * L.d.cin, st));
     return DSP_OK;
 }
 

@@ -136,15 +136,19 @@ struct ConvShape {
     int N, H, W, Cin, Cout, R, S, stride, pad, Ho, Wo;
     int cin_real;  // > 0: only the first cin_real of the Cin input channels carry data (the rest is zero padding);
                    // used for counting the useful multiply-accumulates only
+    double macs;   // > 0: the useful multiply-accumulates of the layer this problem stands for (a layer run in another
+                   // form, e.g. the space-to-depth stem); used for reporting only
     int groups;    // > 1: grouped convolution -- group g maps input channels [g Cin/groups, (g+1) Cin/groups) to output
                    // channels [g Cout/groups, (g+1) Cout/groups); filters [Cout][R][S][Cin/groups].  0 and 1: ungrouped.
 };
 
 inline int conv_groups(const ConvShape& c) { return c.groups > 1 ? c.groups : 1; }
+// Multiply-accumulates of the convolution as defined (taps on padding and padded channels not counted).
+double conv_useful_macs(const ConvShape& c);
 
 inline ConvShape make_conv_shape(int N, int H, int W, int Cin, int Cout, int R, int S, int stride, int pad, int groups = 1)
 {
-    ConvShape c{N, H, W, Cin, Cout, R, S, stride, pad, 0, 0, 0, groups};
+    ConvShape c{N, H, W, Cin, Cout, R, S, stride, pad, 0, 0, 0, 0.0, groups};
     c.Ho = (H + 2 * pad - R) / stride + 1;
     c.Wo = (W + 2 * pad - S) / stride + 1;
     return c;
@@ -284,8 +288,11 @@ int launch_spin(int microseconds, hipStream_t st);
 int launch_add_forward(int dtype, const void* a, const void* b, void* y, int64_t n, hipStream_t st);
 int launch_grad_pass(int dtype, const void* dy, void* dx0, bool acc0, void* dx1, bool acc1, int64_t n, hipStream_t st);
 int launch_pad_channels(int dtype, const void* src, void* dst, int64_t pixels, int C, int Cp, hipStream_t st);
-// dst[row][0..C) = src[row][0..C) for rows of Cp floats: drops the padded channels of a filter gradient.
-int launch_unpad_rows(const float* src, float* dst, int64_t rows, int C, int Cp, hipStream_t st);
+// dst[i] = src[idx[i] - base]: a filter gradient formed in a padded / transformed layout back into the layer's own.
+int launch_gather_f32(const float* src, const int32_t* idx, int32_t base, float* dst, int64_t n, hipStream_t st);
+// Space-to-depth by 2 with channel padding: dst[n][h][w][(dh * 2 + dw) * C + c] = src[n][2h + dh][2w + dw][c], channels
+// 4C .. Cp-1 zero; H and W even, Cp * sizeof(T) a multiple of 16.
+int launch_space_to_depth2(int dtype, const void* src, void* dst, int N, int H, int W, int C, int Cp, hipStream_t st);
 // history[counter[0]] = *loss; counter[0] += 1   (one thread; keeps the loss history index on the device)
 int launch_record_loss(const float* loss, float* history, int32_t* counter, int64_t capacity, hipStream_t st);
 

@@ -2342,6 +2342,7 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
 // forward, backward-data and backward-weight each perform exactly this many.
 double conv_macs(const ConvShape& c)
 {
+    if (c.macs > 0) return c.macs;
     int64_t vh = 0, vw = 0;
     for (int o = 0; o < c.Ho; ++o)
         for (int r = 0; r < c.R; ++r) {
@@ -2371,6 +2372,8 @@ int check_shape(const ConvShape& c)
 }
 
 }  // namespace
+
+double conv_useful_macs(const ConvShape& c) { return conv_macs(c); }
 
 // Geometry of a gather-GEMM: tensor `in` (N x Hi x Wi x Ci) gathered into output rows over N x Ho x Wo.
 static GatherGeom make_geom(int N, int Hi, int Wi, int Ci, int Ho, int Wo, int Co, int R, int S, int pad_h, int pad_w,

@@ -730,12 +730,37 @@ __global__ __launch_bounds__(kThreads) void pad_channels_run_kernel(const T* __r
     }
 }
 
-__global__ __launch_bounds__(kThreads) void unpad_rows_kernel(const float* __restrict__ src, float* __restrict__ dst,
-                                                              int64_t rows, int C, int Cp)
+__global__ __launch_bounds__(kThreads) void gather_f32_kernel(const float* __restrict__ src, const int32_t* __restrict__ idx,
+                                                              int32_t base, float* __restrict__ dst, int64_t n)
 {
-    const int64_t total = rows * C;
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads)
-        dst[i] = src[(i / C) * Cp + i % C];
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kThreads)
+        dst[i] = src[idx[i] - base];
+}
+
+// One thread per output pixel: its CP channels are the four source pixels of a 2x2 cell side by side (then zeros),
+// written as whole 16-byte runs.
+template <typename T, int CP>
+__global__ __launch_bounds__(kThreads) void space_to_depth2_kernel(const T* __restrict__ src, T* __restrict__ dst, int N, int H,
+                                                                   int W, int C)
+{
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+    const int H2 = H / 2, W2 = W / 2;
+    const int64_t pixels = (int64_t)N * H2 * W2;
+    for (int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x; p < pixels; p += (int64_t)gridDim.x * kThreads) {
+        const int w2 = (int)(p % W2);
+        const int64_t t = p / W2;
+        const int h2 = (int)(t % H2);
+        const int64_t n = t / H2;
+        alignas(16) T v[CP];
+#pragma unroll
+        for (int c = 0; c < CP; ++c) v[c] = from_float<T>(0.f);
+        for (int q = 0; q < 4; ++q) {
+            const T* s = src + ((n * H + 2 * h2 + (q >> 1)) * W + 2 * w2 + (q & 1)) * C;
+            for (int c = 0; c < C; ++c) v[q * C + c] = s[c];
+        }
+#pragma unroll
+        for (int k = 0; k < CP * (int)sizeof(T) / 16; ++k) ((u32x4*)(dst + p * CP))[k] = ((const u32x4*)v)[k];
+    }
 }
 
 template <typename T>
@@ -807,11 +832,30 @@ int launch_pad_channels(int dtype, const void* src, void* dst, int64_t pixels, i
     return DSP_OK;
 }
 
-int launch_unpad_rows(const float* src, float* dst, int64_t rows, int C, int Cp, hipStream_t st)
+int launch_gather_f32(const float* src, const int32_t* idx, int32_t base, float* dst, int64_t n, hipStream_t st)
 {
-    DSP_REQUIRE(src && dst && rows > 0 && C > 0 && Cp >= C, DSP_EINVAL, "unpad_rows: bad argument");
-    ProfScope ps("unpad_rows", (double)rows * C * 8.0, 1);
-    DSP_LAUNCH(ps, unpad_rows_kernel, dim3(grid_for(rows * C)), dim3(kThreads), 0, st, src, dst, rows, C, Cp);
+    DSP_REQUIRE(src && idx && dst && n > 0, DSP_EINVAL, "gather: bad argument");
+    ProfScope ps("gather_f32", (double)n * 12.0, 1);
+    DSP_LAUNCH(ps, gather_f32_kernel, dim3(grid_for(n)), dim3(kThreads), 0, st, src, idx, base, dst, n);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+int launch_space_to_depth2(int dtype, const void* src, void* dst, int N, int H, int W, int C, int Cp, hipStream_t st)
+{
+    DSP_REQUIRE(src && dst && N > 0 && H > 0 && W > 0 && H % 2 == 0 && W % 2 == 0 && C > 0 && 4 * C <= Cp &&
+                    ((uintptr_t)dst % 16) == 0,
+                DSP_EINVAL, "space_to_depth: bad argument");
+    const int64_t pixels = (int64_t)N * (H / 2) * (W / 2);
+    ProfScope ps("space_to_depth", (double)pixels * (4 * C + Cp) * dtype_size(dtype), 1);
+    if (dtype == DSP_BF16 && Cp == 16)
+        DSP_LAUNCH(ps, (space_to_depth2_kernel<bf16_t, 16>), dim3(grid_for(pixels)), dim3(kThreads), 0, st, (const bf16_t*)src,
+                   (bf16_t*)dst, N, H, W, C);
+    else if (dtype == DSP_FP32 && Cp == 12)
+        DSP_LAUNCH(ps, (space_to_depth2_kernel<float, 12>), dim3(grid_for(pixels)), dim3(kThreads), 0, st, (const float*)src,
+                   (float*)dst, N, H, W, C);
+    else
+        DSP_REQUIRE(false, DSP_EINVAL, "space_to_depth: %d padded channels unsupported", Cp);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }
