@@ -236,7 +236,7 @@ static int build_graph(dsp_block* b)
             int cin = L.d.cin;
             if (L.d.in0 < 0 && !d.needs_input_grad && cin % run != 0 && G == 1) {
                 L.s2d = L.d.r == 7 && L.d.s == 7 && L.d.stride == 2 && L.d.pad == 3 && s.H % 2 == 0 && s.W % 2 == 0 &&
-                        s.H >= 8 && s.W >= 8 && 4 * cin <= 16;
+                        s.H >= 8 && s.W >= 8 && cin == 3;
                 L.cin_pad = ((L.s2d ? 4 * cin : cin) + run - 1) / run * run;
                 cin = L.cin_pad;
             }

@@ -737,29 +737,37 @@ __global__ __launch_bounds__(kThreads) void gather_f32_kernel(const float* __res
         dst[i] = src[idx[i] - base];
 }
 
-// One thread per output pixel: its CP channels are the four source pixels of a 2x2 cell side by side (then zeros),
-// written as whole 16-byte runs.
-template <typename T, int CP>
+// One thread per output pixel.  Its channels are the two source pixels of the cell's upper row side by side, then
+// those of the lower row: each is one contiguous run of 2 * C elements in the source (a whole number of 32-bit
+// words, 4-byte aligned since W is even), copied word by word; zeros behind; written as whole 16-byte runs.
+template <typename T, int CP, int C>
 __global__ __launch_bounds__(kThreads) void space_to_depth2_kernel(const T* __restrict__ src, T* __restrict__ dst, int N, int H,
-                                                                   int W, int C)
+                                                                   int W)
 {
     typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+    constexpr int WORDS = CP * (int)sizeof(T) / 4;
+    constexpr int seg = 2 * C * (int)sizeof(T) / 4;  // words per row of the cell
+    static_assert(2 * seg <= WORDS && WORDS % 4 == 0, "the two runs fit the padded pixel, which is whole 16-byte runs");
     const int H2 = H / 2, W2 = W / 2;
     const int64_t pixels = (int64_t)N * H2 * W2;
+    const uint32_t* __restrict__ srcw = (const uint32_t*)src;
     for (int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x; p < pixels; p += (int64_t)gridDim.x * kThreads) {
         const int w2 = (int)(p % W2);
         const int64_t t = p / W2;
         const int h2 = (int)(t % H2);
         const int64_t n = t / H2;
-        alignas(16) T v[CP];
+        alignas(16) uint32_t v[WORDS];
 #pragma unroll
-        for (int c = 0; c < CP; ++c) v[c] = from_float<T>(0.f);
-        for (int q = 0; q < 4; ++q) {
-            const T* s = src + ((n * H + 2 * h2 + (q >> 1)) * W + 2 * w2 + (q & 1)) * C;
-            for (int c = 0; c < C; ++c) v[q * C + c] = s[c];
+        for (int k = 0; k < WORDS; ++k) v[k] = 0u;
+        const int64_t row0 = ((n * H + 2 * h2) * W + 2 * w2) * (int64_t)seg / 2;  // word offset of the upper run
+        const int64_t row1 = row0 + (int64_t)W * seg / 2;
+#pragma unroll
+        for (int k = 0; k < seg; ++k) {
+            v[k] = srcw[row0 + k];
+            v[seg + k] = srcw[row1 + k];
         }
 #pragma unroll
-        for (int k = 0; k < CP * (int)sizeof(T) / 16; ++k) ((u32x4*)(dst + p * CP))[k] = ((const u32x4*)v)[k];
+        for (int k = 0; k < WORDS / 4; ++k) ((u32x4*)(dst + p * CP))[k] = ((const u32x4*)v)[k];
     }
 }
 
@@ -844,18 +852,18 @@ int launch_gather_f32(const float* src, const int32_t* idx, int32_t base, float*
 int launch_space_to_depth2(int dtype, const void* src, void* dst, int N, int H, int W, int C, int Cp, hipStream_t st)
 {
     DSP_REQUIRE(src && dst && N > 0 && H > 0 && W > 0 && H % 2 == 0 && W % 2 == 0 && C > 0 && 4 * C <= Cp &&
-                    ((uintptr_t)dst % 16) == 0,
+                    ((uintptr_t)dst % 16) == 0 && ((uintptr_t)src % 4) == 0,
                 DSP_EINVAL, "space_to_depth: bad argument");
     const int64_t pixels = (int64_t)N * (H / 2) * (W / 2);
     ProfScope ps("space_to_depth", (double)pixels * (4 * C + Cp) * dtype_size(dtype), 1);
-    if (dtype == DSP_BF16 && Cp == 16)
-        DSP_LAUNCH(ps, (space_to_depth2_kernel<bf16_t, 16>), dim3(grid_for(pixels)), dim3(kThreads), 0, st, (const bf16_t*)src,
-                   (bf16_t*)dst, N, H, W, C);
-    else if (dtype == DSP_FP32 && Cp == 12)
-        DSP_LAUNCH(ps, (space_to_depth2_kernel<float, 12>), dim3(grid_for(pixels)), dim3(kThreads), 0, st, (const float*)src,
-                   (float*)dst, N, H, W, C);
+    if (dtype == DSP_BF16 && Cp == 16 && C == 3)
+        DSP_LAUNCH(ps, (space_to_depth2_kernel<bf16_t, 16, 3>), dim3(grid_for(pixels)), dim3(kThreads), 0, st, (const bf16_t*)src,
+                   (bf16_t*)dst, N, H, W);
+    else if (dtype == DSP_FP32 && Cp == 12 && C == 3)
+        DSP_LAUNCH(ps, (space_to_depth2_kernel<float, 12, 3>), dim3(grid_for(pixels)), dim3(kThreads), 0, st, (const float*)src,
+                   (float*)dst, N, H, W);
     else
-        DSP_REQUIRE(false, DSP_EINVAL, "space_to_depth: %d padded channels unsupported", Cp);
+        DSP_REQUIRE(false, DSP_EINVAL, "space_to_depth: %d channels padded to %d unsupported", C, Cp);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }
