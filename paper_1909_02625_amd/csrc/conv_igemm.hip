@@ -1661,6 +1661,162 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_tr_kernel(const bf16_t* _
         }
 }
 
+// ---- bf16 backward-weight of 3x3 / stride 1 / pad 1 layers with 64 channels on both sides ----------
+// The whole result (64 x 576 floats) fits the accumulators of one workgroup, so a persistent workgroup keeps it there
+// while it walks its share of the pixels, and writes ONE slice of partials at the end.  Both operands are staged as
+// they lie in memory, once: a tile is two output rows of one image; `dy` goes to LDS as 2 x 64 pixels (columns
+// W .. 63 zero), `x` as 4 x 64 pixels (the rows above and below, one zero column left; zeros outside the image).
+// The contraction runs over the 128 pixel slots of the dy tile (8 MFMA steps of 16); the x operand of tap (r, s) for
+// slot q is slot q + 64 r + s of the x patch -- a constant offset, so the nine-fold im2col expansion happens in the
+// LDS read, and the zero columns of dy cancel whatever the patch holds at the slots that are no pixels.  Operands are
+// formed by the LDS transpose read (see conv_wgrad_tr_kernel) with the same per-256-byte-line chunk swizzle.
+// Wave w multiplies both blocks of 32 output channels with input-channel block w & 1 of the taps (w >> 1), (w >> 1) + 2,
+// ..: 10 (or 8) MFMAs per step from 14 (12) operand reads, instead of 2 reads per MFMA of the tiled kernel.
+// The rows of the next tile are fetched into registers before the steps and written to the other LDS buffer after
+// them (12 16-byte chunks per lane: lane tid moves channel run tid & 7 of columns tid >> 3 and (tid >> 3) + 32).
+struct W64Args {
+    int tiles;          // N * H / 2
+    int tiles_per_wg;   // consecutive tiles per workgroup
+};
+constexpr int kW64DyBytes = 2 * 64 * 128, kW64XBytes = 4 * 64 * 128, kW64Guard = 512;
+constexpr int kW64BufBytes = kW64DyBytes + kW64XBytes + kW64Guard;
+
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void conv3x3_c64_wgrad_bf16_kernel(
+    const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy, float* __restrict__ part, WgradGeom g, W64Args a)
+{
+    constexpr int C = 64, KD = 9 * C, NKS = 8;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int W = g.W, H = g.H, H2 = H / 2;
+    const int ii = wave & 1, pw = wave >> 1, ntaps = pw ? 4 : 5;  // input-channel block, first tap, number of taps
+
+    // the guards behind the x patches stay zero (the taps of the last slots reach two pixels past the patch)
+    for (int b = 0; b < 2; ++b)
+        if (tid < kW64Guard / 16) *(u32x4*)(smem + b * kW64BufBytes + kW64DyBytes + kW64XBytes + tid * 16) = u32x4{0u, 0u, 0u, 0u};
+
+    const uint32_t t_bytes = (uint32_t)g.N * H * W * C * 2u;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, t_bytes), rdy = make_rsrc(dy, t_bytes);
+    const int t_begin = blockIdx.x * a.tiles_per_wg, t_end = min(a.tiles, t_begin + a.tiles_per_wg);
+
+    // fetch: this lane's two columns, as byte offsets inside a tensor row (or "out of range")
+    uint32_t dy_col[2], x_col[2];
+    uint32_t lds_slot[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int col = (tid >> 3) + 32 * h;
+        dy_col[h] = col < W ? (uint32_t)(col * C + (tid & 7) * 8) * 2u : kOutOfRange;
+        x_col[h] = (col >= 1 && col <= W) ? (uint32_t)((col - 1) * C + (tid & 7) * 8) * 2u : kOutOfRange;
+        lds_slot[h] = (uint32_t)swizzled_chunk(col, tid & 7, 128);  // rows of 64 pixels are 32 lines: the swizzle repeats per row
+    }
+    auto fetch = [&](int t, u32x4 (&pre)[12]) {
+        const int n = t / H2, h0 = (t - n * H2) * 2;  // first output row of the tile
+        const uint32_t row_bytes = (uint32_t)W * C * 2u;
+        const uint32_t img = (uint32_t)(n * H) * row_bytes;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t off = img + (uint32_t)(h0 + (i >> 1)) * row_bytes;
+            pre[i] = load16(rdy, dy_col[i & 1] != kOutOfRange ? off + dy_col[i & 1] : kOutOfRange);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int hr = h0 - 1 + (i >> 1);
+            const bool ok = hr >= 0 && hr < H && x_col[i & 1] != kOutOfRange;
+            pre[4 + i] = load16(rx, ok ? img + (uint32_t)hr * row_bytes + x_col[i & 1] : kOutOfRange);
+        }
+    };
+    auto stage = [&](int buf, const u32x4 (&pre)[12]) {
+        char* base = smem + buf * kW64BufBytes;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *(u32x4*)(base + (i >> 1) * 8192 + lds_slot[i & 1]) = pre[i];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *(u32x4*)(base + kW64DyBytes + (i >> 1) * 8192 + lds_slot[i & 1]) = pre[4 + i];
+    };
+
+    // operand reads (transpose reads, see conv_wgrad_tr_kernel): lane (j16, cs, kg) addresses pixel slot
+    // 8 kg + j16 / 4 (+ 4 for the second half) of a step, channels 16 cs + 4 (j16 % 4) .. + 3 of a 32-channel block
+    const int j16 = lane & 15, cs = (lane >> 4) & 1, kg = lane >> 5;
+    const int frag_row = 8 * kg + (j16 >> 2), frag_chunk = cs * 2 + ((j16 & 3) >> 1), frag_half = (j16 & 1) * 8;
+    uint32_t a_addr[2][2];   // [output-channel block][half]
+    uint32_t b_addr[5][2];   // [tap of this wave][half]
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+#pragma unroll
+        for (int ic = 0; ic < 2; ++ic) a_addr[ic][hh] = (uint32_t)(swizzled_chunk(frag_row + 4 * hh, 4 * ic + frag_chunk, 128) + frag_half);
+#pragma unroll
+        for (int k = 0; k < 5; ++k) {
+            const int tap = pw + 2 * k, r = tap / 3, s2 = tap - 3 * r;
+            b_addr[k][hh] = (uint32_t)(kW64DyBytes + swizzled_chunk(frag_row + 4 * hh + 64 * r + s2, 4 * ii + frag_chunk, 128) + frag_half);
+        }
+    }
+
+    typename Mma<bf16_t, 32>::Acc acc[5][2];
+#pragma unroll
+    for (int k = 0; k < 5; ++k)
+#pragma unroll
+        for (int ic = 0; ic < 2; ++ic)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[k][ic][e] = 0.f;
+
+    u32x4 pre[12];
+    if (t_begin < t_end) {
+        fetch(t_begin, pre);
+        stage(0, pre);
+    }
+    int cur = 0;
+    for (int t = t_begin; t < t_end; ++t) {
+        const bool has_next = t + 1 < t_end;
+        __syncthreads();  // this tile is staged; every wave has finished the previous tile (its buffer is written below)
+        if (has_next) fetch(t + 1, pre);
+        const char* buf = smem + cur * kW64BufBytes;
+        auto read_a = [&](int ks, u32x4 (&fa)[2]) {
+#pragma unroll
+            for (int ic = 0; ic < 2; ++ic) {
+                const u32x2 lo = lds_read_tr16(buf + a_addr[ic][0] + ks * 2048), hi = lds_read_tr16(buf + a_addr[ic][1] + ks * 2048);
+                fa[ic] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            }
+        };
+        auto read_b = [&](int ks, u32x4 (&fb)[5]) {
+#pragma unroll
+            for (int k = 0; k < 5; ++k)
+                if (k < 4 || ntaps == 5) {
+                    const u32x2 lo = lds_read_tr16(buf + b_addr[k][0] + ks * 2048), hi = lds_read_tr16(buf + b_addr[k][1] + ks * 2048);
+                    fb[k] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                }
+        };
+        u32x4 fa[2][2], fb[2][5];
+        read_a(0, fa[0]);
+        read_b(0, fb[0]);
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            if (ks + 1 < NKS) {
+                read_a(ks + 1, fa[(ks + 1) & 1]);
+                read_b(ks + 1, fb[(ks + 1) & 1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < 5; ++k)
+                if (k < 4 || ntaps == 5)
+#pragma unroll
+                    for (int ic = 0; ic < 2; ++ic) Mma<bf16_t, 32>::run(fa[ks & 1][ic], fb[ks & 1][k], acc[k][ic]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (has_next) stage(cur ^ 1, pre);
+        cur ^= 1;
+    }
+
+    // one slice of partials per workgroup: dw[co][tap * 64 + ci]
+    float* dst = part + (int64_t)blockIdx.x * C * KD;
+#pragma unroll
+    for (int k = 0; k < 5; ++k)
+        if (k < 4 || ntaps == 5) {
+            const int col = (pw + 2 * k) * C + 32 * ii + (lane & 31);
+#pragma unroll
+            for (int ic = 0; ic < 2; ++ic)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) dst[(int64_t)(32 * ic + acc_row<32>(lane, e)) * KD + col] = acc[k][ic][e];
+        }
+}
+
 // Backward-weight of an fp32 layer with 16 input and 16 output channels.  The GEMM output is only
 // 16 x (R*S*16), so LDS tiling buys nothing: each wave streams its own output pixels straight from
 // global memory into the 16x16x4 MFMA operand layout (lane = (pixel % 4) * 16 + channel, one
@@ -2254,6 +2410,22 @@ int wgrad_splits(const ConvShape& cc, const WgradPlan& pl, int* m_per_split)
     return ceil_div(M, per);
 }
 
+// The persistent accumulators-resident kernel: bf16, 3x3 / stride 1 / pad 1, 64 channels on both sides, image rows of
+// 51 .. 62 pixels, an even number of them, enough tiles (pairs of rows) for every compute unit.
+bool wgrad_c64_eligible(int dtype, const ConvShape& c)
+{
+    return dtype == DSP_BF16 && conv_groups(c) == 1 && c.Cin == 64 && c.Cout == 64 && c.R == 3 && c.S == 3 && c.stride == 1 &&
+           c.pad == 1 && c.Ho == c.H && c.Wo == c.W && c.W >= 51 && c.W <= 62 && c.H % 2 == 0 && (int64_t)c.N * c.H / 2 >= 512;
+}
+// One slice of partials per workgroup, one workgroup per compute unit.
+int wgrad_c64_slices(const ConvShape& c, int* tiles_per_wg)
+{
+    const int tiles = c.N * c.H / 2;
+    const int per = ceil_div(tiles, 256);
+    if (tiles_per_wg) *tiles_per_wg = per;
+    return ceil_div(tiles, per);
+}
+
 // The register-streaming kernel serves fp32 layers with 16 -> 16 channels and 3x3 or 1x1 filters.
 bool wgrad_c16_eligible(int dtype, const ConvShape& c)
 {
@@ -2290,7 +2462,10 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
     fast_div_constants((uint32_t)c.Wo, &g.wo_mul, &g.wo_sh);
     fast_div_constants((uint32_t)c.Ho, &g.ho_mul, &g.ho_sh);
     const bool c16 = wgrad_c16_eligible(dtype, c);
-    const int splits = c16 ? wgrad_c16_splits(c, &g.m_per_split) : wgrad_splits(c, pl, &g.m_per_split);
+    const bool c64 = wgrad_c64_eligible(dtype, c);
+    int c64_per = 0;
+    const int splits = c64 ? wgrad_c64_slices(c, &c64_per)
+                           : c16 ? wgrad_c16_splits(c, &g.m_per_split) : wgrad_splits(c, pl, &g.m_per_split);
     const size_t n = (size_t)c.Cout * g.Kdim;
     float* dst = dw;
     if (splits > 1) {
@@ -2300,7 +2475,20 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
     }
     const bool vec = (g.Ci % E) == 0 && (g.Co % E) == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)dy % 16) == 0;
     int rc;
-    if (c16) {
+    if (c64) {
+        // (the slice count is fixed by the shape; tensors that are not 16-byte aligned cannot use this kernel)
+        DSP_REQUIRE(vec, DSP_EINVAL, "conv backward-weight: x and dy of this layer shape must be 16-byte aligned");
+        W64Args a{c.N * c.H / 2, c64_per};
+        auto kern = conv3x3_c64_wgrad_bf16_kernel;
+        static std::atomic<bool> attr_done{false};
+        if (!attr_done) {
+            DSP_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kW64BufBytes));
+            attr_done = true;
+        }
+        ProfScope ps("conv_wgrad_c64<bf16,accumulators resident>", flops, 0);
+        DSP_LAUNCH(ps, kern, dim3(splits), dim3(kThreads), 2 * kW64BufBytes, st, (const bf16_t*)x, (const bf16_t*)dy, dst, g, a);
+        rc = DSP_OK;
+    } else if (c16) {
         ProfScope ps(c.R == 3 ? "conv_wgrad_c16<fp32,3x3>" : "conv_wgrad_c16<fp32,1x1>", flops, 0);
         if (c.R == 3)
             DSP_LAUNCH(ps, (conv_wgrad_c16_kernel<3, 3>), dim3(splits), dim3(kThreads), 0, st, (const float*)x,
@@ -2513,7 +2701,8 @@ size_t conv_backward_weight_workspace(const ConvShape& c)
     for (int dtype = 0; dtype < 2; ++dtype) {
         const WgradPlan pl = wgrad_plan(dtype, c);
         int per;
-        const int splits = wgrad_c16_eligible(dtype, c) ? wgrad_c16_splits(c, &per) : wgrad_splits(c, pl, &per);
+        const int splits = wgrad_c64_eligible(dtype, c) ? wgrad_c64_slices(c, nullptr)
+                           : wgrad_c16_eligible(dtype, c) ? wgrad_c16_splits(c, &per) : wgrad_splits(c, pl, &per);
         const size_t b = splits > 1 ? (size_t)splits * c.Cout * c.R * c.S * (c.Cin / conv_groups(c)) * sizeof(float) : 0;
         if (b > worst) worst = b;
     }
@@ -2533,6 +2722,7 @@ int conv_backward_weight_slices(int dtype, const ConvShape& c)
 {
     // aligned 16-byte tensors assumed (the slicing does not depend on the alignment)
     int per;
+    if (wgrad_c64_eligible(dtype, c)) return wgrad_c64_slices(c, nullptr);
     if (wgrad_c16_eligible(dtype, c)) return wgrad_c16_splits(c, &per);
     return wgrad_splits(c, wgrad_plan(dtype, c), &per);
 }
