@@ -82,6 +82,7 @@ struct Layer {
     size_t wt_off = 0;      // offset of the backward-data filter copy
     float* mean = nullptr;
     float* invstd = nullptr;
+    float* fcoef = nullptr;  // bn: {scale[C], shift[C]} of the last forward pass over the primary buffers (the backward sweep decides the ReLU with them)
     uint8_t* argmax = nullptr;
     bool in0_grad = true;  // form the gradient w.r.t. in0
     bool in1_grad = true;
@@ -484,6 +485,7 @@ static int build_graph(dsp_block* b)
         if (L.d.op == DSP_OP_BN) {
             DSP_TRY(dev_alloc(b, (void**)&L.mean, (size_t)L.d.cin * 4, &b->ws_bytes));
             DSP_TRY(dev_alloc(b, (void**)&L.invstd, (size_t)L.d.cin * 4, &b->ws_bytes));
+            DSP_TRY(dev_alloc(b, (void**)&L.fcoef, (size_t)L.d.cin * 8, &b->ws_bytes));
             if (L.d.cin > max_c) max_c = L.d.cin;
         }
         if (L.d.op == DSP_OP_MAXPOOL) DSP_TRY(dev_alloc(b, (void**)&L.argmax, t.elems, &b->ws_bytes));
@@ -584,7 +586,7 @@ static int run_forward(dsp_block* b, const ForwardPass& P, const ForwardPass* tw
         auto src_of = [&](const ForwardPass& p, int t) -> const void* { return t < 0 ? p.in : act_of(p, t); };
         auto bn_buffers = [&](const ForwardPass& p) {
             return BnBuffers{p.lane ? p.lane->bn_partial : b->bn_partial, p.lane ? p.lane->mean[i] : L.mean,
-                             p.lane ? p.lane->invstd[i] : L.invstd, p.lane ? p.lane->bn_coef : b->bn_coef};
+                             p.lane ? p.lane->invstd[i] : L.invstd, p.lane ? p.lane->bn_coef : L.fcoef};
         };
         const int passes = twin ? 2 : 1;
         switch (L.d.op) {
@@ -700,7 +702,8 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
             }
             DSP_TRY(launch_bn_backward(b->dtype, dy, src, b->T[i].act, grad_of(L.d.in0), dres, L.in1_acc, L.in0_acc,
                                        b->x + L.p0, b->g + L.p0, b->g + L.p1, (int64_t)s.N * s.H * s.W, s.C,
-                                       L.d.relu != 0, buf, st, dx_add));
+                                       L.d.relu != 0, buf, st, dx_add,
+                                       L.d.in1 == -2 ? L.fcoef : nullptr));
             break;
         }
         case DSP_OP_ADD: {

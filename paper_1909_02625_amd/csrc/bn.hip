@@ -34,9 +34,19 @@ inline RowLayout make_layout(int C, int VW)
     return L;
 }
 
+// scale * x + shift as the forward pass stores it (one fused multiply-add, rounded to the storage type): the backward
+// kernels that decide the ReLU from x call this too, and get the forward pass's decision
+template <typename T>
+__device__ inline float bn_value(float x, float scale, float shift)
+{
+    return to_float<T>(from_float<T>(__builtin_fmaf(x, scale, shift)));
+}
+
 // ---- per-channel sums ---------------------------------------------------------------------------
 // MODE 0: s0 = sum x, s1 = sum x^2.
-// MODE 1: dz = dy * [y > 0] (if RELU); s0 = sum dz, s1 = sum dz * (x - mean) * invstd.
+// MODE 1: dz = dy * [y > 0] (if RM != 0); s0 = sum dz, s1 = sum dz * (x - mean) * invstd.  RM = 1 reads the stored y;
+//         RM = 2 (a batch norm without residual) forms y again from x and the forward pass's {scale, shift} with the
+//         forward kernel's own expression and rounding, so the decision is the same and y is never read.
 // MODE 2: out = x + dy as stored (the element-wise sum of two feature maps); s0 = sum out, s1 = sum out^2:
 //         the sum layer together with the statistics pass of the batch norm that reads it.
 // part[blockIdx.x][c][2]; blockIdx.y walks channel groups when C/VW > 256.
@@ -46,13 +56,13 @@ struct AddOut {
     const T* b1;   // second instance: the other operand and the sum
     T* out1;
 };
-template <typename T, int VW, int MODE, bool RELU>
+template <typename T, int VW, int MODE, int RM>
 __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__ x, const T* __restrict__ dy,
                                                            const T* __restrict__ y, const float* __restrict__ mean,
                                                            const float* __restrict__ invstd, double* __restrict__ part,
                                                            int64_t M, int C, RowLayout L, int rows_per_block,
                                                            const T* __restrict__ x1, double* __restrict__ part1,
-                                                           AddOut<T> add)
+                                                           AddOut<T> add, const float* __restrict__ fcoef)
 {
     // blockIdx.z = 1: the second instance of a twin launch (other tensor, same shape)
     T* __restrict__ out = add.out;
@@ -73,12 +83,16 @@ __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__
     double s0[VW], s1[VW];
 #pragma unroll
     for (int i = 0; i < VW; ++i) s0[i] = s1[i] = 0.0;
-    float mu[VW], is[VW];
+    float mu[VW], is[VW], fsc[VW], fsh[VW];
     if (MODE == 1 && active) {
 #pragma unroll
         for (int i = 0; i < VW; ++i) {
             mu[i] = mean[c0 + i];
             is[i] = invstd[c0 + i];
+            if (RM == 2) {
+                fsc[i] = fcoef[c0 + i];
+                fsh[i] = fcoef[C + c0 + i];
+            }
         }
     }
     const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
@@ -95,7 +109,7 @@ __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__
                 if (ru < r_end) {
                     VecIO<T, VW>::load(x + ru * C + c0, xv[u]);
                     if (MODE >= 1) VecIO<T, VW>::load(dy + ru * C + c0, gv[u]);
-                    if (MODE == 1 && RELU) VecIO<T, VW>::load(y + ru * C + c0, yv[u]);
+                    if (MODE == 1 && RM == 1) VecIO<T, VW>::load(y + ru * C + c0, yv[u]);
                 }
             }
 #pragma unroll
@@ -108,7 +122,8 @@ __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__
                         s0[i] += (double)xv[u][i];
                         s1[i] += (double)xv[u][i] * (double)xv[u][i];
                     } else {
-                        const float dz = (!RELU || yv[u][i] > 0.f) ? gv[u][i] : 0.f;
+                        if (RM == 2) yv[u][i] = bn_value<T>(xv[u][i], fsc[i], fsh[i]);
+                        const float dz = (RM == 0 || yv[u][i] > 0.f) ? gv[u][i] : 0.f;
                         s0[i] += (double)dz;
                         s1[i] += (double)(dz * ((xv[u][i] - mu[i]) * is[i]));
                     }
@@ -265,7 +280,7 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_apply_kernel(BnApplyIo io0, B
         if (HAS_RES) VecIO<T, VW>::load(res + i * VW, rv);
 #pragma unroll
         for (int k = 0; k < VW; ++k) {
-            float v = xv[k] * coef[c0 + k] + coef[C + c0 + k];
+            float v = __builtin_fmaf(xv[k], coef[c0 + k], coef[C + c0 + k]);
             if (HAS_RES) v += rv[k];
             if (RELU) v = v > 0.f ? v : 0.f;
             ov[k] = v;
@@ -274,13 +289,13 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_apply_kernel(BnApplyIo io0, B
     }
 }
 
-// dz = dy*[y>0];  dx = [dx_prev +] c1*dz - c2*x + c0;  dres (+)= dz.  dx_prev is dx itself (accumulate in place)
+// dz = dy*[y>0] (y as stored, or formed again from x: RM as in bn_sums_kernel);  dx = [dx_prev +] c1*dz - c2*x + c0;  dres (+)= dz.  dx_prev is dx itself (accumulate in place)
 // or another tensor's gradient that reaches the same input (the shortcut of a pre-activation unit).
-template <typename T, int VW, bool RELU, bool HAS_RES, bool RES_ACC, bool DX_ACC>
+template <typename T, int VW, int RM, bool HAS_RES, bool RES_ACC, bool DX_ACC>
 __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                                 const T* __restrict__ y, T* dx, const T* dx_prev,
                                                                 T* __restrict__ dres, const float* __restrict__ coef,
-                                                                int64_t nvec, int C, int cv)
+                                                                int64_t nvec, int C, int cv, const float* __restrict__ fcoef)
 {
     // channel vector of element i = i mod cv, carried along the grid-stride loop instead of divided out each trip
     const uint32_t step = gridDim.x * kThreads, step_c = step % (uint32_t)cv;
@@ -291,12 +306,13 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(const T* __restr
         float gv[VW], xv[VW], yv[VW], ov[VW], rv[VW];
         VecIO<T, VW>::load(dy + i * VW, gv);
         VecIO<T, VW>::load(x + i * VW, xv);
-        if (RELU) VecIO<T, VW>::load(y + i * VW, yv);
+        if (RM == 1) VecIO<T, VW>::load(y + i * VW, yv);
         if (DX_ACC) VecIO<T, VW>::load(dx_prev + i * VW, ov);
         if (HAS_RES && RES_ACC) VecIO<T, VW>::load(dres + i * VW, rv);
 #pragma unroll
         for (int k = 0; k < VW; ++k) {
-            const float dz = (!RELU || yv[k] > 0.f) ? gv[k] : 0.f;
+            if (RM == 2) yv[k] = bn_value<T>(xv[k], fcoef[c0 + k], fcoef[C + c0 + k]);
+            const float dz = (RM == 0 || yv[k] > 0.f) ? gv[k] : 0.f;
             const float d = coef[c0 + k] * dz - coef[C + c0 + k] * xv[k] + coef[2 * C + c0 + k];
             ov[k] = DX_ACC ? ov[k] + d : d;
             if (HAS_RES) rv[k] = RES_ACC ? rv[k] + dz : dz;
@@ -341,9 +357,9 @@ int bn_forward_t(const void* x, const void* res, void* y, const float* gamma, co
         nblk = presummed;
     } else {
         ProfScope ps(sizeof(T) == 2 ? "bn_stats<bf16>" : "bn_stats<fp32>", tensor_bytes, 1);
-        DSP_LAUNCH(ps, (bn_sums_kernel<T, VW, 0, false>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)nullptr,
+        DSP_LAUNCH(ps, (bn_sums_kernel<T, VW, 0, 0>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)nullptr,
                    (const T*)nullptr, (const float*)nullptr, (const float*)nullptr, buf.partial, M, C, L, rows,
-                   (const T*)(tw ? tw->x : nullptr), tw ? tw->buf.partial : nullptr, AddOut<T>{});
+                   (const T*)(tw ? tw->x : nullptr), tw ? tw->buf.partial : nullptr, AddOut<T>{}, (const float*)nullptr);
     }
     {
         const BnStatOut o0{buf.partial, buf.mean, buf.invstd, buf.coef};
@@ -369,10 +385,10 @@ int bn_forward_t(const void* x, const void* res, void* y, const float* gamma, co
     return DSP_OK;
 }
 
-template <typename T, int VW, bool RELU>
+template <typename T, int VW, int RM>
 int bn_backward_t(const void* dy, const void* x, const void* y, void* dx, void* dres, bool racc, bool xacc,
                   const float* gamma, float* dgamma, float* dbeta, int64_t M, int C, const BnBuffers& buf, hipStream_t st,
-                  const void* dx_prev)
+                  const void* dx_prev, const float* fcoef)
 {
     const RowLayout L = make_layout(C, VW);
     int nblk;
@@ -380,10 +396,10 @@ int bn_backward_t(const void* dy, const void* x, const void* y, void* dx, void* 
     const dim3 grid(nblk, ceil_div(L.cv, L.cvb));
     const double tensor_bytes = (double)M * C * sizeof(T);
     {
-        ProfScope ps(sizeof(T) == 2 ? "bn_bwd_reduce<bf16>" : "bn_bwd_reduce<fp32>", tensor_bytes * (RELU ? 3 : 2), 1);
-        DSP_LAUNCH(ps, (bn_sums_kernel<T, VW, 1, RELU>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)dy,
+        ProfScope ps(sizeof(T) == 2 ? "bn_bwd_reduce<bf16>" : "bn_bwd_reduce<fp32>", tensor_bytes * (RM == 1 ? 3 : 2), 1);
+        DSP_LAUNCH(ps, (bn_sums_kernel<T, VW, 1, RM>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)dy,
                    (const T*)y, (const float*)buf.mean, (const float*)buf.invstd, buf.partial, M, C, L, rows,
-                   (const T*)nullptr, (double*)nullptr, AddOut<T>{});
+                   (const T*)nullptr, (double*)nullptr, AddOut<T>{}, fcoef);
     }
     {
         ProfScope ps("bn_bwd_finalize", (double)nblk * C * 16.0, 1);
@@ -392,12 +408,14 @@ int bn_backward_t(const void* dy, const void* x, const void* y, void* dx, void* 
     }
     const int64_t nvec = M * (C / VW);
     const dim3 ag(apply_grid(nvec));
-    // reads dy, x (and y for the ReLU mask, and the old values where it accumulates); writes dx (and dres)
+    // reads dy, x (y too where the ReLU is decided from the stored output, and the old values where it accumulates);
+    // writes dx (and dres)
     ProfScope ps(sizeof(T) == 2 ? "bn_bwd_apply<bf16>" : "bn_bwd_apply<fp32>",
-                 tensor_bytes * (2 + (RELU ? 1 : 0) + 1 + (xacc ? 1 : 0) + (dres ? 1 + (racc ? 1 : 0) : 0)), 1);
+                 tensor_bytes * (2 + (RM == 1 ? 1 : 0) + 1 + (xacc ? 1 : 0) + (dres ? 1 + (racc ? 1 : 0) : 0)), 1);
 #define BN_BAPPLY(H, RA, XA)                                                                                   \
-    DSP_LAUNCH(ps, (bn_bwd_apply_kernel<T, VW, RELU, H, RA, XA>), ag, dim3(kThreads), 0, st, (const T*)dy,    \
-               (const T*)x, (const T*)y, (T*)dx, (const T*)dx_prev, (T*)dres, (const float*)buf.coef, nvec, C, L.cv)
+    DSP_LAUNCH(ps, (bn_bwd_apply_kernel<T, VW, (H && RM == 2) ? 1 : RM, H, RA, XA>), ag, dim3(kThreads), 0, st, \
+               (const T*)dy, (const T*)x, (const T*)y, (T*)dx, (const T*)dx_prev, (T*)dres, (const float*)buf.coef,   \
+               nvec, C, L.cv, fcoef)
     if (dres) {
         if (racc) { if (xacc) BN_BAPPLY(true, true, true); else BN_BAPPLY(true, true, false); }
         else      { if (xacc) BN_BAPPLY(true, false, true); else BN_BAPPLY(true, false, false); }
@@ -423,9 +441,10 @@ int add_stats_t(const void* a, const void* b, void* y, int64_t M, int C, double*
     const unsigned ni = tw ? 2 : 1;
     const dim3 grid(nblk, ceil_div(L.cv, L.cvb), ni);
     ProfScope ps("add_fwd_stats", (double)M * C * sizeof(T) * 3.0 * ni, 1);
-    DSP_LAUNCH(ps, (bn_sums_kernel<T, VW, 2, false>), grid, dim3(kThreads), 0, st, (const T*)a, (const T*)b, (const T*)nullptr,
+    DSP_LAUNCH(ps, (bn_sums_kernel<T, VW, 2, 0>), grid, dim3(kThreads), 0, st, (const T*)a, (const T*)b, (const T*)nullptr,
                (const float*)nullptr, (const float*)nullptr, partial, M, C, L, rows, (const T*)(tw ? tw->a : nullptr),
-               tw ? tw->partial : nullptr, (AddOut<T>{(T*)y, (const T*)(tw ? tw->b : nullptr), (T*)(tw ? tw->y : nullptr)}));
+               tw ? tw->partial : nullptr, (AddOut<T>{(T*)y, (const T*)(tw ? tw->b : nullptr), (T*)(tw ? tw->y : nullptr)}),
+               (const float*)nullptr);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
 }
@@ -471,16 +490,20 @@ int launch_bn_forward(int dtype, const void* x, const void* res, void* y, const 
 
 int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, void* dx, void* dres,
                        bool dres_accumulate, bool dx_accumulate, const float* gamma, float* dgamma, float* dbeta,
-                       int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, const void* dx_add)
+                       int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, const void* dx_add,
+                       const float* fwd_coef)
 {
     DSP_REQUIRE(M > 0 && C > 0, DSP_EINVAL, "bn: bad shape");
     const void* dx_prev = dx_add ? dx_add : dx;
     if (dx_add) dx_accumulate = true;
-#define BN_BWD(T, VW)                                                                                              \
-    (relu ? bn_backward_t<T, VW, true>(dy, x, y, dx, dres, dres_accumulate, dx_accumulate, gamma, dgamma, dbeta, M, \
-                                       C, buf, st, dx_prev)                                                        \
-          : bn_backward_t<T, VW, false>(dy, x, y, dx, dres, dres_accumulate, dx_accumulate, gamma, dgamma, dbeta,  \
-                                        M, C, buf, st, dx_prev))
+    // the ReLU of a batch norm without residual can be decided from x (no read of y) when the caller still has the
+    // forward pass's {scale, shift}
+    const bool from_x = relu && fwd_coef && !dres;
+    DSP_REQUIRE(!relu || from_x || y, DSP_EINVAL, "bn backward: the ReLU needs the stored output");
+#define BN_BWD_RM(T, VW, RM)                                                                                        \
+    bn_backward_t<T, VW, RM>(dy, x, y, dx, dres, dres_accumulate, dx_accumulate, gamma, dgamma, dbeta, M, C, buf, st, \
+                             dx_prev, fwd_coef)
+#define BN_BWD(T, VW) (!relu ? BN_BWD_RM(T, VW, 0) : from_x ? BN_BWD_RM(T, VW, 2) : BN_BWD_RM(T, VW, 1))
     if (dtype == DSP_BF16) {
         if (C % 8 == 0) return BN_BWD(bf16_t, 8);
         return BN_BWD(bf16_t, 1);
@@ -488,6 +511,7 @@ int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, 
     if (C % 4 == 0) return BN_BWD(float, 4);
     return BN_BWD(float, 1);
 #undef BN_BWD
+#undef BN_BWD_RM
 }
 
 }  // namespace dsp

@@ -154,9 +154,10 @@ inline ConvShape make_conv_shape(int N, int H, int W, int Cin, int Cout, int R, 
     return c;
 }
 
-// y = conv(x, w);  w in [Cout][R][S][Cin].  With column_sums != nullptr the kernel also writes, per row
-// tile t of y[M][Cout] (conv_forward_row_tiles of them), column_sums[(t*Cout + c)*2 + {0,1}] =
-// {sum y, sum y^2} over the tile's rows of the values as stored -- the statistics a batch norm on y needs.
+// y = conv(x, w);  w in [Cout][R][S][Cin].  With column_sums != nullptr the kernel also writes partial column sums of
+// y[M][Cout]: column_sums[(t*Cout + c)*2 + {0,1}] = {sum y, sum y^2} over the rows of part t, of the values as stored --
+// the statistics a batch norm on y needs.  The conv_forward_row_tiles() parts cover every row once (one part per row
+// tile of the kernel the shape selects, or per workgroup where a workgroup walks many tiles).
 // twin != nullptr: the same launch also computes twin->y = conv(twin->x, w) (and twin->column_sums if
 // column_sums is given): the forward pass of the current mini-batch and the recompute of a stale one
 // share their parameters, so one launch per layer serves both.
@@ -237,9 +238,12 @@ int launch_add_forward_stats(int dtype, const void* a, const void* b, void* y, i
 // dz = dy * [y > 0]; dres (+)= dz; dgamma, dbeta; dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M).
 // dx_add != nullptr: dx = dx_add + (the above) -- the gradient another consumer of the same input left in a
 // buffer of its own (then dx_accumulate is ignored).
+// fwd_coef != nullptr (a batch norm with ReLU and no residual): the forward pass's {scale[C], shift[C]}; the ReLU is
+// then decided by forming y from x again, exactly as the forward kernel did, and y is not read (may be nullptr).
 int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, void* dx, void* dres,
                        bool dres_accumulate, bool dx_accumulate, const float* gamma, float* dgamma, float* dbeta,
-                       int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, const void* dx_add = nullptr);
+                       int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, const void* dx_add = nullptr,
+                       const float* fwd_coef = nullptr);
 
 // ---- small layers and the update (misc.hip) ---------------------------------------------------
 int launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* argmax, int N, int H, int W, int C, int k,

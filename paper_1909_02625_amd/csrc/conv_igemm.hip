@@ -867,9 +867,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::WA
 struct C64Args {
     int buf_bytes;       // bytes of one patch buffer (>= kC64Chunks * 4 KB and >= the staged output tile + column-sum scratch)
     int tiles;           // row tiles of 256 output pixels per problem instance
-    int total_tiles;     // tiles x (1 or 2 instances)
-    int tiles_per_wg;    // consecutive tiles one workgroup walks (neighbouring tiles share input rows: same L2, soon after)
+    int twin;            // 1: a second problem instance (in1 / out1 / stats1)
 };
+// Workgroup w of W walks the consecutive tiles [w * tiles / W, (w + 1) * tiles / W) of the first instance (neighbouring
+// tiles share input rows: same L2, soon after) and then, in a twin launch, the range of workgroup W - 1 - w in the second
+// instance (ranges differ by one tile; pairing a long one with a short one evens the work out).  The column sums for a
+// following batch norm are kept per thread across a whole range and leave as ONE partial row per workgroup and
+// instance: row w of the first instance's sums, row W - 1 - w of the second's.
 constexpr int kC64Zero = 512;    // zero region at the start of LDS
 constexpr int kC64EpiRowB = 64 * 2 + 16;
 constexpr int kC64Chunks = 16;   // 16-byte chunks of a patch per lane: 8 rows of 64 pixels
@@ -916,8 +920,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     const __amdgpu_buffer_rsrc_t rin0 = make_rsrc(in_, in_bytes);
     const __amdgpu_buffer_rsrc_t rin1 = make_rsrc(g.in1 ? g.in1 : in_, in_bytes);
 
-    const int t_begin = blockIdx.x * a.tiles_per_wg;
-    const int t_end = min(a.total_tiles, t_begin + a.tiles_per_wg);
+    const int nw = (int)gridDim.x, w1 = nw - 1 - (int)blockIdx.x;
+    auto range_lo = [&](int w) { return (int)((int64_t)w * a.tiles / nw); };
+    const int b0 = range_lo((int)blockIdx.x), n0 = range_lo((int)blockIdx.x + 1) - b0;
+    const int b1 = range_lo(w1), n1 = a.twin ? range_lo(w1 + 1) - b1 : 0;
+    const int n_steps = n0 + n1;
+    auto tile_at = [&](int s) { return s < n0 ? b0 + s : a.tiles + b1 + (s - n0); };  // second instance: tiles + its row tile
 
     // the input rows of tile t, 16 chunks per lane: chunk i = position tid & 7 of patch pixel (row i >> 1, column
     // (tid >> 3) + 32 (i & 1)); zeros for the border columns, for rows outside the tensor and past the rows the tile touches
@@ -947,13 +955,18 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     };
 
     u32x4 pre[NCH];
-    if (t_begin < t_end) {
-        fetch_patch(t_begin, pre);
+    if (n_steps > 0) {
+        fetch_patch(tile_at(0), pre);
 #pragma unroll
         for (int i = 0; i < NCH; ++i) *(u32x4*)(smem + kC64Zero + (tid + kThreads * i) * 16) = pre[i];
     }
+    // column sums of this thread's 8 channels over the rows it stores, carried across the tiles of a range
+    float cs0[8], cs1[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) cs0[e] = cs1[e] = 0.f;
     int cur = 0;
-    for (int t = t_begin; t < t_end; ++t) {
+    for (int step = 0; step < n_steps; ++step) {
+        const int t = tile_at(step);
         const int inst = t >= a.tiles ? 1 : 0;
         const int row_tile = t - inst * a.tiles;
         const int m0 = row_tile * BM;
@@ -962,12 +975,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         const int R0 = (int)fast_div((uint32_t)m0, g.wo_mul, g.wo_sh) - 1;
         char* patch = smem + kC64Zero + cur * a.buf_bytes;
         char* next_patch = smem + kC64Zero + (cur ^ 1) * a.buf_bytes;
-        const bool has_next = t + 1 < t_end;
+        const bool has_next = step + 1 < n_steps;
 
         // this tile's rows are in LDS (written by all waves during the previous tile, or just above), and every wave is
         // past the previous tile's epilogue, whose staging area this tile's prefetch will overwrite
         lds_barrier();
-        if (has_next) fetch_patch(t + 1, pre);
+        if (has_next) fetch_patch(tile_at(step + 1), pre);
 
         // per lane and 32-pixel block: LDS address of tap row r (or the zero region), swizzle keys of the three tap columns
         uint32_t base_r[2][3], keyf[2][3];
@@ -1000,6 +1013,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+        const int cc = (tid & 7) * 8, lr0 = tid >> 3;  // this thread's part of the output tile: rows lr0 + 32 k, 8 channels from cc
+        static_assert(NKS - 8 >= WR0 + 8, "the first 8 prefetch registers are free for the last 8 steps");
         u32x4 fa[2][2];
         read_frag(0, fa[0]);
 #pragma unroll
@@ -1007,6 +1022,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             if (ks + 1 < NKS) read_frag(ks + 1, fa[(ks + 1) & 1]);
             // the next tile's rows move from registers to the other patch buffer during the last steps
             if (ks >= WR0 && has_next) *(u32x4*)(next_patch + (tid + kThreads * (ks - WR0)) * 16) = pre[ks - WR0];
+            // accumulating launches: what the output tile holds so far, as the 16-byte runs this thread will store
+            // (coalesced, in flight during the last steps), into prefetch registers that have just been written out; the
+            // sum is taken on the rounded tile, in float, and rounded again
+            if (ACCUM && ks >= NKS - 8) {
+                const int m = m0 + lr0 + 32 * (ks - (NKS - 8));
+                pre[ks - (NKS - 8)] = m < g.M ? *(const u32x4*)(out + (int64_t)m * C + cc) : u32x4{0u, 0u, 0u, 0u};
+            }
             __builtin_amdgcn_sched_barrier(0);  // the next step's fragment reads go out before this step's MFMAs
 #pragma unroll
             for (int i = 0; i < 2; ++i)
@@ -1022,16 +1044,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int lr = wave * 64 + i * 32 + frow;
-                const int m = m0 + lr;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int col = j * 32 + acc_row<32>(lane, 4 * q);
-                    if (ACCUM && m < g.M) {
-                        float o[4];
-                        Run4<T>::unpack(*(const RunV*)(out + (int64_t)m * C + col), o);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += o[e];
-                    }
                     *(RunV*)(patch + lr * kC64EpiRowB + col * 2) =
                         Run4<T>::pack(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
                 }
@@ -1039,18 +1054,25 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         lds_barrier();
         {
             // thread = (row tid >> 3 of each group of 32 rows, 16-byte run tid & 7): all eight reads first, then the stores
-            const int cc = (tid & 7) * 8, lr0 = tid >> 3;
             u32x4 v[8];
 #pragma unroll
             for (int k = 0; k < 8; ++k) v[k] = *(const u32x4*)(patch + (lr0 + 32 * k) * kC64EpiRowB + cc * 2);
+            if (ACCUM) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        v[k][e] = pack_bf16x2(__uint_as_float(v[k][e] << 16) + __uint_as_float(pre[k][e] << 16),
+                                              __uint_as_float(v[k][e] & 0xffff0000u) + __uint_as_float(pre[k][e] & 0xffff0000u));
+            }
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 const int m = m0 + lr0 + 32 * k;
                 if (m < g.M) *(u32x4*)(out + (int64_t)m * C + cc) = v[k];
             }
-            if (stats) {
+            if (!ACCUM && stats) {  // (an accumulating launch is a backward-data pass: no sums)
                 // column sums of the staged tile (rows past M hold zeros) from the same registers: this thread's 8 rows
-                // of its 8 channels, then the 32 row groups per channel in a fixed order
+                // of its 8 channels (one float sum per tile, added to the running sums of the range)
                 float s0[8], s1[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) s0[e] = s1[e] = 0.f;
@@ -1064,21 +1086,27 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
                         s0[2 * e + 1] += hi;
                         s1[2 * e + 1] += hi * hi;
                     }
-                float* sred = (float*)(patch + BM * kC64EpiRowB);  // [32 row groups][64 channels][2]
 #pragma unroll
-                for (int e = 0; e < 8; e += 2)
-                    *(f32x4*)(sred + (lr0 * 64 + cc + e) * 2) = f32x4{s0[e], s1[e], s0[e + 1], s1[e + 1]};
-                lds_barrier();
-                if (tid < 64) {
-                    double sa = 0.0, sb = 0.0;
+                for (int e = 0; e < 8; ++e) {
+                    cs0[e] += s0[e];
+                    cs1[e] += s1[e];
+                }
+                if (step == n0 - 1 || step == n_steps - 1) {
+                    // the range ends: the 32 row groups per channel, in double and in a fixed order, into this workgroup's
+                    // partial row of the instance
+                    float* sred = (float*)(patch + BM * kC64EpiRowB);  // [32 row groups][64 channels][2]
+#pragma unroll
+                    for (int e = 0; e < 8; e += 2)
+                        *(f32x4*)(sred + (lr0 * 64 + cc + e) * 2) = f32x4{cs0[e], cs1[e], cs0[e + 1], cs1[e + 1]};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) cs0[e] = cs1[e] = 0.f;
+                    lds_barrier();
+                    if (tid < 128) {
+                        double sa = 0.0;
 #pragma unroll 8
-                    for (int k = 0; k < 32; ++k) {
-                        sa += (double)sred[(k * 64 + tid) * 2];
-                        sb += (double)sred[(k * 64 + tid) * 2 + 1];
+                        for (int k = 0; k < 32; ++k) sa += (double)sred[k * 128 + tid];
+                        stats[(int64_t)(inst ? w1 : (int)blockIdx.x) * (C * 2) + tid] = sa;
                     }
-                    double* dst = stats + ((int64_t)row_tile * C + tid) * 2;
-                    dst[0] = sa;
-                    dst[1] = sb;
                 }
             }
         }
@@ -2154,6 +2182,8 @@ inline int c64_buf_bytes()
     const int epi = 256 * kC64EpiRowB + 32 * 64 * 2 * (int)sizeof(float);
     return (patch > epi ? patch : epi + 1023) / 1024 * 1024;
 }
+// one persistent workgroup per compute unit = one partial row of column sums per instance
+inline int c64_workgroups(const GatherGeom& g) { const int t = ceil_div(g.M, 256); return t < 256 ? t : 256; }
 template <typename T>
 bool c64_eligible(const GatherGeom& g)
 {
@@ -2217,10 +2247,8 @@ int run_c64(const GatherGeom& g, const void* in, const void* w, void* out, hipSt
     C64Args a{};
     a.buf_bytes = c64_buf_bytes();
     a.tiles = ceil_div(g.M, 256);
-    a.total_tiles = a.tiles * (g.in1 ? 2 : 1);
-    const int wgs = a.total_tiles < 256 ? a.total_tiles : 256;  // one persistent workgroup per compute unit
-    a.tiles_per_wg = ceil_div(a.total_tiles, wgs);
-    const int grid = ceil_div(a.total_tiles, a.tiles_per_wg);
+    a.twin = g.in1 ? 1 : 0;
+    const int grid = c64_workgroups(g);
     const int lds = kC64Zero + 2 * a.buf_bytes;
     auto kern = g.accum ? conv3x3_c64_bf16_kernel<true> : conv3x3_c64_bf16_kernel<false>;
     static std::atomic<bool> attr_done{false};
@@ -2266,7 +2294,8 @@ int dispatch_gather(GatherGeom g, bool accum, const void* in, const void* w, voi
     if (id == 21) {
         const bool aligned = vec && g.out_vec && ((uintptr_t)g.in1 % 16) == 0 && ((uintptr_t)g.out1 % 16) == 0;
         if (aligned) return run_c64(g, in, w, out, st, flops);
-        // unaligned tensors (single-layer calls only) take the register-staged tiles; their row tiles are the same 256
+        // unaligned tensors (single-layer calls only) take the register-staged tiles; their partial rows differ
+        DSP_REQUIRE(g.stats == nullptr, DSP_EINVAL, "conv forward with column sums: x, w and y must be 16-byte aligned");
         id = 10;
     }
     if (id == 20) {
@@ -2603,7 +2632,11 @@ int conv_forward_row_tiles(int dtype, const ConvShape& c)
     const GatherGeom g = forward_geom(c);
     if (dtype == DSP_FP32 && direct_eligible<float>(g, nullptr, nullptr)) return direct_grid(g);
     int bm;
-    if (dtype == DSP_BF16) select_gather_tile<bf16_t>(g, &bm); else select_gather_tile<float>(g, &bm);
+    if (dtype == DSP_BF16) {
+        if (select_gather_tile<bf16_t>(g, &bm) == 21) return c64_workgroups(g);
+    } else {
+        select_gather_tile<float>(g, &bm);
+    }
     return ceil_div(g.M, bm);
 }
 
