@@ -404,6 +404,26 @@ int dsp_bn_backward(int32_t dtype, const void* d_dy, const void* d_x, const void
                     int32_t dres_accumulate, int32_t dx_accumulate, const float* d_gamma, const float* d_mean,
                     const float* d_invstd, float* d_dgamma, float* d_dbeta, int64_t M, int32_t C, int32_t relu,
                     void* d_workspace, size_t workspace_bytes, void* stream);
+/*
+ * The two forms a block uses where a batch norm + ReLU has no residual (same definitions as above, fewer passes over
+ * memory; device pointers throughout, errors as above):
+ * dsp_bn_relu_maxpool_forward -- batch norm + ReLU whose only reader is a max pool (k x k window, k <= 4, -inf padding,
+ *   first maximum wins; bf16 tensors with C % 8 == 0 only, else DSP_EINVAL): d_pool[N][Ho][Wo][C] and d_argmax (one byte
+ *   per output element, r * k + s) are the bits dsp_bn_forward(relu = 1) followed by dsp_maxpool_forward leave; the
+ *   normalised tensor itself is never written.  d_scale_shift (2 * C floats, 16-byte aligned) receives the per-channel
+ *   {scale[C], shift[C]} the output was formed with: y = relu(round(fma(x, scale, shift))).
+ * dsp_bn_relu_backward_from_x -- dsp_bn_backward(relu = 1, no residual) without reading y: the ReLU decision [y > 0] is
+ *   taken by forming y from x and the forward pass's d_scale_shift again, with the forward kernel's own expression and
+ *   rounding, so dx, dgamma and dbeta are the bits dsp_bn_backward leaves when given the stored y.
+ */
+int dsp_bn_relu_maxpool_forward(int32_t dtype, const void* d_x, const float* d_gamma, const float* d_beta, float eps, int32_t N,
+                                int32_t H, int32_t W, int32_t C, int32_t k, int32_t stride, int32_t pad, void* d_pool,
+                                uint8_t* d_argmax, float* d_mean, float* d_invstd, float* d_scale_shift, void* d_workspace,
+                                size_t workspace_bytes, void* stream);
+int dsp_bn_relu_backward_from_x(int32_t dtype, const void* d_dy, const void* d_x, const float* d_scale_shift, void* d_dx,
+                                int32_t dx_accumulate, const float* d_gamma, const float* d_mean, const float* d_invstd,
+                                float* d_dgamma, float* d_dbeta, int64_t M, int32_t C, void* d_workspace, size_t workspace_bytes,
+                                void* stream);
 /* k x k max pool (padding = -inf, the first maximum in row-major window order wins); d_argmax keeps one
  * byte per output element (window position r*k+s); backward: dx (+)= the dy of every window that chose the pixel. */
 int dsp_maxpool_forward(int32_t dtype, const void* d_x, void* d_y, uint8_t* d_argmax, int32_t N, int32_t H, int32_t W,

@@ -82,6 +82,10 @@ struct Layer {
     size_t wt_off = 0;      // offset of the backward-data filter copy
     float* mean = nullptr;
     float* invstd = nullptr;
+    // bn whose only reader is the max pool right behind it (pool_fused), and that pool (bn_fused = the bn's index): the
+    // pool kernel forms the batch norm's output on the fly, which is then never stored
+    bool pool_fused = false;
+    int bn_fused = -1;
     float* fcoef = nullptr;  // bn: {scale[C], shift[C]} of the last forward pass over the primary buffers (the backward sweep decides the ReLU with them)
     uint8_t* argmax = nullptr;
     bool in0_grad = true;  // form the gradient w.r.t. in0
@@ -345,6 +349,15 @@ static int build_graph(dsp_block* b)
             consumers[L.d.in0 + 1].push_back({i, 0});
             if ((L.d.op == DSP_OP_BN && L.d.in1 != -2) || L.d.op == DSP_OP_ADD) consumers[L.d.in1 + 1].push_back({i, 1});
         }
+        for (int i = 0; i + 1 < d.n_layers; ++i) {
+            Layer& L = b->layers[i];
+            Layer& nx = b->layers[i + 1];
+            if (L.d.op == DSP_OP_BN && L.d.relu && L.d.in1 == -2 && i != b->out_idx && L.d.in0 >= 0 && nx.d.op == DSP_OP_MAXPOOL &&
+                nx.d.in0 == i && consumers[i + 1].size() == 1 && bn_relu_maxpool_supported(b->dtype, L.d.cin, nx.d.r)) {
+                L.pool_fused = true;
+                nx.bn_fused = i;
+            }
+        }
         for (int i = 0; i < d.n_layers; ++i) {
             Layer& L = b->layers[i];
             if (L.d.op != DSP_OP_ADD || L.d.in0 == L.d.in1) continue;
@@ -480,7 +493,7 @@ static int build_graph(dsp_block* b)
         Layer& L = b->layers[i];
         Tensor& t = b->T[i];
         if (L.d.op == DSP_OP_SOFTMAX_CE) continue;
-        DSP_TRY(dev_alloc(b, &t.act, t.bytes(b->dtype), &b->ws_bytes));
+        if (!L.pool_fused) DSP_TRY(dev_alloc(b, &t.act, t.bytes(b->dtype), &b->ws_bytes));
         if (i != b->out_idx || b->loss_idx >= 0) DSP_TRY(dev_alloc(b, &t.grad, t.bytes(b->dtype), &b->ws_bytes));
         if (L.d.op == DSP_OP_BN) {
             DSP_TRY(dev_alloc(b, (void**)&L.mean, (size_t)L.d.cin * 4, &b->ws_bytes));
@@ -618,7 +631,7 @@ static int run_forward(dsp_block* b, const ForwardPass& P, const ForwardPass* tw
                                    bn_buffers(*twin)};
             DSP_TRY(launch_bn_forward(b->dtype, src_of(P, L.d.in0), L.d.in1 == -2 ? nullptr : src_of(P, L.d.in1),
                                       act_of(P, i), b->x + L.p0, b->x + L.p1, b->desc.bn_eps, (int64_t)s.N * s.H * s.W, s.C,
-                                      L.d.relu != 0, bn_buffers(P), st, L.sum_tiles, twin ? &tw : nullptr));
+                                      L.d.relu != 0, bn_buffers(P), st, L.sum_tiles, twin ? &tw : nullptr, L.pool_fused));
             break;
         }
         case DSP_OP_ADD:
@@ -638,8 +651,16 @@ static int run_forward(dsp_block* b, const ForwardPass& P, const ForwardPass* tw
         case DSP_OP_MAXPOOL:
             for (int q = 0; q < passes; ++q) {
                 const ForwardPass& p = q ? *twin : P;
-                DSP_TRY(launch_maxpool_forward(b->dtype, src_of(p, L.d.in0), act_of(p, i), p.lane ? p.lane->argmax[i] : L.argmax,
-                                               s.N, s.H, s.W, s.C, L.d.r, L.d.stride, L.d.pad, st));
+                uint8_t* am = p.lane ? p.lane->argmax[i] : L.argmax;
+                if (L.bn_fused >= 0) {
+                    // the batch norm in front left only its coefficients (no other batch norm has run since)
+                    const Layer& B = b->layers[L.bn_fused];
+                    DSP_TRY(launch_bn_relu_maxpool_forward(b->dtype, src_of(p, B.d.in0), p.lane ? p.lane->bn_coef : B.fcoef, act_of(p, i),
+                                                           am, s.N, s.H, s.W, s.C, L.d.r, L.d.stride, L.d.pad, st));
+                    continue;
+                }
+                DSP_TRY(launch_maxpool_forward(b->dtype, src_of(p, L.d.in0), act_of(p, i), am, s.N, s.H, s.W, s.C, L.d.r, L.d.stride,
+                                               L.d.pad, st));
             }
             break;
         case DSP_OP_GAP:
@@ -822,7 +843,7 @@ int dsp_block_enable_forward_lane(dsp_block* b)
         const Layer& L = b->layers[i];
         const Tensor& t = b->T[i];
         if (L.d.op == DSP_OP_SOFTMAX_CE) continue;
-        rc = dev_alloc(b, &ln->act[i], t.bytes(b->dtype), &b->ws_bytes);
+        if (!L.pool_fused) rc = dev_alloc(b, &ln->act[i], t.bytes(b->dtype), &b->ws_bytes);
         if (rc == DSP_OK && L.d.op == DSP_OP_BN) {
             rc = dev_alloc(b, (void**)&ln->mean[i], (size_t)L.d.cin * 4, &b->ws_bytes);
             if (rc == DSP_OK) rc = dev_alloc(b, (void**)&ln->invstd[i], (size_t)L.d.cin * 4, &b->ws_bytes);
@@ -1079,10 +1100,23 @@ int dsp_block_get_activation(dsp_block* b, int32_t layer, void* h_dst, size_t by
 {
     DSP_REQUIRE(b && h_dst && layer >= 0 && layer < (int)b->layers.size(), DSP_EINVAL, "dsp_block_get_activation: bad argument");
     const Tensor& t = b->T[layer];
-    DSP_REQUIRE(t.act != nullptr, DSP_EINVAL, "dsp_block_get_activation: layer %d keeps no output", (int)layer);
+    const Layer& L = b->layers[layer];
+    DSP_REQUIRE(t.act != nullptr || L.pool_fused, DSP_EINVAL, "dsp_block_get_activation: layer %d keeps no output", (int)layer);
     DSP_REQUIRE(bytes == t.bytes(b->dtype), DSP_EINVAL, "dsp_block_get_activation: layer %d holds %zu bytes, not %zu", (int)layer,
                 t.bytes(b->dtype), bytes);
     DSP_HIP(hipDeviceSynchronize());
+    if (L.pool_fused) {
+        // the pool kernel formed this output on the fly; it is written out here, from the stored input and the forward
+        // pass's coefficients, by the kernel that stores it where the two layers run apart
+        const Tensor& s = b->T[L.d.in0];
+        void* tmp = nullptr;
+        DSP_HIP(hipMalloc(&tmp, bytes));
+        int rc = launch_bn_apply(b->dtype, s.act, tmp, L.fcoef, (int64_t)s.N * s.H * s.W, s.C, true, nullptr);
+        if (rc == DSP_OK && hipDeviceSynchronize() != hipSuccess) rc = DSP_EHIP;
+        if (rc == DSP_OK && hipMemcpy(h_dst, tmp, bytes, hipMemcpyDeviceToHost) != hipSuccess) rc = DSP_EHIP;
+        (void)hipFree(tmp);
+        return rc;
+    }
     DSP_HIP(hipMemcpy(h_dst, t.act, bytes, hipMemcpyDeviceToHost));
     return DSP_OK;
 }

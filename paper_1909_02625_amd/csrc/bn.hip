@@ -18,6 +18,9 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kMaxPartialBlocks = 512;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 // Layout of a workgroup over x[M][C]: CV channel vectors per row, RL row lanes.
 struct RowLayout {
@@ -322,6 +325,92 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(const T* __restr
     }
 }
 
+// ---- batch norm + ReLU + max pool in one pass (bf16) ---------------------------------------------------------
+// For a batch norm whose only reader is a max pool: y = relu(scale * x + shift) is formed per window tap exactly as
+// bn_fwd_apply_kernel would store it (same expression, same rounding) and never written; the pooled tensor and the
+// chosen taps are the same bits the two separate kernels leave.  After the ReLU every value is a non-negative bf16, so
+// values order like their bit patterns: per channel the kernel keeps one 32-bit key = value bits << 16 | (15 - tap) and
+// takes the unsigned maximum, which is the largest value and, among equal ones, the first tap of the row-major window
+// scan (the rule of maxpool_fwd_kernel).  A thread owns 8 consecutive channels of one output pixel; all taps of a
+// window are loaded before the first is used (out-of-image taps read a clamped address and are masked out).
+// Workgroup ids are dealt round-robin to the 8 XCDs; the remap gives each XCD one contiguous eighth of the output per
+// grid-stride trip, so the input rows two neighbouring output rows share are fetched into one L2, once.
+template <int K>
+__global__ __launch_bounds__(kThreads) void bn_relu_maxpool_bf16_kernel(const bf16_t* __restrict__ x,
+                                                                        const float* __restrict__ coef,
+                                                                        bf16_t* __restrict__ y, uint8_t* __restrict__ arg,
+                                                                        int N, int H, int W, int C, int Ho, int Wo, int k_rt,
+                                                                        int stride, int pad)
+{
+    const int k = K ? K : k_rt;
+    const uint32_t cv = (uint32_t)(C / 8);
+    const uint32_t total = (uint32_t)N * Ho * Wo * cv;
+    const uint32_t nb = gridDim.x, lb = (blockIdx.x & 7u) * (nb >> 3) + (blockIdx.x >> 3);
+    for (uint32_t i = lb * kThreads + threadIdx.x; i < total; i += nb * kThreads) {
+        const uint32_t t = i / cv;
+        const int c = (int)(i - t * cv) * 8;
+        const uint32_t t2 = t / (uint32_t)Wo;
+        const int wo = (int)(t - t2 * Wo);
+        const int n = (int)(t2 / (uint32_t)Ho), ho = (int)(t2 - (uint32_t)n * Ho);
+        float sc[8], sh[8];
+#pragma unroll
+        for (int e = 0; e < 8; e += 4) {
+            const f32x4 a = *(const f32x4*)(coef + c + e), b = *(const f32x4*)(coef + C + c + e);
+            sc[e] = a.x; sc[e + 1] = a.y; sc[e + 2] = a.z; sc[e + 3] = a.w;
+            sh[e] = b.x; sh[e + 1] = b.y; sh[e + 2] = b.z; sh[e + 3] = b.w;
+        }
+        uint32_t key[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) key[e] = 0u;
+        auto tap = [&](int r, int s, u32x4 v) {
+            const int hi = ho * stride + r - pad, wi = wo * stride + s - pad;
+            const bool valid = (unsigned)hi < (unsigned)H && (unsigned)wi < (unsigned)W;
+            const uint32_t code = (uint32_t)(15 - (r * k + s));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float lo = __builtin_fmaf(__uint_as_float(v[e] << 16), sc[2 * e], sh[2 * e]);
+                float hi2 = __builtin_fmaf(__uint_as_float(v[e] & 0xffff0000u), sc[2 * e + 1], sh[2 * e + 1]);
+                lo = lo > 0.f ? lo : 0.f;
+                hi2 = hi2 > 0.f ? hi2 : 0.f;
+                const uint32_t pk = pack_bf16x2(lo, hi2);
+                const uint32_t k0 = valid ? ((pk << 16) | code) : 0u, k1 = valid ? ((pk & 0xffff0000u) | code) : 0u;
+                key[2 * e] = key[2 * e] > k0 ? key[2 * e] : k0;
+                key[2 * e + 1] = key[2 * e + 1] > k1 ? key[2 * e + 1] : k1;
+            }
+        };
+        auto addr = [&](int r, int s) {
+            int hi = ho * stride + r - pad, wi = wo * stride + s - pad;
+            hi = hi < 0 ? 0 : (hi >= H ? H - 1 : hi);
+            wi = wi < 0 ? 0 : (wi >= W ? W - 1 : wi);
+            return (const u32x4*)(x + (((int64_t)n * H + hi) * W + wi) * C + c);
+        };
+        if (K) {
+            u32x4 v[K ? K * K : 1];
+#pragma unroll
+            for (int r = 0; r < K; ++r)
+#pragma unroll
+                for (int s = 0; s < K; ++s) v[r * K + s] = *addr(r, s);
+#pragma unroll
+            for (int r = 0; r < K; ++r)
+#pragma unroll
+                for (int s = 0; s < K; ++s) tap(r, s, v[r * K + s]);
+        } else {
+            for (int r = 0; r < k; ++r)
+                for (int s = 0; s < k; ++s) tap(r, s, *addr(r, s));
+        }
+        u32x4 o;
+        uint32_t a0 = 0u, a1 = 0u;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            o[e] = (key[2 * e] >> 16) | (key[2 * e + 1] & 0xffff0000u);
+            a0 |= (15u - (key[e] & 15u)) << (8 * e);
+            a1 |= (15u - (key[4 + e] & 15u)) << (8 * e);
+        }
+        *(u32x4*)(y + (int64_t)i * 8) = o;
+        if (arg) *(u32x2*)(arg + (int64_t)i * 8) = u32x2{a0, a1};
+    }
+}
+
 int plan_rows(int64_t M, const RowLayout& L, int* nblk)
 {
     // every thread should see >= 4 rows (one trip of the summing loop); at most kMaxPartialBlocks workgroups
@@ -345,7 +434,7 @@ inline int apply_grid(int64_t nvec)
 
 template <typename T, int VW>
 int bn_forward_t(const void* x, const void* res, void* y, const float* gamma, const float* beta, float eps, int64_t M,
-                 int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed, const BnForwardTwin* tw)
+                 int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed, const BnForwardTwin* tw, bool stats_only)
 {
     const RowLayout L = make_layout(C, VW);
     int nblk;
@@ -367,6 +456,10 @@ int bn_forward_t(const void* x, const void* res, void* y, const float* gamma, co
         ProfScope ps("bn_fwd_finalize", (double)nblk * C * 16.0 * ni, 1);
         DSP_LAUNCH(ps, bn_fwd_finalize_kernel, dim3(ceil_div(C, 4), ni), dim3(kMergeLanes * 4), 0, st, o0, o1, nblk, C,
                    1.0 / (double)M, eps, gamma, beta);
+    }
+    if (stats_only) {
+        DSP_HIP(hipGetLastError());
+        return DSP_OK;
     }
     const int64_t nvec = M * (C / VW);
     const dim3 ag(apply_grid(nvec), ni);
@@ -474,18 +567,67 @@ int launch_add_forward_stats(int dtype, const void* a, const void* b, void* y, i
 
 int launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
                       float eps, int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed,
-                      const BnForwardTwin* twin)
+                      const BnForwardTwin* twin, bool stats_only)
 {
     DSP_REQUIRE(M > 0 && C > 0 && presummed >= 0, DSP_EINVAL, "bn: bad shape");
     if (twin)
-        DSP_REQUIRE(twin->x && twin->y && (twin->res != nullptr) == (res != nullptr), DSP_EINVAL,
+        DSP_REQUIRE(twin->x && (twin->y || stats_only) && (twin->res != nullptr) == (res != nullptr), DSP_EINVAL,
                     "bn forward: incomplete second instance");
     if (dtype == DSP_BF16) {
-        if (C % 8 == 0) return bn_forward_t<bf16_t, 8>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin);
-        return bn_forward_t<bf16_t, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin);
+        if (C % 8 == 0) return bn_forward_t<bf16_t, 8>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin, stats_only);
+        return bn_forward_t<bf16_t, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin, stats_only);
     }
-    if (C % 4 == 0) return bn_forward_t<float, 4>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin);
-    return bn_forward_t<float, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin);
+    if (C % 4 == 0) return bn_forward_t<float, 4>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin, stats_only);
+    return bn_forward_t<float, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin, stats_only);
+}
+
+int launch_bn_apply(int dtype, const void* x, void* y, const float* coef, int64_t M, int C, bool relu, hipStream_t st)
+{
+    DSP_REQUIRE(M > 0 && C > 0 && x && y && coef, DSP_EINVAL, "bn apply: bad argument");
+    const BnApplyIo io{x, nullptr, y, coef};
+    const double bytes = (double)M * C * dtype_size(dtype) * 2;
+#define BN_APPLY1(T, VW)                                                                                               \
+    do {                                                                                                               \
+        const int64_t nvec = M * (C / VW);                                                                             \
+        ProfScope ps(sizeof(T) == 2 ? "bn_apply_relu<bf16>" : "bn_apply_relu<fp32>", bytes, 1);                        \
+        if (relu) DSP_LAUNCH(ps, (bn_fwd_apply_kernel<T, VW, true, false>), dim3(apply_grid(nvec)), dim3(kThreads), 0, st, io, io, nvec, C, C / VW); \
+        else DSP_LAUNCH(ps, (bn_fwd_apply_kernel<T, VW, false, false>), dim3(apply_grid(nvec)), dim3(kThreads), 0, st, io, io, nvec, C, C / VW);    \
+    } while (0)
+    if (dtype == DSP_BF16) {
+        if (C % 8 == 0) BN_APPLY1(bf16_t, 8); else BN_APPLY1(bf16_t, 1);
+    } else {
+        if (C % 4 == 0) BN_APPLY1(float, 4); else BN_APPLY1(float, 1);
+    }
+#undef BN_APPLY1
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
+bool bn_relu_maxpool_supported(int dtype, int C, int k) { return dtype == DSP_BF16 && C % 8 == 0 && k >= 1 && k <= 4; }
+
+int launch_bn_relu_maxpool_forward(int dtype, const void* x, const float* coef, void* y, uint8_t* argmax, int N, int H, int W,
+                                   int C, int k, int stride, int pad, hipStream_t st)
+{
+    DSP_REQUIRE(bn_relu_maxpool_supported(dtype, C, k), DSP_EINVAL, "bn + relu + max pool: bf16, channels in runs of 8, window <= 4 x 4");
+    DSP_REQUIRE(x && coef && y && N > 0 && stride >= 1 && pad >= 0 && pad < k && H + 2 * pad >= k && W + 2 * pad >= k, DSP_EINVAL,
+                "bn + relu + max pool: bad argument");
+    DSP_REQUIRE((int64_t)N * H * W * C < (1ll << 31), DSP_EINVAL, "bn + relu + max pool: tensors of 2^31 elements or more are not supported");
+    DSP_REQUIRE(((uintptr_t)x % 16) == 0 && ((uintptr_t)y % 16) == 0 && ((uintptr_t)argmax % 8) == 0 && ((uintptr_t)coef % 16) == 0,
+                DSP_EINVAL, "bn + relu + max pool: unaligned tensor");
+    const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
+    const int64_t total = (int64_t)N * Ho * Wo * (C / 8);
+    int64_t grid = (total + kThreads - 1) / kThreads;
+    grid = (grid + 7) / 8 * 8;
+    if (grid > 256 * 32) grid = 256 * 32;
+    ProfScope ps("bn_relu_maxpool_fwd<bf16>", ((double)N * H * W * C + (double)N * Ho * Wo * C) * 2.0 + (double)N * Ho * Wo * C, 1);
+    if (k == 3)
+        DSP_LAUNCH(ps, (bn_relu_maxpool_bf16_kernel<3>), dim3((unsigned)grid), dim3(kThreads), 0, st, (const bf16_t*)x, coef, (bf16_t*)y,
+                   argmax, N, H, W, C, Ho, Wo, k, stride, pad);
+    else
+        DSP_LAUNCH(ps, (bn_relu_maxpool_bf16_kernel<0>), dim3((unsigned)grid), dim3(kThreads), 0, st, (const bf16_t*)x, coef, (bf16_t*)y,
+                   argmax, N, H, W, C, Ho, Wo, k, stride, pad);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
 }
 
 int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, void* dx, void* dres,

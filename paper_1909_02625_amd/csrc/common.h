@@ -221,7 +221,15 @@ struct BnForwardTwin {
 };
 int launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
                       float eps, int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed = 0,
-                      const BnForwardTwin* twin = nullptr);
+                      const BnForwardTwin* twin = nullptr, bool stats_only = false);
+// stats_only: mean, invstd and buf.coef = {scale[C], shift[C]} only; y is not written (may be nullptr).  The two calls
+// below finish such a layer: launch_bn_apply writes y = [relu](scale * x + shift) from those coefficients, and
+// launch_bn_relu_maxpool_forward (bf16, C % 8 == 0, window k <= 4: bn_relu_maxpool_supported) writes the max pool of that
+// y and the chosen taps without storing y -- the same bits launch_bn_apply + launch_maxpool_forward leave.
+int launch_bn_apply(int dtype, const void* x, void* y, const float* coef, int64_t M, int C, bool relu, hipStream_t st);
+bool bn_relu_maxpool_supported(int dtype, int C, int k);
+int launch_bn_relu_maxpool_forward(int dtype, const void* x, const float* coef, void* y, uint8_t* argmax, int N, int H, int W,
+                                   int C, int k, int stride, int pad, hipStream_t st);
 // y = a + b over [M][C] (as launch_add_forward) and, in the same pass, the per-block column sums {sum y, sum y^2}
 // of the stored values in partial[add_stats_blocks()][C][2]: exactly what launch_bn_forward(y, ...) would compute
 // first, so the batch norm that reads y is called with presummed = add_stats_blocks().  twin: a second instance.

@@ -56,6 +56,41 @@ int dsp_bn_backward(int32_t dtype, const void* d_dy, const void* d_x, const void
                               d_dbeta, M, C, relu != 0, buf, (hipStream_t)stream);
 }
 
+int dsp_bn_relu_backward_from_x(int32_t dtype, const void* d_dy, const void* d_x, const float* d_scale_shift, void* d_dx,
+                                int32_t dx_accumulate, const float* d_gamma, const float* d_mean, const float* d_invstd,
+                                float* d_dgamma, float* d_dbeta, int64_t M, int32_t C, void* d_workspace, size_t workspace_bytes,
+                                void* stream)
+{
+    DSP_REQUIRE(dtype_ok(dtype) && d_dy && d_x && d_scale_shift && d_dx && d_gamma && d_mean && d_invstd && d_dgamma && d_dbeta &&
+                    d_workspace, DSP_EINVAL, "dsp_bn_relu_backward_from_x: bad argument");
+    DSP_REQUIRE(M > 0 && C > 0 && M * (int64_t)C < (1ll << 31), DSP_EINVAL, "dsp_bn_relu_backward_from_x: bad shape");
+    DSP_REQUIRE(workspace_bytes >= bn_ws_bytes(C) && ((uintptr_t)d_workspace % 16) == 0, DSP_EINVAL,
+                "dsp_bn_relu_backward_from_x: workspace too small or not 16-byte aligned (%zu < %zu)", workspace_bytes, bn_ws_bytes(C));
+    BnBuffers buf{(double*)d_workspace, const_cast<float*>(d_mean), const_cast<float*>(d_invstd),
+                  (float*)((char*)d_workspace + bn_partial_bytes(C))};
+    return launch_bn_backward(dtype, d_dy, d_x, nullptr, d_dx, nullptr, false, dx_accumulate != 0, d_gamma, d_dgamma, d_dbeta, M, C,
+                              true, buf, (hipStream_t)stream, nullptr, d_scale_shift);
+}
+
+int dsp_bn_relu_maxpool_forward(int32_t dtype, const void* d_x, const float* d_gamma, const float* d_beta, float eps, int32_t N,
+                                int32_t H, int32_t W, int32_t C, int32_t k, int32_t stride, int32_t pad, void* d_pool,
+                                uint8_t* d_argmax, float* d_mean, float* d_invstd, float* d_scale_shift, void* d_workspace,
+                                size_t workspace_bytes, void* stream)
+{
+    DSP_REQUIRE(dtype_ok(dtype) && d_x && d_gamma && d_beta && d_pool && d_argmax && d_mean && d_invstd && d_scale_shift && d_workspace,
+                DSP_EINVAL, "dsp_bn_relu_maxpool_forward: bad argument");
+    DSP_REQUIRE(N > 0 && H > 0 && W > 0 && C > 0 && eps > 0.f && k > 0 && stride > 0 && pad >= 0 && pad < k && H + 2 * pad >= k &&
+                    W + 2 * pad >= k && (int64_t)N * H * W * C < (1ll << 31), DSP_EINVAL, "dsp_bn_relu_maxpool_forward: bad shape");
+    DSP_REQUIRE(bn_relu_maxpool_supported(dtype, C, k), DSP_EINVAL,
+                "dsp_bn_relu_maxpool_forward: bf16 tensors with channels in runs of 8 and windows up to 4 x 4 only");
+    DSP_REQUIRE(workspace_bytes >= bn_ws_bytes(C) && ((uintptr_t)d_workspace % 16) == 0 && ((uintptr_t)d_scale_shift % 16) == 0,
+                DSP_EINVAL, "dsp_bn_relu_maxpool_forward: workspace too small, or workspace / d_scale_shift not 16-byte aligned");
+    BnBuffers buf{(double*)d_workspace, d_mean, d_invstd, d_scale_shift};
+    DSP_TRY(launch_bn_forward(dtype, d_x, nullptr, nullptr, d_gamma, d_beta, eps, (int64_t)N * H * W, C, true, buf,
+                              (hipStream_t)stream, 0, nullptr, /*stats_only=*/true));
+    return launch_bn_relu_maxpool_forward(dtype, d_x, d_scale_shift, d_pool, d_argmax, N, H, W, C, k, stride, pad, (hipStream_t)stream);
+}
+
 int dsp_maxpool_forward(int32_t dtype, const void* d_x, void* d_y, uint8_t* d_argmax, int32_t N, int32_t H, int32_t W,
                         int32_t C, int32_t k, int32_t stride, int32_t pad, void* stream)
 {

@@ -107,6 +107,83 @@ def test_batch_norm_forward_and_backward(shape, dtype, relu, res):
             assert rel_err(from_dev(d_dr2, shape), dr0 + g) < (1e-6 if dtype == D.DSP_FP32 else 4e-3)
 
 
+FUSED_SHAPES = [  # (N, C, H, W, k, stride, pad)
+    (2, 16, 9, 9, 3, 2, 1),       # odd map: windows cut by every border
+    (3, 24, 8, 10, 2, 2, 0),      # 2 x 2 windows, no padding, three channel vectors
+    (2, 64, 7, 5, 3, 1, 1),       # overlapping stride-1 windows
+    (2, 8, 6, 6, 4, 2, 1),        # the largest window the tap code holds
+    (16, 64, 112, 112, 3, 2, 1),  # ResNet-18 stem at 1/16 of its batch: several grid-stride trips per workgroup
+]
+
+
+@pytest.mark.parametrize("shape", FUSED_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_bn_relu_maxpool_in_one_pass_and_relu_decided_from_x(shape):
+    """The two forms a block uses for a batch norm + ReLU without residual: the pool that forms the normalised tensor on
+    the fly, and the backward pass that takes the ReLU decision from x.  Both must leave the very bits of the separate
+    kernels (which the tests above check against the oracle), so the comparison is bit for bit; on top, the pooled
+    tensor is checked against the oracle's layers on the same stored input."""
+    N, C, H, W, k, st, pd = shape
+    dtype = D.DSP_BF16
+    rng = np.random.default_rng(11 * C + H + k)
+    M = N * H * W
+    x = round_like(rng.standard_normal((N, C, H, W)) * 1.5 + 0.3, dtype)
+    gamma = (1.0 + 0.25 * rng.standard_normal(C)).astype(np.float32)
+    gamma[::5] *= -1.0            # decreasing channels as well
+    beta = (0.25 * rng.standard_normal(C)).astype(np.float32)
+    beta[1::7] = -3.0             # channels the ReLU zeroes almost everywhere: windows full of ties
+    ws_bytes = D.dsp_bn_workspace_bytes(C)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    d_x, d_gamma, d_beta = to_dev(x, dtype), _dev_f32(gamma), _dev_f32(beta)
+    d_y = torch.full((M * C,), float("nan"), device="cuda", dtype=torch.bfloat16)
+    d_mean, d_invstd = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
+    D.dsp_bn_forward(dtype, d_x, None, d_y, d_gamma, d_beta, EPS, M, C, True, d_mean, d_invstd, ws, ws_bytes)
+    Ho, Wo = (H + 2 * pd - k) // st + 1, (W + 2 * pd - k) // st + 1
+    n_out = N * Ho * Wo * C
+    d_p = torch.full((n_out,), float("nan"), device="cuda", dtype=torch.bfloat16)
+    d_a = torch.full((n_out,), 255, device="cuda", dtype=torch.uint8)
+    D.dsp_maxpool_forward(dtype, d_y, d_p, d_a, N, H, W, C, k, st, pd)
+
+    d_p2 = torch.full((n_out,), float("nan"), device="cuda", dtype=torch.bfloat16)
+    d_a2 = torch.full((n_out,), 255, device="cuda", dtype=torch.uint8)
+    d_mean2, d_invstd2 = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
+    d_coef = torch.empty(2 * C, device="cuda")
+    D.dsp_bn_relu_maxpool_forward(dtype, d_x, d_gamma, d_beta, EPS, N, H, W, C, k, st, pd, d_p2, d_a2, d_mean2, d_invstd2, d_coef,
+                                  ws, ws_bytes)
+    torch.cuda.synchronize()
+    assert torch.equal(d_mean, d_mean2) and torch.equal(d_invstd, d_invstd2)
+    assert torch.equal(d_p.view(torch.int16), d_p2.view(torch.int16))
+    assert torch.equal(d_a, d_a2)
+    # against the layers' definitions on the stored input (values: one rounding of the normalised tensor)
+    z, _, _ = O.bn_forward(x, gamma, beta, EPS)
+    p_ref, _ = O.maxpool_forward(np.maximum(z, 0.0), k, st, pd)
+    assert rel_err(from_dev(d_p2, p_ref.shape), p_ref) < 4e-3
+
+    dy = round_like(rng.standard_normal((N, C, H, W)) * 0.1, dtype)
+    d_dy = to_dev(dy, dtype)
+    outs = []
+    for from_x in (False, True):
+        d_dx = torch.full((M * C,), float("nan"), device="cuda", dtype=torch.bfloat16)
+        d_dg, d_db = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
+        if from_x:
+            D.dsp_bn_relu_backward_from_x(dtype, d_dy, d_x, d_coef, d_dx, False, d_gamma, d_mean, d_invstd, d_dg, d_db, M, C, ws, ws_bytes)
+        else:
+            D.dsp_bn_backward(dtype, d_dy, d_x, d_y, d_dx, None, False, False, d_gamma, d_mean, d_invstd, d_dg, d_db, M, C, True,
+                              ws, ws_bytes)
+        torch.cuda.synchronize()
+        outs.append((d_dx.view(torch.int16).clone(), d_dg.clone(), d_db.clone()))
+    for u, v in zip(*outs):
+        assert torch.equal(u, v)
+
+
+def test_bn_relu_maxpool_rejects_what_it_does_not_cover():
+    x = torch.zeros(4096, device="cuda")
+    ws = torch.empty(D.dsp_bn_workspace_bytes(8), dtype=torch.uint8, device="cuda")
+    for args in [(D.DSP_FP32, 8, 3), (D.DSP_BF16, 6, 3), (D.DSP_BF16, 8, 5)]:   # fp32, channels off the 16-byte run, window 5
+        dt, C, k = args
+        with pytest.raises(D.DSPError):
+            D.dsp_bn_relu_maxpool_forward(dt, x, x, x, EPS, 1, 8, 8, C, k, 2, 1, x, x.view(torch.uint8), x, x, x, ws, ws.numel())
+
+
 POOL_SHAPES = [  # (N, C, H, W, k, stride, pad)
     (2, 16, 9, 9, 3, 2, 1),
     (3, 6, 8, 8, 2, 2, 0),       # channel count off the 16-byte run
