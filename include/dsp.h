@@ -415,6 +415,12 @@ int dsp_bn_backward(int32_t dtype, const void* d_dy, const void* d_x, const void
  * dsp_bn_relu_backward_from_x -- dsp_bn_backward(relu = 1, no residual) without reading y: the ReLU decision [y > 0] is
  *   taken by forming y from x and the forward pass's d_scale_shift again, with the forward kernel's own expression and
  *   rounding, so dx, dgamma and dbeta are the bits dsp_bn_backward leaves when given the stored y.
+ * dsp_bn_relu_maxpool_backward -- the backward of dsp_bn_relu_maxpool_forward in two passes over x: the gradient the
+ *   pool hands to each pixel (the sum of d_dpool over the windows whose recorded tap in d_argmax is that pixel, rounded
+ *   to the storage type, as dsp_maxpool_backward stores it) is formed inside the batch-norm kernels instead of being
+ *   stored.  Every masked gradient is the one dsp_maxpool_backward + dsp_bn_backward work on; the per-channel sums are
+ *   taken in another order, so dgamma, dbeta and dx agree with that pair to double-rounding noise (relative 1e-6), not
+ *   bit for bit.  bf16, C % 8 == 0, k = 3, stride = 2, pad = 1, even H and W only, else DSP_EINVAL.
  */
 int dsp_bn_relu_maxpool_forward(int32_t dtype, const void* d_x, const float* d_gamma, const float* d_beta, float eps, int32_t N,
                                 int32_t H, int32_t W, int32_t C, int32_t k, int32_t stride, int32_t pad, void* d_pool,
@@ -424,6 +430,11 @@ int dsp_bn_relu_backward_from_x(int32_t dtype, const void* d_dy, const void* d_x
                                 int32_t dx_accumulate, const float* d_gamma, const float* d_mean, const float* d_invstd,
                                 float* d_dgamma, float* d_dbeta, int64_t M, int32_t C, void* d_workspace, size_t workspace_bytes,
                                 void* stream);
+int dsp_bn_relu_maxpool_backward(int32_t dtype, const void* d_dpool, const uint8_t* d_argmax, const void* d_x,
+                                 const float* d_scale_shift, void* d_dx, int32_t dx_accumulate, const float* d_gamma,
+                                 const float* d_mean, const float* d_invstd, float* d_dgamma, float* d_dbeta, int32_t N, int32_t H,
+                                 int32_t W, int32_t C, int32_t k, int32_t stride, int32_t pad, void* d_workspace,
+                                 size_t workspace_bytes, void* stream);
 /* k x k max pool (padding = -inf, the first maximum in row-major window order wins); d_argmax keeps one
  * byte per output element (window position r*k+s); backward: dx (+)= the dy of every window that chose the pixel. */
 int dsp_maxpool_forward(int32_t dtype, const void* d_x, void* d_y, uint8_t* d_argmax, int32_t N, int32_t H, int32_t W,

@@ -86,6 +86,7 @@ struct Layer {
     // pool kernel forms the batch norm's output on the fly, which is then never stored
     bool pool_fused = false;
     int bn_fused = -1;
+    bool pool_bwd = false;  // such a bn whose backward kernels also form the pool's input gradient on the fly (never stored)
     float* fcoef = nullptr;  // bn: {scale[C], shift[C]} of the last forward pass over the primary buffers (the backward sweep decides the ReLU with them)
     uint8_t* argmax = nullptr;
     bool in0_grad = true;  // form the gradient w.r.t. in0
@@ -356,6 +357,7 @@ static int build_graph(dsp_block* b)
                 nx.d.in0 == i && consumers[i + 1].size() == 1 && bn_relu_maxpool_supported(b->dtype, L.d.cin, nx.d.r)) {
                 L.pool_fused = true;
                 nx.bn_fused = i;
+                L.pool_bwd = L.in0_grad && nx.in0_grad && bn_pool_backward_supported(b->dtype, L.d.cin, b->T[i].H, b->T[i].W, nx.d.r, nx.d.stride, nx.d.pad);
             }
         }
         for (int i = 0; i < d.n_layers; ++i) {
@@ -494,7 +496,7 @@ static int build_graph(dsp_block* b)
         Tensor& t = b->T[i];
         if (L.d.op == DSP_OP_SOFTMAX_CE) continue;
         if (!L.pool_fused) DSP_TRY(dev_alloc(b, &t.act, t.bytes(b->dtype), &b->ws_bytes));
-        if (i != b->out_idx || b->loss_idx >= 0) DSP_TRY(dev_alloc(b, &t.grad, t.bytes(b->dtype), &b->ws_bytes));
+        if ((i != b->out_idx || b->loss_idx >= 0) && !L.pool_bwd) DSP_TRY(dev_alloc(b, &t.grad, t.bytes(b->dtype), &b->ws_bytes));
         if (L.d.op == DSP_OP_BN) {
             DSP_TRY(dev_alloc(b, (void**)&L.mean, (size_t)L.d.cin * 4, &b->ws_bytes));
             DSP_TRY(dev_alloc(b, (void**)&L.invstd, (size_t)L.d.cin * 4, &b->ws_bytes));
@@ -699,9 +701,12 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
         if (L.d.op == DSP_OP_SOFTMAX_CE) continue;
         const Tensor& s = L.d.in0 < 0 ? b->input : b->T[L.d.in0];
         const void* src = L.d.in0 < 0 ? in : b->T[L.d.in0].act;
-        int dyt = i;  // the buffer that holds the gradient of this layer's output
-        while (dyt != b->out_idx && b->grad_alias[dyt] >= 0) dyt = b->grad_alias[dyt];
-        const void* dy = (dyt == b->out_idx) ? gout : b->T[dyt].grad;
+        auto dy_of = [&](int layer) -> const void* {  // the buffer that holds the gradient of a layer's output
+            int t = layer;
+            while (t != b->out_idx && b->grad_alias[t] >= 0) t = b->grad_alias[t];
+            return (t == b->out_idx) ? gout : b->T[t].grad;
+        };
+        const void* dy = dy_of(i);
         switch (L.d.op) {
         case DSP_OP_CONV:
             // per-slice partial sums only; they are summed for all layers after the sweep
@@ -721,10 +726,16 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
                 while (t != b->out_idx && b->grad_alias[t] >= 0) t = b->grad_alias[t];
                 dx_add = (t == b->out_idx) ? gout : b->T[t].grad;
             }
+            PoolGrad pg{};
+            if (L.pool_bwd) {  // dy is the backward of the pool behind this layer, formed inside the kernels
+                const Layer& Pl = b->layers[i + 1];
+                pg = PoolGrad{dy_of(i + 1), Pl.argmax, s.H, s.W, Pl.d.r, Pl.d.stride, Pl.d.pad};
+                dy = nullptr;
+            }
             DSP_TRY(launch_bn_backward(b->dtype, dy, src, b->T[i].act, grad_of(L.d.in0), dres, L.in1_acc, L.in0_acc,
                                        b->x + L.p0, b->g + L.p0, b->g + L.p1, (int64_t)s.N * s.H * s.W, s.C,
                                        L.d.relu != 0, buf, st, dx_add,
-                                       L.d.in1 == -2 ? L.fcoef : nullptr));
+                                       L.d.in1 == -2 ? L.fcoef : nullptr, L.pool_bwd ? &pg : nullptr));
             break;
         }
         case DSP_OP_ADD: {
@@ -742,7 +753,7 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
             break;
         }
         case DSP_OP_MAXPOOL:
-            if (L.in0_grad)
+            if (L.in0_grad && !(L.bn_fused >= 0 && b->layers[L.bn_fused].pool_bwd))
                 DSP_TRY(launch_maxpool_backward(b->dtype, dy, L.argmax, grad_of(L.d.in0), L.in0_acc, s.N, s.H, s.W, s.C,
                                                 L.d.r, L.d.stride, L.d.pad, st));
             break;

@@ -45,6 +45,42 @@ __device__ inline float bn_value(float x, float scale, float shift)
     return to_float<T>(from_float<T>(__builtin_fmaf(x, scale, shift)));
 }
 
+// The tail of the summing kernels: combines the row lanes of each channel vector in a fixed tree (all channels of the
+// vector at once) and writes the workgroup's partial row part_row[c][2].
+template <int VW>
+__device__ inline void combine_row_lanes(const double (&s0)[VW], const double (&s1)[VW], double (&red)[VW][kThreads][2],
+                                         bool active, int rlane, const RowLayout& L, double* __restrict__ part_row, int c0)
+{
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < VW; ++i) {
+        red[i][tid][0] = s0[i];
+        red[i][tid][1] = s1[i];
+    }
+    __syncthreads();
+    int w = 1;
+    while (w < L.rl) w <<= 1;
+    for (w >>= 1; w > 0; w >>= 1) {
+        if (active && rlane < w && rlane + w < L.rl) {
+            const int other = tid + w * L.cvb;
+#pragma unroll
+            for (int i = 0; i < VW; ++i) {
+                red[i][tid][0] += red[i][other][0];
+                red[i][tid][1] += red[i][other][1];
+            }
+        }
+        __syncthreads();
+    }
+    if (active && rlane == 0) {
+#pragma unroll
+        for (int i = 0; i < VW; ++i) {
+            double* dst = part_row + (c0 + i) * 2;
+            dst[0] = red[i][tid][0];
+            dst[1] = red[i][tid][1];
+        }
+    }
+}
+
 // ---- per-channel sums ---------------------------------------------------------------------------
 // MODE 0: s0 = sum x, s1 = sum x^2.
 // MODE 1: dz = dy * [y > 0] (if RM != 0); s0 = sum dz, s1 = sum dz * (x - mean) * invstd.  RM = 1 reads the stored y;
@@ -135,34 +171,7 @@ __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__
             }
         }
     }
-    // combine the row lanes of each channel vector: a fixed tree over the row lanes, all channels of the vector at once
-#pragma unroll
-    for (int i = 0; i < VW; ++i) {
-        red[i][tid][0] = s0[i];
-        red[i][tid][1] = s1[i];
-    }
-    __syncthreads();
-    int w = 1;
-    while (w < L.rl) w <<= 1;
-    for (w >>= 1; w > 0; w >>= 1) {
-        if (active && rlane < w && rlane + w < L.rl) {
-            const int other = tid + w * L.cvb;
-#pragma unroll
-            for (int i = 0; i < VW; ++i) {
-                red[i][tid][0] += red[i][other][0];
-                red[i][tid][1] += red[i][other][1];
-            }
-        }
-        __syncthreads();
-    }
-    if (active && rlane == 0) {
-#pragma unroll
-        for (int i = 0; i < VW; ++i) {
-            double* dst = part + ((int64_t)blockIdx.x * C + c0 + i) * 2;
-            dst[0] = red[i][tid][0];
-            dst[1] = red[i][tid][1];
-        }
-    }
+    combine_row_lanes<VW>(s0, s1, red, active, rlane, L, part + (int64_t)blockIdx.x * C * 2, c0);
 }
 
 // Merging the partials.  The partials of a conv epilogue can be thousands of rows (one per row tile), so a
@@ -411,6 +420,148 @@ __global__ __launch_bounds__(kThreads) void bn_relu_maxpool_bf16_kernel(const bf
     }
 }
 
+// ---- backward of batch norm + ReLU + (3 x 3 / stride 2 / pad 1 max pool) without the pool's input gradient ----------
+// The pool's backward gives input pixel (hi, wi) the sum of the output gradients of the windows whose recorded tap is that
+// pixel.  Seen from a 2 x 2 cell of input pixels (2a + i, 2b + j) only the four windows (a + u, b + v), u, v in {0, 1},
+// can have chosen one of them, each with a fixed tap code r * 3 + s per pixel:
+//     pixel (0,0): window (0,0) tap 4                       pixel (0,1): windows (0,1) tap 3, (0,0) tap 5
+//     pixel (1,0): windows (1,0) tap 1, (0,0) tap 7         pixel (1,1): windows (1,1) tap 0, (1,0) tap 2, (0,1) tap 6, (0,0) tap 8
+// (listed in the order maxpool_bwd_kernel adds them: window rows, then columns, descending).  A thread owns 8 channels
+// of one cell: it loads the four windows' gradients and taps once, forms the four pixels' gradients -- rounded to bf16,
+// the values maxpool_bwd_kernel would have stored -- and goes on with the batch norm's backward for those pixels.  The
+// ReLU is decided from x (RM = 2 of bn_sums_kernel).  Windows past the last row / column do not exist (Ho = H / 2).
+struct PoolCells {
+    const bf16_t* dpool;   // [N][Ho][Wo][C]
+    const uint8_t* arg;    // [N][Ho][Wo][C]
+    int H, W, Ho, Wo;
+    uint32_t wo_mul, wo_sh, ho_mul, ho_sh;  // cell / Wo and (cell / Wo) / Ho by multiplication
+};
+__device__ inline void pool_cell_grad(const PoolCells& p, int n, int a, int b, int c0, int C, float (&g)[4][8])
+{
+    u32x4 gw[4];
+    u32x2 aw[4];
+    bool ok[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int ho = a + (q >> 1), wo = b + (q & 1);
+        ok[q] = ho < p.Ho && wo < p.Wo;
+        const int64_t o = (((int64_t)n * p.Ho + (ho < p.Ho ? ho : a)) * p.Wo + (wo < p.Wo ? wo : b)) * C + c0;
+        gw[q] = *(const u32x4*)(p.dpool + o);
+        aw[q] = *(const u32x2*)(p.arg + o);
+    }
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+        float gq[4];
+        uint32_t tq[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t w = gw[q][v >> 1];
+            gq[q] = __uint_as_float((v & 1) ? (w & 0xffff0000u) : (w << 16));
+            tq[q] = ok[q] ? ((aw[q][v >> 2] >> (8 * (v & 3))) & 0xffu) : 255u;
+        }
+        float s;
+        s = tq[0] == 4u ? gq[0] : 0.f;
+        g[0][v] = to_float<bf16_t>(from_float<bf16_t>(s));
+        s = tq[1] == 3u ? gq[1] : 0.f;
+        if (tq[0] == 5u) s += gq[0];
+        g[1][v] = to_float<bf16_t>(from_float<bf16_t>(s));
+        s = tq[2] == 1u ? gq[2] : 0.f;
+        if (tq[0] == 7u) s += gq[0];
+        g[2][v] = to_float<bf16_t>(from_float<bf16_t>(s));
+        s = tq[3] == 0u ? gq[3] : 0.f;
+        if (tq[2] == 2u) s += gq[2];
+        if (tq[1] == 6u) s += gq[1];
+        if (tq[0] == 8u) s += gq[0];
+        g[3][v] = to_float<bf16_t>(from_float<bf16_t>(s));
+    }
+}
+
+// s0 = sum dz, s1 = sum dz * xhat over the cells of a workgroup (thread = channel vector tid % cv, cell lane tid / cv)
+__global__ __launch_bounds__(kThreads) void bn_pool_bwd_reduce_kernel(const bf16_t* __restrict__ x, PoolCells p,
+                                                                      const float* __restrict__ mean,
+                                                                      const float* __restrict__ invstd,
+                                                                      const float* __restrict__ fcoef,
+                                                                      double* __restrict__ part, uint32_t cells, int C,
+                                                                      RowLayout L, int cells_per_block)
+{
+    __shared__ double red[8][kThreads][2];
+    const int tid = threadIdx.x;
+    const int cvi = blockIdx.y * L.cvb + tid % L.cvb;
+    const int clane = tid / L.cvb;
+    const bool active = clane < L.rl && cvi < L.cv;
+    const int c0 = cvi * 8;
+    double s0[8], s1[8];
+    float mu[8], is[8], fsc[8], fsh[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        s0[i] = s1[i] = 0.0;
+        if (active) {
+            mu[i] = mean[c0 + i];
+            is[i] = invstd[c0 + i];
+            fsc[i] = fcoef[c0 + i];
+            fsh[i] = fcoef[C + c0 + i];
+        }
+    }
+    const uint32_t c_begin = blockIdx.x * (uint32_t)cells_per_block;
+    const uint32_t c_end = c_begin + cells_per_block < cells ? c_begin + cells_per_block : cells;
+    if (active)
+        for (uint32_t cell = c_begin + clane; cell < c_end; cell += L.rl) {
+            const uint32_t t2 = fast_div(cell, p.wo_mul, p.wo_sh);
+            const int b = (int)(cell - t2 * p.Wo);
+            const int n = (int)fast_div(t2, p.ho_mul, p.ho_sh), a = (int)(t2 - (uint32_t)n * p.Ho);
+            const bf16_t* x0 = x + (((int64_t)n * p.H + 2 * a) * p.W + 2 * b) * C + c0;
+            float xv[4][8], g[4][8];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) VecIO<bf16_t, 8>::load(x0 + ((int64_t)(q >> 1) * p.W + (q & 1)) * C, xv[q]);
+            pool_cell_grad(p, n, a, b, c0, C, g);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float dz = bn_value<bf16_t>(xv[q][i], fsc[i], fsh[i]) > 0.f ? g[q][i] : 0.f;
+                    s0[i] += (double)dz;
+                    s1[i] += (double)(dz * ((xv[q][i] - mu[i]) * is[i]));
+                }
+        }
+    combine_row_lanes<8>(s0, s1, red, active, clane, L, part + (int64_t)blockIdx.x * C * 2, c0);
+}
+
+// dx = [dx_prev +] c1*dz - c2*x + c0 for the four pixels of a cell; item i = (cell i / cv, channel vector i % cv)
+template <bool DX_ACC>
+__global__ __launch_bounds__(kThreads) void bn_pool_bwd_apply_kernel(const bf16_t* __restrict__ x, PoolCells p, bf16_t* dx,
+                                                                     const bf16_t* dx_prev, const float* __restrict__ coef,
+                                                                     const float* __restrict__ fcoef, uint32_t items, int C,
+                                                                     uint32_t cv, uint32_t cv_mul, uint32_t cv_sh)
+{
+    const uint32_t nb = gridDim.x, lb = (blockIdx.x & 7u) * (nb >> 3) + (blockIdx.x >> 3);  // an XCD walks neighbouring cells
+    for (uint32_t i = lb * kThreads + threadIdx.x; i < items; i += nb * kThreads) {
+        const uint32_t cell = fast_div(i, cv_mul, cv_sh);
+        const int c0 = (int)(i - cell * cv) * 8;
+        const uint32_t t2 = fast_div(cell, p.wo_mul, p.wo_sh);
+        const int b = (int)(cell - t2 * p.Wo);
+        const int n = (int)fast_div(t2, p.ho_mul, p.ho_sh), a = (int)(t2 - (uint32_t)n * p.Ho);
+        const int64_t o0 = (((int64_t)n * p.H + 2 * a) * p.W + 2 * b) * C + c0;
+        float xv[4][8], g[4][8], ov[4][8];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int64_t o = o0 + ((int64_t)(q >> 1) * p.W + (q & 1)) * C;
+            VecIO<bf16_t, 8>::load(x + o, xv[q]);
+            if (DX_ACC) VecIO<bf16_t, 8>::load(dx_prev + o, ov[q]);
+        }
+        pool_cell_grad(p, n, a, b, c0, C, g);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const float dz = bn_value<bf16_t>(xv[q][k], fcoef[c0 + k], fcoef[C + c0 + k]) > 0.f ? g[q][k] : 0.f;
+                const float d = coef[c0 + k] * dz - coef[C + c0 + k] * xv[q][k] + coef[2 * C + c0 + k];
+                ov[q][k] = DX_ACC ? ov[q][k] + d : d;
+            }
+            VecIO<bf16_t, 8>::store(dx + o0 + ((int64_t)(q >> 1) * p.W + (q & 1)) * C, ov[q]);
+        }
+    }
+}
+
 int plan_rows(int64_t M, const RowLayout& L, int* nblk)
 {
     // every thread should see >= 4 rows (one trip of the summing loop); at most kMaxPartialBlocks workgroups
@@ -630,12 +781,72 @@ int launch_bn_relu_maxpool_forward(int dtype, const void* x, const float* coef, 
     return DSP_OK;
 }
 
+bool bn_pool_backward_supported(int dtype, int C, int H, int W, int k, int stride, int pad)
+{
+    return dtype == DSP_BF16 && C % 8 == 0 && k == 3 && stride == 2 && pad == 1 && H >= 2 && W >= 2 && H % 2 == 0 && W % 2 == 0;
+}
+
+static int bn_pool_backward(const PoolGrad& pg, const void* x, void* dx, bool xacc, const void* dx_prev, const float* gamma,
+                            float* dgamma, float* dbeta, int64_t M, int C, const BnBuffers& buf, hipStream_t st, const float* fcoef)
+{
+    PoolCells p{};
+    p.dpool = (const bf16_t*)pg.dpool;
+    p.arg = pg.argmax;
+    p.H = pg.H;
+    p.W = pg.W;
+    p.Ho = pg.H / 2;
+    p.Wo = pg.W / 2;
+    fast_div_constants((uint32_t)p.Wo, &p.wo_mul, &p.wo_sh);
+    fast_div_constants((uint32_t)p.Ho, &p.ho_mul, &p.ho_sh);
+    const int64_t cells = M / 4;
+    const RowLayout L = make_layout(C, 8);
+    int nblk;
+    const int cells_per_block = plan_rows(cells, L, &nblk);
+    const double tensor_bytes = (double)M * C * 2.0, pool_bytes = (double)cells * C * 3.0;
+    {
+        ProfScope ps("bn_pool_bwd_reduce<bf16>", tensor_bytes + pool_bytes, 1);
+        DSP_LAUNCH(ps, bn_pool_bwd_reduce_kernel, dim3(nblk, ceil_div(L.cv, L.cvb)), dim3(kThreads), 0, st, (const bf16_t*)x, p,
+                   (const float*)buf.mean, (const float*)buf.invstd, fcoef, buf.partial, (uint32_t)cells, C, L, cells_per_block);
+    }
+    {
+        ProfScope ps("bn_bwd_finalize", (double)nblk * C * 16.0, 1);
+        DSP_LAUNCH(ps, bn_bwd_finalize_kernel, dim3(ceil_div(C, 4)), dim3(kMergeLanes * 4), 0, st, (const double*)buf.partial, nblk, C,
+                   1.0 / (double)M, gamma, (const float*)buf.mean, (const float*)buf.invstd, dgamma, dbeta, buf.coef);
+    }
+    const int64_t items = cells * L.cv;
+    int64_t grid = (items + kThreads - 1) / kThreads;
+    grid = (grid + 7) / 8 * 8;
+    if (grid > 256 * 16) grid = 256 * 16;
+    uint32_t cv_mul, cv_sh;
+    fast_div_constants((uint32_t)L.cv, &cv_mul, &cv_sh);
+    ProfScope ps("bn_pool_bwd_apply<bf16>", tensor_bytes * (2 + (xacc ? 1 : 0)) + pool_bytes, 1);
+    if (xacc)
+        DSP_LAUNCH(ps, bn_pool_bwd_apply_kernel<true>, dim3((unsigned)grid), dim3(kThreads), 0, st, (const bf16_t*)x, p, (bf16_t*)dx,
+                   (const bf16_t*)dx_prev, (const float*)buf.coef, fcoef, (uint32_t)items, C, (uint32_t)L.cv, cv_mul, cv_sh);
+    else
+        DSP_LAUNCH(ps, bn_pool_bwd_apply_kernel<false>, dim3((unsigned)grid), dim3(kThreads), 0, st, (const bf16_t*)x, p, (bf16_t*)dx,
+                   (const bf16_t*)dx_prev, (const float*)buf.coef, fcoef, (uint32_t)items, C, (uint32_t)L.cv, cv_mul, cv_sh);
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
 int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, void* dx, void* dres,
                        bool dres_accumulate, bool dx_accumulate, const float* gamma, float* dgamma, float* dbeta,
                        int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, const void* dx_add,
-                       const float* fwd_coef)
+                       const float* fwd_coef, const PoolGrad* pool)
 {
     DSP_REQUIRE(M > 0 && C > 0, DSP_EINVAL, "bn: bad shape");
+    if (pool) {
+        DSP_REQUIRE(relu && fwd_coef && !dres && pool->dpool && pool->argmax && x && dx &&
+                        bn_pool_backward_supported(dtype, C, pool->H, pool->W, pool->k, pool->stride, pool->pad) &&
+                        M % ((int64_t)pool->H * pool->W) == 0 && M * C < (1ll << 31) && ((uintptr_t)pool->dpool % 16) == 0 &&
+                        ((uintptr_t)pool->argmax % 8) == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)dx % 16) == 0 &&
+                        ((uintptr_t)dx_add % 16) == 0,
+                    DSP_EINVAL, "bn backward behind a max pool: bf16, channels in runs of 8, 3 x 3 / 2 / 1 windows over an even map, "
+                                "ReLU without residual, 16-byte aligned tensors");
+        return bn_pool_backward(*pool, x, dx, dx_accumulate || dx_add, dx_add ? dx_add : dx, gamma, dgamma, dbeta, M, C, buf, st,
+                                fwd_coef);
+    }
     const void* dx_prev = dx_add ? dx_add : dx;
     if (dx_add) dx_accumulate = true;
     // the ReLU of a batch norm without residual can be decided from x (no read of y) when the caller still has the

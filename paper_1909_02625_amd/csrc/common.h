@@ -248,10 +248,23 @@ int launch_add_forward_stats(int dtype, const void* a, const void* b, void* y, i
 // buffer of its own (then dx_accumulate is ignored).
 // fwd_coef != nullptr (a batch norm with ReLU and no residual): the forward pass's {scale[C], shift[C]}; the ReLU is
 // then decided by forming y from x again, exactly as the forward kernel did, and y is not read (may be nullptr).
+// pool != nullptr (with fwd_coef; bn_pool_backward_supported: bf16, C % 8 == 0, 3 x 3 / stride 2 / pad 1 windows over an
+// even map): the batch norm's only reader is a max pool, and dy is the backward of that pool, formed on the fly from the
+// pool's own output gradient and recorded taps (summed in the order and rounded to the storage type as
+// launch_maxpool_backward does, so every dz is the same; the per-channel sums are taken in another order, which moves
+// dgamma, dbeta and the coefficients of dx by a few units of double rounding before they become floats), without the
+// pool's input gradient ever being stored.  dy is then ignored.
+struct PoolGrad {
+    const void* dpool;     // gradient of the pool's output, [N][Ho][Wo][C]
+    const uint8_t* argmax; // the pool's recorded taps
+    int H, W;              // the pool's input map = the batch norm's map (M = N * H * W)
+    int k, stride, pad;
+};
+bool bn_pool_backward_supported(int dtype, int C, int H, int W, int k, int stride, int pad);
 int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, void* dx, void* dres,
                        bool dres_accumulate, bool dx_accumulate, const float* gamma, float* dgamma, float* dbeta,
                        int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, const void* dx_add = nullptr,
-                       const float* fwd_coef = nullptr);
+                       const float* fwd_coef = nullptr, const PoolGrad* pool = nullptr);
 
 // ---- small layers and the update (misc.hip) ---------------------------------------------------
 int launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* argmax, int N, int H, int W, int C, int k,
@@ -353,6 +366,16 @@ struct VecIO<bf16_t, 1> {
     __device__ static inline void store(bf16_t* p, const float (&v)[1]) { *p = float_to_bf16(v[0]); }
 };
 
+
+// n / d for n < 2^31 with precomputed mul = floor(2^32 * (2^sh - d) / d) + 1, sh = ceil(log2 d).
+__device__ inline uint32_t fast_div(uint32_t n, uint32_t mul, uint32_t sh) { return (__umulhi(n, mul) + n) >> sh; }
+inline void fast_div_constants(uint32_t d, uint32_t* mul, uint32_t* sh)
+{
+    uint32_t s = 0;
+    while ((1ull << s) < d) ++s;
+    *sh = s;
+    *mul = (uint32_t)(((1ull << 32) * ((1ull << s) - d)) / d + 1);
+}
 
 // ---- in-situ kernel timing (block.hip) ----------------------------------------------------------
 // While a profile is running (dsp_profile_start .. dsp_profile_stop) every instrumented launch goes

@@ -199,15 +199,6 @@ __device__ inline void zero_acc(typename Mma<typename TL::T, TL::MT>::Acc (&acc)
 // The gathered tensor `in` is N x Hi x Wi x Ci; output rows m = (n, ho, wo) over N x Ho x Wo.
 // Tap (r, s) of output pixel (ho, wo) reads position t = o*ostride - pad + tap; with idil = 2
 // (backward-data of a stride-2 conv) only even t exist and they map to source pixel t/2.
-// n / d for n < 2^31 with precomputed mul = floor(2^32 * (2^sh - d) / d) + 1, sh = ceil(log2 d).
-__device__ inline uint32_t fast_div(uint32_t n, uint32_t mul, uint32_t sh) { return (__umulhi(n, mul) + n) >> sh; }
-inline void fast_div_constants(uint32_t d, uint32_t* mul, uint32_t* sh)
-{
-    uint32_t s = 0;
-    while ((1ull << s) < d) ++s;
-    *sh = s;
-    *mul = (uint32_t)(((1ull << 32) * ((1ull << s) - d)) / d + 1);
-}
 
 struct GatherGeom {
     int N, Hi, Wi, Ci, Ho, Wo, Co, R, S, pad_h, pad_w, ostride, idil;

@@ -72,6 +72,27 @@ int dsp_bn_relu_backward_from_x(int32_t dtype, const void* d_dy, const void* d_x
                               true, buf, (hipStream_t)stream, nullptr, d_scale_shift);
 }
 
+int dsp_bn_relu_maxpool_backward(int32_t dtype, const void* d_dpool, const uint8_t* d_argmax, const void* d_x,
+                                 const float* d_scale_shift, void* d_dx, int32_t dx_accumulate, const float* d_gamma,
+                                 const float* d_mean, const float* d_invstd, float* d_dgamma, float* d_dbeta, int32_t N, int32_t H,
+                                 int32_t W, int32_t C, int32_t k, int32_t stride, int32_t pad, void* d_workspace,
+                                 size_t workspace_bytes, void* stream)
+{
+    DSP_REQUIRE(dtype_ok(dtype) && d_dpool && d_argmax && d_x && d_scale_shift && d_dx && d_gamma && d_mean && d_invstd && d_dgamma &&
+                    d_dbeta && d_workspace, DSP_EINVAL, "dsp_bn_relu_maxpool_backward: bad argument");
+    DSP_REQUIRE(N > 0 && H > 0 && W > 0 && C > 0 && k > 0 && stride > 0 && pad >= 0 && pad < k && H + 2 * pad >= k && W + 2 * pad >= k &&
+                    (int64_t)N * H * W * C < (1ll << 31), DSP_EINVAL, "dsp_bn_relu_maxpool_backward: bad shape");
+    DSP_REQUIRE(bn_pool_backward_supported(dtype, C, H, W, k, stride, pad), DSP_EINVAL,
+                "dsp_bn_relu_maxpool_backward: bf16 tensors with channels in runs of 8, 3 x 3 windows at stride 2 and pad 1 over an even map only");
+    DSP_REQUIRE(workspace_bytes >= bn_ws_bytes(C) && ((uintptr_t)d_workspace % 16) == 0, DSP_EINVAL,
+                "dsp_bn_relu_maxpool_backward: workspace too small or not 16-byte aligned (%zu < %zu)", workspace_bytes, bn_ws_bytes(C));
+    BnBuffers buf{(double*)d_workspace, const_cast<float*>(d_mean), const_cast<float*>(d_invstd),
+                  (float*)((char*)d_workspace + bn_partial_bytes(C))};
+    const PoolGrad pg{d_dpool, d_argmax, H, W, k, stride, pad};
+    return launch_bn_backward(dtype, nullptr, d_x, nullptr, d_dx, nullptr, false, dx_accumulate != 0, d_gamma, d_dgamma, d_dbeta,
+                              (int64_t)N * H * W, C, true, buf, (hipStream_t)stream, nullptr, d_scale_shift, &pg);
+}
+
 int dsp_bn_relu_maxpool_forward(int32_t dtype, const void* d_x, const float* d_gamma, const float* d_beta, float eps, int32_t N,
                                 int32_t H, int32_t W, int32_t C, int32_t k, int32_t stride, int32_t pad, void* d_pool,
                                 uint8_t* d_argmax, float* d_mean, float* d_invstd, float* d_scale_shift, void* d_workspace,

@@ -109,6 +109,7 @@ def test_batch_norm_forward_and_backward(shape, dtype, relu, res):
 
 FUSED_SHAPES = [  # (N, C, H, W, k, stride, pad)
     (2, 16, 9, 9, 3, 2, 1),       # odd map: windows cut by every border
+    (3, 24, 6, 10, 3, 2, 1),      # the stem's window on a small even map, three channel vectors
     (3, 24, 8, 10, 2, 2, 0),      # 2 x 2 windows, no padding, three channel vectors
     (2, 64, 7, 5, 3, 1, 1),       # overlapping stride-1 windows
     (2, 8, 6, 6, 4, 2, 1),        # the largest window the tap code holds
@@ -173,6 +174,38 @@ def test_bn_relu_maxpool_in_one_pass_and_relu_decided_from_x(shape):
         outs.append((d_dx.view(torch.int16).clone(), d_dg.clone(), d_db.clone()))
     for u, v in zip(*outs):
         assert torch.equal(u, v)
+
+    # the pool's backward folded into the batch norm's: every masked gradient is the one dsp_maxpool_backward +
+    # dsp_bn_backward work on; the channel sums are taken in another order (doubles, then one rounding to float)
+    if (k, st, pd) == (3, 2, 1) and H % 2 == 0 and W % 2 == 0:
+        dp = round_like(rng.standard_normal((N, C, Ho, Wo)) * 0.1, dtype)
+        d_dp = to_dev(dp, dtype)
+        d_dy2 = torch.full((M * C,), float("nan"), device="cuda", dtype=torch.bfloat16)
+        D.dsp_maxpool_backward(dtype, d_dp, d_a, d_dy2, False, N, H, W, C, k, st, pd)
+        dx0 = to_dev(round_like(rng.standard_normal((N, C, H, W)) * 0.1, dtype), dtype)
+        for acc in (False, True):
+            res = []
+            for fused in (False, True):
+                d_dx = dx0.clone() if acc else torch.full((M * C,), float("nan"), device="cuda", dtype=torch.bfloat16)
+                d_dg, d_db = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
+                if fused:
+                    D.dsp_bn_relu_maxpool_backward(dtype, d_dp, d_a, d_x, d_coef, d_dx, acc, d_gamma, d_mean, d_invstd, d_dg, d_db,
+                                                   N, H, W, C, k, st, pd, ws, ws_bytes)
+                else:
+                    D.dsp_bn_backward(dtype, d_dy2, d_x, d_y, d_dx, None, False, acc, d_gamma, d_mean, d_invstd, d_dg, d_db, M, C, True,
+                                      ws, ws_bytes)
+                torch.cuda.synchronize()
+                res.append((d_dx.float().cpu().numpy(), d_dg.cpu().numpy(), d_db.cpu().numpy()))
+            (dx_a, dg_a, db_a), (dx_b, dg_b, db_b) = res
+            np.testing.assert_allclose(dg_b, dg_a, rtol=1e-6, atol=1e-6 * float(np.abs(dg_a).max()))
+            np.testing.assert_allclose(db_b, db_a, rtol=1e-6, atol=1e-6 * float(np.abs(db_a).max()))
+            # dx: the same bf16 values except where a coefficient moved by an ulp of float and tipped a rounding
+            differ = dx_a != dx_b
+            assert differ.mean() < 1e-3 and np.all(np.abs(dx_a - dx_b)[differ] <= 2.0 ** -7 * np.abs(dx_a)[differ] + 1e-30)
+    else:
+        with pytest.raises(D.DSPError):
+            D.dsp_bn_relu_maxpool_backward(dtype, d_p, d_a, d_x, d_coef, d_y, False, d_gamma, d_mean, d_invstd, d_mean2, d_invstd2,
+                                           N, H, W, C, k, st, pd, ws, ws_bytes)
 
 
 def test_bn_relu_maxpool_rejects_what_it_does_not_cover():
