@@ -1105,6 +1105,212 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     }
 }
 
+
+// ---- bf16 4x4 / stride 1 convolutions of 16 -> 64 channels, filters held in registers -----------------------------
+// The space-to-depth form of a 7x7 / stride-2 stem: 16 (12 used) channels in, 64 out, a 4 x 4 window with two pixels of
+// padding above / left and one below / right (Ho = H, Wo = W), and a very large map (112 x 112 x 256 images).  The
+// contraction is only 256 long, so a launch is bound by writing the output; what the generic tiles lose on it is the
+// fixed cost per tile (row decode, tap masks, epilogue) against eight short k steps.  Same scheme as the 64-channel
+// kernel above: every wave keeps the whole filter bank (64 x 256 bf16 = 32 KB) as first-operand fragments (16 k steps =
+// taps x 2 blocks of output channels x 4 registers = 128 registers), persistent workgroups walk ranges of consecutive
+// tiles of 128 output pixels, the input rows a tile needs (its output rows, two above, one below; two zero columns
+// left, one right) are staged ONCE as they lie in memory -- a pixel is one 32-byte run -- and the fragment of tap (r, s)
+// is read at the shifted address.  A k step is one tap: lane (pixel, fg) reads the 16-byte half fg of its pixel; the
+// two halves of a pixel swap places in every second group of 8 pixels, so that 16 consecutive pixels (512 bytes) read by
+// one half-wave fall on all banks once.  Half the register file suffices, so TWO workgroups share a compute unit and
+// each one's epilogue (staging, stores, column sums) runs under the other's MFMAs.  Column sums as in the kernel
+// above: carried per thread over a whole range, one partial row per workgroup and instance.
+struct C16Args {
+    int tiles;  // row tiles of 128 output pixels per problem instance
+    int twin;   // 1: a second problem instance (in1 / out1 / stats1)
+};
+constexpr int kC16Zero = 4096;      // zero region at the start of LDS (tap rows outside the image read here)
+constexpr int kC16Pitch = 128;      // pixels per patch row
+constexpr int kC16Rows = 6;         // a tile touches at most 3 output rows: 6 input rows
+constexpr int kC16Patch = kC16Rows * kC16Pitch * 32;
+constexpr int kC16EpiRowB = 64 * 2 + 16;
+constexpr int kC16Sred = 32 * 64 * 2 * 4;
+constexpr int kC16Lds = kC16Zero + 2 * kC16Patch + kC16Sred;
+constexpr int kC16MaxWorkgroups = 512;
+
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void conv4x4_c16_bf16_kernel(
+    const bf16_t* __restrict__ in_, const bf16_t* __restrict__ wgt, bf16_t* __restrict__ out_, GatherGeom g, C16Args a)
+{
+    typedef bf16_t T;
+    constexpr int BM = 128, CI = 16, CO = 64, NKS = 16, NCH = kC16Rows, WR0 = NKS - NCH, ROWB = kC16Pitch * 32;
+    static_assert(BM * kC16EpiRowB <= kC16Patch, "the output tile is staged in the patch buffer just multiplied");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int frow = lane & 31, fg = lane >> 5;
+    const int W = g.Wi, H = g.Hi;
+
+    // lane (frow, fg) holds, for output channel 32 j + frow, the channels 8 fg .. + 7 of tap t
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(wgt, (uint32_t)(CO * NKS * CI) * 2u);
+    u32x4 wf[NKS][2];
+#pragma unroll
+    for (int t = 0; t < NKS; ++t)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) wf[t][j] = load16(rw, (uint32_t)(((32 * j + frow) * (NKS * CI)) + CI * t + 8 * fg) * 2u);
+#pragma unroll
+    for (int t = 0; t < NKS; ++t)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) asm volatile("" ::"v"(wf[t][j]));  // complete before the tile loop (see the kernel above)
+
+    *(u32x4*)(smem + tid * 16) = u32x4{0u, 0u, 0u, 0u};  // kC16Zero = 256 threads x 16 bytes
+    const uint32_t in_bytes = (uint32_t)g.N * H * W * CI * 2u;
+    const __amdgpu_buffer_rsrc_t rin0 = make_rsrc(in_, in_bytes);
+    const __amdgpu_buffer_rsrc_t rin1 = make_rsrc(g.in1 ? g.in1 : in_, in_bytes);
+
+    const int nw = (int)gridDim.x, w1 = nw - 1 - (int)blockIdx.x;
+    auto range_lo = [&](int w) { return (int)((int64_t)w * a.tiles / nw); };
+    const int b0 = range_lo((int)blockIdx.x), n0 = range_lo((int)blockIdx.x + 1) - b0;
+    const int b1 = range_lo(w1), n1 = a.twin ? range_lo(w1 + 1) - b1 : 0;
+    const int n_steps = n0 + n1;
+    auto tile_at = [&](int s) { return s < n0 ? b0 + s : a.tiles + b1 + (s - n0); };
+
+    // thread tid moves half tid & 1 of patch pixel tid >> 1 of every row: input column (tid >> 1) - 2
+    const int pcol = tid >> 1, phalf = tid & 1;
+    const bool col_ok = pcol - 2 >= 0 && pcol - 2 < W;
+    const uint32_t col_off = (uint32_t)((pcol - 2) * CI + phalf * 8) * 2u;
+    const uint32_t lds_off = (uint32_t)(pcol * 32 + ((phalf ^ ((pcol >> 3) & 1)) << 4));
+    auto fetch_patch = [&](int t, u32x4 (&pre)[NCH]) {
+        const int inst = t >= a.tiles ? 1 : 0;
+        const int m0 = (t - inst * a.tiles) * BM;
+        const int tq0 = (int)fast_div((uint32_t)m0, g.wo_mul, g.wo_sh);  // flat output row of the tile's first pixel
+        const int m_last = min(m0 + BM, g.M) - 1;
+        const int rows = (int)fast_div((uint32_t)m_last, g.wo_mul, g.wo_sh) - tq0 + 4;  // input rows this tile touches
+        const __amdgpu_buffer_rsrc_t rin = inst ? rin1 : rin0;
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int row = tq0 - 2 + i;
+            const bool row_ok = i < rows && row >= 0 && row < g.N * H;  // uniform
+            pre[i] = load16(rin, (row_ok && col_ok) ? (uint32_t)(row * W * CI) * 2u + col_off : kOutOfRange);
+        }
+    };
+
+    u32x4 pre[NCH];
+    if (n_steps > 0) {
+        fetch_patch(tile_at(0), pre);
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) *(u32x4*)(smem + kC16Zero + i * ROWB + lds_off) = pre[i];
+    }
+    float cs0[8], cs1[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) cs0[e] = cs1[e] = 0.f;
+    int cur = 0;
+    for (int step = 0; step < n_steps; ++step) {
+        const int t = tile_at(step);
+        const int inst = t >= a.tiles ? 1 : 0;
+        const int m0 = (t - inst * a.tiles) * BM;
+        T* __restrict__ out = inst ? (T*)g.out1 : out_;
+        double* stats = inst ? g.stats1 : g.stats;
+        const int tq0 = (int)fast_div((uint32_t)m0, g.wo_mul, g.wo_sh);
+        const uint32_t patch_base = (uint32_t)(kC16Zero + cur * kC16Patch);
+        char* patch = smem + patch_base;
+        char* next_patch = smem + kC16Zero + (cur ^ 1) * kC16Patch;
+        const bool has_next = step + 1 < n_steps;
+
+        lds_barrier();  // this tile's rows are in LDS; every wave is past the previous tile's epilogue
+        if (has_next) fetch_patch(tile_at(step + 1), pre);
+
+        uint32_t base_r[4], koff[4];
+        {
+            const int m = m0 + wave * 32 + frow;
+            const int tq = (int)fast_div((uint32_t)m, g.wo_mul, g.wo_sh), wo = m - tq * W;
+            const int n = (int)fast_div((uint32_t)tq, g.ho_mul, g.ho_sh), ho = tq - n * H;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const bool ok = m < g.M && ho + r - 2 >= 0 && ho + r - 2 < H;
+                base_r[r] = ok ? patch_base + (uint32_t)((tq - tq0 + r) * ROWB) : 0u;
+            }
+#pragma unroll
+            for (int s2 = 0; s2 < 4; ++s2) {
+                const int pc = wo + s2;  // patch column of tap column s2: input column wo - 2 + s2
+                koff[s2] = (uint32_t)(pc * 32 + ((fg ^ ((pc >> 3) & 1)) << 4));
+            }
+        }
+        auto read_frag = [&](int ks) { return *(const u32x4*)(smem + base_r[ks >> 2] + koff[ks & 3]); };
+
+        typename Mma<T, 32>::Acc acc[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+
+        u32x4 fa[2];
+        fa[0] = read_frag(0);
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            if (ks + 1 < NKS) fa[(ks + 1) & 1] = read_frag(ks + 1);
+            if (ks >= WR0 && has_next) *(u32x4*)(next_patch + (ks - WR0) * ROWB + lds_off) = pre[ks - WR0];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) Mma<T, 32>::run(wf[ks][j], fa[ks & 1], acc[j]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        lds_barrier();  // every wave has finished reading the patch: it becomes the staging area of the output tile
+
+        typedef typename Run4<T>::V RunV;
+        const int lr = wave * 32 + frow;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int col = j * 32 + acc_row<32>(lane, 4 * q);
+                *(RunV*)(patch + lr * kC16EpiRowB + col * 2) =
+                    Run4<T>::pack(acc[j][4 * q], acc[j][4 * q + 1], acc[j][4 * q + 2], acc[j][4 * q + 3]);
+            }
+        lds_barrier();
+        {
+            const int cc = (tid & 7) * 8, lr0 = tid >> 3;
+            u32x4 v[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[k] = *(const u32x4*)(patch + (lr0 + 32 * k) * kC16EpiRowB + cc * 2);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int m = m0 + lr0 + 32 * k;
+                if (m < g.M) *(u32x4*)(out + (int64_t)m * CO + cc) = v[k];
+            }
+            if (stats) {
+                float s0[8], s1[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s0[e] = s1[e] = 0.f;
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float lo = __uint_as_float(v[k][e] << 16), hi = __uint_as_float(v[k][e] & 0xffff0000u);
+                        s0[2 * e] += lo;
+                        s1[2 * e] += lo * lo;
+                        s0[2 * e + 1] += hi;
+                        s1[2 * e + 1] += hi * hi;
+                    }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    cs0[e] += s0[e];
+                    cs1[e] += s1[e];
+                }
+                if (step == n0 - 1 || step == n_steps - 1) {
+                    float* sred = (float*)(smem + kC16Zero + 2 * kC16Patch);  // [32 row groups][64 channels][2]
+#pragma unroll
+                    for (int e = 0; e < 8; e += 2)
+                        *(f32x4*)(sred + (lr0 * 64 + cc + e) * 2) = f32x4{cs0[e], cs1[e], cs0[e + 1], cs1[e + 1]};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) cs0[e] = cs1[e] = 0.f;
+                    lds_barrier();
+                    if (tid < 128) {
+                        double sa = 0.0;
+#pragma unroll 8
+                        for (int k = 0; k < 32; ++k) sa += (double)sred[k * 128 + tid];
+                        stats[(int64_t)(inst ? w1 : (int)blockIdx.x) * (CO * 2) + tid] = sa;
+                    }
+                }
+            }
+        }
+        cur ^= 1;
+    }
+}
+
 // ---- fp32 3x3 convolutions with 16 or 32 channels on both sides ----------------------------------
 // With so few channels the whole filter bank of 16 output channels fits in registers (9 * Ci / 16
 // 16-byte runs per lane), so no operand needs LDS: the MFMA computes y^T, D[co][pixel] with
@@ -2183,10 +2389,25 @@ bool c64_eligible(const GatherGeom& g)
            g.Wi + 2 <= kC64Pitch && 4 + 254 / g.Wi <= kC64Chunks / 2;  // rows of the patch: 64 pixels wide, at most 8
 }
 
+// The 16 -> 64 channel 4 x 4 kernel (space-to-depth stems): bf16, stride 1, pad 2 with Ho = H and Wo = W, rows of at most
+// 125 pixels (a patch row holds 128), a map large enough to fill the chip; forward only.
+inline int c16_workgroups(const GatherGeom& g)
+{
+    const int t = ceil_div(g.M, 128);
+    return t < kC16MaxWorkgroups ? t : kC16MaxWorkgroups;  // two persistent workgroups per compute unit
+}
+template <typename T>
+bool c16_eligible(const GatherGeom& g)
+{
+    return sizeof(T) == 2 && g.groups == 1 && g.Ci == 16 && g.Co == 64 && g.R == 4 && g.S == 4 && g.ostride == 1 && g.idil == 1 &&
+           g.pad_h == 2 && g.pad_w == 2 && g.Hi == g.Ho && g.Wi == g.Wo && g.oh_mul == 0 && g.M >= 256 * 256 &&
+           g.Wi + 3 <= kC16Pitch && g.Wi >= 64 && !g.accum;  // a tile of 128 pixels then touches at most 3 rows
+}
 template <typename T>
 int select_gather_tile(const GatherGeom& g, int* bm)
 {
     if (c64_eligible<T>(g)) { *bm = 256; return 21; }
+    if (c16_eligible<T>(g)) { *bm = 128; return 22; }
     if (dma_eligible<T>(g)) { *bm = 256; return 20; }
     if (g.Co <= 16) {
         // (bf16 always takes the 64-row tile: measured in the four-stream resnet56 pipeline)
@@ -2256,6 +2477,26 @@ int run_c64(const GatherGeom& g, const void* in, const void* w, void* out, hipSt
     return DSP_OK;
 }
 
+
+int run_c16(const GatherGeom& g, const void* in, const void* w, void* out, hipStream_t st, double flops)
+{
+    C16Args a{};
+    a.tiles = ceil_div(g.M, 128);
+    a.twin = g.in1 ? 1 : 0;
+    static std::atomic<bool> attr_done{false};
+    if (!attr_done) {
+        DSP_HIP(hipFuncSetAttribute((const void*)conv4x4_c16_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kC16Lds));
+        attr_done = true;
+    }
+    {
+        ProfScope ps("conv4x4_c16<bf16,filters in registers>", flops, 0);
+        DSP_LAUNCH(ps, conv4x4_c16_bf16_kernel, dim3((unsigned)c16_workgroups(g)), dim3(kThreads), kC16Lds, st, (const bf16_t*)in,
+                   (const bf16_t*)w, (bf16_t*)out, g, a);
+    }
+    DSP_HIP(hipGetLastError());
+    return DSP_OK;
+}
+
 template <typename T>
 int dispatch_gather(GatherGeom g, bool accum, const void* in, const void* w, void* out, hipStream_t st, double flops)
 {
@@ -2286,6 +2527,13 @@ int dispatch_gather(GatherGeom g, bool accum, const void* in, const void* w, voi
         const bool aligned = vec && g.out_vec && ((uintptr_t)g.in1 % 16) == 0 && ((uintptr_t)g.out1 % 16) == 0;
         if (aligned) return run_c64(g, in, w, out, st, flops);
         // unaligned tensors (single-layer calls only) take the register-staged tiles; their partial rows differ
+        DSP_REQUIRE(g.stats == nullptr, DSP_EINVAL, "conv forward with column sums: x, w and y must be 16-byte aligned");
+        id = 10;
+    }
+    if (id == 22) {
+        const bool aligned = vec && g.out_vec && ((uintptr_t)g.in1 % 16) == 0 && ((uintptr_t)g.out1 % 16) == 0;
+        if (aligned && !accum) return run_c16(g, in, w, out, st, flops);
+        // unaligned tensors and accumulating calls (single-layer calls only) take the register-staged tiles
         DSP_REQUIRE(g.stats == nullptr, DSP_EINVAL, "conv forward with column sums: x, w and y must be 16-byte aligned");
         id = 10;
     }
@@ -2624,7 +2872,9 @@ int conv_forward_row_tiles(int dtype, const ConvShape& c)
     if (dtype == DSP_FP32 && direct_eligible<float>(g, nullptr, nullptr)) return direct_grid(g);
     int bm;
     if (dtype == DSP_BF16) {
-        if (select_gather_tile<bf16_t>(g, &bm) == 21) return c64_workgroups(g);
+        const int id = select_gather_tile<bf16_t>(g, &bm);
+        if (id == 21) return c64_workgroups(g);
+        if (id == 22) return c16_workgroups(g);
     } else {
         select_gather_tile<float>(g, &bm);
     }

@@ -260,6 +260,17 @@ def _c64_probe():
     return [b.layers]
 
 
+def _stem_probe():
+    """The ImageNet stem alone (7x7 / stride-2 convolution of the 3-channel image, batch norm + ReLU, 3x3 / stride-2 max
+    pool) at its real map size: large enough for the stem's own convolution kernel and for the pool kernels that fold
+    the batch norm in, with a batch small enough for the oracle."""
+    b = _B()
+    a = b.conv(-1, 3, 64, 7, 2, pad=3)
+    a = b.bn(a, 64)
+    b.add(op="maxpool", **{"in": a}, k=3, stride=2, pad=1)
+    return [b.layers]
+
+
 # ----------------------------------------------------------------------------- configs
 CONFIGS = {
     # name: blocks, input (N, C, H, W), classes, DSP(p; m), lr, momentum, weight decay, steps, seed, dtype
@@ -298,6 +309,10 @@ CONFIGS = {
     # one ragged; forward + recompute in one launch, fused batch-norm sums, accumulating backward-data)
     "c64_probe": dict(blocks=_c64_probe, input=(21, 64, 56, 56), classes=None, p=(0,), m=(1,), lr=0.01, beta=0.9,
                       wd=0.0, steps=3, seed=6, dtypes=("bf16",), grad_std=0.1, data_input=False),
+    # the ImageNet stem on 6 full-size images (M = 75264 output pixels of the convolution: 588 tiles of 128 for 512
+    # workgroups; twin launches, fused sums, the pool with the batch norm folded in, forward and backward)
+    "stem_probe": dict(blocks=_stem_probe, input=(6, 3, 224, 224), classes=None, p=(0,), m=(1,), lr=0.01, beta=0.9,
+                       wd=0.0, steps=3, seed=7, dtypes=("bf16",), grad_std=0.1),
     "resnet18": dict(blocks=_resnet18, input=(256, 3, 224, 224), classes=1000, p=(1, 1, 1, 0), m=(6, 4, 2, 0),
                      lr=0.01, beta=0.9, wd=0.0, steps=20, seed=4, dtypes=("bf16",)),
 }
