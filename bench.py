@@ -35,6 +35,7 @@ def parse():
     ap.add_argument("--batch", type=int, default=None, help="override the mini-batch size (not the headline number)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the CPU-oracle baseline leg (0 = skip)")
     ap.add_argument("--profile-steps", type=int, default=5)
+    ap.add_argument("--kernels", type=int, default=12, help="how many kernels (heaviest first) the JSON line lists")
     ap.add_argument("--straggler", type=int, nargs=2, metavar=("BLOCK", "MICROSECONDS"), default=None,
                     help="straggler emulation: block BLOCK's stream idles this long before its work in every tick "
                          "(not the headline number)")
@@ -347,7 +348,7 @@ def main():
         "conv_mfma_util_pct": None if conv_util is None else round(conv_util, 3),
         # sum of all kernel durations of a tick (over the K streams); K * ms_per_step minus this is stream idle time
         "kernel_time_ms_per_step": None if not table else round(sum(k["ms"] for k in table) / a.profile_steps, 4),
-        "library_build_id": D.dsp_build_id(), "roofline": roof, "cpu_baseline": base, "kernels": kernels[:12],
+        "library_build_id": D.dsp_build_id(), "roofline": roof, "cpu_baseline": base, "kernels": kernels[:a.kernels],
     }
     print(json.dumps(out))
 

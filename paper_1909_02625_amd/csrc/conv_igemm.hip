@@ -2042,6 +2042,173 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         }
 }
 
+
+// ---- bf16 backward-weight of the 16 -> 64 channel 4 x 4 layer (space-to-depth stems) -----------------------------
+// dw[64][16 taps x 16 channels] over millions of pixels: the result is 64 KB of floats, so a wave keeps HALF of it in
+// accumulators (2 blocks of output channels x 4 of the 8 blocks of tap pairs = 128 registers; all 256 leave the register
+// allocator no slack and the prefetch spills) and the waves of a persistent workgroup split tap pairs x pixels, 2 x 2.  A tile is two output rows of one image, staged once as they lie in memory:
+// `dy` as 2 x 128 pixel slots of 128 bytes (columns W .. 127 zero), `x` as 5 x 128 slots of 32 bytes (two rows above,
+// one below; two zero columns left, zeros outside the image).  The contraction runs over the 256 slots of the dy tile in
+// 16 steps of 16 pixels, eight per wave; the x operand of tap (r, s) for slot q is slot q + 128 r + s of the patch: a
+// constant offset in the LDS read, and the zero columns of dy cancel whatever finite value the patch holds where a
+// slot is no pixel (a zeroed guard follows the patch).  Operands are formed by the LDS transpose read (see
+// conv_wgrad_tr_kernel); in the x operand the lane halves of a 32-column block are two neighbouring taps.  A step
+// costs 2 + 4 operand fragments for 8 MFMAs.  The next tile is fetched into registers before the steps and written to
+// the other LDS buffer after them.  At the end the two waves of each half are summed through LDS and leave as ONE
+// slice of partials per workgroup.
+struct WStemArgs {
+    int tiles;          // N * H / 2
+    int tiles_per_wg;   // consecutive tiles per workgroup
+};
+constexpr int kWStemDyBytes = 2 * 128 * 128, kWStemXBytes = 5 * 128 * 32, kWStemGuard = 256;
+constexpr int kWStemBufBytes = kWStemDyBytes + kWStemXBytes + kWStemGuard;
+static_assert(2 * kWStemBufBytes >= 2 * 4 * 2 * 16 * 64 * 4, "the final sum stages two waves' accumulators in the tile buffers");
+
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void conv4x4_c16_wgrad_bf16_kernel(
+    const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy, float* __restrict__ part, WgradGeom g, WStemArgs a)
+{
+    constexpr int CI = 16, CO = 64, KD = 16 * CI, NKS = 16;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int W = g.W, H = g.H, H2 = H / 2;
+
+    for (int b = 0; b < 2; ++b)
+        if (tid < kWStemGuard / 16) *(u32x4*)(smem + b * kWStemBufBytes + kWStemDyBytes + kWStemXBytes + tid * 16) = u32x4{0u, 0u, 0u, 0u};
+
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (uint32_t)g.N * H * W * CI * 2u);
+    const __amdgpu_buffer_rsrc_t rdy = make_rsrc(dy, (uint32_t)g.N * H * W * CO * 2u);
+    const int t_begin = blockIdx.x * a.tiles_per_wg, t_end = min(a.tiles, t_begin + a.tiles_per_wg);
+
+    // fetch: dy chunk i = run tid & 7 of column (tid >> 3) + 32 (i & 3) of tile row i >> 2; x chunk j = half tid & 1 of
+    // patch slot tid >> 1 (input column (tid >> 1) - 2) of patch row j
+    uint32_t dy_col[4], dy_lds[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int col = (tid >> 3) + 32 * q;
+        dy_col[q] = col < W ? (uint32_t)(col * CO + (tid & 7) * 8) * 2u : kOutOfRange;
+        dy_lds[q] = (uint32_t)swizzled_chunk(col, tid & 7, 128);  // a row of 128 slots is 64 lines: the swizzle repeats per row
+    }
+    const int xc = (tid >> 1) - 2;
+    const uint32_t x_col = (xc >= 0 && xc < W) ? (uint32_t)(xc * CI + (tid & 1) * 8) * 2u : kOutOfRange;
+    const uint32_t x_lds = (uint32_t)(kWStemDyBytes + (tid >> 1) * 32 + (tid & 1) * 16);
+    auto fetch = [&](int t, u32x4 (&pre)[13]) {
+        const int n = t / H2, h0 = (t - n * H2) * 2;  // first output row of the tile
+        const uint32_t img_row = (uint32_t)(n * H);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t off = (img_row + (uint32_t)(h0 + (i >> 2))) * (uint32_t)(W * CO * 2);
+            pre[i] = load16(rdy, dy_col[i & 3] != kOutOfRange ? off + dy_col[i & 3] : kOutOfRange);
+        }
+#pragma unroll
+        for (int j = 0; j < 5; ++j) {
+            const int hr = h0 - 2 + j;
+            const bool ok = hr >= 0 && hr < H && x_col != kOutOfRange;
+            pre[8 + j] = load16(rx, ok ? (img_row + (uint32_t)hr) * (uint32_t)(W * CI * 2) + x_col : kOutOfRange);
+        }
+    };
+    auto stage = [&](int buf, const u32x4 (&pre)[13]) {
+        char* base = smem + buf * kWStemBufBytes;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) *(u32x4*)(base + (i >> 2) * 16384 + dy_lds[i & 3]) = pre[i];
+#pragma unroll
+        for (int j = 0; j < 5; ++j) *(u32x4*)(base + j * 4096 + x_lds) = pre[8 + j];
+    };
+
+    // operand reads: lane (j16, cs, kg) addresses pixel slot 8 kg + j16 / 4 (+ 4 for the second half) of a step;
+    // dy: channels 16 cs + 4 (j16 % 4) .. + 3 of a 32-channel block; x: channels 4 (j16 % 4) .. + 3 of tap 2 * pair + cs
+    const int j16 = lane & 15, cs = (lane >> 4) & 1, kg = lane >> 5;
+    const int frag_row = 8 * kg + (j16 >> 2);
+    uint32_t a_addr[2][2];  // [output-channel block][half]
+    uint32_t b_addr[2];     // [half]; tap pair p adds ((p >> 1) * 128 + 2 * (p & 1)) * 32
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+#pragma unroll
+        for (int ic = 0; ic < 2; ++ic)
+            a_addr[ic][hh] = (uint32_t)(swizzled_chunk(frag_row + 4 * hh, 4 * ic + cs * 2 + ((j16 & 3) >> 1), 128) + (j16 & 1) * 8);
+        b_addr[hh] = (uint32_t)(kWStemDyBytes + (frag_row + 4 * hh + cs) * 32 + (j16 & 3) * 8);
+    }
+
+    const int ph = wave & 1, kh = wave >> 1;  // this wave: tap pairs 4 ph .. + 3, steps 8 kh .. + 7 of a tile
+    typename Mma<bf16_t, 32>::Acc acc[4][2];
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int ic = 0; ic < 2; ++ic)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[p][ic][e] = 0.f;
+
+    u32x4 pre[13];
+    if (t_begin < t_end) {
+        fetch(t_begin, pre);
+        stage(0, pre);
+    }
+    int cur = 0;
+    for (int t = t_begin; t < t_end; ++t) {
+        const bool has_next = t + 1 < t_end;
+        __syncthreads();  // this tile is staged; every wave has finished the previous tile (its buffer is written below)
+        if (has_next) fetch(t + 1, pre);
+        const char* buf = smem + cur * kWStemBufBytes;
+        // step ks of the tile: slots 16 ks .. + 15 = tile row ks >> 3, columns 16 (ks & 7) ..
+        auto read_a = [&](int ks, u32x4 (&fa)[2]) {
+#pragma unroll
+            for (int ic = 0; ic < 2; ++ic) {
+                const u32x2 lo = lds_read_tr16(buf + a_addr[ic][0] + ks * 2048), hi = lds_read_tr16(buf + a_addr[ic][1] + ks * 2048);
+                fa[ic] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            }
+        };
+        auto read_b = [&](int ks, int p) {  // p: pair within this wave's half; tap row 2 ph + (p >> 1), tap columns 2 (p & 1), + 1
+            const int off = ks * 512 + (((2 * ph + (p >> 1)) * 128 + 2 * (p & 1)) * 32);
+            const u32x2 lo = lds_read_tr16(buf + b_addr[0] + off), hi = lds_read_tr16(buf + b_addr[1] + off);
+            return u32x4{lo[0], lo[1], hi[0], hi[1]};
+        };
+        u32x4 fa[2][2], fb[2][4];
+        read_a(8 * kh, fa[0]);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) fb[0][p] = read_b(8 * kh, p);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (i + 1 < 8) {
+                read_a(8 * kh + i + 1, fa[(i + 1) & 1]);
+#pragma unroll
+                for (int p = 0; p < 4; ++p) fb[(i + 1) & 1][p] = read_b(8 * kh + i + 1, p);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // the next step's operand reads go out before this step's MFMAs
+#pragma unroll
+            for (int p = 0; p < 4; ++p)
+#pragma unroll
+                for (int ic = 0; ic < 2; ++ic) Mma<bf16_t, 32>::run(fa[i & 1][ic], fb[i & 1][p], acc[p][ic]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (has_next) stage(cur ^ 1, pre);
+        cur ^= 1;
+    }
+
+    // the two waves of each half: the one with the later steps parks its sums in LDS (lane-contiguous), the other adds
+    // them to its own and writes its half of the workgroup's slice dw[co][tap * 16 + ci]
+    float* red = (float*)smem + ph * (4 * 2 * 16 * 64);  // [pair][block][register][lane]
+    float* dst = part + (int64_t)blockIdx.x * CO * KD;
+    __syncthreads();
+    if (kh == 1) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+#pragma unroll
+            for (int ic = 0; ic < 2; ++ic)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) red[((p * 2 + ic) * 16 + e) * 64 + lane] = acc[p][ic][e];
+    }
+    __syncthreads();
+    if (kh == 0) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+#pragma unroll
+            for (int ic = 0; ic < 2; ++ic)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    dst[(int64_t)(32 * ic + acc_row<32>(lane, e)) * KD + (4 * ph + p) * 32 + (lane & 31)] =
+                        acc[p][ic][e] + red[((p * 2 + ic) * 16 + e) * 64 + lane];
+    }
+}
+
 // Backward-weight of an fp32 layer with 16 input and 16 output channels.  The GEMM output is only
 // 16 x (R*S*16), so LDS tiling buys nothing: each wave streams its own output pixels straight from
 // global memory into the 16x16x4 MFMA operand layout (lane = (pixel % 4) * 16 + channel, one
@@ -2694,6 +2861,21 @@ int wgrad_c64_slices(const ConvShape& c, int* tiles_per_wg)
     return ceil_div(tiles, per);
 }
 
+// The space-to-depth stem's layer: bf16, 16 -> 64 channels, 4 x 4, stride 1, pad 2 with Ho = H and Wo = W, rows of 64 .. 125
+// pixels, an even number of rows, enough tiles for every compute unit.
+bool wgrad_stem_eligible(int dtype, const ConvShape& c)
+{
+    return dtype == DSP_BF16 && conv_groups(c) == 1 && c.Cin == 16 && c.Cout == 64 && c.R == 4 && c.S == 4 && c.stride == 1 &&
+           c.pad == 2 && c.Ho == c.H && c.Wo == c.W && c.W >= 64 && c.W + 3 <= 128 && c.H % 2 == 0 && (int64_t)c.N * c.H / 2 >= 256;
+}
+int wgrad_stem_slices(const ConvShape& c, int* tiles_per_wg)
+{
+    const int tiles = c.N * c.H / 2;
+    const int per = ceil_div(tiles, 256);
+    if (tiles_per_wg) *tiles_per_wg = per;
+    return ceil_div(tiles, per);
+}
+
 // The register-streaming kernel serves fp32 layers with 16 -> 16 channels and 3x3 or 1x1 filters.
 bool wgrad_c16_eligible(int dtype, const ConvShape& c)
 {
@@ -2731,9 +2913,11 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
     fast_div_constants((uint32_t)c.Ho, &g.ho_mul, &g.ho_sh);
     const bool c16 = wgrad_c16_eligible(dtype, c);
     const bool c64 = wgrad_c64_eligible(dtype, c);
+    const bool stem = wgrad_stem_eligible(dtype, c);
     int c64_per = 0;
     const int splits = c64 ? wgrad_c64_slices(c, &c64_per)
-                           : c16 ? wgrad_c16_splits(c, &g.m_per_split) : wgrad_splits(c, pl, &g.m_per_split);
+                           : stem ? wgrad_stem_slices(c, &c64_per)
+                                  : c16 ? wgrad_c16_splits(c, &g.m_per_split) : wgrad_splits(c, pl, &g.m_per_split);
     const size_t n = (size_t)c.Cout * g.Kdim;
     float* dst = dw;
     if (splits > 1) {
@@ -2755,6 +2939,18 @@ int dispatch_wgrad(const ConvShape& c, const void* x, const void* dy, float* dw,
         }
         ProfScope ps("conv_wgrad_c64<bf16,accumulators resident>", flops, 0);
         DSP_LAUNCH(ps, kern, dim3(splits), dim3(kThreads), 2 * kW64BufBytes, st, (const bf16_t*)x, (const bf16_t*)dy, dst, g, a);
+        rc = DSP_OK;
+    } else if (stem) {
+        DSP_REQUIRE(vec, DSP_EINVAL, "conv backward-weight: x and dy of this layer shape must be 16-byte aligned");
+        WStemArgs a{c.N * c.H / 2, c64_per};
+        auto kern = conv4x4_c16_wgrad_bf16_kernel;
+        static std::atomic<bool> attr_done{false};
+        if (!attr_done) {
+            DSP_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kWStemBufBytes));
+            attr_done = true;
+        }
+        ProfScope ps("conv_wgrad_stem<bf16,accumulators resident>", flops, 0);
+        DSP_LAUNCH(ps, kern, dim3(splits), dim3(kThreads), 2 * kWStemBufBytes, st, (const bf16_t*)x, (const bf16_t*)dy, dst, g, a);
         rc = DSP_OK;
     } else if (c16) {
         ProfScope ps(c.R == 3 ? "conv_wgrad_c16<fp32,3x3>" : "conv_wgrad_c16<fp32,1x1>", flops, 0);
@@ -2976,6 +3172,7 @@ size_t conv_backward_weight_workspace(const ConvShape& c)
         const WgradPlan pl = wgrad_plan(dtype, c);
         int per;
         const int splits = wgrad_c64_eligible(dtype, c) ? wgrad_c64_slices(c, nullptr)
+                           : wgrad_stem_eligible(dtype, c) ? wgrad_stem_slices(c, nullptr)
                            : wgrad_c16_eligible(dtype, c) ? wgrad_c16_splits(c, &per) : wgrad_splits(c, pl, &per);
         const size_t b = splits > 1 ? (size_t)splits * c.Cout * c.R * c.S * (c.Cin / conv_groups(c)) * sizeof(float) : 0;
         if (b > worst) worst = b;
@@ -2997,6 +3194,7 @@ int conv_backward_weight_slices(int dtype, const ConvShape& c)
     // aligned 16-byte tensors assumed (the slicing does not depend on the alignment)
     int per;
     if (wgrad_c64_eligible(dtype, c)) return wgrad_c64_slices(c, nullptr);
+    if (wgrad_stem_eligible(dtype, c)) return wgrad_stem_slices(c, nullptr);
     if (wgrad_c16_eligible(dtype, c)) return wgrad_c16_splits(c, &per);
     return wgrad_splits(c, wgrad_plan(dtype, c), &per);
 }
