@@ -1055,6 +1055,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
                     for (int e = 0; e < 4; ++e)
                         v[k][e] = pack_bf16x2(__uint_as_float(v[k][e] << 16) + __uint_as_float(pre[k][e] << 16),
                                               __uint_as_float(v[k][e] & 0xffff0000u) + __uint_as_float(pre[k][e] & 0xffff0000u));
+                // all sums are formed before the first store goes out: left to itself the compiler sinks each sum into the
+                // guarded block of its store, where the wait for the loaded values becomes a wait for the stores before it
+#pragma unroll
+                for (int k = 0; k < 8; ++k) asm volatile("" : "+v"(v[k]));
             }
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
