@@ -86,6 +86,8 @@ struct Layer {
     // pool kernel forms the batch norm's output on the fly, which is then never stored
     bool pool_fused = false;
     int bn_fused = -1;
+    // conv: backward-data is issued right after that of layer dgrad_after (see the block's init), not in its own turn
+    int dgrad_after = -1;
     bool pool_bwd = false;  // such a bn whose backward kernels also form the pool's input gradient on the fly (never stored)
     float* fcoef = nullptr;  // bn: {scale[C], shift[C]} of the last forward pass over the primary buffers (the backward sweep decides the ReLU with them)
     uint8_t* argmax = nullptr;
@@ -349,6 +351,22 @@ static int build_graph(dsp_block* b)
             if (L.d.op == DSP_OP_SOFTMAX_CE) continue;
             consumers[L.d.in0 + 1].push_back({i, 0});
             if ((L.d.op == DSP_OP_BN && L.d.in1 != -2) || L.d.op == DSP_OP_ADD) consumers[L.d.in1 + 1].push_back({i, 1});
+        }
+        // A tensor read by two convolutions, the later one (in layer order) a 1x1 / stride-2 projection: its backward-data
+        // reaches only one pixel in four, and as the first writer of the gradient buffer it would have to fill the other
+        // three quarters with zeros.  It is issued after the other convolution's backward-data instead and accumulates
+        // onto it: one sparse launch instead of four.
+        for (int t = -1; t < d.n_layers; ++t) {  // -1: the block input
+            const auto& cs = consumers[t + 1];
+            if (cs.size() != 2 || cs[0].second != 0 || cs[1].second != 0) continue;
+            const int lo = cs[0].first < cs[1].first ? cs[0].first : cs[1].first, hi = cs[0].first + cs[1].first - lo;
+            Layer& J = b->layers[lo];
+            Layer& Lh = b->layers[hi];
+            if (J.d.op != DSP_OP_CONV || Lh.d.op != DSP_OP_CONV || !J.in0_grad || !Lh.in0_grad) continue;
+            if (!(Lh.d.stride == 2 && Lh.d.r == 1 && Lh.d.s == 1) || Lh.in0_acc || !J.in0_acc) continue;
+            Lh.in0_acc = true;
+            J.in0_acc = false;
+            Lh.dgrad_after = lo;
         }
         for (int i = 0; i + 1 < d.n_layers; ++i) {
             Layer& L = b->layers[i];
@@ -713,8 +731,13 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
             DSP_TRY(launch_conv_backward_weight(b->dtype, L.cs, L.cin_pad ? L.xpad : src, dy,
                                                 L.cin_pad ? L.dw_pad : b->g + L.p0, (char*)b->wgrad_ws + L.wg_off,
                                                 L.wg_bytes, st, /*defer_reduce=*/true));
-            if (L.in0_grad)
+            if (L.in0_grad && L.dgrad_after < 0)
                 DSP_TRY(launch_conv_backward_data(b->dtype, L.cs, dy, weights_for_dgrad(b, L), grad_of(L.d.in0), L.in0_acc, st));
+            for (int j = i + 1; j < n; ++j) {  // the projection that waited for this layer's backward-data
+                Layer& Pj = b->layers[j];
+                if (Pj.d.op == DSP_OP_CONV && Pj.dgrad_after == i)
+                    DSP_TRY(launch_conv_backward_data(b->dtype, Pj.cs, dy_of(j), weights_for_dgrad(b, Pj), grad_of(Pj.d.in0), true, st));
+            }
             break;
         case DSP_OP_BN: {
             BnBuffers buf{b->bn_partial, L.mean, L.invstd, b->bn_coef};
