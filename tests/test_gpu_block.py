@@ -209,6 +209,7 @@ labels_by_batch = {}
     ("bn_probe", D.DSP_BF16, 3, {}),
     ("c64_probe", D.DSP_BF16, 3, {}),   # a ResNet-18 stage-1 block at a size that takes the filters-in-registers conv kernel
     ("stem_probe", D.DSP_BF16, 3, {}),  # the ImageNet stem at its real map size: its own conv kernel, batch norm folded into the pool
+    ("stem_probe_wide", D.DSP_BF16, 3, {}),  # ... on a 65 x 125 map: widest row of that kernel, odd sizes, ragged last tile
     # VGG-19 with batch norm (2x2 max pools inside the blocks, 512-channel layers on 4x4 and 2x2 maps)
     ("vgg19", D.DSP_FP32, 7, {"batch": 4, "perturb": True}),
     ("vgg19", D.DSP_BF16, 7, {"batch": 16, "perturb": True}),   # 2x2 maps: BN over 4 * batch values per channel

@@ -313,6 +313,10 @@ CONFIGS = {
     # workgroups; twin launches, fused sums, the pool with the batch norm folded in, forward and backward)
     "stem_probe": dict(blocks=_stem_probe, input=(6, 3, 224, 224), classes=None, p=(0,), m=(1,), lr=0.01, beta=0.9,
                        wd=0.0, steps=3, seed=7, dtypes=("bf16",), grad_std=0.1),
+    # the same on 130 x 250 images: the stem's map is 65 x 125 -- the widest row its convolution kernel holds, odd in both
+    # directions (the paths that need an even map fall back to the separate kernels), a ragged last tile (M = 73125)
+    "stem_probe_wide": dict(blocks=_stem_probe, input=(9, 3, 130, 250), classes=None, p=(0,), m=(1,), lr=0.01, beta=0.9,
+                            wd=0.0, steps=3, seed=8, dtypes=("bf16",), grad_std=0.1),
     "resnet18": dict(blocks=_resnet18, input=(256, 3, 224, 224), classes=1000, p=(1, 1, 1, 0), m=(6, 4, 2, 0),
                      lr=0.01, beta=0.9, wd=0.0, steps=20, seed=4, dtypes=("bf16",)),
 }
