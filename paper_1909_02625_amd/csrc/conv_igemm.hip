@@ -847,8 +847,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TL::WA
 // own outstanding direct loads, so the k loop stood still until the next tile had landed.)
 //   patch pixel pp = prow * 64 + pcol (rows of 64 pixels; 51 <= W <= 62, so a tile touches at most 8 flat rows) holds
 //   input pixel (flat row R0 + prow, column pcol - 1), flat row = n * H + h; its 128 bytes keep the 16-byte chunk c
-//   at position c ^ ((pcol >> 1) & 7), so that the 16 consecutive pixels a group of 16 lanes reads (same c) fall on
-//   16 different bank groups.  Lane tid moves position tid & 7 of the columns (tid >> 3) and (tid >> 3) + 32 of every
+//   at position c ^ (((prow * W + pcol) >> 1) & 7), so that the 16 consecutive pixels a group of 16 lanes reads (same
+//   c) fall on 16 different bank groups -- also where the run of pixels wraps from the end of one image row to the
+//   start of the next (prow * W + pcol goes on counting there; more than half of the 32-pixel blocks hold such a wrap).  Lane tid moves position tid & 7 of the columns (tid >> 3) and (tid >> 3) + 32 of every
 //   row: its two column offsets are fixed, the row offset is uniform, so a fetch costs two vector instructions.
 // A tap row that belongs to another image (h + r - 1 outside [0, H)) is a per-lane matter (the same flat row is data
 // for one output row and padding for the next image's): such lanes read from a 512-byte zero region instead.
@@ -926,7 +927,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
     for (int h = 0; h < 2; ++h) {
         const int pcol = (tid >> 3) + 32 * h, wi = pcol - 1;
         col_ok[h] = wi >= 0 && wi < W;
-        col_off[h] = (uint32_t)(wi * C + ((tid & 7) ^ ((pcol >> 1) & 7)) * 8) * 2u;
+        col_off[h] = (uint32_t)(wi * C) * 2u;
     }
     auto fetch_patch = [&](int t, u32x4 (&pre)[NCH]) {
         const int inst = t >= a.tiles ? 1 : 0;
@@ -941,7 +942,10 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
             const int prow = i >> 1, row = R0 + prow;
             const bool row_ok = prow < rows && row >= 0 && row < g.N * H;   // uniform
             const uint32_t row_off = (uint32_t)(row * W * C) * 2u;           // uniform
-            pre[i] = load16(rin, (row_ok && col_ok[i & 1]) ? row_off + col_off[i & 1] : kOutOfRange);
+            // the chunk that belongs at this lane's position of patch pixel (prow, pcol): position ^ key(prow * W + pcol)
+            const uint32_t key = ((uint32_t)(prow * W + (tid >> 3) + 32 * (i & 1)) >> 1) & 7u;
+            const uint32_t chunk = ((uint32_t)(tid & 7) ^ key) << 4;
+            pre[i] = load16(rin, (row_ok && col_ok[i & 1]) ? row_off + col_off[i & 1] + chunk : kOutOfRange);
         }
     };
 
@@ -974,7 +978,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
         if (has_next) fetch_patch(tile_at(step + 1), pre);
 
         // per lane and 32-pixel block: LDS address of tap row r (or the zero region), swizzle keys of the three tap columns
-        uint32_t base_r[2][3], keyf[2][3];
+        uint32_t base_r[2][3], f0[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int m = m0 + wave * 64 + i * 32 + frow;
@@ -986,14 +990,16 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))
                 const bool ok = m < g.M && ho + r - 1 >= 0 && ho + r - 1 < H;
                 base_r[i][r] = ok ? (uint32_t)(kC64Zero + cur * a.buf_bytes) + pix0 + (uint32_t)(r * W2 * 128) : 0u;
             }
-#pragma unroll
-            for (int s2 = 0; s2 < 3; ++s2) keyf[i][s2] = (uint32_t)(((((wo + s2) >> 1) & 7) ^ fg) << 4);
+            f0[i] = (uint32_t)((tq - R0 - 1) * W + wo);  // prow * W + pcol of tap (0, 0)
         }
         auto read_frag = [&](int ks, u32x4 (&f)[2]) {
             const int tap = ks >> 2, r = tap / 3, s2 = tap - 3 * r;
             const uint32_t cx = (uint32_t)((2 * (ks & 3)) << 4);
 #pragma unroll
-            for (int i = 0; i < 2; ++i) f[i] = *(const u32x4*)(smem + (base_r[i][r] + (keyf[i][s2] ^ cx)) + s2 * 128);
+            for (int i = 0; i < 2; ++i) {
+                const uint32_t key = (((f0[i] + (uint32_t)(r * W + s2)) >> 1) & 7u) ^ (uint32_t)fg;
+                f[i] = *(const u32x4*)(smem + (base_r[i][r] + ((key << 4) ^ cx)) + s2 * 128);
+            }
         };
 
         typename Mma<T, 32>::Acc acc[2][2];
