@@ -2077,7 +2077,7 @@ static_assert(2 * kWStemBufBytes >= 2 * 4 * 2 * 16 * 64 * 4, "the final sum stag
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1))) void conv4x4_c16_wgrad_bf16_kernel(
     const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy, float* __restrict__ part, WgradGeom g, WStemArgs a)
 {
-    constexpr int CI = 16, CO = 64, KD = 16 * CI, NKS = 16;
+    constexpr int CI = 16, CO = 64, KD = 16 * CI;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int W = g.W, H = g.H, H2 = H / 2;
