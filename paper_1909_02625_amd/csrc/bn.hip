@@ -374,7 +374,9 @@ __global__ __launch_bounds__(kThreads) void bn_relu_maxpool_bf16_kernel(const bf
         auto tap = [&](int r, int s, u32x4 v) {
             const int hi = ho * stride + r - pad, wi = wo * stride + s - pad;
             const bool valid = (unsigned)hi < (unsigned)H && (unsigned)wi < (unsigned)W;
-            const uint32_t code = (uint32_t)(15 - (r * k + s));
+            // A tap outside the image was loaded from the clamped address, which is a pixel of this same window (pad < k)
+            // whose own tap is inside: its value is in the race anyway, and with code 0 the copy loses every tie.
+            const uint32_t code = valid ? (uint32_t)(15 - (r * k + s)) : 0u;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float lo = __builtin_fmaf(__uint_as_float(v[e] << 16), sc[2 * e], sh[2 * e]);
@@ -382,7 +384,7 @@ __global__ __launch_bounds__(kThreads) void bn_relu_maxpool_bf16_kernel(const bf
                 lo = lo > 0.f ? lo : 0.f;
                 hi2 = hi2 > 0.f ? hi2 : 0.f;
                 const uint32_t pk = pack_bf16x2(lo, hi2);
-                const uint32_t k0 = valid ? ((pk << 16) | code) : 0u, k1 = valid ? ((pk & 0xffff0000u) | code) : 0u;
+                const uint32_t k0 = (pk << 16) | code, k1 = (pk & 0xffff0000u) | code;
                 key[2 * e] = key[2 * e] > k0 ? key[2 * e] : k0;
                 key[2 * e + 1] = key[2 * e + 1] > k1 ? key[2 * e + 1] : k1;
             }
@@ -394,11 +396,21 @@ __global__ __launch_bounds__(kThreads) void bn_relu_maxpool_bf16_kernel(const bf
             return (const u32x4*)(x + (((int64_t)n * H + hi) * W + wi) * C + c);
         };
         if (K) {
+            // element offsets of the window's (clamped) rows and columns: one sum per tap
+            uint32_t roff[K ? K : 1], coff[K ? K : 1];
+#pragma unroll
+            for (int r = 0; r < K; ++r) {
+                int hi = ho * stride + r - pad, wi = wo * stride + r - pad;
+                hi = hi < 0 ? 0 : (hi >= H ? H - 1 : hi);
+                wi = wi < 0 ? 0 : (wi >= W ? W - 1 : wi);
+                roff[r] = (uint32_t)((n * H + hi) * W) * (uint32_t)C + (uint32_t)c;
+                coff[r] = (uint32_t)wi * (uint32_t)C;
+            }
             u32x4 v[K ? K * K : 1];
 #pragma unroll
             for (int r = 0; r < K; ++r)
 #pragma unroll
-                for (int s = 0; s < K; ++s) v[r * K + s] = *addr(r, s);
+                for (int s = 0; s < K; ++s) v[r * K + s] = *(const u32x4*)(x + (roff[r] + coff[s]));
 #pragma unroll
             for (int r = 0; r < K; ++r)
 #pragma unroll
