@@ -422,6 +422,21 @@ int dsp_bn_backward(int32_t dtype, const void* d_dy, const void* d_x, const void
  *   taken in another order, so dgamma, dbeta and dx agree with that pair to double-rounding noise (relative 1e-6), not
  *   bit for bit.  bf16, C % 8 == 0, k = 3, stride = 2, pad = 1, even H and W only, else DSP_EINVAL.
  */
+/*
+ * Batch norm + ReLU WITH a residual input, as a block runs it: dsp_bn_forward_bits is dsp_bn_forward(relu = 1) that also
+ * leaves, in d_relu_bits (dsp_bn_relu_bits_bytes() bytes: one per channel vector of 16 bytes; channel counts that are no
+ * whole number of vectors are refused with DSP_EINVAL), bit k of byte v = element k of vector v of y as stored is positive;
+ * dsp_bn_backward_bits is dsp_bn_backward(relu = 1) that takes its ReLU decisions from those bytes instead of reading y:
+ * the same bits in dx, dres, dgamma, dbeta, one tensor pass less in each of its two kernels.
+ */
+int dsp_bn_relu_bits_bytes(int32_t dtype, int64_t M, int32_t C, size_t* bytes);
+int dsp_bn_forward_bits(int32_t dtype, const void* d_x, const void* d_res, void* d_y, const float* d_gamma, const float* d_beta,
+                        float eps, int64_t M, int32_t C, float* d_mean, float* d_invstd, uint8_t* d_relu_bits, void* d_workspace,
+                        size_t workspace_bytes, void* stream);
+int dsp_bn_backward_bits(int32_t dtype, const void* d_dy, const void* d_x, const uint8_t* d_relu_bits, void* d_dx, void* d_dres,
+                         int32_t dres_accumulate, int32_t dx_accumulate, const float* d_gamma, const float* d_mean,
+                         const float* d_invstd, float* d_dgamma, float* d_dbeta, int64_t M, int32_t C, void* d_workspace,
+                         size_t workspace_bytes, void* stream);
 int dsp_bn_relu_maxpool_forward(int32_t dtype, const void* d_x, const float* d_gamma, const float* d_beta, float eps, int32_t N,
                                 int32_t H, int32_t W, int32_t C, int32_t k, int32_t stride, int32_t pad, void* d_pool,
                                 uint8_t* d_argmax, float* d_mean, float* d_invstd, float* d_scale_shift, void* d_workspace,

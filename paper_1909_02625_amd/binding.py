@@ -27,7 +27,8 @@ __all__ = [
     "dsp_grouped_conv_forward", "dsp_grouped_conv_backward_data", "dsp_grouped_conv_backward_weight",
     "dsp_grouped_conv_workspace_bytes",
     "dsp_conv_backward_weight_static", "dsp_conv_backward_weight_static_bytes",
-    "dsp_bn_workspace_bytes", "dsp_bn_forward", "dsp_bn_backward", "dsp_bn_relu_maxpool_forward", "dsp_bn_relu_backward_from_x", "dsp_bn_relu_maxpool_backward", "dsp_maxpool_forward", "dsp_maxpool_backward",
+    "dsp_bn_workspace_bytes", "dsp_bn_forward", "dsp_bn_backward", "dsp_bn_relu_maxpool_forward", "dsp_bn_relu_backward_from_x", "dsp_bn_relu_maxpool_backward", "dsp_bn_relu_bits_bytes", "dsp_bn_forward_bits",
+    "dsp_bn_backward_bits", "dsp_maxpool_forward", "dsp_maxpool_backward",
     "dsp_add_forward", "dsp_add_backward", "dsp_gap_forward", "dsp_gap_backward", "dsp_linear_forward",
     "dsp_linear_backward", "dsp_softmax_ce", "dsp_block_get_activation", "dsp_block_get_pool_argmax",
     "dsp_profile_start", "dsp_profile_stop", "dsp_profile_get",
@@ -142,6 +143,9 @@ _SIGNATURES = {
     "dsp_bn_relu_maxpool_forward": [_i32, _vp, _vp, _vp, _f] + [_i32] * 7 + [_vp] * 6 + [_sz, _vp],
     "dsp_bn_relu_backward_from_x": [_i32, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _sz, _vp],
     "dsp_bn_relu_maxpool_backward": [_i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp] + [_i32] * 7 + [_vp, _sz, _vp],
+    "dsp_bn_relu_bits_bytes": [_i32, _i64, _i32, C.POINTER(C.c_size_t)],
+    "dsp_bn_forward_bits": [_i32, _vp, _vp, _vp, _vp, _vp, _f, _i64, _i32, _vp, _vp, _vp, _vp, _sz, _vp],
+    "dsp_bn_backward_bits": [_i32, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _sz, _vp],
     "dsp_maxpool_forward": [_i32, _vp, _vp, _vp] + [_i32] * 7 + [_vp],
     "dsp_maxpool_backward": [_i32, _vp, _vp, _vp] + [_i32] * 8 + [_vp],
     "dsp_add_forward": [_i32, _vp, _vp, _vp, _i64, _vp],
@@ -527,6 +531,26 @@ def dsp_bn_relu_backward_from_x(dtype, d_dy, d_x, d_scale_shift, d_dx, dx_accumu
     check(lib().dsp_bn_relu_backward_from_x(dtype, _ptr(d_dy), _ptr(d_x), _ptr(d_scale_shift), _ptr(d_dx), int(dx_accumulate),
                                             _ptr(d_gamma), _ptr(d_mean), _ptr(d_invstd), _ptr(d_dgamma), _ptr(d_dbeta), M, C_,
                                             _ptr(d_workspace), workspace_bytes, _stream(stream)), "dsp_bn_relu_backward_from_x")
+
+
+def dsp_bn_relu_bits_bytes(dtype, M, C_):
+    n = C.c_size_t(0)
+    check(lib().dsp_bn_relu_bits_bytes(dtype, M, C_, C.byref(n)), "dsp_bn_relu_bits_bytes")
+    return int(n.value)
+
+
+def dsp_bn_forward_bits(dtype, d_x, d_res, d_y, d_gamma, d_beta, eps, M, C_, d_mean, d_invstd, d_relu_bits, d_workspace,
+                        workspace_bytes, stream=None):
+    check(lib().dsp_bn_forward_bits(dtype, _ptr(d_x), _ptr(d_res), _ptr(d_y), _ptr(d_gamma), _ptr(d_beta), eps, M, C_, _ptr(d_mean),
+                                    _ptr(d_invstd), _ptr(d_relu_bits), _ptr(d_workspace), workspace_bytes, _stream(stream)),
+          "dsp_bn_forward_bits")
+
+
+def dsp_bn_backward_bits(dtype, d_dy, d_x, d_relu_bits, d_dx, d_dres, dres_accumulate, dx_accumulate, d_gamma, d_mean, d_invstd,
+                         d_dgamma, d_dbeta, M, C_, d_workspace, workspace_bytes, stream=None):
+    check(lib().dsp_bn_backward_bits(dtype, _ptr(d_dy), _ptr(d_x), _ptr(d_relu_bits), _ptr(d_dx), _ptr(d_dres), int(dres_accumulate),
+                                     int(dx_accumulate), _ptr(d_gamma), _ptr(d_mean), _ptr(d_invstd), _ptr(d_dgamma), _ptr(d_dbeta),
+                                     M, C_, _ptr(d_workspace), workspace_bytes, _stream(stream)), "dsp_bn_backward_bits")
 
 
 def dsp_bn_relu_maxpool_backward(dtype, d_dpool, d_argmax, d_x, d_scale_shift, d_dx, dx_accumulate, d_gamma, d_mean, d_invstd,

@@ -89,6 +89,7 @@ struct Layer {
     // conv: backward-data is issued right after that of layer dgrad_after (see the block's init), not in its own turn
     int dgrad_after = -1;
     bool pool_bwd = false;  // such a bn whose backward kernels also form the pool's input gradient on the fly (never stored)
+    uint8_t* relu_bits = nullptr;  // bn with residual + ReLU: sign bytes of the output the primary forward pass left (the backward sweep reads them instead of the output)
     float* fcoef = nullptr;  // bn: {scale[C], shift[C]} of the last forward pass over the primary buffers (the backward sweep decides the ReLU with them)
     uint8_t* argmax = nullptr;
     bool in0_grad = true;  // form the gradient w.r.t. in0
@@ -519,6 +520,10 @@ static int build_graph(dsp_block* b)
             DSP_TRY(dev_alloc(b, (void**)&L.mean, (size_t)L.d.cin * 4, &b->ws_bytes));
             DSP_TRY(dev_alloc(b, (void**)&L.invstd, (size_t)L.d.cin * 4, &b->ws_bytes));
             DSP_TRY(dev_alloc(b, (void**)&L.fcoef, (size_t)L.d.cin * 8, &b->ws_bytes));
+            if (L.d.relu && L.d.in1 != -2) {
+                const size_t nb = bn_relu_bits_bytes(b->dtype, (int64_t)t.N * t.H * t.W, t.C);
+                if (nb) DSP_TRY(dev_alloc(b, (void**)&L.relu_bits, nb, &b->ws_bytes));
+            }
             if (L.d.cin > max_c) max_c = L.d.cin;
         }
         if (L.d.op == DSP_OP_MAXPOOL) DSP_TRY(dev_alloc(b, (void**)&L.argmax, t.elems, &b->ws_bytes));
@@ -648,10 +653,11 @@ static int run_forward(dsp_block* b, const ForwardPass& P, const ForwardPass* tw
             BnForwardTwin tw{};
             if (twin)
                 tw = BnForwardTwin{src_of(*twin, L.d.in0), L.d.in1 == -2 ? nullptr : src_of(*twin, L.d.in1), act_of(*twin, i),
-                                   bn_buffers(*twin)};
+                                   bn_buffers(*twin), twin->lane ? nullptr : L.relu_bits};
             DSP_TRY(launch_bn_forward(b->dtype, src_of(P, L.d.in0), L.d.in1 == -2 ? nullptr : src_of(P, L.d.in1),
                                       act_of(P, i), b->x + L.p0, b->x + L.p1, b->desc.bn_eps, (int64_t)s.N * s.H * s.W, s.C,
-                                      L.d.relu != 0, bn_buffers(P), st, L.sum_tiles, twin ? &tw : nullptr, L.pool_fused));
+                                      L.d.relu != 0, bn_buffers(P), st, L.sum_tiles, twin ? &tw : nullptr, L.pool_fused,
+                                      P.lane ? nullptr : L.relu_bits));
             break;
         }
         case DSP_OP_ADD:
@@ -758,7 +764,7 @@ static int run_backward(dsp_block* b, const void* in, const void* gout, void* gi
             DSP_TRY(launch_bn_backward(b->dtype, dy, src, b->T[i].act, grad_of(L.d.in0), dres, L.in1_acc, L.in0_acc,
                                        b->x + L.p0, b->g + L.p0, b->g + L.p1, (int64_t)s.N * s.H * s.W, s.C,
                                        L.d.relu != 0, buf, st, dx_add,
-                                       L.d.in1 == -2 ? L.fcoef : nullptr, L.pool_bwd ? &pg : nullptr));
+                                       L.d.in1 == -2 ? L.fcoef : nullptr, L.pool_bwd ? &pg : nullptr, L.relu_bits));
             break;
         }
         case DSP_OP_ADD: {

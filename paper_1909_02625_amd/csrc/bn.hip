@@ -86,6 +86,8 @@ __device__ inline void combine_row_lanes(const double (&s0)[VW], const double (&
 // MODE 1: dz = dy * [y > 0] (if RM != 0); s0 = sum dz, s1 = sum dz * (x - mean) * invstd.  RM = 1 reads the stored y;
 //         RM = 2 (a batch norm without residual) forms y again from x and the forward pass's {scale, shift} with the
 //         forward kernel's own expression and rounding, so the decision is the same and y is never read.
+//         RM = 3 (vector paths): `y` points at the sign bytes the forward apply kernel left instead -- one byte per
+//         channel vector, bit k = element k of the stored output is positive: an eighth (bf16: a sixteenth) of y.
 // MODE 2: out = x + dy as stored (the element-wise sum of two feature maps); s0 = sum out, s1 = sum out^2:
 //         the sum layer together with the statistics pass of the batch norm that reads it.
 // part[blockIdx.x][c][2]; blockIdx.y walks channel groups when C/VW > 256.
@@ -149,6 +151,11 @@ __global__ __launch_bounds__(kThreads) void bn_sums_kernel(const T* __restrict__
                     VecIO<T, VW>::load(x + ru * C + c0, xv[u]);
                     if (MODE >= 1) VecIO<T, VW>::load(dy + ru * C + c0, gv[u]);
                     if (MODE == 1 && RM == 1) VecIO<T, VW>::load(y + ru * C + c0, yv[u]);
+                    if (MODE == 1 && RM == 3) {
+                        const uint32_t bits = ((const uint8_t*)y)[ru * L.cv + cvi];
+#pragma unroll
+                        for (int i = 0; i < VW; ++i) yv[u][i] = (bits >> i) & 1u ? 1.f : 0.f;
+                    }
                 }
             }
 #pragma unroll
@@ -272,6 +279,7 @@ struct BnApplyIo {
     const void* res;
     void* y;
     const float* coef;
+    uint8_t* bits;  // if set (vector paths, ReLU): one byte per channel vector, bit k = element k of y as stored is positive
 };
 template <typename T, int VW, bool RELU, bool HAS_RES>
 __global__ __launch_bounds__(kThreads) void bn_fwd_apply_kernel(BnApplyIo io0, BnApplyIo io1, int64_t nvec, int C, int cv)
@@ -298,6 +306,12 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_apply_kernel(BnApplyIo io0, B
             ov[k] = v;
         }
         VecIO<T, VW>::store(y + i * VW, ov);
+        if (RELU && VW > 1 && io.bits) {
+            uint32_t bits = 0u;
+#pragma unroll
+            for (int k = 0; k < VW; ++k) bits |= (to_float<T>(from_float<T>(ov[k])) > 0.f ? 1u : 0u) << k;
+            io.bits[i] = (uint8_t)bits;
+        }
     }
 }
 
@@ -319,6 +333,11 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_kernel(const T* __restr
         VecIO<T, VW>::load(dy + i * VW, gv);
         VecIO<T, VW>::load(x + i * VW, xv);
         if (RM == 1) VecIO<T, VW>::load(y + i * VW, yv);
+        if (RM == 3) {
+            const uint32_t bits = ((const uint8_t*)y)[i];
+#pragma unroll
+            for (int k = 0; k < VW; ++k) yv[k] = (bits >> k) & 1u ? 1.f : 0.f;
+        }
         if (DX_ACC) VecIO<T, VW>::load(dx_prev + i * VW, ov);
         if (HAS_RES && RES_ACC) VecIO<T, VW>::load(dres + i * VW, rv);
 #pragma unroll
@@ -597,7 +616,8 @@ inline int apply_grid(int64_t nvec)
 
 template <typename T, int VW>
 int bn_forward_t(const void* x, const void* res, void* y, const float* gamma, const float* beta, float eps, int64_t M,
-                 int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed, const BnForwardTwin* tw, bool stats_only)
+                 int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed, const BnForwardTwin* tw, bool stats_only,
+                 uint8_t* relu_bits)
 {
     const RowLayout L = make_layout(C, VW);
     int nblk;
@@ -626,8 +646,8 @@ int bn_forward_t(const void* x, const void* res, void* y, const float* gamma, co
     }
     const int64_t nvec = M * (C / VW);
     const dim3 ag(apply_grid(nvec), ni);
-    const BnApplyIo io0{x, res, y, buf.coef};
-    const BnApplyIo io1 = tw ? BnApplyIo{tw->x, tw->res, tw->y, tw->buf.coef} : io0;
+    const BnApplyIo io0{x, res, y, buf.coef, relu_bits};
+    const BnApplyIo io1 = tw ? BnApplyIo{tw->x, tw->res, tw->y, tw->buf.coef, tw->relu_bits} : io0;
     ProfScope ps(sizeof(T) == 2 ? "bn_apply_relu<bf16>" : "bn_apply_relu<fp32>", tensor_bytes * (res ? 3 : 2), 1);
 #define BN_APPLY(R, H) \
     DSP_LAUNCH(ps, (bn_fwd_apply_kernel<T, VW, R, H>), ag, dim3(kThreads), 0, st, io0, io1, nvec, C, L.cv)
@@ -652,7 +672,7 @@ int bn_backward_t(const void* dy, const void* x, const void* y, void* dx, void* 
     const dim3 grid(nblk, ceil_div(L.cv, L.cvb));
     const double tensor_bytes = (double)M * C * sizeof(T);
     {
-        ProfScope ps(sizeof(T) == 2 ? "bn_bwd_reduce<bf16>" : "bn_bwd_reduce<fp32>", tensor_bytes * (RM == 1 ? 3 : 2), 1);
+        ProfScope ps(sizeof(T) == 2 ? "bn_bwd_reduce<bf16>" : "bn_bwd_reduce<fp32>", tensor_bytes * (RM == 1 ? 3 : 2) + (RM == 3 ? tensor_bytes / (VW * sizeof(T)) : 0.0), 1);
         DSP_LAUNCH(ps, (bn_sums_kernel<T, VW, 1, RM>), grid, dim3(kThreads), 0, st, (const T*)x, (const T*)dy,
                    (const T*)y, (const float*)buf.mean, (const float*)buf.invstd, buf.partial, M, C, L, rows,
                    (const T*)nullptr, (double*)nullptr, AddOut<T>{}, fcoef);
@@ -667,7 +687,8 @@ int bn_backward_t(const void* dy, const void* x, const void* y, void* dx, void* 
     // reads dy, x (y too where the ReLU is decided from the stored output, and the old values where it accumulates);
     // writes dx (and dres)
     ProfScope ps(sizeof(T) == 2 ? "bn_bwd_apply<bf16>" : "bn_bwd_apply<fp32>",
-                 tensor_bytes * (2 + (RM == 1 ? 1 : 0) + 1 + (xacc ? 1 : 0) + (dres ? 1 + (racc ? 1 : 0) : 0)), 1);
+                 tensor_bytes * (2 + (RM == 1 ? 1 : 0) + 1 + (xacc ? 1 : 0) + (dres ? 1 + (racc ? 1 : 0) : 0)) +
+                     (RM == 3 ? tensor_bytes / (VW * sizeof(T)) : 0.0), 1);
 #define BN_BAPPLY(H, RA, XA)                                                                                   \
     DSP_LAUNCH(ps, (bn_bwd_apply_kernel<T, VW, (H && RM == 2) ? 1 : RM, H, RA, XA>), ag, dim3(kThreads), 0, st, \
                (const T*)dy, (const T*)x, (const T*)y, (T*)dx, (const T*)dx_prev, (T*)dres, (const float*)buf.coef,   \
@@ -730,24 +751,25 @@ int launch_add_forward_stats(int dtype, const void* a, const void* b, void* y, i
 
 int launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
                       float eps, int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed,
-                      const BnForwardTwin* twin, bool stats_only)
+                      const BnForwardTwin* twin, bool stats_only, uint8_t* relu_bits)
 {
     DSP_REQUIRE(M > 0 && C > 0 && presummed >= 0, DSP_EINVAL, "bn: bad shape");
+    DSP_REQUIRE(!relu_bits || (relu && bn_relu_bits_bytes(dtype, M, C) > 0), DSP_EINVAL, "bn forward: sign bytes need a ReLU and channels in whole 16-byte runs");
     if (twin)
         DSP_REQUIRE(twin->x && (twin->y || stats_only) && (twin->res != nullptr) == (res != nullptr), DSP_EINVAL,
                     "bn forward: incomplete second instance");
     if (dtype == DSP_BF16) {
-        if (C % 8 == 0) return bn_forward_t<bf16_t, 8>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin, stats_only);
-        return bn_forward_t<bf16_t, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin, stats_only);
+        if (C % 8 == 0) return bn_forward_t<bf16_t, 8>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin, stats_only, relu_bits);
+        return bn_forward_t<bf16_t, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin, stats_only, nullptr);
     }
-    if (C % 4 == 0) return bn_forward_t<float, 4>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin, stats_only);
-    return bn_forward_t<float, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin, stats_only);
+    if (C % 4 == 0) return bn_forward_t<float, 4>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin, stats_only, relu_bits);
+    return bn_forward_t<float, 1>(x, res, y, gamma, beta, eps, M, C, relu, buf, st, presummed, twin, stats_only, nullptr);
 }
 
 int launch_bn_apply(int dtype, const void* x, void* y, const float* coef, int64_t M, int C, bool relu, hipStream_t st)
 {
     DSP_REQUIRE(M > 0 && C > 0 && x && y && coef, DSP_EINVAL, "bn apply: bad argument");
-    const BnApplyIo io{x, nullptr, y, coef};
+    const BnApplyIo io{x, nullptr, y, coef, nullptr};
     const double bytes = (double)M * C * dtype_size(dtype) * 2;
 #define BN_APPLY1(T, VW)                                                                                               \
     do {                                                                                                               \
@@ -791,6 +813,12 @@ int launch_bn_relu_maxpool_forward(int dtype, const void* x, const float* coef, 
                    argmax, N, H, W, C, Ho, Wo, k, stride, pad);
     DSP_HIP(hipGetLastError());
     return DSP_OK;
+}
+
+size_t bn_relu_bits_bytes(int dtype, int64_t M, int C)
+{
+    const int vw = dtype == DSP_BF16 ? 8 : 4;
+    return C % vw == 0 ? (size_t)(M * (C / vw)) : 0;
 }
 
 bool bn_pool_backward_supported(int dtype, int C, int H, int W, int k, int stride, int pad)
@@ -845,7 +873,7 @@ static int bn_pool_backward(const PoolGrad& pg, const void* x, void* dx, bool xa
 int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, void* dx, void* dres,
                        bool dres_accumulate, bool dx_accumulate, const float* gamma, float* dgamma, float* dbeta,
                        int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, const void* dx_add,
-                       const float* fwd_coef, const PoolGrad* pool)
+                       const float* fwd_coef, const PoolGrad* pool, const uint8_t* relu_bits)
 {
     DSP_REQUIRE(M > 0 && C > 0, DSP_EINVAL, "bn: bad shape");
     if (pool) {
@@ -864,11 +892,13 @@ int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, 
     // the ReLU of a batch norm without residual can be decided from x (no read of y) when the caller still has the
     // forward pass's {scale, shift}
     const bool from_x = relu && fwd_coef && !dres;
+    const bool from_bits = relu && !from_x && relu_bits && bn_relu_bits_bytes(dtype, M, C) > 0;
+    if (from_bits) y = relu_bits;
     DSP_REQUIRE(!relu || from_x || y, DSP_EINVAL, "bn backward: the ReLU needs the stored output");
 #define BN_BWD_RM(T, VW, RM)                                                                                        \
     bn_backward_t<T, VW, RM>(dy, x, y, dx, dres, dres_accumulate, dx_accumulate, gamma, dgamma, dbeta, M, C, buf, st, \
                              dx_prev, fwd_coef)
-#define BN_BWD(T, VW) (!relu ? BN_BWD_RM(T, VW, 0) : from_x ? BN_BWD_RM(T, VW, 2) : BN_BWD_RM(T, VW, 1))
+#define BN_BWD(T, VW) (!relu ? BN_BWD_RM(T, VW, 0) : from_x ? BN_BWD_RM(T, VW, 2) : (from_bits && VW > 1) ? BN_BWD_RM(T, VW, 3) : BN_BWD_RM(T, VW, 1))
     if (dtype == DSP_BF16) {
         if (C % 8 == 0) return BN_BWD(bf16_t, 8);
         return BN_BWD(bf16_t, 1);

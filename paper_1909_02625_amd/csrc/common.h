@@ -218,10 +218,15 @@ struct BnForwardTwin {
     const void* res;
     void* y;
     BnBuffers buf;
+    uint8_t* relu_bits;  // as the argument of launch_bn_forward, for the second instance (may be nullptr)
 };
 int launch_bn_forward(int dtype, const void* x, const void* res, void* y, const float* gamma, const float* beta,
                       float eps, int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, int presummed = 0,
-                      const BnForwardTwin* twin = nullptr, bool stats_only = false);
+                      const BnForwardTwin* twin = nullptr, bool stats_only = false, uint8_t* relu_bits = nullptr);
+// relu_bits (ReLU layers whose channels come in whole 16-byte runs: bn_relu_bits_bytes() > 0 bytes): the apply kernel also
+// leaves one byte per channel vector, bit k = element k of y as stored is positive.  launch_bn_backward takes the ReLU
+// decision of a layer WITH residual from these bytes instead of reading y (an eighth / a sixteenth of its bytes).
+size_t bn_relu_bits_bytes(int dtype, int64_t M, int C);
 // stats_only: mean, invstd and buf.coef = {scale[C], shift[C]} only; y is not written (may be nullptr).  The two calls
 // below finish such a layer: launch_bn_apply writes y = [relu](scale * x + shift) from those coefficients, and
 // launch_bn_relu_maxpool_forward (bf16, C % 8 == 0, window k <= 4: bn_relu_maxpool_supported) writes the max pool of that
@@ -264,7 +269,7 @@ bool bn_pool_backward_supported(int dtype, int C, int H, int W, int k, int strid
 int launch_bn_backward(int dtype, const void* dy, const void* x, const void* y, void* dx, void* dres,
                        bool dres_accumulate, bool dx_accumulate, const float* gamma, float* dgamma, float* dbeta,
                        int64_t M, int C, bool relu, const BnBuffers& buf, hipStream_t st, const void* dx_add = nullptr,
-                       const float* fwd_coef = nullptr, const PoolGrad* pool = nullptr);
+                       const float* fwd_coef = nullptr, const PoolGrad* pool = nullptr, const uint8_t* relu_bits = nullptr);
 
 // ---- small layers and the update (misc.hip) ---------------------------------------------------
 int launch_maxpool_forward(int dtype, const void* x, void* y, uint8_t* argmax, int N, int H, int W, int C, int k,

@@ -56,6 +56,45 @@ int dsp_bn_backward(int32_t dtype, const void* d_dy, const void* d_x, const void
                               d_dbeta, M, C, relu != 0, buf, (hipStream_t)stream);
 }
 
+int dsp_bn_relu_bits_bytes(int32_t dtype, int64_t M, int32_t C, size_t* bytes)
+{
+    DSP_REQUIRE(bytes && dtype_ok(dtype) && M > 0 && C > 0, DSP_EINVAL, "dsp_bn_relu_bits_bytes: bad argument");
+    *bytes = bn_relu_bits_bytes(dtype, M, C);
+    return DSP_OK;
+}
+
+int dsp_bn_forward_bits(int32_t dtype, const void* d_x, const void* d_res, void* d_y, const float* d_gamma, const float* d_beta,
+                        float eps, int64_t M, int32_t C, float* d_mean, float* d_invstd, uint8_t* d_relu_bits, void* d_workspace,
+                        size_t workspace_bytes, void* stream)
+{
+    DSP_REQUIRE(dtype_ok(dtype) && d_x && d_y && d_gamma && d_beta && d_mean && d_invstd && d_relu_bits && d_workspace, DSP_EINVAL,
+                "dsp_bn_forward_bits: bad argument");
+    DSP_REQUIRE(M > 0 && C > 0 && eps > 0.f && M * (int64_t)C < (1ll << 31), DSP_EINVAL, "dsp_bn_forward_bits: bad shape");
+    DSP_REQUIRE(bn_relu_bits_bytes(dtype, M, C) > 0, DSP_EINVAL, "dsp_bn_forward_bits: channels must come in whole 16-byte runs");
+    DSP_REQUIRE(workspace_bytes >= bn_ws_bytes(C) && ((uintptr_t)d_workspace % 16) == 0, DSP_EINVAL,
+                "dsp_bn_forward_bits: workspace too small or not 16-byte aligned (%zu < %zu)", workspace_bytes, bn_ws_bytes(C));
+    BnBuffers buf{(double*)d_workspace, d_mean, d_invstd, (float*)((char*)d_workspace + bn_partial_bytes(C))};
+    return launch_bn_forward(dtype, d_x, d_res, d_y, d_gamma, d_beta, eps, M, C, true, buf, (hipStream_t)stream, 0, nullptr, false,
+                             d_relu_bits);
+}
+
+int dsp_bn_backward_bits(int32_t dtype, const void* d_dy, const void* d_x, const uint8_t* d_relu_bits, void* d_dx, void* d_dres,
+                         int32_t dres_accumulate, int32_t dx_accumulate, const float* d_gamma, const float* d_mean,
+                         const float* d_invstd, float* d_dgamma, float* d_dbeta, int64_t M, int32_t C, void* d_workspace,
+                         size_t workspace_bytes, void* stream)
+{
+    DSP_REQUIRE(dtype_ok(dtype) && d_dy && d_x && d_relu_bits && d_dx && d_gamma && d_mean && d_invstd && d_dgamma && d_dbeta &&
+                    d_workspace, DSP_EINVAL, "dsp_bn_backward_bits: bad argument");
+    DSP_REQUIRE(M > 0 && C > 0 && M * (int64_t)C < (1ll << 31), DSP_EINVAL, "dsp_bn_backward_bits: bad shape");
+    DSP_REQUIRE(bn_relu_bits_bytes(dtype, M, C) > 0, DSP_EINVAL, "dsp_bn_backward_bits: channels must come in whole 16-byte runs");
+    DSP_REQUIRE(workspace_bytes >= bn_ws_bytes(C) && ((uintptr_t)d_workspace % 16) == 0, DSP_EINVAL,
+                "dsp_bn_backward_bits: workspace too small or not 16-byte aligned (%zu < %zu)", workspace_bytes, bn_ws_bytes(C));
+    BnBuffers buf{(double*)d_workspace, const_cast<float*>(d_mean), const_cast<float*>(d_invstd),
+                  (float*)((char*)d_workspace + bn_partial_bytes(C))};
+    return launch_bn_backward(dtype, d_dy, d_x, nullptr, d_dx, d_dres, dres_accumulate != 0, dx_accumulate != 0, d_gamma, d_dgamma,
+                              d_dbeta, M, C, true, buf, (hipStream_t)stream, nullptr, nullptr, nullptr, d_relu_bits);
+}
+
 int dsp_bn_relu_backward_from_x(int32_t dtype, const void* d_dy, const void* d_x, const float* d_scale_shift, void* d_dx,
                                 int32_t dx_accumulate, const float* d_gamma, const float* d_mean, const float* d_invstd,
                                 float* d_dgamma, float* d_dbeta, int64_t M, int32_t C, void* d_workspace, size_t workspace_bytes,

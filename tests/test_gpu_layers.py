@@ -107,6 +107,65 @@ def test_batch_norm_forward_and_backward(shape, dtype, relu, res):
             assert rel_err(from_dev(d_dr2, shape), dr0 + g) < (1e-6 if dtype == D.DSP_FP32 else 4e-3)
 
 
+@pytest.mark.parametrize("dtype", DTYPES, ids=IDS)
+@pytest.mark.parametrize("shape", [(3, 24, 7, 5), (4, 16, 32, 32), (2, 2048, 3, 3), (32, 64, 56, 56)], ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("res", [True, False], ids=["res", "nores"])
+def test_batch_norm_relu_decided_from_sign_bytes(shape, dtype, res):
+    """The forward apply kernel's sign bytes (bit k of byte v = element k of channel vector v of the stored output is
+    positive) against the stored output itself, and the backward pass that reads them against the one that reads y:
+    the same bits in dx, dres, dgamma, dbeta, overwriting and accumulating."""
+    N, C, H, W = shape
+    rng = np.random.default_rng(C * 7 + H)
+    M = N * H * W
+    td = torch_dtype(dtype)
+    vw = 8 if dtype == D.DSP_BF16 else 4
+    x = round_like(rng.standard_normal(shape) * 1.5 + 0.3, dtype)
+    r = round_like(rng.standard_normal(shape), dtype) if res else None
+    gamma = (1.0 + 0.25 * rng.standard_normal(C)).astype(np.float32)
+    beta = (0.25 * rng.standard_normal(C)).astype(np.float32)
+    ws_bytes = D.dsp_bn_workspace_bytes(C)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    d_x, d_r = to_dev(x, dtype), (to_dev(r, dtype) if res else None)
+    d_gamma, d_beta = _dev_f32(gamma), _dev_f32(beta)
+    d_mean, d_invstd = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
+    d_y = torch.full((M * C,), float("nan"), device="cuda", dtype=td)
+    nb = D.dsp_bn_relu_bits_bytes(dtype, M, C)
+    assert nb == M * C // vw
+    d_bits = torch.full((nb,), 0xAA, device="cuda", dtype=torch.uint8)
+    D.dsp_bn_forward_bits(dtype, d_x, d_r, d_y, d_gamma, d_beta, EPS, M, C, d_mean, d_invstd, d_bits, ws, ws_bytes)
+    d_y2 = torch.full((M * C,), float("nan"), device="cuda", dtype=td)
+    D.dsp_bn_forward(dtype, d_x, d_r, d_y2, d_gamma, d_beta, EPS, M, C, True, d_mean, d_invstd, ws, ws_bytes)
+    torch.cuda.synchronize()
+    assert torch.equal(d_y.view(torch.int16 if dtype == D.DSP_BF16 else torch.int32), d_y2.view(torch.int16 if dtype == D.DSP_BF16 else torch.int32))
+    pos = (d_y.float() > 0).view(-1, vw).to(torch.int32)
+    want = (pos << torch.arange(vw, device="cuda", dtype=torch.int32)).sum(dim=1).to(torch.uint8)
+    assert torch.equal(d_bits, want)
+    dy = to_dev(round_like(rng.standard_normal(shape) * 0.1, dtype), dtype)
+    dx0 = to_dev(round_like(rng.standard_normal(shape) * 0.1, dtype), dtype)
+    for acc in (False, True):
+        outs = []
+        for bits in (False, True):
+            d_dx = dx0.clone() if acc else torch.full((M * C,), float("nan"), device="cuda", dtype=td)
+            d_dr = (dx0.clone() if acc else torch.full((M * C,), float("nan"), device="cuda", dtype=td)) if res else None
+            d_dg, d_db = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
+            if bits:
+                D.dsp_bn_backward_bits(dtype, dy, d_x, d_bits, d_dx, d_dr, acc, acc, d_gamma, d_mean, d_invstd, d_dg, d_db, M, C, ws, ws_bytes)
+            else:
+                D.dsp_bn_backward(dtype, dy, d_x, d_y, d_dx, d_dr, acc, acc, d_gamma, d_mean, d_invstd, d_dg, d_db, M, C, True, ws, ws_bytes)
+            torch.cuda.synchronize()
+            outs.append([d_dx.clone(), d_dg.clone(), d_db.clone()] + ([d_dr.clone()] if res else []))
+        for u, v in zip(*outs):
+            assert torch.equal(u.view(torch.uint8), v.view(torch.uint8))
+
+
+def test_batch_norm_sign_bytes_need_whole_channel_vectors():
+    x = torch.zeros(4096, device="cuda")
+    ws = torch.empty(D.dsp_bn_workspace_bytes(6), dtype=torch.uint8, device="cuda")
+    assert D.dsp_bn_relu_bits_bytes(D.DSP_FP32, 16, 6) == 0
+    with pytest.raises(D.DSPError):
+        D.dsp_bn_forward_bits(D.DSP_FP32, x, None, x, x, x, EPS, 16, 6, x, x, x.view(torch.uint8), ws, ws.numel())
+
+
 FUSED_SHAPES = [  # (N, C, H, W, k, stride, pad)
     (2, 16, 9, 9, 3, 2, 1),       # odd map: windows cut by every border
     (3, 24, 6, 10, 3, 2, 1),      # the stem's window on a small even map, three channel vectors
